@@ -1,0 +1,37 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def parse_golden(name):
+    """tests/golden/<name>: '#' comments, then 'key: v v v ...' lines (ints or floats, a/b fractions allowed)."""
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", name)) as fh:
+        for line in fh:
+            line = line.split("#", 1)[0].strip()
+            if not line:
+                continue
+            key, vals = line.split(":", 1)
+            parsed = []
+            for tok in vals.split():
+                if "/" in tok:
+                    a, b = tok.split("/")
+                    parsed.append(float(a) / float(b))
+                else:
+                    parsed.append(float(tok))
+            out[key.strip()] = parsed
+    return out
+
+
+@pytest.fixture(scope="session")
+def golden5():
+    return parse_golden("five_vertex.txt")

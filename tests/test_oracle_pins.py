@@ -1,0 +1,442 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- a hand-worked example (tests/golden), dense brute force,
+closed forms, invariants, library routines on special cases, finite differences.
+CPU only."""
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+
+rng = np.random.default_rng(20241101)
+
+
+def small_graph(V, ncols, density, seed, dup=True, empty_rows=(), full_rows=()):
+    """Random CSR with duplicates, some empty rows and some full rows (numpy only)."""
+    r = np.random.default_rng(seed)
+    rows, cols = [], []
+    for i in range(V):
+        if i in empty_rows:
+            continue
+        if i in full_rows:
+            c = np.arange(ncols)
+        else:
+            n = r.integers(1, max(2, int(density * ncols)) + 1)
+            c = r.integers(0, ncols, size=n)
+            if dup and n > 2:
+                c[1] = c[0]  # force a duplicate edge
+        c = np.sort(c)
+        rows += [i] * len(c)
+        cols += list(c)
+    rowptr = np.zeros(V + 1, dtype=np.int32)
+    np.add.at(rowptr, np.array(rows, dtype=np.int64) + 1, 1)
+    rowptr = np.cumsum(rowptr).astype(np.int32)
+    return rowptr, np.array(cols, dtype=np.int32), np.array(rows, dtype=np.int32)
+
+
+def dense_from(rowptr, col, row, ncols, w=None):
+    A = np.zeros((rowptr.size - 1, ncols))
+    np.add.at(A, (row, col), 1.0 if w is None else w)
+    return A
+
+
+# ------------------------------------------------------------------ fp16 codec
+def test_codec_exhaustive_decode_matches_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = oracle.decode(bits.view(np.float16))
+    nan = np.isnan(ref)
+    assert np.array_equal(nan, np.isnan(got))
+    assert np.array_equal(ref[~nan], got[~nan])
+    assert np.array_equal(np.signbit(ref[~nan]), np.signbit(got[~nan]))
+
+
+def test_codec_round_trip_and_range():
+    for b in range(65536):
+        v = oracle.half_to_double(b)
+        if v != v:
+            continue
+        assert oracle.double_to_half(v) == b, hex(b)
+    # section 2.2: largest finite (2 - 2^-10) * 2^15, least normal 2^-14
+    assert oracle.half_to_double(0x7BFF) == (2 - 2.0 ** -10) * 2.0 ** 15 == 65504.0
+    assert oracle.half_to_double(0x0400) == 2.0 ** -14
+    assert oracle.double_to_half(65519.99) == 0x7BFF and oracle.double_to_half(65520.0) == 0x7C00
+    assert oracle.double_to_half(-1e9) == 0xFC00
+
+
+def test_codec_rounds_to_nearest_even():
+    one = 0x3C00
+    assert oracle.double_to_half(1 + 2.0 ** -11) == one          # tie -> even (down)
+    assert oracle.double_to_half(1 + 3 * 2.0 ** -11) == one + 2  # tie -> even (up)
+    assert oracle.double_to_half(1 + 2.0 ** -11 + 2.0 ** -30) == one + 1
+    assert oracle.double_to_half(2.0 ** -25) == 0 and oracle.double_to_half(2.0 ** -25 * 1.0001) == 1
+    x = rng.standard_normal(200000) * np.exp(rng.uniform(-20, 12, 200000))
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.double_to_half(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(ref, got)
+
+
+# ------------------------------------------------------------------ hand-worked example
+def g5(golden5):
+    rowptr = np.array(golden5["rowptr"], dtype=np.int32)
+    col = np.array(golden5["col"], dtype=np.int32)
+    X = np.array(golden5["X"]).reshape(5, 2).astype(np.float16)
+    return rowptr, col, X
+
+
+def test_five_vertex_spmm(golden5):
+    rowptr, col, X = g5(golden5)
+    assert np.array_equal(oracle.spmm(rowptr, col, X), np.array(golden5["Y_sum"]).reshape(5, 2))
+    np.testing.assert_allclose(oracle.spmm(rowptr, col, X, reduce=oracle.MEAN),
+                               np.array(golden5["Y_mean"]).reshape(5, 2), rtol=1e-15)
+    w = np.array(golden5["w"], dtype=np.float16).reshape(-1, 1)
+    assert np.array_equal(oracle.spmm(rowptr, col, X, w=w), np.array(golden5["Y_w"]).reshape(5, 2))
+    # subset of rows
+    assert np.array_equal(oracle.spmm(rowptr, col, X, rows=[3, 0]), np.array([[21, 24], [13, 16]]))
+
+
+def test_five_vertex_transpose_and_backward(golden5):
+    rowptr, col, _ = g5(golden5)
+    dY = np.array(golden5["dY"]).reshape(5, 2).astype(np.float16)
+    dX = np.array(golden5["dX"]).reshape(5, 2)
+    assert np.array_equal(oracle.spmm_T_scatter(rowptr, col, dY, 5), dX)
+    rT, cT, eT = oracle.transpose(rowptr, col, 5)
+    assert list(rT) == [0, 2, 5, 8, 11, 14]
+    assert list(cT) == [0, 1, 0, 1, 2, 1, 2, 3, 2, 3, 4, 0, 3, 4]
+    assert list(eT) == [0, 3, 1, 4, 6, 5, 7, 9, 8, 10, 12, 2, 11, 13]
+    assert np.array_equal(oracle.spmm(rT, cT, dY), dX)
+    assert not np.array_equal(oracle.spmm(rowptr, col, dY), dX)  # the example is asymmetric
+
+
+def test_five_vertex_sddmm_softmax_gat(golden5):
+    rowptr, col, X = g5(golden5)
+    dY = np.array(golden5["dY"]).reshape(5, 2).astype(np.float16)
+    assert np.array_equal(oracle.sddmm_dot(rowptr, col, dY, X)[:, 0], np.array(golden5["sddmm"]))
+    e = np.log(np.array(golden5["exp_e"])).reshape(-1, 1)
+    alpha = oracle.edge_softmax(rowptr, e)
+    np.testing.assert_allclose(alpha[:, 0], golden5["alpha"], rtol=1e-14)
+    # alpha as edge weights: values chosen exactly representable where possible; compare loosely
+    # after fp16 rounding of alpha, tightly with the fp64 alpha applied by hand
+    Y = np.zeros((5, 2))
+    row = np.repeat(np.arange(5), np.diff(rowptr))
+    np.add.at(Y, row, alpha * X.astype(np.float64)[col])
+    np.testing.assert_allclose(Y, np.array(golden5["Y_alpha"]).reshape(5, 2), rtol=1e-14)
+    Yo = oracle.spmm(rowptr, col, X, w=alpha.astype(np.float16))
+    np.testing.assert_allclose(Yo, np.array(golden5["Y_alpha"]).reshape(5, 2), rtol=1e-3)
+
+
+def test_five_vertex_plan(golden5):
+    rowptr, _, _ = g5(golden5)
+    p = oracle.segment_plan(rowptr, int(golden5["plan_S"][0]))
+    for k in ("seg_row_lo", "seg_row_hi", "split_row", "split_seg_lo", "split_seg_hi"):
+        assert list(p[k]) == [int(v) for v in golden5[k]], k
+
+
+# ------------------------------------------------------------------ SpMM against dense brute force
+@pytest.mark.parametrize("H", [1, 2, 4])
+@pytest.mark.parametrize("reduce", [oracle.SUM, oracle.MEAN])
+def test_spmm_dense_bruteforce(H, reduce):
+    V, ncols, F = 37, 29, 8
+    rowptr, col, row = small_graph(V, ncols, 0.4, 7 + H, empty_rows=(0, 5, 36), full_rows=(3,))
+    E = col.size
+    X = rng.standard_normal((ncols, F)).astype(np.float16)
+    w = rng.standard_normal((E, H)).astype(np.float16)
+    rs = rng.uniform(0.5, 2.0, V)
+    D = F // H
+    ref = np.zeros((V, F))
+    for h in range(H):  # dense A_h @ X_h per head
+        A = dense_from(rowptr, col, row, ncols, w[:, h].astype(np.float64))
+        ref[:, h * D:(h + 1) * D] = A @ X[:, h * D:(h + 1) * D].astype(np.float64)
+    deg = np.diff(rowptr)
+    if reduce == oracle.MEAN:
+        ref /= np.maximum(deg, 1)[:, None]
+    ref *= rs[:, None]
+    got, sabs = oracle.spmm(rowptr, col, X, w=w, H=H, reduce=reduce, row_scale=rs, want_sabs=True)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+    assert np.all(got[deg == 0] == 0.0)
+    assert np.all(sabs + 1e-12 >= np.abs(got))
+    # unweighted and a non-contiguous (padded) X
+    Xp = np.zeros((ncols, F + 8), dtype=np.float16)
+    Xp[:, :F] = X
+    A1 = dense_from(rowptr, col, row, ncols)
+    np.testing.assert_allclose(oracle.spmm(rowptr, col, Xp[:, :F]), A1 @ X.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_spmm_all_ones_gives_degree():
+    rowptr, col, _ = small_graph(50, 50, 0.3, 11, empty_rows=(4, 9))
+    X = np.ones((50, 4), dtype=np.float16)
+    deg = np.diff(rowptr).astype(np.float64)
+    assert np.array_equal(oracle.spmm(rowptr, col, X), np.repeat(deg[:, None], 4, 1))
+    m = oracle.spmm(rowptr, col, X, reduce=oracle.MEAN)
+    assert np.array_equal(m[deg > 0], np.ones((int((deg > 0).sum()), 4)))
+    assert np.all(m[deg == 0] == 0)
+
+
+@pytest.mark.parametrize("H", [1, 4])
+def test_spmm_adjoint_identity_and_transpose(H):
+    """<A_w X, dY> = <X, A_w^T dY> pins the transposed graph and its edge-id map."""
+    V, ncols, F = 41, 33, 8
+    rowptr, col, row = small_graph(V, ncols, 0.3, 5, empty_rows=(2,))
+    E = col.size
+    X = rng.standard_normal((ncols, F)).astype(np.float16)
+    dY = rng.standard_normal((V, F)).astype(np.float16)
+    w = rng.standard_normal((E, H)).astype(np.float16)
+    Y = oracle.spmm(rowptr, col, X, w=w, H=H)
+    rT, cT, eT = oracle.transpose(rowptr, col, ncols)
+    dX_g = oracle.spmm(rT, cT, dY, w=w, H=H, eid=eT)
+    dX_s = oracle.spmm_T_scatter(rowptr, col, dY, ncols, w=w, H=H)
+    np.testing.assert_allclose(dX_g, dX_s, rtol=1e-12, atol=1e-12)
+    lhs = np.sum(Y * dY.astype(np.float64))
+    rhs = np.sum(X.astype(np.float64) * dX_g)
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+    # structure of the transpose: a permutation, grouped by column, positions ascending inside
+    assert sorted(eT) == list(range(E))
+    assert np.array_equal(col[eT], np.repeat(np.arange(ncols), np.diff(rT)))
+    assert np.array_equal(row[eT], cT)
+    for j in range(ncols):
+        seg = eT[rT[j]:rT[j + 1]]
+        assert np.all(np.diff(seg) > 0)
+
+
+# ------------------------------------------------------------------ SDDMM
+@pytest.mark.parametrize("H", [1, 2])
+def test_sddmm_bruteforce_and_duality(H):
+    V, ncols, F = 23, 31, 8
+    D = F // H
+    rowptr, col, row = small_graph(V, ncols, 0.3, 3)
+    U = rng.standard_normal((V, F)).astype(np.float16)
+    Vt = rng.standard_normal((ncols, F)).astype(np.float16)
+    out = oracle.sddmm_dot(rowptr, col, U, Vt, H=H)
+    for h in range(H):
+        full = U[:, h * D:(h + 1) * D].astype(np.float64) @ Vt[:, h * D:(h + 1) * D].astype(np.float64).T
+        np.testing.assert_allclose(out[:, h], full[row, col], rtol=1e-12, atol=1e-12)
+    ones = np.ones((max(V, ncols), F), dtype=np.float16)
+    assert np.all(oracle.sddmm_dot(rowptr, col, ones[:V], ones[:ncols], H=H) == D)
+    # duality: sum_k dW_k w_k = <dY, A_w X>
+    w = rng.standard_normal((col.size, H)).astype(np.float16)
+    lhs = np.sum(out * w.astype(np.float64))
+    rhs = np.sum(U.astype(np.float64) * oracle.spmm(rowptr, col, Vt, w=w, H=H))
+    assert abs(lhs - rhs) < 1e-9 * max(1.0, abs(lhs))
+    # edge-id indirection: results land in slot eid[k]
+    perm = rng.permutation(col.size).astype(np.int32)
+    out_p = oracle.sddmm_dot(rowptr, col, U, Vt, H=H, eid=perm)
+    assert np.array_equal(out_p[perm], out)
+
+
+# ------------------------------------------------------------------ GAT score
+def test_gat_score_special_cases_and_factorisation():
+    V, H, D = 19, 2, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, V, 0.3, 9)
+    h = rng.standard_normal((V, F)).astype(np.float16)
+    al = (0.1 * rng.standard_normal((H, D))).astype(np.float16)
+    ar = (0.1 * rng.standard_normal((H, D))).astype(np.float16)
+    z = np.zeros((H, D), dtype=np.float16)
+    assert np.all(oracle.gat_score(rowptr, col, h, z, z, H) == 0)
+    # independent evaluation: per-vertex projections, then add and LeakyReLU
+    h64 = h.astype(np.float64).reshape(V, H, D)
+    el = np.einsum("vhd,hd->vh", h64, al.astype(np.float64))
+    er = np.einsum("vhd,hd->vh", h64, ar.astype(np.float64))
+    s = el[row] + er[col]
+    ref = np.where(s > 0, s, 0.2 * s)
+    np.testing.assert_allclose(oracle.gat_score(rowptr, col, h, al, ar, H), ref, rtol=1e-12, atol=1e-15)
+    hp, ap = np.abs(h), np.abs(al)
+    sp = oracle.gat_score(rowptr, col, hp, ap, ap, H)  # positive only: LeakyReLU is the identity
+    hp64 = hp.astype(np.float64).reshape(V, H, D)
+    e1 = np.einsum("vhd,hd->vh", hp64, ap.astype(np.float64))
+    np.testing.assert_allclose(sp, e1[row] + e1[col], rtol=1e-12)
+    sn = oracle.gat_score(rowptr, col, hp, -ap, -ap, H)  # negative only: times the slope
+    np.testing.assert_allclose(sn, -0.2 * (e1[row] + e1[col]), rtol=1e-12)
+    np.testing.assert_allclose(oracle.gat_score(rowptr, col, hp, -ap, -ap, H, slope=0.5), -0.5 * (e1[row] + e1[col]),
+                               rtol=1e-12)
+
+
+# ------------------------------------------------------------------ edge softmax (Eq. 1)
+def test_edge_softmax_invariants_and_library():
+    V, H = 30, 3
+    rowptr, col, row = small_graph(V, 40, 0.5, 21, empty_rows=(7,))
+    E = col.size
+    e = rng.standard_normal((E, H)) * 3
+    a = oracle.edge_softmax(rowptr, e)
+    assert np.all(a >= 0) and np.all(a <= 1)
+    sums = np.zeros((V, H))
+    np.add.at(sums, row, a)
+    deg = np.diff(rowptr)
+    np.testing.assert_allclose(sums[deg > 0], 1.0, rtol=1e-12)
+    for i in range(V):  # library softmax row by row
+        if deg[i]:
+            np.testing.assert_allclose(a[rowptr[i]:rowptr[i + 1]],
+                                       scipy.special.softmax(e[rowptr[i]:rowptr[i + 1]], axis=0), rtol=1e-12)
+    shift = rng.standard_normal((V, H)) * 50
+    np.testing.assert_allclose(oracle.edge_softmax(rowptr, e + shift[row]), a, rtol=1e-9)
+    eq = oracle.edge_softmax(rowptr, np.full((E, H), 1.7))
+    np.testing.assert_allclose(eq, (1.0 / deg[row])[:, None].repeat(H, 1), rtol=1e-14)
+    # numerically safe on huge scores (the max is subtracted first)
+    big = oracle.edge_softmax(rowptr, e + 60000.0)
+    np.testing.assert_allclose(big, a, rtol=1e-9)
+    # degree one
+    rp1 = np.arange(6, dtype=np.int32)
+    assert np.all(oracle.edge_softmax(rp1, rng.standard_normal((5, 2))) == 1.0)
+
+
+def test_zero_attention_gat_equals_mean_spmm():
+    """With a_l = a_r = 0 all scores are equal, alpha = 1/deg, and the GAT output is the mean SpMM."""
+    V, H, D = 26, 2, 4
+    rowptr, col, _ = small_graph(V, V, 0.3, 2)
+    h = rng.standard_normal((V, H * D)).astype(np.float16)
+    z = np.zeros((H, D), dtype=np.float16)
+    alpha = oracle.edge_softmax(rowptr, oracle.gat_score(rowptr, col, h, z, z, H))
+    deg = np.diff(rowptr)
+    row = np.repeat(np.arange(V), deg)
+    np.testing.assert_allclose(alpha, (1.0 / deg[row])[:, None].repeat(H, 1))
+    # alpha is not fp16-exact in general, so apply it by hand in fp64 and compare with MEAN
+    out = np.zeros((V, H * D))
+    np.add.at(out, row, np.repeat(alpha, D, axis=1) * h.astype(np.float64)[col])
+    np.testing.assert_allclose(out, oracle.spmm(rowptr, col, h, reduce=oracle.MEAN), rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ backward formulas by finite differences
+def test_softmax_backward_finite_differences():
+    V, H = 9, 2
+    rowptr, col, row = small_graph(V, 12, 0.5, 33)
+    E = col.size
+    e = rng.standard_normal((E, H))
+    dalpha = rng.standard_normal((E, H))
+    a = oracle.edge_softmax(rowptr, e)
+    de = oracle.edge_softmax_bwd(rowptr, a, dalpha)
+    loss = lambda ee: np.sum(oracle.edge_softmax(rowptr, ee) * dalpha)
+    eps = 1e-6
+    num = np.zeros_like(e)
+    for k in range(E):
+        for h in range(H):
+            ep, em = e.copy(), e.copy()
+            ep[k, h] += eps
+            em[k, h] -= eps
+            num[k, h] = (loss(ep) - loss(em)) / (2 * eps)
+    np.testing.assert_allclose(de, num, rtol=1e-6, atol=1e-8)
+    rs = np.zeros((V, H))
+    np.add.at(rs, row, de)
+    np.testing.assert_allclose(rs, 0, atol=1e-12)  # softmax gradients sum to zero per row
+
+
+def test_score_backward_finite_differences():
+    """d loss / d el and d er through LeakyReLU and Eq. 1: row sums and column sums of ds."""
+    V, H = 8, 2
+    rowptr, col, row = small_graph(V, V, 0.5, 44)
+    E = col.size
+    el = rng.standard_normal((V, H))
+    er = rng.standard_normal((V, H))
+    dalpha = rng.standard_normal((E, H))
+
+    def fwd(el_, er_):
+        s = el_[row] + er_[col]
+        e_ = np.where(s > 0, s, 0.2 * s)
+        return e_, oracle.edge_softmax(rowptr, e_)
+
+    e, a = fwd(el, er)
+    ds = oracle.edge_softmax_bwd(rowptr, a, dalpha, e=e, slope=0.2)
+    d_el = oracle.edge_rowsum(rowptr, ds)
+    d_er = oracle.edge_colsum(rowptr, col, ds, V)
+    eps = 1e-6
+    for (arr, grad, which) in ((el, d_el, 0), (er, d_er, 1)):
+        num = np.zeros_like(arr)
+        for v in range(V):
+            for h in range(H):
+                p, m = arr.copy(), arr.copy()
+                p[v, h] += eps
+                m[v, h] -= eps
+                lp = np.sum((fwd(p, er) if which == 0 else fwd(el, p))[1] * dalpha)
+                lm = np.sum((fwd(m, er) if which == 0 else fwd(el, m))[1] * dalpha)
+                num[v, h] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(grad, num, rtol=1e-5, atol=1e-7)
+    # column sums agree with row sums over the transposed graph read through the edge-id map
+    rT, cT, eT = oracle.transpose(rowptr, col, V)
+    np.testing.assert_allclose(oracle.edge_rowsum(rT, ds[eT]), d_er, rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ segment plan
+def brute_plan(rowptr, S):
+    V, E = rowptr.size - 1, int(rowptr[-1])
+    row_of = np.empty(E, dtype=np.int64)
+    for i in range(V):
+        row_of[rowptr[i]:rowptr[i + 1]] = i
+    nseg = (E + S - 1) // S
+    lo = [int(row_of[k * S:(k + 1) * S].min()) for k in range(nseg)]
+    hi = [int(row_of[k * S:(k + 1) * S].max()) for k in range(nseg)]
+    seg_of = np.arange(E) // S
+    split = []
+    for i in range(V):
+        segs = set(seg_of[rowptr[i]:rowptr[i + 1]])
+        if len(segs) > 1:
+            split.append((i, min(segs), max(segs)))
+    return lo, hi, split
+
+
+@pytest.mark.parametrize("S", [1, 2, 7, 64, 128, 256, 512])
+def test_plan_bruteforce(S):
+    deg = rng.integers(0, 40, size=300)
+    deg[10] = 1500  # a hub spanning many segments
+    deg[11] = 0
+    deg[299] = 0   # trailing empty row
+    deg[0] = 0     # leading empty row
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    p = oracle.segment_plan(rowptr, S)
+    lo, hi, split = brute_plan(rowptr, S)
+    assert list(p["seg_row_lo"]) == lo and list(p["seg_row_hi"]) == hi
+    assert [(int(a), int(b), int(c)) for a, b, c in zip(p["split_row"], p["split_seg_lo"], p["split_seg_hi"])] == split
+    # rule 2: rows never decrease from one segment to the next
+    assert np.all(np.diff(p["seg_row_lo"]) >= 0) and np.all(p["seg_row_hi"] >= p["seg_row_lo"])
+    if S == 1:
+        assert np.array_equal(p["seg_row_lo"], p["seg_row_hi"])
+        assert np.array_equal(p["split_row"], np.nonzero(deg >= 2)[0])  # one edge per segment: any row of 2+ edges is split
+
+
+def test_plan_degenerate():
+    rowptr = np.array([0, 3, 3, 10], dtype=np.int32)
+    for S in (10, 11, 1000):
+        p = oracle.segment_plan(rowptr, S)
+        assert list(p["seg_row_lo"]) == [0] and list(p["seg_row_hi"]) == [2] and p["split_row"].size == 0
+    p = oracle.segment_plan(np.zeros(5, dtype=np.int32), 8)  # no edges at all
+    assert p["seg_row_lo"].size == 0 and p["split_row"].size == 0
+
+
+# ------------------------------------------------------------------ discretized reduction scaling
+def test_discretized_equals_plain_when_partials_are_exact():
+    """Small-integer data: every partial is an integer below 2048, hence exact in fp16,
+    so batching the reduction changes nothing."""
+    deg = rng.integers(0, 30, size=60)
+    deg[7] = 400
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    E = int(rowptr[-1])
+    col = rng.integers(0, 60, size=E).astype(np.int32)
+    X = rng.integers(-3, 4, size=(60, 4)).astype(np.float16)
+    plain = oracle.spmm(rowptr, col, X)
+    for S in (4, 16, 64):
+        disc, mp = oracle.spmm_discretized(rowptr, col, X, S)
+        assert np.array_equal(disc, plain)
+        assert mp <= S * 3
+
+
+def test_discretized_bounds_partials_where_naive_fp16_overflows():
+    """Section 5.2.2: a hub with all-positive features leaves the fp16 range under
+    post-reduction scaling, while per-batch scaling keeps every stored partial small."""
+    deg = np.array([5, 20000, 3], dtype=np.int64)
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    col = rng.integers(0, 64, size=int(rowptr[-1])).astype(np.int32)
+    X = rng.uniform(4, 8, size=(64, 2)).astype(np.float16)
+    exact = oracle.spmm(rowptr, col, X, reduce=oracle.MEAN)
+    naive = oracle.spmm_naive_fp16(rowptr, col, X, reduce=oracle.MEAN, wide_sum=True).astype(np.float64)
+    assert np.all(np.isinf(naive[1])) and np.all(np.isfinite(naive[[0, 2]]))
+    # a running sum kept in fp16 stalls once its spacing exceeds the addends: finite but far off
+    stalled = oracle.spmm_naive_fp16(rowptr, col, X, reduce=oracle.MEAN).astype(np.float64)
+    assert np.all(np.abs(stalled[1] - exact[1]) > 0.5 * np.abs(exact[1]))
+    disc, mp = oracle.spmm_discretized(rowptr, col, X, 256, reduce=oracle.MEAN)
+    assert mp <= 256 * 8 / 20000 + 8  # scaled partials: hub pieces are tiny, small rows at most max|x|
+    np.testing.assert_allclose(disc, exact, rtol=2e-3)
+    # SUM on the hub does not fit fp16 at all; its partials still do (<= S * max|x|)
+    _, mp_sum = oracle.spmm_discretized(rowptr, col, X, 256, reduce=oracle.SUM)
+    assert mp_sum <= 256 * 8 and oracle.spmm(rowptr, col, X)[1].min() > 65504
+    # naive fp16 on small-integer data is exact (pins the emulation itself)
+    Xi = rng.integers(0, 3, size=(64, 2)).astype(np.float16)
+    assert np.array_equal(oracle.spmm_naive_fp16(rowptr[:2], col, Xi).astype(np.float64), oracle.spmm(rowptr[:2], col, Xi))
