@@ -1,0 +1,174 @@
+/*
+ * hgnn -- half-precision sparse aggregation kernels for GNN training on
+ * AMD MI355X (CDNA4, gfx950): C ABI of libhgnn.so.
+ *
+ * The operations are the sparse kernels of "Optimization of GNN Training
+ * Through Half-precision" (HalfGNN, HPDC'25): SpMM  Y <- A_w X  and its
+ * backward  dX <- A_w^T dY  (section 2.1.2), the discretized-reduction SpMM
+ * without atomic writes (section 5.2), SDDMM  dW_e <- A (.) (dY X^T)
+ * (sections 2.1.2, 5.1), and the edge softmax of Eq. 1 with its backward.
+ *
+ * General rules
+ *  - Every pointer in this header that is not marked HOST is a DEVICE pointer
+ *    owned by the caller.  The library never frees or keeps caller memory,
+ *    except that a plan remembers nothing but sizes of the graph it was built for.
+ *  - fp16 data (hgnn_half) is IEEE binary16 stored as 16-bit words.
+ *    Vertex-level tensors are row major [rows][ld] with ld >= F (section 2.1.1:
+ *    |V| x |F|); edge-level tensors are edge major [nnz][H].  Head h owns the
+ *    features [h*D, (h+1)*D), D = F / H.
+ *  - Graph orientation: row i = destination vertex, the non-zeros of row i are
+ *    its neighbourhood N(i); columns are neighbour ids.  Duplicate non-zeros
+ *    are separate edges.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *    compute entry points are asynchronous on that stream, never synchronize and
+ *    never allocate.  hgnn_plan_create, hgnn_plan_export, hgnn_transpose and
+ *    hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
+ *  - Arithmetic: fp16 in memory, fp32 in registers, one round-to-nearest-even
+ *    conversion when a value is stored.
+ *  - Errors: every call returns an hgnn_status; argument errors are detected on
+ *    the host before anything is launched.  hgnn_last_error() returns a
+ *    thread-local detail string for the last failing call of this thread.
+ *  - Feature widths: odd F is rejected (HGNN_EINVAL): pad to the next even
+ *    number as section 4.1 prescribes for half2; the 16-byte vector path needs
+ *    F % 8 == 0, ld % 8 == 0 and 16-byte aligned base pointers, other even
+ *    shapes take a slower scalar path in hgnn_spmm / hgnn_sddmm and are
+ *    HGNN_EUNSUPPORTED in hgnn_spmm_discretized.
+ */
+#ifndef HGNN_H
+#define HGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t hgnn_half; /* IEEE binary16 bit pattern */
+
+typedef enum {
+  HGNN_OK = 0,
+  HGNN_EINVAL = 1,       /* bad argument (NULL, size, alignment, odd F, inconsistent graph) */
+  HGNN_EUNSUPPORTED = 2, /* valid but not implemented for this shape */
+  HGNN_ENOMEM = 3,       /* device or host allocation failed */
+  HGNN_EHIP = 4          /* a HIP call or kernel launch failed */
+} hgnn_status;
+
+/* reduce op of SpMM.  MEAN = SUM followed by the degree norm 1/deg(i)
+ * (section 5.2.2 treats "SpMM + degree-norm" as SpMM with reduce = mean). */
+typedef enum { HGNN_SUM = 0, HGNN_MEAN = 1 } hgnn_reduce;
+
+typedef enum {
+  HGNN_SDDMM_DOT = 0,      /* out[k,h] = sum_d U[row k,h,d] * Vt[col k,h,d]              (section 2.1.2) */
+  HGNN_SDDMM_GAT_SCORE = 1 /* out[k,h] = LeakyReLU(a_l[h].U[row k,h] + a_r[h].Vt[col k,h]) (section 3.1.2) */
+} hgnn_sddmm_op;
+
+/* A sparse matrix / graph in CSR (section 2.1.1: offset array + column ids),
+ * optionally with COO row ids and an edge-id map. */
+typedef struct {
+  int32_t nrows;         /* |V| of the destination side */
+  int32_t ncols;         /* |V| of the neighbour side */
+  int64_t nnz;           /* |E|, must be < 2^31 */
+  const int32_t* rowptr; /* [nrows+1] non-decreasing, rowptr[0] = 0, rowptr[nrows] = nnz */
+  const int32_t* col;    /* [nnz] 0 <= col < ncols, ascending inside a row (duplicates allowed) */
+  const int32_t* row;    /* [nnz] COO row id of every non-zero, or NULL (a plan supplies it) */
+  const int32_t* eid;    /* [nnz] or NULL.  Edge tensors are read at slot eid[k] for CSR position k
+                            (the transposed graph refers to the original graph's edge tensors) */
+} hgnn_csr;
+
+typedef struct hgnn_plan hgnn_plan; /* opaque; device arrays owned by the library */
+
+const char* hgnn_status_str(hgnn_status s);
+const char* hgnn_last_error(void);
+
+/* One device pass over the graph: rowptr monotone with the right end points,
+ * columns in range, row ids (if given) consistent with rowptr, eid (if given)
+ * in [0,nnz).  Synchronizes.  HGNN_EINVAL names the first rule broken. */
+hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream);
+
+/* CSR of A^T plus the edge-id map, for the backward SpMM dX <- A_w^T dY
+ * (section 2.1.2).  Outputs (device, caller allocated): rowptr_T [ncols+1],
+ * col_T [nnz] (= source rows of A), eid_T [nnz] (= CSR position in A of that
+ * non-zero).  Inside a row of A^T entries keep their order in A (a stable sort
+ * by column).  g->eid must be NULL.  Allocates temporary storage, synchronizes. */
+hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T, int32_t* eid_T, void* stream);
+
+/* Segment plan for the discretized SpMM (section 5.2.1, observation rules 1-3):
+ * the non-zeros are dealt out in storage order in segments of seg_edges edges,
+ * segment k = [k*S, min(nnz,(k+1)*S)).  The plan holds, on the device: the row
+ * of the first and last edge of every segment, the ascending list of "split"
+ * rows (first and last edge in different segments) with the segments they
+ * span, COO row ids (built when g->row is NULL), the staging buffer for
+ * conflicting partial sums (2 vectors of max_F halves per segment; the paper's
+ * buffer is one vector per CTA, section 5.2.3) and per-vertex fp32 scratch of
+ * 2*max_H floats per row/column for the factorised GAT score.
+ * The graph is validated first.  A plan may be used by one stream at a time.
+ * seg_edges in [1, 2048]; max_F >= 8 multiple of 8; max_H >= 1. */
+hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, hgnn_plan** out,
+                             void* stream);
+int64_t hgnn_plan_num_segments(const hgnn_plan* p);
+int32_t hgnn_plan_num_split_rows(const hgnn_plan* p);
+int32_t hgnn_plan_seg_edges(const hgnn_plan* p);
+/* Copies the plan's integer arrays to HOST buffers (each may be NULL to skip):
+ * seg_row_lo / seg_row_hi [num_segments]; split_row / split_seg_lo /
+ * split_seg_hi [num_split_rows].  Synchronizes. */
+hgnn_status hgnn_plan_export(const hgnn_plan* p, int32_t* seg_row_lo, int32_t* seg_row_hi, int32_t* split_row,
+                             int32_t* split_seg_lo, int32_t* split_seg_hi);
+void hgnn_plan_destroy(hgnn_plan* p);
+
+/* SpMM, vertex-parallel (sections 2.1.2, 4.1): for every row i
+ *   Y[i,f] = s_i * sum_{k in row i} w[slot(k), f/D] * X[col[k], f],   slot(k) = eid ? eid[k] : k,
+ * w == NULL means all ones (SpMMv); s_i = 1 (SUM) or 1/max(deg_i,1) (MEAN), times
+ * row_scale[i] (fp32 [nrows]) when row_scale != NULL.  The scale is applied once,
+ * after the whole row is reduced (post-reduction scaling).  Y is fully
+ * overwritten (empty rows become 0).  X is [ncols][ldx], Y is [nrows][ldy]. */
+hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
+                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* stream);
+
+/* Discretized-reduction SpMM, edge-parallel, no atomic writes (section 5.2):
+ * same result as hgnn_spmm, but every wavefront reduces one segment of the plan,
+ * each partial sum covers at most seg_edges edges and is scaled by s_i before it
+ * is rounded to fp16 (discretized reduction scaling, section 5.2.2), rows inside
+ * one segment are stored directly, partials of rows that cross a segment boundary
+ * go to the plan's staging buffer and a follow-up kernel adds them in ascending
+ * segment order and stores the row once (section 5.2.3).  Deterministic.
+ * Needs F % 8 == 0, F <= 512, D % 8 == 0, F <= plan max_F, and the plan of this graph. */
+hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                  const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                  hgnn_reduce op, const float* row_scale, void* stream);
+
+/* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
+ *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
+ *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s
+ * U is [nrows][ldu], Vt is [ncols][ldv], a_l / a_r are [H*D] (GAT_SCORE only).
+ * Needs COO row ids: g->row or a plan (p may be NULL when g->row is given).
+ * With a plan, GAT_SCORE first projects every vertex once (fp32 scratch in the
+ * plan) and then adds per edge.  g->eid must be NULL. */
+hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sddmm_op op, int32_t H, int32_t D,
+                       const hgnn_half* U, int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                       const hgnn_half* a_r, float neg_slope, hgnn_half* out, void* stream);
+
+/* Edge softmax, Eq. 1, over every row (neighbourhood) and head:
+ *   m_i = max_k e[k,h];  alpha[k,h] = exp(e[k,h]-m_i) / sum_k exp(e[k,h]-m_i).
+ * exp and the sums are fp32 in registers (the argument is <= 0, so the value is in
+ * (0,1], section 3.1.2).  e and alpha are [nnz][H]; empty rows write nothing.
+ * p may be NULL (then very long rows are slower).  g->eid must be NULL. */
+hgnn_status hgnn_edge_softmax(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* e, hgnn_half* alpha,
+                              void* stream);
+
+/* Backward of Eq. 1:  t_i = sum_k alpha[k,h] dalpha[k,h];  de[k,h] = alpha (dalpha - t_i).
+ * With e != NULL the LeakyReLU of the GAT score is undone as well:
+ *   de[k,h] *= (e[k,h] > 0 ? 1 : neg_slope). */
+hgnn_status hgnn_edge_softmax_bwd(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* alpha,
+                                  const hgnn_half* dalpha, const hgnn_half* e, float neg_slope, hgnn_half* de,
+                                  void* stream);
+
+/* Row sums of an edge tensor: out[i,h] = sum_{k in row i} t[slot(k), h], out is
+ * [nrows][H] fp16.  On g it gives d(e_l); on the transposed graph (with its eid
+ * map) it gives the column sums d(e_r) of the GAT score backward. */
+hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, int32_t H, const hgnn_half* t, hgnn_half* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGNN_H */

@@ -1,0 +1,231 @@
+"""ctypes binding of libhgnn.so: the same entry points as include/hgnn.h, taking
+torch CUDA tensors.  Argument marshalling only -- every step of the path runs in
+the library's HIP kernels; torch supplies device memory and the stream.  There is
+no CPU fallback: a missing library or a failing call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhgnn.so")
+
+HGNN_OK, HGNN_EINVAL, HGNN_EUNSUPPORTED, HGNN_ENOMEM, HGNN_EHIP = range(5)
+HGNN_SUM, HGNN_MEAN = 0, 1
+HGNN_SDDMM_DOT, HGNN_SDDMM_GAT_SCORE = 0, 1
+
+EXPORTS = (
+    "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_plan_create",
+    "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_export",
+    "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_sddmm", "hgnn_edge_softmax",
+    "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum",
+)
+
+
+class HgnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(message)
+        self.status = status
+
+
+class _CsrStruct(ctypes.Structure):
+    _fields_ = [("nrows", ctypes.c_int32), ("ncols", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("rowptr", ctypes.c_void_p), ("col", ctypes.c_void_p), ("row", ctypes.c_void_p),
+                ("eid", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libhgnn.so; raises when it has not been built (no fallback of any kind)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    csr = ctypes.POINTER(_CsrStruct)
+    lib.hgnn_status_str.restype = ctypes.c_char_p
+    lib.hgnn_status_str.argtypes = [ctypes.c_int]
+    lib.hgnn_last_error.restype = ctypes.c_char_p
+    lib.hgnn_last_error.argtypes = []
+    lib.hgnn_csr_validate.argtypes = [csr, vp]
+    lib.hgnn_transpose.argtypes = [csr, vp, vp, vp, vp]
+    lib.hgnn_plan_create.argtypes = [csr, i32, i32, i32, ctypes.POINTER(vp), vp]
+    lib.hgnn_plan_num_segments.restype = i64
+    lib.hgnn_plan_num_segments.argtypes = [vp]
+    lib.hgnn_plan_num_split_rows.restype = i32
+    lib.hgnn_plan_num_split_rows.argtypes = [vp]
+    lib.hgnn_plan_seg_edges.restype = i32
+    lib.hgnn_plan_seg_edges.argtypes = [vp]
+    lib.hgnn_plan_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.hgnn_plan_destroy.restype = None
+    lib.hgnn_plan_destroy.argtypes = [vp]
+    lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
+    lib.hgnn_spmm_discretized.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
+    lib.hgnn_sddmm.argtypes = [csr, vp, ctypes.c_int, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp]
+    lib.hgnn_edge_softmax.argtypes = [csr, vp, i32, vp, vp, vp]
+    lib.hgnn_edge_softmax_bwd.argtypes = [csr, vp, i32, vp, vp, vp, f32, vp, vp]
+    lib.hgnn_edge_rowsum.argtypes = [csr, i32, vp, vp, vp]
+    for name in EXPORTS:
+        getattr(lib, name)  # every declared entry point must be exported
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != HGNN_OK:
+        lib = load()
+        detail = lib.hgnn_last_error().decode()
+        raise HgnnError(status, f"{lib.hgnn_status_str(status).decode()}: {detail}")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("hgnn expects CUDA (HIP) tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ld(t: torch.Tensor) -> int:
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("vertex-level tensors must be 2-D with unit stride along features")
+    return t.stride(0)
+
+
+class Csr:
+    """Device CSR graph (hgnn_csr): int32 tensors, kept alive by this object."""
+
+    def __init__(self, rowptr: torch.Tensor, col: torch.Tensor, ncols: Optional[int] = None,
+                 row: Optional[torch.Tensor] = None, eid: Optional[torch.Tensor] = None):
+        for t in (rowptr, col, row, eid):
+            if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+                raise TypeError("graph arrays must be contiguous int32 CUDA tensors")
+        self.rowptr, self.col, self.row, self.eid = rowptr, col, row, eid
+        self.nrows = rowptr.numel() - 1
+        self.ncols = self.nrows if ncols is None else ncols
+        self.nnz = col.numel()
+        self.struct = _CsrStruct(self.nrows, self.ncols, self.nnz, rowptr.data_ptr(), col.data_ptr(),
+                                 None if row is None else row.data_ptr(), None if eid is None else eid.data_ptr())
+
+    @property
+    def ref(self):
+        return ctypes.byref(self.struct)
+
+
+class Plan:
+    """Owner of an hgnn_plan handle."""
+
+    def __init__(self, handle: int, graph: Csr):
+        self.handle = handle
+        self.graph = graph
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.hgnn_plan_destroy(h)
+
+
+def hgnn_csr_validate(g: Csr, stream=None) -> None:
+    _check(load().hgnn_csr_validate(g.ref, _stream(stream)))
+
+
+def hgnn_transpose(g: Csr, stream=None) -> Csr:
+    """CSR of A^T carrying eid into A's edge tensors."""
+    dev = g.rowptr.device
+    rowptr_T = torch.empty(g.ncols + 1, dtype=torch.int32, device=dev)
+    col_T = torch.empty(g.nnz, dtype=torch.int32, device=dev)
+    eid_T = torch.empty(g.nnz, dtype=torch.int32, device=dev)
+    _check(load().hgnn_transpose(g.ref, rowptr_T.data_ptr(), col_T.data_ptr(), eid_T.data_ptr(), _stream(stream)))
+    return Csr(rowptr_T, col_T, ncols=g.nrows, eid=eid_T)
+
+
+def hgnn_plan_create(g: Csr, seg_edges: int = 256, max_F: int = 128, max_H: int = 8, stream=None) -> Plan:
+    out = ctypes.c_void_p()
+    _check(load().hgnn_plan_create(g.ref, seg_edges, max_F, max_H, ctypes.byref(out), _stream(stream)))
+    return Plan(out.value, g)
+
+
+def hgnn_plan_num_segments(p: Plan) -> int:
+    return load().hgnn_plan_num_segments(p.handle)
+
+
+def hgnn_plan_num_split_rows(p: Plan) -> int:
+    return load().hgnn_plan_num_split_rows(p.handle)
+
+
+def hgnn_plan_seg_edges(p: Plan) -> int:
+    return load().hgnn_plan_seg_edges(p.handle)
+
+
+def hgnn_plan_export(p: Plan):
+    """-> dict of host int32 numpy arrays (seg_row_lo, seg_row_hi, split_row, split_seg_lo, split_seg_hi)."""
+    import numpy as np
+    nseg, ns = hgnn_plan_num_segments(p), hgnn_plan_num_split_rows(p)
+    arrs = {"seg_row_lo": np.empty(nseg, np.int32), "seg_row_hi": np.empty(nseg, np.int32),
+            "split_row": np.empty(ns, np.int32), "split_seg_lo": np.empty(ns, np.int32),
+            "split_seg_hi": np.empty(ns, np.int32)}
+    _check(load().hgnn_plan_export(p.handle, *[a.ctypes.data for a in arrs.values()]))
+    return arrs
+
+
+def hgnn_plan_destroy(p: Plan) -> None:
+    h, p.handle = p.handle, None
+    if h:
+        load().hgnn_plan_destroy(h)
+
+
+def hgnn_spmm(g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
+              op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None, stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    _check(load().hgnn_spmm(g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16), _ld(X),
+                            _ptr(Y, torch.float16), _ld(Y), F, op, _ptr(row_scale, torch.float32), _stream(stream)))
+
+
+def hgnn_spmm_discretized(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
+                          op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None,
+                          stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    _check(load().hgnn_spmm_discretized(p.handle, g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16),
+                                        _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
+                                        _ptr(row_scale, torch.float32), _stream(stream)))
+
+
+def hgnn_sddmm(g: Csr, p: Optional[Plan], op: int, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,
+               out: torch.Tensor, a_l: Optional[torch.Tensor] = None, a_r: Optional[torch.Tensor] = None,
+               neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_sddmm(g.ref, None if p is None else p.handle, op, H, D, _ptr(U, torch.float16), _ld(U),
+                             _ptr(Vt, torch.float16), _ld(Vt), _ptr(a_l, torch.float16), _ptr(a_r, torch.float16),
+                             neg_slope, _ptr(out, torch.float16), _stream(stream)))
+
+
+def hgnn_edge_softmax(g: Csr, p: Optional[Plan], H: int, e: torch.Tensor, alpha: torch.Tensor, stream=None) -> None:
+    _check(load().hgnn_edge_softmax(g.ref, None if p is None else p.handle, H, _ptr(e, torch.float16),
+                                    _ptr(alpha, torch.float16), _stream(stream)))
+
+
+def hgnn_edge_softmax_bwd(g: Csr, p: Optional[Plan], H: int, alpha: torch.Tensor, dalpha: torch.Tensor,
+                          de: torch.Tensor, e: Optional[torch.Tensor] = None, neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_edge_softmax_bwd(g.ref, None if p is None else p.handle, H, _ptr(alpha, torch.float16),
+                                        _ptr(dalpha, torch.float16), _ptr(e, torch.float16), neg_slope,
+                                        _ptr(de, torch.float16), _stream(stream)))
+
+
+def hgnn_edge_rowsum(g: Csr, H: int, t: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    _check(load().hgnn_edge_rowsum(g.ref, H, _ptr(t, torch.float16), _ptr(out, torch.float16), _stream(stream)))

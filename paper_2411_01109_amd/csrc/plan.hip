@@ -1,0 +1,348 @@
+// Status strings, graph validation and the segment plan of the discretized SpMM
+// (paper section 5.2.1: edges are dealt out in storage order in fixed-size batches,
+// observation rules 1-3).  Integer work only; everything here is one-off set-up.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.h"
+
+namespace hgnn {
+
+static thread_local char g_err[512] = "";
+
+hgnn_status fail(hgnn_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+void clear_error() { g_err[0] = 0; }
+
+hgnn_status check_csr_args(const hgnn_csr* g, const char* who) {
+  HGNN_REQUIRE(g != nullptr, HGNN_EINVAL, "%s: graph is NULL", who);
+  HGNN_REQUIRE(g->nrows >= 0 && g->ncols >= 0 && g->nnz >= 0, HGNN_EINVAL, "%s: negative graph size", who);
+  HGNN_REQUIRE(g->nnz < (int64_t(1) << 31), HGNN_EINVAL, "%s: nnz = %lld does not fit int32", who, (long long)g->nnz);
+  HGNN_REQUIRE(g->rowptr != nullptr, HGNN_EINVAL, "%s: rowptr is NULL", who);
+  HGNN_REQUIRE(g->nnz == 0 || g->col != nullptr, HGNN_EINVAL, "%s: col is NULL", who);
+  return HGNN_OK;
+}
+
+// ---- validation ---------------------------------------------------------------------------------
+// err starts at kNoError and receives the smallest rule number broken
+constexpr int kNoError = 0x7f7f7f7f;
+__global__ void validate_kernel(hgnn_csr g, int* err) {
+  int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  int bad = 0;
+  if (i == 0) {
+    if (g.rowptr[0] != 0) bad = 1;
+    else if (int64_t(g.rowptr[g.nrows]) != g.nnz) bad = 2;
+  }
+  if (!bad && i < g.nrows && g.rowptr[i] > g.rowptr[i + 1]) bad = 3;
+  if (!bad && i < g.nnz) {
+    int c = g.col[i];
+    if (c < 0 || c >= g.ncols) bad = 4;
+    if (!bad && g.eid) {
+      int e = g.eid[i];
+      if (e < 0 || int64_t(e) >= g.nnz) bad = 5;
+    }
+    if (!bad && g.row) {
+      int r = g.row[i];
+      if (r < 0 || r >= g.nrows) bad = 6;
+      else if (!(int64_t(g.rowptr[r]) <= i && i < int64_t(g.rowptr[r + 1]))) bad = 6;
+    }
+  }
+  if (bad) atomicMin(err, bad);
+}
+
+static const char* const kRule[] = {"ok",
+                                    "rowptr[0] != 0",
+                                    "rowptr[nrows] != nnz",
+                                    "rowptr decreases",
+                                    "a column id is outside [0, ncols)",
+                                    "an edge id is outside [0, nnz)",
+                                    "a COO row id disagrees with rowptr"};
+
+// ---- COO row ids from the offset array ---------------------------------------------------------------
+__global__ void expand_rows_kernel(const int* __restrict__ rowptr, int nrows, int64_t nnz, int* __restrict__ erow) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k >= nnz) return;
+  // last r with rowptr[r] <= k: upper bound over rowptr[0..nrows], minus one (skips empty rows)
+  int lo = 0, hi = nrows + 1;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (int64_t(rowptr[mid]) <= k) lo = mid + 1;
+    else hi = mid;
+  }
+  erow[k] = lo - 1;
+}
+
+__global__ void seg_rows_kernel(const int* __restrict__ erow, int64_t nnz, int S, int64_t nseg, int* __restrict__ lo,
+                                int* __restrict__ hi) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k >= nseg) return;
+  int64_t e0 = k * S, e1 = e0 + S < nnz ? e0 + S : nnz;
+  lo[k] = erow[e0];
+  hi[k] = erow[e1 - 1];
+}
+
+// ---- ordered compaction of the rows that satisfy a predicate -------------------------------------------
+struct SplitPred {  // first and last edge of the row fall in different segments
+  const int* rowptr;
+  int S;
+  __device__ bool operator()(int r) const {
+    int b = rowptr[r], e = rowptr[r + 1];
+    return e > b && (b / S) != ((e - 1) / S);
+  }
+};
+struct BigPred {  // row longer than a threshold
+  const int* rowptr;
+  int deg;
+  __device__ bool operator()(int r) const { return rowptr[r + 1] - rowptr[r] > deg; }
+};
+
+constexpr int kRowsPerThread = 4;
+constexpr int kRowsPerBlock = kBlock * kRowsPerThread;
+
+__device__ inline int block_exclusive_scan(int v, int* total) {  // blockDim.x == kBlock
+  __shared__ int buf[2][kBlock];
+  int t = threadIdx.x, cur = 0;
+  buf[0][t] = v;
+  __syncthreads();
+  for (int d = 1; d < kBlock; d <<= 1) {
+    int x = buf[cur][t];
+    if (t >= d) x += buf[cur][t - d];
+    buf[cur ^ 1][t] = x;
+    cur ^= 1;
+    __syncthreads();
+  }
+  int incl = buf[cur][t];
+  *total = buf[cur][kBlock - 1];
+  __syncthreads();
+  return incl - v;
+}
+
+template <class Pred>
+__global__ void compact_count_kernel(Pred pred, int nrows, int* __restrict__ block_count) {
+  int base = blockIdx.x * kRowsPerBlock + threadIdx.x * kRowsPerThread;
+  int c = 0;
+  for (int u = 0; u < kRowsPerThread; ++u)
+    if (base + u < nrows && pred(base + u)) ++c;
+  int total;
+  (void)block_exclusive_scan(c, &total);
+  if (threadIdx.x == 0) block_count[blockIdx.x] = total;
+}
+
+// one workgroup: exclusive scan of n block counts in place; total[0] = sum
+__global__ void scan_counts_kernel(int* __restrict__ counts, int n, int* __restrict__ total) {
+  int carry = 0;
+  for (int base = 0; base < n; base += kBlock) {
+    int i = base + threadIdx.x;
+    int v = i < n ? counts[i] : 0;
+    int tot;
+    int ex = block_exclusive_scan(v, &tot);
+    if (i < n) counts[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) total[0] = carry;
+}
+
+template <class Pred>
+__global__ void compact_write_kernel(Pred pred, int nrows, const int* __restrict__ block_offset, int* __restrict__ out) {
+  int base = blockIdx.x * kRowsPerBlock + threadIdx.x * kRowsPerThread;
+  bool f[kRowsPerThread];
+  int c = 0;
+  for (int u = 0; u < kRowsPerThread; ++u) {
+    f[u] = base + u < nrows && pred(base + u);
+    c += f[u];
+  }
+  int total;
+  int pos = block_offset[blockIdx.x] + block_exclusive_scan(c, &total);
+  for (int u = 0; u < kRowsPerThread; ++u)
+    if (f[u]) out[pos++] = base + u;
+}
+
+template <class Pred>
+static hgnn_status compact_rows(Pred pred, int nrows, int** out, int* n_out, hipStream_t s) {
+  *out = nullptr;
+  *n_out = 0;
+  if (nrows == 0) return HGNN_OK;
+  int nblk = int(ceil_div(nrows, kRowsPerBlock));
+  int* counts = nullptr;
+  HGNN_HIP(hipMalloc(&counts, sizeof(int) * (size_t(nblk) + 1)));
+  compact_count_kernel<Pred><<<nblk, kBlock, 0, s>>>(pred, nrows, counts);
+  scan_counts_kernel<<<1, kBlock, 0, s>>>(counts, nblk, counts + nblk);
+  int total = 0;
+  hipError_t e = hipMemcpyAsync(&total, counts + nblk, sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) {
+    (void)hipFree(counts);
+    return fail(HGNN_EHIP, "compact_rows: %s", hipGetErrorString(e));
+  }
+  if (total > 0) {
+    e = hipMalloc(out, sizeof(int) * size_t(total));
+    if (e != hipSuccess) {
+      (void)hipFree(counts);
+      return fail(HGNN_ENOMEM, "compact_rows: %s", hipGetErrorString(e));
+    }
+    compact_write_kernel<Pred><<<nblk, kBlock, 0, s>>>(pred, nrows, counts, *out);
+    e = hipStreamSynchronize(s);
+  }
+  (void)hipFree(counts);
+  if (e != hipSuccess) return fail(HGNN_EHIP, "compact_rows: %s", hipGetErrorString(e));
+  *n_out = total;
+  return HGNN_OK;
+}
+
+__global__ void split_segs_kernel(const int* __restrict__ rowptr, const int* __restrict__ split_row, int n, int S,
+                                  int* __restrict__ lo, int* __restrict__ hi) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  int r = split_row[i];
+  lo[i] = rowptr[r] / S;
+  hi[i] = (rowptr[r + 1] - 1) / S;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" {
+
+const char* hgnn_status_str(hgnn_status s) {
+  switch (s) {
+    case HGNN_OK: return "HGNN_OK";
+    case HGNN_EINVAL: return "HGNN_EINVAL: invalid argument";
+    case HGNN_EUNSUPPORTED: return "HGNN_EUNSUPPORTED: shape not supported";
+    case HGNN_ENOMEM: return "HGNN_ENOMEM: out of memory";
+    case HGNN_EHIP: return "HGNN_EHIP: HIP runtime error";
+  }
+  return "unknown hgnn_status";
+}
+
+const char* hgnn_last_error(void) { return g_err; }
+
+hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream) {
+  clear_error();
+  hgnn_status st = check_csr_args(g, "hgnn_csr_validate");
+  if (st != HGNN_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int* derr = nullptr;
+  HGNN_HIP(hipMalloc(&derr, sizeof(int)));
+  int herr = 0;
+  hipError_t e = hipMemsetAsync(derr, 0x7f, sizeof(int), s);
+  if (e == hipSuccess) {
+    int64_t n = g->nnz > int64_t(g->nrows) + 1 ? g->nnz : int64_t(g->nrows) + 1;
+    validate_kernel<<<dim3(unsigned(ceil_div(n, kBlock))), kBlock, 0, s>>>(*g, derr);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(&herr, derr, sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(derr);
+  if (e != hipSuccess) return fail(HGNN_EHIP, "hgnn_csr_validate: %s", hipGetErrorString(e));
+  if (herr != kNoError) return fail(HGNN_EINVAL, "hgnn_csr_validate: %s", kRule[herr > 0 && herr < 7 ? herr : 0]);
+  return HGNN_OK;
+}
+
+int64_t hgnn_plan_num_segments(const hgnn_plan* p) { return p ? p->nseg : 0; }
+int32_t hgnn_plan_num_split_rows(const hgnn_plan* p) { return p ? p->n_split : 0; }
+int32_t hgnn_plan_seg_edges(const hgnn_plan* p) { return p ? p->S : 0; }
+
+void hgnn_plan_destroy(hgnn_plan* p) {
+  if (!p) return;
+  (void)hipFree(p->seg_row_lo);
+  (void)hipFree(p->seg_row_hi);
+  (void)hipFree(p->split_row);
+  (void)hipFree(p->split_seg_lo);
+  (void)hipFree(p->split_seg_hi);
+  (void)hipFree(p->big_row);
+  (void)hipFree(p->edge_row);
+  (void)hipFree(p->staging);
+  (void)hipFree(p->vscratch);
+  delete p;
+}
+
+static hgnn_status plan_build(hgnn_plan* p, const hgnn_csr* g, hipStream_t s) {
+  const int64_t E = g->nnz;
+  if (E > 0) {
+    HGNN_HIP(hipMalloc(&p->edge_row, sizeof(int) * size_t(E)));
+    expand_rows_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, E, p->edge_row);
+    HGNN_LAUNCH_CHECK("expand_rows_kernel");
+    HGNN_HIP(hipMalloc(&p->seg_row_lo, sizeof(int) * size_t(p->nseg)));
+    HGNN_HIP(hipMalloc(&p->seg_row_hi, sizeof(int) * size_t(p->nseg)));
+    seg_rows_kernel<<<dim3(unsigned(ceil_div(p->nseg, kBlock))), kBlock, 0, s>>>(p->edge_row, E, p->S, p->nseg,
+                                                                                  p->seg_row_lo, p->seg_row_hi);
+    HGNN_LAUNCH_CHECK("seg_rows_kernel");
+    // staging: two partial vectors (entering piece / leaving piece) per segment
+    HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F)));
+    HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F), s));
+  }
+  hgnn_status st = compact_rows(SplitPred{g->rowptr, p->S}, g->nrows, &p->split_row, &p->n_split, s);
+  if (st != HGNN_OK) return st;
+  if (p->n_split > 0) {
+    HGNN_HIP(hipMalloc(&p->split_seg_lo, sizeof(int) * size_t(p->n_split)));
+    HGNN_HIP(hipMalloc(&p->split_seg_hi, sizeof(int) * size_t(p->n_split)));
+    split_segs_kernel<<<dim3(unsigned(ceil_div(p->n_split, kBlock))), kBlock, 0, s>>>(
+        g->rowptr, p->split_row, p->n_split, p->S, p->split_seg_lo, p->split_seg_hi);
+    HGNN_LAUNCH_CHECK("split_segs_kernel");
+  }
+  st = compact_rows(BigPred{g->rowptr, p->big_deg}, g->nrows, &p->big_row, &p->n_big, s);
+  if (st != HGNN_OK) return st;
+  size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
+  if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
+  HGNN_HIP(hipStreamSynchronize(s));
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, hgnn_plan** out,
+                             void* stream) {
+  clear_error();
+  HGNN_REQUIRE(out != nullptr, HGNN_EINVAL, "hgnn_plan_create: out is NULL");
+  *out = nullptr;
+  hgnn_status st = check_csr_args(g, "hgnn_plan_create");
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(seg_edges >= 1 && seg_edges <= 2048, HGNN_EINVAL, "hgnn_plan_create: seg_edges = %d outside [1, 2048]",
+               seg_edges);
+  HGNN_REQUIRE(max_F >= 8 && max_F % 8 == 0, HGNN_EINVAL, "hgnn_plan_create: max_F = %d must be a positive multiple of 8",
+               max_F);
+  HGNN_REQUIRE(max_H >= 1, HGNN_EINVAL, "hgnn_plan_create: max_H = %d must be positive", max_H);
+  st = hgnn_csr_validate(g, stream);
+  if (st != HGNN_OK) return st;
+  hgnn_plan* p = new (std::nothrow) hgnn_plan();
+  HGNN_REQUIRE(p != nullptr, HGNN_ENOMEM, "hgnn_plan_create: host allocation failed");
+  p->nrows = g->nrows;
+  p->ncols = g->ncols;
+  p->nnz = g->nnz;
+  p->S = seg_edges;
+  p->nseg = ceil_div(g->nnz, seg_edges);
+  p->max_F = max_F;
+  p->max_H = max_H;
+  p->big_deg = 2048;
+  st = plan_build(p, g, static_cast<hipStream_t>(stream));
+  if (st != HGNN_OK) {
+    hgnn_plan_destroy(p);
+    return st;
+  }
+  *out = p;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_plan_export(const hgnn_plan* p, int32_t* seg_row_lo, int32_t* seg_row_hi, int32_t* split_row,
+                             int32_t* split_seg_lo, int32_t* split_seg_hi) {
+  clear_error();
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_plan_export: plan is NULL");
+  HGNN_HIP(hipDeviceSynchronize());
+  if (p->nseg > 0) {
+    if (seg_row_lo) HGNN_HIP(hipMemcpy(seg_row_lo, p->seg_row_lo, sizeof(int) * size_t(p->nseg), hipMemcpyDeviceToHost));
+    if (seg_row_hi) HGNN_HIP(hipMemcpy(seg_row_hi, p->seg_row_hi, sizeof(int) * size_t(p->nseg), hipMemcpyDeviceToHost));
+  }
+  if (p->n_split > 0) {
+    size_t b = sizeof(int) * size_t(p->n_split);
+    if (split_row) HGNN_HIP(hipMemcpy(split_row, p->split_row, b, hipMemcpyDeviceToHost));
+    if (split_seg_lo) HGNN_HIP(hipMemcpy(split_seg_lo, p->split_seg_lo, b, hipMemcpyDeviceToHost));
+    if (split_seg_hi) HGNN_HIP(hipMemcpy(split_seg_hi, p->split_seg_hi, b, hipMemcpyDeviceToHost));
+  }
+  return HGNN_OK;
+}
+
+}  // extern "C"

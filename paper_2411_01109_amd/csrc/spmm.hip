@@ -1,0 +1,504 @@
+// fp16 CSR SpMM for gfx950 (wave64): the vertex-parallel kernel behind hgnn_spmm and the
+// edge-parallel discretized-reduction kernels behind hgnn_spmm_discretized
+// (paper sections 2.1.2, 4.1, 5.2).
+//
+// Lane mapping (the wave64 form of the paper's sub-warps, section 4.1): a feature row of F
+// halves is covered by L = pow2 >= F/8 lanes that load 16 bytes (8 halves) each, so a wave
+// holds G = 64/L such groups and touches G different neighbour rows per load instruction.
+// Products are formed and accumulated in fp32 (v_fma_mix), fp16 only when a value is stored.
+#include "common.h"
+
+namespace hgnn {
+
+struct SpmmArgs {
+  const int* rowptr;
+  const int* col;
+  const int* erow;  // COO row ids (discretized kernels only)
+  const int* eid;
+  const half_t* w;  // [nnz][H] or nullptr
+  const half_t* X;
+  half_t* Y;
+  const float* row_scale;
+  int64_t ldx, ldy;
+  int64_t nnz;
+  int nrows;
+  int F, H, D;
+  int reduce;
+  // discretized kernels
+  int S;
+  int64_t nseg;
+  half_t* staging;  // [2*nseg][stage_ld]
+  int stage_ld;
+  const int* split_row;
+  const int* split_lo;
+  const int* split_hi;
+  int n_split;
+};
+
+__device__ __forceinline__ float scale_of(const SpmmArgs& a, int r) {
+  float s = 1.f;
+  if (a.reduce == HGNN_MEAN) {
+    int d = a.rowptr[r + 1] - a.rowptr[r];
+    s = 1.f / float(d > 1 ? d : 1);
+  }
+  if (a.row_scale) s *= a.row_scale[r];
+  return s;
+}
+
+__device__ __forceinline__ void store8(half_t* p, const float (&v)[8], float s) {
+  half8_t h;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
+  *reinterpret_cast<half8_t*>(p) = h;
+}
+
+__device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, float(x[i]), acc[i]);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Vertex-parallel SpMM: one wave per row; the G groups of the wave stride over the row's
+// non-zeros, then their fp32 partial vectors are added across groups with lane shuffles.
+// ---------------------------------------------------------------------------------------------------
+template <int L, bool HAS_W>
+__global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
+  constexpr int G = kWave / L;
+  constexpr int U = 4;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  if (row >= a.nrows) return;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int head = active ? f0 / a.D : 0;
+  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int k = beg + g; k < end; k += G * U) {
+    half8_t x[U];
+    float wv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kk = k + u * G;
+      x[u] = half8_t(0);
+      wv[u] = 0.f;
+      if (kk < end && active) {
+        const int c = a.col[kk];
+        x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0);
+        if (HAS_W) {
+          const int64_t slot = a.eid ? a.eid[kk] : kk;
+          wv[u] = float(a.w[slot * a.H + head]);
+        } else {
+          wv[u] = 1.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) fma8(acc, wv[u], x[u]);
+  }
+#pragma unroll
+  for (int off = L; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += __shfl_xor(acc[i], off);
+  }
+  if (g == 0 && active) store8(a.Y + row * a.ldy + f0, acc, scale_of(a, int(row)));
+}
+
+// Scalar path for shapes the 16-byte path cannot take: one thread per (row, feature).
+__global__ __launch_bounds__(kBlock) void spmm_scalar_kernel(SpmmArgs a) {
+  const int64_t idx = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  if (idx >= int64_t(a.nrows) * a.F) return;
+  const int row = int(idx / a.F), f = int(idx % a.F);
+  const int head = f / a.D;
+  float acc = 0.f;
+  for (int k = a.rowptr[row]; k < a.rowptr[row + 1]; ++k) {
+    float wv = 1.f;
+    if (a.w) {
+      const int64_t slot = a.eid ? a.eid[k] : k;
+      wv = float(a.w[slot * a.H + head]);
+    }
+    acc = fmaf(wv, float(a.X[int64_t(a.col[k]) * a.ldx + f]), acc);
+  }
+  a.Y[int64_t(row) * a.ldy + f] = half_t(acc * scale_of(a, row));
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Discretized-reduction SpMM, pass 1 (section 5.2): one wave per segment of S edges.
+//  phase 1  the wave loads the segment's column ids, row ids and edge values once, coalesced,
+//           into LDS (the two-phase load of section 4.1; LDS reads broadcast to a group);
+//  phase 2  group g walks its contiguous chunk of the segment with a running reduction; a row
+//           piece that starts and ends inside the chunk is scaled and stored straight to Y;
+//  merge    pieces that touch a chunk border are parked in LDS (fp32, scaled) and group 0 sews
+//           them together in order: rows that lie inside the segment are stored to Y, the piece
+//           entering from the previous segment and the piece leaving into the next go to the
+//           staging buffer as fp16 (each covers at most S edges, so it cannot overflow where
+//           S * max|w x| fits fp16).  No atomics; every Y row has exactly one writer.
+// The wave also zero-fills its share of the empty rows.
+// ---------------------------------------------------------------------------------------------------
+__host__ __device__ inline int align16i(int v) { return (v + 15) & ~15; }
+
+struct SegLds {
+  int col_off, row_off, w_off, vec_off, flag_off, total;
+};
+__host__ __device__ inline SegLds seg_lds_layout(int S, int H, bool has_w, int L) {
+  SegLds o;
+  const int G = kWave / L;
+  o.col_off = 0;
+  o.row_off = align16i(S * 4);
+  o.w_off = o.row_off + align16i((S + 2) * 4);
+  o.vec_off = o.w_off + (has_w ? align16i(S * H * 2) : 0);
+  o.flag_off = o.vec_off + 2 * G * 8 * L * 4;
+  o.total = o.flag_off + align16i(3 * G * 4);
+  return o;
+}
+
+template <int L, bool HAS_W>
+__global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
+  constexpr int G = kWave / L;
+  constexpr int U = 4;
+  constexpr int VEC = 8 * L;  // floats per parked vector
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int head = active ? f0 / a.D : 0;
+  const int S = a.S;
+  const SegLds lay = seg_lds_layout(S, a.H, HAS_W, L);
+  unsigned char* base = smem + size_t(wave) * lay.total;
+  int* s_col = reinterpret_cast<int*>(base + lay.col_off);
+  int* s_row = reinterpret_cast<int*>(base + lay.row_off);  // s_row[i+1] = row of edge i; [0] and [n+1] = neighbours
+  half_t* s_w = reinterpret_cast<half_t*>(base + lay.w_off);
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
+  int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
+  int* m_hrow = m_flag + G;
+  int* m_trow = m_hrow + G;
+
+  const int64_t wid = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int64_t seg = wid;
+  const bool valid = seg < a.nseg;
+  const int64_t e0 = seg * S;
+  const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+
+  // ---- phase 1: coalesced stage of the segment's graph data
+  for (int i = lane; i < n; i += kWave) {
+    const int64_t k = e0 + i;
+    s_col[i] = a.col[k];
+    s_row[i + 1] = a.erow[k];
+    if (HAS_W) {
+      const int64_t slot = a.eid ? a.eid[k] : k;
+      for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = a.w[slot * a.H + h];
+    }
+  }
+  if (lane == 0 && valid) {
+    s_row[0] = e0 > 0 ? a.erow[e0 - 1] : -1;
+    s_row[n + 1] = e0 + n < a.nnz ? a.erow[e0 + n] : -1;
+  }
+  if (lane < G) m_flag[lane] = 0;
+  __syncthreads();
+
+  // ---- phase 2: running reduction over this group's chunk
+  const int C = (S + G - 1) / G;
+  const int c0 = g * C < n ? g * C : n;
+  const int c1 = c0 + C < n ? c0 + C : n;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int cur = -1;
+  bool lo = false;  // current piece began before this chunk
+
+  auto flush = [&](bool ro) {
+    const float sc = scale_of(a, cur);
+    if (!lo && !ro) {
+      if (active) store8(a.Y + int64_t(cur) * a.ldy + f0, acc, sc);
+    } else {
+      const int slot = lo ? 2 * g : 2 * g + 1;
+      if (active) {
+        float* dst = m_vec + slot * VEC + f0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = acc[i] * sc;
+      }
+      if (l == 0) {
+        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
+        if (lo) m_hrow[g] = cur;
+        else m_trow[g] = cur;
+      }
+    }
+  };
+
+  if (c0 < c1) {
+    cur = s_row[c0 + 1];
+    lo = s_row[c0] == cur;
+  }
+  for (int i = c0; i < c1; i += U) {
+    half8_t x[U];
+    float wv[U];
+    int r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ii = i + u;
+      x[u] = half8_t(0);
+      wv[u] = 0.f;
+      r[u] = cur;
+      if (ii < c1) {
+        r[u] = s_row[ii + 1];
+        if (active) {
+          x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(s_col[ii]) * a.ldx + f0);
+          wv[u] = HAS_W ? float(s_w[ii * a.H + head]) : 1.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (i + u < c1) {
+        if (r[u] != cur) {
+          flush(false);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+          cur = r[u];
+          lo = false;
+        }
+        fma8(acc, wv[u], x[u]);
+      }
+    }
+  }
+  if (c0 < c1) flush(s_row[c1 + 1] == cur);
+  __syncthreads();
+
+  // ---- merge: group 0 sews the parked pieces together in chunk order
+  if (valid && g == 0) {
+    float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bool open = false, from_before = false;
+    int run_row = -1;
+    for (int gg = 0; gg < G; ++gg) {
+      const int fl = m_flag[gg];
+      if (fl & 1) {
+        if (active) {
+          const float* src = m_vec + (2 * gg) * VEC + f0;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] += src[i];
+        }
+        if (gg == 0) {
+          from_before = true;
+          open = true;
+          run_row = m_hrow[0];
+        }
+        if (!(fl & 2)) {  // the row ends inside chunk gg
+          if (active) {
+            if (from_before) store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
+            else store8(a.Y + int64_t(run_row) * a.ldy + f0, run, 1.f);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] = 0.f;
+          open = false;
+          from_before = false;
+        }
+      }
+      if (fl & 4) {
+        if (active) {
+          const float* src = m_vec + (2 * gg + 1) * VEC + f0;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] = src[i];
+        }
+        run_row = m_trow[gg];
+        open = true;
+        from_before = false;
+      }
+    }
+    if (open && active)  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
+      store8(a.staging + (2 * seg + (from_before ? 0 : 1)) * a.stage_ld + f0, run, 1.f);
+  }
+
+  // ---- zero-fill this wave's share of the empty rows
+  const int64_t nw = int64_t(gridDim.x) * kWavesPerBlock;
+  const int rpw = int((a.nrows + nw - 1) / nw);
+  const int64_t r0 = wid * rpw;
+  const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
+  if (active) {
+    for (int64_t r = r0 + g; r < r1; r += G)
+      if (a.rowptr[r] == a.rowptr[r + 1]) *reinterpret_cast<half8_t*>(a.Y + r * a.ldy + f0) = half8_t(0);
+  }
+}
+
+// Pass 2, the follow-up kernel (section 5.2.3): one group per split row adds the staged fp16
+// partials of that row in ascending segment order (fp32) and stores the row once.
+template <int L>
+__global__ __launch_bounds__(kBlock) void spmm_finish_kernel(SpmmArgs a) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const int64_t idx = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  if (idx >= a.n_split || f0 >= a.F) return;
+  const int r = a.split_row[idx];
+  const int64_t sa = a.split_lo[idx], sb = a.split_hi[idx];
+  float acc[8];
+  {
+    const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * sa + 1) * a.stage_ld + f0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = float(t[i]);
+  }
+  for (int64_t k = sa + 1; k <= sb; ++k) {
+    const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * k) * a.stage_ld + f0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += float(t[i]);
+  }
+  store8(a.Y + int64_t(r) * a.ldy + f0, acc, 1.f);
+}
+
+// ---------------------------------------------------------------------------------------------------
+static hgnn_status check_spmm_args(const char* who, const hgnn_csr* g, const hgnn_half* w, int H, const hgnn_half* X,
+                                   int64_t ldx, hgnn_half* Y, int64_t ldy, int F, hgnn_reduce op) {
+  hgnn_status st = check_csr_args(g, who);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(F > 0, HGNN_EINVAL, "%s: F = %d must be positive", who, F);
+  HGNN_REQUIRE(F % 2 == 0, HGNN_EINVAL, "%s: F = %d is odd; pad the feature length to the next even number", who, F);
+  HGNN_REQUIRE(H >= 1 && F % H == 0, HGNN_EINVAL, "%s: H = %d does not divide F = %d", who, H, F);
+  HGNN_REQUIRE(ldx >= F && ldy >= F, HGNN_EINVAL, "%s: leading dimension smaller than F", who);
+  HGNN_REQUIRE(ldx % 2 == 0 && ldy % 2 == 0, HGNN_EINVAL, "%s: odd leading dimension", who);
+  HGNN_REQUIRE(op == HGNN_SUM || op == HGNN_MEAN, HGNN_EINVAL, "%s: unknown reduce op %d", who, int(op));
+  HGNN_REQUIRE(g->nrows == 0 || Y != nullptr, HGNN_EINVAL, "%s: Y is NULL", who);
+  HGNN_REQUIRE(g->nnz == 0 || X != nullptr, HGNN_EINVAL, "%s: X is NULL", who);
+  (void)w;
+  return HGNN_OK;
+}
+
+static bool vector_path_ok(const hgnn_half* w, int H, const hgnn_half* X, int64_t ldx, const hgnn_half* Y, int64_t ldy,
+                           int F) {
+  if (F % 8 != 0 || F > 512 || ldx % 8 != 0 || ldy % 8 != 0) return false;
+  if (!aligned16(X) || !aligned16(Y)) return false;
+  if (w && H > 1 && (F / H) % 8 != 0) return false;
+  return true;
+}
+
+static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hgnn_half* X, int64_t ldx, hgnn_half* Y,
+                          int64_t ldy, int F, hgnn_reduce op, const float* row_scale) {
+  SpmmArgs a{};
+  a.rowptr = g->rowptr;
+  a.col = g->col;
+  a.erow = g->row;
+  a.eid = g->eid;
+  a.w = reinterpret_cast<const half_t*>(w);
+  a.X = reinterpret_cast<const half_t*>(X);
+  a.Y = reinterpret_cast<half_t*>(Y);
+  a.row_scale = row_scale;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.nnz = g->nnz;
+  a.nrows = g->nrows;
+  a.F = F;
+  a.H = w ? H : 1;  // without edge values the head structure is irrelevant
+  a.D = F / a.H;
+  a.reduce = int(op);
+  return a;
+}
+
+template <bool HAS_W>
+static void launch_row(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
+  switch (L) {
+    case 1: spmm_row_kernel<1, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    case 2: spmm_row_kernel<2, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: spmm_row_kernel<4, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: spmm_row_kernel<8, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: spmm_row_kernel<16, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: spmm_row_kernel<32, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+    default: spmm_row_kernel<64, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+template <bool HAS_W>
+static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a) {
+  switch (L) {
+    case 1: spmm_seg_kernel<1, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: spmm_seg_kernel<2, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: spmm_seg_kernel<4, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: spmm_seg_kernel<8, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: spmm_seg_kernel<16, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: spmm_seg_kernel<32, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    default: spmm_seg_kernel<64, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+  }
+}
+
+static void launch_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
+  switch (L) {
+    case 1: spmm_finish_kernel<1><<<grid, kBlock, 0, s>>>(a); break;
+    case 2: spmm_finish_kernel<2><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: spmm_finish_kernel<4><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: spmm_finish_kernel<8><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: spmm_finish_kernel<16><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: spmm_finish_kernel<32><<<grid, kBlock, 0, s>>>(a); break;
+    default: spmm_finish_kernel<64><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" {
+
+hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
+                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* stream) {
+  clear_error();
+  hgnn_status st = check_spmm_args("hgnn_spmm", g, edge_val, H, X, ldx, Y, ldy, F, op);
+  if (st != HGNN_OK) return st;
+  if (g->nrows == 0) return HGNN_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
+  if (vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
+    const int L = pow2_at_least(F / 8);
+    dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock)));
+    if (edge_val) launch_row<true>(L, grid, s, a);
+    else launch_row<false>(L, grid, s, a);
+    HGNN_LAUNCH_CHECK("spmm_row_kernel");
+  } else {
+    dim3 grid(unsigned(ceil_div(int64_t(g->nrows) * F, kBlock)));
+    spmm_scalar_kernel<<<grid, kBlock, 0, s>>>(a);
+    HGNN_LAUNCH_CHECK("spmm_scalar_kernel");
+  }
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                  const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                  hgnn_reduce op, const float* row_scale, void* stream) {
+  clear_error();
+  hgnn_status st = check_spmm_args("hgnn_spmm_discretized", g, edge_val, H, X, ldx, Y, ldy, F, op);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_spmm_discretized: plan is NULL");
+  HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
+               "hgnn_spmm_discretized: the plan was built for another graph");
+  HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "hgnn_spmm_discretized: F = %d exceeds the plan's max_F = %d", F, p->max_F);
+  HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
+               "hgnn_spmm_discretized: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y");
+  if (g->nrows == 0) return HGNN_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
+  a.erow = g->row ? g->row : p->edge_row;
+  a.S = p->S;
+  a.nseg = p->nseg;
+  a.staging = reinterpret_cast<half_t*>(p->staging);
+  a.stage_ld = p->max_F;
+  a.split_row = p->split_row;
+  a.split_lo = p->split_seg_lo;
+  a.split_hi = p->split_seg_hi;
+  a.n_split = p->n_split;
+  const int L = pow2_at_least(F / 8);
+  const SegLds lay = seg_lds_layout(a.S, a.H, edge_val != nullptr, L);
+  const size_t lds = size_t(lay.total) * kWavesPerBlock;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
+               a.H, lds);
+  const int64_t nblk = ceil_div(p->nseg, kWavesPerBlock);
+  dim3 grid(unsigned(nblk > 0 ? nblk : 1));
+  if (edge_val) launch_seg<true>(L, grid, lds, s, a);
+  else launch_seg<false>(L, grid, lds, s, a);
+  HGNN_LAUNCH_CHECK("spmm_seg_kernel");
+  if (a.n_split > 0) {
+    const int G = kWave / L;
+    dim3 grid2(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * G)));
+    launch_finish(L, grid2, s, a);
+    HGNN_LAUNCH_CHECK("spmm_finish_kernel");
+  }
+  return HGNN_OK;
+}
+
+}  // extern "C"

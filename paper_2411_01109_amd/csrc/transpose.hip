@@ -1,0 +1,92 @@
+// CSR of the transposed graph plus the edge-id map, for the backward SpMM dX <- A_w^T dY
+// (paper section 2.1.2).  One-off set-up: a stable radix sort of the non-zeros by column id
+// (rocPRIM's device radix sort is the library step), then offsets by binary search.
+#include <string.h>
+
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include "common.h"
+
+namespace hgnn {
+
+__global__ void iota_kernel(int* __restrict__ v, int64_t n) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k < n) v[k] = int(k);
+}
+
+// rowptr_T[j] = number of non-zeros whose column is < j = lower bound of j in the sorted column keys
+__global__ void offsets_kernel(const int* __restrict__ sorted_col, int64_t nnz, int ncols, int* __restrict__ rowptr_T) {
+  int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (j > ncols) return;
+  int64_t lo = 0, hi = nnz;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if (sorted_col[mid] < j) lo = mid + 1;
+    else hi = mid;
+  }
+  rowptr_T[j] = int(lo);
+}
+
+// col_T[k'] = row of the non-zero eid_T[k'] of A (upper bound over rowptr, minus one)
+__global__ void source_rows_kernel(const int* __restrict__ rowptr, int nrows, const int* __restrict__ eid_T, int64_t nnz,
+                                   int* __restrict__ col_T) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k >= nnz) return;
+  const int e = eid_T[k];
+  int lo = 0, hi = nrows + 1;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (rowptr[mid] <= e) lo = mid + 1;
+    else hi = mid;
+  }
+  col_T[k] = lo - 1;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T, int32_t* eid_T,
+                                      void* stream) {
+  clear_error();
+  hgnn_status st = check_csr_args(g, "hgnn_transpose");
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(g->eid == nullptr, HGNN_EINVAL, "hgnn_transpose: the input graph must not carry an edge-id map");
+  HGNN_REQUIRE(rowptr_T != nullptr, HGNN_EINVAL, "hgnn_transpose: rowptr_T is NULL");
+  HGNN_REQUIRE(g->nnz == 0 || (col_T && eid_T), HGNN_EINVAL, "hgnn_transpose: col_T or eid_T is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t E = g->nnz;
+  if (E == 0) {
+    HGNN_HIP(hipMemsetAsync(rowptr_T, 0, sizeof(int) * (size_t(g->ncols) + 1), s));
+    HGNN_HIP(hipStreamSynchronize(s));
+    return HGNN_OK;
+  }
+  int bits = 1;
+  while ((int64_t(1) << bits) < int64_t(g->ncols)) ++bits;
+  int *ids = nullptr, *keys_out = nullptr;
+  void* tmp = nullptr;
+  size_t tmp_bytes = 0;
+  hgnn_status rc = HGNN_OK;
+  hipError_t e = hipMalloc(&ids, sizeof(int) * size_t(E));
+  if (e == hipSuccess) e = hipMalloc(&keys_out, sizeof(int) * size_t(E));
+  if (e == hipSuccess) {
+    iota_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(ids, E);
+    e = rocprim::radix_sort_pairs(nullptr, tmp_bytes, g->col, keys_out, ids, eid_T, size_t(E), 0u, unsigned(bits), s);
+  }
+  if (e == hipSuccess) e = hipMalloc(&tmp, tmp_bytes > 0 ? tmp_bytes : 16);
+  if (e == hipSuccess)
+    e = rocprim::radix_sort_pairs(tmp, tmp_bytes, g->col, keys_out, ids, eid_T, size_t(E), 0u, unsigned(bits), s);
+  if (e == hipSuccess) {
+    offsets_kernel<<<dim3(unsigned(ceil_div(int64_t(g->ncols) + 1, kBlock))), kBlock, 0, s>>>(keys_out, E, g->ncols,
+                                                                                               rowptr_T);
+    source_rows_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, eid_T, E, col_T);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess)
+    rc = fail(e == hipErrorOutOfMemory ? HGNN_ENOMEM : HGNN_EHIP, "hgnn_transpose: %s", hipGetErrorString(e));
+  (void)hipFree(ids);
+  (void)hipFree(keys_out);
+  (void)hipFree(tmp);
+  return rc;
+}

@@ -35,3 +35,21 @@ def parse_golden(name):
 @pytest.fixture(scope="session")
 def golden5():
     return parse_golden("five_vertex.txt")
+
+
+@pytest.fixture(scope="session")
+def hgnn():
+    """The GPU binding with the library loaded (built first only when nothing is built)."""
+    import __graft_entry__ as ge
+    ge.ensure_built()
+    import paper_2411_01109_amd as mod
+    mod.load()
+    return mod
+
+
+@pytest.fixture(scope="session")
+def dev():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")

@@ -1,0 +1,49 @@
+"""Shared helpers of the GPU parity tests: device upload and the comparison rule."""
+import numpy as np
+
+REL_L2 = 5e-3      # ||y - ref||_2 / ||ref||_2
+REL_ELEM = 2e-2    # elementwise relative error
+FP16_MAX = 65504.0
+
+
+def compare(name, got16, ref, sabs=None, rel_l2=REL_L2, rel_elem=REL_ELEM, check_finite=True):
+    """got16: numpy float16 from the GPU; ref: float64 oracle values; sabs: oracle's sum of |terms|
+    (natural magnitude).  Elementwise rule: |y - ref| <= rel_elem*|ref| + 2^-11 * sabs, i.e. the stated
+    relative bound plus one fp16 rounding at the magnitude the sum passed through (a pure relative
+    bound cannot be met next to zero by any fp16 output).  Entries whose fp64 value does not fit fp16
+    are excluded from the value checks and must be +-inf with the right sign."""
+    got = got16.astype(np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    fits = np.abs(ref) <= FP16_MAX
+    if check_finite:
+        bad = ~np.isfinite(got) & (np.abs(ref) <= FP16_MAX * (1 - 2.0 ** -10))
+        assert not bad.any(), f"{name}: {int(bad.sum())} non-finite outputs where the exact value fits fp16"
+        fits &= np.isfinite(got)  # within a rounding step of the largest finite value either outcome is legitimate
+    over = np.abs(ref) >= 65520.0 * (1 + 2.0 ** -10)  # clearly beyond the range: must be inf of the right sign
+    if over.any():
+        assert np.all(np.isinf(got[over]) & (np.sign(got[over]) == np.sign(ref[over]))), f"{name}: overflow entries"
+    over = np.abs(ref) > FP16_MAX
+    g, r = got[fits], ref[fits]
+    if r.size == 0:
+        return {"rel_l2": 0.0, "max_rel": 0.0, "n_over": int(over.sum())}
+    denom = np.linalg.norm(r)
+    l2 = np.linalg.norm(g - r) / denom if denom > 0 else np.linalg.norm(g - r)
+    assert l2 <= rel_l2, f"{name}: rel-L2 {l2:.3e} > {rel_l2}"
+    floor = (2.0 ** -11) * (sabs[fits] if sabs is not None else np.abs(r)) + 2.0 ** -24
+    err = np.abs(g - r)
+    viol = err > rel_elem * np.abs(r) + floor
+    assert not viol.any(), (f"{name}: {int(viol.sum())} elements beyond tolerance; worst abs err "
+                            f"{err[viol].max():.3e} at ref {r[viol][np.argmax(err[viol])]:.3e}")
+    nz = np.abs(r) > 0
+    strict = np.max(err[nz] / np.abs(r[nz])) if nz.any() else 0.0
+    return {"rel_l2": float(l2), "max_rel": float(strict), "n_over": int(over.sum())}
+
+
+def sample_rows(rowptr, n, seed, extra_top=8):
+    """n random rows plus the extra_top longest rows (hubs), sorted unique."""
+    rng = np.random.default_rng(seed)
+    V = rowptr.size - 1
+    deg = np.diff(rowptr)
+    pick = rng.integers(0, V, size=min(n, V))
+    top = np.argsort(deg)[-extra_top:]
+    return np.unique(np.concatenate([pick, top])).astype(np.int32)

@@ -1,0 +1,105 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib(hgnn):
+    return hgnn.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hgnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hgnn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib, hgnn):
+    names = declared_symbols()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(hgnn.EXPORTS) == names  # the Python binding covers exactly the declared entry points
+
+
+def test_status_strings(lib):
+    for code in range(5):
+        assert lib.hgnn_status_str(code).decode().startswith("HGNN_")
+    assert b"unknown" in lib.hgnn_status_str(99)
+
+
+def make_csr(hgnn, nrows=4, ncols=4, nnz=8, rowptr=0x1000, col=0x2000):
+    from paper_2411_01109_amd.binding import _CsrStruct
+    return _CsrStruct(nrows, ncols, nnz, rowptr, col, None, None)
+
+
+def test_argument_errors_are_caught_on_the_host(lib, hgnn):
+    """Fake non-NULL device addresses: every call below must return before touching the GPU."""
+    g = make_csr(hgnn)
+    X, Y = 0x10000, 0x20000
+    EINVAL, EUNSUP = hgnn.HGNN_EINVAL, hgnn.HGNN_EUNSUPPORTED
+    call = lambda *a: lib.hgnn_spmm(ctypes.byref(g), None, 1, *a)
+    assert call(X, 8, Y, 8, 7, 0, None, None) == EINVAL          # odd F: pad to even (section 4.1)
+    assert b"odd" in lib.hgnn_last_error()
+    assert call(X, 8, Y, 8, 0, 0, None, None) == EINVAL          # F <= 0
+    assert call(X, 4, Y, 8, 8, 0, None, None) == EINVAL          # ldx < F
+    assert call(X, 8, Y, 8, 8, 5, None, None) == EINVAL          # unknown reduce op
+    assert call(None, 8, Y, 8, 8, 0, None, None) == EINVAL       # X NULL with nnz > 0
+    assert call(X, 8, None, 8, 8, 0, None, None) == EINVAL       # Y NULL
+    assert lib.hgnn_spmm(ctypes.byref(g), None, 3, X, 8, Y, 8, 8, 0, None, None) == EINVAL  # H does not divide F
+    assert lib.hgnn_spmm(None, None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL             # graph NULL
+    bad = make_csr(hgnn, rowptr=None)
+    assert lib.hgnn_spmm(ctypes.byref(bad), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    big = make_csr(hgnn, nnz=1 << 31)
+    assert lib.hgnn_spmm(ctypes.byref(big), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    # discretized: plan required
+    assert lib.hgnn_spmm_discretized(None, ctypes.byref(g), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    # sddmm / softmax
+    sd = lambda *a: lib.hgnn_sddmm(ctypes.byref(g), None, *a)
+    assert sd(0, 1, 7, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # odd F
+    assert sd(7, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # unknown op
+    assert sd(0, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # no COO rows and no plan
+    assert b"COO" in lib.hgnn_last_error()
+    assert sd(1, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # GAT score without a_l / a_r
+    assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 0, X, Y, None) == EINVAL
+    assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 1, None, Y, None) == EINVAL
+    assert lib.hgnn_edge_softmax_bwd(ctypes.byref(g), None, 1, X, None, None, 0.2, Y, None) == EINVAL
+    assert lib.hgnn_edge_rowsum(ctypes.byref(g), 0, X, Y, None) == EINVAL
+    eidg = make_csr(hgnn)
+    eidg.eid = 0x3000
+    assert lib.hgnn_edge_softmax(ctypes.byref(eidg), None, 1, X, Y, None) == EUNSUP
+    # plan_create argument checks come before any device work
+    out = ctypes.c_void_p()
+    assert lib.hgnn_plan_create(ctypes.byref(g), 0, 64, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 4096, 64, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 12, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 64, 1, None, None) == EINVAL
+    assert out.value is None
+    lib.hgnn_plan_destroy(None)  # no-op
+    assert lib.hgnn_plan_num_segments(None) == 0
+
+
+def test_binding_refuses_cpu_tensors(hgnn):
+    import torch
+    with pytest.raises(TypeError):
+        hgnn.Csr(torch.zeros(3, dtype=torch.int32), torch.zeros(2, dtype=torch.int32))
+
+
+def test_product_path_has_no_oracle_or_fallback():
+    """Neither the package nor bench's product leg may import the oracle; the oracle must not import the package."""
+    pkg = os.path.join(ROOT, "paper_2411_01109_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2411_01109_amd" not in text and "libhgnn" not in text and "hgnn.h" not in text, f

@@ -1,0 +1,414 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU fp64 oracle, element by element,
+on seeded inputs that span several tiles and ragged tails, plus the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from parity import compare, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def down(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def rand_graph(V, ncols, avg_deg, seed, hubs=(), empties=()):
+    r = np.random.default_rng(seed)
+    deg = r.poisson(avg_deg, size=V)
+    for i, d in hubs:
+        deg[i] = d
+    for i in empties:
+        deg[i] = 0
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    col = r.integers(0, ncols, size=int(rowptr[-1])).astype(np.int32)
+    for i in range(V):  # ascending inside a row
+        col[rowptr[i]:rowptr[i + 1]].sort()
+    return rowptr, col
+
+
+def f16(a):
+    return wl.to_f16(np.asarray(a, dtype=np.float64))
+
+
+# ------------------------------------------------------------------ plan and transpose: bit exact
+@pytest.mark.parametrize("S", [1, 7, 64, 128, 256, 512, 2048])
+def test_plan_bit_exact(hgnn, dev, S):
+    print(f"plan S={S}", flush=True)
+    rowptr, col = rand_graph(3000, 3000, 9, 1, hubs=((17, 5000), (2999, 700)), empties=(0, 18, 2998))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, S, 64, 4)
+    got = hgnn.hgnn_plan_export(p)
+    ref = oracle.segment_plan(rowptr, S)
+    for k in ref:
+        assert np.array_equal(got[k], ref[k]), k
+    assert hgnn.hgnn_plan_seg_edges(p) == S
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_plan_degenerate_graphs(hgnn, dev):
+    # no edges at all
+    rowptr = np.zeros(11, dtype=np.int32)
+    g = hgnn.Csr(up(rowptr, dev), torch.empty(0, dtype=torch.int32, device=dev))
+    p = hgnn.hgnn_plan_create(g, 256, 64, 1)
+    assert hgnn.hgnn_plan_num_segments(p) == 0 and hgnn.hgnn_plan_num_split_rows(p) == 0
+    Y = torch.full((10, 64), 3.0, dtype=torch.float16, device=dev)
+    X = torch.ones((10, 64), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized(p, g, None, 1, X, Y)
+    assert np.all(down(Y) == 0)
+    Y.fill_(3.0)
+    hgnn.hgnn_spmm(g, None, 1, X, Y)
+    assert np.all(down(Y) == 0)
+    # one segment holding everything (S >= E): no split rows
+    rowptr, col = rand_graph(20, 20, 3, 5)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 2048, 64, 1)
+    assert hgnn.hgnn_plan_num_segments(p) == 1 and hgnn.hgnn_plan_num_split_rows(p) == 0
+
+
+def test_validate_rejects_broken_graphs(hgnn, dev):
+    rowptr, col = rand_graph(50, 50, 4, 3)
+    good = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    hgnn.hgnn_csr_validate(good)
+    bad_col = col.copy()
+    bad_col[5] = 50
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_csr_validate(hgnn.Csr(up(rowptr, dev), up(bad_col, dev)))
+    assert ei.value.status == hgnn.HGNN_EINVAL and "column" in str(ei.value)
+    bad_ptr = rowptr.copy()
+    bad_ptr[10], bad_ptr[11] = bad_ptr[11], bad_ptr[10] - 1
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_plan_create(hgnn.Csr(up(bad_ptr, dev), up(col, dev)), 256, 64, 1)
+    short = rowptr.copy()
+    short[-1] -= 1
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_csr_validate(hgnn.Csr(up(short, dev), up(col, dev)))
+
+
+def test_transpose_bit_exact(hgnn, dev):
+    rowptr, col = rand_graph(2500, 1800, 7, 2, hubs=((3, 4000),), empties=(0, 9))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=1800)
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = oracle.transpose(rowptr, col, 1800)
+    assert np.array_equal(down(gt.rowptr), rT)
+    assert np.array_equal(down(gt.col), cT)
+    assert np.array_equal(down(gt.eid), eT)
+    assert gt.nrows == 1800 and gt.ncols == 2500
+
+
+# ------------------------------------------------------------------ SpMM shapes
+SHAPES = [  # (F, H, has_w, reduce, S, pad)
+    (64, 1, True, 0, 256, 0), (64, 1, False, 1, 128, 0), (128, 1, True, 0, 256, 8), (32, 1, True, 1, 64, 0),
+    (16, 1, False, 0, 512, 0), (8, 1, True, 0, 7, 0), (256, 1, False, 0, 256, 0), (512, 1, True, 1, 1024, 0),
+    (64, 4, True, 0, 256, 0), (128, 8, True, 1, 100, 0), (48, 1, True, 0, 256, 0), (96, 2, True, 0, 33, 16),
+    (24, 3, True, 0, 256, 0), (64, 1, True, 0, 1, 0),
+]
+
+
+@pytest.mark.parametrize("F,H,has_w,reduce,S,pad", SHAPES)
+def test_spmm_plain_and_discretized_shapes(hgnn, dev, F, H, has_w, reduce, S, pad):
+    print(f"spmm F={F} H={H} w={has_w} reduce={reduce} S={S} pad={pad}", flush=True)
+    V, ncols = 1237, 997
+    rowptr, col = rand_graph(V, ncols, 11, F + S, hubs=((5, 3000), (700, 777), (1236, 300)), empties=(0, 6, 1235))
+    E = col.size
+    r = np.random.default_rng(F * 7 + H)
+    Xh = f16(r.standard_normal((ncols, F + pad)))
+    w = f16(r.standard_normal((E, H))) if has_w else None
+    rs = r.uniform(0.5, 2.0, V).astype(np.float32)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    Xd = up(Xh, dev)[:, :F]
+    wd = None if w is None else up(w, dev)
+    ref, sabs = oracle.spmm(rowptr, col, Xh[:, :F], w=w, H=H, reduce=reduce, row_scale=rs.astype(np.float64),
+                            want_sabs=True)
+    Yfull = torch.full((V, F + pad), 7.0, dtype=torch.float16, device=dev)
+    Y = Yfull[:, :F]
+    hgnn.hgnn_spmm(g, wd, H, Xd, Y, op=reduce, row_scale=up(rs, dev))
+    compare("plain", down(Y), ref, sabs)
+    if pad:
+        assert np.all(down(Yfull)[:, F:] == 7.0)  # padding columns untouched
+    p = hgnn.hgnn_plan_create(g, S, max(F, 8), H)
+    Y.fill_(7.0)
+    hgnn.hgnn_spmm_discretized(p, g, wd, H, Xd, Y, op=reduce, row_scale=up(rs, dev))
+    got = down(Y)
+    compare("discretized", got, ref, sabs)
+    Y.fill_(-3.0)
+    hgnn.hgnn_spmm_discretized(p, g, wd, H, Xd, Y, op=reduce, row_scale=up(rs, dev))
+    assert np.array_equal(down(Y).view(np.uint16), got.view(np.uint16))  # deterministic, no atomics
+    if pad:
+        assert np.all(down(Yfull)[:, F:] == 7.0)
+
+
+@pytest.mark.parametrize("F,H", [(2, 1), (6, 3), (10, 1), (64, 16)])
+def test_spmm_scalar_path_and_unsupported(hgnn, dev, F, H):
+    V = 300
+    rowptr, col = rand_graph(V, V, 6, 4, empties=(3,))
+    r = np.random.default_rng(F)
+    Xh, w = f16(r.standard_normal((V, F))), f16(r.standard_normal((col.size, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm(g, up(w, dev), H, up(Xh, dev), Y)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, want_sabs=True)
+    compare("scalar", down(Y), ref, sabs)
+    p = hgnn.hgnn_plan_create(g, 64, 64, 16)
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_spmm_discretized(p, g, up(w, dev), H, up(Xh, dev), Y)
+    assert ei.value.status == hgnn.HGNN_EUNSUPPORTED
+
+
+def test_plan_mismatch_is_rejected(hgnn, dev):
+    rowptr, col = rand_graph(100, 100, 5, 1)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    rowptr2, col2 = rand_graph(101, 101, 5, 2)
+    g2 = hgnn.Csr(up(rowptr2, dev), up(col2, dev))
+    p = hgnn.hgnn_plan_create(g, 64, 64, 1)
+    X = torch.zeros((101, 64), dtype=torch.float16, device=dev)
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_spmm_discretized(p, g2, None, 1, X, X.clone())
+    with pytest.raises(hgnn.HgnnError):  # F above the plan's max_F
+        hgnn.hgnn_spmm_discretized(p, g, None, 1, torch.zeros((100, 128), dtype=torch.float16, device=dev),
+                                   torch.zeros((100, 128), dtype=torch.float16, device=dev))
+
+
+# ------------------------------------------------------------------ config 1: GCN, forward and backward
+def test_config1_gcn_forward_backward(hgnn, dev):
+    w = wl.gcn_tiny()
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    ew = w.tensors["w"].reshape(-1, 1)
+    X, dY, ewd = up(w.tensors["X"], dev), up(w.tensors["dY"], dev), up(ew, dev)
+    p = hgnn.hgnn_plan_create(g, 256, 64, 1)
+    pt = hgnn.hgnn_plan_create(gt, 256, 64, 1)
+    ref_f, sabs_f = oracle.spmm(w.rowptr, w.col, w.tensors["X"], w=ew, want_sabs=True)
+    ref_b = oracle.spmm_T_scatter(w.rowptr, w.col, w.tensors["dY"], w.V, w=ew)  # no transposed graph involved
+    rT, cT, eT = oracle.transpose(w.rowptr, w.col, w.V)
+    _, sabs_b = oracle.spmm(rT, cT, w.tensors["dY"], w=ew, eid=eT, want_sabs=True)
+    Y = torch.empty_like(X)
+    for name, fn in (("plain", lambda G, P, A, B: hgnn.hgnn_spmm(G, ewd, 1, A, B)),
+                     ("disc", lambda G, P, A, B: hgnn.hgnn_spmm_discretized(P, G, ewd, 1, A, B))):
+        fn(g, p, X, Y)
+        s = compare(f"c1 fwd {name}", down(Y), ref_f, sabs_f)
+        fn(gt, pt, dY, Y)
+        s2 = compare(f"c1 bwd {name}", down(Y), ref_b, sabs_b)
+        print(f"c1 {name}: fwd {s} bwd {s2}", flush=True)
+
+
+# ------------------------------------------------------------------ config 2: overflow stress
+@pytest.mark.parametrize("positive", [False, True])
+def test_config2_gin_overflow(hgnn, dev, positive):
+    w = wl.gin_overflow(positive=positive)
+    print(f"c2 positive={positive} E={w.E} max deg={np.diff(w.rowptr).max()}", flush=True)
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    X = up(w.tensors["X"], dev)
+    p = hgnn.hgnn_plan_create(g, 256, 128, 1)
+    Y = torch.empty_like(X)
+    ref_sum, sabs = oracle.spmm(w.rowptr, w.col, w.tensors["X"], want_sabs=True)
+    ref_mean = ref_sum / np.maximum(np.diff(w.rowptr), 1)[:, None]
+    sabs_mean = sabs / np.maximum(np.diff(w.rowptr), 1)[:, None]
+    hgnn.hgnn_spmm(g, None, 1, X, Y)
+    s_plain = compare("c2 plain sum", down(Y), ref_sum, sabs)
+    hgnn.hgnn_spmm_discretized(p, g, None, 1, X, Y)
+    s_disc = compare("c2 disc sum", down(Y), ref_sum, sabs)
+    hgnn.hgnn_spmm_discretized(p, g, None, 1, X, Y, op=hgnn.HGNN_MEAN)
+    got_mean = down(Y)
+    s_mean = compare("c2 disc mean", got_mean, ref_mean, sabs_mean)
+    assert np.isfinite(got_mean.astype(np.float64)).all()          # zero fp16 overflow with per-batch scaling
+    print(f"c2 positive={positive}: plain {s_plain} disc {s_disc} mean {s_mean}", flush=True)
+    if positive:
+        # the hub sums do not fit fp16 at all (the overflow the paper describes for post-reduction scaling) ...
+        assert s_disc["n_over"] > 0 and np.abs(ref_sum).max() > 65504
+        # ... while every staged partial is bounded by S * max|x| and the mean is finite everywhere
+        _, maxpart = oracle.spmm_discretized(w.rowptr, w.col, w.tensors["X"], 256,
+                                             rows=sample_rows(w.rowptr, 64, 1))
+        assert maxpart <= 256 * 8
+    # backward on the transposed graph
+    gt = hgnn.hgnn_transpose(g)
+    pt = hgnn.hgnn_plan_create(gt, 256, 128, 1)
+    dY = up(w.tensors["dY"], dev)
+    hgnn.hgnn_spmm_discretized(pt, gt, None, 1, dY, Y, op=hgnn.HGNN_MEAN)
+    rows = sample_rows(down(gt.rowptr), 3000, 2)
+    refb, sabsb = oracle.spmm(down(gt.rowptr), down(gt.col), w.tensors["dY"], reduce=oracle.MEAN, rows=rows, want_sabs=True)
+    compare("c2 bwd mean", down(Y)[rows], refb, sabsb)
+
+
+# ------------------------------------------------------------------ SDDMM, softmax, GAT
+@pytest.mark.parametrize("H,D", [(1, 64), (4, 16), (2, 8), (1, 128), (8, 8), (3, 16), (1, 6), (2, 24)])
+def test_sddmm_dot_and_score(hgnn, dev, H, D):
+    print(f"sddmm H={H} D={D}", flush=True)
+    V, ncols, F = 777, 555, H * D
+    rowptr, col = rand_graph(V, ncols, 9, H * 100 + D, hubs=((9, 2000),), empties=(0, 776))
+    r = np.random.default_rng(D)
+    U, Vt = f16(r.standard_normal((V, F))), f16(r.standard_normal((ncols, F)))
+    al, ar = f16(0.3 * r.standard_normal((H, D))), f16(0.3 * r.standard_normal((H, D)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    p = hgnn.hgnn_plan_create(g, 256, 64, 8)
+    out = torch.empty((col.size, H), dtype=torch.float16, device=dev)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, up(U, dev), up(Vt, dev), out)
+    ref = oracle.sddmm_dot(rowptr, col, U, Vt, H=H)
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    mag = np.einsum("ehd,ehd->eh", np.abs(U.astype(np.float64)).reshape(V, H, D)[row],
+                    np.abs(Vt.astype(np.float64)).reshape(ncols, H, D)[col])
+    compare("dot", down(out), ref, mag)
+    # GAT score needs both sides on the same vertex set
+    rowptr2, col2 = rand_graph(V, V, 9, H + D, hubs=((9, 2000),))
+    g2 = hgnn.Csr(up(rowptr2, dev), up(col2, dev))
+    p2 = hgnn.hgnn_plan_create(g2, 256, 64, 8)
+    out2 = torch.empty((col2.size, H), dtype=torch.float16, device=dev)
+    ref2 = oracle.gat_score(rowptr2, col2, U, al, ar, H)
+    aU = np.abs(U.astype(np.float64)).reshape(V, H, D)
+    mag2 = (np.einsum("vhd,hd->vh", aU, np.abs(al.astype(np.float64)))[np.repeat(np.arange(V), np.diff(rowptr2))] +
+            np.einsum("vhd,hd->vh", aU, np.abs(ar.astype(np.float64)))[col2])
+    hgnn.hgnn_sddmm(g2, p2, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, up(U, dev), up(U, dev), out2, up(al, dev), up(ar, dev), 0.2)
+    fact = down(out2).copy()
+    compare("score factorised", fact, ref2, mag2)
+    # without a plan: COO rows supplied by the caller, per-edge evaluation
+    row2 = np.repeat(np.arange(V), np.diff(rowptr2)).astype(np.int32)
+    g3 = hgnn.Csr(up(rowptr2, dev), up(col2, dev), row=up(row2, dev))
+    out2.zero_()
+    hgnn.hgnn_sddmm(g3, None, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, up(U, dev), up(U, dev), out2, up(al, dev), up(ar, dev), 0.2)
+    compare("score direct", down(out2), ref2, mag2)
+
+
+@pytest.mark.parametrize("H", [1, 2, 4, 8, 3])
+def test_edge_softmax_forward_backward(hgnn, dev, H):
+    print(f"softmax H={H}", flush=True)
+    V = 900
+    rowptr, col = rand_graph(V, V, 12, 40 + H, hubs=((4, 9000), (500, 2100), (899, 300)), empties=(0, 5))
+    E = col.size
+    r = np.random.default_rng(H)
+    e16 = f16(3 * r.standard_normal((E, H)))
+    da16 = f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, 64, 8)
+    ref_a = oracle.edge_softmax(rowptr, e16.astype(np.float64))
+    for plan in (p, None):  # with the long-row kernel and without
+        alpha = torch.full((E, H), -1.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_softmax(g, plan, H, up(e16, dev), alpha)
+        got = down(alpha).astype(np.float64)
+        assert np.all(got >= 0) and np.all(got <= 1)
+        assert np.abs(got - ref_a).max() <= 2.0 ** -11 + 1e-3 * ref_a.max()
+        compare("alpha", down(alpha), ref_a, np.maximum(ref_a, 2.0 ** -14), rel_elem=2e-2)
+        rows = np.repeat(np.arange(V), np.diff(rowptr))
+        sums = np.zeros((V, H))
+        np.add.at(sums, rows, got)
+        deg = np.diff(rowptr)
+        assert np.all(np.abs(sums[deg > 0] - 1) <= 1e-3 + deg[deg > 0, None] * 2.0 ** -24)
+        # backward consumes the GPU's own fp16 alpha (what a layer would have kept from forward)
+        a16 = down(alpha)
+        for with_e in (False, True):
+            de = torch.empty((E, H), dtype=torch.float16, device=dev)
+            hgnn.hgnn_edge_softmax_bwd(g, plan, H, alpha, up(da16, dev), de, e=up(e16, dev) if with_e else None)
+            ref_de = oracle.edge_softmax_bwd(rowptr, a16.astype(np.float64), da16.astype(np.float64),
+                                             e=e16.astype(np.float64) if with_e else None)
+            t_abs = np.zeros((V, H))
+            np.add.at(t_abs, rows, np.abs(a16.astype(np.float64) * da16.astype(np.float64)))
+            mag = a16.astype(np.float64) * (np.abs(da16.astype(np.float64)) + t_abs[rows])
+            compare(f"de with_e={with_e}", down(de), ref_de, mag + 2.0 ** -14)
+
+
+@pytest.mark.parametrize("H", [1, 4, 3])
+def test_edge_rowsum_rows_and_columns(hgnn, dev, H):
+    V, ncols = 600, 450
+    rowptr, col = rand_graph(V, ncols, 8, 60 + H, hubs=((7, 5000),), empties=(1,))
+    E = col.size
+    t16 = f16(np.random.default_rng(H).standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    td = up(t16, dev)
+    out_r = torch.empty((V, H), dtype=torch.float16, device=dev)
+    out_c = torch.empty((ncols, H), dtype=torch.float16, device=dev)
+    hgnn.hgnn_edge_rowsum(g, H, td, out_r)
+    hgnn.hgnn_edge_rowsum(gt, H, td, out_c)
+    t64 = t16.astype(np.float64)
+    compare("rowsum", down(out_r), oracle.edge_rowsum(rowptr, t64), oracle.edge_rowsum(rowptr, np.abs(t64)))
+    compare("colsum", down(out_c), oracle.edge_colsum(rowptr, col, t64, ncols),
+            oracle.edge_colsum(rowptr, col, np.abs(t64), ncols))
+
+
+def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat"):
+    """GAT forward (score, softmax, weighted SpMM) and backward (transposed SpMM, SDDMM dot, softmax and
+    score backward, row / column sums) against the oracle, each stage fed with the GPU's own fp16
+    output of the stage before (the state tensors a layer keeps)."""
+    V, F = w.V, H * D
+    feat = w.tensors["h"] if "h" in w.tensors else w.tensors["X"]
+    dOut = w.tensors["dOut"] if "dOut" in w.tensors else w.tensors["dY"]
+    al, ar = w.tensors["a_l"], w.tensors["a_r"]
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, F, H)
+    gt = hgnn.hgnn_transpose(g)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    E = w.E
+    hd, dOd = up(feat, dev), up(dOut, dev)
+    e = torch.empty((E, H), dtype=torch.float16, device=dev)
+    alpha = torch.empty_like(e)
+    out = torch.empty_like(hd)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, hd, hd, e, up(al, dev), up(ar, dev), 0.2)
+    hgnn.hgnn_edge_softmax(g, p, H, e, alpha)
+    hgnn.hgnn_spmm_discretized(p, g, alpha, H, hd, out)
+    rows = sample_rows(w.rowptr, 4000, 3) if rows_fwd is None else rows_fwd
+    deg = np.diff(w.rowptr)
+    esel = np.concatenate([np.arange(w.rowptr[r], w.rowptr[r + 1]) for r in rows])
+    # score: sampled rows, oracle evaluated on the sub-graph of those rows
+    sub_ptr = np.concatenate([[0], np.cumsum(deg[rows])]).astype(np.int32)
+    # oracle.gat_score walks rows 0..n-1 of the graph it is given: give it the sampled rows with
+    # their own features in front of the full table
+    feat_rows = np.concatenate([feat[rows], feat])  # rows 0..n-1 = sampled rows, columns shifted by n
+    e_ref = oracle.gat_score(sub_ptr, (w.col[esel] + rows.size).astype(np.int32), feat_rows, al, ar, H)
+    e_gpu = down(e)[esel]
+    assert np.abs(e_gpu.astype(np.float64) - e_ref).max() <= 2e-2 * np.abs(e_ref).max() + 1e-3
+    compare(f"{tag} score", e_gpu, e_ref, np.abs(e_ref) + 0.05)
+    a_ref = oracle.edge_softmax(sub_ptr, e_gpu.astype(np.float64))
+    a_gpu = down(alpha)[esel]
+    compare(f"{tag} alpha", a_gpu, a_ref, np.maximum(a_ref, 2.0 ** -14))
+    a_full = down(alpha)
+    o_ref, o_abs = oracle.spmm(w.rowptr, w.col, feat, w=a_full, H=H, rows=rows, want_sabs=True)
+    s1 = compare(f"{tag} out", down(out)[rows], o_ref, o_abs)
+    # ---- backward
+    dh = torch.empty_like(hd)
+    hgnn.hgnn_spmm_discretized(pt, gt, alpha, H, dOd, dh)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    rows_t = sample_rows(rT, 4000, 4)
+    dh_ref, dh_abs = oracle.spmm(rT, cT, dOut, w=a_full, H=H, eid=eT, rows=rows_t, want_sabs=True)
+    s2 = compare(f"{tag} dh", down(dh)[rows_t], dh_ref, dh_abs)
+    dalpha = torch.empty_like(e)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, dOd, hd, dalpha)
+    dOut_rows = np.concatenate([dOut[rows], dOut[:1]])  # U side: sampled rows in front
+    da_ref = oracle.sddmm_dot(sub_ptr, w.col[esel], dOut_rows, feat, H=H)
+    da_gpu = down(dalpha)[esel]
+    compare(f"{tag} dalpha", da_gpu, da_ref, np.abs(da_ref) + 0.25 * np.sqrt(D))
+    ds = torch.empty_like(e)
+    hgnn.hgnn_edge_softmax_bwd(g, p, H, alpha, dalpha, ds, e=e, neg_slope=0.2)
+    ds_ref = oracle.edge_softmax_bwd(sub_ptr, a_gpu.astype(np.float64), da_gpu.astype(np.float64),
+                                     e=e_gpu.astype(np.float64), slope=0.2)
+    tabs = oracle.edge_rowsum(sub_ptr, np.abs(a_gpu.astype(np.float64) * da_gpu.astype(np.float64)))
+    row_local = np.repeat(np.arange(rows.size), deg[rows])
+    mag = a_gpu.astype(np.float64) * (np.abs(da_gpu.astype(np.float64)) + tabs[row_local]) + 2.0 ** -14
+    compare(f"{tag} ds", down(ds)[esel], ds_ref, mag)
+    d_el = torch.empty((V, H), dtype=torch.float16, device=dev)
+    d_er = torch.empty((V, H), dtype=torch.float16, device=dev)
+    hgnn.hgnn_edge_rowsum(g, H, ds, d_el)
+    hgnn.hgnn_edge_rowsum(gt, H, ds, d_er)
+    ds_full = down(ds).astype(np.float64)
+    compare(f"{tag} d_el", down(d_el), oracle.edge_rowsum(w.rowptr, ds_full),
+            oracle.edge_rowsum(w.rowptr, np.abs(ds_full)) + 2.0 ** -14)
+    compare(f"{tag} d_er", down(d_er), oracle.edge_colsum(w.rowptr, w.col, ds_full, V),
+            oracle.edge_colsum(w.rowptr, w.col, np.abs(ds_full), V) + 2.0 ** -14)
+    print(f"{tag}: out {s1} dh {s2}", flush=True)
+
+
+def test_config3_gat_layer(hgnn, dev):
+    w = wl.gat_rmat()
+    print(f"c3 E={w.E} max deg={np.diff(w.rowptr).max()}", flush=True)
+    gat_layer_check(hgnn, dev, w, 4, 16, tag="c3")
+
+
+def test_gat_small_graph_every_row(hgnn, dev):
+    """A small GAT case where every row (not a sample) is compared."""
+    w = wl.gat_rmat(scale=11, avg_degree=12, H=2, D=32)
+    gat_layer_check(hgnn, dev, w, 2, 32, rows_fwd=np.arange(w.V, dtype=np.int32), tag="gat-small")
