@@ -165,8 +165,10 @@ hgnn_status hgnn_edge_softmax_bwd(const hgnn_csr* g, const hgnn_plan* p, int32_t
 
 /* Row sums of an edge tensor: out[i,h] = sum_{k in row i} t[slot(k), h], out is
  * [nrows][H] fp16.  On g it gives d(e_l); on the transposed graph (with its eid
- * map) it gives the column sums d(e_r) of the GAT score backward. */
-hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, int32_t H, const hgnn_half* t, hgnn_half* out, void* stream);
+ * map) it gives the column sums d(e_r) of the GAT score backward.  p may be NULL
+ * (then very long rows are slower); when given it must be the plan of g. */
+hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* t, hgnn_half* out,
+                             void* stream);
 
 #ifdef __cplusplus
 }

@@ -73,7 +73,7 @@ def load() -> ctypes.CDLL:
     lib.hgnn_sddmm.argtypes = [csr, vp, ctypes.c_int, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp]
     lib.hgnn_edge_softmax.argtypes = [csr, vp, i32, vp, vp, vp]
     lib.hgnn_edge_softmax_bwd.argtypes = [csr, vp, i32, vp, vp, vp, f32, vp, vp]
-    lib.hgnn_edge_rowsum.argtypes = [csr, i32, vp, vp, vp]
+    lib.hgnn_edge_rowsum.argtypes = [csr, vp, i32, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)  # every declared entry point must be exported
     _lib = lib
@@ -227,5 +227,6 @@ def hgnn_edge_softmax_bwd(g: Csr, p: Optional[Plan], H: int, alpha: torch.Tensor
                                         _ptr(de, torch.float16), _stream(stream)))
 
 
-def hgnn_edge_rowsum(g: Csr, H: int, t: torch.Tensor, out: torch.Tensor, stream=None) -> None:
-    _check(load().hgnn_edge_rowsum(g.ref, H, _ptr(t, torch.float16), _ptr(out, torch.float16), _stream(stream)))
+def hgnn_edge_rowsum(g: Csr, p: Optional[Plan], H: int, t: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    _check(load().hgnn_edge_rowsum(g.ref, None if p is None else p.handle, H, _ptr(t, torch.float16),
+                                   _ptr(out, torch.float16), _stream(stream)))

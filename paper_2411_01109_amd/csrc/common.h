@@ -52,6 +52,54 @@ inline int pow2_at_least(int v) {
 
 hgnn_status check_csr_args(const hgnn_csr* g, const char* who);
 
+typedef int int4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
+// ---- per-edge row ids of one plan segment, staged in LDS by one wave ---------------------------------
+// A segment of n <= S consecutive edges starting at e0 touches the rows row_lo..row_hi (plan arrays).
+// Every non-empty row after row_lo marks the slot of its first edge, then a wave-wide running
+// maximum spreads the ids: s_row[i] = row of edge e0+i for i < n, -2 for the padding up to
+// 64*per slots; s_blk[i/4] = common row id of the aligned group of four edges, or -1 when they
+// differ or touch the padding.  Lane t owns the slots [t*per, (t+1)*per); per is a multiple of 4.
+// Contains workgroup barriers: every wave of the workgroup must call it (n = 0 when it has no segment).
+__device__ __forceinline__ int seg_slots_per_lane(int S) { return 4 * ((S + 255) / 256); }
+
+__device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane, int per, int n, int row_lo, int row_hi,
+                                               const int* __restrict__ rowptr, int64_t e0) {
+  for (int i = lane; i < kWave * per; i += kWave) s_row[i] = i == 0 ? row_lo : -1;
+  __syncthreads();
+  for (int r = row_lo + 1 + lane; r <= row_hi; r += kWave) {
+    const int p = rowptr[r], q = rowptr[r + 1];
+    if (q > p) s_row[p - int(e0)] = r;
+  }
+  __syncthreads();
+  const int b0 = lane * per;
+  int run = -1;
+  for (int j = 0; j < per; ++j) {
+    run = max(run, s_row[b0 + j]);
+    s_row[b0 + j] = run;
+  }
+  int inc = run;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc = max(inc, t);
+  }
+  int excl = __shfl_up(inc, 1);
+  if (lane == 0) excl = -1;
+  for (int j = 0; j < per; j += 4) {
+    int v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      v[q] = max(s_row[b0 + j + q], excl);
+      if (b0 + j + q >= n) v[q] = -2;
+      s_row[b0 + j + q] = v[q];
+    }
+    s_blk[(b0 + j) >> 2] = (v[0] == v[1] && v[1] == v[2] && v[2] == v[3]) ? v[0] : -1;
+  }
+  __syncthreads();
+}
+
 }  // namespace hgnn
 
 // The plan object behind the opaque handle of the C ABI.

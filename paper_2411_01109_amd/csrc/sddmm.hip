@@ -1,17 +1,23 @@
 // fp16 SDDMM for gfx950 (paper sections 2.1.2 and 5.1): per non-zero, a reduction along the
 // feature dimension of the row vertex's and the column vertex's vectors.
 //
-// Edge-parallel: a wave owns a tile of consecutive non-zeros; each group of L lanes takes one
-// non-zero at a time and every lane loads 16 bytes (8 halves) of both feature rows -- the wide
-// per-lane load of section 5.1.3 -- so only log2(D/8) shuffle rounds are left per head.  Results
-// are collected in LDS and written back coalesced.
+// Edge-parallel over the plan's segments: a wave owns one segment of consecutive non-zeros and
+// each group of L lanes takes a contiguous chunk of it, four non-zeros per step.  Every lane
+// loads 16 bytes (8 halves) of the column vertex's row -- the wide per-lane load of section
+// 5.1.3 -- while the row vertex's vector stays in registers for as long as the row does not
+// change.  The four partial dot products of a step are reduced across the lanes of a head with a
+// transposing butterfly (each exchange halves the number of live values), so a step costs 2+1
+// exchanges instead of 4*log2(D/8).  Results are collected in LDS and written back coalesced.
 #include "common.h"
 
 namespace hgnn {
 
 struct SddmmArgs {
+  const int* rowptr;
   const int* col;
-  const int* erow;
+  const int* erow;  // COO row ids (kernels that run without a plan)
+  const int* seg_lo;
+  const int* seg_hi;
   const half_t* U;
   const half_t* Vt;
   const half_t* a_l;
@@ -19,13 +25,13 @@ struct SddmmArgs {
   half_t* out;
   float* el;  // [nrows][H] fp32 scratch (factorised GAT score)
   float* er;  // [ncols][H]
-  int64_t ldu, ldv, nnz;
+  int64_t ldu, ldv, nnz, nseg;
   int nrows, ncols;
-  int H, D, F;
+  int H, D, F, S;
   float slope;
 };
 
-constexpr int kTile = 256;  // non-zeros per wave
+constexpr int kTile = 256;  // non-zeros per wave in the kernels that run without a plan
 
 __device__ __forceinline__ float dot8(const half8_t& a, const half8_t& b) {
   float p = 0.f;
@@ -34,6 +40,123 @@ __device__ __forceinline__ float dot8(const half8_t& a, const half8_t& b) {
   return p;
 }
 
+struct SddmmLds {
+  int per, spad, col_off, row_off, blk_off, out_off, total;
+};
+__host__ __device__ inline SddmmLds sddmm_lds_layout(int S, int H) {
+  SddmmLds o;
+  o.per = 4 * ((S + 255) / 256);
+  o.spad = kWave * o.per;
+  o.col_off = 0;
+  o.row_off = o.spad * 4;
+  o.blk_off = o.row_off + o.spad * 4;
+  o.out_off = o.blk_off + ((o.spad + 15) & ~15);
+  o.total = o.out_off + ((o.spad * H * 2 + 15) & ~15);
+  return o;
+}
+
+// DOT over one plan segment per wave:  out[k,h] = <U[row k, h], Vt[col k, h]>
+template <int L>
+__global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
+  constexpr int G = kWave / L;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int LH = a.D / 8;  // lanes per head (power of two)
+  const int head = f0c / a.D;
+  const int lh = l % LH;
+  const int S = a.S;
+  const SddmmLds lay = sddmm_lds_layout(S, a.H);
+  unsigned char* base = smem + size_t(wave) * lay.total;
+  int* s_col = reinterpret_cast<int*>(base + lay.col_off);
+  int* s_row = reinterpret_cast<int*>(base + lay.row_off);
+  int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
+  half_t* s_out = reinterpret_cast<half_t*>(base + lay.out_off);
+
+  const int64_t seg = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const bool valid = seg < a.nseg;
+  const int64_t e0 = seg * S;
+  const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+  const int row_lo = valid ? a.seg_lo[seg] : 0, row_hi = valid ? a.seg_hi[seg] : -1;
+  for (int i = lane; i < lay.spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
+  seg_stage_rows(s_row, s_blk, lane, lay.per, n, row_lo, row_hi, a.rowptr, e0);
+
+  const int C = 4 * ((S + 4 * G - 1) / (4 * G));
+  const int c0 = g * C < n ? g * C : n;
+  const int c1 = c0 + C < n ? c0 + C : n;
+  int cur = -1;
+  half8_t u = half8_t(0);
+  if (c0 < c1) {
+    cur = s_row[c0];
+    u = *reinterpret_cast<const half8_t*>(a.U + int64_t(cur) * a.ldu + f0c);
+  }
+  for (int i = c0; i < c1; i += 4) {
+    const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
+    const int blk = s_blk[i >> 2];
+    half8_t v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const half8_t*>(a.Vt + int64_t(cols[q]) * a.ldv + f0c);
+    float p[4];
+    if (blk == cur) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) p[q] = dot8(u, v[q]);
+    } else {
+      const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        p[q] = 0.f;
+        if (i + q < c1) {
+          if (rows[q] != cur) {
+            cur = rows[q];
+            u = *reinterpret_cast<const half8_t*>(a.U + int64_t(cur) * a.ldu + f0c);
+          }
+          p[q] = dot8(u, v[q]);
+        }
+      }
+    }
+    // transposing butterfly over the LH lanes of a head: 4 values -> 2 -> 1, then plain exchanges
+    if (LH >= 2) {
+      const bool b0 = lh & 1;
+      const float r0 = __shfl_xor(b0 ? p[0] : p[2], 1);
+      const float r1 = __shfl_xor(b0 ? p[1] : p[3], 1);
+      p[0] = (b0 ? p[2] : p[0]) + r0;  // edges {0,1} on even lanes, {2,3} on odd lanes
+      p[1] = (b0 ? p[3] : p[1]) + r1;
+      if (LH >= 4) {
+        const bool b1 = (lh >> 1) & 1;
+        const float r = __shfl_xor(b1 ? p[0] : p[1], 2);
+        p[0] = (b1 ? p[1] : p[0]) + r;  // edge 2*b0 + b1
+        for (int off = 4; off < LH; off <<= 1) p[0] += __shfl_xor(p[0], off);
+        const int e = i + 2 * int(b0) + int(b1);
+        if (active && lh < 4 && e < c1) s_out[e * a.H + head] = half_t(p[0]);
+      } else {
+        const int e = i + 2 * int(b0);
+        if (active && e < c1) s_out[e * a.H + head] = half_t(p[0]);
+        if (active && e + 1 < c1) s_out[(e + 1) * a.H + head] = half_t(p[1]);
+      }
+    } else if (active) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (i + q < c1) s_out[(i + q) * a.H + head] = half_t(p[q]);
+    }
+  }
+  __syncthreads();
+  // coalesced write-back, 16 bytes per lane where the destination allows it
+  const int tot = n * a.H;
+  half_t* dst = a.out + e0 * a.H;
+  if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+    const int nv = tot / 8;
+    for (int j = lane; j < nv; j += kWave)
+      reinterpret_cast<half8_t*>(dst)[j] = reinterpret_cast<const half8_t*>(s_out)[j];
+    for (int j = nv * 8 + lane; j < tot; j += kWave) dst[j] = s_out[j];
+  } else {
+    for (int j = lane; j < tot; j += kWave) dst[j] = s_out[j];
+  }
+}
+
+// Without a plan: tiles of kTile non-zeros, row ids from the caller's COO array.
 // SCORE = false: out = <U[i,h], Vt[j,h]>.  SCORE = true: out = LeakyReLU(<a_l[h],U[i,h]> + <a_r[h],Vt[j,h]>).
 template <int L, bool SCORE>
 __global__ __launch_bounds__(kBlock) void sddmm_edge_kernel(SddmmArgs a) {
@@ -120,14 +243,57 @@ __global__ __launch_bounds__(kBlock) void vertex_proj_kernel(const half_t* __res
   if (active && v < nv && (l % LH) == 0) proj[v * H + l / LH] = p;
 }
 
-// step 2: e[k,h] = LeakyReLU(el[row k, h] + er[col k, h])
-__global__ __launch_bounds__(kBlock) void edge_score_kernel(SddmmArgs a) {
-  const int64_t idx = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  if (idx >= a.nnz * a.H) return;
-  const int64_t k = idx / a.H;
-  const int h = int(idx % a.H);
-  const float s = a.el[int64_t(a.erow[k]) * a.H + h] + a.er[int64_t(a.col[k]) * a.H + h];
-  a.out[idx] = half_t(s > 0.f ? s : a.slope * s);
+// step 2, one plan segment per wave: e[k,h] = LeakyReLU(el[row k, h] + er[col k, h]); row ids
+// come from the offset array (staged in LDS), so the only per-edge stream read is the column id.
+template <int HT>
+__global__ __launch_bounds__(kBlock) void edge_score_seg_kernel(SddmmArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int S = a.S;
+  const int per = seg_slots_per_lane(S), spad = kWave * per;
+  int* s_row = reinterpret_cast<int*>(smem) + size_t(wave) * (spad + spad / 4);
+  int* s_blk = s_row + spad;
+  const int64_t seg = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const bool valid = seg < a.nseg;
+  const int64_t e0 = seg * S;
+  const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+  seg_stage_rows(s_row, s_blk, lane, per, n, valid ? a.seg_lo[seg] : 0, valid ? a.seg_hi[seg] : -1, a.rowptr, e0);
+  if (HT == 0) {  // any head count: one output element per lane and step
+    const int tot = n * a.H;
+    for (int j = lane; j < tot; j += kWave) {
+      const int k = j / a.H, h = j - k * a.H;
+      const float s = a.el[int64_t(s_row[k]) * a.H + h] + a.er[int64_t(a.col[e0 + k]) * a.H + h];
+      a.out[e0 * a.H + j] = half_t(s > 0.f ? s : a.slope * s);
+    }
+    return;
+  }
+  // H in {1,2,4,8}: a lane produces 8 consecutive outputs (8/H non-zeros) and stores them as 16 bytes
+  constexpr int H = HT > 0 ? HT : 1;
+  constexpr int EPL = 8 / H;
+  typedef float fv_t __attribute__((ext_vector_type(H)));
+  half_t* dst = a.out + e0 * H;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+  for (int kb = lane * EPL; kb < n; kb += kWave * EPL) {
+    half8_t o = half8_t(0);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int k = kb + e < n ? kb + e : n - 1;
+      const fv_t vl = *reinterpret_cast<const fv_t*>(a.el + int64_t(s_row[k]) * H);
+      const fv_t vr = *reinterpret_cast<const fv_t*>(a.er + int64_t(a.col[e0 + k]) * H);
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        const float s = vl[h] + vr[h];
+        o[e * H + h] = half_t(s > 0.f ? s : a.slope * s);
+      }
+    }
+    if (vec_ok && kb + EPL <= n) {
+      *reinterpret_cast<half8_t*>(dst + kb * H) = o;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (kb * H + q < n * H) dst[kb * H + q] = o[q];
+    }
+  }
 }
 
 template <bool SCORE>
@@ -140,6 +306,18 @@ static void launch_edge(int L, dim3 grid, size_t lds, hipStream_t s, const Sddmm
     case 16: sddmm_edge_kernel<16, SCORE><<<grid, kBlock, lds, s>>>(a); break;
     case 32: sddmm_edge_kernel<32, SCORE><<<grid, kBlock, lds, s>>>(a); break;
     default: sddmm_edge_kernel<64, SCORE><<<grid, kBlock, lds, s>>>(a); break;
+  }
+}
+
+static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+  switch (L) {
+    case 1: sddmm_seg_kernel<1><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: sddmm_seg_kernel<2><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: sddmm_seg_kernel<4><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: sddmm_seg_kernel<8><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: sddmm_seg_kernel<16><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: sddmm_seg_kernel<32><<<grid, kBlock, lds, s>>>(a); break;
+    default: sddmm_seg_kernel<64><<<grid, kBlock, lds, s>>>(a); break;
   }
 }
 
@@ -182,12 +360,12 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
   if (p)
     HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
                  "hgnn_sddmm: the plan was built for another graph");
-  const int* erow = g->row ? g->row : (p ? p->edge_row : nullptr);
-  HGNN_REQUIRE(erow != nullptr, HGNN_EINVAL, "hgnn_sddmm: needs COO row ids (g->row) or a plan");
+  HGNN_REQUIRE(g->row != nullptr || p != nullptr, HGNN_EINVAL, "hgnn_sddmm: needs COO row ids (g->row) or a plan");
   hipStream_t s = static_cast<hipStream_t>(stream);
   SddmmArgs a{};
+  a.rowptr = g->rowptr;
   a.col = g->col;
-  a.erow = erow;
+  a.erow = g->row ? g->row : p->edge_row;
   a.U = reinterpret_cast<const half_t*>(U);
   a.Vt = reinterpret_cast<const half_t*>(Vt);
   a.a_l = reinterpret_cast<const half_t*>(a_l);
@@ -202,19 +380,19 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
   a.D = D;
   a.F = F;
   a.slope = neg_slope;
+  if (p) {
+    a.seg_lo = p->seg_row_lo;
+    a.seg_hi = p->seg_row_hi;
+    a.nseg = p->nseg;
+    a.S = p->S;
+  }
   const int LH = D / 8;
   const bool vec = D % 8 == 0 && (LH & (LH - 1)) == 0 && F <= 512 && ldu % 8 == 0 && ldv % 8 == 0 && aligned16(U) &&
-                   aligned16(Vt) && (!score || (aligned16(a_l) && aligned16(a_r))) &&
-                   size_t(kTile) * H * sizeof(hgnn_half) * kWavesPerBlock <= 65536;
-  if (!vec) {
-    dim3 grid(unsigned(ceil_div(g->nnz * H, kBlock)));
-    if (score) sddmm_scalar_kernel<true><<<grid, kBlock, 0, s>>>(a);
-    else sddmm_scalar_kernel<false><<<grid, kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("sddmm_scalar_kernel");
-    return HGNN_OK;
-  }
-  const int L = pow2_at_least(F / 8);
-  if (score && p && H <= p->max_H) {
+                   aligned16(Vt) && (!score || (aligned16(a_l) && aligned16(a_r)));
+  const int L = vec ? pow2_at_least(F / 8) : 0;
+  const int64_t seg_blocks = p ? ceil_div(p->nseg, kWavesPerBlock) : 0;
+
+  if (vec && score && p && H <= p->max_H) {
     // project every vertex once, then one add per (edge, head)
     const int G = kWave / L;
     a.el = p->vscratch;
@@ -225,14 +403,38 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     launch_proj(L, dim3(unsigned(ceil_div(g->ncols, int64_t(kWavesPerBlock) * G))), s, a.Vt, ldv, g->ncols, a.a_r, F, D,
                 a.er, H);
     HGNN_LAUNCH_CHECK("vertex_proj_kernel");
-    edge_score_kernel<<<dim3(unsigned(ceil_div(g->nnz * H, kBlock))), kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("edge_score_kernel");
+    const int spad = kWave * 4 * ((a.S + 255) / 256);
+    const size_t lds = size_t(spad + spad / 4) * sizeof(int) * kWavesPerBlock;
+    const dim3 gs{unsigned(seg_blocks), 1u, 1u};
+    switch (H) {
+      case 1: edge_score_seg_kernel<1><<<gs, kBlock, lds, s>>>(a); break;
+      case 2: edge_score_seg_kernel<2><<<gs, kBlock, lds, s>>>(a); break;
+      case 4: edge_score_seg_kernel<4><<<gs, kBlock, lds, s>>>(a); break;
+      case 8: edge_score_seg_kernel<8><<<gs, kBlock, lds, s>>>(a); break;
+      default: edge_score_seg_kernel<0><<<gs, kBlock, lds, s>>>(a); break;
+    }
+    HGNN_LAUNCH_CHECK("edge_score_seg_kernel");
     return HGNN_OK;
   }
-  const size_t lds = size_t(kTile) * H * sizeof(hgnn_half) * kWavesPerBlock;
-  dim3 grid(unsigned(ceil_div(g->nnz, int64_t(kTile) * kWavesPerBlock)));
-  if (score) launch_edge<true>(L, grid, lds, s, a);
-  else launch_edge<false>(L, grid, lds, s, a);
-  HGNN_LAUNCH_CHECK("sddmm_edge_kernel");
+  if (vec && !score && p) {
+    const size_t lds = size_t(sddmm_lds_layout(a.S, H).total) * kWavesPerBlock;
+    if (lds <= 65536) {
+      launch_seg(L, dim3(unsigned(seg_blocks)), lds, s, a);
+      HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
+      return HGNN_OK;
+    }
+  }
+  const size_t lds_tile = size_t(kTile) * H * sizeof(hgnn_half) * kWavesPerBlock;
+  if (vec && lds_tile <= 65536) {
+    dim3 grid(unsigned(ceil_div(g->nnz, int64_t(kTile) * kWavesPerBlock)));
+    if (score) launch_edge<true>(L, grid, lds_tile, s, a);
+    else launch_edge<false>(L, grid, lds_tile, s, a);
+    HGNN_LAUNCH_CHECK("sddmm_edge_kernel");
+    return HGNN_OK;
+  }
+  dim3 grid(unsigned(ceil_div(g->nnz * H, kBlock)));
+  if (score) sddmm_scalar_kernel<true><<<grid, kBlock, 0, s>>>(a);
+  else sddmm_scalar_kernel<false><<<grid, kBlock, 0, s>>>(a);
+  HGNN_LAUNCH_CHECK("sddmm_scalar_kernel");
   return HGNN_OK;
 }

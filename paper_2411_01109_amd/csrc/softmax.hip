@@ -1,235 +1,363 @@
 // Edge softmax (paper Eq. 1), its backward, and row sums of edge tensors, for gfx950.
 //
 // The scores of one row (neighbourhood) are the contiguous slice e[rowptr[i]*H, rowptr[i+1]*H),
-// element j of the slice belonging to head j % H.  A wave owns a row: lane t walks the elements
-// t, t+64, ... (so its head is fixed when H divides 64), keeps the first few in registers so a
-// short row is read once, and the per-head max / sum are finished with xor shuffles over the
-// lanes of equal head.  Rows longer than the plan's threshold are left to a kernel that gives
-// a whole 1024-thread workgroup to each of them.  exp, sums and the division stay in fp32; the
-// exponent is <= 0, so the numerator is in (0,1] (section 3.1.2) and alpha is rounded once.
+// element j of the whole tensor belonging to head j % H.  A "team" of lanes owns a row: a
+// sub-wave group of LR lanes (LR chosen from the mean row length, so short rows do not idle a
+// whole wave), or a whole 1024-thread workgroup for rows longer than the plan's threshold.
+// Every lane moves 16 bytes (8 halves) per access: the slice is walked in 8-element vectors
+// aligned to the tensor's base, the ragged first and last vector are masked, and because H
+// divides 8 the head of each of a lane's 8 elements is fixed.  A row that fits the lanes'
+// registers is read once.  exp, sums and the division stay in fp32; the exponent is <= 0, so
+// the numerator is in (0,1] (section 3.1.2) and alpha is rounded once.
 #include "common.h"
 
 namespace hgnn {
 
-constexpr int kKeep = 4;        // elements per lane held in registers
+constexpr int kKeepVec = 2;     // 8-element vectors per lane held in registers
 constexpr int kBigBlock = 1024; // threads given to one long row
 
-struct SoftmaxArgs {
+struct EdgeRowArgs {
   const int* rowptr;
   const int* big_row;
-  const half_t* e;       // scores (forward) or nullptr / scores for the LeakyReLU mask (backward)
-  const half_t* alpha;   // backward: alpha
-  const half_t* dalpha;  // backward: d alpha
-  half_t* out;           // forward: alpha; backward: de
+  const int* eid;
+  const half_t* x0;  // forward: e.          backward: alpha.   rowsum: t
+  const half_t* x1;  //                      backward: dalpha
+  const half_t* x2;  //                      backward: e (LeakyReLU mask) or nullptr
+  half_t* out;       // forward: alpha.      backward: de.      rowsum: [nrows][H]
+  int64_t total;     // nnz * H
   int nrows, H;
-  int skip_above;        // rows longer than this are skipped by the wave kernel (0 = none)
+  int skip_above;    // rows longer than this are left to the long-row kernel (0 = none)
   float slope;
 };
 
-// reduce over the lanes of a wave whose lane id is congruent modulo H (H divides 64)
-__device__ __forceinline__ float wave_max_heads(float v, int H) {
-  for (int off = H; off < kWave; off <<= 1) v = fmaxf(v, __shfl_xor(v, off));
-  return v;
-}
-__device__ __forceinline__ float wave_sum_heads(float v, int H) {
-  for (int off = H; off < kWave; off <<= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
-__global__ __launch_bounds__(kBlock) void softmax_fwd_wave_kernel(SoftmaxArgs a) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
-  if (row >= a.nrows) return;
-  const int beg = a.rowptr[row], deg = a.rowptr[row + 1] - beg;
-  if (deg == 0 || (a.skip_above > 0 && deg > a.skip_above)) return;
-  const int64_t n = int64_t(deg) * a.H;
-  const half_t* x = a.e + int64_t(beg) * a.H;
-  half_t* y = a.out + int64_t(beg) * a.H;
-  float v[kKeep];
-  float m = -INFINITY;
+// ---- teams -----------------------------------------------------------------------------------------
+template <int LR>
+struct SubWaveTeam {  // LR consecutive lanes of a wave
+  static constexpr int size = LR;
+  int rank;
+  __device__ SubWaveTeam() : rank((threadIdx.x & (kWave - 1)) % LR) {}
+  template <int H, bool IS_MAX>
+  __device__ __forceinline__ void reduce(float (&v)[H]) const {
 #pragma unroll
-  for (int t = 0; t < kKeep; ++t) {
-    const int64_t i = lane + int64_t(kWave) * t;
-    v[t] = i < n ? float(x[i]) : -INFINITY;
-    m = fmaxf(m, v[t]);
-  }
-  for (int64_t i = lane + int64_t(kWave) * kKeep; i < n; i += kWave) m = fmaxf(m, float(x[i]));
-  m = wave_max_heads(m, a.H);
-  float z = 0.f;
+    for (int off = 1; off < LR; off <<= 1)
 #pragma unroll
-  for (int t = 0; t < kKeep; ++t) {
-    v[t] = __expf(v[t] - m);  // exp(-inf) = 0 for the padding
-    z += v[t];
+      for (int h = 0; h < H; ++h) {
+        const float o = __shfl_xor(v[h], off);
+        v[h] = IS_MAX ? fmaxf(v[h], o) : v[h] + o;
+      }
   }
-  for (int64_t i = lane + int64_t(kWave) * kKeep; i < n; i += kWave) z += __expf(float(x[i]) - m);
-  z = wave_sum_heads(z, a.H);
-  const float inv = 1.f / z;
-#pragma unroll
-  for (int t = 0; t < kKeep; ++t) {
-    const int64_t i = lane + int64_t(kWave) * t;
-    if (i < n) y[i] = half_t(v[t] * inv);
-  }
-  for (int64_t i = lane + int64_t(kWave) * kKeep; i < n; i += kWave) y[i] = half_t(__expf(float(x[i]) - m) * inv);
-}
-
-// combine per-wave partials of a 1024-thread workgroup, per head; every thread gets the result of its head
-template <bool IS_MAX>
-__device__ __forceinline__ float block_reduce_heads(float v, int H, float* sm /* [16][64] */) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  v = IS_MAX ? wave_max_heads(v, H) : wave_sum_heads(v, H);
-  __syncthreads();  // protects sm against the previous use
-  if (lane < H) sm[wave * kWave + lane] = v;
-  __syncthreads();
-  const int h = lane % H;
-  float r = sm[h];
-  for (int w = 1; w < kBigBlock / kWave; ++w) r = IS_MAX ? fmaxf(r, sm[w * kWave + h]) : r + sm[w * kWave + h];
-  return r;
-}
-
-__global__ __launch_bounds__(kBigBlock) void softmax_fwd_big_kernel(SoftmaxArgs a) {
-  __shared__ float sm[(kBigBlock / kWave) * kWave];
-  const int row = a.big_row[blockIdx.x];
-  const int beg = a.rowptr[row];
-  const int64_t n = int64_t(a.rowptr[row + 1] - beg) * a.H;
-  const half_t* x = a.e + int64_t(beg) * a.H;
-  half_t* y = a.out + int64_t(beg) * a.H;
-  float m = -INFINITY;
-  for (int64_t i = threadIdx.x; i < n; i += kBigBlock) m = fmaxf(m, float(x[i]));
-  m = block_reduce_heads<true>(m, a.H, sm);
-  float z = 0.f;
-  for (int64_t i = threadIdx.x; i < n; i += kBigBlock) z += __expf(float(x[i]) - m);
-  z = block_reduce_heads<false>(z, a.H, sm);
-  const float inv = 1.f / z;
-  for (int64_t i = threadIdx.x; i < n; i += kBigBlock) y[i] = half_t(__expf(float(x[i]) - m) * inv);
-}
-
-// backward: t = sum alpha*dalpha over the row (per head); de = alpha*(dalpha - t) [* LeakyReLU'(e)]
-__global__ __launch_bounds__(kBlock) void softmax_bwd_wave_kernel(SoftmaxArgs a) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
-  if (row >= a.nrows) return;
-  const int beg = a.rowptr[row], deg = a.rowptr[row + 1] - beg;
-  if (deg == 0 || (a.skip_above > 0 && deg > a.skip_above)) return;
-  const int64_t n = int64_t(deg) * a.H, off = int64_t(beg) * a.H;
-  const half_t* al = a.alpha + off;
-  const half_t* da = a.dalpha + off;
-  float va[kKeep], vd[kKeep];
-  float t = 0.f;
-#pragma unroll
-  for (int q = 0; q < kKeep; ++q) {
-    const int64_t i = lane + int64_t(kWave) * q;
-    va[q] = i < n ? float(al[i]) : 0.f;
-    vd[q] = i < n ? float(da[i]) : 0.f;
-    t = fmaf(va[q], vd[q], t);
-  }
-  for (int64_t i = lane + int64_t(kWave) * kKeep; i < n; i += kWave) t = fmaf(float(al[i]), float(da[i]), t);
-  t = wave_sum_heads(t, a.H);
-#pragma unroll
-  for (int q = 0; q < kKeep; ++q) {
-    const int64_t i = lane + int64_t(kWave) * q;
-    if (i < n) {
-      float d = va[q] * (vd[q] - t);
-      if (a.e) d *= float(a.e[off + i]) > 0.f ? 1.f : a.slope;
-      a.out[off + i] = half_t(d);
-    }
-  }
-  for (int64_t i = lane + int64_t(kWave) * kKeep; i < n; i += kWave) {
-    float d = float(al[i]) * (float(da[i]) - t);
-    if (a.e) d *= float(a.e[off + i]) > 0.f ? 1.f : a.slope;
-    a.out[off + i] = half_t(d);
-  }
-}
-
-__global__ __launch_bounds__(kBigBlock) void softmax_bwd_big_kernel(SoftmaxArgs a) {
-  __shared__ float sm[(kBigBlock / kWave) * kWave];
-  const int row = a.big_row[blockIdx.x];
-  const int beg = a.rowptr[row];
-  const int64_t n = int64_t(a.rowptr[row + 1] - beg) * a.H, off = int64_t(beg) * a.H;
-  const half_t* al = a.alpha + off;
-  const half_t* da = a.dalpha + off;
-  float t = 0.f;
-  for (int64_t i = threadIdx.x; i < n; i += kBigBlock) t = fmaf(float(al[i]), float(da[i]), t);
-  t = block_reduce_heads<false>(t, a.H, sm);
-  for (int64_t i = threadIdx.x; i < n; i += kBigBlock) {
-    float d = float(al[i]) * (float(da[i]) - t);
-    if (a.e) d *= float(a.e[off + i]) > 0.f ? 1.f : a.slope;
-    a.out[off + i] = half_t(d);
-  }
-}
-
-// Scalar path for head counts that do not divide 64: one thread per (row, head).
-__global__ __launch_bounds__(kBlock) void softmax_fwd_scalar_kernel(SoftmaxArgs a) {
-  const int64_t idx = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  if (idx >= int64_t(a.nrows) * a.H) return;
-  const int row = int(idx / a.H), h = int(idx % a.H);
-  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  if (beg == end) return;
-  float m = -INFINITY, z = 0.f;
-  for (int k = beg; k < end; ++k) m = fmaxf(m, float(a.e[int64_t(k) * a.H + h]));
-  for (int k = beg; k < end; ++k) z += __expf(float(a.e[int64_t(k) * a.H + h]) - m);
-  const float inv = 1.f / z;
-  for (int k = beg; k < end; ++k) a.out[int64_t(k) * a.H + h] = half_t(__expf(float(a.e[int64_t(k) * a.H + h]) - m) * inv);
-}
-
-__global__ __launch_bounds__(kBlock) void softmax_bwd_scalar_kernel(SoftmaxArgs a) {
-  const int64_t idx = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  if (idx >= int64_t(a.nrows) * a.H) return;
-  const int row = int(idx / a.H), h = int(idx % a.H);
-  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  float t = 0.f;
-  for (int k = beg; k < end; ++k) t = fmaf(float(a.alpha[int64_t(k) * a.H + h]), float(a.dalpha[int64_t(k) * a.H + h]), t);
-  for (int k = beg; k < end; ++k) {
-    const int64_t i = int64_t(k) * a.H + h;
-    float d = float(a.alpha[i]) * (float(a.dalpha[i]) - t);
-    if (a.e) d *= float(a.e[i]) > 0.f ? 1.f : a.slope;
-    a.out[i] = half_t(d);
-  }
-}
-
-// ---- row sums of an edge tensor ------------------------------------------------------------------------
-struct RowsumArgs {
-  const int* rowptr;
-  const int* eid;
-  const half_t* t;
-  half_t* out;
-  int nrows, H;
 };
 
-__global__ __launch_bounds__(kBlock) void edge_rowsum_wave_kernel(RowsumArgs a) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
-  if (row >= a.nrows) return;
-  const int beg = a.rowptr[row], deg = a.rowptr[row + 1] - beg;
-  const int64_t n = int64_t(deg) * a.H;
-  const int h = lane % a.H;
-  float s = 0.f;
-  if (a.eid) {
-    for (int64_t i = lane; i < n; i += kWave) s += float(a.t[int64_t(a.eid[beg + i / a.H]) * a.H + h]);
-  } else {
-    const half_t* x = a.t + int64_t(beg) * a.H;
-    for (int64_t i = lane; i < n; i += kWave) s += float(x[i]);
+struct BlockTeam {  // a whole workgroup of kBigBlock threads
+  static constexpr int size = kBigBlock;
+  int rank;
+  float* sm;  // [kBigBlock / 64][8]
+  __device__ BlockTeam(float* s) : rank(threadIdx.x), sm(s) {}
+  template <int H, bool IS_MAX>
+  __device__ __forceinline__ void reduce(float (&v)[H]) const {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1)
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        const float o = __shfl_xor(v[h], off);
+        v[h] = IS_MAX ? fmaxf(v[h], o) : v[h] + o;
+      }
+    __syncthreads();  // protects sm against the previous use
+    if (lane == 0)
+#pragma unroll
+      for (int h = 0; h < H; ++h) sm[wave * 8 + h] = v[h];
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+      float r = sm[h];
+      for (int w = 1; w < kBigBlock / kWave; ++w) r = IS_MAX ? fmaxf(r, sm[w * 8 + h]) : r + sm[w * 8 + h];
+      v[h] = r;
+    }
   }
-  s = wave_sum_heads(s, a.H);
-  if (lane < a.H) a.out[row * a.H + lane] = half_t(s);
+};
+
+// 8 elements starting at the 8-aligned index b; a vector that would cross the end of the tensor is read by element
+__device__ __forceinline__ half8_t load_vec(const half_t* p, int64_t b, int64_t total) {
+  if (b + 8 <= total) return *reinterpret_cast<const half8_t*>(p + b);
+  half8_t v = half8_t(0);
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    if (b + q < total) v[q] = p[b + q];
+  return v;
+}
+__device__ __forceinline__ void store_vec(half_t* p, int64_t b, const half8_t& v, int64_t j0, int64_t j1) {
+  if (b >= j0 && b + 8 <= j1) {
+    *reinterpret_cast<half8_t*>(p + b) = v;
+  } else {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (b + q >= j0 && b + q < j1) p[b + q] = v[q];
+  }
 }
 
-__global__ __launch_bounds__(kBlock) void edge_rowsum_scalar_kernel(RowsumArgs a) {
+// ---- forward: one row by one team ----------------------------------------------------------------------
+template <int H, class Team>
+__device__ __forceinline__ void softmax_fwd_row(const EdgeRowArgs& a, const Team& team, int64_t j0, int64_t j1) {
+  const int64_t a0 = j0 & ~int64_t(7);
+  const int64_t nvec = (j1 - a0 + 7) >> 3;
+  half8_t keep[kKeepVec];
+  float m[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) m[h] = -INFINITY;
+  auto visit_max = [&](const half8_t& v, int64_t b) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (b + q >= j0 && b + q < j1) m[q % H] = fmaxf(m[q % H], float(v[q]));
+  };
+#pragma unroll
+  for (int i = 0; i < kKeepVec; ++i) {
+    const int64_t t = team.rank + int64_t(Team::size) * i;
+    keep[i] = half8_t(0);
+    if (t < nvec) {
+      keep[i] = load_vec(a.x0, a0 + 8 * t, a.total);
+      visit_max(keep[i], a0 + 8 * t);
+    }
+  }
+  for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
+    visit_max(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
+  team.template reduce<H, true>(m);
+  float z[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) z[h] = 0.f;
+  auto visit_sum = [&](const half8_t& v, int64_t b) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (b + q >= j0 && b + q < j1) z[q % H] += __expf(float(v[q]) - m[q % H]);
+  };
+#pragma unroll
+  for (int i = 0; i < kKeepVec; ++i) {
+    const int64_t t = team.rank + int64_t(Team::size) * i;
+    if (t < nvec) visit_sum(keep[i], a0 + 8 * t);
+  }
+  for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
+    visit_sum(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
+  team.template reduce<H, false>(z);
+  float inv[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) inv[h] = 1.f / z[h];
+  auto emit = [&](const half8_t& v, int64_t b) {
+    half8_t o;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o[q] = half_t(__expf(float(v[q]) - m[q % H]) * inv[q % H]);
+    store_vec(a.out, b, o, j0, j1);
+  };
+#pragma unroll
+  for (int i = 0; i < kKeepVec; ++i) {
+    const int64_t t = team.rank + int64_t(Team::size) * i;
+    if (t < nvec) emit(keep[i], a0 + 8 * t);
+  }
+  for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
+    emit(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
+}
+
+// ---- backward: t = sum alpha*dalpha (per head); de = alpha*(dalpha - t) [* LeakyReLU'(e)] --------------
+template <int H, class Team>
+__device__ __forceinline__ void softmax_bwd_row(const EdgeRowArgs& a, const Team& team, int64_t j0, int64_t j1) {
+  const int64_t a0 = j0 & ~int64_t(7);
+  const int64_t nvec = (j1 - a0 + 7) >> 3;
+  half8_t ka[kKeepVec], kd[kKeepVec];
+  float t[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) t[h] = 0.f;
+  auto visit = [&](const half8_t& va, const half8_t& vd, int64_t b) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (b + q >= j0 && b + q < j1) t[q % H] = fmaf(float(va[q]), float(vd[q]), t[q % H]);
+  };
+#pragma unroll
+  for (int i = 0; i < kKeepVec; ++i) {
+    const int64_t v = team.rank + int64_t(Team::size) * i;
+    ka[i] = half8_t(0);
+    kd[i] = half8_t(0);
+    if (v < nvec) {
+      ka[i] = load_vec(a.x0, a0 + 8 * v, a.total);
+      kd[i] = load_vec(a.x1, a0 + 8 * v, a.total);
+      visit(ka[i], kd[i], a0 + 8 * v);
+    }
+  }
+  for (int64_t v = team.rank + int64_t(Team::size) * kKeepVec; v < nvec; v += Team::size)
+    visit(load_vec(a.x0, a0 + 8 * v, a.total), load_vec(a.x1, a0 + 8 * v, a.total), a0 + 8 * v);
+  team.template reduce<H, false>(t);
+  auto emit = [&](const half8_t& va, const half8_t& vd, int64_t b) {
+    half8_t o;
+    half8_t ve = half8_t(1);
+    if (a.x2) ve = load_vec(a.x2, b, a.total);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float d = float(va[q]) * (float(vd[q]) - t[q % H]);
+      if (!(float(ve[q]) > 0.f)) d *= a.slope;
+      o[q] = half_t(d);
+    }
+    store_vec(a.out, b, o, j0, j1);
+  };
+#pragma unroll
+  for (int i = 0; i < kKeepVec; ++i) {
+    const int64_t v = team.rank + int64_t(Team::size) * i;
+    if (v < nvec) emit(ka[i], kd[i], a0 + 8 * v);
+  }
+  for (int64_t v = team.rank + int64_t(Team::size) * kKeepVec; v < nvec; v += Team::size)
+    emit(load_vec(a.x0, a0 + 8 * v, a.total), load_vec(a.x1, a0 + 8 * v, a.total), a0 + 8 * v);
+}
+
+// ---- row sums: out[row,h] = sum over the row of t[slot(k), h] -------------------------------------------
+template <int H, class Team>
+__device__ __forceinline__ void rowsum_row(const EdgeRowArgs& a, const Team& team, int row, int beg, int end) {
+  float s[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) s[h] = 0.f;
+  if (a.eid) {  // transposed view: one lane per non-zero, its H values are contiguous at slot eid[k]
+    typedef _Float16 hv_t __attribute__((ext_vector_type(H)));
+    for (int k = beg + team.rank; k < end; k += Team::size) {
+      const int64_t slot = a.eid[k];
+      if (H == 1) {
+        s[0] += float(a.x0[slot]);
+      } else {
+        const hv_t v = *reinterpret_cast<const hv_t*>(a.x0 + slot * H);
+#pragma unroll
+        for (int h = 0; h < H; ++h) s[h] += float(v[h]);
+      }
+    }
+  } else {
+    const int64_t j0 = int64_t(beg) * H, j1 = int64_t(end) * H;
+    const int64_t a0 = j0 & ~int64_t(7);
+    const int64_t nvec = (j1 - a0 + 7) >> 3;
+    for (int64_t t = team.rank; t < nvec; t += Team::size) {
+      const int64_t b = a0 + 8 * t;
+      const half8_t v = load_vec(a.x0, b, a.total);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (b + q >= j0 && b + q < j1) s[q % H] += float(v[q]);
+    }
+  }
+  team.template reduce<H, false>(s);
+  if (team.rank == 0)
+#pragma unroll
+    for (int h = 0; h < H; ++h) a.out[int64_t(row) * H + h] = half_t(s[h]);
+}
+
+enum { kFwd = 0, kBwd = 1, kSum = 2 };
+
+template <int OP, int LR, int H>
+__global__ __launch_bounds__(kBlock) void edge_row_team_kernel(EdgeRowArgs a) {
+  constexpr int GR = kWave / LR;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t row = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * GR + lane / LR;
+  if (row >= a.nrows) return;
+  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+  if (a.skip_above > 0 && end - beg > a.skip_above) return;
+  const SubWaveTeam<LR> team;
+  if (OP == kSum) {
+    rowsum_row<H>(a, team, int(row), beg, end);
+  } else if (end > beg) {
+    if (OP == kFwd) softmax_fwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
+    else softmax_bwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
+  }
+}
+
+template <int OP, int H>
+__global__ __launch_bounds__(kBigBlock) void edge_row_block_kernel(EdgeRowArgs a) {
+  __shared__ float sm[(kBigBlock / kWave) * 8];
+  const int row = a.big_row[blockIdx.x];
+  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+  const BlockTeam team(sm);
+  if (OP == kSum) rowsum_row<H>(a, team, row, beg, end);
+  else if (OP == kFwd) softmax_fwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
+  else softmax_bwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
+}
+
+// Scalar path for head counts that do not divide 8: one thread per (row, head).
+template <int OP>
+__global__ __launch_bounds__(kBlock) void edge_row_scalar_kernel(EdgeRowArgs a) {
   const int64_t idx = int64_t(blockIdx.x) * kBlock + threadIdx.x;
   if (idx >= int64_t(a.nrows) * a.H) return;
   const int row = int(idx / a.H), h = int(idx % a.H);
-  float s = 0.f;
-  for (int k = a.rowptr[row]; k < a.rowptr[row + 1]; ++k) {
-    const int64_t slot = a.eid ? a.eid[k] : k;
-    s += float(a.t[slot * a.H + h]);
+  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+  if (OP == kSum) {
+    float s = 0.f;
+    for (int k = beg; k < end; ++k) s += float(a.x0[(a.eid ? int64_t(a.eid[k]) : int64_t(k)) * a.H + h]);
+    a.out[idx] = half_t(s);
+    return;
   }
-  a.out[idx] = half_t(s);
+  if (beg == end) return;
+  if (OP == kFwd) {
+    float m = -INFINITY, z = 0.f;
+    for (int k = beg; k < end; ++k) m = fmaxf(m, float(a.x0[int64_t(k) * a.H + h]));
+    for (int k = beg; k < end; ++k) z += __expf(float(a.x0[int64_t(k) * a.H + h]) - m);
+    const float inv = 1.f / z;
+    for (int k = beg; k < end; ++k)
+      a.out[int64_t(k) * a.H + h] = half_t(__expf(float(a.x0[int64_t(k) * a.H + h]) - m) * inv);
+  } else {
+    float t = 0.f;
+    for (int k = beg; k < end; ++k) t = fmaf(float(a.x0[int64_t(k) * a.H + h]), float(a.x1[int64_t(k) * a.H + h]), t);
+    for (int k = beg; k < end; ++k) {
+      const int64_t i = int64_t(k) * a.H + h;
+      float d = float(a.x0[i]) * (float(a.x1[i]) - t);
+      if (a.x2 && !(float(a.x2[i]) > 0.f)) d *= a.slope;
+      a.out[i] = half_t(d);
+    }
+  }
 }
 
-static hgnn_status softmax_common(const char* who, const hgnn_csr* g, const hgnn_plan* p, int H) {
+template <int OP, int H>
+static void launch_team_h(int LR, dim3 grid, hipStream_t s, const EdgeRowArgs& a) {
+  switch (LR) {
+    case 4: edge_row_team_kernel<OP, 4, H><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: edge_row_team_kernel<OP, 8, H><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: edge_row_team_kernel<OP, 16, H><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: edge_row_team_kernel<OP, 32, H><<<grid, kBlock, 0, s>>>(a); break;
+    default: edge_row_team_kernel<OP, 64, H><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+// Launches the team kernel (and the long-row kernel when a plan lists long rows) for H in {1,2,4,8}.
+template <int OP>
+static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeRowArgs a, hipStream_t s) {
+  const int H = a.H;
+  if (!(H == 1 || H == 2 || H == 4 || H == 8) || !aligned16(a.x0) || !aligned16(a.out) ||
+      (a.x1 && !aligned16(a.x1)) || (a.x2 && !aligned16(a.x2))) {
+    edge_row_scalar_kernel<OP><<<dim3(unsigned(ceil_div(int64_t(g->nrows) * H, kBlock))), kBlock, 0, s>>>(a);
+    HGNN_LAUNCH_CHECK("edge_row_scalar_kernel");
+    return HGNN_OK;
+  }
+  // lanes per row: about one 8-element vector per lane for the mean row (rowsum over an edge-id map
+  // walks one non-zero per lane instead)
+  const double per_row = double(g->nnz) * ((OP == kSum && a.eid) ? 1.0 : H / 8.0) / double(g->nrows > 0 ? g->nrows : 1);
+  int LR = 4;
+  while (LR < kWave && LR < per_row) LR <<= 1;
+  a.skip_above = (p && p->n_big > 0) ? p->big_deg : 0;
+  a.big_row = p ? p->big_row : nullptr;
+  dim3 grid(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / LR))));
+  switch (H) {
+    case 1: launch_team_h<OP, 1>(LR, grid, s, a); break;
+    case 2: launch_team_h<OP, 2>(LR, grid, s, a); break;
+    case 4: launch_team_h<OP, 4>(LR, grid, s, a); break;
+    default: launch_team_h<OP, 8>(LR, grid, s, a); break;
+  }
+  HGNN_LAUNCH_CHECK("edge_row_team_kernel");
+  if (a.skip_above > 0) {
+    dim3 gb(unsigned(p->n_big));
+    switch (H) {
+      case 1: edge_row_block_kernel<OP, 1><<<gb, kBigBlock, 0, s>>>(a); break;
+      case 2: edge_row_block_kernel<OP, 2><<<gb, kBigBlock, 0, s>>>(a); break;
+      case 4: edge_row_block_kernel<OP, 4><<<gb, kBigBlock, 0, s>>>(a); break;
+      default: edge_row_block_kernel<OP, 8><<<gb, kBigBlock, 0, s>>>(a); break;
+    }
+    HGNN_LAUNCH_CHECK("edge_row_block_kernel");
+  }
+  return HGNN_OK;
+}
+
+static hgnn_status edge_rows_common(const char* who, const hgnn_csr* g, const hgnn_plan* p, int H, bool allow_eid) {
   hgnn_status st = check_csr_args(g, who);
   if (st != HGNN_OK) return st;
   HGNN_REQUIRE(H >= 1, HGNN_EINVAL, "%s: H = %d must be positive", who, H);
-  HGNN_REQUIRE(g->eid == nullptr, HGNN_EUNSUPPORTED, "%s: an edge-id map is not supported here", who);
+  HGNN_REQUIRE(allow_eid || g->eid == nullptr, HGNN_EUNSUPPORTED, "%s: an edge-id map is not supported here", who);
   if (p)
     HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
                  "%s: the plan was built for another graph", who);
@@ -245,84 +373,57 @@ extern "C" {
 hgnn_status hgnn_edge_softmax(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* e, hgnn_half* alpha,
                               void* stream) {
   clear_error();
-  hgnn_status st = softmax_common("hgnn_edge_softmax", g, p, H);
+  hgnn_status st = edge_rows_common("hgnn_edge_softmax", g, p, H, false);
   if (st != HGNN_OK) return st;
   if (g->nnz == 0 || g->nrows == 0) return HGNN_OK;
   HGNN_REQUIRE(e && alpha, HGNN_EINVAL, "hgnn_edge_softmax: e or alpha is NULL");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  SoftmaxArgs a{};
+  EdgeRowArgs a{};
   a.rowptr = g->rowptr;
-  a.e = reinterpret_cast<const half_t*>(e);
+  a.x0 = reinterpret_cast<const half_t*>(e);
   a.out = reinterpret_cast<half_t*>(alpha);
+  a.total = g->nnz * H;
   a.nrows = g->nrows;
   a.H = H;
-  if (kWave % H != 0) {
-    softmax_fwd_scalar_kernel<<<dim3(unsigned(ceil_div(int64_t(g->nrows) * H, kBlock))), kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("softmax_fwd_scalar_kernel");
-    return HGNN_OK;
-  }
-  a.skip_above = p ? p->big_deg : 0;
-  a.big_row = p ? p->big_row : nullptr;
-  softmax_fwd_wave_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(a);
-  HGNN_LAUNCH_CHECK("softmax_fwd_wave_kernel");
-  if (p && p->n_big > 0) {
-    softmax_fwd_big_kernel<<<dim3(unsigned(p->n_big)), kBigBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("softmax_fwd_big_kernel");
-  }
-  return HGNN_OK;
+  return launch_edge_rows<kFwd>(g, p, a, static_cast<hipStream_t>(stream));
 }
 
 hgnn_status hgnn_edge_softmax_bwd(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* alpha,
                                   const hgnn_half* dalpha, const hgnn_half* e, float neg_slope, hgnn_half* de,
                                   void* stream) {
   clear_error();
-  hgnn_status st = softmax_common("hgnn_edge_softmax_bwd", g, p, H);
+  hgnn_status st = edge_rows_common("hgnn_edge_softmax_bwd", g, p, H, false);
   if (st != HGNN_OK) return st;
   if (g->nnz == 0 || g->nrows == 0) return HGNN_OK;
   HGNN_REQUIRE(alpha && dalpha && de, HGNN_EINVAL, "hgnn_edge_softmax_bwd: alpha, dalpha or de is NULL");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  SoftmaxArgs a{};
+  EdgeRowArgs a{};
   a.rowptr = g->rowptr;
-  a.e = reinterpret_cast<const half_t*>(e);
-  a.alpha = reinterpret_cast<const half_t*>(alpha);
-  a.dalpha = reinterpret_cast<const half_t*>(dalpha);
+  a.x0 = reinterpret_cast<const half_t*>(alpha);
+  a.x1 = reinterpret_cast<const half_t*>(dalpha);
+  a.x2 = reinterpret_cast<const half_t*>(e);
   a.out = reinterpret_cast<half_t*>(de);
+  a.total = g->nnz * H;
   a.nrows = g->nrows;
   a.H = H;
   a.slope = neg_slope;
-  if (kWave % H != 0) {
-    softmax_bwd_scalar_kernel<<<dim3(unsigned(ceil_div(int64_t(g->nrows) * H, kBlock))), kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("softmax_bwd_scalar_kernel");
-    return HGNN_OK;
-  }
-  a.skip_above = p ? p->big_deg : 0;
-  a.big_row = p ? p->big_row : nullptr;
-  softmax_bwd_wave_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(a);
-  HGNN_LAUNCH_CHECK("softmax_bwd_wave_kernel");
-  if (p && p->n_big > 0) {
-    softmax_bwd_big_kernel<<<dim3(unsigned(p->n_big)), kBigBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("softmax_bwd_big_kernel");
-  }
-  return HGNN_OK;
+  return launch_edge_rows<kBwd>(g, p, a, static_cast<hipStream_t>(stream));
 }
 
-hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, int32_t H, const hgnn_half* t, hgnn_half* out, void* stream) {
+hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* t, hgnn_half* out,
+                             void* stream) {
   clear_error();
-  hgnn_status st = check_csr_args(g, "hgnn_edge_rowsum");
+  hgnn_status st = edge_rows_common("hgnn_edge_rowsum", g, p, H, true);
   if (st != HGNN_OK) return st;
-  HGNN_REQUIRE(H >= 1, HGNN_EINVAL, "hgnn_edge_rowsum: H = %d must be positive", H);
   if (g->nrows == 0) return HGNN_OK;
   HGNN_REQUIRE(out != nullptr && (g->nnz == 0 || t != nullptr), HGNN_EINVAL, "hgnn_edge_rowsum: t or out is NULL");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  RowsumArgs a{g->rowptr, g->eid, reinterpret_cast<const half_t*>(t), reinterpret_cast<half_t*>(out), g->nrows, H};
-  if (kWave % H != 0) {
-    edge_rowsum_scalar_kernel<<<dim3(unsigned(ceil_div(int64_t(g->nrows) * H, kBlock))), kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("edge_rowsum_scalar_kernel");
-  } else {
-    edge_rowsum_wave_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("edge_rowsum_wave_kernel");
-  }
-  return HGNN_OK;
+  EdgeRowArgs a{};
+  a.rowptr = g->rowptr;
+  a.eid = g->eid;
+  a.x0 = reinterpret_cast<const half_t*>(t);
+  a.out = reinterpret_cast<half_t*>(out);
+  a.total = g->nnz * H;
+  a.nrows = g->nrows;
+  a.H = H;
+  return launch_edge_rows<kSum>(g, p, a, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -13,7 +13,6 @@ namespace hgnn {
 struct SpmmArgs {
   const int* rowptr;
   const int* col;
-  const int* erow;  // COO row ids (discretized kernels only)
   const int* eid;
   const half_t* w;  // [nnz][H] or nullptr
   const half_t* X;
@@ -24,9 +23,12 @@ struct SpmmArgs {
   int nrows;
   int F, H, D;
   int reduce;
+  float one;  // 1.0f
   // discretized kernels
   int S;
   int64_t nseg;
+  const int* seg_lo;  // row of the first / last edge of every segment
+  const int* seg_hi;
   half_t* staging;  // [2*nseg][stage_ld]
   int stage_ld;
   const int* split_row;
@@ -60,20 +62,17 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x)
 // ---------------------------------------------------------------------------------------------------
 // Vertex-parallel SpMM: one wave per row; the G groups of the wave stride over the row's
 // non-zeros, then their fp32 partial vectors are added across groups with lane shuffles.
+// Rows longer than kLongRow are left to a second kernel that gives a 1024-thread workgroup
+// to each of them (a single wave cannot keep enough loads in flight for a hub of 10^5 edges).
 // ---------------------------------------------------------------------------------------------------
-template <int L, bool HAS_W>
-__global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
+constexpr int kLongRow = 4096;
+constexpr int kLongBlock = 1024;
+
+// acc += sum over the non-zeros k in [beg, end) visited by group g (stride G) of w_k * X[col_k, f0..f0+7]
+template <int L, bool HAS_W, int U>
+__device__ __forceinline__ void row_accumulate(const SpmmArgs& a, int beg, int end, int g, int f0c, int head,
+                                               float (&acc)[8]) {
   constexpr int G = kWave / L;
-  constexpr int U = 4;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int g = lane / L, l = lane % L;
-  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
-  if (row >= a.nrows) return;
-  const int f0 = 8 * l;
-  const bool active = f0 < a.F;
-  const int head = active ? f0 / a.D : 0;
-  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int k = beg + g; k < end; k += G * U) {
     half8_t x[U];
     float wv[U];
@@ -82,14 +81,14 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
       const int kk = k + u * G;
       x[u] = half8_t(0);
       wv[u] = 0.f;
-      if (kk < end && active) {
+      if (kk < end) {
         const int c = a.col[kk];
-        x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0);
+        x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
         if (HAS_W) {
           const int64_t slot = a.eid ? a.eid[kk] : kk;
           wv[u] = float(a.w[slot * a.H + head]);
         } else {
-          wv[u] = 1.f;
+          wv[u] = a.one;
         }
       }
     }
@@ -101,7 +100,66 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] += __shfl_xor(acc[i], off);
   }
+}
+
+template <int L, bool HAS_W>
+__global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  if (row >= a.nrows) return;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+  if (end - beg > kLongRow) return;  // handled by spmm_longrow_kernel
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  row_accumulate<L, HAS_W, 4>(a, beg, end, g, f0c, f0c / a.D, acc);
   if (g == 0 && active) store8(a.Y + row * a.ldy + f0, acc, scale_of(a, int(row)));
+}
+
+// Workgroup b looks at rows [b*1024, (b+1)*1024); every row longer than kLongRow is reduced by all
+// 16 waves together: wave w takes the w-th sixteenth of the row, partial vectors meet in LDS and
+// wave 0 adds them in wave order and stores the row.  No atomics, fixed order.
+template <int L, bool HAS_W>
+__global__ __launch_bounds__(kLongBlock) void spmm_longrow_kernel(SpmmArgs a) {
+  constexpr int NW = kLongBlock / kWave;
+  __shared__ int s_list[kLongBlock];
+  __shared__ int s_n;
+  __shared__ float s_part[NW][8 * L];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  if (threadIdx.x == 0) s_n = 0;
+  __syncthreads();
+  const int64_t r = int64_t(blockIdx.x) * kLongBlock + threadIdx.x;
+  if (r < a.nrows && a.rowptr[r + 1] - a.rowptr[r] > kLongRow) s_list[atomicAdd(&s_n, 1)] = int(r);
+  __syncthreads();
+  const int nlong = s_n;
+  for (int t = 0; t < nlong; ++t) {
+    const int row = s_list[t];
+    const int beg = a.rowptr[row], end = a.rowptr[row + 1];
+    const int chunk = (end - beg + NW - 1) / NW;
+    const int b = beg + wave * chunk < end ? beg + wave * chunk : end;
+    const int e = b + chunk < end ? b + chunk : end;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    row_accumulate<L, HAS_W, 8>(a, b, e, g, f0c, f0c / a.D, acc);
+    if (g == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s_part[wave][f0 + i] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0 && g == 0 && active) {
+      float tot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tot[i] += s_part[w][f0 + i];
+      store8(a.Y + int64_t(row) * a.ldy + f0, tot, scale_of(a, row));
+    }
+    __syncthreads();
+  }
 }
 
 // Scalar path for shapes the 16-byte path cannot take: one thread per (row, feature).
@@ -124,10 +182,14 @@ __global__ __launch_bounds__(kBlock) void spmm_scalar_kernel(SpmmArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 // Discretized-reduction SpMM, pass 1 (section 5.2): one wave per segment of S edges.
-//  phase 1  the wave loads the segment's column ids, row ids and edge values once, coalesced,
-//           into LDS (the two-phase load of section 4.1; LDS reads broadcast to a group);
-//  phase 2  group g walks its contiguous chunk of the segment with a running reduction; a row
-//           piece that starts and ends inside the chunk is scaled and stored straight to Y;
+//  phase 1  the wave loads the segment's column ids and edge values once, coalesced, into LDS
+//           (the two-phase load of section 4.1; LDS reads broadcast to a group) and derives the
+//           row id of every edge from the offset array: the rows seg_row_lo..seg_row_hi mark
+//           their first edge in LDS and a wave-wide running maximum spreads the ids.  No per-edge
+//           row array is read from memory.
+//  phase 2  group g walks its contiguous chunk of the segment, four edges per step, with a
+//           running reduction; a row piece that starts and ends inside the chunk is scaled and
+//           stored straight to Y;
 //  merge    pieces that touch a chunk border are parked in LDS (fp32, scaled) and group 0 sews
 //           them together in order: rows that lie inside the segment are stored to Y, the piece
 //           entering from the previous segment and the piece leaving into the next go to the
@@ -138,36 +200,42 @@ __global__ __launch_bounds__(kBlock) void spmm_scalar_kernel(SpmmArgs a) {
 __host__ __device__ inline int align16i(int v) { return (v + 15) & ~15; }
 
 struct SegLds {
-  int col_off, row_off, w_off, vec_off, flag_off, total;
+  int per;   // LDS entries per lane (multiple of 4); the padded segment holds 64*per edges
+  int spad;
+  int col_off, row_off, blk_off, w_off, vec_off, flag_off, total;
 };
 __host__ __device__ inline SegLds seg_lds_layout(int S, int H, bool has_w, int L) {
   SegLds o;
   const int G = kWave / L;
+  o.per = 4 * ((S + 255) / 256);  // = seg_slots_per_lane(S)
+  o.spad = kWave * o.per;
   o.col_off = 0;
-  o.row_off = align16i(S * 4);
-  o.w_off = o.row_off + align16i((S + 2) * 4);
-  o.vec_off = o.w_off + (has_w ? align16i(S * H * 2) : 0);
+  o.row_off = o.col_off + o.spad * 4;
+  o.blk_off = o.row_off + o.spad * 4;
+  o.w_off = o.blk_off + align16i(o.spad);  // one int per 4 edges
+  o.vec_off = o.w_off + (has_w ? align16i(o.spad * H * 2) : 0);
   o.flag_off = o.vec_off + 2 * G * 8 * L * 4;
   o.total = o.flag_off + align16i(3 * G * 4);
   return o;
 }
 
-template <int L, bool HAS_W>
+template <int L, bool HAS_W, bool OFF32>
 __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
-  constexpr int U = 4;
   constexpr int VEC = 8 * L;  // floats per parked vector
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
-  const int head = active ? f0 / a.D : 0;
+  const int f0c = active ? f0 : 0;  // idle lanes of a group load a valid address and drop the result
+  const int head = f0c / a.D;
   const int S = a.S;
   const SegLds lay = seg_lds_layout(S, a.H, HAS_W, L);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
-  int* s_row = reinterpret_cast<int*>(base + lay.row_off);  // s_row[i+1] = row of edge i; [0] and [n+1] = neighbours
+  int* s_row = reinterpret_cast<int*>(base + lay.row_off);  // row id of every edge of the segment
+  int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);  // per 4 edges: their common row id, or -1
   half_t* s_w = reinterpret_cast<half_t*>(base + lay.w_off);
   float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
@@ -179,26 +247,32 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+  const int per = lay.per, spad = lay.spad;
+  int row_lo = 0, row_hi = -1;
+  bool seg_left_open = false, seg_right_open = false;
+  if (valid) {
+    row_lo = a.seg_lo[seg];
+    row_hi = a.seg_hi[seg];
+    seg_left_open = int64_t(a.rowptr[row_lo]) < e0;
+    seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
+  }
 
-  // ---- phase 1: coalesced stage of the segment's graph data
-  for (int i = lane; i < n; i += kWave) {
+  // ---- phase 1: coalesced stage of column ids and edge values, then the row id of every edge
+  for (int i = lane; i < spad; i += kWave) {
+    const bool in = i < n;
     const int64_t k = e0 + i;
-    s_col[i] = a.col[k];
-    s_row[i + 1] = a.erow[k];
+    const int c = in ? a.col[k] : 0;
+    s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;  // OFF32: byte offset of the neighbour's row
     if (HAS_W) {
-      const int64_t slot = a.eid ? a.eid[k] : k;
-      for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = a.w[slot * a.H + h];
+      const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
+      for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
     }
   }
-  if (lane == 0 && valid) {
-    s_row[0] = e0 > 0 ? a.erow[e0 - 1] : -1;
-    s_row[n + 1] = e0 + n < a.nnz ? a.erow[e0 + n] : -1;
-  }
   if (lane < G) m_flag[lane] = 0;
-  __syncthreads();
+  seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
 
   // ---- phase 2: running reduction over this group's chunk
-  const int C = (S + G - 1) / G;
+  const int C = 4 * ((S + 4 * G - 1) / (4 * G));  // edges per group, a multiple of 4
   const int c0 = g * C < n ? g * C : n;
   const int c1 = c0 + C < n ? c0 + C : n;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -223,44 +297,56 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
       }
     }
   };
+  auto gather = [&](int c) -> half8_t {
+    if (OFF32) {  // byte offset in 32 bits: scalar base address + per-lane offset
+      const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
+      return *reinterpret_cast<const half8_t*>(reinterpret_cast<const char*>(a.X) + boff);
+    }
+    return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+  };
 
   if (c0 < c1) {
-    cur = s_row[c0 + 1];
-    lo = s_row[c0] == cur;
+    cur = s_row[c0];
+    lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
   }
-  for (int i = c0; i < c1; i += U) {
-    half8_t x[U];
-    float wv[U];
-    int r[U];
+  for (int i = c0; i < c1; i += 4) {
+    const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
+    const int blk = s_blk[i >> 2];
+    half8_t x[4];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int ii = i + u;
-      x[u] = half8_t(0);
-      wv[u] = 0.f;
-      r[u] = cur;
-      if (ii < c1) {
-        r[u] = s_row[ii + 1];
-        if (active) {
-          x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(s_col[ii]) * a.ldx + f0);
-          wv[u] = HAS_W ? float(s_w[ii * a.H + head]) : 1.f;
+    for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
+    float wv[4] = {a.one, a.one, a.one, a.one};  // 1.0 the compiler cannot fold: keeps convert+add in one v_fma_mix
+    if (HAS_W) {
+      if (a.H == 1) {
+        const half4_t w4 = *reinterpret_cast<const half4_t*>(s_w + i);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = float(w4[u]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = float(s_w[(i + u) * a.H + head]);
+      }
+    }
+    if (blk == cur) {  // the four edges continue the current row: no bookkeeping at all
+#pragma unroll
+      for (int u = 0; u < 4; ++u) fma8(acc, wv[u], x[u]);
+    } else {
+      const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i + u < c1) {
+          if (rows[u] != cur) {
+            flush(false);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+            cur = rows[u];
+            lo = false;
+          }
+          fma8(acc, wv[u], x[u]);
         }
       }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (i + u < c1) {
-        if (r[u] != cur) {
-          flush(false);
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-          cur = r[u];
-          lo = false;
-        }
-        fma8(acc, wv[u], x[u]);
-      }
-    }
   }
-  if (c0 < c1) flush(s_row[c1 + 1] == cur);
+  if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
   __syncthreads();
 
   // ---- merge: group 0 sews the parked pieces together in chunk order
@@ -374,7 +460,6 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
   SpmmArgs a{};
   a.rowptr = g->rowptr;
   a.col = g->col;
-  a.erow = g->row;
   a.eid = g->eid;
   a.w = reinterpret_cast<const half_t*>(w);
   a.X = reinterpret_cast<const half_t*>(X);
@@ -388,32 +473,39 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
   a.H = w ? H : 1;  // without edge values the head structure is irrelevant
   a.D = F / a.H;
   a.reduce = int(op);
+  a.one = 1.0f;
   return a;
 }
 
-template <bool HAS_W>
-static void launch_row(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
-  switch (L) {
-    case 1: spmm_row_kernel<1, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    case 2: spmm_row_kernel<2, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    case 4: spmm_row_kernel<4, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    case 8: spmm_row_kernel<8, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    case 16: spmm_row_kernel<16, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    case 32: spmm_row_kernel<32, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-    default: spmm_row_kernel<64, HAS_W><<<grid, kBlock, 0, s>>>(a); break;
-  }
+template <int L, bool HAS_W>
+static void launch_row_pair(dim3 grid, dim3 grid_long, hipStream_t s, const SpmmArgs& a) {
+  spmm_row_kernel<L, HAS_W><<<grid, kBlock, 0, s>>>(a);
+  spmm_longrow_kernel<L, HAS_W><<<grid_long, kLongBlock, 0, s>>>(a);
 }
 
 template <bool HAS_W>
+static void launch_row(int L, dim3 grid, dim3 grid_long, hipStream_t s, const SpmmArgs& a) {
+  switch (L) {
+    case 1: launch_row_pair<1, HAS_W>(grid, grid_long, s, a); break;
+    case 2: launch_row_pair<2, HAS_W>(grid, grid_long, s, a); break;
+    case 4: launch_row_pair<4, HAS_W>(grid, grid_long, s, a); break;
+    case 8: launch_row_pair<8, HAS_W>(grid, grid_long, s, a); break;
+    case 16: launch_row_pair<16, HAS_W>(grid, grid_long, s, a); break;
+    case 32: launch_row_pair<32, HAS_W>(grid, grid_long, s, a); break;
+    default: launch_row_pair<64, HAS_W>(grid, grid_long, s, a); break;
+  }
+}
+
+template <bool HAS_W, bool OFF32>
 static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a) {
   switch (L) {
-    case 1: spmm_seg_kernel<1, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: spmm_seg_kernel<2, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: spmm_seg_kernel<4, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: spmm_seg_kernel<8, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: spmm_seg_kernel<16, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: spmm_seg_kernel<32, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
-    default: spmm_seg_kernel<64, HAS_W><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: spmm_seg_kernel<1, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: spmm_seg_kernel<2, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: spmm_seg_kernel<4, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: spmm_seg_kernel<8, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: spmm_seg_kernel<16, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: spmm_seg_kernel<32, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    default: spmm_seg_kernel<64, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
   }
 }
 
@@ -446,9 +538,10 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
   if (vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
     const int L = pow2_at_least(F / 8);
     dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock)));
-    if (edge_val) launch_row<true>(L, grid, s, a);
-    else launch_row<false>(L, grid, s, a);
-    HGNN_LAUNCH_CHECK("spmm_row_kernel");
+    dim3 grid_long(unsigned(ceil_div(g->nrows, kLongBlock)));
+    if (edge_val) launch_row<true>(L, grid, grid_long, s, a);
+    else launch_row<false>(L, grid, grid_long, s, a);
+    HGNN_LAUNCH_CHECK("spmm_row_kernel / spmm_longrow_kernel");
   } else {
     dim3 grid(unsigned(ceil_div(int64_t(g->nrows) * F, kBlock)));
     spmm_scalar_kernel<<<grid, kBlock, 0, s>>>(a);
@@ -472,7 +565,8 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
   if (g->nrows == 0) return HGNN_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
-  a.erow = g->row ? g->row : p->edge_row;
+  a.seg_lo = p->seg_row_lo;
+  a.seg_hi = p->seg_row_hi;
   a.S = p->S;
   a.nseg = p->nseg;
   a.staging = reinterpret_cast<half_t*>(p->staging);
@@ -489,8 +583,15 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
                a.H, lds);
   const int64_t nblk = ceil_div(p->nseg, kWavesPerBlock);
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
-  if (edge_val) launch_seg<true>(L, grid, lds, s, a);
-  else launch_seg<false>(L, grid, lds, s, a);
+  // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
+  const bool off32 = uint64_t(g->ncols) * uint64_t(ldx) * 2u < (uint64_t(1) << 32);
+  if (edge_val) {
+    if (off32) launch_seg<true, true>(L, grid, lds, s, a);
+    else launch_seg<true, false>(L, grid, lds, s, a);
+  } else {
+    if (off32) launch_seg<false, true>(L, grid, lds, s, a);
+    else launch_seg<false, false>(L, grid, lds, s, a);
+  }
   HGNN_LAUNCH_CHECK("spmm_seg_kernel");
   if (a.n_split > 0) {
     const int G = kWave / L;

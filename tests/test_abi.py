@@ -70,7 +70,7 @@ def test_argument_errors_are_caught_on_the_host(lib, hgnn):
     assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 0, X, Y, None) == EINVAL
     assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 1, None, Y, None) == EINVAL
     assert lib.hgnn_edge_softmax_bwd(ctypes.byref(g), None, 1, X, None, None, 0.2, Y, None) == EINVAL
-    assert lib.hgnn_edge_rowsum(ctypes.byref(g), 0, X, Y, None) == EINVAL
+    assert lib.hgnn_edge_rowsum(ctypes.byref(g), None, 0, X, Y, None) == EINVAL
     eidg = make_csr(hgnn)
     eidg.eid = 0x3000
     assert lib.hgnn_edge_softmax(ctypes.byref(eidg), None, 1, X, Y, None) == EUNSUP

@@ -116,7 +116,7 @@ SHAPES = [  # (F, H, has_w, reduce, S, pad)
 def test_spmm_plain_and_discretized_shapes(hgnn, dev, F, H, has_w, reduce, S, pad):
     print(f"spmm F={F} H={H} w={has_w} reduce={reduce} S={S} pad={pad}", flush=True)
     V, ncols = 1237, 997
-    rowptr, col = rand_graph(V, ncols, 11, F + S, hubs=((5, 3000), (700, 777), (1236, 300)), empties=(0, 6, 1235))
+    rowptr, col = rand_graph(V, ncols, 11, F + S, hubs=((5, 5000), (700, 777), (1236, 300)), empties=(0, 6, 1235))
     E = col.size
     r = np.random.default_rng(F * 7 + H)
     Xh = f16(r.standard_normal((ncols, F + pad)))
@@ -312,7 +312,7 @@ def test_edge_softmax_forward_backward(hgnn, dev, H):
             compare(f"de with_e={with_e}", down(de), ref_de, mag + 2.0 ** -14)
 
 
-@pytest.mark.parametrize("H", [1, 4, 3])
+@pytest.mark.parametrize("H", [1, 2, 4, 8, 3])
 def test_edge_rowsum_rows_and_columns(hgnn, dev, H):
     V, ncols = 600, 450
     rowptr, col = rand_graph(V, ncols, 8, 60 + H, hubs=((7, 5000),), empties=(1,))
@@ -323,12 +323,17 @@ def test_edge_rowsum_rows_and_columns(hgnn, dev, H):
     td = up(t16, dev)
     out_r = torch.empty((V, H), dtype=torch.float16, device=dev)
     out_c = torch.empty((ncols, H), dtype=torch.float16, device=dev)
-    hgnn.hgnn_edge_rowsum(g, H, td, out_r)
-    hgnn.hgnn_edge_rowsum(gt, H, td, out_c)
     t64 = t16.astype(np.float64)
-    compare("rowsum", down(out_r), oracle.edge_rowsum(rowptr, t64), oracle.edge_rowsum(rowptr, np.abs(t64)))
-    compare("colsum", down(out_c), oracle.edge_colsum(rowptr, col, t64, ncols),
-            oracle.edge_colsum(rowptr, col, np.abs(t64), ncols))
+    for with_plan in (False, True):  # with a plan the long row goes to the workgroup-per-row kernel
+        p = hgnn.hgnn_plan_create(g, 256, 64, 8) if with_plan else None
+        pt = hgnn.hgnn_plan_create(gt, 256, 64, 8) if with_plan else None
+        out_r.fill_(9.0)
+        out_c.fill_(9.0)
+        hgnn.hgnn_edge_rowsum(g, p, H, td, out_r)
+        hgnn.hgnn_edge_rowsum(gt, pt, H, td, out_c)
+        compare("rowsum", down(out_r), oracle.edge_rowsum(rowptr, t64), oracle.edge_rowsum(rowptr, np.abs(t64)))
+        compare("colsum", down(out_c), oracle.edge_colsum(rowptr, col, t64, ncols),
+                oracle.edge_colsum(rowptr, col, np.abs(t64), ncols))
 
 
 def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat"):
@@ -392,8 +397,8 @@ def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat"):
     compare(f"{tag} ds", down(ds)[esel], ds_ref, mag)
     d_el = torch.empty((V, H), dtype=torch.float16, device=dev)
     d_er = torch.empty((V, H), dtype=torch.float16, device=dev)
-    hgnn.hgnn_edge_rowsum(g, H, ds, d_el)
-    hgnn.hgnn_edge_rowsum(gt, H, ds, d_er)
+    hgnn.hgnn_edge_rowsum(g, p, H, ds, d_el)
+    hgnn.hgnn_edge_rowsum(gt, pt, H, ds, d_er)
     ds_full = down(ds).astype(np.float64)
     compare(f"{tag} d_el", down(d_el), oracle.edge_rowsum(w.rowptr, ds_full),
             oracle.edge_rowsum(w.rowptr, np.abs(ds_full)) + 2.0 ** -14)
