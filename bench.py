@@ -24,6 +24,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 
+# L2-miss bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated
+# against a 1 GiB copy; see profiles/hgnn_kernels_*.md.  Keyed by (workload, kernel instantiation).
+MEASURED_TRAFFIC = {
+    ("c5_dense_degree", "hgnn::spmm_seg_kernel<8, false, true>"): 12.06e9,
+    ("c4_gcn_large", "hgnn::spmm_seg_kernel<16, true, true>"): 15.80e9,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -89,48 +96,64 @@ def main():
         d_el = torch.empty((V, H), dtype=half, device=dev)
         d_er = torch.empty((V, H), dtype=half, device=dev)
 
-    # ---- algorithmic (compulsory) bytes per op: every input read once, every output written once
-    wbytes = 2 if ew is not None else 0
+    # ---- bytes per op.  "min": algorithmic / compulsory (every input read once, every output written once,
+    # i.e. an infinite cache) -- the figure the roofline fraction uses, it can never exceed the peak.
+    # "req": requested bytes of a cache-less machine (one feature row gathered per non-zero).
+    def spmm_min(hw, transposed):
+        return E * (4 + 2 * hw + (4 if (transposed and hw) else 0)) + 4 * (V + 1) + 2 * (2 * V * F)
 
-    def spmm_bytes(weighted_h, transposed):
-        return E * (4 + 2 * weighted_h + (4 if (transposed and weighted_h) else 0)) + 4 * (V + 1) + 2 * (2 * V * F)
+    def spmm_req(hw, transposed):
+        return E * (4 + 2 * hw + (4 if (transposed and hw) else 0) + 2 * F) + V * (4 + 2 * F)
 
-    ops = []  # (name, kernel family, bytes, fn)
+    Lg = 1
+    while Lg < F // 8:
+        Lg *= 2
+    off32 = "true" if V * X.stride(0) * 2 < (1 << 32) else "false"
+    seg_name = lambda hw: f"hgnn::spmm_seg_kernel<{Lg}, {'true' if hw else 'false'}, {off32}>"
+    row_name = lambda hw: f"hgnn::spmm_row_kernel<{Lg}, {'true' if hw else 'false'}> (+ spmm_longrow_kernel)"
+    ops = []  # (name, kernel, min bytes, fn, requested bytes)
     wH = 1 if ew is not None else 0
-    ops.append(("spmm_fwd_plain", "spmm_row", spmm_bytes(wH, False), lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y)))
-    ops.append(("spmm_bwd_plain", "spmm_row", spmm_bytes(wH, True), lambda: hgnn.hgnn_spmm(gt, ew, 1, dY, Y)))
-    ops.append(("spmm_fwd_disc", "spmm_seg", spmm_bytes(wH, False),
-                lambda: hgnn.hgnn_spmm_discretized(plan, g, ew, 1, X, Y)))
-    ops.append(("spmm_bwd_disc", "spmm_seg", spmm_bytes(wH, True),
-                lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, ew, 1, dY, Y)))
+    ops.append(("spmm_fwd_plain", row_name(wH), spmm_min(wH, False), lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y), spmm_req(wH, False)))
+    ops.append(("spmm_bwd_plain", row_name(wH), spmm_min(wH, True), lambda: hgnn.hgnn_spmm(gt, ew, 1, dY, Y), spmm_req(wH, True)))
+    ops.append(("spmm_fwd_disc", seg_name(wH), spmm_min(wH, False),
+                lambda: hgnn.hgnn_spmm_discretized(plan, g, ew, 1, X, Y), spmm_req(wH, False)))
+    ops.append(("spmm_bwd_disc", seg_name(wH), spmm_min(wH, True),
+                lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, ew, 1, dY, Y), spmm_req(wH, True)))
     if args.workload in ("c2", "c5"):  # GIN: mean aggregation as well (discretized reduction scaling)
-        ops.append(("spmm_fwd_disc_mean", "spmm_seg", spmm_bytes(0, False),
-                    lambda: hgnn.hgnn_spmm_discretized(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN)))
-        ops.append(("spmm_bwd_disc_mean", "spmm_seg", spmm_bytes(0, True),
-                    lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, None, 1, dY, Y, op=hgnn.HGNN_MEAN)))
+        ops.append(("spmm_fwd_disc_mean", seg_name(0), spmm_min(0, False),
+                    lambda: hgnn.hgnn_spmm_discretized(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN), spmm_req(0, False)))
+        ops.append(("spmm_bwd_disc_mean", seg_name(0), spmm_min(0, True),
+                    lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, None, 1, dY, Y, op=hgnn.HGNN_MEAN), spmm_req(0, True)))
     if has_gat:
         EH = E * H
-        ops.append(("gat_score", "sddmm", E * 4 + 4 * (V + 1) + 2 * V * F + 2 * EH,
-                    lambda: hgnn.hgnn_sddmm(g, plan, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, X, X, e, a_l, a_r, 0.2)))
-        ops.append(("edge_softmax", "softmax", 4 * EH + 4 * (V + 1), lambda: hgnn.hgnn_edge_softmax(g, plan, H, e, alpha)))
-        ops.append(("gat_spmm_fwd", "spmm_seg", spmm_bytes(H, False),
-                    lambda: hgnn.hgnn_spmm_discretized(plan, g, alpha, H, X, out)))
-        ops.append(("gat_spmm_bwd", "spmm_seg", spmm_bytes(H, True),
-                    lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, alpha, H, dY, dh)))
-        ops.append(("sddmm_dot", "sddmm", E * 4 + 4 * (V + 1) + 2 * (2 * V * F) + 2 * EH,
-                    lambda: hgnn.hgnn_sddmm(g, plan, hgnn.HGNN_SDDMM_DOT, H, D, dY, X, dalpha)))
-        ops.append(("edge_softmax_bwd", "softmax", 8 * EH + 4 * (V + 1),
-                    lambda: hgnn.hgnn_edge_softmax_bwd(g, plan, H, alpha, dalpha, ds, e=e, neg_slope=0.2)))
-        ops.append(("score_bwd_rowsum", "rowsum", 2 * EH + 4 * (V + 1) + 2 * V * H, lambda: hgnn.hgnn_edge_rowsum(g, plan, H, ds, d_el)))
-        ops.append(("score_bwd_colsum", "rowsum", 2 * EH + 4 * E + 4 * (V + 1) + 2 * V * H,
-                    lambda: hgnn.hgnn_edge_rowsum(gt, plan_t, H, ds, d_er)))
+        b = E * 4 + 4 * (V + 1) + 2 * V * F + 2 * EH
+        ops.append(("gat_score", f"hgnn::edge_score_seg_kernel<{H}> (+ vertex_proj_kernel)", b,
+                    lambda: hgnn.hgnn_sddmm(g, plan, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, X, X, e, a_l, a_r, 0.2), b + 8 * EH))
+        b = 4 * EH + 4 * (V + 1)
+        ops.append(("edge_softmax", "hgnn::edge_row_team_kernel<0, ..> (+ edge_row_block_kernel)", b,
+                    lambda: hgnn.hgnn_edge_softmax(g, plan, H, e, alpha), b))
+        ops.append(("gat_spmm_fwd", seg_name(H), spmm_min(H, False),
+                    lambda: hgnn.hgnn_spmm_discretized(plan, g, alpha, H, X, out), spmm_req(H, False)))
+        ops.append(("gat_spmm_bwd", seg_name(H), spmm_min(H, True),
+                    lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, alpha, H, dY, dh), spmm_req(H, True)))
+        b = E * 4 + 4 * (V + 1) + 2 * (2 * V * F) + 2 * EH
+        ops.append(("sddmm_dot", f"hgnn::sddmm_seg_kernel<{Lg}>", b,
+                    lambda: hgnn.hgnn_sddmm(g, plan, hgnn.HGNN_SDDMM_DOT, H, D, dY, X, dalpha), b + E * 2 * F))
+        b = 8 * EH + 4 * (V + 1)
+        ops.append(("edge_softmax_bwd", "hgnn::edge_row_team_kernel<1, ..> (+ edge_row_block_kernel)", b,
+                    lambda: hgnn.hgnn_edge_softmax_bwd(g, plan, H, alpha, dalpha, ds, e=e, neg_slope=0.2), b))
+        b = 2 * EH + 4 * (V + 1) + 2 * V * H
+        ops.append(("score_bwd_rowsum", "hgnn::edge_row_team_kernel<2, ..>", b,
+                    lambda: hgnn.hgnn_edge_rowsum(g, plan, H, ds, d_el), b))
+        ops.append(("score_bwd_colsum", "hgnn::edge_row_team_kernel<2, ..>", b + 4 * E,
+                    lambda: hgnn.hgnn_edge_rowsum(gt, plan_t, H, ds, d_er), b + 4 * E))
     step_bytes = sum(o[2] for o in ops)
 
     def step(events=None):
-        for i, (_, _, _, fn) in enumerate(ops):
+        for i, o in enumerate(ops):
             if events is not None:
                 events[i][0].record()
-            fn()
+            o[3]()
             if events is not None:
                 events[i][1].record()
 
@@ -144,6 +167,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # events are recorded on torch's current stream, which is the stream handed to every hgnn call
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
           for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -156,16 +180,29 @@ def main():
     op_ms = np.array([[a.elapsed_time(b) for (a, b) in ev[k]] for k in range(args.steps)])  # [steps, ops]
     op_avg = op_ms.mean(axis=0)
 
-    # dominant op = the one with the most time; its roofline uses its own algorithmic bytes
-    dom = int(np.argmax(op_avg))
-    dom_name, dom_family, dom_bytes, _ = ops[dom]
-    dom_gbps = dom_bytes / (op_avg[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                "algorithmic_bytes": int(dom_bytes), "avg_ms": round(float(op_avg[dom]), 4)}
+    # dominant kernel = the kernel instantiation with the most time in a step; its launches are averaged
+    by_kernel = {}
+    for i, o in enumerate(ops):
+        by_kernel.setdefault(o[1], []).append(i)
+    dom_kernel = max(by_kernel, key=lambda k: sum(op_avg[i] for i in by_kernel[k]))
+    idx = by_kernel[dom_kernel]
+    dom_ms = float(np.mean([op_avg[i] for i in idx]))
+    dom_bytes = float(np.mean([ops[i][2] for i in idx]))
+    dom_req = float(np.mean([ops[i][4] for i in idx]))
+    dom_gbps = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get((w.name, dom_kernel))
+    roofline = {"bound": "hbm", "kernel": dom_kernel, "launches_per_step": len(idx),
+                "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "algorithmic_bytes": int(dom_bytes), "avg_ms": round(dom_ms, 4),
+                "requested_bytes": int(dom_req), "requested_GBps": round(dom_req / (dom_ms * 1e-3) / 1e9, 1),
+                "note": "achieved = compulsory (infinite-cache) bytes / time; requested_* counts one gathered "
+                        "feature row per non-zero and may exceed the peak when caches hit; traffic = L2-miss "
+                        "bytes per launch from rocprofv3 (profiles/), which includes Infinity-Cache hits"}
 
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
-    detail = {n: {"ms": round(float(t), 4), "GBps": round(b / (t * 1e-3) / 1e9, 1)} for (n, _, b, _), t in zip(ops, op_avg)}
+    detail = {o[0]: {"ms": round(float(t), 4), "min_GBps": round(o[2] / (t * 1e-3) / 1e9, 1),
+                     "req_GBps": round(o[4] / (t * 1e-3) / 1e9, 1)} for o, t in zip(ops, op_avg)}
     layer_ms = {}
     if has_gat:
         layer_ms["gat_fwd_bwd_ms"] = round(float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in (
@@ -205,8 +242,9 @@ def main():
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
-        for (n, fam, b, _), t in zip(ops, op_avg):
-            print(f"{n:22s} {fam:9s} {t:9.4f} ms  {b / 1e6:10.1f} MB  {b / (t * 1e-3) / 1e9:9.1f} GB/s", file=sys.stderr)
+        for o, t in zip(ops, op_avg):
+            print(f"{o[0]:20s} {t:9.4f} ms  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
+                  f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
     print(json.dumps(line))
     return 0
 

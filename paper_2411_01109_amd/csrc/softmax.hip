@@ -26,7 +26,8 @@ struct EdgeRowArgs {
   half_t* out;       // forward: alpha.      backward: de.      rowsum: [nrows][H]
   int64_t total;     // nnz * H
   int nrows, H;
-  int skip_above;    // rows longer than this are left to the long-row kernel (0 = none)
+  int skip_above;    // rows longer than this are left to a later tier (0 = none)
+  int skip_below;    // rows of at most this many non-zeros were done by an earlier tier (-1 = none)
   float slope;
 };
 
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(kBlock) void edge_row_team_kernel(EdgeRowArgs a) {
   const int64_t row = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * GR + lane / LR;
   if (row >= a.nrows) return;
   const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  if (a.skip_above > 0 && end - beg > a.skip_above) return;
+  if ((a.skip_above > 0 && end - beg > a.skip_above) || end - beg <= a.skip_below) return;
   const SubWaveTeam<LR> team;
   if (OP == kSum) {
     rowsum_row<H>(a, team, int(row), beg, end);
@@ -330,17 +331,26 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   const double per_row = double(g->nnz) * ((OP == kSum && a.eid) ? 1.0 : H / 8.0) / double(g->nrows > 0 ? g->nrows : 1);
   int LR = 4;
   while (LR < kWave && LR < per_row) LR <<= 1;
-  a.skip_above = (p && p->n_big > 0) ? p->big_deg : 0;
+  const int big = (p && p->n_big > 0) ? p->big_deg : 0;
   a.big_row = p ? p->big_row : nullptr;
-  dim3 grid(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / LR))));
-  switch (H) {
-    case 1: launch_team_h<OP, 1>(LR, grid, s, a); break;
-    case 2: launch_team_h<OP, 2>(LR, grid, s, a); break;
-    case 4: launch_team_h<OP, 4>(LR, grid, s, a); break;
-    default: launch_team_h<OP, 8>(LR, grid, s, a); break;
+  // tier 1: sub-wave teams take the rows they can hold in registers; tier 2: a whole wave per row
+  // for the rows between that and the plan's long-row threshold; tier 3: a workgroup per long row.
+  const int t1 = (OP == kSum && a.eid) ? LR * 4 : LR * 8 * kKeepVec / H;
+  for (int tier = 0; tier < 2; ++tier) {
+    const int lr = tier == 0 ? LR : kWave;
+    if (tier == 1 && (LR == kWave || (big > 0 && t1 >= big))) break;
+    a.skip_below = tier == 0 ? -1 : t1;
+    a.skip_above = (tier == 0 && LR < kWave) ? (big > 0 && big < t1 ? big : t1) : big;
+    dim3 grid(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / lr))));
+    switch (H) {
+      case 1: launch_team_h<OP, 1>(lr, grid, s, a); break;
+      case 2: launch_team_h<OP, 2>(lr, grid, s, a); break;
+      case 4: launch_team_h<OP, 4>(lr, grid, s, a); break;
+      default: launch_team_h<OP, 8>(lr, grid, s, a); break;
+    }
+    HGNN_LAUNCH_CHECK("edge_row_team_kernel");
   }
-  HGNN_LAUNCH_CHECK("edge_row_team_kernel");
-  if (a.skip_above > 0) {
+  if (big > 0) {
     dim3 gb(unsigned(p->n_big));
     switch (H) {
       case 1: edge_row_block_kernel<OP, 1><<<gb, kBigBlock, 0, s>>>(a); break;
