@@ -71,7 +71,7 @@ typedef struct {
   int64_t nnz;           /* |E|, must be < 2^31 */
   const int32_t* rowptr; /* [nrows+1] non-decreasing, rowptr[0] = 0, rowptr[nrows] = nnz */
   const int32_t* col;    /* [nnz] 0 <= col < ncols, ascending inside a row (duplicates allowed) */
-  const int32_t* row;    /* [nnz] COO row id of every non-zero, or NULL (a plan supplies it) */
+  const int32_t* row;    /* [nnz] COO row id of every non-zero, or NULL (only read by hgnn_sddmm without a plan) */
   const int32_t* eid;    /* [nnz] or NULL.  Edge tensors are read at slot eid[k] for CSR position k
                             (the transposed graph refers to the original graph's edge tensors) */
 } hgnn_csr;
@@ -98,7 +98,7 @@ hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T,
  * segment k = [k*S, min(nnz,(k+1)*S)).  The plan holds, on the device: the row
  * of the first and last edge of every segment, the ascending list of "split"
  * rows (first and last edge in different segments) with the segments they
- * span, COO row ids (built when g->row is NULL), the staging buffer for
+ * span, the list of rows longer than 2048 edges, the staging buffer for
  * conflicting partial sums (2 vectors of max_F halves per segment; the paper's
  * buffer is one vector per CTA, section 5.2.3) and per-vertex fp32 scratch of
  * 2*max_H floats per row/column for the factorised GAT score.
@@ -141,9 +141,11 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s
  * U is [nrows][ldu], Vt is [ncols][ldv], a_l / a_r are [H*D] (GAT_SCORE only).
- * Needs COO row ids: g->row or a plan (p may be NULL when g->row is given).
- * With a plan, GAT_SCORE first projects every vertex once (fp32 scratch in the
- * plan) and then adds per edge.  g->eid must be NULL. */
+ * With a plan (p != NULL, the fast path) the kernels walk the plan's segments and
+ * take row ids from rowptr; GAT_SCORE then projects every vertex once (fp32
+ * scratch in the plan) and adds per edge.  Without a plan the row of a non-zero
+ * comes from g->row when given, else from a binary search in rowptr (slow).
+ * g->eid must be NULL. */
 hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sddmm_op op, int32_t H, int32_t D,
                        const hgnn_half* U, int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
                        const hgnn_half* a_r, float neg_slope, hgnn_half* out, void* stream);

@@ -52,6 +52,18 @@ inline int pow2_at_least(int v) {
 
 hgnn_status check_csr_args(const hgnn_csr* g, const char* who);
 
+// row that holds CSR position k: the last r with rowptr[r] <= k (an upper bound minus one, so
+// empty rows are skipped)
+__host__ __device__ inline int row_of_edge(const int* rowptr, int nrows, int64_t k) {
+  int lo = 0, hi = nrows + 1;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (int64_t(rowptr[mid]) <= k) lo = mid + 1;
+    else hi = mid;
+  }
+  return lo - 1;
+}
+
 typedef int int4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 
@@ -118,7 +130,6 @@ struct hgnn_plan {
   int32_t* split_seg_lo = nullptr;  // [n_split]
   int32_t* split_seg_hi = nullptr;  // [n_split]
   int32_t* big_row = nullptr;       // [n_big]
-  int32_t* edge_row = nullptr;      // [nnz] COO row ids (owned copy, built from rowptr)
   hgnn_half* staging = nullptr;     // [2*nseg][max_F]
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32
 };

@@ -63,27 +63,14 @@ static const char* const kRule[] = {"ok",
                                     "an edge id is outside [0, nnz)",
                                     "a COO row id disagrees with rowptr"};
 
-// ---- COO row ids from the offset array ---------------------------------------------------------------
-__global__ void expand_rows_kernel(const int* __restrict__ rowptr, int nrows, int64_t nnz, int* __restrict__ erow) {
-  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-  if (k >= nnz) return;
-  // last r with rowptr[r] <= k: upper bound over rowptr[0..nrows], minus one (skips empty rows)
-  int lo = 0, hi = nrows + 1;
-  while (lo < hi) {
-    int mid = (lo + hi) >> 1;
-    if (int64_t(rowptr[mid]) <= k) lo = mid + 1;
-    else hi = mid;
-  }
-  erow[k] = lo - 1;
-}
-
-__global__ void seg_rows_kernel(const int* __restrict__ erow, int64_t nnz, int S, int64_t nseg, int* __restrict__ lo,
-                                int* __restrict__ hi) {
+// ---- first and last row of every segment: binary searches in the offset array ------------------------
+__global__ void seg_rows_kernel(const int* __restrict__ rowptr, int nrows, int64_t nnz, int S, int64_t nseg,
+                                int* __restrict__ lo, int* __restrict__ hi) {
   int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   if (k >= nseg) return;
   int64_t e0 = k * S, e1 = e0 + S < nnz ? e0 + S : nnz;
-  lo[k] = erow[e0];
-  hi[k] = erow[e1 - 1];
+  lo[k] = row_of_edge(rowptr, nrows, e0);
+  hi[k] = row_of_edge(rowptr, nrows, e1 - 1);
 }
 
 // ---- ordered compaction of the rows that satisfy a predicate -------------------------------------------
@@ -256,7 +243,6 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->split_seg_lo);
   (void)hipFree(p->split_seg_hi);
   (void)hipFree(p->big_row);
-  (void)hipFree(p->edge_row);
   (void)hipFree(p->staging);
   (void)hipFree(p->vscratch);
   delete p;
@@ -265,12 +251,9 @@ void hgnn_plan_destroy(hgnn_plan* p) {
 static hgnn_status plan_build(hgnn_plan* p, const hgnn_csr* g, hipStream_t s) {
   const int64_t E = g->nnz;
   if (E > 0) {
-    HGNN_HIP(hipMalloc(&p->edge_row, sizeof(int) * size_t(E)));
-    expand_rows_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, E, p->edge_row);
-    HGNN_LAUNCH_CHECK("expand_rows_kernel");
     HGNN_HIP(hipMalloc(&p->seg_row_lo, sizeof(int) * size_t(p->nseg)));
     HGNN_HIP(hipMalloc(&p->seg_row_hi, sizeof(int) * size_t(p->nseg)));
-    seg_rows_kernel<<<dim3(unsigned(ceil_div(p->nseg, kBlock))), kBlock, 0, s>>>(p->edge_row, E, p->S, p->nseg,
+    seg_rows_kernel<<<dim3(unsigned(ceil_div(p->nseg, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, E, p->S, p->nseg,
                                                                                   p->seg_row_lo, p->seg_row_hi);
     HGNN_LAUNCH_CHECK("seg_rows_kernel");
     // staging: two partial vectors (entering piece / leaving piece) per segment

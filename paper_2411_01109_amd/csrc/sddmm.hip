@@ -15,7 +15,7 @@ namespace hgnn {
 struct SddmmArgs {
   const int* rowptr;
   const int* col;
-  const int* erow;  // COO row ids (kernels that run without a plan)
+  const int* erow;  // COO row ids from the caller, or nullptr (then the row is searched in rowptr)
   const int* seg_lo;
   const int* seg_hi;
   const half_t* U;
@@ -188,7 +188,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_edge_kernel(SddmmArgs a) {
       v[q] = half8_t(0);
       if (i + q < c1 && active) {
         const int64_t k = e0 + i + q;
-        u[q] = *reinterpret_cast<const half8_t*>(a.U + int64_t(a.erow[k]) * a.ldu + f0);
+        const int r = a.erow ? a.erow[k] : row_of_edge(a.rowptr, a.nrows, k);
+        u[q] = *reinterpret_cast<const half8_t*>(a.U + int64_t(r) * a.ldu + f0);
         v[q] = *reinterpret_cast<const half8_t*>(a.Vt + int64_t(a.col[k]) * a.ldv + f0);
       }
     }
@@ -211,7 +212,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_scalar_kernel(SddmmArgs a) {
   if (idx >= a.nnz * a.H) return;
   const int64_t k = idx / a.H;
   const int h = int(idx % a.H);
-  const half_t* u = a.U + int64_t(a.erow[k]) * a.ldu + h * a.D;
+  const int r = a.erow ? a.erow[k] : row_of_edge(a.rowptr, a.nrows, k);
+  const half_t* u = a.U + int64_t(r) * a.ldu + h * a.D;
   const half_t* v = a.Vt + int64_t(a.col[k]) * a.ldv + h * a.D;
   float p = 0.f;
   if (SCORE) {
@@ -360,12 +362,11 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
   if (p)
     HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
                  "hgnn_sddmm: the plan was built for another graph");
-  HGNN_REQUIRE(g->row != nullptr || p != nullptr, HGNN_EINVAL, "hgnn_sddmm: needs COO row ids (g->row) or a plan");
   hipStream_t s = static_cast<hipStream_t>(stream);
   SddmmArgs a{};
   a.rowptr = g->rowptr;
   a.col = g->col;
-  a.erow = g->row ? g->row : p->edge_row;
+  a.erow = g->row;
   a.U = reinterpret_cast<const half_t*>(U);
   a.Vt = reinterpret_cast<const half_t*>(Vt);
   a.a_l = reinterpret_cast<const half_t*>(a_l);

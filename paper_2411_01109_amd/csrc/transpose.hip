@@ -32,14 +32,7 @@ __global__ void source_rows_kernel(const int* __restrict__ rowptr, int nrows, co
                                    int* __restrict__ col_T) {
   int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   if (k >= nnz) return;
-  const int e = eid_T[k];
-  int lo = 0, hi = nrows + 1;
-  while (lo < hi) {
-    int mid = (lo + hi) >> 1;
-    if (rowptr[mid] <= e) lo = mid + 1;
-    else hi = mid;
-  }
-  col_T[k] = lo - 1;
+  col_T[k] = row_of_edge(rowptr, nrows, eid_T[k]);
 }
 
 }  // namespace hgnn

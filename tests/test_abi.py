@@ -64,8 +64,7 @@ def test_argument_errors_are_caught_on_the_host(lib, hgnn):
     sd = lambda *a: lib.hgnn_sddmm(ctypes.byref(g), None, *a)
     assert sd(0, 1, 7, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # odd F
     assert sd(7, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # unknown op
-    assert sd(0, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # no COO rows and no plan
-    assert b"COO" in lib.hgnn_last_error()
+    assert sd(0, 1, 8, None, 8, X, 8, None, None, 0.2, Y, None) == EINVAL   # U NULL
     assert sd(1, 1, 8, X, 8, X, 8, None, None, 0.2, Y, None) == EINVAL      # GAT score without a_l / a_r
     assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 0, X, Y, None) == EINVAL
     assert lib.hgnn_edge_softmax(ctypes.byref(g), None, 1, None, Y, None) == EINVAL

@@ -255,6 +255,9 @@ def test_sddmm_dot_and_score(hgnn, dev, H, D):
     mag = np.einsum("ehd,ehd->eh", np.abs(U.astype(np.float64)).reshape(V, H, D)[row],
                     np.abs(Vt.astype(np.float64)).reshape(ncols, H, D)[col])
     compare("dot", down(out), ref, mag)
+    out.zero_()  # no plan and no COO rows: the row of a non-zero is searched in the offset array
+    hgnn.hgnn_sddmm(g, None, hgnn.HGNN_SDDMM_DOT, H, D, up(U, dev), up(Vt, dev), out)
+    compare("dot without plan", down(out), ref, mag)
     # GAT score needs both sides on the same vertex set
     rowptr2, col2 = rand_graph(V, V, 9, H + D, hubs=((9, 2000),))
     g2 = hgnn.Csr(up(rowptr2, dev), up(col2, dev))
