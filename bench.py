@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--seg-edges", type=int, default=256)
+    ap.add_argument("--col-blocks", type=int, default=0, help="column blocks of the SpMM plans: 0 = automatic, 1 = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print a per-op table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -80,8 +81,8 @@ def main():
     g = hgnn.Csr(up(w.rowptr), up(w.col))
     t0 = time.time()
     gt = hgnn.hgnn_transpose(g)
-    plan = hgnn.hgnn_plan_create(g, args.seg_edges, F, H)
-    plan_t = hgnn.hgnn_plan_create(gt, args.seg_edges, F, H)
+    plan = hgnn.hgnn_plan_create(g, args.seg_edges, F, H, col_blocks=args.col_blocks)
+    plan_t = hgnn.hgnn_plan_create(gt, args.seg_edges, F, H, col_blocks=args.col_blocks)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
     X, dY = up(feat_np), up(grad_np)
@@ -234,7 +235,7 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": w.name, "V": V, "E": E, "F": F, "H": H, "seg_edges": args.seg_edges,
+        "config": {"workload": w.name, "V": V, "E": E, "F": F, "H": H, "seg_edges": args.seg_edges, "col_blocks": hgnn.hgnn_plan_col_blocks(plan),
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),

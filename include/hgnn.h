@@ -103,12 +103,31 @@ hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T,
  * buffer is one vector per CTA, section 5.2.3) and per-vertex fp32 scratch of
  * 2*max_H floats per row/column for the factorised GAT score.
  * The graph is validated first.  A plan may be used by one stream at a time.
- * seg_edges in [1, 2048]; max_F >= 8 multiple of 8; max_H >= 1. */
-hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, hgnn_plan** out,
-                             void* stream);
+ * seg_edges in [1, 2048]; max_F >= 8 multiple of 8; max_H >= 1.
+ *
+ * col_blocks: column blocking of hgnn_spmm_discretized.  1 = none.  n in [2, 64]:
+ * the columns are cut into n equal ranges, the non-zeros of every range are
+ * copied into a CSR of their own (a row's share of a range is a contiguous piece
+ * of the row because columns ascend inside a row) with a segment plan each; the
+ * SpMM then runs range after range, so that all compute units gather from one
+ * slice of X at a time, into n partial outputs [n][nrows][max_F] fp16 that one
+ * more pass adds per row.  Every partial still covers at most seg_edges edges and
+ * is scaled before it is rounded (section 5.2.2).  0 = automatic: blocking is
+ * chosen when the feature table (ncols * max_F halves) is larger than an L2 but
+ * fits the Infinity Cache and rows are long.  Costs nnz * 8 bytes plus the
+ * partial outputs.  The other entry points ignore it. */
+hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, int32_t col_blocks,
+                             hgnn_plan** out, void* stream);
 int64_t hgnn_plan_num_segments(const hgnn_plan* p);
 int32_t hgnn_plan_num_split_rows(const hgnn_plan* p);
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p);
+int32_t hgnn_plan_col_blocks(const hgnn_plan* p); /* 1 when the plan is not column blocked */
+/* Column block b of a blocked plan, copied to HOST buffers (each may be NULL):
+ * *nnz_b; rowptr_b [nrows+1]; col_b, eid_b [*nnz_b] (eid_b = slot in the edge
+ * tensors = g->eid[k] or k of the original non-zero k); seg_row_lo / seg_row_hi
+ * [ceil(*nnz_b / seg_edges)].  Call once with NULL arrays to learn *nnz_b.  Synchronizes. */
+hgnn_status hgnn_plan_block_export(const hgnn_plan* p, int32_t b, int64_t* nnz_b, int32_t* rowptr_b, int32_t* col_b,
+                                   int32_t* eid_b, int32_t* seg_row_lo, int32_t* seg_row_hi);
 /* Copies the plan's integer arrays to HOST buffers (each may be NULL to skip):
  * seg_row_lo / seg_row_hi [num_segments]; split_row / split_seg_lo /
  * split_seg_hi [num_split_rows].  Synchronizes. */

@@ -20,7 +20,8 @@ HGNN_SDDMM_DOT, HGNN_SDDMM_GAT_SCORE = 0, 1
 
 EXPORTS = (
     "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_plan_create",
-    "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_export",
+    "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks",
+    "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum",
 )
@@ -58,7 +59,7 @@ def load() -> ctypes.CDLL:
     lib.hgnn_last_error.argtypes = []
     lib.hgnn_csr_validate.argtypes = [csr, vp]
     lib.hgnn_transpose.argtypes = [csr, vp, vp, vp, vp]
-    lib.hgnn_plan_create.argtypes = [csr, i32, i32, i32, ctypes.POINTER(vp), vp]
+    lib.hgnn_plan_create.argtypes = [csr, i32, i32, i32, i32, ctypes.POINTER(vp), vp]
     lib.hgnn_plan_num_segments.restype = i64
     lib.hgnn_plan_num_segments.argtypes = [vp]
     lib.hgnn_plan_num_split_rows.restype = i32
@@ -66,6 +67,9 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_seg_edges.restype = i32
     lib.hgnn_plan_seg_edges.argtypes = [vp]
     lib.hgnn_plan_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.hgnn_plan_col_blocks.restype = i32
+    lib.hgnn_plan_col_blocks.argtypes = [vp]
+    lib.hgnn_plan_block_export.argtypes = [vp, i32, ctypes.POINTER(i64), vp, vp, vp, vp, vp]
     lib.hgnn_plan_destroy.restype = None
     lib.hgnn_plan_destroy.argtypes = [vp]
     lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
@@ -156,10 +160,31 @@ def hgnn_transpose(g: Csr, stream=None) -> Csr:
     return Csr(rowptr_T, col_T, ncols=g.nrows, eid=eid_T)
 
 
-def hgnn_plan_create(g: Csr, seg_edges: int = 256, max_F: int = 128, max_H: int = 8, stream=None) -> Plan:
+def hgnn_plan_create(g: Csr, seg_edges: int = 256, max_F: int = 128, max_H: int = 8, col_blocks: int = 1,
+                     stream=None) -> Plan:
+    """col_blocks: 1 = no column blocking, 0 = automatic, n >= 2 = n column blocks."""
     out = ctypes.c_void_p()
-    _check(load().hgnn_plan_create(g.ref, seg_edges, max_F, max_H, ctypes.byref(out), _stream(stream)))
+    _check(load().hgnn_plan_create(g.ref, seg_edges, max_F, max_H, col_blocks, ctypes.byref(out), _stream(stream)))
     return Plan(out.value, g)
+
+
+def hgnn_plan_col_blocks(p: Plan) -> int:
+    return load().hgnn_plan_col_blocks(p.handle)
+
+
+def hgnn_plan_block_export(p: Plan, b: int):
+    """-> dict of host int32 numpy arrays of column block b (rowptr, col, eid, seg_row_lo, seg_row_hi)."""
+    import numpy as np
+    lib = load()
+    n = ctypes.c_int64(0)
+    _check(lib.hgnn_plan_block_export(p.handle, b, ctypes.byref(n), None, None, None, None, None))
+    S = hgnn_plan_seg_edges(p)
+    nseg = (n.value + S - 1) // S
+    arrs = {"rowptr": np.empty(p.graph.nrows + 1, np.int32), "col": np.empty(n.value, np.int32),
+            "eid": np.empty(n.value, np.int32), "seg_row_lo": np.empty(nseg, np.int32),
+            "seg_row_hi": np.empty(nseg, np.int32)}
+    _check(lib.hgnn_plan_block_export(p.handle, b, ctypes.byref(n), *[a.ctypes.data for a in arrs.values()]))
+    return arrs
 
 
 def hgnn_plan_num_segments(p: Plan) -> int:

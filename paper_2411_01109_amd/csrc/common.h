@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "hgnn.h"
 
 namespace hgnn {
@@ -132,4 +134,19 @@ struct hgnn_plan {
   int32_t* big_row = nullptr;       // [n_big]
   hgnn_half* staging = nullptr;     // [2*nseg][max_F]
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32
+  // column blocking of the SpMM (nb > 1): block b holds the non-zeros whose column lies in
+  // [b*block_width, (b+1)*block_width), stored block after block as a CSR of their own
+  int32_t nb = 1;
+  int32_t block_width = 0;
+  int32_t* brp = nullptr;           // [nb][nrows+1] offset arrays of the blocks
+  int32_t* bcol = nullptr;          // [nnz] column ids, block-major
+  int32_t* beid = nullptr;          // [nnz] slot in the edge tensors of every blocked non-zero
+  std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
+  std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
+  hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs
 };
+
+namespace hgnn {
+hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
+hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);
+}  // namespace hgnn

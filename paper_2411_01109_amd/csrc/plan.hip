@@ -51,6 +51,8 @@ __global__ void validate_kernel(hgnn_csr g, int* err) {
       if (r < 0 || r >= g.nrows) bad = 6;
       else if (!(int64_t(g.rowptr[r]) <= i && i < int64_t(g.rowptr[r + 1]))) bad = 6;
     }
+    // a column id may only drop where a new row starts
+    if (!bad && i > 0 && g.col[i - 1] > c && int64_t(g.rowptr[row_of_edge(g.rowptr, g.nrows, i)]) != i) bad = 7;
   }
   if (bad) atomicMin(err, bad);
 }
@@ -61,7 +63,8 @@ static const char* const kRule[] = {"ok",
                                     "rowptr decreases",
                                     "a column id is outside [0, ncols)",
                                     "an edge id is outside [0, nnz)",
-                                    "a COO row id disagrees with rowptr"};
+                                    "a COO row id disagrees with rowptr",
+                                    "column ids are not ascending inside a row"};
 
 // ---- first and last row of every segment: binary searches in the offset array ------------------------
 __global__ void seg_rows_kernel(const int* __restrict__ rowptr, int nrows, int64_t nnz, int S, int64_t nseg,
@@ -190,6 +193,39 @@ __global__ void split_segs_kernel(const int* __restrict__ rowptr, const int* __r
   hi[i] = (rowptr[r + 1] - 1) / S;
 }
 
+// Builds the segment arrays, split-row list and staging buffer of p for the graph g (p->S, p->nseg,
+// p->max_F set by the caller).  sub = true: p is the sub-plan of one column block.
+hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub) {
+  const int64_t E = g->nnz;
+  if (E > 0) {
+    HGNN_HIP(hipMalloc(&p->seg_row_lo, sizeof(int) * size_t(p->nseg)));
+    HGNN_HIP(hipMalloc(&p->seg_row_hi, sizeof(int) * size_t(p->nseg)));
+    seg_rows_kernel<<<dim3(unsigned(ceil_div(p->nseg, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, E, p->S, p->nseg,
+                                                                                  p->seg_row_lo, p->seg_row_hi);
+    HGNN_LAUNCH_CHECK("seg_rows_kernel");
+    // staging: two partial vectors (entering piece / leaving piece) per segment
+    HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F)));
+    HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F), s));
+  }
+  hgnn_status st = compact_rows(SplitPred{g->rowptr, p->S}, g->nrows, &p->split_row, &p->n_split, s);
+  if (st != HGNN_OK) return st;
+  if (p->n_split > 0) {
+    HGNN_HIP(hipMalloc(&p->split_seg_lo, sizeof(int) * size_t(p->n_split)));
+    HGNN_HIP(hipMalloc(&p->split_seg_hi, sizeof(int) * size_t(p->n_split)));
+    split_segs_kernel<<<dim3(unsigned(ceil_div(p->n_split, kBlock))), kBlock, 0, s>>>(
+        g->rowptr, p->split_row, p->n_split, p->S, p->split_seg_lo, p->split_seg_hi);
+    HGNN_LAUNCH_CHECK("split_segs_kernel");
+  }
+  if (!sub) {  // a column block's sub-plan only serves the SpMM kernels
+    st = compact_rows(BigPred{g->rowptr, p->big_deg}, g->nrows, &p->big_row, &p->n_big, s);
+    if (st != HGNN_OK) return st;
+    size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
+    if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
+  }
+  HGNN_HIP(hipStreamSynchronize(s));
+  return HGNN_OK;
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
@@ -227,7 +263,7 @@ hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream) {
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   (void)hipFree(derr);
   if (e != hipSuccess) return fail(HGNN_EHIP, "hgnn_csr_validate: %s", hipGetErrorString(e));
-  if (herr != kNoError) return fail(HGNN_EINVAL, "hgnn_csr_validate: %s", kRule[herr > 0 && herr < 7 ? herr : 0]);
+  if (herr != kNoError) return fail(HGNN_EINVAL, "hgnn_csr_validate: %s", kRule[herr > 0 && herr < 8 ? herr : 0]);
   return HGNN_OK;
 }
 
@@ -235,8 +271,15 @@ int64_t hgnn_plan_num_segments(const hgnn_plan* p) { return p ? p->nseg : 0; }
 int32_t hgnn_plan_num_split_rows(const hgnn_plan* p) { return p ? p->n_split : 0; }
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p) { return p ? p->S : 0; }
 
+int32_t hgnn_plan_col_blocks(const hgnn_plan* p) { return p ? p->nb : 0; }
+
 void hgnn_plan_destroy(hgnn_plan* p) {
   if (!p) return;
+  for (hgnn_plan* q : p->sub) hgnn_plan_destroy(q);
+  (void)hipFree(p->brp);
+  (void)hipFree(p->bcol);
+  (void)hipFree(p->beid);
+  (void)hipFree(p->bstage);
   (void)hipFree(p->seg_row_lo);
   (void)hipFree(p->seg_row_hi);
   (void)hipFree(p->split_row);
@@ -248,37 +291,8 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   delete p;
 }
 
-static hgnn_status plan_build(hgnn_plan* p, const hgnn_csr* g, hipStream_t s) {
-  const int64_t E = g->nnz;
-  if (E > 0) {
-    HGNN_HIP(hipMalloc(&p->seg_row_lo, sizeof(int) * size_t(p->nseg)));
-    HGNN_HIP(hipMalloc(&p->seg_row_hi, sizeof(int) * size_t(p->nseg)));
-    seg_rows_kernel<<<dim3(unsigned(ceil_div(p->nseg, kBlock))), kBlock, 0, s>>>(g->rowptr, g->nrows, E, p->S, p->nseg,
-                                                                                  p->seg_row_lo, p->seg_row_hi);
-    HGNN_LAUNCH_CHECK("seg_rows_kernel");
-    // staging: two partial vectors (entering piece / leaving piece) per segment
-    HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F)));
-    HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F), s));
-  }
-  hgnn_status st = compact_rows(SplitPred{g->rowptr, p->S}, g->nrows, &p->split_row, &p->n_split, s);
-  if (st != HGNN_OK) return st;
-  if (p->n_split > 0) {
-    HGNN_HIP(hipMalloc(&p->split_seg_lo, sizeof(int) * size_t(p->n_split)));
-    HGNN_HIP(hipMalloc(&p->split_seg_hi, sizeof(int) * size_t(p->n_split)));
-    split_segs_kernel<<<dim3(unsigned(ceil_div(p->n_split, kBlock))), kBlock, 0, s>>>(
-        g->rowptr, p->split_row, p->n_split, p->S, p->split_seg_lo, p->split_seg_hi);
-    HGNN_LAUNCH_CHECK("split_segs_kernel");
-  }
-  st = compact_rows(BigPred{g->rowptr, p->big_deg}, g->nrows, &p->big_row, &p->n_big, s);
-  if (st != HGNN_OK) return st;
-  size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
-  if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
-  HGNN_HIP(hipStreamSynchronize(s));
-  return HGNN_OK;
-}
-
-hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, hgnn_plan** out,
-                             void* stream) {
+hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, int32_t col_blocks,
+                             hgnn_plan** out, void* stream) {
   clear_error();
   HGNN_REQUIRE(out != nullptr, HGNN_EINVAL, "hgnn_plan_create: out is NULL");
   *out = nullptr;
@@ -289,6 +303,8 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
   HGNN_REQUIRE(max_F >= 8 && max_F % 8 == 0, HGNN_EINVAL, "hgnn_plan_create: max_F = %d must be a positive multiple of 8",
                max_F);
   HGNN_REQUIRE(max_H >= 1, HGNN_EINVAL, "hgnn_plan_create: max_H = %d must be positive", max_H);
+  HGNN_REQUIRE(col_blocks >= 0 && col_blocks <= 64, HGNN_EINVAL, "hgnn_plan_create: col_blocks = %d outside [0, 64]",
+               col_blocks);
   st = hgnn_csr_validate(g, stream);
   if (st != HGNN_OK) return st;
   hgnn_plan* p = new (std::nothrow) hgnn_plan();
@@ -301,12 +317,51 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
   p->max_F = max_F;
   p->max_H = max_H;
   p->big_deg = 2048;
-  st = plan_build(p, g, static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  st = plan_build_arrays(p, g, s, false);
+  if (st == HGNN_OK) {
+    int nb = col_blocks;
+    if (nb == 0) {
+      // automatic: block only when the feature table is too large for an XCD's 4 MB L2 but small enough
+      // for the 256 MB Infinity Cache, and rows are long enough that a row piece per block still amortises
+      // its partial vector; about 8 MB of feature rows per block
+      const double table = double(g->ncols) * max_F * 2.0;
+      const double mean_deg = g->nrows > 0 ? double(g->nnz) / g->nrows : 0.0;
+      nb = 1;
+      if (table > 12e6 && table < 200e6 && mean_deg >= 128.0) {
+        nb = int(table / 8e6 + 0.5);
+        if (nb < 2) nb = 2;
+        if (nb > 16) nb = 16;
+      }
+    }
+    if (nb > 1 && g->nnz > 0 && g->ncols >= nb) st = build_col_blocks(p, g, nb, s);
+  }
   if (st != HGNN_OK) {
     hgnn_plan_destroy(p);
     return st;
   }
   *out = p;
+  return HGNN_OK;
+}
+
+hgnn_status hgnn_plan_block_export(const hgnn_plan* p, int32_t b, int64_t* nnz_b, int32_t* rowptr_b, int32_t* col_b,
+                                   int32_t* eid_b, int32_t* seg_row_lo, int32_t* seg_row_hi) {
+  clear_error();
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_plan_block_export: plan is NULL");
+  HGNN_REQUIRE(p->nb > 1 && b >= 0 && b < p->nb, HGNN_EINVAL, "hgnn_plan_block_export: block %d of %d", b, p->nb);
+  HGNN_HIP(hipDeviceSynchronize());
+  const int64_t off = p->boff[size_t(b)], n = p->boff[size_t(b) + 1] - off;
+  if (nnz_b) *nnz_b = n;
+  if (rowptr_b)
+    HGNN_HIP(hipMemcpy(rowptr_b, p->brp + size_t(b) * (size_t(p->nrows) + 1), sizeof(int) * (size_t(p->nrows) + 1),
+                       hipMemcpyDeviceToHost));
+  if (n > 0) {
+    if (col_b) HGNN_HIP(hipMemcpy(col_b, p->bcol + off, sizeof(int) * size_t(n), hipMemcpyDeviceToHost));
+    if (eid_b) HGNN_HIP(hipMemcpy(eid_b, p->beid + off, sizeof(int) * size_t(n), hipMemcpyDeviceToHost));
+    const hgnn_plan* q = p->sub[size_t(b)];
+    if (seg_row_lo) HGNN_HIP(hipMemcpy(seg_row_lo, q->seg_row_lo, sizeof(int) * size_t(q->nseg), hipMemcpyDeviceToHost));
+    if (seg_row_hi) HGNN_HIP(hipMemcpy(seg_row_hi, q->seg_row_hi, sizeof(int) * size_t(q->nseg), hipMemcpyDeviceToHost));
+  }
   return HGNN_OK;
 }
 

@@ -12,6 +12,7 @@ namespace hgnn {
 
 struct SpmmArgs {
   const int* rowptr;
+  const int* deg_rowptr;  // offset array that defines deg(i) for MEAN (the whole graph's, also when a column block runs)
   const int* col;
   const int* eid;
   const half_t* w;  // [nnz][H] or nullptr
@@ -40,7 +41,7 @@ struct SpmmArgs {
 __device__ __forceinline__ float scale_of(const SpmmArgs& a, int r) {
   float s = 1.f;
   if (a.reduce == HGNN_MEAN) {
-    int d = a.rowptr[r + 1] - a.rowptr[r];
+    int d = a.deg_rowptr[r + 1] - a.deg_rowptr[r];
     s = 1.f / float(d > 1 ? d : 1);
   }
   if (a.row_scale) s *= a.row_scale[r];
@@ -459,6 +460,7 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
                           int64_t ldy, int F, hgnn_reduce op, const float* row_scale) {
   SpmmArgs a{};
   a.rowptr = g->rowptr;
+  a.deg_rowptr = g->rowptr;
   a.col = g->col;
   a.eid = g->eid;
   a.w = reinterpret_cast<const half_t*>(w);
@@ -521,6 +523,77 @@ static void launch_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
   }
 }
 
+// Pass 1 and pass 2 of the discretized SpMM for the graph in `a` with the segment arrays of plan q.
+static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, bool has_w, int ncols, hipStream_t s) {
+  a.seg_lo = q->seg_row_lo;
+  a.seg_hi = q->seg_row_hi;
+  a.S = q->S;
+  a.nseg = q->nseg;
+  a.staging = reinterpret_cast<half_t*>(q->staging);
+  a.stage_ld = q->max_F;
+  a.split_row = q->split_row;
+  a.split_lo = q->split_seg_lo;
+  a.split_hi = q->split_seg_hi;
+  a.n_split = q->n_split;
+  const int L = pow2_at_least(a.F / 8);
+  const SegLds lay = seg_lds_layout(a.S, a.H, has_w, L);
+  const size_t lds = size_t(lay.total) * kWavesPerBlock;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
+               a.H, lds);
+  const int64_t nblk = ceil_div(q->nseg, kWavesPerBlock);
+  dim3 grid(unsigned(nblk > 0 ? nblk : 1));
+  // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  if (has_w) {
+    if (off32) launch_seg<true, true>(L, grid, lds, s, a);
+    else launch_seg<true, false>(L, grid, lds, s, a);
+  } else {
+    if (off32) launch_seg<false, true>(L, grid, lds, s, a);
+    else launch_seg<false, false>(L, grid, lds, s, a);
+  }
+  HGNN_LAUNCH_CHECK("spmm_seg_kernel");
+  if (a.n_split > 0) {
+    const int G = kWave / L;
+    dim3 grid2(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * G)));
+    launch_finish(L, grid2, s, a);
+    HGNN_LAUNCH_CHECK("spmm_finish_kernel");
+  }
+  return HGNN_OK;
+}
+
+// Column-blocked plans: Y[r] = sum over the blocks of their (already scaled, fp16) partial rows; fp32 sum in
+// block order, one store per row.
+template <int L>
+__global__ __launch_bounds__(kBlock) void spmm_block_sum_kernel(SpmmArgs a, const half_t* __restrict__ part, int nb,
+                                                                 int part_ld) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const int64_t r = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  if (r >= a.nrows || f0 >= a.F) return;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int b = 0; b < nb; ++b) {
+    const half8_t t = *reinterpret_cast<const half8_t*>(part + (int64_t(b) * a.nrows + r) * part_ld + f0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += float(t[i]);
+  }
+  store8(a.Y + r * a.ldy + f0, acc, 1.f);
+}
+
+static void launch_block_sum(int L, dim3 grid, hipStream_t s, const SpmmArgs& a, const half_t* part, int nb, int part_ld) {
+  switch (L) {
+    case 1: spmm_block_sum_kernel<1><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    case 2: spmm_block_sum_kernel<2><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    case 4: spmm_block_sum_kernel<4><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    case 8: spmm_block_sum_kernel<8><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    case 16: spmm_block_sum_kernel<16><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    case 32: spmm_block_sum_kernel<32><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+    default: spmm_block_sum_kernel<64><<<grid, kBlock, 0, s>>>(a, part, nb, part_ld); break;
+  }
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
@@ -565,40 +638,27 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
   if (g->nrows == 0) return HGNN_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
-  a.seg_lo = p->seg_row_lo;
-  a.seg_hi = p->seg_row_hi;
-  a.S = p->S;
-  a.nseg = p->nseg;
-  a.staging = reinterpret_cast<half_t*>(p->staging);
-  a.stage_ld = p->max_F;
-  a.split_row = p->split_row;
-  a.split_lo = p->split_seg_lo;
-  a.split_hi = p->split_seg_hi;
-  a.n_split = p->n_split;
+  if (p->nb <= 1) return run_segments(p, a, edge_val != nullptr, g->ncols, s);
+  // column-blocked plan: one discretized SpMM per block into that block's partial output, blocks one
+  // after the other so that all compute units gather from the same slice of X, then one pass adds
+  // the partials of every row.  Scales are applied per partial (section 5.2.2); the sum only adds.
+  for (int b = 0; b < p->nb; ++b) {
+    const hgnn_plan* q = p->sub[size_t(b)];
+    SpmmArgs ab = a;
+    ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
+    ab.col = p->bcol + p->boff[size_t(b)];
+    ab.eid = p->beid + p->boff[size_t(b)];
+    ab.nnz = q->nnz;
+    ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * size_t(p->nrows) * size_t(p->max_F);
+    ab.ldy = p->max_F;
+    st = run_segments(q, ab, edge_val != nullptr, g->ncols, s);
+    if (st != HGNN_OK) return st;
+  }
   const int L = pow2_at_least(F / 8);
-  const SegLds lay = seg_lds_layout(a.S, a.H, edge_val != nullptr, L);
-  const size_t lds = size_t(lay.total) * kWavesPerBlock;
-  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
-               "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
-               a.H, lds);
-  const int64_t nblk = ceil_div(p->nseg, kWavesPerBlock);
-  dim3 grid(unsigned(nblk > 0 ? nblk : 1));
-  // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
-  const bool off32 = uint64_t(g->ncols) * uint64_t(ldx) * 2u < (uint64_t(1) << 32);
-  if (edge_val) {
-    if (off32) launch_seg<true, true>(L, grid, lds, s, a);
-    else launch_seg<true, false>(L, grid, lds, s, a);
-  } else {
-    if (off32) launch_seg<false, true>(L, grid, lds, s, a);
-    else launch_seg<false, false>(L, grid, lds, s, a);
-  }
-  HGNN_LAUNCH_CHECK("spmm_seg_kernel");
-  if (a.n_split > 0) {
-    const int G = kWave / L;
-    dim3 grid2(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * G)));
-    launch_finish(L, grid2, s, a);
-    HGNN_LAUNCH_CHECK("spmm_finish_kernel");
-  }
+  const int G = kWave / L;
+  launch_block_sum(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, a,
+                   reinterpret_cast<const half_t*>(p->bstage), p->nb, p->max_F);
+  HGNN_LAUNCH_CHECK("spmm_block_sum_kernel");
   return HGNN_OK;
 }
 

@@ -75,10 +75,11 @@ def test_argument_errors_are_caught_on_the_host(lib, hgnn):
     assert lib.hgnn_edge_softmax(ctypes.byref(eidg), None, 1, X, Y, None) == EUNSUP
     # plan_create argument checks come before any device work
     out = ctypes.c_void_p()
-    assert lib.hgnn_plan_create(ctypes.byref(g), 0, 64, 1, ctypes.byref(out), None) == EINVAL
-    assert lib.hgnn_plan_create(ctypes.byref(g), 4096, 64, 1, ctypes.byref(out), None) == EINVAL
-    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 12, 1, ctypes.byref(out), None) == EINVAL
-    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 64, 1, None, None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 0, 64, 1, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 4096, 64, 1, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 12, 1, 1, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 64, 1, 65, ctypes.byref(out), None) == EINVAL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 64, 1, 1, None, None) == EINVAL
     assert out.value is None
     lib.hgnn_plan_destroy(None)  # no-op
     assert lib.hgnn_plan_num_segments(None) == 0

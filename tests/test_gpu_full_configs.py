@@ -75,7 +75,16 @@ def test_config5_dense_degree_gin_and_gat(hgnn, dev):
         s2 = compare(f"c5 gin disc bwd red={red}", down(Y)[rows_t], ref_b, abs_b)
         hgnn.hgnn_spmm(gt, None, 1, dY, Y, op=red)
         s3 = compare(f"c5 gin plain bwd red={red}", down(Y)[rows_t], ref_b, abs_b)
-        print(f"c5 gin red={red}: {s} {s1} {s2} {s3}", flush=True)
+        # column-blocked plans chosen automatically for this table size (about 30 MB, rows of ~490 edges)
+        pb = hgnn.hgnn_plan_create(g, 256, 64, 1, col_blocks=0)
+        ptb = hgnn.hgnn_plan_create(gt, 256, 64, 1, col_blocks=0)
+        assert hgnn.hgnn_plan_col_blocks(pb) == 4 and hgnn.hgnn_plan_col_blocks(ptb) == 4
+        hgnn.hgnn_spmm_discretized(pb, g, None, 1, X, Y, op=red)
+        s4 = compare(f"c5 gin blocked fwd red={red}", down(Y)[rows], ref_f, abs_f)
+        hgnn.hgnn_spmm_discretized(ptb, gt, None, 1, dY, Y, op=red)
+        s5 = compare(f"c5 gin blocked bwd red={red}", down(Y)[rows_t], ref_b, abs_b)
+        del pb, ptb
+        print(f"c5 gin red={red}: {s} {s1} {s2} {s3} blocked {s4} {s5}", flush=True)
     del Y, p, pt, gt, g
     torch.cuda.empty_cache()
     gat_layer_check(hgnn, dev, w, 1, 64, rows_fwd=sample_rows(w.rowptr, 1200, 53), tag="c5 gat")

@@ -420,3 +420,85 @@ def test_gat_small_graph_every_row(hgnn, dev):
     """A small GAT case where every row (not a sample) is compared."""
     w = wl.gat_rmat(scale=11, avg_degree=12, H=2, D=32)
     gat_layer_check(hgnn, dev, w, 2, 32, rows_fwd=np.arange(w.V, dtype=np.int32), tag="gat-small")
+
+
+# ------------------------------------------------------------------ column-blocked plans
+def numpy_block(rowptr, col, eid, V, width, b):
+    """Reference for one column block: the non-zeros with col // width == b, in storage order."""
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    m = (col // width) == b
+    rp = np.zeros(V + 1, dtype=np.int64)
+    np.add.at(rp, row[m] + 1, 1)
+    pos = np.nonzero(m)[0]
+    return np.cumsum(rp).astype(np.int32), col[m], (pos if eid is None else eid[pos]).astype(np.int32)
+
+
+@pytest.mark.parametrize("nb,S", [(2, 256), (3, 64), (8, 128), (5, 7)])
+def test_blocked_plan_bit_exact(hgnn, dev, nb, S):
+    V, ncols = 1500, 1100
+    rowptr, col = rand_graph(V, ncols, 25, 70 + nb, hubs=((3, 6000), (1499, 900)), empties=(0, 7))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    for graph, rp, cl, ei, nc in ((g, rowptr, col, None, ncols),
+                                  (gt, down(gt.rowptr), down(gt.col), down(gt.eid), V)):
+        p = hgnn.hgnn_plan_create(graph, S, 64, 1, col_blocks=nb)
+        assert hgnn.hgnn_plan_col_blocks(p) == nb
+        width = -(-nc // nb)
+        total = 0
+        for b in range(nb):
+            got = hgnn.hgnn_plan_block_export(p, b)
+            ref_rp, ref_col, ref_eid = numpy_block(rp, cl, ei, graph.nrows, width, b)
+            assert np.array_equal(got["rowptr"], ref_rp) and np.array_equal(got["col"], ref_col)
+            assert np.array_equal(got["eid"], ref_eid)
+            ref_plan = oracle.segment_plan(ref_rp, S)
+            assert np.array_equal(got["seg_row_lo"], ref_plan["seg_row_lo"])
+            assert np.array_equal(got["seg_row_hi"], ref_plan["seg_row_hi"])
+            total += ref_col.size
+        assert total == cl.size
+        # the top-level plan is unchanged by blocking
+        top, ref_top = hgnn.hgnn_plan_export(p), oracle.segment_plan(rp, S)
+        for k in ref_top:
+            assert np.array_equal(top[k], ref_top[k]), k
+
+
+def test_unsorted_columns_are_rejected(hgnn, dev):
+    rowptr, col = rand_graph(60, 60, 6, 9)
+    bad = col.copy()
+    r = int(np.argmax(np.diff(rowptr) >= 2))
+    bad[rowptr[r]], bad[rowptr[r] + 1] = 50, 3
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_csr_validate(hgnn.Csr(up(rowptr, dev), up(bad, dev)))
+    assert "ascending" in str(ei.value)
+
+
+@pytest.mark.parametrize("F,H,has_w,reduce,S,nb", [(64, 1, False, 0, 256, 4), (64, 1, True, 1, 128, 3), (128, 4, True, 0, 256, 8),
+                                                   (32, 1, False, 1, 64, 2), (48, 1, True, 0, 100, 5)])
+def test_spmm_blocked_matches_oracle(hgnn, dev, F, H, has_w, reduce, S, nb):
+    print(f"blocked spmm F={F} H={H} w={has_w} reduce={reduce} S={S} nb={nb}", flush=True)
+    V, ncols = 1237, 997
+    rowptr, col = rand_graph(V, ncols, 40, F + nb, hubs=((5, 5000), (700, 777)), empties=(0, 6, 1236))
+    E = col.size
+    r = np.random.default_rng(F + nb)
+    Xh, dYh = f16(r.standard_normal((ncols, F))), f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, H))) if has_w else None
+    rs = r.uniform(0.5, 2.0, V).astype(np.float32)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    wd = None if w is None else up(w, dev)
+    p = hgnn.hgnn_plan_create(g, S, F, H, col_blocks=nb)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, reduce=reduce, row_scale=rs.astype(np.float64), want_sabs=True)
+    Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized(p, g, wd, H, up(Xh, dev), Y, op=reduce, row_scale=up(rs, dev))
+    got = down(Y)
+    compare("blocked fwd", got, ref, sabs)
+    Y.fill_(-1.0)
+    hgnn.hgnn_spmm_discretized(p, g, wd, H, up(Xh, dev), Y, op=reduce, row_scale=up(rs, dev))
+    assert np.array_equal(down(Y).view(np.uint16), got.view(np.uint16))
+    # backward: the transposed graph carries an edge-id map, the blocks compose it
+    gt = hgnn.hgnn_transpose(g)
+    pt = hgnn.hgnn_plan_create(gt, S, F, H, col_blocks=nb)
+    dX = torch.empty((ncols, F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized(pt, gt, wd, H, up(dYh, dev), dX, op=reduce)
+    refb, sabsb = oracle.spmm(down(gt.rowptr), down(gt.col), dYh, w=w, H=H, reduce=reduce, eid=down(gt.eid), want_sabs=True)
+    compare("blocked bwd", down(dX), refb, sabsb)
+    if reduce == 0:
+        np.testing.assert_allclose(refb, oracle.spmm_T_scatter(rowptr, col, dYh, ncols, w=w, H=H), rtol=1e-9, atol=1e-9)
