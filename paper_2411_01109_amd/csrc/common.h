@@ -144,6 +144,7 @@ struct hgnn_plan {
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs
+  float* bsum = nullptr;            // [nb][nrows][max_H] per-block partial row sums of edge tensors
 };
 
 namespace hgnn {

@@ -18,6 +18,7 @@ struct SddmmArgs {
   const int* erow;  // COO row ids from the caller, or nullptr (then the row is searched in rowptr)
   const int* seg_lo;
   const int* seg_hi;
+  const int* eid;  // result slot of every non-zero (column-blocked plans), or nullptr: slot = position
   const half_t* U;
   const half_t* Vt;
   const half_t* a_l;
@@ -146,7 +147,12 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   // coalesced write-back, 16 bytes per lane where the destination allows it
   const int tot = n * a.H;
   half_t* dst = a.out + e0 * a.H;
-  if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+  if (a.eid) {  // a column block: the non-zeros of a row piece are consecutive in the result, pieces are not
+    for (int j = lane; j < tot; j += kWave) {
+      const int k = j / a.H;
+      a.out[int64_t(a.eid[e0 + k]) * a.H + (j - k * a.H)] = s_out[j];
+    }
+  } else if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
     const int nv = tot / 8;
     for (int j = lane; j < nv; j += kWave)
       reinterpret_cast<half8_t*>(dst)[j] = reinterpret_cast<const half8_t*>(s_out)[j];
@@ -419,6 +425,24 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
   }
   if (vec && !score && p) {
     const size_t lds = size_t(sddmm_lds_layout(a.S, H).total) * kWavesPerBlock;
+    if (lds <= 65536 && p->nb > 1) {
+      // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
+      for (int b = 0; b < p->nb; ++b) {
+        const hgnn_plan* q = p->sub[size_t(b)];
+        if (q->nnz == 0) continue;
+        SddmmArgs ab = a;
+        ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
+        ab.col = p->bcol + p->boff[size_t(b)];
+        ab.eid = p->beid + p->boff[size_t(b)];
+        ab.seg_lo = q->seg_row_lo;
+        ab.seg_hi = q->seg_row_hi;
+        ab.nseg = q->nseg;
+        ab.nnz = q->nnz;
+        launch_seg(L, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
+        HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
+      }
+      return HGNN_OK;
+    }
     if (lds <= 65536) {
       launch_seg(L, dim3(unsigned(seg_blocks)), lds, s, a);
       HGNN_LAUNCH_CHECK("sddmm_seg_kernel");

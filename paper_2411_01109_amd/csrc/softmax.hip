@@ -24,6 +24,7 @@ struct EdgeRowArgs {
   const half_t* x1;  //                      backward: dalpha
   const half_t* x2;  //                      backward: e (LeakyReLU mask) or nullptr
   half_t* out;       // forward: alpha.      backward: de.      rowsum: [nrows][H]
+  float* out_f32;    // rowsum only: when set, the sums are written here in fp32 instead of out
   int64_t total;     // nnz * H
   int nrows, H;
   int skip_above;    // rows longer than this are left to a later tier (0 = none)
@@ -237,9 +238,13 @@ __device__ __forceinline__ void rowsum_row(const EdgeRowArgs& a, const Team& tea
     }
   }
   team.template reduce<H, false>(s);
-  if (team.rank == 0)
+  if (team.rank == 0) {
 #pragma unroll
-    for (int h = 0; h < H; ++h) a.out[int64_t(row) * H + h] = half_t(s[h]);
+    for (int h = 0; h < H; ++h) {
+      if (a.out_f32) a.out_f32[int64_t(row) * H + h] = s[h];
+      else a.out[int64_t(row) * H + h] = half_t(s[h]);
+    }
+  }
 }
 
 enum { kFwd = 0, kBwd = 1, kSum = 2 };
@@ -282,7 +287,8 @@ __global__ __launch_bounds__(kBlock) void edge_row_scalar_kernel(EdgeRowArgs a) 
   if (OP == kSum) {
     float s = 0.f;
     for (int k = beg; k < end; ++k) s += float(a.x0[(a.eid ? int64_t(a.eid[k]) : int64_t(k)) * a.H + h]);
-    a.out[idx] = half_t(s);
+    if (a.out_f32) a.out_f32[idx] = s;
+    else a.out[idx] = half_t(s);
     return;
   }
   if (beg == end) return;
@@ -363,6 +369,16 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   return HGNN_OK;
 }
 
+// column-blocked row sums: out[i] = sum over the blocks of their fp32 partial sums
+__global__ __launch_bounds__(kBlock) void rowsum_block_sum_kernel(const float* __restrict__ part, int nb, int64_t n,
+                                                                   half_t* __restrict__ out) {
+  const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int b = 0; b < nb; ++b) s += part[int64_t(b) * n + i];
+  out[i] = half_t(s);
+}
+
 static hgnn_status edge_rows_common(const char* who, const hgnn_csr* g, const hgnn_plan* p, int H, bool allow_eid) {
   hgnn_status st = check_csr_args(g, who);
   if (st != HGNN_OK) return st;
@@ -433,7 +449,26 @@ hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, c
   a.total = g->nnz * H;
   a.nrows = g->nrows;
   a.H = H;
-  return launch_edge_rows<kSum>(g, p, a, static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!(p && p->nb > 1 && g->eid && H <= p->max_H && g->nnz > 0)) return launch_edge_rows<kSum>(g, p, a, s);
+  // column-blocked plan of a graph with an edge-id map (the transposed view): the slots a block reads
+  // lie in one contiguous part of the edge tensor, so block after block the random reads stay cache
+  // resident; fp32 partial sums per block, then one pass adds them
+  const int64_t nout = int64_t(g->nrows) * H;
+  for (int b = 0; b < p->nb; ++b) {
+    hgnn_csr view{g->nrows, g->ncols, p->boff[size_t(b) + 1] - p->boff[size_t(b)],
+                  p->brp + size_t(b) * (size_t(g->nrows) + 1), p->bcol + p->boff[size_t(b)], nullptr,
+                  p->beid + p->boff[size_t(b)]};
+    EdgeRowArgs ab = a;
+    ab.rowptr = view.rowptr;
+    ab.eid = view.eid;
+    ab.out_f32 = p->bsum + size_t(b) * size_t(nout);
+    st = launch_edge_rows<kSum>(&view, nullptr, ab, s);
+    if (st != HGNN_OK) return st;
+  }
+  rowsum_block_sum_kernel<<<dim3(unsigned(ceil_div(nout, kBlock))), kBlock, 0, s>>>(p->bsum, p->nb, nout, a.out);
+  HGNN_LAUNCH_CHECK("rowsum_block_sum_kernel");
+  return HGNN_OK;
 }
 
 }  // extern "C"

@@ -88,3 +88,5 @@ def test_config5_dense_degree_gin_and_gat(hgnn, dev):
     del Y, p, pt, gt, g
     torch.cuda.empty_cache()
     gat_layer_check(hgnn, dev, w, 1, 64, rows_fwd=sample_rows(w.rowptr, 1200, 53), tag="c5 gat")
+    # the same layer with column-blocked plans (what the benchmark times on this configuration)
+    gat_layer_check(hgnn, dev, w, 1, 64, rows_fwd=sample_rows(w.rowptr, 1200, 54), tag="c5 gat blocked", col_blocks=0)

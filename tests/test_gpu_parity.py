@@ -339,7 +339,7 @@ def test_edge_rowsum_rows_and_columns(hgnn, dev, H):
                 oracle.edge_colsum(rowptr, col, np.abs(t64), ncols))
 
 
-def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat"):
+def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat", col_blocks=1):
     """GAT forward (score, softmax, weighted SpMM) and backward (transposed SpMM, SDDMM dot, softmax and
     score backward, row / column sums) against the oracle, each stage fed with the GPU's own fp16
     output of the stage before (the state tensors a layer keeps)."""
@@ -348,9 +348,9 @@ def gat_layer_check(hgnn, dev, w, H, D, rows_fwd=None, tag="gat"):
     dOut = w.tensors["dOut"] if "dOut" in w.tensors else w.tensors["dY"]
     al, ar = w.tensors["a_l"], w.tensors["a_r"]
     g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
-    p = hgnn.hgnn_plan_create(g, 256, F, H)
+    p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=col_blocks)
     gt = hgnn.hgnn_transpose(g)
-    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=col_blocks)
     E = w.E
     hd, dOd = up(feat, dev), up(dOut, dev)
     e = torch.empty((E, H), dtype=torch.float16, device=dev)
@@ -502,3 +502,28 @@ def test_spmm_blocked_matches_oracle(hgnn, dev, F, H, has_w, reduce, S, nb):
     compare("blocked bwd", down(dX), refb, sabsb)
     if reduce == 0:
         np.testing.assert_allclose(refb, oracle.spmm_T_scatter(rowptr, col, dYh, ncols, w=w, H=H), rtol=1e-9, atol=1e-9)
+
+
+@pytest.mark.parametrize("H,D,nb", [(1, 64, 4), (4, 16, 3), (2, 32, 8)])
+def test_blocked_sddmm_and_column_sums(hgnn, dev, H, D, nb):
+    """With a column-blocked plan the SDDMM dot and the row sums over an edge-id map run block after block."""
+    V, F = 900, H * D
+    rowptr, col = rand_graph(V, V, 30, 90 + nb, hubs=((9, 4000),), empties=(0, 899))
+    E = col.size
+    r = np.random.default_rng(nb)
+    U, Vt, t16 = f16(r.standard_normal((V, F))), f16(r.standard_normal((V, F))), f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 128, F, H, col_blocks=nb)
+    out = torch.full((E, H), 5.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, up(U, dev), up(Vt, dev), out)
+    ref = oracle.sddmm_dot(rowptr, col, U, Vt, H=H)
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    mag = np.einsum("ehd,ehd->eh", np.abs(U.astype(np.float64)).reshape(V, H, D)[row],
+                    np.abs(Vt.astype(np.float64)).reshape(V, H, D)[col])
+    compare("blocked dot", down(out), ref, mag)
+    gt = hgnn.hgnn_transpose(g)
+    pt = hgnn.hgnn_plan_create(gt, 128, F, H, col_blocks=nb)
+    cs = torch.full((V, H), 5.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_edge_rowsum(gt, pt, H, up(t16, dev), cs)
+    t64 = t16.astype(np.float64)
+    compare("blocked colsum", down(cs), oracle.edge_colsum(rowptr, col, t64, V), oracle.edge_colsum(rowptr, col, np.abs(t64), V))
