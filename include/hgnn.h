@@ -156,6 +156,28 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
                                   const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
                                   hgnn_reduce op, const float* row_scale, void* stream);
 
+/* Degree norms and the GIN epilogue fused into the discretized SpMM (sections 3.1.3,
+ * 5.2.2; Eq. 2, Eq. 3 and its half-precision form):
+ *   Y[i,f] = self_coef * self[i,f] + sum over the partials P of row i of fp16(P),
+ *   P = agg_coef * s_i * sum_{k in batch} w[slot(k), f/D] * col_scale[col[k]] * X[col[k], f]
+ * with s_i as in hgnn_spmm (reduce op and row_scale).  GCN "both" norm: row_scale =
+ * deg^-1/2 of the rows, col_scale = deg^-1/2 of the columns, no edge values.  GIN:
+ * self = X, self_coef = 1 + eps, agg_coef = 1 (Eq. 3) or lambda with reduce = MEAN
+ * (the overflow-safe form, lambda = 0.1 in the paper).  Empty rows get the self term
+ * alone.  A NULL pointer or fz == NULL drops that part (agg_coef must then be 1). */
+typedef struct {
+  const float* col_scale; /* [ncols] fp32 or NULL */
+  const hgnn_half* self;  /* [nrows][ld_self] fp16 or NULL; ld_self >= F, ld_self % 8 == 0, 16-byte aligned */
+  int64_t ld_self;
+  float self_coef;
+  float agg_coef;
+} hgnn_spmm_fusion;
+
+hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                        const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                        hgnn_reduce op, const float* row_scale, const hgnn_spmm_fusion* fz,
+                                        void* stream);
+
 /* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s

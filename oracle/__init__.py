@@ -44,7 +44,7 @@ def _load():
     lib.orc_decode.restype = None
     lib.orc_decode.argtypes = [vp, vp, i64]
     lib.orc_spmm.restype = None
-    lib.orc_spmm.argtypes = [i32, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, vp, i32, vp, vp]
+    lib.orc_spmm.argtypes = [i32, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, i64, dbl, dbl, vp, i32, vp, vp]
     lib.orc_spmm_T_scatter.restype = None
     lib.orc_spmm_T_scatter.argtypes = [i32, i32, vp, vp, vp, i32, vp, i64, i32, vp]
     lib.orc_transpose.restype = None
@@ -107,16 +107,18 @@ def decode(x: np.ndarray) -> np.ndarray:
 
 
 def spmm(rowptr, col, X, w=None, H: int = 1, reduce: int = SUM, row_scale=None, eid=None, rows=None,
-         want_sabs: bool = False):
-    """Y = s . (A_w X); rows=None gives all rows, else only the listed ones."""
+         want_sabs: bool = False, col_scale=None, self_feat=None, self_coef: float = 0.0, agg_coef: float = 1.0):
+    """Y = self_coef*self + agg_coef * s . (A_w diag(col_scale) X); rows=None gives all rows, else the listed ones."""
     rowptr, col, eid, rows = _i32(rowptr), _i32(col), _i32(eid), _i32(rows)
-    X, w, row_scale = _f16(X), _f16(w), _f64(row_scale)
+    X, w, row_scale, col_scale, self_feat = _f16(X), _f16(w), _f64(row_scale), _f64(col_scale), _f16(self_feat)
     V, F = rowptr.size - 1, X.shape[1]
     n = V if rows is None else rows.size
     out = np.empty((n, F), dtype=np.float64)
     sabs = np.empty((n, F), dtype=np.float64) if want_sabs else None
     _load().orc_spmm(V, _ptr(rowptr), _ptr(col), _ptr(eid), _ptr(w), H, _ptr(X), X.strides[0] // 2, F, reduce,
-                     _ptr(row_scale), _ptr(rows), 0 if rows is None else rows.size, _ptr(out), _ptr(sabs))
+                     _ptr(row_scale), _ptr(col_scale), _ptr(self_feat),
+                     0 if self_feat is None else self_feat.strides[0] // 2, self_coef, agg_coef,
+                     _ptr(rows), 0 if rows is None else rows.size, _ptr(out), _ptr(sabs))
     return (out, sabs) if want_sabs else out
 
 

@@ -62,13 +62,17 @@ void orc_decode(const uint16_t* in, double* out, int64_t n) {
 }
 
 /* ---- SpMM: Y <- A_w X (section 2.1.2; SpMMve, and SpMMv when w == NULL) ----
- * Y[i,f] = s_i * sum_{k in row i} w[idx(k), f/D] * X[col[k], f]
+ * Y[i,f] = self_coef * self[i,f] + agg_coef * s_i * sum_{k in row i} w[idx(k), f/D] * cs[col[k]] * X[col[k], f]
  * s_i = 1 (reduce 0, sum), 1/max(deg_i,1) (reduce 1, mean = SpMM + degree-norm,
- * section 5.2.2), times row_scale[i] when given.
+ * section 5.2.2), times row_scale[i] when given.  cs = col_scale (NULL: 1): with
+ * row_scale = col_scale = D^-1/2 this is Eq. 2's D^-1/2 A D^-1/2 X.  self (NULL: no
+ * self term) with self_coef = 1 + eps, agg_coef = 1 is Eq. 3 (GIN); reduce = mean with
+ * agg_coef = lambda is the half-precision form printed after it.
  * sel == NULL: all V rows, out is [V][F]; otherwise out is [nsel][F] for rows sel[].
- * sabs (may be NULL) receives s_i * sum |w x| (the natural magnitude of the sum). */
+ * sabs (may be NULL) receives |self term| + |agg_coef s_i| * sum |w cs x| (natural magnitude). */
 void orc_spmm(int32_t V, const int32_t* rowptr, const int32_t* col, const int32_t* eid, const uint16_t* w, int32_t H,
               const uint16_t* X, int64_t ldx, int32_t F, int32_t reduce, const double* row_scale,
+              const double* col_scale, const uint16_t* self, int64_t ld_self, double self_coef, double agg_coef,
               const int32_t* sel, int32_t nsel, double* out, double* sabs) {
   int32_t D = F / H;
   int32_t nout = sel ? nsel : V;
@@ -78,17 +82,20 @@ void orc_spmm(int32_t V, const int32_t* rowptr, const int32_t* col, const int32_
     double s = 1.0;
     if (reduce == 1) s = 1.0 / (double)(deg > 1 ? deg : 1);
     if (row_scale) s *= row_scale[i];
+    s *= agg_coef;
     for (int32_t f = 0; f < F; ++f) {
       double acc = 0.0, aabs = 0.0;
       for (int32_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
         int64_t slot = eid ? eid[k] : k;
         double wk = w ? orc_half_to_double(w[slot * H + f / D]) : 1.0;
+        if (col_scale) wk *= col_scale[col[k]];
         double t = wk * orc_half_to_double(X[(int64_t)col[k] * ldx + f]);
         acc += t;
         aabs += fabs(t);
       }
-      out[(int64_t)o * F + f] = s * acc;
-      if (sabs) sabs[(int64_t)o * F + f] = fabs(s) * aabs;
+      double selfterm = self ? self_coef * orc_half_to_double(self[(int64_t)i * ld_self + f]) : 0.0;
+      out[(int64_t)o * F + f] = selfterm + s * acc;
+      if (sabs) sabs[(int64_t)o * F + f] = fabs(selfterm) + fabs(s) * aabs;
     }
   }
 }

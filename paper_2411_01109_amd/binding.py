@@ -22,7 +22,7 @@ EXPORTS = (
     "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_plan_create",
     "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks",
     "hgnn_plan_block_export", "hgnn_plan_export",
-    "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_sddmm", "hgnn_edge_softmax",
+    "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum",
 )
 
@@ -31,6 +31,11 @@ class HgnnError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(message)
         self.status = status
+
+
+class _FusionStruct(ctypes.Structure):
+    _fields_ = [("col_scale", ctypes.c_void_p), ("self", ctypes.c_void_p), ("ld_self", ctypes.c_int64),
+                ("self_coef", ctypes.c_float), ("agg_coef", ctypes.c_float)]
 
 
 class _CsrStruct(ctypes.Structure):
@@ -74,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_destroy.argtypes = [vp]
     lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.hgnn_spmm_discretized.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
+    lib.hgnn_spmm_discretized_fused.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp,
+                                                ctypes.POINTER(_FusionStruct), vp]
     lib.hgnn_sddmm.argtypes = [csr, vp, ctypes.c_int, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp]
     lib.hgnn_edge_softmax.argtypes = [csr, vp, i32, vp, vp, vp]
     lib.hgnn_edge_softmax_bwd.argtypes = [csr, vp, i32, vp, vp, vp, f32, vp, vp]
@@ -230,6 +237,18 @@ def hgnn_spmm_discretized(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: 
     _check(load().hgnn_spmm_discretized(p.handle, g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16),
                                         _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
                                         _ptr(row_scale, torch.float32), _stream(stream)))
+
+
+def hgnn_spmm_discretized_fused(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor,
+                                Y: torch.Tensor, op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None,
+                                col_scale: Optional[torch.Tensor] = None, self_feat: Optional[torch.Tensor] = None,
+                                self_coef: float = 0.0, agg_coef: float = 1.0, F: Optional[int] = None, stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    fz = _FusionStruct(_ptr(col_scale, torch.float32), _ptr(self_feat, torch.float16),
+                       0 if self_feat is None else _ld(self_feat), self_coef, agg_coef)
+    _check(load().hgnn_spmm_discretized_fused(p.handle, g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16),
+                                              _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
+                                              _ptr(row_scale, torch.float32), ctypes.byref(fz), _stream(stream)))
 
 
 def hgnn_sddmm(g: Csr, p: Optional[Plan], op: int, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,

@@ -25,6 +25,12 @@ struct SpmmArgs {
   int F, H, D;
   int reduce;
   float one;  // 1.0f
+  // fused scaling and epilogue (discretized kernels): Y = self_coef*self + sum of partials, every partial
+  // = agg_coef * s_i * sum_batch w * col_scale[j] * x_j
+  const float* col_scale;  // [ncols] or nullptr
+  const half_t* self;      // [nrows][ld_self] or nullptr
+  int64_t ld_self;
+  float self_coef, agg_coef;
   // discretized kernels
   int S;
   int64_t nseg;
@@ -45,7 +51,7 @@ __device__ __forceinline__ float scale_of(const SpmmArgs& a, int r) {
     s = 1.f / float(d > 1 ? d : 1);
   }
   if (a.row_scale) s *= a.row_scale[r];
-  return s;
+  return s * a.agg_coef;
 }
 
 __device__ __forceinline__ void store8(half_t* p, const float (&v)[8], float s) {
@@ -53,6 +59,20 @@ __device__ __forceinline__ void store8(half_t* p, const float (&v)[8], float s) 
 #pragma unroll
   for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
   *reinterpret_cast<half8_t*>(p) = h;
+}
+
+// Y[row, f0..f0+7] = self_coef * self[row] + s * v  (the self term only when the call carries one)
+__device__ __forceinline__ void store_row(const SpmmArgs& a, int64_t row, int f0, const float (&v)[8], float s) {
+  half8_t h;
+  if (a.self) {
+    const half8_t sv = *reinterpret_cast<const half8_t*>(a.self + row * a.ld_self + f0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = half_t(fmaf(a.self_coef, float(sv[i]), v[i] * s));
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
+  }
+  *reinterpret_cast<half8_t*>(a.Y + row * a.ldy + f0) = h;
 }
 
 __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x) {
@@ -205,7 +225,8 @@ struct SegLds {
   int spad;
   int col_off, row_off, blk_off, w_off, vec_off, flag_off, total;
 };
-__host__ __device__ inline SegLds seg_lds_layout(int S, int H, bool has_w, int L) {
+// wm: 0 = no per-edge factor, 1 = fp16 edge values, 2 = fp32 factor (edge value times column scale)
+__host__ __device__ inline SegLds seg_lds_layout(int S, int H, int wm, int L) {
   SegLds o;
   const int G = kWave / L;
   o.per = 4 * ((S + 255) / 256);  // = seg_slots_per_lane(S)
@@ -214,13 +235,13 @@ __host__ __device__ inline SegLds seg_lds_layout(int S, int H, bool has_w, int L
   o.row_off = o.col_off + o.spad * 4;
   o.blk_off = o.row_off + o.spad * 4;
   o.w_off = o.blk_off + align16i(o.spad);  // one int per 4 edges
-  o.vec_off = o.w_off + (has_w ? align16i(o.spad * H * 2) : 0);
+  o.vec_off = o.w_off + (wm == 0 ? 0 : align16i(o.spad * H * (wm == 2 ? 4 : 2)));
   o.flag_off = o.vec_off + 2 * G * 8 * L * 4;
   o.total = o.flag_off + align16i(3 * G * 4);
   return o;
 }
 
-template <int L, bool HAS_W, bool OFF32>
+template <int L, int WM, bool OFF32>
 __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;  // floats per parked vector
@@ -232,12 +253,13 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   const int f0c = active ? f0 : 0;  // idle lanes of a group load a valid address and drop the result
   const int head = f0c / a.D;
   const int S = a.S;
-  const SegLds lay = seg_lds_layout(S, a.H, HAS_W, L);
+  const SegLds lay = seg_lds_layout(S, a.H, WM, L);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);  // row id of every edge of the segment
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);  // per 4 edges: their common row id, or -1
-  half_t* s_w = reinterpret_cast<half_t*>(base + lay.w_off);
+  half_t* s_w = reinterpret_cast<half_t*>(base + lay.w_off);   // WM == 1
+  float* s_wf = reinterpret_cast<float*>(base + lay.w_off);    // WM == 2
   float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
   int* m_hrow = m_flag + G;
@@ -264,9 +286,13 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
     const int64_t k = e0 + i;
     const int c = in ? a.col[k] : 0;
     s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;  // OFF32: byte offset of the neighbour's row
-    if (HAS_W) {
+    if (WM == 1) {
       const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
       for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
+    } else if (WM == 2) {
+      const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
+      const float cs = (in && a.col_scale) ? a.col_scale[c] : (in ? 1.f : 0.f);
+      for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
     }
   }
   if (lane < G) m_flag[lane] = 0;
@@ -283,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   auto flush = [&](bool ro) {
     const float sc = scale_of(a, cur);
     if (!lo && !ro) {
-      if (active) store8(a.Y + int64_t(cur) * a.ldy + f0, acc, sc);
+      if (active) store_row(a, cur, f0, acc, sc);
     } else {
       const int slot = lo ? 2 * g : 2 * g + 1;
       if (active) {
@@ -317,7 +343,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
     float wv[4] = {a.one, a.one, a.one, a.one};  // 1.0 the compiler cannot fold: keeps convert+add in one v_fma_mix
-    if (HAS_W) {
+    if (WM == 1) {
       if (a.H == 1) {
         const half4_t w4 = *reinterpret_cast<const half4_t*>(s_w + i);
 #pragma unroll
@@ -325,6 +351,17 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
       } else {
 #pragma unroll
         for (int u = 0; u < 4; ++u) wv[u] = float(s_w[(i + u) * a.H + head]);
+      }
+    } else if (WM == 2) {
+      if (a.H == 1) {
+        const float4 w4 = *reinterpret_cast<const float4*>(s_wf + i);
+        wv[0] = w4.x;
+        wv[1] = w4.y;
+        wv[2] = w4.z;
+        wv[3] = w4.w;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = s_wf[(i + u) * a.H + head];
       }
     }
     if (blk == cur) {  // the four edges continue the current row: no bookkeeping at all
@@ -371,7 +408,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
         if (!(fl & 2)) {  // the row ends inside chunk gg
           if (active) {
             if (from_before) store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
-            else store8(a.Y + int64_t(run_row) * a.ldy + f0, run, 1.f);
+            else store_row(a, run_row, f0, run, 1.f);
           }
 #pragma unroll
           for (int i = 0; i < 8; ++i) run[i] = 0.f;
@@ -400,8 +437,9 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
   if (active) {
+    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int64_t r = r0 + g; r < r1; r += G)
-      if (a.rowptr[r] == a.rowptr[r + 1]) *reinterpret_cast<half8_t*>(a.Y + r * a.ldy + f0) = half8_t(0);
+      if (a.rowptr[r] == a.rowptr[r + 1]) store_row(a, r, f0, zero, 0.f);
   }
 }
 
@@ -428,7 +466,7 @@ __global__ __launch_bounds__(kBlock) void spmm_finish_kernel(SpmmArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] += float(t[i]);
   }
-  store8(a.Y + int64_t(r) * a.ldy + f0, acc, 1.f);
+  store_row(a, r, f0, acc, 1.f);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -476,6 +514,8 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
   a.D = F / a.H;
   a.reduce = int(op);
   a.one = 1.0f;
+  a.agg_coef = 1.0f;
+  a.self_coef = 0.0f;
   return a;
 }
 
@@ -498,16 +538,16 @@ static void launch_row(int L, dim3 grid, dim3 grid_long, hipStream_t s, const Sp
   }
 }
 
-template <bool HAS_W, bool OFF32>
+template <int WM, bool OFF32>
 static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a) {
   switch (L) {
-    case 1: spmm_seg_kernel<1, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: spmm_seg_kernel<2, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: spmm_seg_kernel<4, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: spmm_seg_kernel<8, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: spmm_seg_kernel<16, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: spmm_seg_kernel<32, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    default: spmm_seg_kernel<64, HAS_W, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: spmm_seg_kernel<1, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: spmm_seg_kernel<2, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: spmm_seg_kernel<4, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: spmm_seg_kernel<8, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: spmm_seg_kernel<16, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: spmm_seg_kernel<32, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    default: spmm_seg_kernel<64, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
   }
 }
 
@@ -524,7 +564,8 @@ static void launch_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
 }
 
 // Pass 1 and pass 2 of the discretized SpMM for the graph in `a` with the segment arrays of plan q.
-static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, bool has_w, int ncols, hipStream_t s) {
+static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipStream_t s) {
+  const int wm = a.col_scale ? 2 : (a.w ? 1 : 0);
   a.seg_lo = q->seg_row_lo;
   a.seg_hi = q->seg_row_hi;
   a.S = q->S;
@@ -536,7 +577,7 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, bool has_w, int 
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const SegLds lay = seg_lds_layout(a.S, a.H, has_w, L);
+  const SegLds lay = seg_lds_layout(a.S, a.H, wm, L);
   const size_t lds = size_t(lay.total) * kWavesPerBlock;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
@@ -545,12 +586,15 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, bool has_w, int 
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
   // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
-  if (has_w) {
-    if (off32) launch_seg<true, true>(L, grid, lds, s, a);
-    else launch_seg<true, false>(L, grid, lds, s, a);
+  if (wm == 2) {
+    if (off32) launch_seg<2, true>(L, grid, lds, s, a);
+    else launch_seg<2, false>(L, grid, lds, s, a);
+  } else if (wm == 1) {
+    if (off32) launch_seg<1, true>(L, grid, lds, s, a);
+    else launch_seg<1, false>(L, grid, lds, s, a);
   } else {
-    if (off32) launch_seg<false, true>(L, grid, lds, s, a);
-    else launch_seg<false, false>(L, grid, lds, s, a);
+    if (off32) launch_seg<0, true>(L, grid, lds, s, a);
+    else launch_seg<0, false>(L, grid, lds, s, a);
   }
   HGNN_LAUNCH_CHECK("spmm_seg_kernel");
   if (a.n_split > 0) {
@@ -579,7 +623,7 @@ __global__ __launch_bounds__(kBlock) void spmm_block_sum_kernel(SpmmArgs a, cons
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] += float(t[i]);
   }
-  store8(a.Y + r * a.ldy + f0, acc, 1.f);
+  store_row(a, r, f0, acc, 1.f);
 }
 
 static void launch_block_sum(int L, dim3 grid, hipStream_t s, const SpmmArgs& a, const half_t* part, int nb, int part_ld) {
@@ -623,25 +667,41 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
   return HGNN_OK;
 }
 
-hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
-                                  const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
-                                  hgnn_reduce op, const float* row_scale, void* stream) {
+hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                        const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                        hgnn_reduce op, const float* row_scale, const hgnn_spmm_fusion* fz,
+                                        void* stream) {
   clear_error();
-  hgnn_status st = check_spmm_args("hgnn_spmm_discretized", g, edge_val, H, X, ldx, Y, ldy, F, op);
+  const char* who = "hgnn_spmm_discretized";
+  hgnn_status st = check_spmm_args(who, g, edge_val, H, X, ldx, Y, ldy, F, op);
   if (st != HGNN_OK) return st;
-  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_spmm_discretized: plan is NULL");
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
   HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
-               "hgnn_spmm_discretized: the plan was built for another graph");
-  HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "hgnn_spmm_discretized: F = %d exceeds the plan's max_F = %d", F, p->max_F);
+               "%s: the plan was built for another graph", who);
+  HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "%s: F = %d exceeds the plan's max_F = %d", who, F, p->max_F);
   HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
-               "hgnn_spmm_discretized: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y");
+               "%s: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y", who);
+  if (fz && fz->self)
+    HGNN_REQUIRE(fz->ld_self >= F && fz->ld_self % 8 == 0 && aligned16(fz->self), HGNN_EINVAL,
+                 "%s: self features need ld_self >= F, ld_self %% 8 == 0 and a 16-byte aligned base", who);
   if (g->nrows == 0) return HGNN_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
-  if (p->nb <= 1) return run_segments(p, a, edge_val != nullptr, g->ncols, s);
+  if (fz) {
+    a.col_scale = fz->col_scale;
+    a.self = reinterpret_cast<const half_t*>(fz->self);
+    a.ld_self = fz->ld_self;
+    a.self_coef = fz->self_coef;
+    a.agg_coef = fz->agg_coef;
+    if (a.col_scale && !edge_val) {  // the per-edge factor is the column scale alone; heads are irrelevant
+      a.H = 1;
+      a.D = F;
+    }
+  }
+  if (p->nb <= 1) return run_segments(p, a, g->ncols, s);
   // column-blocked plan: one discretized SpMM per block into that block's partial output, blocks one
   // after the other so that all compute units gather from the same slice of X, then one pass adds
-  // the partials of every row.  Scales are applied per partial (section 5.2.2); the sum only adds.
+  // the partials of every row (and the self term, once).  Scales are applied per partial (section 5.2.2).
   for (int b = 0; b < p->nb; ++b) {
     const hgnn_plan* q = p->sub[size_t(b)];
     SpmmArgs ab = a;
@@ -651,7 +711,8 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
     ab.nnz = q->nnz;
     ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * size_t(p->nrows) * size_t(p->max_F);
     ab.ldy = p->max_F;
-    st = run_segments(q, ab, edge_val != nullptr, g->ncols, s);
+    ab.self = nullptr;
+    st = run_segments(q, ab, g->ncols, s);
     if (st != HGNN_OK) return st;
   }
   const int L = pow2_at_least(F / 8);
@@ -660,6 +721,12 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
                    reinterpret_cast<const half_t*>(p->bstage), p->nb, p->max_F);
   HGNN_LAUNCH_CHECK("spmm_block_sum_kernel");
   return HGNN_OK;
+}
+
+hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                  const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                  hgnn_reduce op, const float* row_scale, void* stream) {
+  return hgnn_spmm_discretized_fused(p, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, nullptr, stream);
 }
 
 }  // extern "C"

@@ -527,3 +527,47 @@ def test_blocked_sddmm_and_column_sums(hgnn, dev, H, D, nb):
     hgnn.hgnn_edge_rowsum(gt, pt, H, up(t16, dev), cs)
     t64 = t16.astype(np.float64)
     compare("blocked colsum", down(cs), oracle.edge_colsum(rowptr, col, t64, V), oracle.edge_colsum(rowptr, col, np.abs(t64), V))
+
+
+# ------------------------------------------------------------------ fused norms and GIN epilogue
+@pytest.mark.parametrize("F,nb,S", [(64, 1, 256), (128, 1, 100), (64, 4, 128), (32, 3, 64)])
+def test_spmm_fused_gcn_norm_and_gin_epilogue(hgnn, dev, F, nb, S):
+    print(f"fused F={F} nb={nb} S={S}", flush=True)
+    V = 1100
+    rowptr, col = rand_graph(V, V, 30, 300 + F + nb, hubs=((5, 5000), (600, 700)), empties=(0, 9, 1099))
+    E = col.size
+    r = np.random.default_rng(F + 7 * nb)
+    Xh = f16(r.standard_normal((V, F)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, S, F, 4, col_blocks=nb)
+    Xd = up(Xh, dev)
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    # GCN "both" norm (Eq. 2) from degree vectors, no edge values
+    dr = np.maximum(np.diff(rowptr), 1).astype(np.float64) ** -0.5
+    dc = np.maximum(np.bincount(col, minlength=V), 1).astype(np.float64) ** -0.5
+    hgnn.hgnn_spmm_discretized_fused(p, g, None, 1, Xd, Y, row_scale=up(dr.astype(np.float32), dev),
+                                     col_scale=up(dc.astype(np.float32), dev))
+    ref, sabs = oracle.spmm(rowptr, col, Xh, row_scale=dr.astype(np.float32).astype(np.float64),
+                            col_scale=dc.astype(np.float32).astype(np.float64), want_sabs=True)
+    compare("gcn both norm", down(Y), ref, sabs)
+    # GIN, Eq. 3 and its half-precision form
+    for reduce, lam in ((0, 1.0), (1, 0.1)):
+        Y.fill_(3.0)
+        hgnn.hgnn_spmm_discretized_fused(p, g, None, 1, Xd, Y, op=reduce, self_feat=Xd, self_coef=1.25, agg_coef=lam)
+        ref, sabs = oracle.spmm(rowptr, col, Xh, reduce=reduce, self_feat=Xh, self_coef=1.25, agg_coef=np.float32(lam).item(),
+                                want_sabs=True)
+        compare(f"gin reduce={reduce}", down(Y), ref, sabs)
+    # everything at once: edge values with heads, column scale, row scale, mean, self term
+    H = 4
+    w = f16(r.standard_normal((E, H)))
+    rs, cs = r.uniform(0.5, 2.0, V).astype(np.float32), r.uniform(0.5, 2.0, V).astype(np.float32)
+    hgnn.hgnn_spmm_discretized_fused(p, g, up(w, dev), H, Xd, Y, op=1, row_scale=up(rs, dev), col_scale=up(cs, dev),
+                                     self_feat=Xd, self_coef=-0.5, agg_coef=2.0)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, reduce=1, row_scale=rs.astype(np.float64), col_scale=cs.astype(np.float64),
+                            self_feat=Xh, self_coef=-0.5, agg_coef=2.0, want_sabs=True)
+    compare("all fused", down(Y), ref, sabs)
+    # the plain entry point is the fused one without fusion
+    Y2 = torch.empty_like(Y)
+    hgnn.hgnn_spmm_discretized(p, g, up(w, dev), H, Xd, Y)
+    hgnn.hgnn_spmm_discretized_fused(p, g, up(w, dev), H, Xd, Y2)
+    assert np.array_equal(down(Y).view(np.uint16), down(Y2).view(np.uint16))

@@ -440,3 +440,51 @@ def test_discretized_bounds_partials_where_naive_fp16_overflows():
     # naive fp16 on small-integer data is exact (pins the emulation itself)
     Xi = rng.integers(0, 3, size=(64, 2)).astype(np.float16)
     assert np.array_equal(oracle.spmm_naive_fp16(rowptr[:2], col, Xi).astype(np.float64), oracle.spmm(rowptr[:2], col, Xi))
+
+
+# ------------------------------------------------------------------ fused norms and the GIN epilogue
+def test_gcn_both_norm_dense_bruteforce():
+    """Eq. 2: D^-1/2 A D^-1/2 X with row degrees on the left and column degrees on the right."""
+    V, F = 31, 4
+    rowptr, col, row = small_graph(V, V, 0.3, 17, empty_rows=(4,))
+    A = dense_from(rowptr, col, row, V)
+    dr = np.maximum(A.sum(1), 1.0)
+    dc = np.maximum(A.sum(0), 1.0)
+    X = rng.standard_normal((V, F)).astype(np.float16)
+    ref = np.diag(dr ** -0.5) @ A @ np.diag(dc ** -0.5) @ X.astype(np.float64)
+    got = oracle.spmm(rowptr, col, X, row_scale=dr ** -0.5, col_scale=dc ** -0.5)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-13)
+    # the same through per-edge values 1/sqrt(deg_i deg_j), up to their fp16 rounding
+    wsym = (1.0 / np.sqrt(dr[row] * dc[col])).astype(np.float16).reshape(-1, 1)
+    np.testing.assert_allclose(oracle.spmm(rowptr, col, X, w=wsym), ref, rtol=2e-3, atol=1e-3)
+    # left norm only = column scale only
+    np.testing.assert_allclose(oracle.spmm(rowptr, col, X, col_scale=1.0 / dc), A @ np.diag(1.0 / dc) @ X.astype(np.float64),
+                               rtol=1e-12, atol=1e-13)
+
+
+def test_gin_aggregation_dense_bruteforce():
+    """Eq. 3: (1+eps) x_u + sum x_v, and the half-precision form (1+eps) x_u + lambda * mean x_v."""
+    V, F, eps, lam = 29, 6, 0.25, 0.1
+    rowptr, col, row = small_graph(V, V, 0.4, 23, empty_rows=(0, 11))
+    A = dense_from(rowptr, col, row, V)
+    X = rng.standard_normal((V, F)).astype(np.float16)
+    X64 = X.astype(np.float64)
+    got = oracle.spmm(rowptr, col, X, self_feat=X, self_coef=1 + eps, agg_coef=1.0)
+    np.testing.assert_allclose(got, (1 + eps) * X64 + A @ X64, rtol=1e-12, atol=1e-13)
+    deg = np.maximum(A.sum(1), 1.0)
+    got2, sabs = oracle.spmm(rowptr, col, X, reduce=oracle.MEAN, self_feat=X, self_coef=1 + eps, agg_coef=lam, want_sabs=True)
+    np.testing.assert_allclose(got2, (1 + eps) * X64 + lam * (A @ X64) / deg[:, None], rtol=1e-12, atol=1e-13)
+    assert np.array_equal(got2[[0, 11]], (1 + eps) * X64[[0, 11]])  # empty rows keep the self term alone
+    assert np.all(sabs + 1e-12 >= np.abs(got2))
+    # weighted, multi-head, row subset, all options at once against a dense evaluation per head
+    H = 2
+    w = rng.standard_normal((col.size, H)).astype(np.float16)
+    cs, rs = rng.uniform(0.5, 1.5, V), rng.uniform(0.5, 1.5, V)
+    ref = np.zeros((V, F))
+    for h in range(H):
+        Ah = dense_from(rowptr, col, row, V, w[:, h].astype(np.float64))
+        ref[:, h * 3:(h + 1) * 3] = Ah @ (cs[:, None] * X64[:, h * 3:(h + 1) * 3])
+    ref = 0.5 * X64 + 2.0 * rs[:, None] * ref
+    rows = np.array([5, 0, 28], dtype=np.int32)
+    got3 = oracle.spmm(rowptr, col, X, w=w, H=H, row_scale=rs, col_scale=cs, self_feat=X, self_coef=0.5, agg_coef=2.0, rows=rows)
+    np.testing.assert_allclose(got3, ref[rows], rtol=1e-12, atol=1e-12)
