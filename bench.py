@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # L2-miss bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated
 # against a 1 GiB copy; see profiles/hgnn_kernels_*.md.  Keyed by (workload, kernel instantiation).
 MEASURED_TRAFFIC = {
-    ("c5_dense_degree", "hgnn::spmm_seg_kernel<8, false, true>"): 12.06e9,
-    ("c4_gcn_large", "hgnn::spmm_seg_kernel<16, true, true>"): 15.80e9,
+    ("c5_dense_degree", "hgnn::spmm_seg_kernel<8, 0, true>"): 12.06e9,
+    ("c4_gcn_large", "hgnn::spmm_seg_kernel<16, 1, true>"): 15.80e9,
 }
 
 
@@ -110,7 +110,7 @@ def main():
     while Lg < F // 8:
         Lg *= 2
     off32 = "true" if V * X.stride(0) * 2 < (1 << 32) else "false"
-    seg_name = lambda hw: f"hgnn::spmm_seg_kernel<{Lg}, {'true' if hw else 'false'}, {off32}>"
+    seg_name = lambda hw: f"hgnn::spmm_seg_kernel<{Lg}, {1 if hw else 0}, {off32}>"
     row_name = lambda hw: f"hgnn::spmm_row_kernel<{Lg}, {'true' if hw else 'false'}> (+ spmm_longrow_kernel)"
     ops = []  # (name, kernel, min bytes, fn, requested bytes)
     wH = 1 if ew is not None else 0
@@ -125,6 +125,28 @@ def main():
                     lambda: hgnn.hgnn_spmm_discretized(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN), spmm_req(0, False)))
         ops.append(("spmm_bwd_disc_mean", seg_name(0), spmm_min(0, True),
                     lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, None, 1, dY, Y, op=hgnn.HGNN_MEAN), spmm_req(0, True)))
+    # the next-step fusions, measured beside the path: degree norms / GIN epilogue inside the discretized SpMM
+    deg_r = torch.clamp(g.rowptr[1:] - g.rowptr[:-1], min=1).to(torch.float32)
+    deg_c = torch.clamp(gt.rowptr[1:] - gt.rowptr[:-1], min=1).to(torch.float32)
+    fused_name = f"hgnn::spmm_seg_kernel<{Lg}, 2, {off32}>"
+    if args.workload in ("c2", "c5"):  # GIN, half-precision form: (1+eps) x + lambda * mean, forward and backward
+        lam_over_deg = (0.1 / deg_r).contiguous()
+        b = spmm_min(0, False) + 2 * V * F
+        ops.append(("gin_fused_fwd", seg_name(0), b,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN, self_feat=X,
+                                                             self_coef=1.0, agg_coef=0.1), spmm_req(0, False) + 2 * V * F))
+        ops.append(("gin_fused_bwd", fused_name, b + 4 * V + 4 * E,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, col_scale=lam_over_deg,
+                                                             self_feat=dY, self_coef=1.0), spmm_req(0, True) + 2 * V * F + 4 * E))
+    else:  # GCN "both" norm from degree vectors instead of per-edge values
+        rs_f, cs_f = deg_r.rsqrt().contiguous(), deg_c.rsqrt().contiguous()
+        b = spmm_min(0, False) + 8 * V
+        ops.append(("gcn_norm_fused_fwd", fused_name, b + 4 * E,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, row_scale=rs_f, col_scale=cs_f),
+                    spmm_req(0, False) + 8 * V + 4 * E))
+        ops.append(("gcn_norm_fused_bwd", fused_name, b + 4 * E,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, row_scale=cs_f, col_scale=rs_f),
+                    spmm_req(0, True) + 8 * V + 4 * E))
     if has_gat:
         EH = E * H
         b = E * 4 + 4 * (V + 1) + 2 * V * F + 2 * EH
