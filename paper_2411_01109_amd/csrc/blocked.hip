@@ -55,6 +55,16 @@ __global__ void block_rowptr_kernel(const int* __restrict__ goff, int nrows, int
   brp[idx] = int(here - base);
 }
 
+// delta[b*nrows + r] = (first CSR position of row r's piece in block b) - (its position inside block b), so that
+// the original position of a blocked non-zero is its block position + delta of its row
+__global__ void block_delta_kernel(const int* __restrict__ cut, const int* __restrict__ goff, int nrows, int nb,
+                                   int* __restrict__ delta) {
+  const int64_t idx = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (idx >= int64_t(nrows) * nb) return;
+  const int b = int(idx / nrows), r = int(idx % nrows);
+  delta[idx] = cut[int64_t(r) * (nb + 1) + b] - (goff[idx] - goff[int64_t(b) * nrows]);
+}
+
 // every non-zero k of the graph goes to its block, keeping its place inside the row piece
 __global__ void block_fill_kernel(hgnn_csr g, const int* __restrict__ cut, const int* __restrict__ goff, int nb, int width,
                                   int* __restrict__ bcol, int* __restrict__ beid) {
@@ -87,6 +97,7 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   if (e == hipSuccess) e = hipMalloc(&p->beid, sizeof(int) * size_t(E));
   if (e == hipSuccess) e = hipMalloc(&p->bstage, sizeof(hgnn_half) * n_flat * size_t(p->max_F));
   if (e == hipSuccess) e = hipMalloc(&p->bsum, sizeof(float) * n_flat * size_t(p->max_H));
+  if (e == hipSuccess && !g->eid) e = hipMalloc(&p->bdelta, sizeof(int) * n_flat);
   if (e == hipSuccess) {
     block_cuts_kernel<<<dim3(unsigned(ceil_div(int64_t(V) * (nb + 1), kBlock))), kBlock, 0, s>>>(g->rowptr, g->col, V, nb,
                                                                                                  width, cut);
@@ -98,6 +109,8 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   if (e == hipSuccess) {
     block_rowptr_kernel<<<dim3(unsigned(ceil_div(int64_t(nb) * (V + 1), kBlock))), kBlock, 0, s>>>(goff, V, nb, E, p->brp);
     block_fill_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(*g, cut, goff, nb, width, p->bcol, p->beid);
+    if (p->bdelta)
+      block_delta_kernel<<<dim3(unsigned(ceil_div(int64_t(n_flat), kBlock))), kBlock, 0, s>>>(cut, goff, V, nb, p->bdelta);
     e = hipGetLastError();
   }
   p->boff.assign(size_t(nb) + 1, 0);

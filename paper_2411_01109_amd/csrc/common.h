@@ -141,6 +141,7 @@ struct hgnn_plan {
   int32_t* brp = nullptr;           // [nb][nrows+1] offset arrays of the blocks
   int32_t* bcol = nullptr;          // [nnz] column ids, block-major
   int32_t* beid = nullptr;          // [nnz] slot in the edge tensors of every blocked non-zero
+  int32_t* bdelta = nullptr;        // [nb][nrows] graphs without edge-id map: slot = block position + bdelta[b][row]
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs

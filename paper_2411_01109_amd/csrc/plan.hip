@@ -279,6 +279,7 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->brp);
   (void)hipFree(p->bcol);
   (void)hipFree(p->beid);
+  (void)hipFree(p->bdelta);
   (void)hipFree(p->bstage);
   (void)hipFree(p->bsum);
   (void)hipFree(p->seg_row_lo);

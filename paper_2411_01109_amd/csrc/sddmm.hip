@@ -283,11 +283,30 @@ __global__ __launch_bounds__(kBlock) void edge_score_seg_kernel(SddmmArgs a) {
   const bool vec_ok = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
   for (int kb = lane * EPL; kb < n; kb += kWave * EPL) {
     half8_t o = half8_t(0);
+    int rows[EPL], cols[EPL];
+    if (EPL >= 4 && kb + EPL <= n && (reinterpret_cast<uintptr_t>(a.col + e0 + kb) & 15u) == 0) {  // 16-byte loads of ids
+#pragma unroll
+      for (int v = 0; v < EPL / 4; ++v) {
+        const int4_t c4 = *reinterpret_cast<const int4_t*>(a.col + e0 + kb + 4 * v);
+        const int4_t r4 = *reinterpret_cast<const int4_t*>(s_row + kb + 4 * v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          cols[4 * v + q] = c4[q];
+          rows[4 * v + q] = r4[q];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const int k = kb + e < n ? kb + e : n - 1;
+        cols[e] = a.col[e0 + k];
+        rows[e] = s_row[k];
+      }
+    }
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
-      const int k = kb + e < n ? kb + e : n - 1;
-      const fv_t vl = *reinterpret_cast<const fv_t*>(a.el + int64_t(s_row[k]) * H);
-      const fv_t vr = *reinterpret_cast<const fv_t*>(a.er + int64_t(a.col[e0 + k]) * H);
+      const fv_t vl = *reinterpret_cast<const fv_t*>(a.el + int64_t(rows[e]) * H);
+      const fv_t vr = *reinterpret_cast<const fv_t*>(a.er + int64_t(cols[e]) * H);
 #pragma unroll
       for (int h = 0; h < H; ++h) {
         const float s = vl[h] + vr[h];

@@ -15,6 +15,7 @@ struct SpmmArgs {
   const int* deg_rowptr;  // offset array that defines deg(i) for MEAN (the whole graph's, also when a column block runs)
   const int* col;
   const int* eid;
+  const int* delta;  // column blocks of a graph without edge-id map: slot of non-zero k of row r = k + delta[r]
   const half_t* w;  // [nnz][H] or nullptr
   const half_t* X;
   half_t* Y;
@@ -286,17 +287,34 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
     const int64_t k = e0 + i;
     const int c = in ? a.col[k] : 0;
     s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;  // OFF32: byte offset of the neighbour's row
-    if (WM == 1) {
-      const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
-      for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
-    } else if (WM == 2) {
-      const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
-      const float cs = (in && a.col_scale) ? a.col_scale[c] : (in ? 1.f : 0.f);
-      for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
+    if (!a.delta) {
+      if (WM == 1) {
+        const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
+        for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
+      } else if (WM == 2) {
+        const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
+        const float cs = (in && a.col_scale) ? a.col_scale[c] : (in ? 1.f : 0.f);
+        for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
+      }
     }
   }
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
+  if (WM != 0 && a.delta) {
+    // a row piece of a column block is a run of consecutive slots: slot = position + delta[row], so the
+    // edge values are read coalesced without an edge-id array (the row ids are known only now)
+    for (int i = lane; i < spad; i += kWave) {
+      const bool in = i < n;
+      const int64_t slot = in ? e0 + i + a.delta[s_row[i]] : 0;
+      if (WM == 1) {
+        for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
+      } else {
+        const float cs = in ? (a.col_scale ? a.col_scale[a.col[e0 + i]] : 1.f) : 0.f;
+        for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
+      }
+    }
+    __syncthreads();
+  }
 
   // ---- phase 2: running reduction over this group's chunk
   const int C = 4 * ((S + 4 * G - 1) / (4 * G));  // edges per group, a multiple of 4
@@ -708,6 +726,7 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
     ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
     ab.col = p->bcol + p->boff[size_t(b)];
     ab.eid = p->beid + p->boff[size_t(b)];
+    ab.delta = p->bdelta ? p->bdelta + size_t(b) * size_t(p->nrows) : nullptr;
     ab.nnz = q->nnz;
     ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * size_t(p->nrows) * size_t(p->max_F);
     ab.ldy = p->max_F;
