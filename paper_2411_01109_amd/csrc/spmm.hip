@@ -26,6 +26,7 @@ struct SpmmArgs {
   int F, H, D;
   int reduce;
   float one;  // 1.0f
+  int rows_per_wave;  // spmm_row_kernel: rows a wave owns, 1 or 64/L
   // fused scaling and epilogue (discretized kernels): Y = self_coef*self + sum of partials, every partial
   // = agg_coef * s_i * sum_batch w * col_scale[j] * x_j
   const float* col_scale;  // [ncols] or nullptr
@@ -82,30 +83,36 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Vertex-parallel SpMM: one wave per row; the G groups of the wave stride over the row's
-// non-zeros, then their fp32 partial vectors are added across groups with lane shuffles.
-// Rows longer than kLongRow are left to a second kernel that gives a 1024-thread workgroup
-// to each of them (a single wave cannot keep enough loads in flight for a hub of 10^5 edges).
+// Vertex-parallel SpMM (no plan).  A wave owns G = 64/L consecutive rows.  Rows of at most kShortRow
+// non-zeros are reduced by one lane group each, all G of them at once and with no exchange between
+// lanes; every longer row is reduced by the whole wave, the groups striding over its non-zeros
+// and their fp32 partial vectors added across groups with lane shuffles.  Rows longer than
+// kLongRow are left to a second kernel that gives a 1024-thread workgroup to each of them (a
+// single wave cannot keep enough loads in flight for a hub of 10^5 edges).
 // ---------------------------------------------------------------------------------------------------
+constexpr int kShortRow = 32;
 constexpr int kLongRow = 4096;
 constexpr int kLongBlock = 1024;
 
-// acc += sum over the non-zeros k in [beg, end) visited by group g (stride G) of w_k * X[col_k, f0..f0+7]
-template <int L, bool HAS_W, int U>
-__device__ __forceinline__ void row_accumulate(const SpmmArgs& a, int beg, int end, int g, int f0c, int head,
-                                               float (&acc)[8]) {
-  constexpr int G = kWave / L;
-  for (int k = beg + g; k < end; k += G * U) {
+// acc += sum over the non-zeros k = first, first + STRIDE, ... < end of w_k * X[col_k, f0..f0+7],
+// U of them in flight at a time; the column ids of the next U are fetched while the rows of
+// the current U are on their way, so one trip through the loop costs one memory latency, not two
+template <int STRIDE, bool HAS_W, int U>
+__device__ __forceinline__ void edges_accumulate(const SpmmArgs& a, int first, int end, int f0c, int head,
+                                                 float (&acc)[8]) {
+  int c[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) c[u] = first + u * STRIDE < end ? a.col[first + u * STRIDE] : 0;
+  for (int k = first; k < end; k += STRIDE * U) {
     half8_t x[U];
     float wv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kk = k + u * G;
+      const int kk = k + u * STRIDE;
       x[u] = half8_t(0);
       wv[u] = 0.f;
       if (kk < end) {
-        const int c = a.col[kk];
-        x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+        x[u] = *reinterpret_cast<const half8_t*>(a.X + int64_t(c[u]) * a.ldx + f0c);
         if (HAS_W) {
           const int64_t slot = a.eid ? a.eid[kk] : kk;
           wv[u] = float(a.w[slot * a.H + head]);
@@ -115,8 +122,18 @@ __device__ __forceinline__ void row_accumulate(const SpmmArgs& a, int beg, int e
       }
     }
 #pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kn = k + (U + u) * STRIDE;
+      c[u] = kn < end ? a.col[kn] : 0;
+    }
+#pragma unroll
     for (int u = 0; u < U; ++u) fma8(acc, wv[u], x[u]);
   }
+}
+
+// every lane ends up with the sum of its feature slice over the wave's G groups
+template <int L>
+__device__ __forceinline__ void groups_reduce(float (&acc)[8]) {
 #pragma unroll
   for (int off = L; off < kWave; off <<= 1) {
 #pragma unroll
@@ -126,18 +143,38 @@ __device__ __forceinline__ void row_accumulate(const SpmmArgs& a, int beg, int e
 
 template <int L, bool HAS_W>
 __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
+  constexpr int G = kWave / L;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
-  const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
-  if (row >= a.nrows) return;
+  const int rw = a.rows_per_wave;  // 1 or G
+  const int64_t r0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * rw;
+  if (r0 >= a.nrows) return;
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  if (end - beg > kLongRow) return;  // handled by spmm_longrow_kernel
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  row_accumulate<L, HAS_W, 4>(a, beg, end, g, f0c, f0c / a.D, acc);
-  if (g == 0 && active) store8(a.Y + row * a.ldy + f0, acc, scale_of(a, int(row)));
+  const int head = f0c / a.D;
+  // the group's own row
+  const int64_t rg = r0 + g;
+  const bool has_row = g < rw && rg < a.nrows;
+  int beg_g = 0, end_g = 0;
+  if (has_row) {
+    beg_g = a.rowptr[rg];
+    end_g = a.rowptr[rg + 1];
+  }
+  if (has_row && end_g - beg_g <= kShortRow) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    edges_accumulate<1, HAS_W, 4>(a, beg_g, end_g, f0c, head, acc);
+    if (active) store8(a.Y + rg * a.ldy + f0, acc, scale_of(a, int(rg)));
+  }
+  // the wave's mid-length rows, one after the other
+  for (int j = 0; j < rw; ++j) {
+    const int beg = __shfl(beg_g, j * L), end = __shfl(end_g, j * L);
+    if (end - beg <= kShortRow || end - beg > kLongRow) continue;  // done above / spmm_longrow_kernel
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    edges_accumulate<G, HAS_W, 4>(a, beg + g, end, f0c, head, acc);
+    groups_reduce<L>(acc);
+    if (g == 0 && active) store8(a.Y + (r0 + j) * a.ldy + f0, acc, scale_of(a, int(r0 + j)));
+  }
 }
 
 // Workgroup b looks at rows [b*1024, (b+1)*1024); every row longer than kLongRow is reduced by all
@@ -167,7 +204,8 @@ __global__ __launch_bounds__(kLongBlock) void spmm_longrow_kernel(SpmmArgs a) {
     const int b = beg + wave * chunk < end ? beg + wave * chunk : end;
     const int e = b + chunk < end ? b + chunk : end;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    row_accumulate<L, HAS_W, 8>(a, b, e, g, f0c, f0c / a.D, acc);
+    edges_accumulate<kWave / L, HAS_W, 4>(a, b + g, e, f0c, f0c / a.D, acc);
+    groups_reduce<L>(acc);
     if (g == 0) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) s_part[wave][f0 + i] = acc[i];
@@ -175,6 +213,7 @@ __global__ __launch_bounds__(kLongBlock) void spmm_longrow_kernel(SpmmArgs a) {
     __syncthreads();
     if (wave == 0 && g == 0 && active) {
       float tot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
       for (int w = 0; w < NW; ++w)
 #pragma unroll
         for (int i = 0; i < 8; ++i) tot[i] += s_part[w][f0 + i];
@@ -461,30 +500,70 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   }
 }
 
-// Pass 2, the follow-up kernel (section 5.2.3): one group per split row adds the staged fp16
-// partials of that row in ascending segment order (fp32) and stores the row once.
+// Pass 2, the follow-up kernel (section 5.2.3): adds the staged fp16 partials of every split row
+// (fp32, fixed order) and stores the row once.  A wave owns G split rows: a row of at most
+// kFinishShort pieces is summed by its own lane group, a hub that spans more segments by the
+// whole wave, the groups striding over its pieces.
+constexpr int kFinishShort = 8;
+
+template <int STRIDE>
+__device__ __forceinline__ void pieces_accumulate(const SpmmArgs& a, int64_t first, int64_t last, int f0,
+                                                  float (&acc)[8]) {
+  constexpr int U = 4;
+  for (int64_t k = first; k <= last; k += STRIDE * U) {
+    half8_t t[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t kk = k + u * STRIDE;
+      t[u] = half8_t(0);
+      if (kk <= last) t[u] = *reinterpret_cast<const half8_t*>(a.staging + (2 * kk) * a.stage_ld + f0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += float(t[u][i]);
+  }
+}
+
 template <int L>
 __global__ __launch_bounds__(kBlock) void spmm_finish_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
   const int f0 = 8 * l;
-  const int64_t idx = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
-  if (idx >= a.n_split || f0 >= a.F) return;
-  const int r = a.split_row[idx];
-  const int64_t sa = a.split_lo[idx], sb = a.split_hi[idx];
-  float acc[8];
-  {
-    const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * sa + 1) * a.stage_ld + f0);
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  if (i0 >= a.n_split) return;
+  const int64_t idx = i0 + g;
+  int r = 0, sa = 0, sb = -1;
+  if (idx < a.n_split) {
+    r = a.split_row[idx];
+    sa = a.split_lo[idx];
+    sb = a.split_hi[idx];
+  }
+  // the tail piece of segment sa, then the head pieces of segments sa+1 .. sb
+  if (idx < a.n_split && sb - sa <= kFinishShort) {
+    float acc[8];
+    const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * int64_t(sa) + 1) * a.stage_ld + f0c);
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = float(t[i]);
+    pieces_accumulate<1>(a, int64_t(sa) + 1, sb, f0c, acc);
+    if (active) store_row(a, r, f0, acc, 1.f);
   }
-  for (int64_t k = sa + 1; k <= sb; ++k) {
-    const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * k) * a.stage_ld + f0);
+  for (int j = 0; j < G; ++j) {
+    const int rj = __shfl(r, j * L), sj = __shfl(sa, j * L), ej = __shfl(sb, j * L);
+    if (ej - sj <= kFinishShort) continue;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (g == 0) {
+      const half8_t t = *reinterpret_cast<const half8_t*>(a.staging + (2 * int64_t(sj) + 1) * a.stage_ld + f0c);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] += float(t[i]);
+      for (int i = 0; i < 8; ++i) acc[i] = float(t[i]);
+    }
+    pieces_accumulate<G>(a, int64_t(sj) + 1 + g, ej, f0c, acc);
+    groups_reduce<L>(acc);
+    if (g == 0 && active) store_row(a, rj, f0, acc, 1.f);
   }
-  store_row(a, r, f0, acc, 1.f);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -672,7 +751,9 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
   if (vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
     const int L = pow2_at_least(F / 8);
-    dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock)));
+    // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
+    a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
+    dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock * a.rows_per_wave)));
     dim3 grid_long(unsigned(ceil_div(g->nrows, kLongBlock)));
     if (edge_val) launch_row<true>(L, grid, grid_long, s, a);
     else launch_row<false>(L, grid, grid_long, s, a);
