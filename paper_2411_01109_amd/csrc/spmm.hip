@@ -8,6 +8,8 @@
 // Products are formed and accumulated in fp32 (v_fma_mix), fp16 only when a value is stored.
 #include "common.h"
 
+#include <mutex>
+
 namespace hgnn {
 
 struct SpmmArgs {
@@ -87,12 +89,10 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x)
 // non-zeros are reduced by one lane group each, all G of them at once and with no exchange between
 // lanes; every longer row is reduced by the whole wave, the groups striding over its non-zeros
 // and their fp32 partial vectors added across groups with lane shuffles.  Rows longer than
-// kLongRow are left to a second kernel that gives a 1024-thread workgroup to each of them (a
-// single wave cannot keep enough loads in flight for a hub of 10^5 edges).
+// kLongRow are hubs: they are left to the chunked kernels further down.
 // ---------------------------------------------------------------------------------------------------
 constexpr int kShortRow = 32;
 constexpr int kLongRow = 4096;
-constexpr int kLongBlock = 1024;
 
 // acc += sum over the non-zeros k = first, first + STRIDE, ... < end of w_k * X[col_k, f0..f0+7],
 // U of them in flight at a time; the column ids of the next U are fetched while the rows of
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
   // the wave's mid-length rows, one after the other
   for (int j = 0; j < rw; ++j) {
     const int beg = __shfl(beg_g, j * L), end = __shfl(end_g, j * L);
-    if (end - beg <= kShortRow || end - beg > kLongRow) continue;  // done above / spmm_longrow_kernel
+    if (end - beg <= kShortRow || end - beg > kLongRow) continue;  // done above / a hub
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     edges_accumulate<G, HAS_W, 4>(a, beg + g, end, f0c, head, acc);
     groups_reduce<L>(acc);
@@ -177,50 +177,107 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
   }
 }
 
-// Workgroup b looks at rows [b*1024, (b+1)*1024); every row longer than kLongRow is reduced by all
-// 16 waves together: wave w takes the w-th sixteenth of the row, partial vectors meet in LDS and
-// wave 0 adds them in wave order and stores the row.  No atomics, fixed order.
+// Hubs.  A row longer than kLongRow is cut into chunks of kHubChunk non-zeros, one workgroup per
+// chunk, so that a hub of 10^5 edges keeps dozens of compute units busy instead of one.  Three
+// launches: hub_scan_kernel lists the hubs and hands every one a run of consecutive chunk slots
+// (the slot numbers depend on the order in which the atomic counter is reached, the values
+// computed do not); spmm_hub_kernel reduces one chunk per workgroup into an fp32 partial row in
+// scratch memory; spmm_hub_sum_kernel adds a hub's partial rows in chunk order and stores the row.
+// No atomics touch feature data and the summation order is fixed.
+constexpr int kHubChunk = 2048;
+
+struct HubLists {
+  int* count;      // [0] chunks handed out, [1] hubs listed
+  int* chunk_row;  // [max_chunks] the hub a chunk slot belongs to
+  int* chunk_no;   // [max_chunks] its number within the hub
+  int* hub_row;    // [max_hubs]
+  int* hub_base;   // [max_hubs] first chunk slot of the hub
+  float* part;     // [max_chunks][F]
+  int max_chunks, max_hubs;
+};
+
+__global__ __launch_bounds__(kBlock) void hub_zero_kernel(HubLists h) {
+  if (threadIdx.x < 2) h.count[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(kBlock) void hub_scan_kernel(SpmmArgs a, HubLists h) {
+  const int64_t r = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  if (r >= a.nrows) return;
+  const int deg = a.rowptr[r + 1] - a.rowptr[r];
+  if (deg <= kLongRow) return;
+  const int nch = (deg + kHubChunk - 1) / kHubChunk;
+  const int base = atomicAdd(&h.count[0], nch);
+  const int i = atomicAdd(&h.count[1], 1);
+  if (base + nch > h.max_chunks || i >= h.max_hubs) return;  // cannot happen for a valid rowptr
+  h.hub_row[i] = int(r);
+  h.hub_base[i] = base;
+  for (int c = 0; c < nch; ++c) {
+    h.chunk_row[base + c] = int(r);
+    h.chunk_no[base + c] = c;
+  }
+}
+
 template <int L, bool HAS_W>
-__global__ __launch_bounds__(kLongBlock) void spmm_longrow_kernel(SpmmArgs a) {
-  constexpr int NW = kLongBlock / kWave;
-  __shared__ int s_list[kLongBlock];
-  __shared__ int s_n;
-  __shared__ float s_part[NW][8 * L];
+__global__ __launch_bounds__(kBlock) void spmm_hub_kernel(SpmmArgs a, HubLists h) {
+  constexpr int G = kWave / L;
+  __shared__ float s_part[kWavesPerBlock][8 * L];
+  const int nchunks = h.count[0] < h.max_chunks ? h.count[0] : h.max_chunks;
+  if (int(blockIdx.x) >= nchunks) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  if (threadIdx.x == 0) s_n = 0;
-  __syncthreads();
-  const int64_t r = int64_t(blockIdx.x) * kLongBlock + threadIdx.x;
-  if (r < a.nrows && a.rowptr[r + 1] - a.rowptr[r] > kLongRow) s_list[atomicAdd(&s_n, 1)] = int(r);
-  __syncthreads();
-  const int nlong = s_n;
-  for (int t = 0; t < nlong; ++t) {
-    const int row = s_list[t];
-    const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-    const int chunk = (end - beg + NW - 1) / NW;
-    const int b = beg + wave * chunk < end ? beg + wave * chunk : end;
-    const int e = b + chunk < end ? b + chunk : end;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    edges_accumulate<kWave / L, HAS_W, 4>(a, b + g, e, f0c, f0c / a.D, acc);
-    groups_reduce<L>(acc);
-    if (g == 0) {
+  const int row = h.chunk_row[blockIdx.x];
+  const int row_end = a.rowptr[row + 1];
+  const int cb = a.rowptr[row] + h.chunk_no[blockIdx.x] * kHubChunk;
+  constexpr int per_wave = kHubChunk / kWavesPerBlock;
+  const int b = cb + wave * per_wave < row_end ? cb + wave * per_wave : row_end;
+  const int e = b + per_wave < row_end ? b + per_wave : row_end;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  edges_accumulate<G, HAS_W, 4>(a, b + g, e, f0c, f0c / a.D, acc);
+  groups_reduce<L>(acc);
+  if (g == 0) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) s_part[wave][f0 + i] = acc[i];
-    }
-    __syncthreads();
-    if (wave == 0 && g == 0 && active) {
-      float tot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-      for (int w = 0; w < NW; ++w)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) tot[i] += s_part[w][f0 + i];
-      store8(a.Y + int64_t(row) * a.ldy + f0, tot, scale_of(a, row));
-    }
-    __syncthreads();
+    for (int i = 0; i < 8; ++i) s_part[wave][f0 + i] = acc[i];
   }
+  __syncthreads();
+  if (wave == 0 && g == 0 && active) {
+    float* out = h.part + int64_t(blockIdx.x) * a.F + f0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float t = s_part[0][f0 + i];
+#pragma unroll
+      for (int w = 1; w < kWavesPerBlock; ++w) t += s_part[w][f0 + i];
+      out[i] = t;
+    }
+  }
+}
+
+// one wave per hub; its groups stride over the hub's partial rows
+template <int L>
+__global__ __launch_bounds__(kBlock) void spmm_hub_sum_kernel(SpmmArgs a, HubLists h) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int nhubs = h.count[1] < h.max_hubs ? h.count[1] : h.max_hubs;
+  const int i = int(blockIdx.x) * kWavesPerBlock + wave;
+  if (i >= nhubs) return;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int row = h.hub_row[i];
+  const int nch = (a.rowptr[row + 1] - a.rowptr[row] + kHubChunk - 1) / kHubChunk;
+  const float* part = h.part + int64_t(h.hub_base[i]) * a.F + f0c;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int c = g; c < nch; c += G) {
+    const float4 lo = *reinterpret_cast<const float4*>(part + int64_t(c) * a.F);
+    const float4 hi = *reinterpret_cast<const float4*>(part + int64_t(c) * a.F + 4);
+    acc[0] += lo.x, acc[1] += lo.y, acc[2] += lo.z, acc[3] += lo.w;
+    acc[4] += hi.x, acc[5] += hi.y, acc[6] += hi.z, acc[7] += hi.w;
+  }
+  groups_reduce<L>(acc);
+  if (g == 0 && active) store8(a.Y + int64_t(row) * a.ldy + f0, acc, scale_of(a, row));
 }
 
 // Scalar path for shapes the 16-byte path cannot take: one thread per (row, feature).
@@ -617,22 +674,83 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
 }
 
 template <int L, bool HAS_W>
-static void launch_row_pair(dim3 grid, dim3 grid_long, hipStream_t s, const SpmmArgs& a) {
+static void launch_row_set(dim3 grid, hipStream_t s, const SpmmArgs& a, const HubLists* h) {
   spmm_row_kernel<L, HAS_W><<<grid, kBlock, 0, s>>>(a);
-  spmm_longrow_kernel<L, HAS_W><<<grid_long, kLongBlock, 0, s>>>(a);
+  if (h) {
+    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks)), kBlock, 0, s>>>(a, *h);
+    spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
+  }
 }
 
 template <bool HAS_W>
-static void launch_row(int L, dim3 grid, dim3 grid_long, hipStream_t s, const SpmmArgs& a) {
+static void launch_row(int L, dim3 grid, hipStream_t s, const SpmmArgs& a, const HubLists* h) {
   switch (L) {
-    case 1: launch_row_pair<1, HAS_W>(grid, grid_long, s, a); break;
-    case 2: launch_row_pair<2, HAS_W>(grid, grid_long, s, a); break;
-    case 4: launch_row_pair<4, HAS_W>(grid, grid_long, s, a); break;
-    case 8: launch_row_pair<8, HAS_W>(grid, grid_long, s, a); break;
-    case 16: launch_row_pair<16, HAS_W>(grid, grid_long, s, a); break;
-    case 32: launch_row_pair<32, HAS_W>(grid, grid_long, s, a); break;
-    default: launch_row_pair<64, HAS_W>(grid, grid_long, s, a); break;
+    case 1: launch_row_set<1, HAS_W>(grid, s, a, h); break;
+    case 2: launch_row_set<2, HAS_W>(grid, s, a, h); break;
+    case 4: launch_row_set<4, HAS_W>(grid, s, a, h); break;
+    case 8: launch_row_set<8, HAS_W>(grid, s, a, h); break;
+    case 16: launch_row_set<16, HAS_W>(grid, s, a, h); break;
+    case 32: launch_row_set<32, HAS_W>(grid, s, a, h); break;
+    default: launch_row_set<64, HAS_W>(grid, s, a, h); break;
   }
+}
+
+// Stream-ordered scratch for the hub kernels, from a memory pool of the library's own per device
+// that keeps what it has been given, so that only the first call on a device pays for an allocation.
+constexpr int kMaxDevices = 64;
+static hipMemPool_t g_pool[kMaxDevices] = {};
+static std::mutex g_pool_mutex;
+
+static hgnn_status scratch_pool(hipMemPool_t* out) {
+  int dev = 0;
+  HGNN_HIP(hipGetDevice(&dev));
+  HGNN_REQUIRE(dev >= 0 && dev < kMaxDevices, HGNN_EUNSUPPORTED, "hgnn_spmm: device ordinal %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_pool_mutex);
+  if (!g_pool[dev]) {
+    hipMemPoolProps props{};
+    props.allocType = hipMemAllocationTypePinned;
+    props.handleTypes = hipMemHandleTypeNone;
+    props.location.type = hipMemLocationTypeDevice;
+    props.location.id = dev;
+    hipMemPool_t pool = nullptr;
+    HGNN_HIP(hipMemPoolCreate(&pool, &props));
+    uint64_t keep = UINT64_MAX;
+    HGNN_HIP(hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep));
+    g_pool[dev] = pool;
+  }
+  *out = g_pool[dev];
+  return HGNN_OK;
+}
+
+// Lists and partial rows for the hubs of a graph with nnz non-zeros; nothing when no row can be a hub.
+static hgnn_status hub_lists_alloc(int64_t nnz, int F, hipStream_t s, HubLists* h, void** base) {
+  *base = nullptr;
+  if (nnz <= kLongRow) return HGNN_OK;
+  // sum over hubs of ceil(deg / chunk) <= nnz / chunk + number of hubs, and there are fewer than nnz / kLongRow hubs
+  const int64_t max_hubs = nnz / kLongRow + 1;
+  const int64_t max_chunks = nnz / kHubChunk + max_hubs + 1;
+  auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
+  const int64_t o_count = 0;
+  const int64_t o_crow = o_count + 256;
+  const int64_t o_cno = o_crow + up(max_chunks * 4);
+  const int64_t o_hrow = o_cno + up(max_chunks * 4);
+  const int64_t o_hbase = o_hrow + up(max_hubs * 4);
+  const int64_t o_part = o_hbase + up(max_hubs * 4);
+  const int64_t bytes = o_part + up(max_chunks * int64_t(F) * 4);
+  hipMemPool_t pool = nullptr;
+  hgnn_status st = scratch_pool(&pool);
+  if (st != HGNN_OK) return st;
+  HGNN_HIP(hipMallocFromPoolAsync(base, size_t(bytes), pool, s));
+  char* p = static_cast<char*>(*base);
+  h->count = reinterpret_cast<int*>(p + o_count);
+  h->chunk_row = reinterpret_cast<int*>(p + o_crow);
+  h->chunk_no = reinterpret_cast<int*>(p + o_cno);
+  h->hub_row = reinterpret_cast<int*>(p + o_hrow);
+  h->hub_base = reinterpret_cast<int*>(p + o_hbase);
+  h->part = reinterpret_cast<float*>(p + o_part);
+  h->max_chunks = int(max_chunks);
+  h->max_hubs = int(max_hubs);
+  return HGNN_OK;
 }
 
 template <int WM, bool OFF32>
@@ -754,10 +872,19 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
     // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
     a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
     dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock * a.rows_per_wave)));
-    dim3 grid_long(unsigned(ceil_div(g->nrows, kLongBlock)));
-    if (edge_val) launch_row<true>(L, grid, grid_long, s, a);
-    else launch_row<false>(L, grid, grid_long, s, a);
-    HGNN_LAUNCH_CHECK("spmm_row_kernel / spmm_longrow_kernel");
+    HubLists h{};
+    void* scratch = nullptr;
+    st = hub_lists_alloc(g->nnz, F, s, &h, &scratch);
+    if (st != HGNN_OK) return st;
+    if (scratch) {
+      hub_zero_kernel<<<1, kBlock, 0, s>>>(h);
+      hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock))), kBlock, 0, s>>>(a, h);
+    }
+    if (edge_val) launch_row<true>(L, grid, s, a, scratch ? &h : nullptr);
+    else launch_row<false>(L, grid, s, a, scratch ? &h : nullptr);
+    const hipError_t launch_err = hipGetLastError();
+    if (scratch) HGNN_HIP(hipFreeAsync(scratch, s));
+    HGNN_REQUIRE(launch_err == hipSuccess, HGNN_EHIP, "hgnn_spmm: kernel launch failed: %s", hipGetErrorString(launch_err));
   } else {
     dim3 grid(unsigned(ceil_div(int64_t(g->nrows) * F, kBlock)));
     spmm_scalar_kernel<<<grid, kBlock, 0, s>>>(a);
