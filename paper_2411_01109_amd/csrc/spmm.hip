@@ -92,7 +92,7 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x)
 // kLongRow are hubs: they are left to the chunked kernels further down.
 // ---------------------------------------------------------------------------------------------------
 constexpr int kShortRow = 32;
-constexpr int kLongRow = 4096;
+constexpr int kLongRow = 1024;
 
 // acc += sum over the non-zeros k = first, first + STRIDE, ... < end of w_k * X[col_k, f0..f0+7],
 // U of them in flight at a time; the column ids of the next U are fetched while the rows of
@@ -231,7 +231,8 @@ __global__ __launch_bounds__(kBlock) void spmm_hub_kernel(SpmmArgs a, HubLists h
   const int row = h.chunk_row[blockIdx.x];
   const int row_end = a.rowptr[row + 1];
   const int cb = a.rowptr[row] + h.chunk_no[blockIdx.x] * kHubChunk;
-  constexpr int per_wave = kHubChunk / kWavesPerBlock;
+  const int len = row_end - cb < kHubChunk ? row_end - cb : kHubChunk;
+  const int per_wave = (len + kWavesPerBlock - 1) / kWavesPerBlock;
   const int b = cb + wave * per_wave < row_end ? cb + wave * per_wave : row_end;
   const int e = b + per_wave < row_end ? b + per_wave : row_end;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
