@@ -66,7 +66,9 @@ def _load():
     lib.orc_spmm_naive_fp16.restype = None
     lib.orc_spmm_naive_fp16.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, vp, i32, vp]
     lib.orc_spmm_discretized.restype = None
-    lib.orc_spmm_discretized.argtypes = [i32, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.orc_spmm_discretized.argtypes = [i32, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, i32, i32, vp, i32, vp, vp]
+    lib.orc_neighbor_groups.restype = i64
+    lib.orc_neighbor_groups.argtypes = [i32, vp, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -203,6 +205,18 @@ def segment_plan(rowptr, S: int):
             "split_seg_hi": sb[:n].copy()}
 
 
+def neighbor_groups(rowptr, ng: int):
+    """-> (grp_row, grp_first): the neighbour groups of at most ng non-zeros, in row order."""
+    rowptr = _i32(rowptr)
+    V = rowptr.size - 1
+    lib = _load()
+    n = lib.orc_neighbor_groups(V, _ptr(rowptr), ng, None, None)
+    row = np.empty(max(n, 1), dtype=np.int32)
+    first = np.empty(max(n, 1), dtype=np.int32)
+    lib.orc_neighbor_groups(V, _ptr(rowptr), ng, _ptr(row), _ptr(first))
+    return row[:n].copy(), first[:n].copy()
+
+
 def spmm_naive_fp16(rowptr, col, X, reduce: int = SUM, rows=None, wide_sum: bool = False):
     rowptr, col, rows, X = _i32(rowptr), _i32(col), _i32(rows), _f16(X)
     V, F = rowptr.size - 1, X.shape[1]
@@ -213,8 +227,10 @@ def spmm_naive_fp16(rowptr, col, X, reduce: int = SUM, rows=None, wide_sum: bool
     return out.view(np.float16)
 
 
-def spmm_discretized(rowptr, col, X, S: int, w=None, H: int = 1, reduce: int = SUM, row_scale=None, eid=None, rows=None):
-    """(sum of fp16-rounded scaled partials per row, max |partial| before rounding)."""
+def spmm_discretized(rowptr, col, X, S: int, w=None, H: int = 1, reduce: int = SUM, row_scale=None, eid=None, rows=None,
+                     by_row: bool = False):
+    """(sum of fp16-rounded scaled partials per row, max |partial| before rounding).  by_row: the batches are
+    the row's own neighbour groups of S (vertex-parallel form) instead of the storage-order segments."""
     rowptr, col, eid, rows = _i32(rowptr), _i32(col), _i32(eid), _i32(rows)
     X, w, row_scale = _f16(X), _f16(w), _f64(row_scale)
     V, F = rowptr.size - 1, X.shape[1]
@@ -222,6 +238,6 @@ def spmm_discretized(rowptr, col, X, S: int, w=None, H: int = 1, reduce: int = S
     out = np.empty((n, F), dtype=np.float64)
     mp = ctypes.c_double(0.0)
     _load().orc_spmm_discretized(V, _ptr(rowptr), _ptr(col), _ptr(eid), _ptr(w), H, _ptr(X), X.strides[0] // 2, F, reduce,
-                                 _ptr(row_scale), S, _ptr(rows), 0 if rows is None else rows.size, _ptr(out),
-                                 ctypes.byref(mp))
+                                 _ptr(row_scale), S, 1 if by_row else 0, _ptr(rows), 0 if rows is None else rows.size,
+                                 _ptr(out), ctypes.byref(mp))
     return out, mp.value

@@ -252,6 +252,22 @@ int32_t orc_segment_plan(int32_t V, const int32_t* rowptr, int32_t S, int32_t* s
   return ns;
 }
 
+/* ---- neighbour groups of the vertex-parallel variant (section 5.5): every row is cut,
+ * from its first non-zero on, into groups of at most ng neighbours; a group never holds
+ * non-zeros of two rows, the last group of a row may be shorter, an empty row has none.
+ * Groups are listed in row order: grp_row[j] = row, grp_first[j] = CSR position of the
+ * group's first non-zero.  Returns the number of groups; with NULL arrays it only counts. ---- */
+int64_t orc_neighbor_groups(int32_t V, const int32_t* rowptr, int32_t ng, int32_t* grp_row, int32_t* grp_first) {
+  int64_t n = 0;
+  for (int32_t i = 0; i < V; ++i)
+    for (int32_t k = rowptr[i]; k < rowptr[i + 1]; k += ng) {
+      if (grp_row) grp_row[n] = i;
+      if (grp_first) grp_first[n] = k;
+      ++n;
+    }
+  return n;
+}
+
 /* ---- demonstration helper (tests only): post-reduction scaling in half precision, the
  * scheme section 3.1.3 says overflows.  mode 0: the running sum itself is kept in fp16
  * (every addition rounds to fp16; large sums stall or reach INF).  mode 1: the sum is
@@ -279,13 +295,16 @@ void orc_spmm_naive_fp16(int32_t V, const int32_t* rowptr, const int32_t* col, c
 /* ---- discretized reduction scaling as the paper states it (section 5.2.2): reduce a
  * batch of at most S neighbours, scale that partial, round it to fp16 (the stored
  * partial), move to the next batch; the per-row result is the sum of its partials.
- * Batches are the plan's segments (edge ranges [k*S,(k+1)*S) cut at row boundaries).
+ * by_row = 0: batches are the plan's segments (edge ranges [k*S,(k+1)*S) cut at row
+ * boundaries), the edge-parallel form.  by_row = 1: batches are the row's own neighbour
+ * groups, S neighbours each counted from the start of the row (section 5.5: the
+ * vertex-parallel form never splits a row inside a batch).
  * Returns through out the fp64 sum of the fp16-rounded scaled partials and through
  * maxpart the largest |partial| met before rounding (overflow evidence). ---- */
 void orc_spmm_discretized(int32_t V, const int32_t* rowptr, const int32_t* col, const int32_t* eid, const uint16_t* w,
                           int32_t H, const uint16_t* X, int64_t ldx, int32_t F, int32_t reduce,
-                          const double* row_scale, int32_t S, const int32_t* sel, int32_t nsel, double* out,
-                          double* maxpart) {
+                          const double* row_scale, int32_t S, int32_t by_row, const int32_t* sel, int32_t nsel,
+                          double* out, double* maxpart) {
   int32_t D = F / H;
   int32_t nout = sel ? nsel : V;
   double mp = 0.0;
@@ -299,7 +318,7 @@ void orc_spmm_discretized(int32_t V, const int32_t* rowptr, const int32_t* col, 
       double total = 0.0;
       int32_t k = rowptr[i];
       while (k < rowptr[i + 1]) {
-        int32_t kend = (k / S + 1) * S;
+        int32_t kend = by_row ? rowptr[i] + ((k - rowptr[i]) / S + 1) * S : (k / S + 1) * S;
         if (kend > rowptr[i + 1]) kend = rowptr[i + 1];
         double part = 0.0;
         for (; k < kend; ++k) {

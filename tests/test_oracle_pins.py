@@ -442,6 +442,63 @@ def test_discretized_bounds_partials_where_naive_fp16_overflows():
     assert np.array_equal(oracle.spmm_naive_fp16(rowptr[:2], col, Xi).astype(np.float64), oracle.spmm(rowptr[:2], col, Xi))
 
 
+# ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
+@pytest.mark.parametrize("ng", [1, 4, 32, 64])
+def test_neighbor_groups_bruteforce(ng):
+    """Section 5.5: groups of at most ng neighbours that never cross a row."""
+    deg = rng.integers(0, 90, size=200)
+    deg[3] = 1000
+    deg[4] = 0
+    deg[5] = ng
+    deg[6] = ng + 1
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    row, first = oracle.neighbor_groups(rowptr, ng)
+    # definition, in python: walk every row in steps of ng
+    want = [(i, k) for i in range(len(deg)) for k in range(int(rowptr[i]), int(rowptr[i + 1]), ng)]
+    assert list(zip(row.tolist(), first.tolist())) == want
+    # invariants: closed-form count; the groups tile [0, E) in order; no group leaves its row
+    assert row.size == int(np.sum((deg + ng - 1) // ng))
+    end = np.minimum(first + ng, rowptr[row + 1])
+    assert np.array_equal(first[1:], end[:-1]) and first[0] == 0 and end[-1] == rowptr[-1]
+    assert np.all(first >= rowptr[row]) and np.all(end <= rowptr[row + 1]) and np.all(end - first <= ng)
+    assert not np.any(row == 4)
+
+
+def test_neighbor_groups_degenerate():
+    row, first = oracle.neighbor_groups(np.zeros(4, dtype=np.int32), 64)
+    assert row.size == 0 and first.size == 0
+    # the misalignment example of section 5.5: a first vertex with 11 neighbours makes the next
+    # vertex's groups start at an odd position
+    row, first = oracle.neighbor_groups(np.array([0, 11, 80], dtype=np.int32), 32)
+    assert row.tolist() == [0, 1, 1, 1] and first.tolist() == [0, 11, 43, 75]
+
+
+def test_discretized_by_row_batches():
+    """Per-row batching: exact data gives the plain result; the largest partial is bounded by the
+    group size; with S at least the longest row there is one batch per row, i.e. one rounding."""
+    deg = rng.integers(0, 30, size=60)
+    deg[7] = 400
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    E = int(rowptr[-1])
+    col = rng.integers(0, 60, size=E).astype(np.int32)
+    X = rng.integers(-3, 4, size=(60, 4)).astype(np.float16)
+    plain = oracle.spmm(rowptr, col, X)
+    for S in (4, 16, 64):
+        disc, mp = oracle.spmm_discretized(rowptr, col, X, S, by_row=True)
+        assert np.array_equal(disc, plain) and mp <= S * 3
+    Xr = rng.standard_normal((60, 4)).astype(np.float16)
+    one, _ = oracle.spmm_discretized(rowptr, col, Xr, 400, reduce=oracle.MEAN, by_row=True)
+    ref = oracle.spmm(rowptr, col, Xr, reduce=oracle.MEAN)
+    assert np.array_equal(one, ref.astype(np.float16).astype(np.float64))
+    # the two batchings differ only in where a row is cut: a row that starts on a segment
+    # boundary is cut at the same places
+    rp = np.array([0, 64, 64 + 150], dtype=np.int32)
+    c2 = rng.integers(0, 60, size=int(rp[-1])).astype(np.int32)
+    a, _ = oracle.spmm_discretized(rp, c2, Xr, 64, by_row=False)
+    b, _ = oracle.spmm_discretized(rp, c2, Xr, 64, by_row=True)
+    assert np.array_equal(a, b)
+
+
 # ------------------------------------------------------------------ fused norms and the GIN epilogue
 def test_gcn_both_norm_dense_bruteforce():
     """Eq. 2: D^-1/2 A D^-1/2 X with row degrees on the left and column degrees on the right."""
