@@ -178,6 +178,40 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
                                         hgnn_reduce op, const float* row_scale, const hgnn_spmm_fusion* fz,
                                         void* stream);
 
+/* The two comparison variants of the discretized SpMM that the paper measures against its own
+ * design (sections 5.4, 6.3.2 "atomic vs. non-atomic writes", 6.3.3 vertex-parallel form); same
+ * arguments, same result up to fp16 rounding order, always on the whole graph (a plan's
+ * column blocks are not used).
+ *  HGNN_EDGE_SEGMENTS          the library's own design, identical to hgnn_spmm_discretized.
+ *  HGNN_EDGE_SEGMENTS_ATOMIC   same segment kernel, but the partials of a row that crosses a
+ *      segment boundary are added to Y with packed fp16 atomic adds (rows concerned are zeroed
+ *      first) instead of going through the staging buffer and the follow-up kernel; the order
+ *      of those additions, hence the last bits of such rows, varies from run to run.
+ *  HGNN_VERTEX_GROUPS          vertex-parallel: every row is cut into neighbour groups of at
+ *      most group_edges non-zeros, a wavefront reduces one group, so no batch holds two rows;
+ *      a row of several groups stages one scaled fp16 partial per group and a follow-up kernel
+ *      adds them (no atomics, deterministic).  Edge values of a group that starts at an odd
+ *      position are fetched as aligned pairs from one position earlier.  Needs
+ *      hgnn_plan_add_groups on the plan first. */
+typedef enum { HGNN_EDGE_SEGMENTS = 0, HGNN_EDGE_SEGMENTS_ATOMIC = 1, HGNN_VERTEX_GROUPS = 2 } hgnn_spmm_variant;
+
+hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                          const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                          hgnn_reduce op, const float* row_scale, hgnn_spmm_variant variant,
+                                          void* stream);
+
+/* Builds (or rebuilds) inside plan p the neighbour groups of graph g for HGNN_VERTEX_GROUPS
+ * (section 5.4): group_edges in [1, 1024] neighbours per group, groups listed in row order, a
+ * staging slot of max_F halves for every group of a row that has more than one.  Device
+ * allocations owned by the plan; synchronizes the stream.  Not to be called while a kernel
+ * that uses the plan is in flight. */
+hgnn_status hgnn_plan_add_groups(hgnn_plan* p, const hgnn_csr* g, int32_t group_edges, void* stream);
+int64_t hgnn_plan_num_groups(const hgnn_plan* p);
+int32_t hgnn_plan_group_edges(const hgnn_plan* p);
+/* Copies the group list to host arrays of hgnn_plan_num_groups entries: group_row[j] = row of
+ * group j, group_first[j] = CSR position of its first non-zero.  Synchronizes the device. */
+hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32_t* group_row, int32_t* group_first);
+
 /* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s

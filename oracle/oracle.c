@@ -252,7 +252,7 @@ int32_t orc_segment_plan(int32_t V, const int32_t* rowptr, int32_t S, int32_t* s
   return ns;
 }
 
-/* ---- neighbour groups of the vertex-parallel variant (section 5.5): every row is cut,
+/* ---- neighbour groups of the vertex-parallel variant (section 5.4): every row is cut,
  * from its first non-zero on, into groups of at most ng neighbours; a group never holds
  * non-zeros of two rows, the last group of a row may be shorter, an empty row has none.
  * Groups are listed in row order: grp_row[j] = row, grp_first[j] = CSR position of the
@@ -297,7 +297,7 @@ void orc_spmm_naive_fp16(int32_t V, const int32_t* rowptr, const int32_t* col, c
  * partial), move to the next batch; the per-row result is the sum of its partials.
  * by_row = 0: batches are the plan's segments (edge ranges [k*S,(k+1)*S) cut at row
  * boundaries), the edge-parallel form.  by_row = 1: batches are the row's own neighbour
- * groups, S neighbours each counted from the start of the row (section 5.5: the
+ * groups, S neighbours each counted from the start of the row (section 5.4: the
  * vertex-parallel form never splits a row inside a batch).
  * Returns through out the fp64 sum of the fp16-rounded scaled partials and through
  * maxpart the largest |partial| met before rounding (overflow evidence). ---- */

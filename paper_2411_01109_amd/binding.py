@@ -23,8 +23,11 @@ EXPORTS = (
     "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks",
     "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
-    "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum",
+    "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
+    "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export",
 )
+
+HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
 
 
 class HgnnError(RuntimeError):
@@ -85,6 +88,13 @@ def load() -> ctypes.CDLL:
     lib.hgnn_edge_softmax.argtypes = [csr, vp, i32, vp, vp, vp]
     lib.hgnn_edge_softmax_bwd.argtypes = [csr, vp, i32, vp, vp, vp, f32, vp, vp]
     lib.hgnn_edge_rowsum.argtypes = [csr, vp, i32, vp, vp, vp]
+    lib.hgnn_spmm_discretized_variant.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, ctypes.c_int, vp]
+    lib.hgnn_plan_add_groups.argtypes = [vp, csr, i32, vp]
+    lib.hgnn_plan_num_groups.restype = i64
+    lib.hgnn_plan_num_groups.argtypes = [vp]
+    lib.hgnn_plan_group_edges.restype = i32
+    lib.hgnn_plan_group_edges.argtypes = [vp]
+    lib.hgnn_plan_groups_export.argtypes = [vp, csr, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)  # every declared entry point must be exported
     _lib = lib
@@ -249,6 +259,36 @@ def hgnn_spmm_discretized_fused(p: Plan, g: Csr, edge_val: Optional[torch.Tensor
     _check(load().hgnn_spmm_discretized_fused(p.handle, g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16),
                                               _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
                                               _ptr(row_scale, torch.float32), ctypes.byref(fz), _stream(stream)))
+
+
+def hgnn_spmm_discretized_variant(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor,
+                                  Y: torch.Tensor, variant: int, op: int = HGNN_SUM,
+                                  row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None, stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    _check(load().hgnn_spmm_discretized_variant(p.handle, g.ref, _ptr(edge_val, torch.float16), H,
+                                                _ptr(X, torch.float16), _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
+                                                _ptr(row_scale, torch.float32), variant, _stream(stream)))
+
+
+def hgnn_plan_add_groups(p: Plan, g: Csr, group_edges: int, stream=None) -> None:
+    _check(load().hgnn_plan_add_groups(p.handle, g.ref, group_edges, _stream(stream)))
+
+
+def hgnn_plan_num_groups(p: Plan) -> int:
+    return load().hgnn_plan_num_groups(p.handle)
+
+
+def hgnn_plan_group_edges(p: Plan) -> int:
+    return load().hgnn_plan_group_edges(p.handle)
+
+
+def hgnn_plan_groups_export(p: Plan, g: Csr):
+    """-> (group_row, group_first) host int32 numpy arrays."""
+    import numpy as np
+    n = hgnn_plan_num_groups(p)
+    row, first = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
+    _check(load().hgnn_plan_groups_export(p.handle, g.ref, row.ctypes.data, first.ctypes.data))
+    return row[:n], first[:n]
 
 
 def hgnn_sddmm(g: Csr, p: Optional[Plan], op: int, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,

@@ -146,6 +146,15 @@ struct hgnn_plan {
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs
   float* bsum = nullptr;            // [nb][nrows][max_H] per-block partial row sums of edge tensors
+  // neighbour groups of the vertex-parallel variant (hgnn_plan_add_groups): row r owns the groups
+  // goff[r] .. goff[r+1]-1, group j of the row covers the non-zeros rowptr[r] + j*ng ...
+  int32_t ng = 0;                   // neighbours per group; 0 = not built
+  int64_t n_groups = 0;
+  int64_t n_gslots = 0;             // groups that belong to rows with more than one group
+  int32_t* goff = nullptr;          // [nrows+1]
+  int32_t* moff = nullptr;          // [nrows+1] first staging slot of a row with more than one group
+  int32_t* grp_row = nullptr;       // [n_groups]
+  hgnn_half* gstage = nullptr;      // [n_gslots][max_F]
 };
 
 namespace hgnn {

@@ -290,6 +290,10 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->big_row);
   (void)hipFree(p->staging);
   (void)hipFree(p->vscratch);
+  (void)hipFree(p->goff);
+  (void)hipFree(p->moff);
+  (void)hipFree(p->grp_row);
+  (void)hipFree(p->gstage);
   delete p;
 }
 

@@ -46,6 +46,7 @@ struct SpmmArgs {
   const int* split_lo;
   const int* split_hi;
   int n_split;
+  int atomic_y;  // 1: conflicting pieces are added to Y with packed fp16 atomics instead of being staged (comparison variant)
 };
 
 __device__ __forceinline__ float scale_of(const SpmmArgs& a, int r) {
@@ -82,6 +83,18 @@ __device__ __forceinline__ void store_row(const SpmmArgs& a, int64_t row, int f0
 __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, float(x[i]), acc[i]);
+}
+
+// p[0..7] += v with four packed fp16 atomic adds (the conflict-write scheme the paper removes, section 5.2.3)
+__device__ __forceinline__ void atomic_add8(half_t* p, const float (&v)[8]) {
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    half2_t h;
+    h[0] = half_t(v[2 * q]);
+    h[1] = half_t(v[2 * q + 1]);
+    (void)__builtin_amdgcn_flat_atomic_fadd_v2f16(reinterpret_cast<half2_t*>(p) + q, h);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -522,8 +535,9 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
         }
         if (!(fl & 2)) {  // the row ends inside chunk gg
           if (active) {
-            if (from_before) store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
-            else store_row(a, run_row, f0, run, 1.f);
+            if (!from_before) store_row(a, run_row, f0, run, 1.f);
+            else if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run);
+            else store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
           }
 #pragma unroll
           for (int i = 0; i < 8; ++i) run[i] = 0.f;
@@ -542,8 +556,10 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
         from_before = false;
       }
     }
-    if (open && active)  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
-      store8(a.staging + (2 * seg + (from_before ? 0 : 1)) * a.stage_ld + f0, run, 1.f);
+    if (open && active) {  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
+      if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run);
+      else store8(a.staging + (2 * seg + (from_before ? 0 : 1)) * a.stage_ld + f0, run, 1.f);
+    }
   }
 
   // ---- zero-fill this wave's share of the empty rows
@@ -564,7 +580,8 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
 // whole wave, the groups striding over its pieces.
 constexpr int kFinishShort = 8;
 
-template <int STRIDE>
+// acc += staging rows MUL*k for k = first, first + STRIDE, ... <= last
+template <int STRIDE, int MUL = 2>
 __device__ __forceinline__ void pieces_accumulate(const SpmmArgs& a, int64_t first, int64_t last, int f0,
                                                   float (&acc)[8]) {
   constexpr int U = 4;
@@ -574,7 +591,7 @@ __device__ __forceinline__ void pieces_accumulate(const SpmmArgs& a, int64_t fir
     for (int u = 0; u < U; ++u) {
       const int64_t kk = k + u * STRIDE;
       t[u] = half8_t(0);
-      if (kk <= last) t[u] = *reinterpret_cast<const half8_t*>(a.staging + (2 * kk) * a.stage_ld + f0);
+      if (kk <= last) t[u] = *reinterpret_cast<const half8_t*>(a.staging + (MUL * kk) * a.stage_ld + f0);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -622,6 +639,184 @@ __global__ __launch_bounds__(kBlock) void spmm_finish_kernel(SpmmArgs a) {
     groups_reduce<L>(acc);
     if (g == 0 && active) store_row(a, rj, f0, acc, 1.f);
   }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Vertex-parallel variant of the discretized SpMM (section 5.4): a wave reduces one neighbour group,
+// at most ng non-zeros of a single row, so there is no row change inside a wave and no merge; what
+// is left of the conflict is between the waves that share a long row.  A row with one group is
+// stored directly; the groups of a longer row store their scaled fp16 partials in staging slots of
+// their own and spmm_vgroup_finish_kernel adds them.  Edge values of a group start at an arbitrary
+// position of the edge tensor: with one value per edge they are fetched as aligned pairs, starting
+// one position early when the group starts at an odd position, and the pair is taken apart while it
+// is copied to LDS.
+// ---------------------------------------------------------------------------------------------------
+struct VGroupArgs {
+  const int* grp_row;
+  const int* goff;
+  const int* moff;
+  int64_t n_groups;
+  int ng;
+  int pair_loads;  // edge values: one per edge, no edge-id map, 4-byte aligned base
+};
+
+__host__ __device__ inline int vgroup_lds_bytes(int ng, int H, bool has_w) {
+  const int spad = kWave * 4 * ((ng + 255) / 256);
+  return spad * 4 + (has_w ? align16i(spad * H * 2) : 0);
+}
+
+template <int L, bool HAS_W, bool OFF32>
+__global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupArgs v) {
+  constexpr int G = kWave / L;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int head = f0c / a.D;
+  const int spad = kWave * 4 * ((v.ng + 255) / 256);
+  unsigned char* base = smem + size_t(wave) * vgroup_lds_bytes(v.ng, a.H, HAS_W);
+  int* s_col = reinterpret_cast<int*>(base);
+  half_t* s_w = reinterpret_cast<half_t*>(base + spad * 4);
+
+  const int64_t j = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const bool valid = j < v.n_groups;
+  int row = 0, idx = 0, cnt = 1, k0 = 0, n = 0;
+  if (valid) {
+    row = v.grp_row[j];
+    idx = int(j - v.goff[row]);
+    cnt = v.goff[row + 1] - v.goff[row];
+    k0 = a.rowptr[row] + idx * v.ng;
+    const int left = a.rowptr[row + 1] - k0;
+    n = left < v.ng ? left : v.ng;
+  }
+
+  // ---- phase 1: coalesced stage of column ids (as byte offsets) and edge values
+  const bool pairs = HAS_W && v.pair_loads;
+  for (int i = lane; i < spad; i += kWave) {
+    const bool in = i < n;
+    const int c = in ? a.col[k0 + i] : 0;
+    s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;
+    if (HAS_W) {
+      if (!pairs) {
+        const int64_t slot = in ? (a.eid ? int64_t(a.eid[k0 + i]) : int64_t(k0 + i)) : 0;
+        for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
+      } else if (!in) {
+        s_w[i] = half_t(0);
+      }
+    }
+  }
+  if (pairs) {
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    const int odd = k0 & 1;
+    const int64_t b = int64_t(k0) - odd;  // even position at or just before the group's first value
+    for (int i = lane; 2 * i < n + odd; i += kWave) {
+      half2_t pr;
+      if (b + 2 * i + 1 < a.nnz) {
+        pr = *reinterpret_cast<const half2_t*>(a.w + b + 2 * i);
+      } else {
+        pr[0] = a.w[b + 2 * i];
+        pr[1] = half_t(0);
+      }
+      const int i0 = 2 * i - odd;
+      if (i0 >= 0 && i0 < n) s_w[i0] = pr[0];
+      if (i0 + 1 < n) s_w[i0 + 1] = pr[1];
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 2: the groups of lanes take consecutive chunks of the neighbour group
+  const int C = 4 * ((v.ng + 4 * G - 1) / (4 * G));
+  const int c0 = g * C < n ? g * C : n;
+  const int c1 = c0 + C < n ? c0 + C : n;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto gather = [&](int c) -> half8_t {
+    if (OFF32) {
+      const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
+      return *reinterpret_cast<const half8_t*>(reinterpret_cast<const char*>(a.X) + boff);
+    }
+    return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+  };
+  for (int i = c0; i < c1; i += 4) {
+    const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
+    half8_t x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);  // padding holds offset 0, a valid row
+    float wv[4] = {a.one, a.one, a.one, a.one};
+    if (HAS_W) {
+      if (a.H == 1) {
+        const half4_t w4 = *reinterpret_cast<const half4_t*>(s_w + i);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = float(w4[u]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = float(s_w[(i + u) * a.H + head]);
+      }
+    }
+    if (i + 4 <= c1) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) fma8(acc, wv[u], x[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i + u < c1) fma8(acc, wv[u], x[u]);
+    }
+  }
+  groups_reduce<L>(acc);
+  if (valid && g == 0 && active) {
+    const float sc = scale_of(a, row);
+    if (cnt == 1) store_row(a, row, f0, acc, sc);
+    else store8(a.staging + (int64_t(v.moff[row]) + idx) * a.stage_ld + f0, acc, sc);
+  }
+}
+
+// Follow-up kernel of the vertex-parallel variant; it also writes the empty rows.  A wave looks at G
+// rows: rows with up to kFinishShort groups are summed by their own lane group, longer ones by the wave.
+template <int L>
+__global__ __launch_bounds__(kBlock) void spmm_vgroup_finish_kernel(SpmmArgs a, VGroupArgs v) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int64_t r0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  if (r0 >= a.nrows) return;
+  const int64_t r = r0 + g;
+  int cnt = 1, first = 0;  // cnt = 1: nothing to do
+  if (r < a.nrows) {
+    cnt = v.goff[r + 1] - v.goff[r];
+    first = v.moff[r];
+  }
+  if (cnt == 0 && active) {
+    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_row(a, r, f0, zero, 0.f);
+  }
+  if (cnt > 1 && cnt <= kFinishShort) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    pieces_accumulate<1, 1>(a, first, int64_t(first) + cnt - 1, f0c, acc);
+    if (active) store_row(a, r, f0, acc, 1.f);
+  }
+  for (int j = 0; j < G; ++j) {
+    const int cj = __shfl(cnt, j * L), fj = __shfl(first, j * L);
+    if (cj <= kFinishShort) continue;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    pieces_accumulate<G, 1>(a, int64_t(fj) + g, int64_t(fj) + cj - 1, f0c, acc);
+    groups_reduce<L>(acc);
+    if (g == 0 && active) store_row(a, r0 + j, f0, acc, 1.f);
+  }
+}
+
+// zero the rows whose pieces the atomic comparison variant adds into Y
+template <int L>
+__global__ __launch_bounds__(kBlock) void zero_split_rows_kernel(SpmmArgs a) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int64_t idx = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  if (idx >= a.n_split || 8 * l >= a.F) return;
+  *reinterpret_cast<half8_t*>(a.Y + int64_t(a.split_row[idx]) * a.ldy + 8 * l) = half8_t(0);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -779,6 +974,67 @@ static void launch_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
   }
 }
 
+static void launch_zero_split(int L, dim3 grid, hipStream_t s, const SpmmArgs& a) {
+  switch (L) {
+    case 1: zero_split_rows_kernel<1><<<grid, kBlock, 0, s>>>(a); break;
+    case 2: zero_split_rows_kernel<2><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: zero_split_rows_kernel<4><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: zero_split_rows_kernel<8><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: zero_split_rows_kernel<16><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: zero_split_rows_kernel<32><<<grid, kBlock, 0, s>>>(a); break;
+    default: zero_split_rows_kernel<64><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+template <int L>
+static void launch_vgroup_l(bool has_w, bool off32, dim3 grid, dim3 grid2, size_t lds, hipStream_t s, const SpmmArgs& a,
+                            const VGroupArgs& v) {
+  if (v.n_groups > 0) {
+    if (has_w) {
+      if (off32) spmm_vgroup_kernel<L, true, true><<<grid, kBlock, lds, s>>>(a, v);
+      else spmm_vgroup_kernel<L, true, false><<<grid, kBlock, lds, s>>>(a, v);
+    } else {
+      if (off32) spmm_vgroup_kernel<L, false, true><<<grid, kBlock, lds, s>>>(a, v);
+      else spmm_vgroup_kernel<L, false, false><<<grid, kBlock, lds, s>>>(a, v);
+    }
+  }
+  spmm_vgroup_finish_kernel<L><<<grid2, kBlock, 0, s>>>(a, v);
+}
+
+// The vertex-parallel variant for the graph in `a` with the neighbour groups of plan p.
+static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStream_t s) {
+  VGroupArgs v{};
+  v.grp_row = p->grp_row;
+  v.goff = p->goff;
+  v.moff = p->moff;
+  v.n_groups = p->n_groups;
+  v.ng = p->ng;
+  v.pair_loads = (a.w && a.H == 1 && !a.eid && (reinterpret_cast<uintptr_t>(a.w) & 3u) == 0) ? 1 : 0;
+  a.staging = reinterpret_cast<half_t*>(p->gstage);
+  a.stage_ld = p->max_F;
+  const int L = pow2_at_least(a.F / 8);
+  const int G = kWave / L;
+  const size_t lds = size_t(vgroup_lds_bytes(v.ng, a.H, a.w != nullptr)) * kWavesPerBlock;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_spmm_discretized_variant: group_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)",
+               v.ng, a.H, lds);
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  dim3 grid(unsigned(ceil_div(v.n_groups > 0 ? v.n_groups : 1, kWavesPerBlock)));
+  dim3 grid2(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * G)));
+  const bool has_w = a.w != nullptr;
+  switch (L) {
+    case 1: launch_vgroup_l<1>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    case 2: launch_vgroup_l<2>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    case 4: launch_vgroup_l<4>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    case 8: launch_vgroup_l<8>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    case 16: launch_vgroup_l<16>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    case 32: launch_vgroup_l<32>(has_w, off32, grid, grid2, lds, s, a, v); break;
+    default: launch_vgroup_l<64>(has_w, off32, grid, grid2, lds, s, a, v); break;
+  }
+  HGNN_LAUNCH_CHECK("spmm_vgroup_kernel / spmm_vgroup_finish_kernel");
+  return HGNN_OK;
+}
+
 // Pass 1 and pass 2 of the discretized SpMM for the graph in `a` with the segment arrays of plan q.
 static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipStream_t s) {
   const int wm = a.col_scale ? 2 : (a.w ? 1 : 0);
@@ -802,6 +1058,10 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
   // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  if (a.atomic_y && a.n_split > 0) {
+    launch_zero_split(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
+    HGNN_LAUNCH_CHECK("zero_split_rows_kernel");
+  }
   if (wm == 2) {
     if (off32) launch_seg<2, true>(L, grid, lds, s, a);
     else launch_seg<2, false>(L, grid, lds, s, a);
@@ -813,7 +1073,7 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
     else launch_seg<0, false>(L, grid, lds, s, a);
   }
   HGNN_LAUNCH_CHECK("spmm_seg_kernel");
-  if (a.n_split > 0) {
+  if (a.n_split > 0 && !a.atomic_y) {
     const int G = kWave / L;
     dim3 grid2(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * G)));
     launch_finish(L, grid2, s, a);
@@ -955,6 +1215,34 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
                                   const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
                                   hgnn_reduce op, const float* row_scale, void* stream) {
   return hgnn_spmm_discretized_fused(p, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, nullptr, stream);
+}
+
+hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
+                                          const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
+                                          hgnn_reduce op, const float* row_scale, hgnn_spmm_variant variant,
+                                          void* stream) {
+  if (variant == HGNN_EDGE_SEGMENTS)
+    return hgnn_spmm_discretized_fused(p, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, nullptr, stream);
+  clear_error();
+  const char* who = "hgnn_spmm_discretized_variant";
+  HGNN_REQUIRE(variant == HGNN_EDGE_SEGMENTS_ATOMIC || variant == HGNN_VERTEX_GROUPS, HGNN_EINVAL,
+               "%s: unknown variant %d", who, int(variant));
+  hgnn_status st = check_spmm_args(who, g, edge_val, H, X, ldx, Y, ldy, F, op);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
+  HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
+               "%s: the plan was built for another graph", who);
+  HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "%s: F = %d exceeds the plan's max_F = %d", who, F, p->max_F);
+  HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
+               "%s: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y", who);
+  HGNN_REQUIRE(variant != HGNN_VERTEX_GROUPS || p->ng > 0, HGNN_EINVAL,
+               "%s: the plan holds no neighbour groups (hgnn_plan_add_groups)", who);
+  if (g->nrows == 0) return HGNN_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
+  if (variant == HGNN_VERTEX_GROUPS) return run_vgroups(p, a, g->ncols, s);
+  a.atomic_y = 1;  // always on the whole graph: column blocks are not used by the comparison variants
+  return run_segments(p, a, g->ncols, s);
 }
 
 }  // extern "C"

@@ -1,0 +1,176 @@
+"""GPU parity of the comparison variants of the discretized SpMM (vertex-parallel neighbour groups,
+atomic conflict writes) against the CPU fp64 oracle, and of the neighbour-group lists, bit exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from parity import compare, sample_rows
+from test_gpu_parity import down, f16, rand_graph, up
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("ng", [1, 7, 32, 64, 256, 1024])
+def test_neighbor_groups_bit_exact(hgnn, dev, ng):
+    print(f"groups ng={ng}", flush=True)
+    rowptr, col = rand_graph(3000, 3000, 9, 1, hubs=((17, 5000), (2999, 700), (40, ng), (41, ng + 1)),
+                             empties=(0, 18, 2998))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, 64, 1)
+    assert hgnn.hgnn_plan_num_groups(p) == 0 and hgnn.hgnn_plan_group_edges(p) == 0
+    hgnn.hgnn_plan_add_groups(p, g, ng)
+    ref_row, ref_first = oracle.neighbor_groups(rowptr, ng)
+    row, first = hgnn.hgnn_plan_groups_export(p, g)
+    assert hgnn.hgnn_plan_num_groups(p) == ref_row.size and hgnn.hgnn_plan_group_edges(p) == ng
+    assert np.array_equal(row, ref_row) and np.array_equal(first, ref_first)
+    # rebuilding with another size replaces the lists
+    hgnn.hgnn_plan_add_groups(p, g, 2 * ng if ng < 1024 else 3)
+    ref_row, ref_first = oracle.neighbor_groups(rowptr, 2 * ng if ng < 1024 else 3)
+    row, first = hgnn.hgnn_plan_groups_export(p, g)
+    assert np.array_equal(row, ref_row) and np.array_equal(first, ref_first)
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_neighbor_groups_of_an_empty_graph(hgnn, dev):
+    rowptr = np.zeros(11, dtype=np.int32)
+    g = hgnn.Csr(up(rowptr, dev), torch.empty(0, dtype=torch.int32, device=dev))
+    p = hgnn.hgnn_plan_create(g, 256, 64, 1)
+    hgnn.hgnn_plan_add_groups(p, g, 64)
+    assert hgnn.hgnn_plan_num_groups(p) == 0
+    X = torch.ones((10, 64), dtype=torch.float16, device=dev)
+    Y = torch.full((10, 64), 5.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized_variant(p, g, None, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)
+    assert np.all(down(Y) == 0)
+    hgnn.hgnn_plan_destroy(p)
+
+
+VSHAPES = [  # (F, H, has_w, reduce, ng, pad)
+    (64, 1, True, 0, 64, 0), (64, 1, False, 1, 256, 0), (128, 1, True, 1, 256, 8), (32, 1, True, 0, 32, 0),
+    (16, 1, False, 0, 512, 0), (8, 1, True, 0, 7, 0), (256, 1, False, 0, 64, 0), (512, 1, True, 1, 1024, 0),
+    (64, 4, True, 0, 64, 0), (128, 8, True, 1, 100, 0), (48, 1, True, 0, 64, 0), (64, 1, True, 0, 1, 0),
+]
+
+
+@pytest.mark.parametrize("F,H,has_w,reduce,ng,pad", VSHAPES)
+def test_vertex_groups_shapes(hgnn, dev, F, H, has_w, reduce, ng, pad):
+    print(f"vgroups F={F} H={H} w={has_w} reduce={reduce} ng={ng} pad={pad}", flush=True)
+    V, ncols = 1237, 997
+    rowptr, col = rand_graph(V, ncols, 11, F + ng, hubs=((5, 5000), (700, 777), (1236, 300)), empties=(0, 6, 1235))
+    E = col.size
+    r = np.random.default_rng(F * 7 + H)
+    Xh = f16(r.standard_normal((ncols, F + pad)))
+    w = f16(r.standard_normal((E, H))) if has_w else None
+    rs = r.uniform(0.5, 2.0, V).astype(np.float32)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    Xd = up(Xh, dev)[:, :F]
+    ref, sabs = oracle.spmm(rowptr, col, Xh[:, :F], w=w, H=H, reduce=reduce, row_scale=rs.astype(np.float64),
+                            want_sabs=True)
+    p = hgnn.hgnn_plan_create(g, 256, max(F, 8), H)
+    hgnn.hgnn_plan_add_groups(p, g, ng)
+    Yfull = torch.full((V, F + pad), 7.0, dtype=torch.float16, device=dev)
+    Y = Yfull[:, :F]
+    bits = []
+    # edge values at a 4-byte aligned base (pair fetch) and at an odd element offset (element fetch)
+    for shift in ((0, 1) if has_w else (0,)):
+        wd = None
+        if has_w:
+            buf = torch.zeros(E * H + 1, dtype=torch.float16, device=dev)
+            buf[shift:shift + E * H] = up(w, dev).reshape(-1)
+            wd = buf[shift:shift + E * H].view(E, H)
+        Y.fill_(7.0)
+        hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, Xd, Y, hgnn.HGNN_VERTEX_GROUPS, op=reduce, row_scale=up(rs, dev))
+        got = down(Y)
+        compare(f"vertex groups shift={shift}", got, ref, sabs)
+        bits.append(got.view(np.uint16).copy())
+    Y.fill_(-3.0)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, Xd, Y, hgnn.HGNN_VERTEX_GROUPS, op=reduce, row_scale=up(rs, dev))
+    assert all(np.array_equal(down(Y).view(np.uint16), b) for b in bits)  # deterministic, whatever the fetch path
+    if pad:
+        assert np.all(down(Yfull)[:, F:] == 7.0)
+    hgnn.hgnn_plan_destroy(p)
+
+
+@pytest.mark.parametrize("F,H,has_w,reduce,S", [(64, 1, True, 0, 256), (128, 1, False, 1, 128), (64, 4, True, 1, 64),
+                                                (32, 1, True, 0, 7)])
+def test_atomic_variant_shapes(hgnn, dev, F, H, has_w, reduce, S):
+    print(f"atomic F={F} H={H} w={has_w} reduce={reduce} S={S}", flush=True)
+    V, ncols = 1237, 997
+    rowptr, col = rand_graph(V, ncols, 11, F + S, hubs=((5, 5000), (700, 777), (1236, 300)), empties=(0, 6, 1235))
+    r = np.random.default_rng(F * 7 + H)
+    Xh = f16(r.standard_normal((ncols, F)))
+    w = f16(r.standard_normal((col.size, H))) if has_w else None
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    wd = None if w is None else up(w, dev)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, reduce=reduce, want_sabs=True)
+    p = hgnn.hgnn_plan_create(g, S, F, H)
+    Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, up(Xh, dev), Y, hgnn.HGNN_EDGE_SEGMENTS_ATOMIC, op=reduce)
+    got = down(Y)
+    # every addition into a split row rounds to fp16 at the magnitude of the running sum: allow one such
+    # rounding per piece on top of the usual rule
+    pieces = np.maximum((rowptr[1:] - 1) // S - rowptr[:-1] // S, 0)[:, None]
+    compare("atomic", got, ref, sabs * (1 + pieces))
+    # rows inside one segment never meet an atomic: bit-identical to the staged design
+    Y2 = torch.empty_like(Y)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, up(Xh, dev), Y2, hgnn.HGNN_EDGE_SEGMENTS, op=reduce)
+    whole = (pieces[:, 0] == 0)
+    assert np.array_equal(got[whole].view(np.uint16), down(Y2)[whole].view(np.uint16))
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_vertex_groups_on_the_transposed_graph_with_edge_ids(hgnn, dev):
+    V, ncols, F, H = 900, 1100, 64, 2
+    rowptr, col = rand_graph(V, ncols, 14, 3, hubs=((9, 1500),), empties=(2,))
+    r = np.random.default_rng(5)
+    w = f16(r.standard_normal((col.size, H)))
+    dY = f16(r.standard_normal((V, F)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    ref, sabs = oracle.spmm(rT, cT, dY, w=w, H=H, eid=eT, want_sabs=True)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    hgnn.hgnn_plan_add_groups(pt, gt, 64)
+    dX = torch.empty((ncols, F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized_variant(pt, gt, up(w, dev), H, up(dY, dev), dX, hgnn.HGNN_VERTEX_GROUPS)
+    compare("vgroups transposed", down(dX), ref, sabs)
+    hgnn.hgnn_plan_destroy(pt)
+
+
+def test_vertex_groups_do_not_overflow_where_naive_fp16_does(hgnn, dev):
+    """Config 2b (all-positive features, hubs > 10^4): per-group scaling keeps every stored partial in range."""
+    w = wl.gin_overflow(positive=True)
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, w.F, 1)
+    hgnn.hgnn_plan_add_groups(p, g, 64)
+    X = up(w.tensors["X"], dev)
+    Y = torch.empty((w.V, w.F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized_variant(p, g, None, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS, op=hgnn.HGNN_MEAN)
+    got = down(Y)
+    assert np.all(np.isfinite(got))
+    rows = sample_rows(w.rowptr, 400, 11)
+    ref, sabs = oracle.spmm(w.rowptr, w.col, w.tensors["X"], reduce=oracle.MEAN, rows=rows, want_sabs=True)
+    compare("c2b vertex groups mean", got[rows], ref, sabs)
+    _, maxpart = oracle.spmm_discretized(w.rowptr, w.col, w.tensors["X"], 64, reduce=oracle.MEAN, rows=rows, by_row=True)
+    assert maxpart <= 8.0
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_variant_argument_errors(hgnn, dev):
+    rowptr, col = rand_graph(50, 50, 4, 2)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 64, 64, 1)
+    X = torch.ones((50, 64), dtype=torch.float16, device=dev)
+    Y = torch.empty_like(X)
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_spmm_discretized_variant(p, g, None, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)
+    assert ei.value.status == hgnn.HGNN_EINVAL and "neighbour groups" in str(ei.value)
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_spmm_discretized_variant(p, g, None, 1, X, Y, 9)
+    assert ei.value.status == hgnn.HGNN_EINVAL
+    for bad in (0, 1025):
+        with pytest.raises(hgnn.HgnnError) as ei:
+            hgnn.hgnn_plan_add_groups(p, g, bad)
+        assert ei.value.status == hgnn.HGNN_EINVAL
+    hgnn.hgnn_plan_destroy(p)

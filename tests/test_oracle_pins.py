@@ -445,7 +445,7 @@ def test_discretized_bounds_partials_where_naive_fp16_overflows():
 # ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
 @pytest.mark.parametrize("ng", [1, 4, 32, 64])
 def test_neighbor_groups_bruteforce(ng):
-    """Section 5.5: groups of at most ng neighbours that never cross a row."""
+    """Section 5.4: groups of at most ng neighbours that never cross a row."""
     deg = rng.integers(0, 90, size=200)
     deg[3] = 1000
     deg[4] = 0
@@ -467,7 +467,7 @@ def test_neighbor_groups_bruteforce(ng):
 def test_neighbor_groups_degenerate():
     row, first = oracle.neighbor_groups(np.zeros(4, dtype=np.int32), 64)
     assert row.size == 0 and first.size == 0
-    # the misalignment example of section 5.5: a first vertex with 11 neighbours makes the next
+    # the misalignment example of section 5.4: a first vertex with 11 neighbours makes the next
     # vertex's groups start at an odd position
     row, first = oracle.neighbor_groups(np.array([0, 11, 80], dtype=np.int32), 32)
     assert row.tolist() == [0, 1, 1, 1] and first.tolist() == [0, 11, 43, 75]
