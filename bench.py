@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--col-blocks", type=int, default=0, help="column blocks of the SpMM plans: 0 = automatic, 1 = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print a per-op table to stderr")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the comparison variants of the discretized SpMM (atomic conflict writes, "
+                         "vertex-parallel neighbour groups) beside the path; reported under 'variants', not in the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first copy a 1 GiB buffer three times (a plain kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -111,7 +114,7 @@ def main():
         Lg *= 2
     off32 = "true" if V * X.stride(0) * 2 < (1 << 32) else "false"
     seg_name = lambda hw: f"hgnn::spmm_seg_kernel<{Lg}, {1 if hw else 0}, {off32}>"
-    row_name = lambda hw: f"hgnn::spmm_row_kernel<{Lg}, {'true' if hw else 'false'}> (+ spmm_longrow_kernel)"
+    row_name = lambda hw: f"hgnn::spmm_row_kernel<{Lg}, {'true' if hw else 'false'}> (+ spmm_hub_kernel)"
     ops = []  # (name, kernel, min bytes, fn, requested bytes)
     wH = 1 if ew is not None else 0
     ops.append(("spmm_fwd_plain", row_name(wH), spmm_min(wH, False), lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y), spmm_req(wH, False)))
@@ -234,6 +237,38 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
+    variants = None
+    if args.variants:
+        # the paper's two SpMM micro-benchmarks (atomic vs. non-atomic conflict writes; the vertex-parallel
+        # form with neighbour groups), forward SpMM of this workload, all on the whole graph (no column blocks)
+        plan1 = hgnn.hgnn_plan_create(g, args.seg_edges, F, H, col_blocks=1)
+        cand = [("edge_segments_staged", lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_EDGE_SEGMENTS)),
+                ("edge_segments_atomic", lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_EDGE_SEGMENTS_ATOMIC))]
+        variants = {}
+
+        def time_fn(fn):
+            for _ in range(max(args.warmup, 1)):
+                fn()
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for a, b in pairs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
+        for name, fn in cand:
+            variants[name] = {"ms": round(time_fn(fn), 4)}
+        for ng in (64, 256):
+            hgnn.hgnn_plan_add_groups(plan1, g, ng)
+            variants[f"vertex_groups_{ng}"] = {
+                "ms": round(time_fn(lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)), 4),
+                "groups": hgnn.hgnn_plan_num_groups(plan1)}
+        variants["vertex_rows_no_plan"] = {"ms": round(time_fn(lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y)), 4)}
+        for k in variants:
+            variants[k]["req_GBps"] = round(spmm_req(wH, False) / (variants[k]["ms"] * 1e-3) / 1e9, 1)
+        hgnn.hgnn_plan_destroy(plan1)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -261,13 +296,16 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail,
+        "layers": layer_ms, "ops": detail, "variants": variants,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        if variants:
+            for k, v in variants.items():
+                print(f"variant {k:24s} {v['ms']:9.4f} ms  req {v['req_GBps']:8.1f} GB/s", file=sys.stderr)
     print(json.dumps(line))
     return 0
 

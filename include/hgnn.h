@@ -20,8 +20,12 @@
  *    its neighbourhood N(i); columns are neighbour ids.  Duplicate non-zeros
  *    are separate edges.
  *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
- *    compute entry points are asynchronous on that stream, never synchronize and
- *    never allocate.  hgnn_plan_create, hgnn_plan_export, hgnn_transpose and
+ *    compute entry points are asynchronous on that stream and never synchronize;
+ *    those that take a plan never allocate.  hgnn_spmm (no plan) takes scratch for
+ *    rows longer than 1024 non-zeros from a stream-ordered memory pool of the
+ *    library's own (hipMallocFromPoolAsync / hipFreeAsync on `stream`; the pool
+ *    keeps its memory, so only the first call on a device reaches the driver).
+ *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose and
  *    hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
  *  - Arithmetic: fp16 in memory, fp32 in registers, one round-to-nearest-even
  *    conversion when a value is stored.
@@ -29,10 +33,14 @@
  *    the host before anything is launched.  hgnn_last_error() returns a
  *    thread-local detail string for the last failing call of this thread.
  *  - Feature widths: odd F is rejected (HGNN_EINVAL): pad to the next even
- *    number as section 4.1 prescribes for half2; the 16-byte vector path needs
- *    F % 8 == 0, ld % 8 == 0 and 16-byte aligned base pointers, other even
- *    shapes take a slower scalar path in hgnn_spmm / hgnn_sddmm and are
- *    HGNN_EUNSUPPORTED in hgnn_spmm_discretized.
+ *    number as section 4.1 prescribes for half2.  The 16-byte vector path needs
+ *    row pitches (ld) that are multiples of 8 halves and 16-byte aligned base
+ *    pointers; F itself may be any even number up to 512 (e.g. 42 classes in rows
+ *    of pitch 48): rows are read in 16-byte pieces up to the pitch, whatever the
+ *    padding columns hold never reaches a result, and padding columns of outputs
+ *    are not written.  With several heads of edge values (or SDDMM heads) D must
+ *    be a multiple of 8.  Other shapes take a slower scalar path in hgnn_spmm /
+ *    hgnn_sddmm and are HGNN_EUNSUPPORTED in hgnn_spmm_discretized.
  */
 #ifndef HGNN_H
 #define HGNN_H
@@ -151,7 +159,8 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
  * one segment are stored directly, partials of rows that cross a segment boundary
  * go to the plan's staging buffer and a follow-up kernel adds them in ascending
  * segment order and stores the row once (section 5.2.3).  Deterministic.
- * Needs F % 8 == 0, F <= 512, D % 8 == 0, F <= plan max_F, and the plan of this graph. */
+ * Needs F <= 512, ld % 8 == 0, 16-byte aligned X and Y, D % 8 == 0 when edge values have
+ * several heads, F <= plan max_F, and the plan of this graph. */
 hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
                                   const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,
                                   hgnn_reduce op, const float* row_scale, void* stream);

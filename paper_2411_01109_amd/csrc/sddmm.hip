@@ -57,7 +57,9 @@ __host__ __device__ inline SddmmLds sddmm_lds_layout(int S, int H) {
 }
 
 // DOT over one plan segment per wave:  out[k,h] = <U[row k, h], Vt[col k, h]>
-template <int L>
+// MASK: one head whose length is not a multiple of 8 -- the group's lanes cover the padded row pitch and
+// the elements past D are forced to zero on both operands (whatever the padding columns hold).
+template <int L, bool MASK>
 __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   constexpr int G = kWave / L;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -66,8 +68,19 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  const int LH = a.D / 8;  // lanes per head (power of two)
+  const int LH = MASK ? L : a.D / 8;  // lanes per head (power of two)
   const int head = f0c / a.D;
+  const int nvalid = active ? a.F - f0 : 0;  // MASK: elements of this lane's vector that exist
+  const bool writer = MASK || active;         // MASK: every lane of the group may end up holding a result
+  auto load8 = [&](const half_t* p) -> half8_t {
+    half8_t v = *reinterpret_cast<const half8_t*>(p);
+    if (MASK && nvalid < 8) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (i >= nvalid) v[i] = half_t(0);
+    }
+    return v;
+  };
   const int lh = l % LH;
   const int S = a.S;
   const SddmmLds lay = sddmm_lds_layout(S, a.H);
@@ -92,14 +105,14 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   half8_t u = half8_t(0);
   if (c0 < c1) {
     cur = s_row[c0];
-    u = *reinterpret_cast<const half8_t*>(a.U + int64_t(cur) * a.ldu + f0c);
+    u = load8(a.U + int64_t(cur) * a.ldu + f0c);
   }
   for (int i = c0; i < c1; i += 4) {
     const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
     const int blk = s_blk[i >> 2];
     half8_t v[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const half8_t*>(a.Vt + int64_t(cols[q]) * a.ldv + f0c);
+    for (int q = 0; q < 4; ++q) v[q] = load8(a.Vt + int64_t(cols[q]) * a.ldv + f0c);
     float p[4];
     if (blk == cur) {
 #pragma unroll
@@ -112,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
         if (i + q < c1) {
           if (rows[q] != cur) {
             cur = rows[q];
-            u = *reinterpret_cast<const half8_t*>(a.U + int64_t(cur) * a.ldu + f0c);
+            u = load8(a.U + int64_t(cur) * a.ldu + f0c);
           }
           p[q] = dot8(u, v[q]);
         }
@@ -131,7 +144,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
         p[0] = (b1 ? p[1] : p[0]) + r;  // edge 2*b0 + b1
         for (int off = 4; off < LH; off <<= 1) p[0] += __shfl_xor(p[0], off);
         const int e = i + 2 * int(b0) + int(b1);
-        if (active && lh < 4 && e < c1) s_out[e * a.H + head] = half_t(p[0]);
+        if (writer && lh < 4 && e < c1) s_out[e * a.H + head] = half_t(p[0]);
       } else {
         const int e = i + 2 * int(b0);
         if (active && e < c1) s_out[e * a.H + head] = half_t(p[0]);
@@ -336,15 +349,20 @@ static void launch_edge(int L, dim3 grid, size_t lds, hipStream_t s, const Sddmm
   }
 }
 
-static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+static void launch_seg(int L, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+#define LAUNCH_SEG(LL)                                                    \
+  do {                                                                   \
+    if (mask) sddmm_seg_kernel<LL, true><<<grid, kBlock, lds, s>>>(a);   \
+    else sddmm_seg_kernel<LL, false><<<grid, kBlock, lds, s>>>(a);       \
+  } while (0)
   switch (L) {
-    case 1: sddmm_seg_kernel<1><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: sddmm_seg_kernel<2><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: sddmm_seg_kernel<4><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: sddmm_seg_kernel<8><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: sddmm_seg_kernel<16><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: sddmm_seg_kernel<32><<<grid, kBlock, lds, s>>>(a); break;
-    default: sddmm_seg_kernel<64><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: LAUNCH_SEG(1); break;
+    case 2: LAUNCH_SEG(2); break;
+    case 4: LAUNCH_SEG(4); break;
+    case 8: LAUNCH_SEG(8); break;
+    case 16: LAUNCH_SEG(16); break;
+    case 32: LAUNCH_SEG(32); break;
+    default: LAUNCH_SEG(64); break;
   }
 }
 
@@ -413,9 +431,11 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     a.S = p->S;
   }
   const int LH = D / 8;
-  const bool vec = D % 8 == 0 && (LH & (LH - 1)) == 0 && F <= 512 && ldu % 8 == 0 && ldv % 8 == 0 && aligned16(U) &&
-                   aligned16(Vt) && (!score || (aligned16(a_l) && aligned16(a_r)));
-  const int L = vec ? pow2_at_least(F / 8) : 0;
+  const bool wide = F <= 512 && ldu % 8 == 0 && ldv % 8 == 0 && aligned16(U) && aligned16(Vt);
+  const bool vec = wide && D % 8 == 0 && (LH & (LH - 1)) == 0 && (!score || (aligned16(a_l) && aligned16(a_r)));
+  // one head of any even length: 16-byte loads up to the padded pitch, the tail masked (DOT over a plan only)
+  const bool masked = wide && !vec && !score && H == 1 && p != nullptr;
+  const int L = (vec || masked) ? pow2_at_least((F + 7) / 8) : 0;
   const int64_t seg_blocks = p ? ceil_div(p->nseg, kWavesPerBlock) : 0;
 
   if (vec && score && p && H <= p->max_H) {
@@ -442,7 +462,7 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     HGNN_LAUNCH_CHECK("edge_score_seg_kernel");
     return HGNN_OK;
   }
-  if (vec && !score && p) {
+  if ((vec || masked) && !score && p) {
     const size_t lds = size_t(sddmm_lds_layout(a.S, H).total) * kWavesPerBlock;
     if (lds <= 65536 && p->nb > 1) {
       // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
@@ -457,13 +477,13 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
         ab.seg_hi = q->seg_row_hi;
         ab.nseg = q->nseg;
         ab.nnz = q->nnz;
-        launch_seg(L, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
+        launch_seg(L, masked, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
         HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       }
       return HGNN_OK;
     }
     if (lds <= 65536) {
-      launch_seg(L, dim3(unsigned(seg_blocks)), lds, s, a);
+      launch_seg(L, masked, dim3(unsigned(seg_blocks)), lds, s, a);
       HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       return HGNN_OK;
     }

@@ -77,7 +77,14 @@ __device__ __forceinline__ void store_row(const SpmmArgs& a, int64_t row, int f0
 #pragma unroll
     for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
   }
-  *reinterpret_cast<half8_t*>(a.Y + row * a.ldy + f0) = h;
+  half_t* y = a.Y + row * a.ldy + f0;
+  if (f0 + 8 <= a.F) {
+    *reinterpret_cast<half8_t*>(y) = h;
+  } else {  // F is not a multiple of 8: the last lane of a row owns fewer than 8 features
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (f0 + i < a.F) y[i] = h[i];
+  }
 }
 
 __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x) {
@@ -86,10 +93,11 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const half8_t& x)
 }
 
 // p[0..7] += v with four packed fp16 atomic adds (the conflict-write scheme the paper removes, section 5.2.3)
-__device__ __forceinline__ void atomic_add8(half_t* p, const float (&v)[8]) {
+__device__ __forceinline__ void atomic_add8(half_t* p, const float (&v)[8], int nvalid) {
   typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
+    if (2 * q >= nvalid) break;  // F is even, so a pair is valid as a whole
     half2_t h;
     h[0] = half_t(v[2 * q]);
     h[1] = half_t(v[2 * q + 1]);
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
   if (has_row && end_g - beg_g <= kShortRow) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     edges_accumulate<1, HAS_W, 4>(a, beg_g, end_g, f0c, head, acc);
-    if (active) store8(a.Y + rg * a.ldy + f0, acc, scale_of(a, int(rg)));
+    if (active) store_row(a, rg, f0, acc, scale_of(a, int(rg)));
   }
   // the wave's mid-length rows, one after the other
   for (int j = 0; j < rw; ++j) {
@@ -186,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     edges_accumulate<G, HAS_W, 4>(a, beg + g, end, f0c, head, acc);
     groups_reduce<L>(acc);
-    if (g == 0 && active) store8(a.Y + (r0 + j) * a.ldy + f0, acc, scale_of(a, int(r0 + j)));
+    if (g == 0 && active) store_row(a, r0 + j, f0, acc, scale_of(a, int(r0 + j)));
   }
 }
 
@@ -205,7 +213,7 @@ struct HubLists {
   int* chunk_no;   // [max_chunks] its number within the hub
   int* hub_row;    // [max_hubs]
   int* hub_base;   // [max_hubs] first chunk slot of the hub
-  float* part;     // [max_chunks][F]
+  float* part;     // [max_chunks][F rounded up to a multiple of 8]
   int max_chunks, max_hubs;
 };
 
@@ -257,7 +265,7 @@ __global__ __launch_bounds__(kBlock) void spmm_hub_kernel(SpmmArgs a, HubLists h
   }
   __syncthreads();
   if (wave == 0 && g == 0 && active) {
-    float* out = h.part + int64_t(blockIdx.x) * a.F + f0;
+    float* out = h.part + int64_t(blockIdx.x) * ((a.F + 7) & ~7) + f0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float t = s_part[0][f0 + i];
@@ -282,16 +290,17 @@ __global__ __launch_bounds__(kBlock) void spmm_hub_sum_kernel(SpmmArgs a, HubLis
   const int f0c = active ? f0 : 0;
   const int row = h.hub_row[i];
   const int nch = (a.rowptr[row + 1] - a.rowptr[row] + kHubChunk - 1) / kHubChunk;
-  const float* part = h.part + int64_t(h.hub_base[i]) * a.F + f0c;
+  const int pitch = (a.F + 7) & ~7;
+  const float* part = h.part + int64_t(h.hub_base[i]) * pitch + f0c;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int c = g; c < nch; c += G) {
-    const float4 lo = *reinterpret_cast<const float4*>(part + int64_t(c) * a.F);
-    const float4 hi = *reinterpret_cast<const float4*>(part + int64_t(c) * a.F + 4);
+    const float4 lo = *reinterpret_cast<const float4*>(part + int64_t(c) * pitch);
+    const float4 hi = *reinterpret_cast<const float4*>(part + int64_t(c) * pitch + 4);
     acc[0] += lo.x, acc[1] += lo.y, acc[2] += lo.z, acc[3] += lo.w;
     acc[4] += hi.x, acc[5] += hi.y, acc[6] += hi.z, acc[7] += hi.w;
   }
   groups_reduce<L>(acc);
-  if (g == 0 && active) store8(a.Y + int64_t(row) * a.ldy + f0, acc, scale_of(a, row));
+  if (g == 0 && active) store_row(a, row, f0, acc, scale_of(a, row));
 }
 
 // Scalar path for shapes the 16-byte path cannot take: one thread per (row, feature).
@@ -536,7 +545,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
         if (!(fl & 2)) {  // the row ends inside chunk gg
           if (active) {
             if (!from_before) store_row(a, run_row, f0, run, 1.f);
-            else if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run);
+            else if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run, a.F - f0);
             else store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
           }
 #pragma unroll
@@ -557,7 +566,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
       }
     }
     if (open && active) {  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
-      if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run);
+      if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run, a.F - f0);
       else store8(a.staging + (2 * seg + (from_before ? 0 : 1)) * a.stage_ld + f0, run, 1.f);
     }
   }
@@ -816,7 +825,10 @@ __global__ __launch_bounds__(kBlock) void zero_split_rows_kernel(SpmmArgs a) {
   const int g = lane / L, l = lane % L;
   const int64_t idx = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
   if (idx >= a.n_split || 8 * l >= a.F) return;
-  *reinterpret_cast<half8_t*>(a.Y + int64_t(a.split_row[idx]) * a.ldy + 8 * l) = half8_t(0);
+  const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  SpmmArgs b = a;
+  b.self = nullptr;
+  store_row(b, a.split_row[idx], 8 * l, zero, 0.f);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -838,7 +850,9 @@ static hgnn_status check_spmm_args(const char* who, const hgnn_csr* g, const hgn
 
 static bool vector_path_ok(const hgnn_half* w, int H, const hgnn_half* X, int64_t ldx, const hgnn_half* Y, int64_t ldy,
                            int F) {
-  if (F % 8 != 0 || F > 512 || ldx % 8 != 0 || ldy % 8 != 0) return false;
+  // F itself need not be a multiple of 8: rows are read in 16-byte pieces up to the padded pitch and the
+  // last piece is stored by element
+  if (F > 512 || ldx % 8 != 0 || ldy % 8 != 0) return false;
   if (!aligned16(X) || !aligned16(Y)) return false;
   if (w && H > 1 && (F / H) % 8 != 0) return false;
   return true;
@@ -932,7 +946,7 @@ static hgnn_status hub_lists_alloc(int64_t nnz, int F, hipStream_t s, HubLists* 
   const int64_t o_hrow = o_cno + up(max_chunks * 4);
   const int64_t o_hbase = o_hrow + up(max_hubs * 4);
   const int64_t o_part = o_hbase + up(max_hubs * 4);
-  const int64_t bytes = o_part + up(max_chunks * int64_t(F) * 4);
+  const int64_t bytes = o_part + up(max_chunks * int64_t((F + 7) & ~7) * 4);
   hipMemPool_t pool = nullptr;
   hgnn_status st = scratch_pool(&pool);
   if (st != HGNN_OK) return st;
@@ -1012,7 +1026,7 @@ static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStr
   v.pair_loads = (a.w && a.H == 1 && !a.eid && (reinterpret_cast<uintptr_t>(a.w) & 3u) == 0) ? 1 : 0;
   a.staging = reinterpret_cast<half_t*>(p->gstage);
   a.stage_ld = p->max_F;
-  const int L = pow2_at_least(a.F / 8);
+  const int L = pow2_at_least((a.F + 7) / 8);
   const int G = kWave / L;
   const size_t lds = size_t(vgroup_lds_bytes(v.ng, a.H, a.w != nullptr)) * kWavesPerBlock;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
@@ -1048,7 +1062,7 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
   a.split_lo = q->split_seg_lo;
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
-  const int L = pow2_at_least(a.F / 8);
+  const int L = pow2_at_least((a.F + 7) / 8);
   const SegLds lay = seg_lds_layout(a.S, a.H, wm, L);
   const size_t lds = size_t(lay.total) * kWavesPerBlock;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
@@ -1129,7 +1143,7 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
   if (vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
-    const int L = pow2_at_least(F / 8);
+    const int L = pow2_at_least((F + 7) / 8);
     // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
     a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
     dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock * a.rows_per_wave)));
@@ -1167,7 +1181,7 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
                "%s: the plan was built for another graph", who);
   HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "%s: F = %d exceeds the plan's max_F = %d", who, F, p->max_F);
   HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
-               "%s: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y", who);
+               "%s: needs F <= 512, ld %% 8 == 0, 16-byte aligned X, Y, and D %% 8 == 0 when edge values have several heads", who);
   if (fz && fz->self)
     HGNN_REQUIRE(fz->ld_self >= F && fz->ld_self % 8 == 0 && aligned16(fz->self), HGNN_EINVAL,
                  "%s: self features need ld_self >= F, ld_self %% 8 == 0 and a 16-byte aligned base", who);
@@ -1203,7 +1217,7 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
     st = run_segments(q, ab, g->ncols, s);
     if (st != HGNN_OK) return st;
   }
-  const int L = pow2_at_least(F / 8);
+  const int L = pow2_at_least((F + 7) / 8);
   const int G = kWave / L;
   launch_block_sum(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, a,
                    reinterpret_cast<const half_t*>(p->bstage), p->nb, p->max_F);
@@ -1234,7 +1248,7 @@ hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g,
                "%s: the plan was built for another graph", who);
   HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "%s: F = %d exceeds the plan's max_F = %d", who, F, p->max_F);
   HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
-               "%s: needs F %% 8 == 0, F <= 512, D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned X, Y", who);
+               "%s: needs F <= 512, ld %% 8 == 0, 16-byte aligned X, Y, and D %% 8 == 0 when edge values have several heads", who);
   HGNN_REQUIRE(variant != HGNN_VERTEX_GROUPS || p->ng > 0, HGNN_EINVAL,
                "%s: the plan holds no neighbour groups (hgnn_plan_add_groups)", who);
   if (g->nrows == 0) return HGNN_OK;

@@ -174,3 +174,66 @@ def test_variant_argument_errors(hgnn, dev):
             hgnn.hgnn_plan_add_groups(p, g, bad)
         assert ei.value.status == hgnn.HGNN_EINVAL
     hgnn.hgnn_plan_destroy(p)
+
+
+# ------------------------------------------------------------------ feature lengths that are not multiples of 8
+@pytest.mark.parametrize("F", [2, 6, 8, 14, 42, 48, 130])
+def test_padded_feature_lengths(hgnn, dev, F):
+    """Class counts such as 7, 41, 47 (Table 1) padded to the next even number: rows keep a pitch that is a
+    multiple of 8 halves, the padding columns hold NaN on input and must come back untouched on output."""
+    print(f"padded F={F}", flush=True)
+    V, ncols = 700, 640
+    pitch = (F + 7) // 8 * 8 + 8
+    rowptr, col = rand_graph(V, ncols, 9, F, hubs=((5, 3000), (300, 400)), empties=(0, 6, 699))
+    E = col.size
+    r = np.random.default_rng(F)
+    Xh = np.full((ncols, pitch), np.nan, dtype=np.float16)
+    Xh[:, :F] = f16(r.standard_normal((ncols, F)))
+    Uh = np.full((V, pitch), np.nan, dtype=np.float16)
+    Uh[:, :F] = f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, 1)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    Xd, Ud, wd = up(Xh, dev), up(Uh, dev), up(w, dev)
+    ref, sabs = oracle.spmm(rowptr, col, Xh[:, :F], w=w, reduce=oracle.MEAN, want_sabs=True)
+    Yfull = torch.full((V, pitch), 7.0, dtype=torch.float16, device=dev)
+    Y = Yfull[:, :F]
+
+    def check(name):
+        got = down(Yfull)
+        compare(name, got[:, :F], ref, sabs)
+        assert np.all(got[:, F:] == 7.0), f"{name}: padding columns written"
+        Yfull.fill_(7.0)
+
+    hgnn.hgnn_spmm(g, wd, 1, Xd[:, :F], Y, op=hgnn.HGNN_MEAN)
+    check("plain")
+    for nb in (1, 3):
+        p = hgnn.hgnn_plan_create(g, 64, pitch, 1, col_blocks=nb)
+        hgnn.hgnn_spmm_discretized(p, g, wd, 1, Xd[:, :F], Y, op=hgnn.HGNN_MEAN)
+        check(f"discretized nb={nb}")
+        if nb == 1:
+            hgnn.hgnn_spmm_discretized_variant(p, g, wd, 1, Xd[:, :F], Y, hgnn.HGNN_EDGE_SEGMENTS_ATOMIC, op=hgnn.HGNN_MEAN)
+            pieces = np.maximum((rowptr[1:] - 1) // 64 - rowptr[:-1] // 64, 0)[:, None]
+            got = down(Yfull)
+            compare("atomic", got[:, :F], ref, sabs * (1 + pieces))
+            assert np.all(got[:, F:] == 7.0)
+            Yfull.fill_(7.0)
+            hgnn.hgnn_plan_add_groups(p, g, 64)
+            hgnn.hgnn_spmm_discretized_variant(p, g, wd, 1, Xd[:, :F], Y, hgnn.HGNN_VERTEX_GROUPS, op=hgnn.HGNN_MEAN)
+            check("vertex groups")
+        # GIN epilogue with the self term read from a padded table
+        gin_ref, gin_sabs = oracle.spmm(rowptr, col, Xh[:ncols, :F], w=w, reduce=oracle.MEAN, self_feat=Uh[:, :F],
+                                        self_coef=1.25, agg_coef=0.1, want_sabs=True)
+        hgnn.hgnn_spmm_discretized_fused(p, g, wd, 1, Xd[:, :F], Y, op=hgnn.HGNN_MEAN, self_feat=Ud[:, :F], self_coef=1.25,
+                                         agg_coef=0.1)
+        got = down(Yfull)
+        compare(f"gin epilogue nb={nb}", got[:, :F], gin_ref, gin_sabs)
+        assert np.all(got[:, F:] == 7.0)
+        Yfull.fill_(7.0)
+        # SDDMM dot, one head of length F
+        e = torch.full((E, 1), 3.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, 1, F, Ud[:, :F], Xd[:, :F], e)
+        row = np.repeat(np.arange(V), np.diff(rowptr))
+        dref = oracle.sddmm_dot(rowptr, col, Uh[:, :F], Xh[:, :F], H=1)
+        dabs = np.einsum("ef,ef->e", np.abs(Uh[row, :F].astype(np.float64)), np.abs(Xh[col, :F].astype(np.float64)))[:, None]
+        compare(f"sddmm dot nb={nb}", down(e), dref, dabs)
+        hgnn.hgnn_plan_destroy(p)
