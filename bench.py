@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--seg-edges", type=int, default=256)
     ap.add_argument("--col-blocks", type=int, default=0, help="column blocks of the SpMM plans: 0 = automatic, 1 = none")
+    ap.add_argument("--width-sweep", action="store_true",
+                    help="also time SDDMM dot and the vertex-group SpMM at 2, 4 and 8 halves per lane for "
+                         "F in {16, 32, 64, 128} on this workload's graph; reported under 'width_sweep'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print a per-op table to stderr")
     ap.add_argument("--variants", action="store_true",
@@ -269,6 +272,39 @@ def main():
             variants[k]["req_GBps"] = round(spmm_req(wH, False) / (variants[k]["ms"] * 1e-3) / 1e9, 1)
         hgnn.hgnn_plan_destroy(plan1)
 
+    width_sweep = None
+    if args.width_sweep:
+        # the half2-against-half8 study of the paper's micro-benchmarks, on this GPU: same kernels, 4 / 8 / 16 bytes per lane
+        width_sweep = {}
+        plan1 = hgnn.hgnn_plan_create(g, args.seg_edges, 128, 1, col_blocks=1)
+        hgnn.hgnn_plan_add_groups(plan1, g, 256)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(0x48474E4E)
+        e1 = torch.empty((E, 1), dtype=half, device=dev)
+
+        def time_call(fn):
+            for _ in range(max(args.warmup, 1)):
+                fn()
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for a, b in pairs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            return round(float(np.mean([a.elapsed_time(b) for a, b in pairs])), 4)
+
+        for Fs in (16, 32, 64, 128):
+            Xs = torch.randn((V, Fs), generator=gen, device=dev, dtype=torch.float32).to(half)
+            Ys = torch.empty_like(Xs)
+            for vw in (2, 4, 8):
+                hgnn.hgnn_set_vector_halves(vw)
+                width_sweep[f"F{Fs}_halves{vw}"] = {
+                    "sddmm_dot_ms": time_call(lambda: hgnn.hgnn_sddmm(g, plan1, hgnn.HGNN_SDDMM_DOT, 1, Fs, Xs, Xs, e1)),
+                    "spmm_vertex_groups_ms": time_call(lambda: hgnn.hgnn_spmm_discretized_variant(
+                        plan1, g, None, 1, Xs, Ys, hgnn.HGNN_VERTEX_GROUPS))}
+        hgnn.hgnn_set_vector_halves(8)
+        hgnn.hgnn_plan_destroy(plan1)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -296,13 +332,17 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "variants": variants,
+        "layers": layer_ms, "ops": detail, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        if width_sweep:
+            for k, v in width_sweep.items():
+                print(f"width {k:18s} sddmm_dot {v['sddmm_dot_ms']:9.4f} ms   spmm_vertex_groups {v['spmm_vertex_groups_ms']:9.4f} ms",
+                      file=sys.stderr)
         if variants:
             for k, v in variants.items():
                 print(f"variant {k:24s} {v['ms']:9.4f} ms  req {v['req_GBps']:8.1f} GB/s", file=sys.stderr)

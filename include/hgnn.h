@@ -221,6 +221,17 @@ int32_t hgnn_plan_group_edges(const hgnn_plan* p);
  * group j, group_first[j] = CSR position of its first non-zero.  Synchronizes the device. */
 hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32_t* group_row, int32_t* group_first);
 
+/* Vector-width study (sections 5.1.2-5.1.3 and 6.3.1: half2 against half8): halves that a lane
+ * moves per feature load, 8 (16 bytes, the default and the library's design), 4 or 2.  A
+ * process-wide setting read at launch time by the two kernels that exist in all three widths:
+ * the SDDMM DOT over a plan (hgnn_sddmm) and the main kernel of HGNN_VERTEX_GROUPS.  A narrower
+ * width uses more lanes per feature row (F <= 64 * halves, D % halves == 0, feature table
+ * below 4 GiB for the SpMM; otherwise HGNN_EUNSUPPORTED).  Every other kernel ignores it.
+ * Results are the same up to the order of the fp32 additions.  Not synchronized with calls
+ * in flight on other threads. */
+hgnn_status hgnn_set_vector_halves(int32_t halves);
+int32_t hgnn_get_vector_halves(void);
+
 /* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s

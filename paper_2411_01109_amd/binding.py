@@ -24,7 +24,8 @@ EXPORTS = (
     "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
-    "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export",
+    "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
+    "hgnn_get_vector_halves",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -95,6 +96,9 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_group_edges.restype = i32
     lib.hgnn_plan_group_edges.argtypes = [vp]
     lib.hgnn_plan_groups_export.argtypes = [vp, csr, vp, vp]
+    lib.hgnn_set_vector_halves.argtypes = [i32]
+    lib.hgnn_get_vector_halves.restype = i32
+    lib.hgnn_get_vector_halves.argtypes = []
     for name in EXPORTS:
         getattr(lib, name)  # every declared entry point must be exported
     _lib = lib
@@ -289,6 +293,14 @@ def hgnn_plan_groups_export(p: Plan, g: Csr):
     row, first = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
     _check(load().hgnn_plan_groups_export(p.handle, g.ref, row.ctypes.data, first.ctypes.data))
     return row[:n], first[:n]
+
+
+def hgnn_set_vector_halves(halves: int) -> None:
+    _check(load().hgnn_set_vector_halves(halves))
+
+
+def hgnn_get_vector_halves() -> int:
+    return load().hgnn_get_vector_halves()
 
 
 def hgnn_sddmm(g: Csr, p: Optional[Plan], op: int, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,

@@ -158,6 +158,7 @@ struct hgnn_plan {
 };
 
 namespace hgnn {
+int vector_halves();  // process-wide setting of hgnn_set_vector_halves: 8 (default), 4 or 2
 hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
 hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);
 }  // namespace hgnn

@@ -6,6 +6,8 @@
 
 #include "common.h"
 
+#include <atomic>
+
 namespace hgnn {
 
 static thread_local char g_err[512] = "";
@@ -18,6 +20,9 @@ hgnn_status fail(hgnn_status s, const char* fmt, ...) {
   return s;
 }
 void clear_error() { g_err[0] = 0; }
+
+static std::atomic<int> g_vector_halves{8};
+int vector_halves() { return g_vector_halves.load(std::memory_order_relaxed); }
 
 hgnn_status check_csr_args(const hgnn_csr* g, const char* who) {
   HGNN_REQUIRE(g != nullptr, HGNN_EINVAL, "%s: graph is NULL", who);
@@ -244,6 +249,15 @@ const char* hgnn_status_str(hgnn_status s) {
 }
 
 const char* hgnn_last_error(void) { return g_err; }
+
+hgnn_status hgnn_set_vector_halves(int32_t halves) {
+  clear_error();
+  HGNN_REQUIRE(halves == 2 || halves == 4 || halves == 8, HGNN_EINVAL, "hgnn_set_vector_halves: %d is not 2, 4 or 8", halves);
+  g_vector_halves.store(halves, std::memory_order_relaxed);
+  return HGNN_OK;
+}
+
+int32_t hgnn_get_vector_halves(void) { return vector_halves(); }
 
 hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream) {
   clear_error();

@@ -59,27 +59,36 @@ __host__ __device__ inline SddmmLds sddmm_lds_layout(int S, int H) {
 // DOT over one plan segment per wave:  out[k,h] = <U[row k, h], Vt[col k, h]>
 // MASK: one head whose length is not a multiple of 8 -- the group's lanes cover the padded row pitch and
 // the elements past D are forced to zero on both operands (whatever the padding columns hold).
-template <int L, bool MASK>
+// VW = halves per lane and load: 8 (16 bytes), or 4 / 2 for the vector-width study of section 6.3.1 (a head
+// then spans D/VW lanes and the reduction across lanes has more rounds).
+template <int L, int VW, bool MASK>
 __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   constexpr int G = kWave / L;
+  typedef _Float16 hv_t __attribute__((ext_vector_type(VW)));
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
-  const int f0 = 8 * l;
+  const int f0 = VW * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  const int LH = MASK ? L : a.D / 8;  // lanes per head (power of two)
+  const int LH = MASK ? L : a.D / VW;  // lanes per head (power of two)
   const int head = f0c / a.D;
   const int nvalid = active ? a.F - f0 : 0;  // MASK: elements of this lane's vector that exist
   const bool writer = MASK || active;         // MASK: every lane of the group may end up holding a result
-  auto load8 = [&](const half_t* p) -> half8_t {
-    half8_t v = *reinterpret_cast<const half8_t*>(p);
-    if (MASK && nvalid < 8) {
+  auto load8 = [&](const half_t* p) -> hv_t {
+    hv_t v = *reinterpret_cast<const hv_t*>(p);
+    if (MASK && nvalid < VW) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < VW; ++i)
         if (i >= nvalid) v[i] = half_t(0);
     }
     return v;
+  };
+  auto dot = [&](const hv_t& x, const hv_t& y) -> float {
+    float p = 0.f;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) p = fmaf(float(x[i]), float(y[i]), p);
+    return p;
   };
   const int lh = l % LH;
   const int S = a.S;
@@ -102,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   const int c0 = g * C < n ? g * C : n;
   const int c1 = c0 + C < n ? c0 + C : n;
   int cur = -1;
-  half8_t u = half8_t(0);
+  hv_t u = hv_t(0);
   if (c0 < c1) {
     cur = s_row[c0];
     u = load8(a.U + int64_t(cur) * a.ldu + f0c);
@@ -110,13 +119,13 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   for (int i = c0; i < c1; i += 4) {
     const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
     const int blk = s_blk[i >> 2];
-    half8_t v[4];
+    hv_t v[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) v[q] = load8(a.Vt + int64_t(cols[q]) * a.ldv + f0c);
     float p[4];
     if (blk == cur) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) p[q] = dot8(u, v[q]);
+      for (int q = 0; q < 4; ++q) p[q] = dot(u, v[q]);
     } else {
       const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
 #pragma unroll
@@ -127,7 +136,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
             cur = rows[q];
             u = load8(a.U + int64_t(cur) * a.ldu + f0c);
           }
-          p[q] = dot8(u, v[q]);
+          p[q] = dot(u, v[q]);
         }
       }
     }
@@ -349,11 +358,12 @@ static void launch_edge(int L, dim3 grid, size_t lds, hipStream_t s, const Sddmm
   }
 }
 
-static void launch_seg(int L, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
-#define LAUNCH_SEG(LL)                                                    \
-  do {                                                                   \
-    if (mask) sddmm_seg_kernel<LL, true><<<grid, kBlock, lds, s>>>(a);   \
-    else sddmm_seg_kernel<LL, false><<<grid, kBlock, lds, s>>>(a);       \
+template <int VW>
+static void launch_seg_vw(int L, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+#define LAUNCH_SEG(LL)                                                                   \
+  do {                                                                                  \
+    if (mask && VW == 8) sddmm_seg_kernel<LL, 8, true><<<grid, kBlock, lds, s>>>(a);    \
+    else sddmm_seg_kernel<LL, VW, false><<<grid, kBlock, lds, s>>>(a);                  \
   } while (0)
   switch (L) {
     case 1: LAUNCH_SEG(1); break;
@@ -364,6 +374,13 @@ static void launch_seg(int L, bool mask, dim3 grid, size_t lds, hipStream_t s, c
     case 32: LAUNCH_SEG(32); break;
     default: LAUNCH_SEG(64); break;
   }
+#undef LAUNCH_SEG
+}
+
+static void launch_seg(int L, int vw, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+  if (vw == 8) launch_seg_vw<8>(L, mask, grid, lds, s, a);
+  else if (vw == 4) launch_seg_vw<4>(L, false, grid, lds, s, a);
+  else launch_seg_vw<2>(L, false, grid, lds, s, a);
 }
 
 static void launch_proj(int L, dim3 grid, hipStream_t s, const half_t* feat, int64_t ld, int nv, const half_t* avec, int F,
@@ -463,6 +480,15 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     return HGNN_OK;
   }
   if ((vec || masked) && !score && p) {
+    // halves per lane: the process-wide setting, when the shape allows a narrower load than 16 bytes
+    int vw = vector_halves();
+    int Ls = L;
+    if (vw != 8) {
+      const int lh = D / vw;
+      HGNN_REQUIRE(vec && F <= kWave * vw && D % vw == 0 && (lh & (lh - 1)) == 0, HGNN_EUNSUPPORTED,
+                   "hgnn_sddmm: %d halves per lane needs F <= %d and D / %d a power of two", vw, kWave * vw, vw);
+      Ls = pow2_at_least(F / vw);
+    }
     const size_t lds = size_t(sddmm_lds_layout(a.S, H).total) * kWavesPerBlock;
     if (lds <= 65536 && p->nb > 1) {
       // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
@@ -477,13 +503,13 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
         ab.seg_hi = q->seg_row_hi;
         ab.nseg = q->nseg;
         ab.nnz = q->nnz;
-        launch_seg(L, masked, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
+        launch_seg(Ls, vw, masked, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
         HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       }
       return HGNN_OK;
     }
     if (lds <= 65536) {
-      launch_seg(L, masked, dim3(unsigned(seg_blocks)), lds, s, a);
+      launch_seg(Ls, vw, masked, dim3(unsigned(seg_blocks)), lds, s, a);
       HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       return HGNN_OK;
     }

@@ -674,13 +674,16 @@ __host__ __device__ inline int vgroup_lds_bytes(int ng, int H, bool has_w) {
   return spad * 4 + (has_w ? align16i(spad * H * 2) : 0);
 }
 
-template <int L, bool HAS_W, bool OFF32>
+// VW = halves per lane and load: 8 (16 bytes), 4 or 2 -- the narrower forms exist for the vector-width
+// study (section 6.3.1 carried over to SpMM); a row of F halves then takes L = pow2 >= F/VW lanes.
+template <int L, int VW, bool HAS_W, bool OFF32>
 __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupArgs v) {
   constexpr int G = kWave / L;
+  typedef _Float16 hv_t __attribute__((ext_vector_type(VW)));
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
-  const int f0 = 8 * l;
+  const int f0 = VW * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
   const int head = f0c / a.D;
@@ -739,17 +742,19 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
   const int C = 4 * ((v.ng + 4 * G - 1) / (4 * G));
   const int c0 = g * C < n ? g * C : n;
   const int c1 = c0 + C < n ? c0 + C : n;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  auto gather = [&](int c) -> half8_t {
+  float acc[VW];
+#pragma unroll
+  for (int q = 0; q < VW; ++q) acc[q] = 0.f;
+  auto gather = [&](int c) -> hv_t {
     if (OFF32) {
       const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
-      return *reinterpret_cast<const half8_t*>(reinterpret_cast<const char*>(a.X) + boff);
+      return *reinterpret_cast<const hv_t*>(reinterpret_cast<const char*>(a.X) + boff);
     }
-    return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+    return *reinterpret_cast<const hv_t*>(a.X + int64_t(c) * a.ldx + f0c);
   };
   for (int i = c0; i < c1; i += 4) {
     const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
-    half8_t x[4];
+    hv_t x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);  // padding holds offset 0, a valid row
     float wv[4] = {a.one, a.one, a.one, a.one};
@@ -763,20 +768,32 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
         for (int u = 0; u < 4; ++u) wv[u] = float(s_w[(i + u) * a.H + head]);
       }
     }
-    if (i + 4 <= c1) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) fma8(acc, wv[u], x[u]);
-    } else {
+    for (int u = 0; u < 4; ++u) {
+      if (i + 4 <= c1 || i + u < c1) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (i + u < c1) fma8(acc, wv[u], x[u]);
+        for (int q = 0; q < VW; ++q) acc[q] = fmaf(wv[u], float(x[u][q]), acc[q]);
+      }
     }
   }
-  groups_reduce<L>(acc);
+#pragma unroll
+  for (int off = L; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int q = 0; q < VW; ++q) acc[q] += __shfl_xor(acc[q], off);
+  }
   if (valid && g == 0 && active) {
     const float sc = scale_of(a, row);
-    if (cnt == 1) store_row(a, row, f0, acc, sc);
-    else store8(a.staging + (int64_t(v.moff[row]) + idx) * a.stage_ld + f0, acc, sc);
+    hv_t h;
+#pragma unroll
+    for (int q = 0; q < VW; ++q) h[q] = half_t(acc[q] * sc);
+    half_t* dst = cnt == 1 ? a.Y + int64_t(row) * a.ldy + f0 : a.staging + (int64_t(v.moff[row]) + idx) * a.stage_ld + f0;
+    if (cnt != 1 || f0 + VW <= a.F) {  // staging rows are padded to a multiple of 8
+      *reinterpret_cast<hv_t*>(dst) = h;
+    } else {
+#pragma unroll
+      for (int q = 0; q < VW; ++q)
+        if (f0 + q < a.F) dst[q] = h[q];
+    }
   }
 }
 
@@ -1000,19 +1017,42 @@ static void launch_zero_split(int L, dim3 grid, hipStream_t s, const SpmmArgs& a
   }
 }
 
-template <int L>
-static void launch_vgroup_l(bool has_w, bool off32, dim3 grid, dim3 grid2, size_t lds, hipStream_t s, const SpmmArgs& a,
-                            const VGroupArgs& v) {
-  if (v.n_groups > 0) {
-    if (has_w) {
-      if (off32) spmm_vgroup_kernel<L, true, true><<<grid, kBlock, lds, s>>>(a, v);
-      else spmm_vgroup_kernel<L, true, false><<<grid, kBlock, lds, s>>>(a, v);
-    } else {
-      if (off32) spmm_vgroup_kernel<L, false, true><<<grid, kBlock, lds, s>>>(a, v);
-      else spmm_vgroup_kernel<L, false, false><<<grid, kBlock, lds, s>>>(a, v);
-    }
+template <int L, int VW>
+static void launch_vgroup_main(bool has_w, bool off32, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a,
+                               const VGroupArgs& v) {
+  if (has_w) {
+    if (off32) spmm_vgroup_kernel<L, VW, true, true><<<grid, kBlock, lds, s>>>(a, v);
+    else if (VW == 8) spmm_vgroup_kernel<L, 8, true, false><<<grid, kBlock, lds, s>>>(a, v);
+  } else {
+    if (off32) spmm_vgroup_kernel<L, VW, false, true><<<grid, kBlock, lds, s>>>(a, v);
+    else if (VW == 8) spmm_vgroup_kernel<L, 8, false, false><<<grid, kBlock, lds, s>>>(a, v);
   }
-  spmm_vgroup_finish_kernel<L><<<grid2, kBlock, 0, s>>>(a, v);
+}
+
+template <int VW>
+static void launch_vgroup_vw(int L, bool has_w, bool off32, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a,
+                             const VGroupArgs& v) {
+  switch (L) {
+    case 1: launch_vgroup_main<1, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 2: launch_vgroup_main<2, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 4: launch_vgroup_main<4, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 8: launch_vgroup_main<8, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 16: launch_vgroup_main<16, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 32: launch_vgroup_main<32, VW>(has_w, off32, grid, lds, s, a, v); break;
+    default: launch_vgroup_main<64, VW>(has_w, off32, grid, lds, s, a, v); break;
+  }
+}
+
+static void launch_vgroup_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs& a, const VGroupArgs& v) {
+  switch (L) {
+    case 1: spmm_vgroup_finish_kernel<1><<<grid, kBlock, 0, s>>>(a, v); break;
+    case 2: spmm_vgroup_finish_kernel<2><<<grid, kBlock, 0, s>>>(a, v); break;
+    case 4: spmm_vgroup_finish_kernel<4><<<grid, kBlock, 0, s>>>(a, v); break;
+    case 8: spmm_vgroup_finish_kernel<8><<<grid, kBlock, 0, s>>>(a, v); break;
+    case 16: spmm_vgroup_finish_kernel<16><<<grid, kBlock, 0, s>>>(a, v); break;
+    case 32: spmm_vgroup_finish_kernel<32><<<grid, kBlock, 0, s>>>(a, v); break;
+    default: spmm_vgroup_finish_kernel<64><<<grid, kBlock, 0, s>>>(a, v); break;
+  }
 }
 
 // The vertex-parallel variant for the graph in `a` with the neighbour groups of plan p.
@@ -1026,25 +1066,29 @@ static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStr
   v.pair_loads = (a.w && a.H == 1 && !a.eid && (reinterpret_cast<uintptr_t>(a.w) & 3u) == 0) ? 1 : 0;
   a.staging = reinterpret_cast<half_t*>(p->gstage);
   a.stage_ld = p->max_F;
-  const int L = pow2_at_least((a.F + 7) / 8);
-  const int G = kWave / L;
+  // halves per lane: 8 unless the process-wide setting asks for a narrower load and the shape allows it
+  int vw = vector_halves();
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  if (vw != 8) {
+    HGNN_REQUIRE(off32 && a.F <= kWave * vw && a.D % vw == 0, HGNN_EUNSUPPORTED,
+                 "hgnn_spmm_discretized_variant: %d halves per lane needs F <= %d, D %% %d == 0 and a feature table below 4 GiB",
+                 vw, kWave * vw, vw);
+  }
+  const int L = pow2_at_least((a.F + vw - 1) / vw);   // lanes per row in the main kernel
+  const int L8 = pow2_at_least((a.F + 7) / 8);        // the follow-up kernel always moves 16 bytes per lane
   const size_t lds = size_t(vgroup_lds_bytes(v.ng, a.H, a.w != nullptr)) * kWavesPerBlock;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_spmm_discretized_variant: group_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)",
                v.ng, a.H, lds);
-  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   dim3 grid(unsigned(ceil_div(v.n_groups > 0 ? v.n_groups : 1, kWavesPerBlock)));
-  dim3 grid2(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * G)));
+  dim3 grid2(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * (kWave / L8))));
   const bool has_w = a.w != nullptr;
-  switch (L) {
-    case 1: launch_vgroup_l<1>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    case 2: launch_vgroup_l<2>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    case 4: launch_vgroup_l<4>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    case 8: launch_vgroup_l<8>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    case 16: launch_vgroup_l<16>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    case 32: launch_vgroup_l<32>(has_w, off32, grid, grid2, lds, s, a, v); break;
-    default: launch_vgroup_l<64>(has_w, off32, grid, grid2, lds, s, a, v); break;
+  if (v.n_groups > 0) {
+    if (vw == 8) launch_vgroup_vw<8>(L, has_w, off32, grid, lds, s, a, v);
+    else if (vw == 4) launch_vgroup_vw<4>(L, has_w, off32, grid, lds, s, a, v);
+    else launch_vgroup_vw<2>(L, has_w, off32, grid, lds, s, a, v);
   }
+  launch_vgroup_finish(L8, grid2, s, a, v);
   HGNN_LAUNCH_CHECK("spmm_vgroup_kernel / spmm_vgroup_finish_kernel");
   return HGNN_OK;
 }

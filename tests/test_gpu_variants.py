@@ -237,3 +237,50 @@ def test_padded_feature_lengths(hgnn, dev, F):
         dabs = np.einsum("ef,ef->e", np.abs(Uh[row, :F].astype(np.float64)), np.abs(Xh[col, :F].astype(np.float64)))[:, None]
         compare(f"sddmm dot nb={nb}", down(e), dref, dabs)
         hgnn.hgnn_plan_destroy(p)
+
+
+# ------------------------------------------------------------------ vector-width study: 2, 4, 8 halves per lane
+@pytest.fixture
+def restore_width(hgnn):
+    yield
+    hgnn.hgnn_set_vector_halves(8)
+
+
+@pytest.mark.parametrize("F,H", [(16, 1), (32, 1), (64, 1), (128, 1), (64, 4), (128, 8), (256, 2)])
+def test_vector_width_variants(hgnn, dev, restore_width, F, H):
+    print(f"width F={F} H={H}", flush=True)
+    V, ncols = 900, 800
+    rowptr, col = rand_graph(V, ncols, 10, F + H, hubs=((5, 2500), (300, 300)), empties=(0, 899))
+    E = col.size
+    r = np.random.default_rng(F + H)
+    Xh, Uh = f16(r.standard_normal((ncols, F))), f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    Xd, Ud, wd = up(Xh, dev), up(Uh, dev), up(w, dev)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, want_sabs=True)
+    dref = oracle.sddmm_dot(rowptr, col, Uh, Xh, H=H)
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    D = F // H
+    dabs = (np.abs(Uh[row].astype(np.float64)) * np.abs(Xh[col].astype(np.float64))).reshape(E, H, D).sum(-1)
+    p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=1)
+    hgnn.hgnn_plan_add_groups(p, g, 64)
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    e = torch.empty((E, H), dtype=torch.float16, device=dev)
+    for vw in (2, 4, 8):
+        hgnn.hgnn_set_vector_halves(vw)
+        assert hgnn.hgnn_get_vector_halves() == vw
+        fits = F <= 64 * vw and D % vw == 0
+        if not fits:
+            with pytest.raises(hgnn.HgnnError) as ei:
+                hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, Xd, Y, hgnn.HGNN_VERTEX_GROUPS)
+            assert ei.value.status == hgnn.HGNN_EUNSUPPORTED
+            continue
+        Y.fill_(7.0)
+        hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, Xd, Y, hgnn.HGNN_VERTEX_GROUPS)
+        compare(f"vertex groups, {vw} halves per lane", down(Y), ref, sabs)
+        e.fill_(7.0)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, Ud, Xd, e)
+        compare(f"sddmm dot, {vw} halves per lane", down(e), dref, dabs)
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_set_vector_halves(3)
+    hgnn.hgnn_plan_destroy(p)
