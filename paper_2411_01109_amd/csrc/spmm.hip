@@ -221,20 +221,60 @@ __global__ __launch_bounds__(kBlock) void hub_zero_kernel(HubLists h) {
   if (threadIdx.x < 2) h.count[threadIdx.x] = 0;
 }
 
+constexpr int kScanRows = 16;  // rows per thread in hub_scan_kernel
+
+// A workgroup looks at kBlock * kScanRows rows, adds up what its hubs need in LDS and reserves it with one
+// pair of atomic adds (thousands of single adds on one address would take longer than the SpMM of a small graph).
 __global__ __launch_bounds__(kBlock) void hub_scan_kernel(SpmmArgs a, HubLists h) {
-  const int64_t r = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  if (r >= a.nrows) return;
-  const int deg = a.rowptr[r + 1] - a.rowptr[r];
-  if (deg <= kLongRow) return;
-  const int nch = (deg + kHubChunk - 1) / kHubChunk;
-  const int base = atomicAdd(&h.count[0], nch);
-  const int i = atomicAdd(&h.count[1], 1);
-  if (base + nch > h.max_chunks || i >= h.max_hubs) return;  // cannot happen for a valid rowptr
-  h.hub_row[i] = int(r);
-  h.hub_base[i] = base;
-  for (int c = 0; c < nch; ++c) {
-    h.chunk_row[base + c] = int(r);
-    h.chunk_no[base + c] = c;
+  __shared__ int s_chunks[kBlock], s_hubs[kBlock];
+  __shared__ int s_base[2];
+  const int64_t r0 = int64_t(blockIdx.x) * (kBlock * kScanRows);
+  int my_chunks = 0, my_hubs = 0;
+  for (int u = 0; u < kScanRows; ++u) {
+    const int64_t r = r0 + u * kBlock + threadIdx.x;
+    if (r >= a.nrows) break;
+    const int deg = a.rowptr[r + 1] - a.rowptr[r];
+    if (deg > kLongRow) {
+      my_chunks += (deg + kHubChunk - 1) / kHubChunk;
+      ++my_hubs;
+    }
+  }
+  s_chunks[threadIdx.x] = my_chunks;
+  s_hubs[threadIdx.x] = my_hubs;
+  __syncthreads();
+  // inclusive scan over the workgroup (Hillis-Steele; kBlock is small)
+  for (int off = 1; off < kBlock; off <<= 1) {
+    const int c = threadIdx.x >= off ? s_chunks[threadIdx.x - off] : 0;
+    const int n = threadIdx.x >= off ? s_hubs[threadIdx.x - off] : 0;
+    __syncthreads();
+    s_chunks[threadIdx.x] += c;
+    s_hubs[threadIdx.x] += n;
+    __syncthreads();
+  }
+  if (threadIdx.x == kBlock - 1) {
+    s_base[0] = s_chunks[kBlock - 1] > 0 ? atomicAdd(&h.count[0], s_chunks[kBlock - 1]) : 0;
+    s_base[1] = s_hubs[kBlock - 1] > 0 ? atomicAdd(&h.count[1], s_hubs[kBlock - 1]) : 0;
+  }
+  __syncthreads();
+  if (my_hubs == 0) return;
+  int base = s_base[0] + s_chunks[threadIdx.x] - my_chunks;
+  int i = s_base[1] + s_hubs[threadIdx.x] - my_hubs;
+  for (int u = 0; u < kScanRows; ++u) {
+    const int64_t r = r0 + u * kBlock + threadIdx.x;
+    if (r >= a.nrows) break;
+    const int deg = a.rowptr[r + 1] - a.rowptr[r];
+    if (deg <= kLongRow) continue;
+    const int nch = (deg + kHubChunk - 1) / kHubChunk;
+    if (base + nch <= h.max_chunks && i < h.max_hubs) {  // always true for a valid rowptr
+      h.hub_row[i] = int(r);
+      h.hub_base[i] = base;
+      for (int c = 0; c < nch; ++c) {
+        h.chunk_row[base + c] = int(r);
+        h.chunk_no[base + c] = c;
+      }
+    }
+    base += nch;
+    ++i;
   }
 }
 
@@ -1197,7 +1237,7 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
     if (st != HGNN_OK) return st;
     if (scratch) {
       hub_zero_kernel<<<1, kBlock, 0, s>>>(h);
-      hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock))), kBlock, 0, s>>>(a, h);
+      hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock * kScanRows))), kBlock, 0, s>>>(a, h);
     }
     if (edge_val) launch_row<true>(L, grid, s, a, scratch ? &h : nullptr);
     else launch_row<false>(L, grid, s, a, scratch ? &h : nullptr);
