@@ -169,6 +169,53 @@ void orc_gat_score(int32_t V, const int32_t* rowptr, const int32_t* col, int32_t
       }
 }
 
+/* ---- one GAT aggregation, forward, with nothing rounded in between (sections 2.1.1 and
+ * 3.1.2: score from both end points, Eq. 1 over the neighbourhood, then the weighted sum
+ * of the neighbours' features).  For row i and head h, over the non-zeros k of the row:
+ *   s_k   = a_l[h].U[i,h] + a_r[h].Vt[col k,h];   e_k = s_k > 0 ? s_k : slope*s_k
+ *   alpha_k = exp(e_k - m) / sum_k exp(e_k - m),   m = max_k e_k
+ *   out[i, h*D+d] = sum_k alpha_k * Vt[col k, h*D+d]
+ * lse[i,h] = m + log(sum_k exp(e_k - m)) (what a backward pass needs to rebuild alpha);
+ * sabs = sum_k alpha_k * |Vt| (magnitude for tolerances).  An empty row gives out = 0,
+ * lse = 0.  U is [V][ldu] (row side), Vt is [ncols][ldv] (column side). ---- */
+void orc_gat_forward(int32_t V, const int32_t* rowptr, const int32_t* col, int32_t H, int32_t D, const uint16_t* U,
+                     int64_t ldu, const uint16_t* Vt, int64_t ldv, const uint16_t* a_l, const uint16_t* a_r,
+                     double slope, double* out, double* lse, double* sabs) {
+  int32_t F = H * D;
+  for (int32_t i = 0; i < V; ++i) {
+    int32_t beg = rowptr[i], end = rowptr[i + 1];
+    double* e = (double*)malloc(sizeof(double) * (size_t)(end > beg ? end - beg : 1));
+    for (int32_t h = 0; h < H; ++h) {
+      double el = 0.0;
+      for (int32_t d = 0; d < D; ++d)
+        el += orc_half_to_double(a_l[h * D + d]) * orc_half_to_double(U[(int64_t)i * ldu + h * D + d]);
+      double m = -INFINITY;
+      for (int32_t k = beg; k < end; ++k) {
+        double s = el;
+        for (int32_t d = 0; d < D; ++d)
+          s += orc_half_to_double(a_r[h * D + d]) * orc_half_to_double(Vt[(int64_t)col[k] * ldv + h * D + d]);
+        e[k - beg] = s > 0.0 ? s : slope * s;
+        m = fmax(m, e[k - beg]);
+      }
+      double z = 0.0;
+      for (int32_t k = beg; k < end; ++k) z += exp(e[k - beg] - m);
+      for (int32_t d = 0; d < D; ++d) {
+        double acc = 0.0, sa = 0.0;
+        for (int32_t k = beg; k < end; ++k) {
+          double alpha = exp(e[k - beg] - m) / z;
+          double x = orc_half_to_double(Vt[(int64_t)col[k] * ldv + h * D + d]);
+          acc += alpha * x;
+          sa += alpha * fabs(x);
+        }
+        out[(int64_t)i * F + h * D + d] = acc;
+        if (sabs) sabs[(int64_t)i * F + h * D + d] = sa;
+      }
+      if (lse) lse[(int64_t)i * H + h] = end > beg ? m + log(z) : 0.0;
+    }
+    free(e);
+  }
+}
+
 /* ---- edge softmax, Eq. 1: m_i = max_j e_ij; e'_ij = exp(e_ij - m_i);
  * alpha_ij = e'_ij / sum_j e'_ij, over the neighbourhood (CSR row) of i, per head.
  * Input is fp64 (the caller decodes fp16 scores). ---- */

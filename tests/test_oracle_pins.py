@@ -442,6 +442,68 @@ def test_discretized_bounds_partials_where_naive_fp16_overflows():
     assert np.array_equal(oracle.spmm_naive_fp16(rowptr[:2], col, Xi).astype(np.float64), oracle.spmm(rowptr[:2], col, Xi))
 
 
+# ------------------------------------------------------------------ one GAT aggregation, unrounded chain
+def test_gat_forward_dense_bruteforce():
+    """Sections 2.1.1 / 3.1.2 and Eq. 1 with dense matrices: scores on a V x ncols grid, softmax over the
+    neighbours with multiplicity (A counts duplicate edges), then P @ Vt."""
+    V, ncols, H, D = 23, 19, 2, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, ncols, 0.4, 5, empty_rows=(3,), full_rows=(7,))
+    A = dense_from(rowptr, col, row, ncols)
+    U = rng.standard_normal((V, F)).astype(np.float16)
+    Vt = rng.standard_normal((ncols, F)).astype(np.float16)
+    a_l = (0.5 * rng.standard_normal(F)).astype(np.float16)
+    a_r = (0.5 * rng.standard_normal(F)).astype(np.float16)
+    out, lse, sabs = oracle.gat_forward(rowptr, col, U, Vt, a_l, a_r, H, slope=0.2)
+    U64, V64, al, ar = (x.astype(np.float64) for x in (U, Vt, a_l, a_r))
+    for h in range(H):
+        sl = slice(h * D, (h + 1) * D)
+        S = (U64[:, sl] @ al[sl])[:, None] + (V64[:, sl] @ ar[sl])[None, :]
+        S = np.where(S > 0, S, 0.2 * S)
+        W = A * np.exp(S)  # multiplicity times exp(score); small scores, no shift needed
+        Z = W.sum(1)
+        P = W / np.where(Z > 0, Z, 1.0)[:, None]
+        np.testing.assert_allclose(out[:, sl], P @ V64[:, sl], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sabs[:, sl], P @ np.abs(V64[:, sl]), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(lse[Z > 0, h], np.log(Z[Z > 0]), rtol=1e-12, atol=1e-13)
+    assert np.all(out[3] == 0) and np.all(lse[3] == 0)
+
+
+def test_gat_forward_special_cases():
+    V, ncols, H, D = 40, 40, 4, 2
+    F = H * D
+    rowptr, col, row = small_graph(V, ncols, 0.2, 9, empty_rows=(0,))
+    X = rng.standard_normal((V, F)).astype(np.float16)
+    zero = np.zeros(F, dtype=np.float16)
+    # zero attention vectors: every score is 0, alpha = 1/deg, the result is the mean aggregation
+    out, lse, _ = oracle.gat_forward(rowptr, col, X, X, zero, zero, H)
+    np.testing.assert_allclose(out, oracle.spmm(rowptr, col, X, reduce=oracle.MEAN), rtol=1e-12, atol=1e-14)
+    deg = np.diff(rowptr)
+    np.testing.assert_allclose(lse[deg > 0], np.log(deg[deg > 0])[:, None].repeat(H, 1), rtol=1e-12)
+    # the row-side term is constant over a row and cancels in Eq. 1: a_l does not change the weights where
+    # LeakyReLU is linear (all scores of one sign); with slope 1 it never does
+    a_l = rng.standard_normal(F).astype(np.float16)
+    a_r = rng.standard_normal(F).astype(np.float16)
+    o1, l1, _ = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H, slope=1.0)
+    o0, l0, _ = oracle.gat_forward(rowptr, col, X, X, zero, a_r, H, slope=1.0)
+    np.testing.assert_allclose(o1, o0, rtol=1e-10, atol=1e-12)
+    el = (X.astype(np.float64).reshape(V, H, D) * a_l.astype(np.float64).reshape(H, D)).sum(-1)
+    np.testing.assert_allclose((l1 - l0)[deg > 0], el[deg > 0], rtol=1e-10, atol=1e-12)
+    # it is the composition of the three separately pinned definitions (score, Eq. 1, weighted sum)
+    e = oracle.gat_score(rowptr, col, X, a_l, a_r, H, slope=0.2)
+    alpha = oracle.edge_softmax(rowptr, e)
+    o2, l2, _ = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H, slope=0.2)
+    ref = np.zeros((V, F))
+    X64 = X.astype(np.float64)
+    for k in range(col.size):
+        ref[row[k]] += np.repeat(alpha[k], D) * X64[col[k]]
+    np.testing.assert_allclose(o2, ref, rtol=1e-11, atol=1e-13)
+    # huge scores do not overflow (the shift by the row maximum of Eq. 1)
+    big = np.full(F, 60.0, dtype=np.float16)
+    o3, l3, _ = oracle.gat_forward(rowptr, col, np.abs(X) * 50, np.abs(X) * 50, big, big, H)
+    assert np.all(np.isfinite(o3)) and np.all(np.isfinite(l3)) and l3.max() > 1000
+
+
 # ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
 @pytest.mark.parametrize("ng", [1, 4, 32, 64])
 def test_neighbor_groups_bruteforce(ng):
