@@ -245,6 +245,30 @@ hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sddmm_op op, 
                        const hgnn_half* U, int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
                        const hgnn_half* a_r, float neg_slope, hgnn_half* out, void* stream);
 
+/* One GAT aggregation in a single pass over the graph (score, edge softmax of Eq. 1 and the
+ * weighted sum of section 2.1.1 fused; no |E| x H tensor is written):
+ *   e_k = LeakyReLU(a_l[h].U[i,h] + a_r[h].Vt[col k,h]),  alpha = softmax over row i,
+ *   out[i, h*D+d] = sum_k alpha_k * Vt[col k, h*D+d],      lse[i,h] = log sum_k exp(e_k).
+ * U [nrows][ldu] is the row side, Vt [ncols][ldv] the column side (the same table for a GAT
+ * layer), a_l / a_r are [H*D], out is [nrows][ldo], lse is fp32 [nrows][H] or NULL.  Empty
+ * rows give out = 0, lse = 0.  Walks the plan's segments (and column blocks); partial
+ * results of a row are merged by rescaling to the larger maximum, pieces that cross a segment
+ * border are staged as normalised fp16 vectors plus fp32 (max, sum) and merged by a follow-up
+ * kernel: no atomics, deterministic.  Needs a plan with max_H >= H and max_F >= H*D,
+ * D = 8 * 2^k, H*D <= 512, ld % 8 == 0 and 16-byte aligned tensors; g without edge-id map.
+ * Overwrites the plan's per-vertex scratch (as hgnn_sddmm GAT_SCORE does). */
+hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                   int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                   const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                   void* stream);
+
+/* Rebuilds alpha[k,h] = exp(e_k - lse[i,h]) (fp16 [nnz][H]) from the lse of
+ * hgnn_gat_forward_fused, for a backward pass that wants the attention weights as a tensor.
+ * Same requirements as above. */
+hgnn_status hgnn_gat_alpha(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U, int64_t ldu,
+                           const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, float neg_slope,
+                           const float* lse, hgnn_half* alpha, void* stream);
+
 /* Edge softmax, Eq. 1, over every row (neighbourhood) and head:
  *   m_i = max_k e[k,h];  alpha[k,h] = exp(e[k,h]-m_i) / sum_k exp(e[k,h]-m_i).
  * exp and the sums are fp32 in registers (the argument is <= 0, so the value is in

@@ -25,7 +25,7 @@ EXPORTS = (
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
-    "hgnn_get_vector_halves",
+    "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -97,6 +97,8 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_group_edges.argtypes = [vp]
     lib.hgnn_plan_groups_export.argtypes = [vp, csr, vp, vp]
     lib.hgnn_set_vector_halves.argtypes = [i32]
+    lib.hgnn_gat_forward_fused.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp]
+    lib.hgnn_gat_alpha.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp, vp]
     lib.hgnn_get_vector_halves.restype = i32
     lib.hgnn_get_vector_halves.argtypes = []
     for name in EXPORTS:
@@ -293,6 +295,21 @@ def hgnn_plan_groups_export(p: Plan, g: Csr):
     row, first = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
     _check(load().hgnn_plan_groups_export(p.handle, g.ref, row.ctypes.data, first.ctypes.data))
     return row[:n], first[:n]
+
+
+def hgnn_gat_forward_fused(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor, a_l: torch.Tensor,
+                           a_r: torch.Tensor, out: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                           neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_gat_forward_fused(g.ref, p.handle, H, D, _ptr(U, torch.float16), _ld(U), _ptr(Vt, torch.float16),
+                                         _ld(Vt), _ptr(a_l, torch.float16), _ptr(a_r, torch.float16), neg_slope,
+                                         _ptr(out, torch.float16), _ld(out), _ptr(lse, torch.float32), _stream(stream)))
+
+
+def hgnn_gat_alpha(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor, a_l: torch.Tensor,
+                   a_r: torch.Tensor, lse: torch.Tensor, alpha: torch.Tensor, neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_gat_alpha(g.ref, p.handle, H, D, _ptr(U, torch.float16), _ld(U), _ptr(Vt, torch.float16), _ld(Vt),
+                                 _ptr(a_l, torch.float16), _ptr(a_r, torch.float16), neg_slope, _ptr(lse, torch.float32),
+                                 _ptr(alpha, torch.float16), _stream(stream)))
 
 
 def hgnn_set_vector_halves(halves: int) -> None:

@@ -133,6 +133,7 @@ struct hgnn_plan {
   int32_t* split_seg_hi = nullptr;  // [n_split]
   int32_t* big_row = nullptr;       // [n_big]
   hgnn_half* staging = nullptr;     // [2*nseg][max_F]
+  float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32
   // column blocking of the SpMM (nb > 1): block b holds the non-zeros whose column lies in
   // [b*block_width, (b+1)*block_width), stored block after block as a CSR of their own
@@ -145,7 +146,7 @@ struct hgnn_plan {
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs
-  float* bsum = nullptr;            // [nb][nrows][max_H] per-block partial row sums of edge tensors
+  float* bsum = nullptr;            // [nb][nrows][max_H][2] per-block partial row sums of edge tensors / GAT (max, sum)
   // neighbour groups of the vertex-parallel variant (hgnn_plan_add_groups): row r owns the groups
   // goff[r] .. goff[r+1]-1, group j of the row covers the non-zeros rowptr[r] + j*ng ...
   int32_t ng = 0;                   // neighbours per group; 0 = not built
@@ -158,6 +159,10 @@ struct hgnn_plan {
 };
 
 namespace hgnn {
+// el[i,h] = a_l[h].U[i,h] and er[j,h] = a_r[h].Vt[j,h] into the plan's fp32 scratch (el first, then er)
+hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, const hgnn_half* U, int64_t ldu,
+                        const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, hipStream_t s,
+                        const char* who);
 int vector_halves();  // process-wide setting of hgnn_set_vector_halves: 8 (default), 4 or 2
 hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
 hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);

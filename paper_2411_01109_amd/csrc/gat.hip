@@ -1,0 +1,545 @@
+// Single-pass GAT aggregation for gfx950: score, edge softmax and weighted sum of the neighbours'
+// features in one read of the graph, with no per-edge tensor written (the paper, sections 3.1.2 and
+// 5.2, keeps them as three kernels with an |E| x H score tensor and an |E| x H alpha tensor between
+// them; this fuses them on top of the same discretized, atomic-free segment design).
+//
+//   s_k = el[i,h] + er[col k,h],  e_k = LeakyReLU(s_k),  alpha_k = softmax over row i (Eq. 1),
+//   out[i, h*D+d] = sum_k alpha_k * X[col k, h*D+d],    lse[i,h] = log sum_k exp(e_k)
+//
+// el / er are the per-vertex projections a_l.U[i,h], a_r.X[j,h] (fp32, formed once per vertex).
+// A partial result over any subset of a row's edges is kept as a triple (m, z, acc): m = largest
+// score met, z = sum exp(e - m), acc = sum exp(e - m) * x.  Two triples of the same row merge by
+// rescaling both to the larger m (the online form of Eq. 1's shift by the row maximum), so the
+// segment kernel can cut rows anywhere: lane groups carry a running triple along their chunk,
+// pieces that touch a chunk border meet in LDS, pieces that cross a segment border are staged as
+// (m, z) in fp32 plus the normalised vector acc/z in fp16 -- a convex combination of feature rows,
+// hence never larger than the features themselves (the discretized-scaling idea of section 5.2.2
+// applied to the softmax weights) -- and a follow-up kernel merges them.  No atomics, one writer per
+// output row, fixed merge order.
+#include "common.h"
+
+namespace hgnn {
+
+struct GatArgs {
+  const int* rowptr;
+  const int* col;
+  const half_t* X;  // column-side features [ncols][ldx]
+  half_t* Y;        // [nrows][ldy]: the result, or (part_mz set) this block's normalised partial rows
+  int64_t ldx, ldy, nnz;
+  int nrows, F, H, D;
+  float slope;
+  const float* el;  // [nrows][H]
+  const float* er;  // [ncols][H]
+  float* lse;       // [nrows][H] or nullptr
+  float* part_mz;   // column blocks: [nrows][H][2] (m, z) of this block's partial rows; else nullptr
+  int S;
+  int64_t nseg;
+  const int* seg_lo;
+  const int* seg_hi;
+  half_t* staging;  // [2*nseg][stage_ld] normalised vectors of the pieces that cross a segment border
+  float* stage_mz;  // [2*nseg][H][2]
+  int stage_ld;
+  const int* split_row;
+  const int* split_lo;
+  const int* split_hi;
+  int n_split;
+};
+
+// (m, z, acc) <- merge with (m2, z2, acc2)
+__device__ __forceinline__ void soft_merge(float& m, float& z, float (&acc)[8], float m2, float z2, const float (&acc2)[8]) {
+  const float M = fmaxf(m, m2);
+  if (M == -INFINITY) return;  // both empty
+  const float fa = __expf(m - M), fb = __expf(m2 - M);  // exp(-inf) = 0 drops an empty side
+  z = z * fa + z2 * fb;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = acc[i] * fa + acc2[i] * fb;
+  m = M;
+}
+
+// merge a staged piece: (mp, zp) and its normalised vector o = acc/z
+__device__ __forceinline__ void soft_merge_normalised(float& m, float& z, float (&acc)[8], float mp, float zp, const half8_t& o) {
+  const float M = fmaxf(m, mp);
+  if (M == -INFINITY) return;
+  const float fa = __expf(m - M), fb = __expf(mp - M) * zp;
+  z = z * fa + fb;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = acc[i] * fa + fb * float(o[i]);
+  m = M;
+}
+
+__device__ __forceinline__ void store_vec8(const GatArgs& a, half_t* p, int f0, const float (&v)[8], float s) {
+  half8_t h;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
+  *reinterpret_cast<half8_t*>(p + f0) = h;
+}
+
+// a finished row (or, with part_mz, a finished partial row of a column block)
+__device__ __forceinline__ void row_store(const GatArgs& a, int64_t row, int f0, int head, bool leader, float m, float z,
+                                          const float (&acc)[8]) {
+  const float inv = z > 0.f ? 1.f / z : 0.f;
+  store_vec8(a, a.Y + row * a.ldy, f0, acc, inv);
+  if (!leader) return;
+  if (a.part_mz) {
+    a.part_mz[(row * a.H + head) * 2] = m;
+    a.part_mz[(row * a.H + head) * 2 + 1] = z;
+  } else if (a.lse) {
+    a.lse[row * a.H + head] = z > 0.f ? m + __logf(z) : 0.f;
+  }
+}
+
+__device__ __forceinline__ void stage_store(const GatArgs& a, int64_t slot, int f0, int head, bool leader, float m, float z,
+                                            const float (&acc)[8]) {
+  store_vec8(a, a.staging + slot * a.stage_ld, f0, acc, z > 0.f ? 1.f / z : 0.f);
+  if (leader) {
+    a.stage_mz[(slot * a.H + head) * 2] = m;
+    a.stage_mz[(slot * a.H + head) * 2 + 1] = z;
+  }
+}
+
+struct GatLds {
+  int per, spad, col_off, row_off, blk_off, sc_off, vec_off, mz_off, flag_off, total;
+};
+__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L) {
+  GatLds o;
+  const int G = kWave / L;
+  o.per = 4 * ((S + 255) / 256);
+  o.spad = kWave * o.per;
+  o.col_off = 0;
+  o.row_off = o.col_off + o.spad * 4;
+  o.blk_off = o.row_off + o.spad * 4;
+  o.sc_off = o.blk_off + ((o.spad + 15) & ~15);
+  o.vec_off = o.sc_off + o.spad * H * 4;
+  o.mz_off = o.vec_off + 2 * G * 8 * L * 4;
+  o.flag_off = o.mz_off + 2 * G * L * 2 * 4;
+  o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
+  return o;
+}
+
+template <int L, bool OFF32>
+__global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
+  constexpr int G = kWave / L;
+  constexpr int VEC = 8 * L;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int head = f0c / a.D;
+  const bool leader = active && (f0 % a.D) == 0;  // the lane that writes its head's scalars
+  const int S = a.S;
+  const GatLds lay = gat_lds_layout(S, a.H, L);
+  unsigned char* base = smem + size_t(wave) * lay.total;
+  int* s_col = reinterpret_cast<int*>(base + lay.col_off);
+  int* s_row = reinterpret_cast<int*>(base + lay.row_off);
+  int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
+  float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
+  float* m_mz = reinterpret_cast<float*>(base + lay.mz_off);    // [2*G][L][2]: (m, z) of the parked pieces, per lane
+  int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
+  int* m_hrow = m_flag + G;
+  int* m_trow = m_hrow + G;
+
+  const int64_t wid = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int64_t seg = wid;
+  const bool valid = seg < a.nseg;
+  const int64_t e0 = seg * S;
+  const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+  const int per = lay.per, spad = lay.spad;
+  int row_lo = 0, row_hi = -1;
+  bool seg_left_open = false, seg_right_open = false;
+  if (valid) {
+    row_lo = a.seg_lo[seg];
+    row_hi = a.seg_hi[seg];
+    seg_left_open = int64_t(a.rowptr[row_lo]) < e0;
+    seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
+  }
+
+  // ---- phase 1: column ids, row ids, then the score of every (edge, head), once per wave
+  for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
+  if (lane < G) m_flag[lane] = 0;
+  seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
+  for (int i = lane; i < spad; i += kWave) {
+    const bool in = i < n;
+    const int c = s_col[i];
+    const int r = in ? s_row[i] : 0;
+    for (int h = 0; h < a.H; ++h) {
+      float s = -INFINITY;  // padding: weight exp(-inf - m) = 0
+      if (in) {
+        s = a.el[int64_t(r) * a.H + h] + a.er[int64_t(c) * a.H + h];
+        s = s > 0.f ? s : a.slope * s;
+      }
+      s_sc[i * a.H + h] = s;
+    }
+    if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);  // from here on: byte offset of the neighbour's row
+  }
+  __syncthreads();
+
+  // ---- phase 2: running (m, z, acc) over this group's chunk
+  const int C = 4 * ((S + 4 * G - 1) / (4 * G));
+  const int c0 = g * C < n ? g * C : n;
+  const int c1 = c0 + C < n ? c0 + C : n;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, z = 0.f;
+  int cur = -1;
+  bool lo = false;  // current piece began before this chunk
+
+  auto flush = [&](bool ro) {
+    if (!lo && !ro) {
+      if (active) row_store(a, cur, f0, head, leader, m, z, acc);
+    } else {
+      const int slot = lo ? 2 * g : 2 * g + 1;
+      if (active) {
+        float* dst = m_vec + slot * VEC + f0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = acc[i];
+      }
+      m_mz[(slot * L + l) * 2] = m;
+      m_mz[(slot * L + l) * 2 + 1] = z;
+      if (l == 0) {
+        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
+        if (lo) m_hrow[g] = cur;
+        else m_trow[g] = cur;
+      }
+    }
+  };
+  auto gather = [&](int c) -> half8_t {
+    if (OFF32) {
+      const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
+      return *reinterpret_cast<const half8_t*>(reinterpret_cast<const char*>(a.X) + boff);
+    }
+    return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+  };
+
+  if (c0 < c1) {
+    cur = s_row[c0];
+    lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
+  }
+  for (int i = c0; i < c1; i += 4) {
+    const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
+    const int blk = s_blk[i >> 2];
+    half8_t x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
+    float sc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
+    if (blk == cur) {  // four more edges of the current row: one rescale, four terms
+      const float mn = fmaxf(fmaxf(m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
+      const float f = __expf(m - mn);
+      z *= f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] *= f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float p = __expf(sc[u] - mn);
+        z += p;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = fmaf(p, float(x[u][q]), acc[q]);
+      }
+      m = mn;
+    } else {
+      const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i + u < c1) {
+          if (rows[u] != cur) {
+            flush(false);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+            m = -INFINITY;
+            z = 0.f;
+            cur = rows[u];
+            lo = false;
+          }
+          const float mn = fmaxf(m, sc[u]);
+          const float f = __expf(m - mn), p = __expf(sc[u] - mn);
+          z = z * f + p;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[q] = fmaf(p, float(x[u][q]), acc[q] * f);
+          m = mn;
+        }
+      }
+    }
+  }
+  if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
+  __syncthreads();
+
+  // ---- merge: group 0 sews the parked pieces together in chunk order
+  if (valid && g == 0) {
+    float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float rm = -INFINITY, rz = 0.f;
+    bool open = false, from_before = false;
+    int run_row = -1;
+    for (int gg = 0; gg < G; ++gg) {
+      const int fl = m_flag[gg];
+      if (fl & 1) {
+        float t[8];
+        const float* src = m_vec + (2 * gg) * VEC + f0c;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = src[i];
+        soft_merge(rm, rz, run, m_mz[((2 * gg) * L + l) * 2], m_mz[((2 * gg) * L + l) * 2 + 1], t);
+        if (gg == 0) {
+          from_before = true;
+          open = true;
+          run_row = m_hrow[0];
+        }
+        if (!(fl & 2)) {  // the row ends inside chunk gg
+          if (active) {
+            if (from_before) stage_store(a, 2 * seg, f0, head, leader, rm, rz, run);
+            else row_store(a, run_row, f0, head, leader, rm, rz, run);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] = 0.f;
+          rm = -INFINITY;
+          rz = 0.f;
+          open = false;
+          from_before = false;
+        }
+      }
+      if (fl & 4) {
+        const float* src = m_vec + (2 * gg + 1) * VEC + f0c;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) run[i] = src[i];
+        rm = m_mz[((2 * gg + 1) * L + l) * 2];
+        rz = m_mz[((2 * gg + 1) * L + l) * 2 + 1];
+        run_row = m_trow[gg];
+        open = true;
+        from_before = false;
+      }
+    }
+    if (open && active)  // leaves into the next segment; a piece that also entered uses slot 2*seg
+      stage_store(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, rm, rz, run);
+  }
+
+  // ---- this wave's share of the empty rows
+  const int64_t nw = int64_t(gridDim.x) * kWavesPerBlock;
+  const int rpw = int((a.nrows + nw - 1) / nw);
+  const int64_t r0 = wid * rpw;
+  const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
+  if (active) {
+    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int64_t r = r0 + g; r < r1; r += G)
+      if (a.rowptr[r] == a.rowptr[r + 1]) row_store(a, r, f0, head, leader, -INFINITY, 0.f, zero);
+  }
+}
+
+// Follow-up kernel: merges the staged pieces of every row that crosses a segment border (the tail
+// piece of its first segment, then the head pieces of the following ones) and stores the row.
+// A wave owns G split rows; rows of up to kShortPieces pieces are merged by their own lane group,
+// hubs by the whole wave with a final merge across the groups.
+constexpr int kShortPieces = 8;
+
+template <int L>
+__global__ __launch_bounds__(kBlock) void gat_finish_kernel(GatArgs a) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int head = f0c / a.D;
+  const bool leader = active && (f0 % a.D) == 0;
+  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  if (i0 >= a.n_split) return;
+  const int64_t idx = i0 + g;
+  int r = 0, sa = 0, sb = -1;
+  if (idx < a.n_split) {
+    r = a.split_row[idx];
+    sa = a.split_lo[idx];
+    sb = a.split_hi[idx];
+  }
+  auto take = [&](float& m, float& z, float (&acc)[8], int64_t slot) {
+    const half8_t o = *reinterpret_cast<const half8_t*>(a.staging + slot * a.stage_ld + f0c);
+    soft_merge_normalised(m, z, acc, a.stage_mz[(slot * a.H + head) * 2], a.stage_mz[(slot * a.H + head) * 2 + 1], o);
+  };
+  if (idx < a.n_split && sb - sa <= kShortPieces) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, z = 0.f;
+    take(m, z, acc, 2 * int64_t(sa) + 1);
+    for (int64_t k = int64_t(sa) + 1; k <= sb; ++k) take(m, z, acc, 2 * k);
+    if (active) row_store(a, r, f0, head, leader, m, z, acc);
+  }
+  for (int j = 0; j < G; ++j) {
+    const int rj = __shfl(r, j * L), sj = __shfl(sa, j * L), ej = __shfl(sb, j * L);
+    if (ej - sj <= kShortPieces) continue;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, z = 0.f;
+    if (g == 0) take(m, z, acc, 2 * int64_t(sj) + 1);
+    for (int64_t k = int64_t(sj) + 1 + g; k <= ej; k += G) take(m, z, acc, 2 * k);
+#pragma unroll
+    for (int off = L; off < kWave; off <<= 1) {
+      float t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = __shfl_xor(acc[i], off);
+      soft_merge(m, z, acc, __shfl_xor(m, off), __shfl_xor(z, off), t);
+    }
+    if (g == 0 && active) row_store(a, rj, f0, head, leader, m, z, acc);
+  }
+}
+
+// Column-blocked plans: merges the nb partial rows (normalised fp16 vector + (m, z)) of every row.
+template <int L>
+__global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, const half_t* __restrict__ part, int part_ld,
+                                                                 const float* __restrict__ part_mz, int64_t mz_stride, int nb) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const int64_t r = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  if (r >= a.nrows || f0 >= a.F) return;
+  const int head = f0 / a.D;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, z = 0.f;
+  for (int b = 0; b < nb; ++b) {
+    const int64_t pr = int64_t(b) * a.nrows + r;
+    const half8_t o = *reinterpret_cast<const half8_t*>(part + pr * part_ld + f0);
+    const float* mz = part_mz + b * mz_stride + (r * a.H + head) * 2;
+    soft_merge_normalised(m, z, acc, mz[0], mz[1], o);
+  }
+  row_store(a, r, f0, head, (f0 % a.D) == 0, m, z, acc);
+}
+
+template <bool OFF32>
+static void launch_gat_seg(int L, dim3 grid, size_t lds, hipStream_t s, const GatArgs& a) {
+  switch (L) {
+    case 1: gat_seg_kernel<1, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: gat_seg_kernel<2, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: gat_seg_kernel<4, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: gat_seg_kernel<8, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: gat_seg_kernel<16, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: gat_seg_kernel<32, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    default: gat_seg_kernel<64, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+  }
+}
+
+static void launch_gat_finish(int L, dim3 grid, hipStream_t s, const GatArgs& a) {
+  switch (L) {
+    case 1: gat_finish_kernel<1><<<grid, kBlock, 0, s>>>(a); break;
+    case 2: gat_finish_kernel<2><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: gat_finish_kernel<4><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: gat_finish_kernel<8><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: gat_finish_kernel<16><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: gat_finish_kernel<32><<<grid, kBlock, 0, s>>>(a); break;
+    default: gat_finish_kernel<64><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+static void launch_gat_block_merge(int L, dim3 grid, hipStream_t s, const GatArgs& a, const half_t* part, int part_ld,
+                                   const float* part_mz, int64_t mz_stride, int nb) {
+  switch (L) {
+    case 1: gat_block_merge_kernel<1><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 2: gat_block_merge_kernel<2><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 4: gat_block_merge_kernel<4><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 8: gat_block_merge_kernel<8><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 16: gat_block_merge_kernel<16><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 32: gat_block_merge_kernel<32><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    default: gat_block_merge_kernel<64><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+  }
+}
+
+// segment pass + follow-up pass for the graph in `a` with the segment arrays of plan q
+static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hipStream_t s) {
+  a.seg_lo = q->seg_row_lo;
+  a.seg_hi = q->seg_row_hi;
+  a.S = q->S;
+  a.nseg = q->nseg;
+  a.staging = reinterpret_cast<half_t*>(q->staging);
+  a.stage_mz = q->stage_mz;
+  a.stage_ld = q->max_F;
+  a.split_row = q->split_row;
+  a.split_lo = q->split_seg_lo;
+  a.split_hi = q->split_seg_hi;
+  a.n_split = q->n_split;
+  const int L = pow2_at_least(a.F / 8);
+  const size_t lds = size_t(gat_lds_layout(a.S, a.H, L).total) * kWavesPerBlock;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_gat_forward_fused: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
+               a.H, lds);
+  const int64_t nblk = ceil_div(q->nseg, kWavesPerBlock);
+  dim3 grid(unsigned(nblk > 0 ? nblk : 1));
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  if (off32) launch_gat_seg<true>(L, grid, lds, s, a);
+  else launch_gat_seg<false>(L, grid, lds, s, a);
+  HGNN_LAUNCH_CHECK("gat_seg_kernel");
+  if (a.n_split > 0) {
+    launch_gat_finish(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
+    HGNN_LAUNCH_CHECK("gat_finish_kernel");
+  }
+  return HGNN_OK;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" {
+
+hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                   int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                   const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                   void* stream) {
+  clear_error();
+  const char* who = "hgnn_gat_forward_fused";
+  hgnn_status st = check_csr_args(g, who);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
+  HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
+               "%s: the plan was built for another graph", who);
+  HGNN_REQUIRE(g->eid == nullptr, HGNN_EUNSUPPORTED, "%s: an edge-id map is not supported here", who);
+  HGNN_REQUIRE(H >= 1 && D >= 1 && int64_t(H) * D <= 512, HGNN_EINVAL, "%s: H = %d, D = %d out of range", who, H, D);
+  const int F = H * D;
+  HGNN_REQUIRE(H <= p->max_H && F <= p->max_F, HGNN_EINVAL, "%s: H = %d / F = %d exceed the plan's max_H = %d / max_F = %d",
+               who, H, F, p->max_H, p->max_F);
+  HGNN_REQUIRE(ldo >= F && ldv >= F && ldu >= F, HGNN_EINVAL, "%s: leading dimension smaller than F", who);
+  HGNN_REQUIRE(g->nrows == 0 || out != nullptr, HGNN_EINVAL, "%s: out is NULL", who);
+  if (g->nrows == 0) return HGNN_OK;
+  HGNN_REQUIRE(U && Vt && a_l && a_r, HGNN_EINVAL, "%s: U, Vt, a_l or a_r is NULL", who);
+  HGNN_REQUIRE(D % 8 == 0 && ldv % 8 == 0 && ldo % 8 == 0 && aligned16(Vt) && aligned16(out), HGNN_EUNSUPPORTED,
+               "%s: needs D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned Vt, out", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // per-vertex projections el, er into the plan's fp32 scratch
+  st = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, who);
+  if (st != HGNN_OK) return st;
+  GatArgs a{};
+  a.rowptr = g->rowptr;
+  a.col = g->col;
+  a.X = reinterpret_cast<const half_t*>(Vt);
+  a.Y = reinterpret_cast<half_t*>(out);
+  a.ldx = ldv;
+  a.ldy = ldo;
+  a.nnz = g->nnz;
+  a.nrows = g->nrows;
+  a.F = F;
+  a.H = H;
+  a.D = D;
+  a.slope = neg_slope;
+  a.el = p->vscratch;
+  a.er = p->vscratch + size_t(g->nrows) * H;
+  a.lse = lse;
+  if (p->nb <= 1) return run_gat_segments(p, a, g->ncols, s);
+  // column-blocked plan: every block leaves a normalised partial row and its (m, z) per row; one pass merges them
+  const size_t V = size_t(p->nrows);
+  for (int b = 0; b < p->nb; ++b) {
+    const hgnn_plan* q = p->sub[size_t(b)];
+    GatArgs ab = a;
+    ab.rowptr = p->brp + size_t(b) * (V + 1);
+    ab.col = p->bcol + p->boff[size_t(b)];
+    ab.nnz = q->nnz;
+    ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * V * size_t(p->max_F);
+    ab.ldy = p->max_F;
+    ab.lse = nullptr;
+    ab.part_mz = p->bsum + size_t(b) * V * size_t(p->max_H) * 2;
+    st = run_gat_segments(q, ab, g->ncols, s);
+    if (st != HGNN_OK) return st;
+  }
+  const int L = pow2_at_least(F / 8);
+  GatArgs am = a;
+  launch_gat_block_merge(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, am,
+                         reinterpret_cast<const half_t*>(p->bstage), p->max_F, p->bsum, int64_t(V) * p->max_H * 2, p->nb);
+  HGNN_LAUNCH_CHECK("gat_block_merge_kernel");
+  return HGNN_OK;
+}
+
+}  // extern "C"

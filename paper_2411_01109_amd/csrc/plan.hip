@@ -211,6 +211,7 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
     // staging: two partial vectors (entering piece / leaving piece) per segment
     HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F)));
     HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F), s));
+    HGNN_HIP(hipMalloc(&p->stage_mz, sizeof(float) * size_t(4) * size_t(p->nseg) * size_t(p->max_H)));
   }
   hgnn_status st = compact_rows(SplitPred{g->rowptr, p->S}, g->nrows, &p->split_row, &p->n_split, s);
   if (st != HGNN_OK) return st;
@@ -303,6 +304,7 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->split_seg_hi);
   (void)hipFree(p->big_row);
   (void)hipFree(p->staging);
+  (void)hipFree(p->stage_mz);
   (void)hipFree(p->vscratch);
   (void)hipFree(p->goff);
   (void)hipFree(p->moff);

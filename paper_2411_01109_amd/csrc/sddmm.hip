@@ -24,6 +24,7 @@ struct SddmmArgs {
   const half_t* a_l;
   const half_t* a_r;
   half_t* out;
+  const float* lse;  // [nrows][H] or nullptr; when set the edge score kernel writes exp(score - lse[row]) = alpha
   float* el;  // [nrows][H] fp32 scratch (factorised GAT score)
   float* er;  // [ncols][H]
   int64_t ldu, ldv, nnz, nseg;
@@ -292,8 +293,10 @@ __global__ __launch_bounds__(kBlock) void edge_score_seg_kernel(SddmmArgs a) {
     const int tot = n * a.H;
     for (int j = lane; j < tot; j += kWave) {
       const int k = j / a.H, h = j - k * a.H;
-      const float s = a.el[int64_t(s_row[k]) * a.H + h] + a.er[int64_t(a.col[e0 + k]) * a.H + h];
-      a.out[e0 * a.H + j] = half_t(s > 0.f ? s : a.slope * s);
+      float s = a.el[int64_t(s_row[k]) * a.H + h] + a.er[int64_t(a.col[e0 + k]) * a.H + h];
+      s = s > 0.f ? s : a.slope * s;
+      if (a.lse) s = __expf(s - a.lse[int64_t(s_row[k]) * a.H + h]);
+      a.out[e0 * a.H + j] = half_t(s);
     }
     return;
   }
@@ -331,8 +334,10 @@ __global__ __launch_bounds__(kBlock) void edge_score_seg_kernel(SddmmArgs a) {
       const fv_t vr = *reinterpret_cast<const fv_t*>(a.er + int64_t(cols[e]) * H);
 #pragma unroll
       for (int h = 0; h < H; ++h) {
-        const float s = vl[h] + vr[h];
-        o[e * H + h] = half_t(s > 0.f ? s : a.slope * s);
+        float s = vl[h] + vr[h];
+        s = s > 0.f ? s : a.slope * s;
+        if (a.lse) s = __expf(s - a.lse[int64_t(rows[e]) * H + h]);
+        o[e * H + h] = half_t(s);
       }
     }
     if (vec_ok && kb + EPL <= n) {
@@ -396,6 +401,43 @@ static void launch_proj(int L, dim3 grid, hipStream_t s, const half_t* feat, int
   }
 }
 
+static hgnn_status launch_edge_score(const SddmmArgs& a, int64_t seg_blocks, hipStream_t s) {
+  const int spad = kWave * 4 * ((a.S + 255) / 256);
+  const size_t lds = size_t(spad + spad / 4) * sizeof(int) * kWavesPerBlock;
+  const dim3 gs{unsigned(seg_blocks > 0 ? seg_blocks : 1), 1u, 1u};
+  switch (a.H) {
+    case 1: edge_score_seg_kernel<1><<<gs, kBlock, lds, s>>>(a); break;
+    case 2: edge_score_seg_kernel<2><<<gs, kBlock, lds, s>>>(a); break;
+    case 4: edge_score_seg_kernel<4><<<gs, kBlock, lds, s>>>(a); break;
+    case 8: edge_score_seg_kernel<8><<<gs, kBlock, lds, s>>>(a); break;
+    default: edge_score_seg_kernel<0><<<gs, kBlock, lds, s>>>(a); break;
+  }
+  HGNN_LAUNCH_CHECK("edge_score_seg_kernel");
+  return HGNN_OK;
+}
+
+hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, const hgnn_half* U, int64_t ldu,
+                        const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, hipStream_t s,
+                        const char* who) {
+  const int F = H * D, LH = D / 8;
+  HGNN_REQUIRE(D % 8 == 0 && (LH & (LH - 1)) == 0 && F <= 512 && ldu % 8 == 0 && ldv % 8 == 0 && aligned16(U) &&
+                   aligned16(Vt) && aligned16(a_l) && aligned16(a_r),
+               HGNN_EUNSUPPORTED,
+               "%s: the per-vertex projection needs D = 8 * 2^k, H * D <= 512, ld %% 8 == 0 and 16-byte aligned U, Vt, a_l, a_r",
+               who);
+  HGNN_REQUIRE(H <= p->max_H, HGNN_EINVAL, "%s: H = %d exceeds the plan's max_H = %d", who, H, p->max_H);
+  const int L = pow2_at_least(F / 8), G = kWave / L;
+  float* el = p->vscratch;
+  float* er = p->vscratch + size_t(g->nrows) * H;
+  launch_proj(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, reinterpret_cast<const half_t*>(U), ldu,
+              g->nrows, reinterpret_cast<const half_t*>(a_l), F, D, el, H);
+  HGNN_LAUNCH_CHECK("vertex_proj_kernel");
+  launch_proj(L, dim3(unsigned(ceil_div(g->ncols, int64_t(kWavesPerBlock) * G))), s, reinterpret_cast<const half_t*>(Vt), ldv,
+              g->ncols, reinterpret_cast<const half_t*>(a_r), F, D, er, H);
+  HGNN_LAUNCH_CHECK("vertex_proj_kernel");
+  return HGNN_OK;
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
@@ -457,27 +499,11 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
 
   if (vec && score && p && H <= p->max_H) {
     // project every vertex once, then one add per (edge, head)
-    const int G = kWave / L;
+    hgnn_status st2 = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, "hgnn_sddmm");
+    if (st2 != HGNN_OK) return st2;
     a.el = p->vscratch;
     a.er = p->vscratch + size_t(g->nrows) * H;
-    launch_proj(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, a.U, ldu, g->nrows, a.a_l, F, D,
-                a.el, H);
-    HGNN_LAUNCH_CHECK("vertex_proj_kernel");
-    launch_proj(L, dim3(unsigned(ceil_div(g->ncols, int64_t(kWavesPerBlock) * G))), s, a.Vt, ldv, g->ncols, a.a_r, F, D,
-                a.er, H);
-    HGNN_LAUNCH_CHECK("vertex_proj_kernel");
-    const int spad = kWave * 4 * ((a.S + 255) / 256);
-    const size_t lds = size_t(spad + spad / 4) * sizeof(int) * kWavesPerBlock;
-    const dim3 gs{unsigned(seg_blocks), 1u, 1u};
-    switch (H) {
-      case 1: edge_score_seg_kernel<1><<<gs, kBlock, lds, s>>>(a); break;
-      case 2: edge_score_seg_kernel<2><<<gs, kBlock, lds, s>>>(a); break;
-      case 4: edge_score_seg_kernel<4><<<gs, kBlock, lds, s>>>(a); break;
-      case 8: edge_score_seg_kernel<8><<<gs, kBlock, lds, s>>>(a); break;
-      default: edge_score_seg_kernel<0><<<gs, kBlock, lds, s>>>(a); break;
-    }
-    HGNN_LAUNCH_CHECK("edge_score_seg_kernel");
-    return HGNN_OK;
+    return launch_edge_score(a, seg_blocks, s);
   }
   if ((vec || masked) && !score && p) {
     // halves per lane: the process-wide setting, when the shape allows a narrower load than 16 bytes
@@ -527,4 +553,43 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
   else sddmm_scalar_kernel<false><<<grid, kBlock, 0, s>>>(a);
   HGNN_LAUNCH_CHECK("sddmm_scalar_kernel");
   return HGNN_OK;
+}
+
+extern "C" hgnn_status hgnn_gat_alpha(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                      int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                      const hgnn_half* a_r, float neg_slope, const float* lse, hgnn_half* alpha,
+                                      void* stream) {
+  clear_error();
+  const char* who = "hgnn_gat_alpha";
+  hgnn_status st = check_csr_args(g, who);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
+  HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
+               "%s: the plan was built for another graph", who);
+  HGNN_REQUIRE(g->eid == nullptr, HGNN_EUNSUPPORTED, "%s: an edge-id map is not supported here", who);
+  HGNN_REQUIRE(H >= 1 && D >= 1 && int64_t(H) * D <= 512, HGNN_EINVAL, "%s: H = %d, D = %d out of range", who, H, D);
+  if (g->nnz == 0) return HGNN_OK;
+  HGNN_REQUIRE(U && Vt && a_l && a_r && lse && alpha, HGNN_EINVAL, "%s: NULL argument", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  st = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, who);
+  if (st != HGNN_OK) return st;
+  SddmmArgs a{};
+  a.rowptr = g->rowptr;
+  a.col = g->col;
+  a.out = reinterpret_cast<half_t*>(alpha);
+  a.nnz = g->nnz;
+  a.nrows = g->nrows;
+  a.ncols = g->ncols;
+  a.H = H;
+  a.D = D;
+  a.F = H * D;
+  a.slope = neg_slope;
+  a.seg_lo = p->seg_row_lo;
+  a.seg_hi = p->seg_row_hi;
+  a.nseg = p->nseg;
+  a.S = p->S;
+  a.el = p->vscratch;
+  a.er = p->vscratch + size_t(g->nrows) * H;
+  a.lse = lse;
+  return launch_edge_score(a, ceil_div(p->nseg, kWavesPerBlock), s);
 }

@@ -1,0 +1,139 @@
+"""GPU parity of the single-pass GAT aggregation (score + edge softmax + weighted sum in one kernel
+sequence) against the CPU fp64 oracle's unrounded chain."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from parity import compare, sample_rows
+from test_gpu_parity import down, f16, rand_graph, up
+
+pytestmark = pytest.mark.gpu
+
+
+def check_lse(name, got, ref, deg):
+    nz = deg > 0
+    err = np.abs(got[nz].astype(np.float64) - ref[nz])
+    assert np.all(err <= 2e-3 + 1e-3 * np.abs(ref[nz])), f"{name}: lse off by {err.max():.3e}"
+    assert np.all(got[~nz] == 0)
+
+
+CASES = [  # (H, D, S, col_blocks, scale of the attention vectors)
+    (1, 64, 256, 1, 0.1), (4, 16, 256, 1, 0.1), (8, 8, 128, 1, 0.3), (2, 32, 64, 1, 0.1), (1, 8, 7, 1, 0.5),
+    (1, 128, 256, 1, 0.1), (1, 64, 256, 3, 0.1), (4, 16, 100, 4, 0.2), (1, 64, 256, 1, 3.0), (2, 64, 512, 1, 0.1),
+]
+
+
+@pytest.mark.parametrize("H,D,S,nb,ascale", CASES)
+def test_gat_forward_fused_shapes(hgnn, dev, H, D, S, nb, ascale):
+    print(f"gat fused H={H} D={D} S={S} nb={nb} ascale={ascale}", flush=True)
+    V = 1100
+    F = H * D
+    rowptr, col = rand_graph(V, V, 12, H * 100 + D + S, hubs=((5, 5000), (700, 777), (1099, 300)), empties=(0, 6, 1098))
+    r = np.random.default_rng(H * 7 + D)
+    X = f16(r.standard_normal((V, F)))
+    a_l, a_r = f16(ascale * r.standard_normal(F)), f16(ascale * r.standard_normal(F))
+    ref, ref_lse, sabs = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H, slope=0.2)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, S, F, H, col_blocks=nb)
+    assert hgnn.hgnn_plan_col_blocks(p) == nb
+    Xd = up(X, dev)
+    out = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    lse = torch.full((V, H), 7.0, dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, up(a_l, dev), up(a_r, dev), out, lse)
+    got = down(out)
+    compare("gat fused", got, ref, sabs)
+    deg = np.diff(rowptr)
+    check_lse("gat fused", down(lse), ref_lse, deg)
+    # deterministic; lse optional
+    out2 = torch.full((V, F), -3.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, up(a_l, dev), up(a_r, dev), out2, None)
+    assert np.array_equal(down(out2).view(np.uint16), got.view(np.uint16))
+    # alpha rebuilt from lse = the edge softmax of the scores
+    alpha = torch.full((col.size, H), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_gat_alpha(g, p, H, D, Xd, Xd, up(a_l, dev), up(a_r, dev), lse, alpha)
+    aref = oracle.edge_softmax(rowptr, oracle.gat_score(rowptr, col, X, a_l, a_r, H, slope=0.2))
+    compare("alpha from lse", down(alpha), aref, None, rel_l2=5e-3, rel_elem=2e-2)
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_gat_forward_fused_separate_row_and_column_tables(hgnn, dev):
+    V, ncols, H, D = 500, 700, 2, 16
+    F = H * D
+    rowptr, col = rand_graph(V, ncols, 8, 3, hubs=((9, 900),), empties=(2,))
+    r = np.random.default_rng(1)
+    U, Vt = f16(r.standard_normal((V, F))), f16(r.standard_normal((ncols, F)))
+    a_l, a_r = f16(0.2 * r.standard_normal(F)), f16(0.2 * r.standard_normal(F))
+    ref, ref_lse, sabs = oracle.gat_forward(rowptr, col, U, Vt, a_l, a_r, H)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    p = hgnn.hgnn_plan_create(g, 128, F, H)
+    out = torch.empty((V, F), dtype=torch.float16, device=dev)
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, up(U, dev), up(Vt, dev), up(a_l, dev), up(a_r, dev), out, lse)
+    compare("gat fused, two tables", down(out), ref, sabs)
+    check_lse("gat fused, two tables", down(lse), ref_lse, np.diff(rowptr))
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_gat_forward_fused_large_scores_stay_finite(hgnn, dev):
+    """Scores of several hundred: Eq. 1's shift by the maximum, carried through every merge."""
+    V, H, D = 600, 1, 16
+    rowptr, col = rand_graph(V, V, 10, 8, hubs=((3, 2000),))
+    r = np.random.default_rng(2)
+    X = f16(np.abs(r.standard_normal((V, D))) * 8)
+    a_l, a_r = f16(np.full(D, 4.0)), f16(np.full(D, 4.0))
+    ref, ref_lse, sabs = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H)
+    assert ref_lse.max() > 500
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 64, D, H)
+    out = torch.empty((V, D), dtype=torch.float16, device=dev)
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, up(X, dev), up(X, dev), up(a_l, dev), up(a_r, dev), out, lse)
+    got = down(out)
+    assert np.all(np.isfinite(got)) and np.all(np.isfinite(down(lse)))
+    # el, er are fp32 sums of fp16 products of magnitude ~500: scores carry ~1e-4 absolute error, weights ~1e-4 relative
+    compare("gat fused, large scores", got, ref, sabs)
+    hgnn.hgnn_plan_destroy(p)
+
+
+def test_gat_forward_fused_argument_errors(hgnn, dev):
+    rowptr, col = rand_graph(50, 50, 4, 2)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 64, 64, 1)
+    X = torch.ones((50, 64), dtype=torch.float16, device=dev)
+    a = torch.ones(64, dtype=torch.float16, device=dev)
+    out = torch.empty_like(X)
+    with pytest.raises(hgnn.HgnnError) as ei:  # more heads than the plan allows
+        hgnn.hgnn_gat_forward_fused(g, p, 2, 32, X, X, a, a, out)
+    assert ei.value.status == hgnn.HGNN_EINVAL
+    X12 = torch.ones((50, 16), dtype=torch.float16, device=dev)
+    with pytest.raises(hgnn.HgnnError) as ei:  # D = 12 is not 8 * 2^k
+        hgnn.hgnn_gat_forward_fused(g, p, 1, 12, X12[:, :12], X12[:, :12], a, a, out[:, :16])
+    assert ei.value.status == hgnn.HGNN_EUNSUPPORTED
+    hgnn.hgnn_plan_destroy(p)
+
+
+@pytest.mark.parametrize("maker,nb", [(wl.gat_rmat, 1), (wl.dense_degree, 0)])
+def test_gat_forward_fused_full_configs(hgnn, dev, maker, nb):
+    """Configs 3 and 5 at full size in the launch configuration of the benchmark, on sampled rows."""
+    w = maker()
+    print(f"gat fused full config {w.name}", flush=True)
+    feat = w.tensors["h"] if "h" in w.tensors else w.tensors["X"]
+    H, D = w.H, w.F // w.H
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, w.F, H, col_blocks=nb)
+    Xd = up(feat, dev)
+    out = torch.empty((w.V, w.F), dtype=torch.float16, device=dev)
+    lse = torch.empty((w.V, H), dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, up(w.tensors["a_l"], dev), up(w.tensors["a_r"], dev), out, lse)
+    got, got_lse = down(out), down(lse)
+    assert np.all(np.isfinite(got))
+    rows = sample_rows(w.rowptr, 300, 5)
+    # the oracle on the sampled rows only: a sub-graph with those rows and all columns
+    sub_ptr = np.concatenate([[0], np.cumsum(np.diff(w.rowptr)[rows])]).astype(np.int32)
+    sub_col = np.concatenate([w.col[w.rowptr[r]:w.rowptr[r + 1]] for r in rows]).astype(np.int32)
+    ref, ref_lse, sabs = oracle.gat_forward(sub_ptr, sub_col, feat[rows], feat, w.tensors["a_l"], w.tensors["a_r"], H)
+    compare(f"{w.name} gat fused", got[rows], ref, sabs)
+    check_lse(f"{w.name} gat fused", got_lse[rows], ref_lse, np.diff(sub_ptr))
+    hgnn.hgnn_plan_destroy(p)
