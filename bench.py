@@ -252,6 +252,28 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
+    fused = None
+    if has_gat:
+        # the single-pass GAT aggregation beside the three-call forward path (not part of the step)
+        lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+
+        def time_one(fn):
+            for _ in range(max(args.warmup, 1)):
+                fn()
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for a, b in pairs:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
+        t_f = time_one(lambda: hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse))
+        t_a = time_one(lambda: hgnn.hgnn_gat_alpha(g, plan, H, D, X, X, a_l, a_r, lse, alpha))
+        three = float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in ("gat_score", "edge_softmax", "gat_spmm_fwd")))
+        fused = {"gat_forward_fused_ms": round(t_f, 4), "three_call_forward_ms": round(three, 4),
+                 "alpha_from_lse_ms": round(t_a, 4)}
+
     variants = None
     if args.variants:
         # the paper's two SpMM micro-benchmarks (atomic vs. non-atomic conflict writes; the vertex-parallel
@@ -346,13 +368,15 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "variants": variants, "width_sweep": width_sweep,
+        "layers": layer_ms, "ops": detail, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        if fused:
+            print("gat fused forward " + json.dumps(fused), file=sys.stderr)
         if width_sweep:
             for k, v in width_sweep.items():
                 print(f"width {k:18s} sddmm_dot {v['sddmm_dot_ms']:9.4f} ms   spmm_vertex_groups {v['spmm_vertex_groups_ms']:9.4f} ms",

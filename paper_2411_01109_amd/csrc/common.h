@@ -66,6 +66,16 @@ __host__ __device__ inline int row_of_edge(const int* rowptr, int nrows, int64_t
   return lo - 1;
 }
 
+// Orders the LDS accesses of one wave: what its lanes wrote before is visible to all its lanes after.
+// The kernels that stage a segment give every wave a private LDS region, so nothing wider than the
+// wave has to meet; a workgroup barrier there would only put the four waves in lock step and stall
+// three of them whenever one waits for memory.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 typedef int int4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 
@@ -75,18 +85,23 @@ typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 // maximum spreads the ids: s_row[i] = row of edge e0+i for i < n, -2 for the padding up to
 // 64*per slots; s_blk[i/4] = common row id of the aligned group of four edges, or -1 when they
 // differ or touch the padding.  Lane t owns the slots [t*per, (t+1)*per); per is a multiple of 4.
-// Contains workgroup barriers: every wave of the workgroup must call it (n = 0 when it has no segment).
+// s_row / s_blk are private to the calling wave, so wave-level ordering is enough; BLOCK_SYNC = true uses
+// workgroup barriers instead (every wave of the workgroup must then call it, n = 0 without a segment),
+// which keeps the four waves of a streaming kernel in step on consecutive segments.
 __device__ __forceinline__ int seg_slots_per_lane(int S) { return 4 * ((S + 255) / 256); }
 
+template <bool BLOCK_SYNC = false>
 __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane, int per, int n, int row_lo, int row_hi,
                                                const int* __restrict__ rowptr, int64_t e0) {
   for (int i = lane; i < kWave * per; i += kWave) s_row[i] = i == 0 ? row_lo : -1;
-  __syncthreads();
+  if (BLOCK_SYNC) __syncthreads();
+  else wave_sync();
   for (int r = row_lo + 1 + lane; r <= row_hi; r += kWave) {
     const int p = rowptr[r], q = rowptr[r + 1];
     if (q > p) s_row[p - int(e0)] = r;
   }
-  __syncthreads();
+  if (BLOCK_SYNC) __syncthreads();
+  else wave_sync();
   const int b0 = lane * per;
   int run = -1;
   for (int j = 0; j < per; ++j) {
@@ -111,7 +126,8 @@ __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane,
     }
     s_blk[(b0 + j) >> 2] = (v[0] == v[1] && v[1] == v[2] && v[2] == v[3]) ? v[0] : -1;
   }
-  __syncthreads();
+  if (BLOCK_SYNC) __syncthreads();
+  else wave_sync();
 }
 
 }  // namespace hgnn
@@ -159,7 +175,8 @@ struct hgnn_plan {
 };
 
 namespace hgnn {
-// el[i,h] = a_l[h].U[i,h] and er[j,h] = a_r[h].Vt[j,h] into the plan's fp32 scratch (el first, then er)
+// el[i,h] = a_l[h].U[i,h] and er[j,h] = a_r[h].Vt[j,h] into the plan's fp32 scratch (el first, then er;
+// Vt == nullptr skips er)
 hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, const hgnn_half* U, int64_t ldu,
                         const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, hipStream_t s,
                         const char* who);

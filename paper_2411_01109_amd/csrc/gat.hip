@@ -29,7 +29,8 @@ struct GatArgs {
   int nrows, F, H, D;
   float slope;
   const float* el;  // [nrows][H]
-  const float* er;  // [ncols][H]
+  const half_t* a_r;  // [H*D]  (FLY kernels)
+  const float* er;    // [ncols][H]  (other kernels)
   float* lse;       // [nrows][H] or nullptr
   float* part_mz;   // column blocks: [nrows][H][2] (m, z) of this block's partial rows; else nullptr
   int S;
@@ -44,6 +45,41 @@ struct GatArgs {
   const int* split_hi;
   int n_split;
 };
+
+// v += the value of the lane that the data-parallel-primitive control CTRL pairs this lane with (one VALU
+// instruction, no trip through the LDS crossbar).  Controls used: quad_perm [1,0,3,2] and [2,3,0,1]
+// (lane ^ 1, lane ^ 2), row_half_mirror (lane i <-> 7 - i of each 8) and row_mirror (i <-> 15 - i of each 16).
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(t);
+}
+
+// all-reduce (sum) of four values over the LH consecutive lanes of a head; LH is a power of two and the
+// head's lanes are aligned to LH.  After quads are summed, a mirror inside 8 (16) lanes pairs every lane with
+// one of the other quad (half), whose partial sum is the same on all its lanes.
+__device__ __forceinline__ void head_allreduce4(float (&v)[4], int LH) {
+  if (LH >= 2) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0xB1>(v[u]);
+  }
+  if (LH >= 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x4E>(v[u]);
+  }
+  if (LH >= 8) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x141>(v[u]);
+  }
+  if (LH >= 16) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x140>(v[u]);
+  }
+  for (int off = 16; off < LH; off <<= 1) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], off);
+  }
+}
 
 // (m, z, acc) <- merge with (m2, z2, acc2)
 __device__ __forceinline__ void soft_merge(float& m, float& z, float (&acc)[8], float m2, float z2, const float (&acc2)[8]) {
@@ -116,7 +152,11 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L) {
   return o;
 }
 
-template <int L, bool OFF32>
+// FLY = true: the column-side score term a_r.X[col] is formed from the gathered row itself (eight extra
+// products per lane and an exchange among the lanes of a head, no per-edge scalar fetched; wins for heads of
+// up to 16 features).  FLY = false: it is gathered from the per-vertex projection er while the segment is
+// staged (one 4-byte gather per edge and head; wins for long heads, where the exchange costs more).
+template <int L, bool OFF32, bool FLY>
 __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;
@@ -156,7 +196,8 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
   }
 
-  // ---- phase 1: column ids, row ids, then the score of every (edge, head), once per wave
+  // ---- phase 1: column ids, row ids, and per (edge, head) the row-side score term el[row] (FLY) or the
+  // finished score LeakyReLU(el[row] + er[col])
   for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
@@ -165,16 +206,19 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     const int c = s_col[i];
     const int r = in ? s_row[i] : 0;
     for (int h = 0; h < a.H; ++h) {
-      float s = -INFINITY;  // padding: weight exp(-inf - m) = 0
+      float s = FLY ? 0.f : -INFINITY;  // padding (never read by FLY; weight exp(-inf - m) = 0 otherwise)
       if (in) {
-        s = a.el[int64_t(r) * a.H + h] + a.er[int64_t(c) * a.H + h];
-        s = s > 0.f ? s : a.slope * s;
+        s = a.el[int64_t(r) * a.H + h];
+        if (!FLY) {
+          s += a.er[int64_t(c) * a.H + h];
+          s = s > 0.f ? s : a.slope * s;
+        }
       }
       s_sc[i * a.H + h] = s;
     }
     if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);  // from here on: byte offset of the neighbour's row
   }
-  __syncthreads();
+  wave_sync();
 
   // ---- phase 2: running (m, z, acc) over this group's chunk
   const int C = 4 * ((S + 4 * G - 1) / (4 * G));
@@ -216,6 +260,18 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     cur = s_row[c0];
     lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
   }
+  const int LH = a.D / 8;  // lanes per head (power of two)
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  half2_t ar2[4];
+  if (FLY) {
+    const half8_t t = *reinterpret_cast<const half8_t*>(a.a_r + f0c);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ar2[q][0] = active ? t[2 * q] : half_t(0);
+      ar2[q][1] = active ? t[2 * q + 1] : half_t(0);
+    }
+  }
+  // the lanes of a group share their chunk, so the exchanges between the lanes of a head always meet
   for (int i = c0; i < c1; i += 4) {
     const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
     const int blk = s_blk[i >> 2];
@@ -223,8 +279,29 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
     float sc[4];
+    if (FLY) {  // column-side term a_r.x from the row just gathered, summed over the lanes of the head
 #pragma unroll
-    for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
+      for (int u = 0; u < 4; ++u) {
+        float d = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {  // two fp16 products per instruction, fp32 sum
+          half2_t xv;
+          xv[0] = x[u][2 * q];
+          xv[1] = x[u][2 * q + 1];
+          d = __builtin_amdgcn_fdot2(ar2[q], xv, d, false);
+        }
+        sc[u] = d;
+      }
+      head_allreduce4(sc, LH);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float t = sc[u] + s_sc[(i + u) * a.H + head];
+        sc[u] = t > 0.f ? t : a.slope * t;
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
+    }
     if (blk == cur) {  // four more edges of the current row: one rescale, four terms
       const float mn = fmaxf(fmaxf(m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
       const float f = __expf(m - mn);
@@ -264,7 +341,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     }
   }
   if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
-  __syncthreads();
+  wave_sync();
 
   // ---- merge: group 0 sews the parked pieces together in chunk order
   if (valid && g == 0) {
@@ -401,16 +478,16 @@ __global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, cons
   row_store(a, r, f0, head, (f0 % a.D) == 0, m, z, acc);
 }
 
-template <bool OFF32>
+template <bool OFF32, bool FLY>
 static void launch_gat_seg(int L, dim3 grid, size_t lds, hipStream_t s, const GatArgs& a) {
   switch (L) {
-    case 1: gat_seg_kernel<1, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: gat_seg_kernel<2, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: gat_seg_kernel<4, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: gat_seg_kernel<8, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: gat_seg_kernel<16, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: gat_seg_kernel<32, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    default: gat_seg_kernel<64, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: gat_seg_kernel<1, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 2: gat_seg_kernel<2, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 4: gat_seg_kernel<4, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 8: gat_seg_kernel<8, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 16: gat_seg_kernel<16, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 32: gat_seg_kernel<32, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    default: gat_seg_kernel<64, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
   }
 }
 
@@ -460,8 +537,13 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   const int64_t nblk = ceil_div(q->nseg, kWavesPerBlock);
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
-  if (off32) launch_gat_seg<true>(L, grid, lds, s, a);
-  else launch_gat_seg<false>(L, grid, lds, s, a);
+  if (a.a_r) {
+    if (off32) launch_gat_seg<true, true>(L, grid, lds, s, a);
+    else launch_gat_seg<false, true>(L, grid, lds, s, a);
+  } else {
+    if (off32) launch_gat_seg<true, false>(L, grid, lds, s, a);
+    else launch_gat_seg<false, false>(L, grid, lds, s, a);
+  }
   HGNN_LAUNCH_CHECK("gat_seg_kernel");
   if (a.n_split > 0) {
     launch_gat_finish(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
@@ -499,8 +581,10 @@ hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_
   HGNN_REQUIRE(D % 8 == 0 && ldv % 8 == 0 && ldo % 8 == 0 && aligned16(Vt) && aligned16(out), HGNN_EUNSUPPORTED,
                "%s: needs D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned Vt, out", who);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // per-vertex projections el, er into the plan's fp32 scratch
-  st = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, who);
+  // per-vertex projections into the plan's fp32 scratch: el[i,h] = a_l[h].U[i,h] always; er[j,h] = a_r[h].Vt[j,h]
+  // only for long heads (short heads form that term in the kernel from the gathered row)
+  const bool fly = D <= 16;
+  st = gat_project(p, g, H, D, U, ldu, fly ? nullptr : Vt, ldv, a_l, a_r, s, who);
   if (st != HGNN_OK) return st;
   GatArgs a{};
   a.rowptr = g->rowptr;
@@ -516,6 +600,7 @@ hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_
   a.D = D;
   a.slope = neg_slope;
   a.el = p->vscratch;
+  a.a_r = fly ? reinterpret_cast<const half_t*>(a_r) : nullptr;
   a.er = p->vscratch + size_t(g->nrows) * H;
   a.lse = lse;
   if (p->nb <= 1) return run_gat_segments(p, a, g->ncols, s);

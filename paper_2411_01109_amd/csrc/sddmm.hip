@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
         if (i + q < c1) s_out[(i + q) * a.H + head] = half_t(p[q]);
     }
   }
-  __syncthreads();
+  wave_sync();
   // coalesced write-back, 16 bytes per lane where the destination allows it
   const int tot = n * a.H;
   half_t* dst = a.out + e0 * a.H;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_edge_kernel(SddmmArgs a) {
       if (i + q < c1 && active && (l % LH) == 0) s_out[(i + q) * a.H + head] = half_t(p);
     }
   }
-  __syncthreads();
+  wave_sync();
   for (int j = lane; j < n * a.H; j += kWave) a.out[e0 * a.H + j] = s_out[j];
 }
 
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void edge_score_seg_kernel(SddmmArgs a) {
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
-  seg_stage_rows(s_row, s_blk, lane, per, n, valid ? a.seg_lo[seg] : 0, valid ? a.seg_hi[seg] : -1, a.rowptr, e0);
+  seg_stage_rows<true>(s_row, s_blk, lane, per, n, valid ? a.seg_lo[seg] : 0, valid ? a.seg_hi[seg] : -1, a.rowptr, e0);
   if (HT == 0) {  // any head count: one output element per lane and step
     const int tot = n * a.H;
     for (int j = lane; j < tot; j += kWave) {
@@ -420,6 +420,7 @@ hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, con
                         const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, hipStream_t s,
                         const char* who) {
   const int F = H * D, LH = D / 8;
+  // Vt == nullptr: only the row side is wanted
   HGNN_REQUIRE(D % 8 == 0 && (LH & (LH - 1)) == 0 && F <= 512 && ldu % 8 == 0 && ldv % 8 == 0 && aligned16(U) &&
                    aligned16(Vt) && aligned16(a_l) && aligned16(a_r),
                HGNN_EUNSUPPORTED,
@@ -432,9 +433,11 @@ hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, con
   launch_proj(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, reinterpret_cast<const half_t*>(U), ldu,
               g->nrows, reinterpret_cast<const half_t*>(a_l), F, D, el, H);
   HGNN_LAUNCH_CHECK("vertex_proj_kernel");
-  launch_proj(L, dim3(unsigned(ceil_div(g->ncols, int64_t(kWavesPerBlock) * G))), s, reinterpret_cast<const half_t*>(Vt), ldv,
-              g->ncols, reinterpret_cast<const half_t*>(a_r), F, D, er, H);
-  HGNN_LAUNCH_CHECK("vertex_proj_kernel");
+  if (Vt) {
+    launch_proj(L, dim3(unsigned(ceil_div(g->ncols, int64_t(kWavesPerBlock) * G))), s, reinterpret_cast<const half_t*>(Vt),
+                ldv, g->ncols, reinterpret_cast<const half_t*>(a_r), F, D, er, H);
+    HGNN_LAUNCH_CHECK("vertex_proj_kernel");
+  }
   return HGNN_OK;
 }
 

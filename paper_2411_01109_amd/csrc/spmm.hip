@@ -472,7 +472,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
         for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
       }
     }
-    __syncthreads();
+    wave_sync();
   }
 
   // ---- phase 2: running reduction over this group's chunk
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
     }
   }
   if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
-  __syncthreads();
+  wave_sync();
 
   // ---- merge: group 0 sews the parked pieces together in chunk order
   if (valid && g == 0) {
@@ -776,7 +776,7 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
       if (i0 + 1 < n) s_w[i0 + 1] = pr[1];
     }
   }
-  __syncthreads();
+  wave_sync();
 
   // ---- phase 2: the groups of lanes take consecutive chunks of the neighbour group
   const int C = 4 * ((v.ng + 4 * G - 1) / (4 * G));
