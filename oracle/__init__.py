@@ -55,6 +55,8 @@ def _load():
     lib.orc_gat_score.argtypes = [i32, vp, vp, i32, i32, vp, i64, vp, vp, dbl, vp]
     lib.orc_gat_forward.restype = None
     lib.orc_gat_forward.argtypes = [i32, vp, vp, i32, i32, vp, i64, vp, i64, vp, vp, dbl, vp, vp, vp]
+    lib.orc_gat_backward.restype = None
+    lib.orc_gat_backward.argtypes = [i32, i32, vp, vp, i32, i32, vp, i64, vp, i64, vp, vp, dbl, vp, i64, vp, vp, vp]
     lib.orc_edge_softmax.restype = None
     lib.orc_edge_softmax.argtypes = [i32, vp, i32, vp, vp]
     lib.orc_edge_softmax_bwd.restype = None
@@ -172,6 +174,19 @@ def gat_forward(rowptr, col, U, Vt, a_l, a_r, H: int, slope: float = 0.2):
     _load().orc_gat_forward(V, _ptr(rowptr), _ptr(col), H, F // H, _ptr(U), U.strides[0] // 2, _ptr(Vt),
                             Vt.strides[0] // 2, _ptr(a_l), _ptr(a_r), slope, _ptr(out), _ptr(lse), _ptr(sabs))
     return out, lse, sabs
+
+
+def gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H: int, slope: float = 0.2):
+    """-> (dV [ncols][F], d_el [V][H], d_er [ncols][H]) of L = sum <dOut, out> for one GAT aggregation."""
+    rowptr, col, U, Vt, a_l, a_r, dOut = _i32(rowptr), _i32(col), _f16(U), _f16(Vt), _f16(a_l), _f16(a_r), _f16(dOut)
+    V, F, ncols = rowptr.size - 1, U.shape[1], Vt.shape[0]
+    dV = np.empty((ncols, F), dtype=np.float64)
+    d_el = np.empty((V, H), dtype=np.float64)
+    d_er = np.empty((ncols, H), dtype=np.float64)
+    _load().orc_gat_backward(V, ncols, _ptr(rowptr), _ptr(col), H, F // H, _ptr(U), U.strides[0] // 2, _ptr(Vt),
+                             Vt.strides[0] // 2, _ptr(a_l), _ptr(a_r), slope, _ptr(dOut), dOut.strides[0] // 2, _ptr(dV),
+                             _ptr(d_el), _ptr(d_er))
+    return dV, d_el, d_er
 
 
 def edge_softmax(rowptr, e):

@@ -216,6 +216,70 @@ void orc_gat_forward(int32_t V, const int32_t* rowptr, const int32_t* col, int32
   }
 }
 
+/* ---- backward of that aggregation.  With L = sum_i <dOut_i, out_i>, and e, alpha as in
+ * orc_gat_forward (recomputed here from the inputs):
+ *   dalpha_k = <dOut[i,h], Vt[col k,h]>              (SDDMM of section 2.1.2)
+ *   t        = sum_k alpha_k * dalpha_k              (= <dOut[i,h], out[i,h]>)
+ *   ds_k     = alpha_k * (dalpha_k - t) * (s_k > 0 ? 1 : slope)   (Eq. 1 differentiated, LeakyReLU mask)
+ *   d_el[i,h] = sum over row i of ds_k,  d_er[j,h] = sum over the non-zeros with column j of ds_k
+ *   dV[j, h*D+d] = sum over the non-zeros with column j of alpha_k * dOut[i, h*D+d]
+ * dV is the gradient through the aggregated values only; the gradient through the scores
+ * reaches the features as d_el * a_l and d_er * a_r (dense, outside this function). ---- */
+void orc_gat_backward(int32_t V, int32_t ncols, const int32_t* rowptr, const int32_t* col, int32_t H, int32_t D,
+                      const uint16_t* U, int64_t ldu, const uint16_t* Vt, int64_t ldv, const uint16_t* a_l,
+                      const uint16_t* a_r, double slope, const uint16_t* dOut, int64_t lddo, double* dV, double* d_el,
+                      double* d_er) {
+  int32_t F = H * D;
+  memset(dV, 0, sizeof(double) * (size_t)ncols * F);
+  memset(d_er, 0, sizeof(double) * (size_t)ncols * H);
+  for (int32_t i = 0; i < V; ++i) {
+    int32_t beg = rowptr[i], end = rowptr[i + 1];
+    int32_t n = end - beg;
+    double* s = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    double* alpha = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (int32_t h = 0; h < H; ++h) {
+      d_el[(int64_t)i * H + h] = 0.0;
+      if (n == 0) continue;
+      double el = 0.0;
+      for (int32_t d = 0; d < D; ++d)
+        el += orc_half_to_double(a_l[h * D + d]) * orc_half_to_double(U[(int64_t)i * ldu + h * D + d]);
+      double m = -INFINITY;
+      for (int32_t k = 0; k < n; ++k) {
+        double v = el;
+        for (int32_t d = 0; d < D; ++d)
+          v += orc_half_to_double(a_r[h * D + d]) * orc_half_to_double(Vt[(int64_t)col[beg + k] * ldv + h * D + d]);
+        s[k] = v;
+        double e = v > 0.0 ? v : slope * v;
+        m = fmax(m, e);
+      }
+      double z = 0.0;
+      for (int32_t k = 0; k < n; ++k) z += exp((s[k] > 0.0 ? s[k] : slope * s[k]) - m);
+      double t = 0.0;
+      for (int32_t k = 0; k < n; ++k) {
+        alpha[k] = exp((s[k] > 0.0 ? s[k] : slope * s[k]) - m) / z;
+        double da = 0.0;
+        for (int32_t d = 0; d < D; ++d)
+          da += orc_half_to_double(dOut[(int64_t)i * lddo + h * D + d]) *
+                orc_half_to_double(Vt[(int64_t)col[beg + k] * ldv + h * D + d]);
+        t += alpha[k] * da;
+      }
+      for (int32_t k = 0; k < n; ++k) {
+        int64_t j = col[beg + k];
+        double da = 0.0;
+        for (int32_t d = 0; d < D; ++d)
+          da += orc_half_to_double(dOut[(int64_t)i * lddo + h * D + d]) * orc_half_to_double(Vt[j * ldv + h * D + d]);
+        double ds = alpha[k] * (da - t) * (s[k] > 0.0 ? 1.0 : slope);
+        d_el[(int64_t)i * H + h] += ds;
+        d_er[j * H + h] += ds;
+        for (int32_t d = 0; d < D; ++d)
+          dV[j * F + h * D + d] += alpha[k] * orc_half_to_double(dOut[(int64_t)i * lddo + h * D + d]);
+      }
+    }
+    free(s);
+    free(alpha);
+  }
+}
+
 /* ---- edge softmax, Eq. 1: m_i = max_j e_ij; e'_ij = exp(e_ij - m_i);
  * alpha_ij = e'_ij / sum_j e'_ij, over the neighbourhood (CSR row) of i, per head.
  * Input is fp64 (the caller decodes fp16 scores). ---- */

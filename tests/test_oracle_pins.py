@@ -504,6 +504,72 @@ def test_gat_forward_special_cases():
     assert np.all(np.isfinite(o3)) and np.all(np.isfinite(l3)) and l3.max() > 1000
 
 
+def test_gat_backward_matches_finite_differences_of_the_forward():
+    """L = sum <dOut, out>.  U enters the forward only through el = a_l.U, so dL/dU = d_el * a_l; Vt enters
+    through er = a_r.Vt and through the aggregated values, so dL/dVt = d_er * a_r + dV; dL/da_r = sum_j d_er_j Vt_j."""
+    V, ncols, H, D = 9, 8, 2, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, ncols, 0.5, 21, empty_rows=(2,))
+    # values on a coarse binary grid so that fp16 storage of the perturbed inputs is exact
+    q = lambda x: (np.round(x * 64) / 64).astype(np.float16)
+    U, Vt, dOut = q(rng.standard_normal((V, F))), q(rng.standard_normal((ncols, F))), q(rng.standard_normal((V, F)))
+    a_l, a_r = q(0.5 * rng.standard_normal(F)), q(0.5 * rng.standard_normal(F))
+    dV, d_el, d_er = oracle.gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H, slope=0.25)
+
+    def loss(U_, Vt_, a_r_):
+        out, _, _ = oracle.gat_forward(rowptr, col, U_, Vt_, a_l, a_r_, H, slope=0.25)
+        return float((out * dOut.astype(np.float64)).sum())
+
+    eps = 2.0 ** -8  # exactly representable next to the grid values
+    al, ar = a_l.astype(np.float64).reshape(H, D), a_r.astype(np.float64).reshape(H, D)
+    for (i, f) in [(0, 0), (3, 5), (8, 7), (5, 2)]:
+        Up, Um = U.copy(), U.copy()
+        Up[i, f] += np.float16(eps)
+        Um[i, f] -= np.float16(eps)
+        fd = (loss(Up, Vt, a_r) - loss(Um, Vt, a_r)) / (2 * eps)
+        assert abs(fd - d_el[i, f // D] * al[f // D, f % D]) < 2e-3, (i, f)
+    for (j, f) in [(0, 0), (4, 6), (7, 3), (2, 1)]:
+        Vp, Vm = Vt.copy(), Vt.copy()
+        Vp[j, f] += np.float16(eps)
+        Vm[j, f] -= np.float16(eps)
+        fd = (loss(U, Vp, a_r) - loss(U, Vm, a_r)) / (2 * eps)
+        assert abs(fd - (d_er[j, f // D] * ar[f // D, f % D] + dV[j, f])) < 2e-3, (j, f)
+    for f in (0, 3, 6):
+        ap, am = a_r.copy(), a_r.copy()
+        ap[f] += np.float16(eps)
+        am[f] -= np.float16(eps)
+        fd = (loss(U, Vt, ap) - loss(U, Vt, am)) / (2 * eps)
+        want = (d_er[:, f // D] * Vt.astype(np.float64)[:, f]).sum()
+        assert abs(fd - want) < 2e-3, f
+
+
+def test_gat_backward_special_cases_and_composition():
+    V, ncols, H, D = 30, 26, 2, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, ncols, 0.3, 4, empty_rows=(1,))
+    U, Vt = rng.standard_normal((V, F)).astype(np.float16), rng.standard_normal((ncols, F)).astype(np.float16)
+    dOut = rng.standard_normal((V, F)).astype(np.float16)
+    a_l, a_r = (0.4 * rng.standard_normal(F)).astype(np.float16), (0.4 * rng.standard_normal(F)).astype(np.float16)
+    dV, d_el, d_er = oracle.gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H)
+    # the composition of the separately pinned pieces: alpha, SDDMM dot, softmax backward with mask, sums, SpMM on A^T
+    el = (U.astype(np.float64).reshape(V, H, D) * a_l.astype(np.float64).reshape(H, D)).sum(-1)
+    er = (Vt.astype(np.float64).reshape(ncols, H, D) * a_r.astype(np.float64).reshape(H, D)).sum(-1)
+    raw = el[row] + er[col]
+    e = np.where(raw > 0, raw, 0.2 * raw)
+    alpha = oracle.edge_softmax(rowptr, e)
+    dalpha = oracle.sddmm_dot(rowptr, col, dOut, Vt, H=H)
+    ds = oracle.edge_softmax_bwd(rowptr, alpha, dalpha, e=e, slope=0.2)
+    np.testing.assert_allclose(d_el, oracle.edge_rowsum(rowptr, ds), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(d_er, oracle.edge_colsum(rowptr, col, ds, ncols), rtol=1e-10, atol=1e-12)
+    ref = np.zeros((ncols, F))
+    for k in range(col.size):
+        ref[col[k]] += np.repeat(alpha[k], D) * dOut.astype(np.float64)[row[k]]
+    np.testing.assert_allclose(dV, ref, rtol=1e-10, atol=1e-12)
+    # slope 1 (no mask): the score gradients of a row sum to zero (softmax weights sum to one)
+    _, d_el1, _ = oracle.gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H, slope=1.0)
+    assert np.max(np.abs(d_el1)) < 1e-12
+
+
 # ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
 @pytest.mark.parametrize("ng", [1, 4, 32, 64])
 def test_neighbor_groups_bruteforce(ng):
