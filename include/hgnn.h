@@ -262,6 +262,24 @@ hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_
                                    const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
                                    void* stream);
 
+/* Backward of hgnn_gat_forward_fused without per-edge tensors.  Given the forward inputs, the
+ * forward result out, its lse, and dOut (the gradient of out), with
+ *   alpha_ij = exp(e_ij - lse_i),  dalpha_ij = <dOut[i,h], Vt[j,h]>,  t_i = <dOut[i,h], out[i,h]>,
+ *   ds_ij = alpha_ij * (dalpha_ij - t_i) * (score_ij > 0 ? 1 : neg_slope)      (Eq. 1 differentiated)
+ * it writes  dV[j, h*D+d] = sum_i alpha_ij * dOut[i, h*D+d]   (fp16 [ncols][lddv], the gradient
+ * through the aggregated values), d_el[i,h] = sum_j ds_ij (fp16 [nrows][H]) and
+ * d_er[j,h] = sum_i ds_ij (fp16 [ncols][H]); the gradients of the features through the scores
+ * are the dense products d_el * a_l and d_er * a_r, outside this call.  Two passes: over gt with
+ * plan pt (gathers dOut rows: dV and d_er) and over g with plan p (gathers Vt rows: d_el).
+ * gt must be the transpose of g (hgnn_transpose; its edge-id map is not used).  Same shape
+ * requirements as the forward call, for both plans.  Overwrites the per-vertex scratch of p. */
+hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt, const hgnn_plan* pt,
+                                    int32_t H, int32_t D, const hgnn_half* U, int64_t ldu, const hgnn_half* Vt,
+                                    int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, float neg_slope,
+                                    const hgnn_half* out, int64_t ldo, const float* lse, const hgnn_half* dOut,
+                                    int64_t lddo, hgnn_half* dV, int64_t lddv, hgnn_half* d_el, hgnn_half* d_er,
+                                    void* stream);
+
 /* Rebuilds alpha[k,h] = exp(e_k - lse[i,h]) (fp16 [nnz][H]) from the lse of
  * hgnn_gat_forward_fused, for a backward pass that wants the attention weights as a tensor.
  * Same requirements as above. */

@@ -25,7 +25,7 @@ EXPORTS = (
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
-    "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha",
+    "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -99,6 +99,8 @@ def load() -> ctypes.CDLL:
     lib.hgnn_set_vector_halves.argtypes = [i32]
     lib.hgnn_gat_forward_fused.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp]
     lib.hgnn_gat_alpha.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp, vp]
+    lib.hgnn_gat_backward_fused.argtypes = [csr, vp, csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64,
+                                            vp, i64, vp, vp, vp]
     lib.hgnn_get_vector_halves.restype = i32
     lib.hgnn_get_vector_halves.argtypes = []
     for name in EXPORTS:
@@ -303,6 +305,18 @@ def hgnn_gat_forward_fused(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt:
     _check(load().hgnn_gat_forward_fused(g.ref, p.handle, H, D, _ptr(U, torch.float16), _ld(U), _ptr(Vt, torch.float16),
                                          _ld(Vt), _ptr(a_l, torch.float16), _ptr(a_r, torch.float16), neg_slope,
                                          _ptr(out, torch.float16), _ld(out), _ptr(lse, torch.float32), _stream(stream)))
+
+
+def hgnn_gat_backward_fused(g: Csr, p: Plan, gt: Csr, pt: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,
+                            a_l: torch.Tensor, a_r: torch.Tensor, out: torch.Tensor, lse: torch.Tensor,
+                            dOut: torch.Tensor, dV: torch.Tensor, d_el: torch.Tensor, d_er: torch.Tensor,
+                            neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_gat_backward_fused(g.ref, p.handle, gt.ref, pt.handle, H, D, _ptr(U, torch.float16), _ld(U),
+                                          _ptr(Vt, torch.float16), _ld(Vt), _ptr(a_l, torch.float16),
+                                          _ptr(a_r, torch.float16), neg_slope, _ptr(out, torch.float16), _ld(out),
+                                          _ptr(lse, torch.float32), _ptr(dOut, torch.float16), _ld(dOut),
+                                          _ptr(dV, torch.float16), _ld(dV), _ptr(d_el, torch.float16),
+                                          _ptr(d_er, torch.float16), _stream(stream)))
 
 
 def hgnn_gat_alpha(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor, a_l: torch.Tensor,

@@ -151,6 +151,7 @@ struct hgnn_plan {
   hgnn_half* staging = nullptr;     // [2*nseg][max_F]
   float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32
+  float* vtab = nullptr;            // [nrows][max_H][4] fp32 per-vertex (el, lse, t, -) of the fused GAT backward
   // column blocking of the SpMM (nb > 1): block b holds the non-zeros whose column lies in
   // [b*block_width, (b+1)*block_width), stored block after block as a CSR of their own
   int32_t nb = 1;

@@ -1,0 +1,697 @@
+// Backward of the single-pass GAT aggregation for gfx950, again without any per-edge tensor.
+//
+// With alpha rebuilt from per-vertex scalars, alpha_ij = exp(LeakyReLU(el_i + er_j) - lse_i), and
+// t_i = sum_j alpha_ij * dalpha_ij = <dOut_i, out_i> known per vertex, every per-edge quantity of
+// the backward pass (sections 2.1.2 and 3.1.2: SDDMM for dalpha, Eq. 1 differentiated, the
+// alpha-weighted SpMM on the transpose) follows from one gathered feature row and a few scalars:
+//   dalpha_ij = <dOut_i, h_j>,   ds_ij = alpha_ij * (dalpha_ij - t_i) * LeakyReLU'(el_i + er_j)
+// Two passes over the graph, both on the segment design (no atomics, staged pieces, follow-up):
+//   transposed pass (rows j, gathers dOut_i):  dV_j = sum_i alpha_ij * dOut_i,  d_er_j = sum_i ds_ij
+//   forward pass    (rows i, gathers h_j):     d_el_i = sum_j ds_ij
+// The destination vertex's scalars (el, lse, t) sit in one 16-byte entry per (vertex, head), so the
+// transposed pass fetches them with a single gather from a table that stays in L2; the weight and
+// the mask are formed once per edge and wave while the segment is staged.
+#include "common.h"
+
+namespace hgnn {
+
+struct GatBwdArgs {
+  const int* rowptr;
+  const int* col;
+  const half_t* X;     // gathered, column-side vectors [ncols of this graph][ldx]
+  const half_t* R;     // row-side vectors [nrows of this graph][ldr]
+  half_t* Y;           // VEC kernels: [nrows][ldy] = sum over the row of alpha * X[col]
+  int64_t ldx, ldr, ldy, nnz;
+  int nrows, F, H, D;
+  float slope;
+  const float4* vtab;  // [destination vertex][H]: (el, lse, t, unused)
+  const float* er;     // [source vertex][H]
+  int dst_is_col;      // 1: the destination vertex of a non-zero is its column (transposed pass), 0: its row
+  half_t* dsum;        // [nrows][H] sum over the row of ds (fp16), or
+  float* dsum_f32;     // column blocks: this block's partial sums in fp32
+  int S;
+  int64_t nseg;
+  const int* seg_lo;
+  const int* seg_hi;
+  half_t* staging;     // [2*nseg][stage_ld]
+  float* stage_ds;     // [2*nseg][H][2], first float = partial sum of ds
+  int stage_ld;
+  const int* split_row;
+  const int* split_lo;
+  const int* split_hi;
+  int n_split;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add_b(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(t);
+}
+
+// all-reduce (sum) of four values over the LH consecutive, LH-aligned lanes of a head (LH a power of two):
+// quad_perm exchanges, then mirrors inside 8 and 16 lanes, then cross-row exchanges
+__device__ __forceinline__ void head_sum4(float (&v)[4], int LH) {
+  if (LH >= 2) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0xB1>(v[u]);
+  }
+  if (LH >= 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x4E>(v[u]);
+  }
+  if (LH >= 8) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x141>(v[u]);
+  }
+  if (LH >= 16) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x140>(v[u]);
+  }
+  for (int off = 16; off < LH; off <<= 1) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], off);
+  }
+}
+
+__device__ __forceinline__ float head_sum1(float v, int LH) {
+  if (LH >= 2) v = dpp_add_b<0xB1>(v);
+  if (LH >= 4) v = dpp_add_b<0x4E>(v);
+  if (LH >= 8) v = dpp_add_b<0x141>(v);
+  if (LH >= 16) v = dpp_add_b<0x140>(v);
+  for (int off = 16; off < LH; off <<= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+struct GatBwdLds {
+  int per, spad, col_off, row_off, blk_off, a_off, t_off, vec_off, ds_off, flag_off, total;
+};
+__host__ __device__ inline GatBwdLds gat_bwd_lds_layout(int S, int H, int L, bool vec) {
+  GatBwdLds o;
+  const int G = kWave / L;
+  o.per = 4 * ((S + 255) / 256);
+  o.spad = kWave * o.per;
+  o.col_off = 0;
+  o.row_off = o.col_off + o.spad * 4;
+  o.blk_off = o.row_off + o.spad * 4;
+  o.a_off = o.blk_off + ((o.spad + 15) & ~15);
+  o.t_off = o.a_off + o.spad * H * 4;
+  o.vec_off = o.t_off + o.spad * H * 4;
+  o.ds_off = o.vec_off + (vec ? 2 * G * 8 * L * 4 : 0);
+  o.flag_off = o.ds_off + 2 * G * L * 4;
+  o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
+  return o;
+}
+
+// one finished row: the vector (VEC) and the head's scalar
+template <bool VEC>
+__device__ __forceinline__ void bwd_row_store(const GatBwdArgs& a, int64_t row, int f0, int head, bool leader,
+                                              const float (&acc)[8], float ds) {
+  if (VEC) {
+    half8_t h;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = half_t(acc[i]);
+    *reinterpret_cast<half8_t*>(a.Y + row * a.ldy + f0) = h;
+  }
+  if (leader) {
+    if (a.dsum_f32) a.dsum_f32[row * a.H + head] = ds;
+    else a.dsum[row * a.H + head] = half_t(ds);
+  }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void bwd_stage_store(const GatBwdArgs& a, int64_t slot, int f0, int head, bool leader,
+                                                const float (&acc)[8], float ds) {
+  if (VEC) {
+    half8_t h;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = half_t(acc[i]);
+    *reinterpret_cast<half8_t*>(a.staging + slot * a.stage_ld + f0) = h;
+  }
+  if (leader) a.stage_ds[(slot * a.H + head) * 2] = ds;
+}
+
+template <int L, bool OFF32, bool VEC>
+__global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
+  constexpr int G = kWave / L;
+  constexpr int VECF = 8 * L;
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int head = f0c / a.D;
+  const bool leader = active && (f0 % a.D) == 0;
+  const int LH = a.D / 8;
+  const int S = a.S;
+  const GatBwdLds lay = gat_bwd_lds_layout(S, a.H, L, VEC);
+  unsigned char* base = smem + size_t(wave) * lay.total;
+  int* s_col = reinterpret_cast<int*>(base + lay.col_off);
+  int* s_row = reinterpret_cast<int*>(base + lay.row_off);
+  int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
+  float* s_a = reinterpret_cast<float*>(base + lay.a_off);    // [spad][H]: alpha, negated where the score is <= 0
+  float* s_t = reinterpret_cast<float*>(base + lay.t_off);    // [spad][H]: t of the destination vertex
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VECF] parked vectors (VEC)
+  float* m_ds = reinterpret_cast<float*>(base + lay.ds_off);    // [2*G][L] parked ds sums, per lane
+  int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);
+  int* m_hrow = m_flag + G;
+  int* m_trow = m_hrow + G;
+
+  const int wpb = int(blockDim.x) / kWave;  // 4 waves per workgroup, fewer when the heads' LDS tables are large
+  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
+  const int64_t seg = wid;
+  const bool valid = seg < a.nseg;
+  const int64_t e0 = seg * S;
+  const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
+  const int per = lay.per, spad = lay.spad;
+  int row_lo = 0, row_hi = -1;
+  bool seg_left_open = false, seg_right_open = false;
+  if (valid) {
+    row_lo = a.seg_lo[seg];
+    row_hi = a.seg_hi[seg];
+    seg_left_open = int64_t(a.rowptr[row_lo]) < e0;
+    seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
+  }
+
+  // ---- phase 1: column ids, row ids, then per (edge, head) the attention weight with the LeakyReLU branch in
+  // its sign, and t of the destination vertex
+  for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
+  if (lane < G) m_flag[lane] = 0;
+  seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
+  for (int i = lane; i < spad; i += kWave) {
+    const bool in = i < n;
+    const int c = s_col[i];
+    const int r = in ? s_row[i] : 0;
+    const int64_t dst = a.dst_is_col ? c : r, src = a.dst_is_col ? r : c;
+    for (int h = 0; h < a.H; ++h) {
+      float av = 0.f, tv = 0.f;
+      if (in) {
+        const float4 v = a.vtab[dst * a.H + h];
+        const float sc = v.x + a.er[src * a.H + h];
+        const float alpha = __expf((sc > 0.f ? sc : a.slope * sc) - v.y);
+        av = sc > 0.f ? alpha : -alpha;
+        tv = v.z;
+      }
+      s_a[i * a.H + h] = av;
+      s_t[i * a.H + h] = tv;
+    }
+    if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
+  }
+  wave_sync();
+
+  // ---- phase 2
+  const int C = 4 * ((S + 4 * G - 1) / (4 * G));
+  const int c0 = g * C < n ? g * C : n;
+  const int c1 = c0 + C < n ? c0 + C : n;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float dsv = 0.f;
+  int cur = -1;
+  bool lo = false;
+  half2_t ur[4];  // this lane's slice of the row-side vector
+  auto load_row_vec = [&](int r) {
+    const half8_t t = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ur[q][0] = active ? t[2 * q] : half_t(0);
+      ur[q][1] = active ? t[2 * q + 1] : half_t(0);
+    }
+  };
+  auto flush = [&](bool ro) {
+    if (!lo && !ro) {
+      if (active) bwd_row_store<VEC>(a, cur, f0, head, leader, acc, dsv);
+    } else {
+      const int slot = lo ? 2 * g : 2 * g + 1;
+      if (VEC && active) {
+        float* dst = m_vec + slot * VECF + f0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = acc[i];
+      }
+      m_ds[slot * L + l] = dsv;
+      if (l == 0) {
+        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
+        if (lo) m_hrow[g] = cur;
+        else m_trow[g] = cur;
+      }
+    }
+  };
+  auto gather = [&](int c) -> half8_t {
+    if (OFF32) {
+      const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
+      return *reinterpret_cast<const half8_t*>(reinterpret_cast<const char*>(a.X) + boff);
+    }
+    return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
+  };
+
+  if (c0 < c1) {
+    cur = s_row[c0];
+    lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
+    load_row_vec(cur);
+  }
+  for (int i = c0; i < c1; i += 4) {
+    const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
+    const int blk = s_blk[i >> 2];
+    half8_t x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
+    float av[4], tv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      av[u] = s_a[(i + u) * a.H + head];
+      tv[u] = s_t[(i + u) * a.H + head];
+    }
+    auto dots = [&](float (&d)[4]) {  // <row-side vector, gathered vector> per head, on every lane of the head
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float p = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          half2_t xv;
+          xv[0] = x[u][2 * q];
+          xv[1] = x[u][2 * q + 1];
+          p = __builtin_amdgcn_fdot2(ur[q], xv, p, false);
+        }
+        d[u] = p;
+      }
+      head_sum4(d, LH);
+    };
+    if (blk == cur) {
+      float d[4];
+      dots(d);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float alpha = fabsf(av[u]);
+        dsv += alpha * (d[u] - tv[u]) * (av[u] > 0.f ? 1.f : a.slope);
+        if (VEC) {
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[q] = fmaf(alpha, float(x[u][q]), acc[q]);
+        }
+      }
+    } else {
+      // rows change inside these four edges: the dot products need the row-side vector of each edge's own
+      // row, so they are formed edge by edge (all lanes of the group take the same path)
+      const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i + u < c1) {
+          if (rows[u] != cur) {
+            flush(false);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+            dsv = 0.f;
+            cur = rows[u];
+            lo = false;
+            load_row_vec(cur);
+          }
+          float p = 0.f;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            half2_t xv;
+            xv[0] = x[u][2 * q];
+            xv[1] = x[u][2 * q + 1];
+            p = __builtin_amdgcn_fdot2(ur[q], xv, p, false);
+          }
+          p = head_sum1(p, LH);
+          const float alpha = fabsf(av[u]);
+          dsv += alpha * (p - tv[u]) * (av[u] > 0.f ? 1.f : a.slope);
+          if (VEC) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(alpha, float(x[u][q]), acc[q]);
+          }
+        }
+      }
+    }
+  }
+  if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
+  wave_sync();
+
+  // ---- merge: group 0 sews the parked pieces together in chunk order
+  if (valid && g == 0) {
+    float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float rds = 0.f;
+    bool open = false, from_before = false;
+    int run_row = -1;
+    for (int gg = 0; gg < G; ++gg) {
+      const int fl = m_flag[gg];
+      if (fl & 1) {
+        if (VEC) {
+          const float* src = m_vec + (2 * gg) * VECF + f0c;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] += src[i];
+        }
+        rds += m_ds[(2 * gg) * L + l];
+        if (gg == 0) {
+          from_before = true;
+          open = true;
+          run_row = m_hrow[0];
+        }
+        if (!(fl & 2)) {
+          if (active) {
+            if (from_before) bwd_stage_store<VEC>(a, 2 * seg, f0, head, leader, run, rds);
+            else bwd_row_store<VEC>(a, run_row, f0, head, leader, run, rds);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] = 0.f;
+          rds = 0.f;
+          open = false;
+          from_before = false;
+        }
+      }
+      if (fl & 4) {
+        if (VEC) {
+          const float* src = m_vec + (2 * gg + 1) * VECF + f0c;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run[i] = src[i];
+        }
+        rds = m_ds[(2 * gg + 1) * L + l];
+        run_row = m_trow[gg];
+        open = true;
+        from_before = false;
+      }
+    }
+    if (open && active) bwd_stage_store<VEC>(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, run, rds);
+  }
+
+  // ---- this wave's share of the empty rows
+  const int64_t nw = int64_t(gridDim.x) * wpb;
+  const int rpw = int((a.nrows + nw - 1) / nw);
+  const int64_t r0 = wid * rpw;
+  const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
+  if (active) {
+    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int64_t r = r0 + g; r < r1; r += G)
+      if (a.rowptr[r] == a.rowptr[r + 1]) bwd_row_store<VEC>(a, r, f0, head, leader, zero, 0.f);
+  }
+}
+
+// Follow-up kernel: sums the staged pieces of every row that crosses a segment border, in segment order.
+template <int L, bool VEC>
+__global__ __launch_bounds__(kBlock) void gat_bwd_finish_kernel(GatBwdArgs a) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int head = f0c / a.D;
+  const bool leader = active && (f0 % a.D) == 0;
+  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  if (i0 >= a.n_split) return;
+  const int64_t idx = i0 + g;
+  int r = 0, sa = 0, sb = -1;
+  if (idx < a.n_split) {
+    r = a.split_row[idx];
+    sa = a.split_lo[idx];
+    sb = a.split_hi[idx];
+  }
+  auto take = [&](float (&acc)[8], float& ds, int64_t slot) {
+    if (VEC) {
+      const half8_t o = *reinterpret_cast<const half8_t*>(a.staging + slot * a.stage_ld + f0c);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += float(o[i]);
+    }
+    ds += a.stage_ds[(slot * a.H + head) * 2];
+  };
+  if (idx < a.n_split && sb - sa <= 8) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float ds = 0.f;
+    take(acc, ds, 2 * int64_t(sa) + 1);
+    for (int64_t k = int64_t(sa) + 1; k <= sb; ++k) take(acc, ds, 2 * k);
+    if (active) bwd_row_store<VEC>(a, r, f0, head, leader, acc, ds);
+  }
+  for (int j = 0; j < G; ++j) {
+    const int rj = __shfl(r, j * L), sj = __shfl(sa, j * L), ej = __shfl(sb, j * L);
+    if (ej - sj <= 8) continue;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float ds = 0.f;
+    if (g == 0) take(acc, ds, 2 * int64_t(sj) + 1);
+    for (int64_t k = int64_t(sj) + 1 + g; k <= ej; k += G) take(acc, ds, 2 * k);
+#pragma unroll
+    for (int off = L; off < kWave; off <<= 1) {
+      if (VEC) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += __shfl_xor(acc[i], off);
+      }
+      ds += __shfl_xor(ds, off);
+    }
+    if (g == 0 && active) bwd_row_store<VEC>(a, rj, f0, head, leader, acc, ds);
+  }
+}
+
+// Column-blocked plans: adds the nb partial rows (fp16 vectors, fp32 ds sums) of every row.
+template <int L, bool VEC>
+__global__ __launch_bounds__(kBlock) void gat_bwd_block_sum_kernel(GatBwdArgs a, const half_t* __restrict__ part,
+                                                                   int part_ld, const float* __restrict__ part_ds,
+                                                                   int64_t ds_stride, int nb) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const int64_t r = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  if (r >= a.nrows || f0 >= a.F) return;
+  const int head = f0 / a.D;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float ds = 0.f;
+  for (int b = 0; b < nb; ++b) {
+    if (VEC) {
+      const half8_t o = *reinterpret_cast<const half8_t*>(part + (int64_t(b) * a.nrows + r) * part_ld + f0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += float(o[i]);
+    }
+    ds += part_ds[b * ds_stride + r * a.H + head];
+  }
+  bwd_row_store<VEC>(a, r, f0, head, (f0 % a.D) == 0, acc, ds);
+}
+
+// vtab[i,h] = (el[i,h], lse[i,h], t[i,h] = <dOut[i,h], out[i,h]>, 0) for every destination vertex
+template <int L>
+__global__ __launch_bounds__(kBlock) void gat_vtab_kernel(const float* __restrict__ el, const float* __restrict__ lse,
+                                                           const half_t* __restrict__ dOut, int64_t lddo,
+                                                           const half_t* __restrict__ out, int64_t ldo, int nv, int F, int D,
+                                                           int H, float4* __restrict__ vtab) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int f0 = 8 * l;
+  const bool active = f0 < F;
+  const int LH = D / 8;
+  const int64_t v = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  float p = 0.f;
+  if (active && v < nv) {
+    const half8_t x = *reinterpret_cast<const half8_t*>(dOut + v * lddo + f0);
+    const half8_t y = *reinterpret_cast<const half8_t*>(out + v * ldo + f0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p = fmaf(float(x[i]), float(y[i]), p);
+  }
+  for (int off = 1; off < LH; off <<= 1) p += __shfl_xor(p, off);
+  if (active && v < nv && (l % LH) == 0) {
+    const int64_t k = v * H + l / LH;
+    vtab[k] = make_float4(el[k], lse[k], p, 0.f);
+  }
+}
+
+template <bool OFF32, bool VEC>
+static void launch_bwd_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const GatBwdArgs& a) {
+  switch (L) {
+    case 1: gat_bwd_seg_kernel<1, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 2: gat_bwd_seg_kernel<2, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 4: gat_bwd_seg_kernel<4, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 8: gat_bwd_seg_kernel<8, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 16: gat_bwd_seg_kernel<16, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 32: gat_bwd_seg_kernel<32, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    default: gat_bwd_seg_kernel<64, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+  }
+}
+
+template <bool VEC>
+static void launch_bwd_finish(int L, dim3 grid, hipStream_t s, const GatBwdArgs& a) {
+  switch (L) {
+    case 1: gat_bwd_finish_kernel<1, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    case 2: gat_bwd_finish_kernel<2, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: gat_bwd_finish_kernel<4, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    case 8: gat_bwd_finish_kernel<8, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    case 16: gat_bwd_finish_kernel<16, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    case 32: gat_bwd_finish_kernel<32, VEC><<<grid, kBlock, 0, s>>>(a); break;
+    default: gat_bwd_finish_kernel<64, VEC><<<grid, kBlock, 0, s>>>(a); break;
+  }
+}
+
+template <bool VEC>
+static void launch_bwd_block_sum(int L, dim3 grid, hipStream_t s, const GatBwdArgs& a, const half_t* part, int part_ld,
+                                 const float* part_ds, int64_t ds_stride, int nb) {
+  switch (L) {
+    case 1: gat_bwd_block_sum_kernel<1, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    case 2: gat_bwd_block_sum_kernel<2, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    case 4: gat_bwd_block_sum_kernel<4, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    case 8: gat_bwd_block_sum_kernel<8, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    case 16: gat_bwd_block_sum_kernel<16, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    case 32: gat_bwd_block_sum_kernel<32, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+    default: gat_bwd_block_sum_kernel<64, VEC><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_ds, ds_stride, nb); break;
+  }
+}
+
+static void launch_vtab(int L, dim3 grid, hipStream_t s, const float* el, const float* lse, const half_t* dOut, int64_t lddo,
+                        const half_t* out, int64_t ldo, int nv, int F, int D, int H, float4* vtab) {
+  switch (L) {
+    case 1: gat_vtab_kernel<1><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 2: gat_vtab_kernel<2><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 4: gat_vtab_kernel<4><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 8: gat_vtab_kernel<8><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 16: gat_vtab_kernel<16><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 32: gat_vtab_kernel<32><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    default: gat_vtab_kernel<64><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+  }
+}
+
+// one pass (segment kernel + follow-up) over the graph in `a` with the segment arrays of plan q
+template <bool VEC>
+static hgnn_status run_bwd_segments(const hgnn_plan* q, GatBwdArgs a, int ncols, hipStream_t s) {
+  a.seg_lo = q->seg_row_lo;
+  a.seg_hi = q->seg_row_hi;
+  a.S = q->S;
+  a.nseg = q->nseg;
+  a.staging = reinterpret_cast<half_t*>(q->staging);
+  a.stage_ds = q->stage_mz;
+  a.stage_ld = q->max_F;
+  a.split_row = q->split_row;
+  a.split_lo = q->split_seg_lo;
+  a.split_hi = q->split_seg_hi;
+  a.n_split = q->n_split;
+  const int L = pow2_at_least(a.F / 8);
+  const size_t per_wave = size_t(gat_bwd_lds_layout(a.S, a.H, L, VEC).total);
+  int wpb = kWavesPerBlock;  // waves per workgroup: as many of 4, 2, 1 as fit 64 KB of LDS
+  while (wpb > 1 && per_wave * wpb > 65536) wpb >>= 1;
+  const size_t lds = per_wave * wpb;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_gat_backward_fused: seg_edges = %d with H = %d needs %zu bytes of LDS per wavefront (limit 65536)", a.S,
+               a.H, lds);
+  const int64_t nblk = ceil_div(q->nseg, wpb);
+  dim3 grid(unsigned(nblk > 0 ? nblk : 1));
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  if (off32) launch_bwd_seg<true, VEC>(L, grid, wpb * kWave, lds, s, a);
+  else launch_bwd_seg<false, VEC>(L, grid, wpb * kWave, lds, s, a);
+  HGNN_LAUNCH_CHECK("gat_bwd_seg_kernel");
+  if (a.n_split > 0) {
+    launch_bwd_finish<VEC>(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
+    HGNN_LAUNCH_CHECK("gat_bwd_finish_kernel");
+  }
+  return HGNN_OK;
+}
+
+// a pass over graph gg with plan q (column-blocked or not)
+template <bool VEC>
+static hgnn_status run_bwd_pass(const hgnn_plan* q, const hgnn_csr* gg, GatBwdArgs a, hipStream_t s) {
+  if (q->nb <= 1) return run_bwd_segments<VEC>(q, a, gg->ncols, s);
+  const size_t V = size_t(q->nrows);
+  const int64_t ds_stride = int64_t(V) * q->max_H * 2;
+  for (int b = 0; b < q->nb; ++b) {
+    const hgnn_plan* sub = q->sub[size_t(b)];
+    GatBwdArgs ab = a;
+    ab.rowptr = q->brp + size_t(b) * (V + 1);
+    ab.col = q->bcol + q->boff[size_t(b)];
+    ab.nnz = sub->nnz;
+    ab.Y = reinterpret_cast<half_t*>(q->bstage) + size_t(b) * V * size_t(q->max_F);
+    ab.ldy = q->max_F;
+    ab.dsum = nullptr;
+    ab.dsum_f32 = q->bsum + size_t(b) * size_t(ds_stride);
+    hgnn_status st = run_bwd_segments<VEC>(sub, ab, gg->ncols, s);
+    if (st != HGNN_OK) return st;
+  }
+  const int L = pow2_at_least(a.F / 8);
+  launch_bwd_block_sum<VEC>(L, dim3(unsigned(ceil_div(gg->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, a,
+                            reinterpret_cast<const half_t*>(q->bstage), q->max_F, q->bsum, ds_stride, q->nb);
+  HGNN_LAUNCH_CHECK("gat_bwd_block_sum_kernel");
+  return HGNN_OK;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt,
+                                               const hgnn_plan* pt, int32_t H, int32_t D, const hgnn_half* U, int64_t ldu,
+                                               const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r,
+                                               float neg_slope, const hgnn_half* out, int64_t ldo, const float* lse,
+                                               const hgnn_half* dOut, int64_t lddo, hgnn_half* dV, int64_t lddv,
+                                               hgnn_half* d_el, hgnn_half* d_er, void* stream) {
+  clear_error();
+  const char* who = "hgnn_gat_backward_fused";
+  hgnn_status st = check_csr_args(g, who);
+  if (st != HGNN_OK) return st;
+  st = check_csr_args(gt, who);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(p != nullptr && pt != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
+  HGNN_REQUIRE(p->nrows == g->nrows && p->ncols == g->ncols && p->nnz == g->nnz, HGNN_EINVAL,
+               "%s: plan p was built for another graph than g", who);
+  HGNN_REQUIRE(pt->nrows == gt->nrows && pt->ncols == gt->ncols && pt->nnz == gt->nnz, HGNN_EINVAL,
+               "%s: plan pt was built for another graph than gt", who);
+  HGNN_REQUIRE(gt->nrows == g->ncols && gt->ncols == g->nrows && gt->nnz == g->nnz, HGNN_EINVAL,
+               "%s: gt is not the transpose of g", who);
+  HGNN_REQUIRE(g->eid == nullptr, HGNN_EUNSUPPORTED, "%s: g must not carry an edge-id map", who);
+  HGNN_REQUIRE(H >= 1 && D >= 1 && int64_t(H) * D <= 512, HGNN_EINVAL, "%s: H = %d, D = %d out of range", who, H, D);
+  const int F = H * D;
+  HGNN_REQUIRE(H <= p->max_H && F <= p->max_F && H <= pt->max_H && F <= pt->max_F, HGNN_EINVAL,
+               "%s: H = %d / F = %d exceed a plan's max_H / max_F", who, H, F);
+  HGNN_REQUIRE(ldu >= F && ldv >= F && ldo >= F && lddo >= F && lddv >= F, HGNN_EINVAL,
+               "%s: leading dimension smaller than F", who);
+  if (g->nrows == 0 && g->ncols == 0) return HGNN_OK;
+  HGNN_REQUIRE(U && Vt && a_l && a_r && out && lse && dOut && dV && d_el && d_er, HGNN_EINVAL, "%s: NULL argument", who);
+  HGNN_REQUIRE(ldo % 8 == 0 && lddo % 8 == 0 && lddv % 8 == 0 && aligned16(out) && aligned16(dOut) && aligned16(dV),
+               HGNN_EUNSUPPORTED, "%s: needs ld %% 8 == 0 and 16-byte aligned out, dOut, dV", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // per-vertex scalars in plan p's scratch: el, er, then (el, lse, t) packed per destination vertex
+  st = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, who);
+  if (st != HGNN_OK) return st;
+  const int L = pow2_at_least(F / 8), G = kWave / L;
+  const float* el = p->vscratch;
+  const float* er = p->vscratch + size_t(g->nrows) * H;
+  float4* vtab = reinterpret_cast<float4*>(p->vtab);
+  if (g->nrows > 0) {
+    launch_vtab(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, el, lse,
+                reinterpret_cast<const half_t*>(dOut), lddo, reinterpret_cast<const half_t*>(out), ldo, g->nrows, F, D, H,
+                vtab);
+    HGNN_LAUNCH_CHECK("gat_vtab_kernel");
+  }
+  GatBwdArgs a{};
+  a.F = F;
+  a.H = H;
+  a.D = D;
+  a.slope = neg_slope;
+  a.vtab = vtab;
+  a.er = er;
+  // transposed pass: rows j (sources), gathers dOut_i; dV_j and d_er_j
+  if (gt->nrows > 0) {
+    GatBwdArgs t = a;
+    t.rowptr = gt->rowptr;
+    t.col = gt->col;
+    t.nnz = gt->nnz;
+    t.nrows = gt->nrows;
+    t.X = reinterpret_cast<const half_t*>(dOut);
+    t.ldx = lddo;
+    t.R = reinterpret_cast<const half_t*>(Vt);
+    t.ldr = ldv;
+    t.Y = reinterpret_cast<half_t*>(dV);
+    t.ldy = lddv;
+    t.dsum = reinterpret_cast<half_t*>(d_er);
+    t.dst_is_col = 1;
+    st = run_bwd_pass<true>(pt, gt, t, s);
+    if (st != HGNN_OK) return st;
+  }
+  // forward pass: rows i (destinations), gathers h_j; d_el_i only
+  if (g->nrows > 0) {
+    GatBwdArgs f = a;
+    f.rowptr = g->rowptr;
+    f.col = g->col;
+    f.nnz = g->nnz;
+    f.nrows = g->nrows;
+    f.X = reinterpret_cast<const half_t*>(Vt);
+    f.ldx = ldv;
+    f.R = reinterpret_cast<const half_t*>(dOut);
+    f.ldr = lddo;
+    f.dsum = reinterpret_cast<half_t*>(d_el);
+    f.dst_is_col = 0;
+    st = run_bwd_pass<false>(p, g, f, s);
+    if (st != HGNN_OK) return st;
+  }
+  return HGNN_OK;
+}

@@ -227,6 +227,7 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
     if (st != HGNN_OK) return st;
     size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
     if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
+    if (g->nrows > 0) HGNN_HIP(hipMalloc(&p->vtab, sizeof(float) * 4 * size_t(g->nrows) * size_t(p->max_H)));
   }
   HGNN_HIP(hipStreamSynchronize(s));
   return HGNN_OK;
@@ -306,6 +307,7 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->staging);
   (void)hipFree(p->stage_mz);
   (void)hipFree(p->vscratch);
+  (void)hipFree(p->vtab);
   (void)hipFree(p->goff);
   (void)hipFree(p->moff);
   (void)hipFree(p->grp_row);

@@ -137,3 +137,106 @@ def test_gat_forward_fused_full_configs(hgnn, dev, maker, nb):
     compare(f"{w.name} gat fused", got[rows], ref, sabs)
     check_lse(f"{w.name} gat fused", got_lse[rows], ref_lse, np.diff(sub_ptr))
     hgnn.hgnn_plan_destroy(p)
+
+
+# ------------------------------------------------------------------ fused backward
+def gat_backward_check(hgnn, dev, rowptr, col, ncols, U, Vt, a_l, a_r, dOut, H, S, nb, name, rows=None, cols=None):
+    """Forward + backward through the C ABI; compares dV, d_el, d_er with the oracle (on sampled rows/columns when given)."""
+    V = rowptr.size - 1
+    F = U.shape[1]
+    D = F // H
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, S, F, H, col_blocks=nb)
+    pt = hgnn.hgnn_plan_create(gt, S, F, H, col_blocks=nb)
+    Ud, Vd, ald, ard, dOd = up(U, dev), up(Vt, dev), up(a_l, dev), up(a_r, dev), up(dOut, dev)
+    out = torch.empty((V, F), dtype=torch.float16, device=dev)
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Ud, Vd, ald, ard, out, lse)
+    dV = torch.full((ncols, F), 7.0, dtype=torch.float16, device=dev)
+    d_el = torch.full((V, H), 7.0, dtype=torch.float16, device=dev)
+    d_er = torch.full((ncols, H), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, Ud, Vd, ald, ard, out, lse, dOd, dV, d_el, d_er)
+    got = (down(dV), down(d_el), down(d_er))
+    # deterministic
+    dV2, d_el2, d_er2 = torch.empty_like(dV), torch.empty_like(d_el), torch.empty_like(d_er)
+    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, Ud, Vd, ald, ard, out, lse, dOd, dV2, d_el2, d_er2)
+    for a, b in zip(got, (down(dV2), down(d_el2), down(d_er2))):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
+    return got
+
+
+def bwd_reference(rowptr, col, ncols, U, Vt, a_l, a_r, dOut, H, slope=0.2):
+    """Oracle values plus magnitudes (sum of |terms|) for the tolerance rule."""
+    V, F = U.shape
+    D = F // H
+    dV, d_el, d_er = oracle.gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H, slope=slope)
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    el = (U.astype(np.float64).reshape(V, H, D) * a_l.astype(np.float64).reshape(H, D)).sum(-1)
+    er = (Vt.astype(np.float64).reshape(ncols, H, D) * a_r.astype(np.float64).reshape(H, D)).sum(-1)
+    raw = el[row] + er[col]
+    e = np.where(raw > 0, raw, slope * raw)
+    alpha = oracle.edge_softmax(rowptr, e)
+    dO, V64 = dOut.astype(np.float64), Vt.astype(np.float64)
+    dalpha_abs = (np.abs(dO[row]) * np.abs(V64[col])).reshape(-1, H, D).sum(-1)
+    t_abs = oracle.edge_rowsum(rowptr, alpha * dalpha_abs)
+    ds_abs = alpha * (dalpha_abs + t_abs[row])
+    dV_abs = np.zeros((ncols, F))
+    np.add.at(dV_abs, col, np.repeat(alpha, D, axis=1) * np.abs(dO[row]))
+    return (dV, dV_abs), (d_el, oracle.edge_rowsum(rowptr, ds_abs)), (d_er, oracle.edge_colsum(rowptr, col, ds_abs, ncols))
+
+
+BWD_CASES = [(1, 64, 256, 1), (4, 16, 256, 1), (8, 8, 128, 1), (2, 32, 64, 1), (1, 8, 7, 1), (1, 128, 256, 1),
+             (1, 64, 256, 3), (4, 16, 100, 4)]
+
+
+@pytest.mark.parametrize("H,D,S,nb", BWD_CASES)
+def test_gat_backward_fused_shapes(hgnn, dev, H, D, S, nb):
+    print(f"gat fused backward H={H} D={D} S={S} nb={nb}", flush=True)
+    V, ncols = 900, 1000
+    F = H * D
+    rowptr, col = rand_graph(V, ncols, 12, H * 100 + D + S, hubs=((5, 4000), (700, 777), (899, 300)), empties=(0, 6, 898))
+    r = np.random.default_rng(H * 7 + D)
+    U, Vt, dOut = f16(r.standard_normal((V, F))), f16(r.standard_normal((ncols, F))), f16(r.standard_normal((V, F)))
+    a_l, a_r = f16(0.2 * r.standard_normal(F)), f16(0.2 * r.standard_normal(F))
+    (dV, dV_abs), (d_el, el_abs), (d_er, er_abs) = bwd_reference(rowptr, col, ncols, U, Vt, a_l, a_r, dOut, H)
+    g_dV, g_el, g_er = gat_backward_check(hgnn, dev, rowptr, col, ncols, U, Vt, a_l, a_r, dOut, H, S, nb, "bwd")
+    compare("dV", g_dV, dV, dV_abs)
+    compare("d_el", g_el, d_el, el_abs, rel_l2=2e-2)  # cancelling sums: the L2 norm of the result is far below that of its terms
+    compare("d_er", g_er, d_er, er_abs, rel_l2=2e-2)
+
+
+@pytest.mark.parametrize("maker,nb", [(wl.gat_rmat, 1), (wl.dense_degree, 0)])
+def test_gat_backward_fused_full_configs(hgnn, dev, maker, nb):
+    """Configs 3 and 5 at full size; the oracle runs on the sub-graphs of sampled rows and of sampled columns."""
+    w = maker()
+    print(f"gat fused backward full config {w.name}", flush=True)
+    feat = w.tensors["h"] if "h" in w.tensors else w.tensors["X"]
+    dOut = w.tensors["dOut"] if "dOut" in w.tensors else w.tensors["dY"]
+    H = w.H
+    a_l, a_r = w.tensors["a_l"], w.tensors["a_r"]
+    g_dV, g_el, g_er = gat_backward_check(hgnn, dev, w.rowptr, w.col, w.V, feat, feat, a_l, a_r, dOut, H, 256, nb, w.name)
+    assert np.all(np.isfinite(g_dV)) and np.all(np.isfinite(g_el)) and np.all(np.isfinite(g_er))
+    # d_el on sampled rows: a sub-graph with those rows and all columns
+    rows = sample_rows(w.rowptr, 200, 5)
+    sub_ptr = np.concatenate([[0], np.cumsum(np.diff(w.rowptr)[rows])]).astype(np.int32)
+    sub_col = np.concatenate([w.col[w.rowptr[r]:w.rowptr[r + 1]] for r in rows]).astype(np.int32)
+    (_, _), (d_el, el_abs), (_, _) = bwd_reference(sub_ptr, sub_col, w.V, feat[rows], feat, a_l, a_r, dOut[rows], H)
+    compare(f"{w.name} d_el", g_el[rows], d_el, el_abs, rel_l2=2e-2)
+    # dV and d_er on sampled columns: every row that has one of them as neighbour is needed in full (softmax),
+    # so the columns are drawn among the neighbours of a few rows and only those rows' contribution is... not enough:
+    # take the full rows of all in-neighbours of the sampled columns instead
+    rng_ = np.random.default_rng(3)
+    cols = np.unique(rng_.integers(0, w.V, size=12)).astype(np.int64)
+    row_of = np.repeat(np.arange(w.V), np.diff(w.rowptr))
+    need = np.unique(row_of[np.isin(w.col, cols)])
+    if need.size > 40000:  # keep the oracle's work bounded on the dense-degree graph
+        cols = cols[:3]
+        need = np.unique(row_of[np.isin(w.col, cols)])
+    sub_ptr = np.concatenate([[0], np.cumsum(np.diff(w.rowptr)[need])]).astype(np.int32)
+    sub_col = np.concatenate([w.col[w.rowptr[r]:w.rowptr[r + 1]] for r in need]).astype(np.int32)
+    (dV, dV_abs), (_, _), (d_er, er_abs) = bwd_reference(sub_ptr, sub_col, w.V, feat[need], feat, a_l, a_r, dOut[need], H)
+    compare(f"{w.name} dV", g_dV[cols], dV[cols], dV_abs[cols])
+    compare(f"{w.name} d_er", g_er[cols], d_er[cols], er_abs[cols], rel_l2=2e-2)
