@@ -271,8 +271,14 @@ def main():
         t_f = time_one(lambda: hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse))
         t_a = time_one(lambda: hgnn.hgnn_gat_alpha(g, plan, H, D, X, X, a_l, a_r, lse, alpha))
         three = float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in ("gat_score", "edge_softmax", "gat_spmm_fwd")))
+        five = float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in (
+            "gat_spmm_bwd", "sddmm_dot", "edge_softmax_bwd", "score_bwd_rowsum", "score_bwd_colsum")))
+        hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse)
+        t_b = time_one(lambda: hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, X, X, a_l, a_r, out, lse, dY, dh,
+                                                            d_el, d_er))
         fused = {"gat_forward_fused_ms": round(t_f, 4), "three_call_forward_ms": round(three, 4),
-                 "alpha_from_lse_ms": round(t_a, 4)}
+                 "gat_backward_fused_ms": round(t_b, 4), "five_call_backward_ms": round(five, 4),
+                 "gat_fwd_bwd_fused_ms": round(t_f + t_b, 4), "alpha_from_lse_ms": round(t_a, 4)}
 
     variants = None
     if args.variants:

@@ -10,7 +10,10 @@
 //   forward pass    (rows i, gathers h_j):     d_el_i = sum_j ds_ij
 // The destination vertex's scalars (el, lse, t) sit in one 16-byte entry per (vertex, head), so the
 // transposed pass fetches them with a single gather from a table that stays in L2; the weight and
-// the mask are formed once per edge and wave while the segment is staged.
+// the mask are formed once per edge and wave while the segment is staged.  Because the sum of ds over
+// any piece of a row is linear in the gathered vectors, no dot product is formed per edge: the
+// kernels accumulate the mask-weighted vector sum and one scalar, and take the dot product with the
+// row-side vector once per piece.
 #include "common.h"
 
 namespace hgnn {
@@ -48,31 +51,10 @@ __device__ __forceinline__ float dpp_add_b(float v) {
   return v + __int_as_float(t);
 }
 
-// all-reduce (sum) of four values over the LH consecutive, LH-aligned lanes of a head (LH a power of two):
-// quad_perm exchanges, then mirrors inside 8 and 16 lanes, then cross-row exchanges
-__device__ __forceinline__ void head_sum4(float (&v)[4], int LH) {
-  if (LH >= 2) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0xB1>(v[u]);
-  }
-  if (LH >= 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x4E>(v[u]);
-  }
-  if (LH >= 8) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x141>(v[u]);
-  }
-  if (LH >= 16) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add_b<0x140>(v[u]);
-  }
-  for (int off = 16; off < LH; off <<= 1) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], off);
-  }
-}
-
+// all-reduce (sum) of a value over the LH consecutive, LH-aligned lanes of a head (LH a power of two):
+// quad_perm exchanges [1,0,3,2] and [2,3,0,1], then mirrors inside 8 and 16 lanes (after the quads are
+// summed a mirror pairs every lane with one of the other quad / half, whose sum is the same on all its
+// lanes), then cross-row exchanges
 __device__ __forceinline__ float head_sum1(float v, int LH) {
   if (LH >= 2) v = dpp_add_b<0xB1>(v);
   if (LH >= 4) v = dpp_add_b<0x4E>(v);
@@ -134,7 +116,6 @@ template <int L, bool OFF32, bool VEC>
 __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   constexpr int G = kWave / L;
   constexpr int VECF = 8 * L;
-  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
@@ -151,7 +132,7 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   float* s_a = reinterpret_cast<float*>(base + lay.a_off);    // [spad][H]: alpha, negated where the score is <= 0
-  float* s_t = reinterpret_cast<float*>(base + lay.t_off);    // [spad][H]: t of the destination vertex
+  float* s_t = reinterpret_cast<float*>(base + lay.t_off);    // [spad][H]: alpha * mask * t of the destination vertex
   float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VECF] parked vectors (VEC)
   float* m_ds = reinterpret_cast<float*>(base + lay.ds_off);    // [2*G][L] parked ds sums, per lane
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);
@@ -175,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   }
 
   // ---- phase 1: column ids, row ids, then per (edge, head) the attention weight with the LeakyReLU branch in
-  // its sign, and t of the destination vertex
+  // its sign, and u = alpha * mask * t of the destination vertex
   for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
@@ -185,39 +166,43 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
     const int r = in ? s_row[i] : 0;
     const int64_t dst = a.dst_is_col ? c : r, src = a.dst_is_col ? r : c;
     for (int h = 0; h < a.H; ++h) {
-      float av = 0.f, tv = 0.f;
+      float av = 0.f, uv = 0.f;
       if (in) {
         const float4 v = a.vtab[dst * a.H + h];
         const float sc = v.x + a.er[src * a.H + h];
         const float alpha = __expf((sc > 0.f ? sc : a.slope * sc) - v.y);
         av = sc > 0.f ? alpha : -alpha;
-        tv = v.z;
+        uv = (sc > 0.f ? alpha : a.slope * alpha) * v.z;
       }
       s_a[i * a.H + h] = av;
-      s_t[i * a.H + h] = tv;
+      s_t[i * a.H + h] = uv;
     }
     if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
   }
   wave_sync();
 
-  // ---- phase 2
+  // ---- phase 2.  The sum of ds over a piece of a row is linear in the gathered vectors:
+  //   sum_k alpha_k m_k (<r, x_k> - t_k) = <r, sum_k alpha_k m_k x_k> - sum_k alpha_k m_k t_k
+  // (r = the row-side vector, m = the LeakyReLU slope of the edge), so the inner loop only accumulates the
+  // mask-weighted vector wacc beside acc and one scalar; the dot product with r and the exchange between
+  // the lanes of a head happen once per piece, when it is flushed.
   const int C = 4 * ((S + 4 * G - 1) / (4 * G));
   const int c0 = g * C < n ? g * C : n;
   const int c1 = c0 + C < n ? c0 + C : n;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float dsv = 0.f;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // sum alpha * x          (VEC)
+  float wacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // sum alpha * m * x
+  float csum = 0.f;                                           // sum alpha * m * t
   int cur = -1;
   bool lo = false;
-  half2_t ur[4];  // this lane's slice of the row-side vector
-  auto load_row_vec = [&](int r) {
-    const half8_t t = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      ur[q][0] = active ? t[2 * q] : half_t(0);
-      ur[q][1] = active ? t[2 * q + 1] : half_t(0);
-    }
-  };
+  half8_t ur = half8_t(0);  // this lane's slice of the current row's row-side vector
+  auto load_row_vec = [&](int r) { ur = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c); };
   auto flush = [&](bool ro) {
+    float d = 0.f;
+    if (active) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) d = fmaf(wacc[q], float(ur[q]), d);
+    }
+    const float dsv = head_sum1(d, LH) - csum;
     if (!lo && !ro) {
       if (active) bwd_row_store<VEC>(a, cur, f0, head, leader, acc, dsv);
     } else {
@@ -242,6 +227,17 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
     }
     return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
   };
+  auto add_edge = [&](float av, float uv, const half8_t& x) {
+    const float alpha = fabsf(av);
+    const float am = av > 0.f ? av : -a.slope * av;
+    csum += uv;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float xf = float(x[q]);
+      if (VEC) acc[q] = fmaf(alpha, xf, acc[q]);
+      wacc[q] = fmaf(am, xf, wacc[q]);
+    }
+  };
 
   if (c0 < c1) {
     cur = s_row[c0];
@@ -254,42 +250,16 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
     half8_t x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
-    float av[4], tv[4];
+    float av[4], uv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       av[u] = s_a[(i + u) * a.H + head];
-      tv[u] = s_t[(i + u) * a.H + head];
+      uv[u] = s_t[(i + u) * a.H + head];
     }
-    auto dots = [&](float (&d)[4]) {  // <row-side vector, gathered vector> per head, on every lane of the head
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        float p = 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          half2_t xv;
-          xv[0] = x[u][2 * q];
-          xv[1] = x[u][2 * q + 1];
-          p = __builtin_amdgcn_fdot2(ur[q], xv, p, false);
-        }
-        d[u] = p;
-      }
-      head_sum4(d, LH);
-    };
     if (blk == cur) {
-      float d[4];
-      dots(d);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float alpha = fabsf(av[u]);
-        dsv += alpha * (d[u] - tv[u]) * (av[u] > 0.f ? 1.f : a.slope);
-        if (VEC) {
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[q] = fmaf(alpha, float(x[u][q]), acc[q]);
-        }
-      }
+      for (int u = 0; u < 4; ++u) add_edge(av[u], uv[u], x[u]);
     } else {
-      // rows change inside these four edges: the dot products need the row-side vector of each edge's own
-      // row, so they are formed edge by edge (all lanes of the group take the same path)
       const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -297,27 +267,16 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
           if (rows[u] != cur) {
             flush(false);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-            dsv = 0.f;
+            for (int q = 0; q < 8; ++q) {
+              acc[q] = 0.f;
+              wacc[q] = 0.f;
+            }
+            csum = 0.f;
             cur = rows[u];
             lo = false;
             load_row_vec(cur);
           }
-          float p = 0.f;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            half2_t xv;
-            xv[0] = x[u][2 * q];
-            xv[1] = x[u][2 * q + 1];
-            p = __builtin_amdgcn_fdot2(ur[q], xv, p, false);
-          }
-          p = head_sum1(p, LH);
-          const float alpha = fabsf(av[u]);
-          dsv += alpha * (p - tv[u]) * (av[u] > 0.f ? 1.f : a.slope);
-          if (VEC) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = fmaf(alpha, float(x[u][q]), acc[q]);
-          }
+          add_edge(av[u], uv[u], x[u]);
         }
       }
     }
