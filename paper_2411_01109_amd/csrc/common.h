@@ -140,6 +140,8 @@ struct hgnn_plan {
   int64_t nseg = 0;     // ceil(nnz / S)
   int32_t n_split = 0;  // rows whose edges span more than one segment
   int32_t n_big = 0;    // rows longer than big_deg (edge softmax hands them to a whole workgroup)
+  int32_t n_mid = 0;    // rows longer than mid_deg and at most big_deg (edge softmax: one wave each)
+  int32_t mid_deg = 0;
   int32_t big_deg = 0;
   int32_t max_F = 0, max_H = 0;
   int32_t* seg_row_lo = nullptr;    // [nseg]
@@ -148,6 +150,7 @@ struct hgnn_plan {
   int32_t* split_seg_lo = nullptr;  // [n_split]
   int32_t* split_seg_hi = nullptr;  // [n_split]
   int32_t* big_row = nullptr;       // [n_big]
+  int32_t* mid_row = nullptr;       // [n_mid]
   hgnn_half* staging = nullptr;     // [2*nseg][max_F]
   float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32

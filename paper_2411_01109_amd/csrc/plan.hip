@@ -90,6 +90,14 @@ struct SplitPred {  // first and last edge of the row fall in different segments
     return e > b && (b / S) != ((e - 1) / S);
   }
 };
+struct MidPred {  // row longer than lo and at most hi
+  const int* rowptr;
+  int lo, hi;
+  __device__ bool operator()(int r) const {
+    const int d = rowptr[r + 1] - rowptr[r];
+    return d > lo && d <= hi;
+  }
+};
 struct BigPred {  // row longer than a threshold
   const int* rowptr;
   int deg;
@@ -225,6 +233,8 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
   if (!sub) {  // a column block's sub-plan only serves the SpMM kernels
     st = compact_rows(BigPred{g->rowptr, p->big_deg}, g->nrows, &p->big_row, &p->n_big, s);
     if (st != HGNN_OK) return st;
+    st = compact_rows(MidPred{g->rowptr, p->mid_deg, p->big_deg}, g->nrows, &p->mid_row, &p->n_mid, s);
+    if (st != HGNN_OK) return st;
     size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
     if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
     if (g->nrows > 0) HGNN_HIP(hipMalloc(&p->vtab, sizeof(float) * 4 * size_t(g->nrows) * size_t(p->max_H)));
@@ -304,6 +314,7 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->split_seg_lo);
   (void)hipFree(p->split_seg_hi);
   (void)hipFree(p->big_row);
+  (void)hipFree(p->mid_row);
   (void)hipFree(p->staging);
   (void)hipFree(p->stage_mz);
   (void)hipFree(p->vscratch);
@@ -341,6 +352,7 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
   p->max_F = max_F;
   p->max_H = max_H;
   p->big_deg = 2048;
+  p->mid_deg = 32;
   hipStream_t s = static_cast<hipStream_t>(stream);
   st = plan_build_arrays(p, g, s, false);
   if (st == HGNN_OK) {

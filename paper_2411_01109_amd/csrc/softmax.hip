@@ -19,6 +19,8 @@ constexpr int kBigBlock = 1024; // threads given to one long row
 struct EdgeRowArgs {
   const int* rowptr;
   const int* big_row;
+  const int* row_list;  // when set, the team kernel takes its rows from this list of n_list rows
+  int n_list;
   const int* eid;
   const half_t* x0;  // forward: e.          backward: alpha.   rowsum: t
   const half_t* x1;  //                      backward: dalpha
@@ -253,7 +255,11 @@ template <int OP, int LR, int H>
 __global__ __launch_bounds__(kBlock) void edge_row_team_kernel(EdgeRowArgs a) {
   constexpr int GR = kWave / LR;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int64_t row = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * GR + lane / LR;
+  int64_t row = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * GR + lane / LR;
+  if (a.row_list) {
+    if (row >= a.n_list) return;
+    row = a.row_list[row];
+  }
   if (row >= a.nrows) return;
   const int beg = a.rowptr[row], end = a.rowptr[row + 1];
   if ((a.skip_above > 0 && end - beg > a.skip_above) || end - beg <= a.skip_below) return;
@@ -341,13 +347,26 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   a.big_row = p ? p->big_row : nullptr;
   // tier 1: sub-wave teams take the rows they can hold in registers; tier 2: a whole wave per row
   // for the rows between that and the plan's long-row threshold; tier 3: a workgroup per long row.
-  const int t1 = (OP == kSum && a.eid) ? LR * 4 : LR * 8 * kKeepVec / H;
+  int t1 = (OP == kSum && a.eid) ? LR * 4 : LR * 8 * kKeepVec / H;
+  // a plan lists the rows between its mid and long thresholds: the wave-per-row tier then walks that list
+  // instead of starting a wave for every row of the graph only to find most of them done
+  const bool mid_list = p && LR < kWave && (big == 0 || big > p->mid_deg);
+  if (mid_list && t1 < p->mid_deg) t1 = p->mid_deg;  // the sub-wave tier takes what the list leaves out
   for (int tier = 0; tier < 2; ++tier) {
     const int lr = tier == 0 ? LR : kWave;
     if (tier == 1 && (LR == kWave || (big > 0 && t1 >= big))) break;
     a.skip_below = tier == 0 ? -1 : t1;
     a.skip_above = (tier == 0 && LR < kWave) ? (big > 0 && big < t1 ? big : t1) : big;
-    dim3 grid(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / lr))));
+    int64_t nrows_tier = g->nrows;
+    a.row_list = nullptr;
+    a.n_list = 0;
+    if (tier == 1 && mid_list) {
+      if (p->n_mid == 0) break;
+      a.row_list = p->mid_row;
+      a.n_list = p->n_mid;
+      nrows_tier = p->n_mid;
+    }
+    dim3 grid(unsigned(ceil_div(nrows_tier, int64_t(kWavesPerBlock) * (kWave / lr))));
     switch (H) {
       case 1: launch_team_h<OP, 1>(lr, grid, s, a); break;
       case 2: launch_team_h<OP, 2>(lr, grid, s, a); break;
