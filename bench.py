@@ -212,6 +212,26 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     op_ms = np.array([[a.elapsed_time(b) for (a, b) in ev[k]] for k in range(args.steps)])  # [steps, ops]
     op_avg = op_ms.mean(axis=0)
+    op_med, op_min = np.median(op_ms, axis=0), op_ms.min(axis=0)
+
+    # cold numbers: every op once more after a 512 MiB scrub buffer has been written, so that nothing of its
+    # inputs is left in the 256 MB Infinity Cache or the L2s from the previous iteration (the figure to set
+    # beside the measured HBM traffic); a few repetitions, outside the timed step
+    scrub = torch.empty(1 << 28, dtype=half, device=dev)
+    cold_reps = 3
+    op_cold = np.zeros(len(ops))
+    for i, o in enumerate(ops):
+        ts = []
+        for _ in range(cold_reps):
+            scrub.fill_(1.0)
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0_.record()
+            o[3]()
+            e1_.record()
+            torch.cuda.synchronize()
+            ts.append(e0_.elapsed_time(e1_))
+        op_cold[i] = float(np.median(ts))
+    del scrub
 
     # dominant kernel = the kernel instantiation with the most time in a step; its launches are averaged
     by_kernel = {}
@@ -232,7 +252,7 @@ def main():
                 "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes": int(dom_bytes / per_call), "avg_ms": round(dom_ms / per_call, 4),
-                "call_ms": round(dom_ms, 4),
+                "call_ms": round(dom_ms, 4), "call_cold_ms": round(float(np.mean([op_cold[i] for i in idx])), 4),
                 "requested_bytes": int(dom_req / per_call),
                 "requested_GBps": round(dom_req / (dom_ms * 1e-3) / 1e9, 1),
                 "traffic_GBps": None if traffic is None else round(traffic * per_call / (dom_ms * 1e-3) / 1e9, 1),
@@ -242,8 +262,9 @@ def main():
                         "rocprofv3 (profiles/), which includes Infinity-Cache hits"}
 
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
-    detail = {o[0]: {"ms": round(float(t), 4), "min_GBps": round(o[2] / (t * 1e-3) / 1e9, 1),
-                     "req_GBps": round(o[4] / (t * 1e-3) / 1e9, 1)} for o, t in zip(ops, op_avg)}
+    detail = {o[0]: {"ms": round(float(t), 4), "median_ms": round(float(op_med[i]), 4), "min_ms": round(float(op_min[i]), 4),
+                     "cold_ms": round(float(op_cold[i]), 4), "min_GBps": round(o[2] / (t * 1e-3) / 1e9, 1),
+                     "req_GBps": round(o[4] / (t * 1e-3) / 1e9, 1)} for i, (o, t) in enumerate(zip(ops, op_avg))}
     layer_ms = {}
     if has_gat:
         layer_ms["gat_fwd_bwd_ms"] = round(float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in (
@@ -379,7 +400,7 @@ def main():
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
-            print(f"{o[0]:20s} {t:9.4f} ms  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
+            print(f"{o[0]:20s} {t:9.4f} ms  (cold {op_cold[ops.index(o)]:8.4f})  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
         if fused:
             print("gat fused forward " + json.dumps(fused), file=sys.stderr)
