@@ -27,6 +27,11 @@
  *    keeps its memory, so only the first call on a device reaches the driver).
  *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose and
  *    hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
+ *  - A plan owns scratch that the calls using it write (staging rows, per-vertex
+ *    tables, per-block partial outputs): calls that use the same plan must be ordered
+ *    on one stream, or otherwise not overlap in time; different plans are independent.
+ *    Host-side, the library keeps no mutable state except the thread-local error string,
+ *    the vector-width setting and the per-device memory pool of hgnn_spmm (mutex-guarded).
  *  - Arithmetic: fp16 in memory, fp32 in registers, one round-to-nearest-even
  *    conversion when a value is stored.
  *  - Errors: every call returns an hgnn_status; argument errors are detected on
