@@ -284,3 +284,67 @@ def test_vector_width_variants(hgnn, dev, restore_width, F, H):
     with pytest.raises(hgnn.HgnnError):
         hgnn.hgnn_set_vector_halves(3)
     hgnn.hgnn_plan_destroy(p)
+
+
+# ------------------------------------------------------------------ feature tables of 4 GiB and more (64-bit row addresses)
+def test_feature_table_beyond_4gib(hgnn, dev):
+    """Below 4 GiB the kernels address neighbour rows with 32-bit byte offsets from a scalar base; this table is
+    larger, so every segment kernel takes its 64-bit path.  Only the referenced rows are filled; the oracle
+    works on the compacted table."""
+    ncols, pitch, F, H = (1 << 21) + 64, 1024, 64, 1  # 2^21 rows of 2 KiB
+    V = 600
+    r = np.random.default_rng(12)
+    rowptr, col_small = rand_graph(V, 5000, 10, 7, hubs=((3, 1500),), empties=(1,))
+    pick = np.sort(r.choice(ncols, size=5000, replace=False)).astype(np.int64)
+    pick[-1] = ncols - 1  # the very last row of the table is referenced
+    col = pick[col_small].astype(np.int32)  # ascending inside a row is preserved (pick is increasing)
+    Xs = f16(r.standard_normal((5000, F)))
+    w = f16(r.standard_normal((col.size, 1)))
+    ref, sabs = oracle.spmm(rowptr, col_small, Xs, w=w, reduce=oracle.MEAN, want_sabs=True)
+    Xbig = torch.zeros((ncols, pitch), dtype=torch.float16, device=dev)
+    assert Xbig.numel() * 2 >= (1 << 32)
+    Xbig[torch.from_numpy(pick).to(dev), :F] = up(Xs, dev)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    p = hgnn.hgnn_plan_create(g, 256, F, H)
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    X = Xbig[:, :F]
+    hgnn.hgnn_spmm(g, up(w, dev), 1, X, Y, op=hgnn.HGNN_MEAN)
+    compare("plain, 64-bit rows", down(Y), ref, sabs)
+    hgnn.hgnn_spmm_discretized(p, g, up(w, dev), 1, X, Y, op=hgnn.HGNN_MEAN)
+    compare("discretized, 64-bit rows", down(Y), ref, sabs)
+    hgnn.hgnn_plan_add_groups(p, g, 64)
+    hgnn.hgnn_spmm_discretized_variant(p, g, up(w, dev), 1, X, Y, hgnn.HGNN_VERTEX_GROUPS, op=hgnn.HGNN_MEAN)
+    compare("vertex groups, 64-bit rows", down(Y), ref, sabs)
+    # fused GAT forward with the big table on the column side
+    U = f16(r.standard_normal((V, F)))
+    a_l, a_r = f16(0.2 * r.standard_normal(F)), f16(0.2 * r.standard_normal(F))
+    gref, gl, gabs = oracle.gat_forward(rowptr, col_small, U, Xs, a_l, a_r, H)
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, F, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse)
+    compare("gat fused, 64-bit rows", down(Y), gref, gabs)
+    # fused GAT backward: its forward-graph pass gathers rows of the big table
+    dOut = f16(r.standard_normal((V, F)))
+    gt = hgnn.hgnn_transpose(g)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    dV = torch.zeros((ncols, F), dtype=torch.float16, device=dev)
+    d_el = torch.empty((V, H), dtype=torch.float16, device=dev)
+    d_er = torch.empty((ncols, H), dtype=torch.float16, device=dev)
+    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, F, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse, up(dOut, dev), dV,
+                                 d_el, d_er)
+    bV, b_el, b_er = oracle.gat_backward(rowptr, col_small, U, Xs, a_l, a_r, dOut, H)
+    pick_d = torch.from_numpy(pick).to(dev)
+    scale = np.abs(bV).max()
+    assert np.max(np.abs(down(dV[pick_d]).astype(np.float64) - bV)) <= 2e-2 * scale
+    assert np.max(np.abs(down(d_er[pick_d]).astype(np.float64) - b_er)) <= 2e-2 * max(np.abs(b_er).max(), 1e-3)
+    assert np.max(np.abs(down(d_el).astype(np.float64) - b_el)) <= 2e-2 * max(np.abs(b_el).max(), 1e-3)
+    hgnn.hgnn_plan_destroy(pt)
+    # SDDMM dot against the big table
+    e = torch.empty((col.size, 1), dtype=torch.float16, device=dev)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, 1, F, up(U, dev), X, e)
+    dref = oracle.sddmm_dot(rowptr, col_small, U, Xs, H=1)
+    row = np.repeat(np.arange(V), np.diff(rowptr))
+    dabs = (np.abs(U[row].astype(np.float64)) * np.abs(Xs[col_small].astype(np.float64))).sum(-1, keepdims=True)
+    compare("sddmm dot, 64-bit rows", down(e), dref, dabs)
+    hgnn.hgnn_plan_destroy(p)
+    del Xbig
+    torch.cuda.empty_cache()
