@@ -130,6 +130,12 @@ def main():
                 lambda: hgnn.hgnn_spmm_discretized(plan, g, ew, 1, X, Y), spmm_req(wH, False)))
     ops.append(("spmm_bwd_disc", seg_name(wH), spmm_min(wH, True),
                 lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, ew, 1, dY, Y), spmm_req(wH, True)))
+    if ew is not None:
+        # static edge values (GCN norm weights): brought into transposed order once at set-up, so that the backward
+        # SpMM reads them as a stream instead of gathering them through the edge-id map
+        ew_T = torch.empty_like(ew)
+        hgnn.hgnn_edge_to_transposed(gt, 1, ew, ew_T)
+        gt_plain = hgnn.Csr(gt.rowptr, gt.col, ncols=V)
     if args.workload in ("c2", "c5"):  # GIN: mean aggregation as well (discretized reduction scaling)
         ops.append(("spmm_fwd_disc_mean", seg_name(0), spmm_min(0, False),
                     lambda: hgnn.hgnn_spmm_discretized(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN), spmm_req(0, False)))
@@ -273,6 +279,19 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
+    static_w = None
+    if ew is not None:
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for _ in range(max(args.warmup, 1)):
+            hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y)
+        for a, b in pairs:
+            a.record()
+            hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y)
+            b.record()
+        torch.cuda.synchronize()
+        static_w = {"spmm_bwd_disc_static_w_ms": round(float(np.mean([a.elapsed_time(b) for a, b in pairs])), 4),
+                    "spmm_bwd_disc_ms": round(float(op_avg[3]), 4)}
+
     fused = None
     if has_gat:
         # the single-pass GAT aggregation beside the three-call forward path (not part of the step)
@@ -395,13 +414,15 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
+        "layers": layer_ms, "ops": detail, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  (cold {op_cold[ops.index(o)]:8.4f})  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        if static_w:
+            print("static edge values " + json.dumps(static_w), file=sys.stderr)
         if fused:
             print("gat fused forward " + json.dumps(fused), file=sys.stderr)
         if width_sweep:

@@ -106,6 +106,13 @@ hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream);
  * by column).  g->eid must be NULL.  Allocates temporary storage, synchronizes. */
 hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T, int32_t* eid_T, void* stream);
 
+/* Brings an edge tensor into the edge order of the transposed graph: t_T[k,h] = t[gt->eid[k], h]
+ * (fp16 [nnz][H], not in place).  For edge values that do not change between steps (the
+ * normalised weights of a GCN, section 3.1.3) this is done once; the backward SpMM then runs
+ * on the transposed graph *without* its edge-id map, reading t_T as a stream instead of
+ * gathering two bytes per non-zero.  Asynchronous on `stream`. */
+hgnn_status hgnn_edge_to_transposed(const hgnn_csr* gt, int32_t H, const hgnn_half* t, hgnn_half* t_T, void* stream);
+
 /* Segment plan for the discretized SpMM (section 5.2.1, observation rules 1-3):
  * the non-zeros are dealt out in storage order in segments of seg_edges edges,
  * segment k = [k*S, min(nnz,(k+1)*S)).  The plan holds, on the device: the row

@@ -65,6 +65,8 @@ def _load():
     lib.orc_edge_rowsum.argtypes = [i32, vp, i32, vp, vp]
     lib.orc_edge_colsum.restype = None
     lib.orc_edge_colsum.argtypes = [i32, i32, vp, vp, i32, vp, vp]
+    lib.orc_edge_gather.restype = None
+    lib.orc_edge_gather.argtypes = [i64, vp, i32, vp, vp]
     lib.orc_segment_plan.restype = i32
     lib.orc_segment_plan.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     lib.orc_spmm_naive_fp16.restype = None
@@ -215,6 +217,14 @@ def edge_colsum(rowptr, col, t, ncols: int):
     rowptr, col, t = _i32(rowptr), _i32(col), _f64(t)
     out = np.empty((ncols, t.shape[1]), dtype=np.float64)
     _load().orc_edge_colsum(rowptr.size - 1, ncols, _ptr(rowptr), _ptr(col), t.shape[1], _ptr(t), _ptr(out))
+    return out
+
+
+def edge_gather(eid, t):
+    """t (fp16 [nnz][H]) in the edge order of the transposed graph."""
+    eid, t = _i32(eid), _f16(t)
+    out = np.empty_like(t)
+    _load().orc_edge_gather(eid.size, _ptr(eid), t.shape[1], _ptr(t), _ptr(out))
     return out
 
 

@@ -330,6 +330,14 @@ void orc_edge_colsum(int32_t V, int32_t ncols, const int32_t* rowptr, const int3
       for (int32_t h = 0; h < H; ++h) out[(int64_t)col[k] * H + h] += t[(int64_t)k * H + h];
 }
 
+/* ---- an edge tensor in the edge order of the transposed graph: out[k,h] = t[eid[k],h], eid from
+ * orc_transpose (section 2.1.2: the backward SpMM walks A^T, whose k-th non-zero is the
+ * eid[k]-th non-zero of A).  Values are copied, not converted. ---- */
+void orc_edge_gather(int64_t nnz, const int32_t* eid, int32_t H, const uint16_t* t, uint16_t* out) {
+  for (int64_t k = 0; k < nnz; ++k)
+    for (int32_t h = 0; h < H; ++h) out[k * H + h] = t[(int64_t)eid[k] * H + h];
+}
+
 /* ---- segment plan for the discretized SpMM (section 5.2: edges are dealt out in
  * fixed-size batches in storage order, observation rules 1-3).
  * Segment k owns edges [k*S, min(E,(k+1)*S)).  seg_row_lo/hi[k] = row of its first /

@@ -35,6 +35,15 @@ __global__ void source_rows_kernel(const int* __restrict__ rowptr, int nrows, co
   col_T[k] = row_of_edge(rowptr, nrows, eid_T[k]);
 }
 
+// out[k*H + h] = in[eid[k]*H + h]: an edge tensor brought into the edge order of the transposed graph
+__global__ void edge_gather_kernel(const int* __restrict__ eid, int64_t total, int H, const half_t* __restrict__ in,
+                                   half_t* __restrict__ out) {
+  const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (j >= total) return;
+  const int64_t k = j / H;
+  out[j] = in[int64_t(eid[k]) * H + (j - k * H)];
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
@@ -82,4 +91,22 @@ extern "C" hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int3
   (void)hipFree(keys_out);
   (void)hipFree(tmp);
   return rc;
+}
+
+extern "C" hgnn_status hgnn_edge_to_transposed(const hgnn_csr* gt, int32_t H, const hgnn_half* t, hgnn_half* t_T,
+                                               void* stream) {
+  clear_error();
+  const char* who = "hgnn_edge_to_transposed";
+  hgnn_status st = check_csr_args(gt, who);
+  if (st != HGNN_OK) return st;
+  HGNN_REQUIRE(gt->eid != nullptr, HGNN_EINVAL, "%s: the graph carries no edge-id map", who);
+  HGNN_REQUIRE(H >= 1, HGNN_EINVAL, "%s: H = %d must be positive", who, H);
+  if (gt->nnz == 0) return HGNN_OK;
+  HGNN_REQUIRE(t != nullptr && t_T != nullptr, HGNN_EINVAL, "%s: t or t_T is NULL", who);
+  HGNN_REQUIRE(t != t_T, HGNN_EINVAL, "%s: the permutation cannot run in place", who);
+  const int64_t total = gt->nnz * H;
+  edge_gather_kernel<<<dim3(unsigned(ceil_div(total, kBlock))), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
+      gt->eid, total, H, reinterpret_cast<const half_t*>(t), reinterpret_cast<half_t*>(t_T));
+  HGNN_LAUNCH_CHECK("edge_gather_kernel");
+  return HGNN_OK;
 }

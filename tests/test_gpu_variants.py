@@ -348,3 +348,32 @@ def test_feature_table_beyond_4gib(hgnn, dev):
     hgnn.hgnn_plan_destroy(p)
     del Xbig
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ static edge values in transposed order
+@pytest.mark.parametrize("H", [1, 4])
+def test_edge_to_transposed_and_backward_without_edge_ids(hgnn, dev, H):
+    V, ncols, F = 800, 900, 64
+    rowptr, col = rand_graph(V, ncols, 11, 4 + H, hubs=((7, 3000),), empties=(3,))
+    r = np.random.default_rng(H)
+    w = f16(r.standard_normal((col.size, H)))
+    dY = f16(r.standard_normal((V, F)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    eT = down(gt.eid)
+    wT = torch.empty((col.size, H), dtype=torch.float16, device=dev)
+    hgnn.hgnn_edge_to_transposed(gt, H, up(w, dev), wT)
+    assert np.array_equal(down(wT).view(np.uint16), oracle.edge_gather(eT, w).view(np.uint16))  # a permutation: bit exact
+    # the backward SpMM on the transposed graph without its edge-id map, reading wT as a stream
+    gt_plain = hgnn.Csr(gt.rowptr, gt.col, ncols=V)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    a = torch.empty((ncols, F), dtype=torch.float16, device=dev)
+    b = torch.empty_like(a)
+    hgnn.hgnn_spmm_discretized(pt, gt, up(w, dev), H, up(dY, dev), a)
+    hgnn.hgnn_spmm_discretized(pt, gt_plain, wT, H, up(dY, dev), b)
+    assert np.array_equal(down(a).view(np.uint16), down(b).view(np.uint16))  # same edges in the same order
+    ref, sabs = oracle.spmm(down(gt.rowptr), down(gt.col), dY, w=w, H=H, eid=eT, want_sabs=True)
+    compare("backward with pre-permuted values", down(b), ref, sabs)
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_edge_to_transposed(g, H, up(w, dev), wT)  # no edge-id map
+    hgnn.hgnn_plan_destroy(pt)

@@ -570,6 +570,24 @@ def test_gat_backward_special_cases_and_composition():
     assert np.max(np.abs(d_el1)) < 1e-12
 
 
+def test_edge_gather_is_the_transposed_order():
+    """The k-th non-zero of the transpose carries the value of non-zero eid[k]: with the pre-permuted values and no
+    edge-id map the transposed SpMM gives the same result as with the map, and the dense transpose agrees."""
+    V, ncols = 17, 13
+    rowptr, col, row = small_graph(V, ncols, 0.4, 31, empty_rows=(5,))
+    w = rng.standard_normal((col.size, 2)).astype(np.float16)
+    rT, cT, eT = oracle.transpose(rowptr, col, ncols)
+    wT = oracle.edge_gather(eT, w)
+    assert np.array_equal(wT.view(np.uint16), w[eT].view(np.uint16))
+    X = rng.standard_normal((V, 4)).astype(np.float16)
+    a = oracle.spmm(rT, cT, X, w=w, H=2, eid=eT)
+    b = oracle.spmm(rT, cT, X, w=wT, H=2)
+    assert np.array_equal(a, b)
+    for h in range(2):
+        A = dense_from(rowptr, col, row, ncols, w=w[:, h].astype(np.float64))
+        np.testing.assert_allclose(b[:, 2 * h:2 * h + 2], A.T @ X.astype(np.float64)[:, 2 * h:2 * h + 2], rtol=1e-12, atol=1e-13)
+
+
 # ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
 @pytest.mark.parametrize("ng", [1, 4, 32, 64])
 def test_neighbor_groups_bruteforce(ng):
