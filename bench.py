@@ -239,6 +239,18 @@ def main():
         op_cold[i] = float(np.median(ts))
     del scrub
 
+    def time_call(fn):
+        """mean milliseconds of args.steps calls of fn after warm-up, HIP events on the launch stream"""
+        for _ in range(max(args.warmup, 1)):
+            fn()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in pairs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
     # dominant kernel = the kernel instantiation with the most time in a step; its launches are averaged
     by_kernel = {}
     for i, o in enumerate(ops):
@@ -281,15 +293,8 @@ def main():
 
     static_w = None
     if ew is not None:
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        for _ in range(max(args.warmup, 1)):
-            hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y)
-        for a, b in pairs:
-            a.record()
-            hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y)
-            b.record()
-        torch.cuda.synchronize()
-        static_w = {"spmm_bwd_disc_static_w_ms": round(float(np.mean([a.elapsed_time(b) for a, b in pairs])), 4),
+        t_static = time_call(lambda: hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y))
+        static_w = {"spmm_bwd_disc_static_w_ms": round(t_static, 4),
                     "spmm_bwd_disc_ms": round(float(op_avg[3]), 4)}
 
     fused = None
@@ -297,24 +302,13 @@ def main():
         # the single-pass GAT aggregation beside the three-call forward path (not part of the step)
         lse = torch.empty((V, H), dtype=torch.float32, device=dev)
 
-        def time_one(fn):
-            for _ in range(max(args.warmup, 1)):
-                fn()
-            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            for a, b in pairs:
-                a.record()
-                fn()
-                b.record()
-            torch.cuda.synchronize()
-            return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
-
-        t_f = time_one(lambda: hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse))
-        t_a = time_one(lambda: hgnn.hgnn_gat_alpha(g, plan, H, D, X, X, a_l, a_r, lse, alpha))
+        t_f = time_call(lambda: hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse))
+        t_a = time_call(lambda: hgnn.hgnn_gat_alpha(g, plan, H, D, X, X, a_l, a_r, lse, alpha))
         three = float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in ("gat_score", "edge_softmax", "gat_spmm_fwd")))
         five = float(sum(op_avg[i] for i, o in enumerate(ops) if o[0] in (
             "gat_spmm_bwd", "sddmm_dot", "edge_softmax_bwd", "score_bwd_rowsum", "score_bwd_colsum")))
         hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse)
-        t_b = time_one(lambda: hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, X, X, a_l, a_r, out, lse, dY, dh,
+        t_b = time_call(lambda: hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, X, X, a_l, a_r, out, lse, dY, dh,
                                                             d_el, d_er))
         fused = {"gat_forward_fused_ms": round(t_f, 4), "three_call_forward_ms": round(three, 4),
                  "gat_backward_fused_ms": round(t_b, 4), "five_call_backward_ms": round(five, 4),
@@ -329,25 +323,14 @@ def main():
                 ("edge_segments_atomic", lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_EDGE_SEGMENTS_ATOMIC))]
         variants = {}
 
-        def time_fn(fn):
-            for _ in range(max(args.warmup, 1)):
-                fn()
-            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            for a, b in pairs:
-                a.record()
-                fn()
-                b.record()
-            torch.cuda.synchronize()
-            return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
-
         for name, fn in cand:
-            variants[name] = {"ms": round(time_fn(fn), 4)}
+            variants[name] = {"ms": round(time_call(fn), 4)}
         for ng in (64, 256):
             hgnn.hgnn_plan_add_groups(plan1, g, ng)
             variants[f"vertex_groups_{ng}"] = {
-                "ms": round(time_fn(lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)), 4),
+                "ms": round(time_call(lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)), 4),
                 "groups": hgnn.hgnn_plan_num_groups(plan1)}
-        variants["vertex_rows_no_plan"] = {"ms": round(time_fn(lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y)), 4)}
+        variants["vertex_rows_no_plan"] = {"ms": round(time_call(lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y)), 4)}
         for k in variants:
             variants[k]["req_GBps"] = round(spmm_req(wH, False) / (variants[k]["ms"] * 1e-3) / 1e9, 1)
         hgnn.hgnn_plan_destroy(plan1)
@@ -362,26 +345,15 @@ def main():
         gen.manual_seed(0x48474E4E)
         e1 = torch.empty((E, 1), dtype=half, device=dev)
 
-        def time_call(fn):
-            for _ in range(max(args.warmup, 1)):
-                fn()
-            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            for a, b in pairs:
-                a.record()
-                fn()
-                b.record()
-            torch.cuda.synchronize()
-            return round(float(np.mean([a.elapsed_time(b) for a, b in pairs])), 4)
-
         for Fs in (16, 32, 64, 128):
             Xs = torch.randn((V, Fs), generator=gen, device=dev, dtype=torch.float32).to(half)
             Ys = torch.empty_like(Xs)
             for vw in (2, 4, 8):
                 hgnn.hgnn_set_vector_halves(vw)
                 width_sweep[f"F{Fs}_halves{vw}"] = {
-                    "sddmm_dot_ms": time_call(lambda: hgnn.hgnn_sddmm(g, plan1, hgnn.HGNN_SDDMM_DOT, 1, Fs, Xs, Xs, e1)),
-                    "spmm_vertex_groups_ms": time_call(lambda: hgnn.hgnn_spmm_discretized_variant(
-                        plan1, g, None, 1, Xs, Ys, hgnn.HGNN_VERTEX_GROUPS))}
+                    "sddmm_dot_ms": round(time_call(lambda: hgnn.hgnn_sddmm(g, plan1, hgnn.HGNN_SDDMM_DOT, 1, Fs, Xs, Xs, e1)), 4),
+                    "spmm_vertex_groups_ms": round(time_call(lambda: hgnn.hgnn_spmm_discretized_variant(
+                        plan1, g, None, 1, Xs, Ys, hgnn.HGNN_VERTEX_GROUPS)), 4)}
         hgnn.hgnn_set_vector_halves(8)
         hgnn.hgnn_plan_destroy(plan1)
 

@@ -76,6 +76,52 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// v += the value of the lane that the data-parallel-primitive control CTRL pairs this lane with (one VALU
+// instruction, no trip through the LDS crossbar).  Controls used: quad_perm [1,0,3,2] = 0xB1 and [2,3,0,1] =
+// 0x4E (lane ^ 1, lane ^ 2), row_half_mirror = 0x141 (lane i <-> 7 - i of each 8), row_mirror = 0x140
+// (i <-> 15 - i of each 16).
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(t);
+}
+
+// All-reduce (sum) over the LH consecutive, LH-aligned lanes of a head; LH is a power of two.  After the
+// quads are summed, a mirror inside 8 (16) lanes pairs every lane with one of the other quad (half), whose
+// partial sum is the same on all its lanes; beyond a row of 16 lanes the exchange goes through ds_bpermute.
+__device__ __forceinline__ float head_sum1(float v, int LH) {
+  if (LH >= 2) v = dpp_add<0xB1>(v);
+  if (LH >= 4) v = dpp_add<0x4E>(v);
+  if (LH >= 8) v = dpp_add<0x141>(v);
+  if (LH >= 16) v = dpp_add<0x140>(v);
+  for (int off = 16; off < LH; off <<= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// the same for four independent values at once (four chains in flight)
+__device__ __forceinline__ void head_sum4(float (&v)[4], int LH) {
+  if (LH >= 2) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0xB1>(v[u]);
+  }
+  if (LH >= 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x4E>(v[u]);
+  }
+  if (LH >= 8) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x141>(v[u]);
+  }
+  if (LH >= 16) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x140>(v[u]);
+  }
+  for (int off = 16; off < LH; off <<= 1) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], off);
+  }
+}
+
 typedef int int4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 

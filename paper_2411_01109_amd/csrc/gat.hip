@@ -46,41 +46,6 @@ struct GatArgs {
   int n_split;
 };
 
-// v += the value of the lane that the data-parallel-primitive control CTRL pairs this lane with (one VALU
-// instruction, no trip through the LDS crossbar).  Controls used: quad_perm [1,0,3,2] and [2,3,0,1]
-// (lane ^ 1, lane ^ 2), row_half_mirror (lane i <-> 7 - i of each 8) and row_mirror (i <-> 15 - i of each 16).
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-  return v + __int_as_float(t);
-}
-
-// all-reduce (sum) of four values over the LH consecutive lanes of a head; LH is a power of two and the
-// head's lanes are aligned to LH.  After quads are summed, a mirror inside 8 (16) lanes pairs every lane with
-// one of the other quad (half), whose partial sum is the same on all its lanes.
-__device__ __forceinline__ void head_allreduce4(float (&v)[4], int LH) {
-  if (LH >= 2) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0xB1>(v[u]);
-  }
-  if (LH >= 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x4E>(v[u]);
-  }
-  if (LH >= 8) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x141>(v[u]);
-  }
-  if (LH >= 16) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = dpp_add<0x140>(v[u]);
-  }
-  for (int off = 16; off < LH; off <<= 1) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], off);
-  }
-}
-
 // (m, z, acc) <- merge with (m2, z2, acc2)
 __device__ __forceinline__ void soft_merge(float& m, float& z, float (&acc)[8], float m2, float z2, const float (&acc2)[8]) {
   const float M = fmaxf(m, m2);
@@ -292,7 +257,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
         }
         sc[u] = d;
       }
-      head_allreduce4(sc, LH);
+      head_sum4(sc, LH);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float t = sc[u] + s_sc[(i + u) * a.H + head];

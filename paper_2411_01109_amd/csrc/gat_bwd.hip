@@ -45,25 +45,6 @@ struct GatBwdArgs {
   int n_split;
 };
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add_b(float v) {
-  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-  return v + __int_as_float(t);
-}
-
-// all-reduce (sum) of a value over the LH consecutive, LH-aligned lanes of a head (LH a power of two):
-// quad_perm exchanges [1,0,3,2] and [2,3,0,1], then mirrors inside 8 and 16 lanes (after the quads are
-// summed a mirror pairs every lane with one of the other quad / half, whose sum is the same on all its
-// lanes), then cross-row exchanges
-__device__ __forceinline__ float head_sum1(float v, int LH) {
-  if (LH >= 2) v = dpp_add_b<0xB1>(v);
-  if (LH >= 4) v = dpp_add_b<0x4E>(v);
-  if (LH >= 8) v = dpp_add_b<0x141>(v);
-  if (LH >= 16) v = dpp_add_b<0x140>(v);
-  for (int off = 16; off < LH; off <<= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
 struct GatBwdLds {
   int per, spad, col_off, row_off, blk_off, a_off, t_off, vec_off, ds_off, flag_off, total;
 };

@@ -1,5 +1,8 @@
-"""Shared helpers of the GPU parity tests: device upload and the comparison rule."""
+"""Shared helpers of the GPU parity tests: device upload, random graphs and the comparison rule."""
 import numpy as np
+import torch
+
+import workloads as wl
 
 REL_L2 = 5e-3      # ||y - ref||_2 / ||ref||_2
 REL_ELEM = 2e-2    # elementwise relative error
@@ -47,3 +50,30 @@ def sample_rows(rowptr, n, seed, extra_top=8):
     pick = rng.integers(0, V, size=min(n, V))
     top = np.argsort(deg)[-extra_top:]
     return np.unique(np.concatenate([pick, top])).astype(np.int32)
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def down(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def rand_graph(V, ncols, avg_deg, seed, hubs=(), empties=()):
+    r = np.random.default_rng(seed)
+    deg = r.poisson(avg_deg, size=V)
+    for i, d in hubs:
+        deg[i] = d
+    for i in empties:
+        deg[i] = 0
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    col = r.integers(0, ncols, size=int(rowptr[-1])).astype(np.int32)
+    for i in range(V):  # ascending inside a row
+        col[rowptr[i]:rowptr[i + 1]].sort()
+    return rowptr, col
+
+
+def f16(a):
+    return wl.to_f16(np.asarray(a, dtype=np.float64))

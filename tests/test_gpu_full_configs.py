@@ -7,8 +7,8 @@ import torch
 
 import oracle
 import workloads as wl
-from parity import compare, sample_rows
-from test_gpu_parity import down, gat_layer_check, up
+from parity import compare, down, sample_rows, up
+from test_gpu_parity import gat_layer_check
 
 pytestmark = pytest.mark.gpu
 

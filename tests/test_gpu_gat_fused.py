@@ -6,8 +6,7 @@ import torch
 
 import oracle
 import workloads as wl
-from parity import compare, sample_rows
-from test_gpu_parity import down, f16, rand_graph, up
+from parity import compare, down, f16, rand_graph, sample_rows, up
 
 pytestmark = pytest.mark.gpu
 

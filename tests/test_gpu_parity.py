@@ -6,36 +6,9 @@ import torch
 
 import oracle
 import workloads as wl
-from parity import compare, sample_rows
+from parity import compare, down, f16, rand_graph, sample_rows, up
 
 pytestmark = pytest.mark.gpu
-
-
-def up(a, dev):
-    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-
-
-def down(t):
-    torch.cuda.synchronize()
-    return t.cpu().numpy()
-
-
-def rand_graph(V, ncols, avg_deg, seed, hubs=(), empties=()):
-    r = np.random.default_rng(seed)
-    deg = r.poisson(avg_deg, size=V)
-    for i, d in hubs:
-        deg[i] = d
-    for i in empties:
-        deg[i] = 0
-    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
-    col = r.integers(0, ncols, size=int(rowptr[-1])).astype(np.int32)
-    for i in range(V):  # ascending inside a row
-        col[rowptr[i]:rowptr[i + 1]].sort()
-    return rowptr, col
-
-
-def f16(a):
-    return wl.to_f16(np.asarray(a, dtype=np.float64))
 
 
 # ------------------------------------------------------------------ plan and transpose: bit exact
