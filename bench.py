@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--width-sweep", action="store_true",
                     help="also time SDDMM dot and the vertex-group SpMM at 2, 4 and 8 halves per lane for "
                          "F in {16, 32, 64, 128} on this workload's graph; reported under 'width_sweep'")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the plan-based ops of the step into one HIP graph and time its replay "
+                         "(launch-bound small configs); reported under 'graph'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print a per-op table to stderr")
     ap.add_argument("--variants", action="store_true",
@@ -291,6 +294,23 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
+    graph_info = None
+    if args.graph:
+        # the ops that take a plan neither allocate nor synchronize: record them once, replay the whole sequence
+        gops = [o for o in ops if not o[0].endswith("_plain")]
+        for o in gops:
+            o[3]()
+        torch.cuda.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cg):
+            for o in gops:
+                o[3]()
+        t_graph = time_call(cg.replay)
+        t_eager_wall = time_call(lambda: [o[3]() for o in gops])
+        graph_info = {"ops": [o[0] for o in gops], "graph_replay_ms": round(t_graph, 4),
+                      "eager_ms": round(t_eager_wall, 4),
+                      "sum_of_op_ms": round(float(sum(op_avg[i] for i, o in enumerate(ops) if not o[0].endswith("_plain"))), 4)}
+
     static_w = None
     if ew is not None:
         t_static = time_call(lambda: hgnn.hgnn_spmm_discretized(plan_t, gt_plain, ew_T, 1, dY, Y))
@@ -386,13 +406,15 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
+        "layers": layer_ms, "ops": detail, "graph": graph_info, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  (cold {op_cold[ops.index(o)]:8.4f})  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        if graph_info:
+            print("graph " + json.dumps({k: v for k, v in graph_info.items() if k != "ops"}), file=sys.stderr)
         if static_w:
             print("static edge values " + json.dumps(static_w), file=sys.stderr)
         if fused:

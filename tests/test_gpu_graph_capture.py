@@ -1,0 +1,70 @@
+"""The compute entry points that take a plan neither allocate nor synchronize, so a whole layer can be
+recorded into a HIP graph and replayed: every replay must give, bit for bit, what the same calls give eagerly."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from parity import down, f16, rand_graph, up
+
+pytestmark = pytest.mark.gpu
+
+
+def test_gat_layer_and_spmm_under_graph_replay(hgnn, dev):
+    V, H, D = 3000, 4, 16
+    F = H * D
+    rowptr, col = rand_graph(V, V, 12, 21, hubs=((5, 6000), (2999, 400)), empties=(0, 17))
+    r = np.random.default_rng(0)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, 256, F, H)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    a_l, a_r = up(f16(0.2 * r.standard_normal(F)), dev), up(f16(0.2 * r.standard_normal(F)), dev)
+    E = col.size
+    # static buffers of the recorded step
+    X = torch.empty((V, F), dtype=torch.float16, device=dev)
+    dO = torch.empty((V, F), dtype=torch.float16, device=dev)
+    bufs = {k: torch.empty((V, F), dtype=torch.float16, device=dev) for k in ("out", "dV", "agg", "out3")}
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    d_el = torch.empty((V, H), dtype=torch.float16, device=dev)
+    d_er = torch.empty((V, H), dtype=torch.float16, device=dev)
+    e = torch.empty((E, H), dtype=torch.float16, device=dev)
+    alpha = torch.empty((E, H), dtype=torch.float16, device=dev)
+
+    def step(o):
+        hgnn.hgnn_gat_forward_fused(g, p, H, D, X, X, a_l, a_r, o["out"], lse)
+        hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, X, X, a_l, a_r, o["out"], lse, dO, o["dV"], d_el, d_er)
+        hgnn.hgnn_spmm_discretized(p, g, None, 1, X, o["agg"], op=hgnn.HGNN_MEAN)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, X, X, e, a_l, a_r, 0.2)
+        hgnn.hgnn_edge_softmax(g, p, H, e, alpha)
+        hgnn.hgnn_spmm_discretized(p, g, alpha, H, X, o["out3"])
+
+    def fill(seed):
+        rr = np.random.default_rng(seed)
+        X.copy_(up(f16(rr.standard_normal((V, F))), dev))
+        dO.copy_(up(f16(rr.standard_normal((V, F))), dev))
+
+    fill(1)
+    step(bufs)  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(bufs)
+    eager = {k: torch.empty_like(v) for k, v in bufs.items()}
+    for rep in range(4):
+        fill(10 + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: down(v).copy() for k, v in bufs.items()}
+        got_s = (down(d_el).copy(), down(d_er).copy(), down(lse).copy())
+        # the program's own eager work and synchronisation between replays
+        step(eager)
+        torch.cuda.synchronize()
+        for k in bufs:
+            assert np.array_equal(got[k].view(np.uint16), down(eager[k]).view(np.uint16)), (rep, k)
+        assert np.array_equal(got_s[0].view(np.uint16), down(d_el).view(np.uint16)), rep
+        assert np.array_equal(got_s[1].view(np.uint16), down(d_er).view(np.uint16)), rep
+        assert np.array_equal(got_s[2], down(lse)), rep
+        assert np.all(np.isfinite(got["out"])) and np.abs(got["out"]).max() > 0
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
