@@ -95,8 +95,9 @@ const char* hgnn_status_str(hgnn_status s);
 const char* hgnn_last_error(void);
 
 /* One device pass over the graph: rowptr monotone with the right end points,
- * columns in range, row ids (if given) consistent with rowptr, eid (if given)
- * in [0,nnz).  Synchronizes.  HGNN_EINVAL names the first rule broken. */
+ * columns in range and ascending inside a row, row ids (if given) consistent with
+ * rowptr, eid (if given) in [0,nnz).  Synchronizes.  HGNN_EINVAL names the first
+ * rule broken. */
 hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream);
 
 /* CSR of A^T plus the edge-id map, for the backward SpMM dX <- A_w^T dY
