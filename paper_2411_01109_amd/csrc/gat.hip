@@ -146,7 +146,8 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
 
-  const int64_t wid = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int wpb = int(blockDim.x) / kWave;  // waves per workgroup (4, 2 or 1, chosen on the host for LDS packing)
+  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
   const int64_t seg = wid;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   }
 
   // ---- this wave's share of the empty rows
-  const int64_t nw = int64_t(gridDim.x) * kWavesPerBlock;
+  const int64_t nw = int64_t(gridDim.x) * wpb;
   const int rpw = int((a.nrows + nw - 1) / nw);
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
@@ -444,15 +445,15 @@ __global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, cons
 }
 
 template <bool OFF32, bool FLY>
-static void launch_gat_seg(int L, dim3 grid, size_t lds, hipStream_t s, const GatArgs& a) {
+static void launch_gat_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
   switch (L) {
-    case 1: gat_seg_kernel<1, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: gat_seg_kernel<2, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: gat_seg_kernel<4, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: gat_seg_kernel<8, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: gat_seg_kernel<16, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: gat_seg_kernel<32, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
-    default: gat_seg_kernel<64, OFF32, FLY><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: gat_seg_kernel<1, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 2: gat_seg_kernel<2, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 4: gat_seg_kernel<4, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 8: gat_seg_kernel<8, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 16: gat_seg_kernel<16, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 32: gat_seg_kernel<32, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    default: gat_seg_kernel<64, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
   }
 }
 
@@ -495,19 +496,22 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const size_t lds = size_t(gat_lds_layout(a.S, a.H, L).total) * kWavesPerBlock;
+  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L).total);
+  const int wpb = waves_per_block_for_lds(per_wave, true);
+  const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_gat_forward_fused: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
                a.H, lds);
-  const int64_t nblk = ceil_div(q->nseg, kWavesPerBlock);
+  const int64_t nblk = ceil_div(q->nseg, wpb);
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
+  const int threads = wpb * kWave;
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   if (a.a_r) {
-    if (off32) launch_gat_seg<true, true>(L, grid, lds, s, a);
-    else launch_gat_seg<false, true>(L, grid, lds, s, a);
+    if (off32) launch_gat_seg<true, true>(L, grid, threads, lds, s, a);
+    else launch_gat_seg<false, true>(L, grid, threads, lds, s, a);
   } else {
-    if (off32) launch_gat_seg<true, false>(L, grid, lds, s, a);
-    else launch_gat_seg<false, false>(L, grid, lds, s, a);
+    if (off32) launch_gat_seg<true, false>(L, grid, threads, lds, s, a);
+    else launch_gat_seg<false, false>(L, grid, threads, lds, s, a);
   }
   HGNN_LAUNCH_CHECK("gat_seg_kernel");
   if (a.n_split > 0) {

@@ -499,8 +499,7 @@ static hgnn_status run_bwd_segments(const hgnn_plan* q, GatBwdArgs a, int ncols,
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
   const size_t per_wave = size_t(gat_bwd_lds_layout(a.S, a.H, L, VEC).total);
-  int wpb = kWavesPerBlock;  // waves per workgroup: as many of 4, 2, 1 as fit 64 KB of LDS
-  while (wpb > 1 && per_wave * wpb > 65536) wpb >>= 1;
+  const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_gat_backward_fused: seg_edges = %d with H = %d needs %zu bytes of LDS per wavefront (limit 65536)", a.S,

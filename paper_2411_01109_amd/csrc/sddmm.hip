@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   half_t* s_out = reinterpret_cast<half_t*>(base + lay.out_off);
 
-  const int64_t seg = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int64_t seg = int64_t(blockIdx.x) * (int(blockDim.x) / kWave) + wave;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
@@ -364,11 +364,11 @@ static void launch_edge(int L, dim3 grid, size_t lds, hipStream_t s, const Sddmm
 }
 
 template <int VW>
-static void launch_seg_vw(int L, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
+static void launch_seg_vw(int L, bool mask, dim3 grid, int threads, size_t lds, hipStream_t s, const SddmmArgs& a) {
 #define LAUNCH_SEG(LL)                                                                   \
   do {                                                                                  \
-    if (mask && VW == 8) sddmm_seg_kernel<LL, 8, true><<<grid, kBlock, lds, s>>>(a);    \
-    else sddmm_seg_kernel<LL, VW, false><<<grid, kBlock, lds, s>>>(a);                  \
+    if (mask && VW == 8) sddmm_seg_kernel<LL, 8, true><<<grid, threads, lds, s>>>(a);   \
+    else sddmm_seg_kernel<LL, VW, false><<<grid, threads, lds, s>>>(a);                 \
   } while (0)
   switch (L) {
     case 1: LAUNCH_SEG(1); break;
@@ -382,10 +382,10 @@ static void launch_seg_vw(int L, bool mask, dim3 grid, size_t lds, hipStream_t s
 #undef LAUNCH_SEG
 }
 
-static void launch_seg(int L, int vw, bool mask, dim3 grid, size_t lds, hipStream_t s, const SddmmArgs& a) {
-  if (vw == 8) launch_seg_vw<8>(L, mask, grid, lds, s, a);
-  else if (vw == 4) launch_seg_vw<4>(L, false, grid, lds, s, a);
-  else launch_seg_vw<2>(L, false, grid, lds, s, a);
+static void launch_seg(int L, int vw, bool mask, dim3 grid, int threads, size_t lds, hipStream_t s, const SddmmArgs& a) {
+  if (vw == 8) launch_seg_vw<8>(L, mask, grid, threads, lds, s, a);
+  else if (vw == 4) launch_seg_vw<4>(L, false, grid, threads, lds, s, a);
+  else launch_seg_vw<2>(L, false, grid, threads, lds, s, a);
 }
 
 static void launch_proj(int L, dim3 grid, hipStream_t s, const half_t* feat, int64_t ld, int nv, const half_t* avec, int F,
@@ -518,7 +518,9 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
                    "hgnn_sddmm: %d halves per lane needs F <= %d and D / %d a power of two", vw, kWave * vw, vw);
       Ls = pow2_at_least(F / vw);
     }
-    const size_t lds = size_t(sddmm_lds_layout(a.S, H).total) * kWavesPerBlock;
+    const size_t seg_per_wave = size_t(sddmm_lds_layout(a.S, H).total);
+    const int wpb = waves_per_block_for_lds(seg_per_wave, true);
+    const size_t lds = seg_per_wave * wpb;
     if (lds <= 65536 && p->nb > 1) {
       // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
       for (int b = 0; b < p->nb; ++b) {
@@ -532,13 +534,13 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
         ab.seg_hi = q->seg_row_hi;
         ab.nseg = q->nseg;
         ab.nnz = q->nnz;
-        launch_seg(Ls, vw, masked, dim3(unsigned(ceil_div(q->nseg, kWavesPerBlock))), lds, s, ab);
+        launch_seg(Ls, vw, masked, dim3(unsigned(ceil_div(q->nseg, wpb))), wpb * kWave, lds, s, ab);
         HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       }
       return HGNN_OK;
     }
     if (lds <= 65536) {
-      launch_seg(Ls, vw, masked, dim3(unsigned(seg_blocks)), lds, s, a);
+      launch_seg(Ls, vw, masked, dim3(unsigned(ceil_div(p->nseg, wpb))), wpb * kWave, lds, s, a);
       HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       return HGNN_OK;
     }

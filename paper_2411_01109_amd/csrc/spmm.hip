@@ -425,7 +425,8 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
 
-  const int64_t wid = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int wpb = int(blockDim.x) / kWave;  // waves per workgroup (4, 2 or 1, chosen on the host for LDS packing)
+  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
   const int64_t seg = wid;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
@@ -612,7 +613,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   }
 
   // ---- zero-fill this wave's share of the empty rows
-  const int64_t nw = int64_t(gridDim.x) * kWavesPerBlock;
+  const int64_t nw = int64_t(gridDim.x) * wpb;
   const int rpw = int((a.nrows + nw - 1) / nw);
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
@@ -732,7 +733,7 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
   int* s_col = reinterpret_cast<int*>(base);
   half_t* s_w = reinterpret_cast<half_t*>(base + spad * 4);
 
-  const int64_t j = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  const int64_t j = int64_t(blockIdx.x) * (int(blockDim.x) / kWave) + wave;
   const bool valid = j < v.n_groups;
   int row = 0, idx = 0, cnt = 1, k0 = 0, n = 0;
   if (valid) {
@@ -1021,15 +1022,15 @@ static hgnn_status hub_lists_alloc(int64_t nnz, int F, hipStream_t s, HubLists* 
 }
 
 template <int WM, bool OFF32>
-static void launch_seg(int L, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a) {
+static void launch_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const SpmmArgs& a) {
   switch (L) {
-    case 1: spmm_seg_kernel<1, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 2: spmm_seg_kernel<2, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 4: spmm_seg_kernel<4, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 8: spmm_seg_kernel<8, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 16: spmm_seg_kernel<16, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    case 32: spmm_seg_kernel<32, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
-    default: spmm_seg_kernel<64, WM, OFF32><<<grid, kBlock, lds, s>>>(a); break;
+    case 1: spmm_seg_kernel<1, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    case 2: spmm_seg_kernel<2, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    case 4: spmm_seg_kernel<4, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    case 8: spmm_seg_kernel<8, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    case 16: spmm_seg_kernel<16, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    case 32: spmm_seg_kernel<32, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
+    default: spmm_seg_kernel<64, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
   }
 }
 
@@ -1058,28 +1059,28 @@ static void launch_zero_split(int L, dim3 grid, hipStream_t s, const SpmmArgs& a
 }
 
 template <int L, int VW>
-static void launch_vgroup_main(bool has_w, bool off32, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a,
+static void launch_vgroup_main(bool has_w, bool off32, dim3 grid, int threads, size_t lds, hipStream_t s, const SpmmArgs& a,
                                const VGroupArgs& v) {
   if (has_w) {
-    if (off32) spmm_vgroup_kernel<L, VW, true, true><<<grid, kBlock, lds, s>>>(a, v);
-    else if (VW == 8) spmm_vgroup_kernel<L, 8, true, false><<<grid, kBlock, lds, s>>>(a, v);
+    if (off32) spmm_vgroup_kernel<L, VW, true, true><<<grid, threads, lds, s>>>(a, v);
+    else if (VW == 8) spmm_vgroup_kernel<L, 8, true, false><<<grid, threads, lds, s>>>(a, v);
   } else {
-    if (off32) spmm_vgroup_kernel<L, VW, false, true><<<grid, kBlock, lds, s>>>(a, v);
-    else if (VW == 8) spmm_vgroup_kernel<L, 8, false, false><<<grid, kBlock, lds, s>>>(a, v);
+    if (off32) spmm_vgroup_kernel<L, VW, false, true><<<grid, threads, lds, s>>>(a, v);
+    else if (VW == 8) spmm_vgroup_kernel<L, 8, false, false><<<grid, threads, lds, s>>>(a, v);
   }
 }
 
 template <int VW>
-static void launch_vgroup_vw(int L, bool has_w, bool off32, dim3 grid, size_t lds, hipStream_t s, const SpmmArgs& a,
+static void launch_vgroup_vw(int L, bool has_w, bool off32, dim3 grid, int threads, size_t lds, hipStream_t s, const SpmmArgs& a,
                              const VGroupArgs& v) {
   switch (L) {
-    case 1: launch_vgroup_main<1, VW>(has_w, off32, grid, lds, s, a, v); break;
-    case 2: launch_vgroup_main<2, VW>(has_w, off32, grid, lds, s, a, v); break;
-    case 4: launch_vgroup_main<4, VW>(has_w, off32, grid, lds, s, a, v); break;
-    case 8: launch_vgroup_main<8, VW>(has_w, off32, grid, lds, s, a, v); break;
-    case 16: launch_vgroup_main<16, VW>(has_w, off32, grid, lds, s, a, v); break;
-    case 32: launch_vgroup_main<32, VW>(has_w, off32, grid, lds, s, a, v); break;
-    default: launch_vgroup_main<64, VW>(has_w, off32, grid, lds, s, a, v); break;
+    case 1: launch_vgroup_main<1, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    case 2: launch_vgroup_main<2, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    case 4: launch_vgroup_main<4, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    case 8: launch_vgroup_main<8, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    case 16: launch_vgroup_main<16, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    case 32: launch_vgroup_main<32, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
+    default: launch_vgroup_main<64, VW>(has_w, off32, grid, threads, lds, s, a, v); break;
   }
 }
 
@@ -1116,17 +1117,19 @@ static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStr
   }
   const int L = pow2_at_least((a.F + vw - 1) / vw);   // lanes per row in the main kernel
   const int L8 = pow2_at_least((a.F + 7) / 8);        // the follow-up kernel always moves 16 bytes per lane
-  const size_t lds = size_t(vgroup_lds_bytes(v.ng, a.H, a.w != nullptr)) * kWavesPerBlock;
+  const size_t vg_per_wave = size_t(vgroup_lds_bytes(v.ng, a.H, a.w != nullptr));
+  const int wpb = waves_per_block_for_lds(vg_per_wave, a.w != nullptr);
+  const size_t lds = vg_per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_spmm_discretized_variant: group_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)",
                v.ng, a.H, lds);
-  dim3 grid(unsigned(ceil_div(v.n_groups > 0 ? v.n_groups : 1, kWavesPerBlock)));
+  dim3 grid(unsigned(ceil_div(v.n_groups > 0 ? v.n_groups : 1, wpb)));
   dim3 grid2(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * (kWave / L8))));
   const bool has_w = a.w != nullptr;
   if (v.n_groups > 0) {
-    if (vw == 8) launch_vgroup_vw<8>(L, has_w, off32, grid, lds, s, a, v);
-    else if (vw == 4) launch_vgroup_vw<4>(L, has_w, off32, grid, lds, s, a, v);
-    else launch_vgroup_vw<2>(L, has_w, off32, grid, lds, s, a, v);
+    if (vw == 8) launch_vgroup_vw<8>(L, has_w, off32, grid, wpb * kWave, lds, s, a, v);
+    else if (vw == 4) launch_vgroup_vw<4>(L, has_w, off32, grid, wpb * kWave, lds, s, a, v);
+    else launch_vgroup_vw<2>(L, has_w, off32, grid, wpb * kWave, lds, s, a, v);
   }
   launch_vgroup_finish(L8, grid2, s, a, v);
   HGNN_LAUNCH_CHECK("spmm_vgroup_kernel / spmm_vgroup_finish_kernel");
@@ -1148,11 +1151,13 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
   a.n_split = q->n_split;
   const int L = pow2_at_least((a.F + 7) / 8);
   const SegLds lay = seg_lds_layout(a.S, a.H, wm, L);
-  const size_t lds = size_t(lay.total) * kWavesPerBlock;
+  const int wpb = waves_per_block_for_lds(size_t(lay.total), wm != 0);
+  const int threads = wpb * kWave;
+  const size_t lds = size_t(lay.total) * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
                "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
                a.H, lds);
-  const int64_t nblk = ceil_div(q->nseg, kWavesPerBlock);
+  const int64_t nblk = ceil_div(q->nseg, wpb);
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
   // feature table below 2^32 bytes: 32-bit byte offsets from a scalar base address
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
@@ -1161,14 +1166,14 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
     HGNN_LAUNCH_CHECK("zero_split_rows_kernel");
   }
   if (wm == 2) {
-    if (off32) launch_seg<2, true>(L, grid, lds, s, a);
-    else launch_seg<2, false>(L, grid, lds, s, a);
+    if (off32) launch_seg<2, true>(L, grid, threads, lds, s, a);
+    else launch_seg<2, false>(L, grid, threads, lds, s, a);
   } else if (wm == 1) {
-    if (off32) launch_seg<1, true>(L, grid, lds, s, a);
-    else launch_seg<1, false>(L, grid, lds, s, a);
+    if (off32) launch_seg<1, true>(L, grid, threads, lds, s, a);
+    else launch_seg<1, false>(L, grid, threads, lds, s, a);
   } else {
-    if (off32) launch_seg<0, true>(L, grid, lds, s, a);
-    else launch_seg<0, false>(L, grid, lds, s, a);
+    if (off32) launch_seg<0, true>(L, grid, threads, lds, s, a);
+    else launch_seg<0, false>(L, grid, threads, lds, s, a);
   }
   HGNN_LAUNCH_CHECK("spmm_seg_kernel");
   if (a.n_split > 0 && !a.atomic_y) {
