@@ -15,6 +15,7 @@ namespace hgnn {
 
 constexpr int kKeepVec = 2;     // 8-element vectors per lane held in registers
 constexpr int kBigBlock = 1024; // threads given to one long row
+constexpr int kTeamThreads = 64;  // workgroup size of the team kernel: its waves never meet, so one wave each
 
 struct EdgeRowArgs {
   const int* rowptr;
@@ -255,7 +256,7 @@ template <int OP, int LR, int H>
 __global__ __launch_bounds__(kBlock) void edge_row_team_kernel(EdgeRowArgs a) {
   constexpr int GR = kWave / LR;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  int64_t row = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * GR + lane / LR;
+  int64_t row = (int64_t(blockIdx.x) * (int(blockDim.x) / kWave) + wave) * GR + lane / LR;
   if (a.row_list) {
     if (row >= a.n_list) return;
     row = a.row_list[row];
@@ -320,11 +321,11 @@ __global__ __launch_bounds__(kBlock) void edge_row_scalar_kernel(EdgeRowArgs a) 
 template <int OP, int H>
 static void launch_team_h(int LR, dim3 grid, hipStream_t s, const EdgeRowArgs& a) {
   switch (LR) {
-    case 4: edge_row_team_kernel<OP, 4, H><<<grid, kBlock, 0, s>>>(a); break;
-    case 8: edge_row_team_kernel<OP, 8, H><<<grid, kBlock, 0, s>>>(a); break;
-    case 16: edge_row_team_kernel<OP, 16, H><<<grid, kBlock, 0, s>>>(a); break;
-    case 32: edge_row_team_kernel<OP, 32, H><<<grid, kBlock, 0, s>>>(a); break;
-    default: edge_row_team_kernel<OP, 64, H><<<grid, kBlock, 0, s>>>(a); break;
+    case 4: edge_row_team_kernel<OP, 4, H><<<grid, kTeamThreads, 0, s>>>(a); break;
+    case 8: edge_row_team_kernel<OP, 8, H><<<grid, kTeamThreads, 0, s>>>(a); break;
+    case 16: edge_row_team_kernel<OP, 16, H><<<grid, kTeamThreads, 0, s>>>(a); break;
+    case 32: edge_row_team_kernel<OP, 32, H><<<grid, kTeamThreads, 0, s>>>(a); break;
+    default: edge_row_team_kernel<OP, 64, H><<<grid, kTeamThreads, 0, s>>>(a); break;
   }
 }
 
@@ -366,7 +367,7 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
       a.n_list = p->n_mid;
       nrows_tier = p->n_mid;
     }
-    dim3 grid(unsigned(ceil_div(nrows_tier, int64_t(kWavesPerBlock) * (kWave / lr))));
+    dim3 grid(unsigned(ceil_div(nrows_tier, int64_t(kTeamThreads / kWave) * (kWave / lr))));
     switch (H) {
       case 1: launch_team_h<OP, 1>(lr, grid, s, a); break;
       case 2: launch_team_h<OP, 2>(lr, grid, s, a); break;
