@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
   const int rw = a.rows_per_wave;  // 1 or G
-  const int64_t r0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * rw;
+  const int64_t r0 = (int64_t(blockIdx.x) * (int(blockDim.x) / kWave) + wave) * rw;
   if (r0 >= a.nrows) return;
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
@@ -943,7 +943,7 @@ static SpmmArgs make_args(const hgnn_csr* g, const hgnn_half* w, int H, const hg
 
 template <int L, bool HAS_W>
 static void launch_row_set(dim3 grid, hipStream_t s, const SpmmArgs& a, const HubLists* h) {
-  spmm_row_kernel<L, HAS_W><<<grid, kBlock, 0, s>>>(a);
+  spmm_row_kernel<L, HAS_W><<<grid, kWave, 0, s>>>(a);  // its waves never meet: single-wave workgroups
   if (h) {
     spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks)), kBlock, 0, s>>>(a, *h);
     spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
@@ -1235,7 +1235,7 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
     const int L = pow2_at_least((F + 7) / 8);
     // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
     a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
-    dim3 grid(unsigned(ceil_div(g->nrows, kWavesPerBlock * a.rows_per_wave)));
+    dim3 grid(unsigned(ceil_div(g->nrows, a.rows_per_wave)));
     HubLists h{};
     void* scratch = nullptr;
     st = hub_lists_alloc(g->nnz, F, s, &h, &scratch);
