@@ -294,6 +294,22 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
+    # the column-side norm applied to the table first (one V x F pass), then the SpMM without a per-edge factor:
+    # what the fused col_scale costs against this is the reason the design doc advises pre-scaling on long rows
+    Xs_buf = torch.empty_like(X)
+    if args.workload in ("c2", "c5"):
+        def prescaled_bwd():
+            hgnn.hgnn_scale_rows(dY, lam_over_deg, Xs_buf)
+            hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, Xs_buf, Y, self_feat=dY, self_coef=1.0)
+        prescaled = {"gin_bwd_prescaled_ms": round(time_call(prescaled_bwd), 4),
+                     "gin_fused_bwd_ms": round(float(op_avg[[o[0] for o in ops].index("gin_fused_bwd")]), 4)}
+    else:
+        def prescaled_fwd():
+            hgnn.hgnn_scale_rows(X, cs_f, Xs_buf)
+            hgnn.hgnn_spmm_discretized(plan, g, None, 1, Xs_buf, Y, row_scale=rs_f)
+        prescaled = {"gcn_norm_prescaled_fwd_ms": round(time_call(prescaled_fwd), 4),
+                     "gcn_norm_fused_fwd_ms": round(float(op_avg[[o[0] for o in ops].index("gcn_norm_fused_fwd")]), 4)}
+
     graph_info = None
     if args.graph:
         # the ops that take a plan neither allocate nor synchronize: record them once, replay the whole sequence
@@ -406,13 +422,14 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "graph": graph_info, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
+        "layers": layer_ms, "ops": detail, "column_norm": prescaled, "graph": graph_info, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:
         for o, t in zip(ops, op_avg):
             print(f"{o[0]:20s} {t:9.4f} ms  (cold {op_cold[ops.index(o)]:8.4f})  min {o[2] / 1e6:9.1f} MB {o[2] / (t * 1e-3) / 1e9:8.1f} GB/s   "
                   f"req {o[4] / 1e6:9.1f} MB {o[4] / (t * 1e-3) / 1e9:8.1f} GB/s   {o[1]}", file=sys.stderr)
+        print("column norm " + json.dumps(prescaled), file=sys.stderr)
         if graph_info:
             print("graph " + json.dumps({k: v for k, v in graph_info.items() if k != "ops"}), file=sys.stderr)
         if static_w:

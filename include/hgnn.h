@@ -245,6 +245,14 @@ hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32
 hgnn_status hgnn_set_vector_halves(int32_t halves);
 int32_t hgnn_get_vector_halves(void);
 
+/* out[i, f] = fp16(scale[i] * X[i, f]) for i < n, f < F (rows of pitch ldx / ldo, both multiples of 8;
+ * the last 16-byte piece of a row is written up to the pitch when F is not a multiple of 8).  The
+ * cheaper way to apply a column-side degree norm (Eq. 2) on graphs with more than a few edges per
+ * vertex: scale the feature table once, then run the SpMM without a per-edge factor, instead of
+ * col_scale in hgnn_spmm_discretized_fused, which fetches four more bytes per non-zero. */
+hgnn_status hgnn_scale_rows(int64_t n, int32_t F, const hgnn_half* X, int64_t ldx, const float* scale, hgnn_half* out,
+                            int64_t ldo, void* stream);
+
 /* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s

@@ -26,7 +26,7 @@ EXPORTS = (
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
     "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
-    "hgnn_edge_to_transposed",
+    "hgnn_edge_to_transposed", "hgnn_scale_rows",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -100,6 +100,7 @@ def load() -> ctypes.CDLL:
     lib.hgnn_set_vector_halves.argtypes = [i32]
     lib.hgnn_gat_forward_fused.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp]
     lib.hgnn_edge_to_transposed.argtypes = [csr, i32, vp, vp, vp]
+    lib.hgnn_scale_rows.argtypes = [i64, i32, vp, i64, vp, vp, i64, vp]
     lib.hgnn_gat_alpha.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp, vp]
     lib.hgnn_gat_backward_fused.argtypes = [csr, vp, csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64,
                                             vp, i64, vp, vp, vp]
@@ -319,6 +320,12 @@ def hgnn_gat_backward_fused(g: Csr, p: Plan, gt: Csr, pt: Plan, H: int, D: int, 
                                           _ptr(lse, torch.float32), _ptr(dOut, torch.float16), _ld(dOut),
                                           _ptr(dV, torch.float16), _ld(dV), _ptr(d_el, torch.float16),
                                           _ptr(d_er, torch.float16), _stream(stream)))
+
+
+def hgnn_scale_rows(X: torch.Tensor, scale: torch.Tensor, out: torch.Tensor, F: Optional[int] = None, stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    _check(load().hgnn_scale_rows(X.shape[0], F, _ptr(X, torch.float16), _ld(X), _ptr(scale, torch.float32),
+                                  _ptr(out, torch.float16), _ld(out), _stream(stream)))
 
 
 def hgnn_edge_to_transposed(gt: Csr, H: int, t: torch.Tensor, t_T: torch.Tensor, stream=None) -> None:

@@ -35,6 +35,21 @@ __global__ void source_rows_kernel(const int* __restrict__ rowptr, int nrows, co
   col_T[k] = row_of_edge(rowptr, nrows, eid_T[k]);
 }
 
+// out[i, f] = fp16(scale[i] * X[i, f]), 8 halves per thread
+__global__ void scale_rows_kernel(int64_t n, int F8, const half_t* __restrict__ X, int64_t ldx, const float* __restrict__ scale,
+                                  half_t* __restrict__ out, int64_t ldo) {
+  const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (j >= n * F8) return;
+  const int64_t i = j / F8;
+  const int f0 = int(j - i * F8) * 8;
+  const float sc = scale[i];
+  const half8_t x = *reinterpret_cast<const half8_t*>(X + i * ldx + f0);
+  half8_t y;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) y[q] = half_t(sc * float(x[q]));
+  *reinterpret_cast<half8_t*>(out + i * ldo + f0) = y;
+}
+
 // out[k*H + h] = in[eid[k]*H + h]: an edge tensor brought into the edge order of the transposed graph
 __global__ void edge_gather_kernel(const int* __restrict__ eid, int64_t total, int H, const half_t* __restrict__ in,
                                    half_t* __restrict__ out) {
@@ -108,5 +123,22 @@ extern "C" hgnn_status hgnn_edge_to_transposed(const hgnn_csr* gt, int32_t H, co
   edge_gather_kernel<<<dim3(unsigned(ceil_div(total, kBlock))), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
       gt->eid, total, H, reinterpret_cast<const half_t*>(t), reinterpret_cast<half_t*>(t_T));
   HGNN_LAUNCH_CHECK("edge_gather_kernel");
+  return HGNN_OK;
+}
+
+extern "C" hgnn_status hgnn_scale_rows(int64_t n, int32_t F, const hgnn_half* X, int64_t ldx, const float* scale,
+                                       hgnn_half* out, int64_t ldo, void* stream) {
+  clear_error();
+  const char* who = "hgnn_scale_rows";
+  HGNN_REQUIRE(n >= 0 && F > 0, HGNN_EINVAL, "%s: n = %lld, F = %d", who, static_cast<long long>(n), F);
+  HGNN_REQUIRE(ldx >= F && ldo >= F, HGNN_EINVAL, "%s: leading dimension smaller than F", who);
+  if (n == 0) return HGNN_OK;
+  HGNN_REQUIRE(X && scale && out, HGNN_EINVAL, "%s: NULL argument", who);
+  HGNN_REQUIRE(ldx % 8 == 0 && ldo % 8 == 0 && aligned16(X) && aligned16(out), HGNN_EUNSUPPORTED,
+               "%s: needs ld %% 8 == 0 and 16-byte aligned X, out (rows are moved in 16-byte pieces up to the pitch)", who);
+  const int F8 = (F + 7) / 8;
+  scale_rows_kernel<<<dim3(unsigned(ceil_div(n * F8, kBlock))), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
+      n, F8, reinterpret_cast<const half_t*>(X), ldx, scale, reinterpret_cast<half_t*>(out), ldo);
+  HGNN_LAUNCH_CHECK("scale_rows_kernel");
   return HGNN_OK;
 }

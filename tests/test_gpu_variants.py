@@ -376,3 +376,25 @@ def test_edge_to_transposed_and_backward_without_edge_ids(hgnn, dev, H):
     with pytest.raises(hgnn.HgnnError):
         hgnn.hgnn_edge_to_transposed(g, H, up(w, dev), wT)  # no edge-id map
     hgnn.hgnn_plan_destroy(pt)
+
+
+def test_scale_rows_then_unweighted_spmm_is_the_column_norm(hgnn, dev):
+    """Eq. 2 with the column-side norm applied to the table first: the same as col_scale in the fused call, up to
+    one fp16 rounding of every scaled feature."""
+    V, ncols, F = 500, 600, 64
+    rowptr, col = rand_graph(V, ncols, 10, 5, hubs=((4, 2000),), empties=(9,))
+    r = np.random.default_rng(3)
+    X = f16(r.standard_normal((ncols, F)))
+    cs = r.uniform(0.05, 1.0, ncols).astype(np.float32)
+    rs = r.uniform(0.05, 1.0, V).astype(np.float32)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    p = hgnn.hgnn_plan_create(g, 256, F, 1)
+    Xs = torch.empty((ncols, F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_scale_rows(up(X, dev), up(cs, dev), Xs)
+    want = (cs[:, None] * X.astype(np.float32)).astype(np.float16)  # fp32 product, then one RNE rounding to fp16
+    assert np.array_equal(down(Xs).view(np.uint16), want.view(np.uint16))
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized(p, g, None, 1, Xs, Y, row_scale=up(rs, dev))
+    ref, sabs = oracle.spmm(rowptr, col, X, row_scale=rs.astype(np.float64), col_scale=cs.astype(np.float64), want_sabs=True)
+    compare("pre-scaled column norm", down(Y), ref, 2 * sabs)  # the extra rounding of the scaled table
+    hgnn.hgnn_plan_destroy(p)
