@@ -198,14 +198,14 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
   }
 }
 
-// Hubs.  A row longer than kLongRow is cut into chunks of kHubChunk non-zeros, one workgroup per
-// chunk, so that a hub of 10^5 edges keeps dozens of compute units busy instead of one.  Three
+// Hubs.  A row longer than kLongRow is cut into chunks of kHubChunk non-zeros, one wave per chunk,
+// so that a hub of 10^5 edges keeps dozens of compute units busy instead of one.  Three
 // launches: hub_scan_kernel lists the hubs and hands every one a run of consecutive chunk slots
 // (the slot numbers depend on the order in which the atomic counter is reached, the values
-// computed do not); spmm_hub_kernel reduces one chunk per workgroup into an fp32 partial row in
+// computed do not); spmm_hub_kernel reduces one chunk per wave into an fp32 partial row in
 // scratch memory; spmm_hub_sum_kernel adds a hub's partial rows in chunk order and stores the row.
 // No atomics touch feature data and the summation order is fixed.
-constexpr int kHubChunk = 2048;
+constexpr int kHubChunk = 512;
 
 struct HubLists {
   int* count;      // [0] chunks handed out, [1] hubs listed
@@ -278,40 +278,29 @@ __global__ __launch_bounds__(kBlock) void hub_scan_kernel(SpmmArgs a, HubLists h
   }
 }
 
+// one wave per chunk, single-wave workgroups walking the chunk list with a grid stride
 template <int L, bool HAS_W>
-__global__ __launch_bounds__(kBlock) void spmm_hub_kernel(SpmmArgs a, HubLists h) {
+__global__ __launch_bounds__(kWave) void spmm_hub_kernel(SpmmArgs a, HubLists h) {
   constexpr int G = kWave / L;
-  __shared__ float s_part[kWavesPerBlock][8 * L];
   const int nchunks = h.count[0] < h.max_chunks ? h.count[0] : h.max_chunks;
-  if (int(blockIdx.x) >= nchunks) return;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x;
   const int g = lane / L, l = lane % L;
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  const int row = h.chunk_row[blockIdx.x];
-  const int row_end = a.rowptr[row + 1];
-  const int cb = a.rowptr[row] + h.chunk_no[blockIdx.x] * kHubChunk;
-  const int len = row_end - cb < kHubChunk ? row_end - cb : kHubChunk;
-  const int per_wave = (len + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int b = cb + wave * per_wave < row_end ? cb + wave * per_wave : row_end;
-  const int e = b + per_wave < row_end ? b + per_wave : row_end;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  edges_accumulate<G, HAS_W, 4>(a, b + g, e, f0c, f0c / a.D, acc);
-  groups_reduce<L>(acc);
-  if (g == 0) {
+  const int pitch = (a.F + 7) & ~7;
+  for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+    const int row = h.chunk_row[c];
+    const int row_end = a.rowptr[row + 1];
+    const int b = a.rowptr[row] + h.chunk_no[c] * kHubChunk;
+    const int e = b + kHubChunk < row_end ? b + kHubChunk : row_end;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    edges_accumulate<G, HAS_W, 4>(a, b + g, e, f0c, f0c / a.D, acc);
+    groups_reduce<L>(acc);
+    if (g == 0 && active) {
+      float* out = h.part + c * pitch + f0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) s_part[wave][f0 + i] = acc[i];
-  }
-  __syncthreads();
-  if (wave == 0 && g == 0 && active) {
-    float* out = h.part + int64_t(blockIdx.x) * ((a.F + 7) & ~7) + f0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float t = s_part[0][f0 + i];
-#pragma unroll
-      for (int w = 1; w < kWavesPerBlock; ++w) t += s_part[w][f0 + i];
-      out[i] = t;
+      for (int i = 0; i < 8; ++i) out[i] = acc[i];
     }
   }
 }
@@ -945,7 +934,7 @@ template <int L, bool HAS_W>
 static void launch_row_set(dim3 grid, hipStream_t s, const SpmmArgs& a, const HubLists* h) {
   spmm_row_kernel<L, HAS_W><<<grid, kWave, 0, s>>>(a);  // its waves never meet: single-wave workgroups
   if (h) {
-    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks)), kBlock, 0, s>>>(a, *h);
+    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < 131072 ? h->max_chunks : 131072)), kWave, 0, s>>>(a, *h);
     spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
   }
 }
