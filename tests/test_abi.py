@@ -85,6 +85,34 @@ def test_argument_errors_are_caught_on_the_host(lib, hgnn):
     assert lib.hgnn_plan_num_segments(None) == 0
 
 
+def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
+    """The variant, group, fused-GAT and table helpers refuse a missing plan or a bad scalar before any launch."""
+    g = make_csr(hgnn)
+    gp = ctypes.byref(g)
+    X, Y, A = 0x10000, 0x20000, 0x30000
+    EINVAL = hgnn.HGNN_EINVAL
+    assert lib.hgnn_spmm_discretized_variant(None, gp, None, 1, X, 8, Y, 8, 8, 0, None, 0, None) == EINVAL
+    assert lib.hgnn_plan_add_groups(None, gp, 32, None) == EINVAL
+    assert lib.hgnn_plan_num_groups(None) == 0
+    assert lib.hgnn_plan_group_edges(None) == 0
+    assert lib.hgnn_plan_groups_export(None, gp, X, Y) == EINVAL
+    assert lib.hgnn_gat_forward_fused(gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, None) == EINVAL
+    assert lib.hgnn_gat_alpha(gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, A, Y, None) == EINVAL
+    assert lib.hgnn_gat_backward_fused(gp, None, gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, X, 8,
+                                       Y, 8, A, A, None) == EINVAL
+    assert lib.hgnn_edge_to_transposed(None, 1, X, Y, None) == EINVAL
+    assert lib.hgnn_edge_to_transposed(gp, 1, X, Y, None) == EINVAL           # a transposed graph carries eid
+    assert lib.hgnn_scale_rows(4, 0, X, 8, A, Y, 8, None) == EINVAL            # F <= 0
+    assert lib.hgnn_scale_rows(4, 8, X, 12, A, Y, 8, None) == hgnn.HGNN_EUNSUPPORTED  # pitch not a multiple of 8
+    assert lib.hgnn_scale_rows(4, 8, X, 4, A, Y, 8, None) == EINVAL            # pitch < F
+    assert lib.hgnn_scale_rows(4, 8, X, 8, None, Y, 8, None) == EINVAL         # scale NULL
+    assert lib.hgnn_scale_rows(-1, 8, X, 8, A, Y, 8, None) == EINVAL
+    keep = lib.hgnn_get_vector_halves()
+    assert lib.hgnn_set_vector_halves(3) == EINVAL
+    assert lib.hgnn_set_vector_halves(2) == hgnn.HGNN_OK and lib.hgnn_get_vector_halves() == 2
+    assert lib.hgnn_set_vector_halves(keep) == hgnn.HGNN_OK
+
+
 def test_binding_refuses_cpu_tensors(hgnn):
     import torch
     with pytest.raises(TypeError):
