@@ -67,6 +67,12 @@ def _load():
     lib.orc_edge_colsum.argtypes = [i32, i32, vp, vp, i32, vp, vp]
     lib.orc_edge_gather.restype = None
     lib.orc_edge_gather.argtypes = [i64, vp, i32, vp, vp]
+    lib.orc_linear.restype = None
+    lib.orc_linear.argtypes = [i64, i32, i32, vp, i64, vp, i64, i32, vp, vp]
+    lib.orc_linear_wgrad.restype = None
+    lib.orc_linear_wgrad.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, vp]
+    lib.orc_gat_feature_grad.restype = None
+    lib.orc_gat_feature_grad.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.orc_segment_plan.restype = i32
     lib.orc_segment_plan.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     lib.orc_spmm_naive_fp16.restype = None
@@ -226,6 +232,43 @@ def edge_gather(eid, t):
     out = np.empty_like(t)
     _load().orc_edge_gather(eid.size, _ptr(eid), t.shape[1], _ptr(t), _ptr(out))
     return out
+
+
+def linear(X, W, trans: bool = False, want_sabs: bool = False):
+    """Y = X.W (W is [K][F]) or X.W^T (trans, W is [F][K]); fp16 in, fp64 out."""
+    X, W = _f16(X), _f16(W)
+    n, K = X.shape
+    F = W.shape[0] if trans else W.shape[1]
+    assert (W.shape[1] if trans else W.shape[0]) == K
+    out = np.empty((n, F), dtype=np.float64)
+    sabs = np.empty((n, F), dtype=np.float64)
+    _load().orc_linear(n, K, F, _ptr(X), X.shape[1], _ptr(W), W.shape[1], 1 if trans else 0, _ptr(out), _ptr(sabs))
+    return (out, sabs) if want_sabs else out
+
+
+def linear_wgrad(X, dY, want_sabs: bool = False):
+    """dW = X^T.dY ([K][F]); fp16 in, fp64 out."""
+    X, dY = _f16(X), _f16(dY)
+    n, K = X.shape
+    F = dY.shape[1]
+    assert dY.shape[0] == n
+    out = np.empty((K, F), dtype=np.float64)
+    sabs = np.empty((K, F), dtype=np.float64)
+    _load().orc_linear_wgrad(n, K, F, _ptr(X), K, _ptr(dY), F, _ptr(out), _ptr(sabs))
+    return (out, sabs) if want_sabs else out
+
+
+def gat_feature_grad(dV, d_el, d_er, a_l, a_r, hfeat, H: int):
+    """-> dh [V][F], da_l [F], da_r [F], and the term magnitudes of da_l, da_r (all fp64) from fp16 inputs."""
+    dV, d_el, d_er, hfeat = _f16(dV), _f16(d_el), _f16(d_er), _f16(hfeat)
+    a_l, a_r = _f16(np.asarray(a_l).reshape(-1)), _f16(np.asarray(a_r).reshape(-1))
+    V, F = dV.shape
+    D = F // H
+    dh = np.empty((V, F), dtype=np.float64)
+    da_l, da_r, sl, sr = (np.empty(F, dtype=np.float64) for _ in range(4))
+    _load().orc_gat_feature_grad(V, H, D, _ptr(dV), F, _ptr(d_el), _ptr(d_er), _ptr(a_l), _ptr(a_r), _ptr(hfeat), F,
+                                 _ptr(dh), _ptr(da_l), _ptr(da_r), _ptr(sl), _ptr(sr))
+    return dh, da_l, da_r, sl, sr
 
 
 def segment_plan(rowptr, S: int):

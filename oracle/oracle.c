@@ -338,6 +338,67 @@ void orc_edge_gather(int64_t nnz, const int32_t* eid, int32_t H, const uint16_t*
     for (int32_t h = 0; h < H; ++h) out[k * H + h] = t[(int64_t)eid[k] * H + h];
 }
 
+/* ---- the dense side of a layer (section 3.1.3, Eq. 2: the linear layer turns the previous
+ * activation into the dense input of the SpMM; section 6: the input width is projected to the
+ * intermediate width by a GeMM).  Y[i,f] = sum_k X[i,k] * W[k,f] (trans = 0, W is K x F) or
+ * sum_k X[i,k] * W[f,k] (trans = 1, W is F x K: the product with the transposed weight that
+ * carries a gradient back through the layer).  sabs = sum_k |X*W| per output, for tolerances. ---- */
+void orc_linear(int64_t n, int32_t K, int32_t F, const uint16_t* X, int64_t ldx, const uint16_t* W, int64_t ldw,
+                int32_t trans, double* Y, double* sabs) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int32_t f = 0; f < F; ++f) {
+      double acc = 0.0, sa = 0.0;
+      for (int32_t k = 0; k < K; ++k) {
+        double w = orc_half_to_double(trans ? W[(int64_t)f * ldw + k] : W[(int64_t)k * ldw + f]);
+        double t = orc_half_to_double(X[i * ldx + k]) * w;
+        acc += t;
+        sa += fabs(t);
+      }
+      Y[i * F + f] = acc;
+      if (sabs) sabs[i * F + f] = sa;
+    }
+}
+
+/* ---- gradient of the weight of that layer: dW[k,f] = sum_i X[i,k] * dY[i,f] (K x F) ---- */
+void orc_linear_wgrad(int64_t n, int32_t K, int32_t F, const uint16_t* X, int64_t ldx, const uint16_t* dY, int64_t ldy,
+                      double* dW, double* sabs) {
+  for (int32_t k = 0; k < K; ++k)
+    for (int32_t f = 0; f < F; ++f) {
+      double acc = 0.0, sa = 0.0;
+      for (int64_t i = 0; i < n; ++i) {
+        double t = orc_half_to_double(X[i * ldx + k]) * orc_half_to_double(dY[i * ldy + f]);
+        acc += t;
+        sa += fabs(t);
+      }
+      dW[(int64_t)k * F + f] = acc;
+      if (sabs) sabs[(int64_t)k * F + f] = sa;
+    }
+}
+
+/* ---- gradient of the projected features of a GAT layer and of its attention vectors, from what
+ * orc_gat_backward leaves (section 2.1.1: the score is a_l.h_i + a_r.h_j, so it reaches the
+ * features through both vectors):
+ *   dh[i, h*D+d]  = dV[i, h*D+d] + d_el[i,h] * a_l[h*D+d] + d_er[i,h] * a_r[h*D+d]
+ *   da_l[h*D+d]   = sum_i d_el[i,h] * hfeat[i, h*D+d],   da_r likewise with d_er. ---- */
+void orc_gat_feature_grad(int32_t V, int32_t H, int32_t D, const uint16_t* dV, int64_t lddv, const uint16_t* d_el,
+                          const uint16_t* d_er, const uint16_t* a_l, const uint16_t* a_r, const uint16_t* hfeat,
+                          int64_t ldh, double* dh, double* da_l, double* da_r, double* sabs_l, double* sabs_r) {
+  int32_t F = H * D;
+  for (int32_t f = 0; f < F; ++f) da_l[f] = da_r[f] = sabs_l[f] = sabs_r[f] = 0.0;
+  for (int32_t i = 0; i < V; ++i)
+    for (int32_t f = 0; f < F; ++f) {
+      int32_t h = f / D;
+      double gl = orc_half_to_double(d_el[(int64_t)i * H + h]), gr = orc_half_to_double(d_er[(int64_t)i * H + h]);
+      double x = orc_half_to_double(hfeat[(int64_t)i * ldh + f]);
+      dh[(int64_t)i * F + f] = orc_half_to_double(dV[(int64_t)i * lddv + f]) + gl * orc_half_to_double(a_l[f]) +
+                               gr * orc_half_to_double(a_r[f]);
+      da_l[f] += gl * x;
+      da_r[f] += gr * x;
+      sabs_l[f] += fabs(gl * x);
+      sabs_r[f] += fabs(gr * x);
+    }
+}
+
 /* ---- segment plan for the discretized SpMM (section 5.2: edges are dealt out in
  * fixed-size batches in storage order, observation rules 1-3).
  * Segment k owns edges [k*S, min(E,(k+1)*S)).  seg_row_lo/hi[k] = row of its first /

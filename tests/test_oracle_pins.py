@@ -588,6 +588,102 @@ def test_edge_gather_is_the_transposed_order():
         np.testing.assert_allclose(b[:, 2 * h:2 * h + 2], A.T @ X.astype(np.float64)[:, 2 * h:2 * h + 2], rtol=1e-12, atol=1e-13)
 
 
+# ------------------------------------------------------------------ dense side of a layer
+def test_linear_against_matmul_and_special_cases():
+    """Section 3.1.3 (Eq. 2): the linear layer is a plain matrix product; numpy's fp64 matmul is the library form."""
+    n, K, F = 23, 12, 10
+    X = rng.standard_normal((n, K)).astype(np.float16)
+    W = rng.standard_normal((K, F)).astype(np.float16)
+    Xd, Wd = X.astype(np.float64), W.astype(np.float64)
+    Y, sabs = oracle.linear(X, W, want_sabs=True)
+    np.testing.assert_allclose(Y, Xd @ Wd, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sabs, np.abs(Xd) @ np.abs(Wd), rtol=1e-13, atol=1e-13)
+    # the transposed form reads the same weight the other way round
+    np.testing.assert_allclose(oracle.linear(X, np.ascontiguousarray(W.T), trans=True), Y, rtol=0, atol=0)
+    G = rng.standard_normal((n, F)).astype(np.float16)
+    np.testing.assert_allclose(oracle.linear(G, W, trans=True), G.astype(np.float64) @ Wd.T, rtol=1e-13, atol=1e-13)
+    # identity weight copies the input; a one-hot input row picks one row of W (not a column)
+    assert np.array_equal(oracle.linear(X, np.eye(K, dtype=np.float16)), Xd)
+    onehot = np.zeros((K, K), dtype=np.float16)
+    onehot[np.arange(K), np.arange(K)[::-1]] = 1
+    assert np.array_equal(oracle.linear(onehot, W), Wd[::-1])
+    # non-square, asymmetric closed form: X = column index pattern, W = outer product
+    u, v = np.arange(1, K + 1, dtype=np.float64), np.arange(1, F + 1, dtype=np.float64)
+    Y2 = oracle.linear(np.ones((3, K), dtype=np.float16), np.outer(u, v).astype(np.float16))
+    np.testing.assert_allclose(Y2, np.tile(u.sum() * v, (3, 1)), rtol=1e-13)
+
+
+def test_linear_adjoints():
+    """<X W, G> = <X, G W^T> = <W, X^T G>: ties the forward product, the transposed product and the weight gradient."""
+    n, K, F = 31, 7, 5
+    X = rng.standard_normal((n, K)).astype(np.float16)
+    W = rng.standard_normal((K, F)).astype(np.float16)
+    G = rng.standard_normal((n, F)).astype(np.float16)
+    a = float((oracle.linear(X, W) * G.astype(np.float64)).sum())
+    b = float((X.astype(np.float64) * oracle.linear(G, W, trans=True)).sum())
+    dW, sabs = oracle.linear_wgrad(X, G, want_sabs=True)
+    c = float((W.astype(np.float64) * dW).sum())
+    assert abs(a - b) < 1e-10 and abs(a - c) < 1e-10
+    np.testing.assert_allclose(dW, X.astype(np.float64).T @ G.astype(np.float64), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(sabs, np.abs(X.astype(np.float64)).T @ np.abs(G.astype(np.float64)), rtol=1e-13, atol=1e-13)
+    # a single row: the weight gradient is the outer product x g^T (k indexes rows, f columns)
+    np.testing.assert_array_equal(oracle.linear_wgrad(X[:1], G[:1]), np.outer(X[0].astype(np.float64), G[0].astype(np.float64)))
+
+
+def test_gat_layer_gradients_match_finite_differences():
+    """A whole layer, h = X W then the aggregation on (h, h): L = sum <dOut, out>.  Its gradients, chained as
+    gat_backward -> gat_feature_grad -> linear (transposed) / linear_wgrad, against central differences of the
+    forward chain.  All values sit on binary grids so that every perturbed h is exact in fp16; the chained
+    gradients pass through fp16 (as on the device), hence the 5e-3 band."""
+    V, H, D, K = 9, 2, 4, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, V, 0.5, 77, empty_rows=(4,))
+    grid = lambda shape: (rng.integers(-4, 5, size=shape) / 4.0).astype(np.float16)
+    X, W, dOut = grid((V, K)), grid((K, F)), grid((V, F))
+    a_l, a_r = grid(F), grid(F)
+    slope = 0.25
+
+    def forward(X_, W_, al_, ar_):
+        h64 = oracle.linear(X_, W_)
+        h = h64.astype(np.float16)
+        assert np.array_equal(h.astype(np.float64), h64)  # exact: nothing is lost between the two stages
+        out, _, _ = oracle.gat_forward(rowptr, col, h, h, al_, ar_, H, slope=slope)
+        return h, float((out * dOut.astype(np.float64)).sum())
+
+    h, _ = forward(X, W, a_l, a_r)
+    dV, d_el, d_er = oracle.gat_backward(rowptr, col, h, h, a_l, a_r, dOut, H, slope=slope)
+    dh, da_l, da_r, _, _ = oracle.gat_feature_grad(dV.astype(np.float16), d_el.astype(np.float16), d_er.astype(np.float16),
+                                                   a_l, a_r, h, H)
+    # the un-rounded definition of the feature gradient, term by term
+    want = dV + np.repeat(d_el, D, axis=1) * a_l.astype(np.float64) + np.repeat(d_er, D, axis=1) * a_r.astype(np.float64)
+    assert np.max(np.abs(dh - want)) < 5e-3
+    dX = oracle.linear(dh.astype(np.float16), W, trans=True)
+    dW = oracle.linear_wgrad(X, dh.astype(np.float16))
+    eps = 2.0 ** -6
+
+    def central(make):
+        return (forward(*make(+eps))[1] - forward(*make(-eps))[1]) / (2 * eps)
+
+    def bump(a, idx, d):
+        b = a.copy()
+        b[idx] += np.float16(d)
+        return b
+
+    for idx in [(0, 0), (3, 2), (8, 3), (4, 1)]:
+        fd = central(lambda d: (bump(X, idx, d), W, a_l, a_r))
+        assert abs(fd - dX[idx]) < 5e-3, (idx, fd, dX[idx])
+    for idx in [(0, 0), (1, 5), (3, 7), (2, 2)]:
+        fd = central(lambda d: (X, bump(W, idx, d), a_l, a_r))
+        assert abs(fd - dW[idx]) < 5e-3, (idx, fd, dW[idx])
+    for f in (0, 3, 6):
+        fd = central(lambda d: (X, W, bump(a_l, f, d), a_r))
+        assert abs(fd - da_l[f]) < 5e-3, (f, fd, da_l[f])
+        fd = central(lambda d: (X, W, a_l, bump(a_r, f, d)))
+        assert abs(fd - da_r[f]) < 5e-3, (f, fd, da_r[f])
+    # the gradients are not trivially small: the bands above mean something
+    assert np.abs(dX).max() > 0.2 and np.abs(dW).max() > 0.2 and np.abs(da_l).max() > 0.05 and np.abs(da_r).max() > 0.05
+
+
 # ------------------------------------------------------------------ neighbour groups (vertex-parallel variant)
 @pytest.mark.parametrize("ng", [1, 4, 32, 64])
 def test_neighbor_groups_bruteforce(ng):
