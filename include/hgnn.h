@@ -253,6 +253,44 @@ int32_t hgnn_get_vector_halves(void);
 hgnn_status hgnn_scale_rows(int64_t n, int32_t F, const hgnn_half* X, int64_t ldx, const float* scale, hgnn_half* out,
                             int64_t ldo, void* stream);
 
+/* ---- the dense side of a layer, on the matrix cores ----------------------------------------------
+ * The linear layer's output is the dense input of the sparse kernels (section 3.1.3, Eq. 2); the input
+ * width is projected to the intermediate width by a GeMM (section 6).  These calls make a whole layer
+ * expressible on this library; they use v_mfma_f32_32x32x16_f16 with fp32 accumulation. */
+
+/* Y[i, f] = fp16( sum_k X[i, k] * W[k, f] )   (trans_w = 0, W is [K][ldw >= F]) or
+ *           fp16( sum_k X[i, k] * W[f, k] )   (trans_w != 0, W is [F][ldw >= K]: the product with the
+ * transposed weight, which carries the gradient of Y back to X).  X is [n][ldx], Y is [n][ldy]; all
+ * device pointers, caller-owned.  Needs K % 8 == 0, ldx % 8 == 0, ldy % 8 == 0 and 16-byte aligned X, Y
+ * (HGNN_EUNSUPPORTED otherwise: pad with zeros); F may be any positive number.  W needs no alignment. */
+hgnn_status hgnn_linear(int64_t n, int32_t K, int32_t F, const hgnn_half* X, int64_t ldx, const hgnn_half* W, int64_t ldw,
+                        int32_t trans_w, hgnn_half* Y, int64_t ldy, void* stream);
+
+/* dW[k, f] = sum_i X[i, k] * dY[i, f], fp32 [K][lddw >= F]: the gradient of the weight of hgnn_linear
+ * (trans_w = 0) given the gradient dY of its output.  Partial sums of fixed row sets are written to the
+ * workspace and added in a fixed order: no atomics, the same bits on every run.  workspace is device
+ * memory of at least hgnn_linear_wgrad_workspace(K, F) bytes (4-byte aligned), owned by the caller and
+ * overwritten; the call allocates nothing.  Needs K, F, ldx, ldy % 8 == 0, K, F <= 4096 and 16-byte
+ * aligned X, dY. */
+size_t hgnn_linear_wgrad_workspace(int32_t K, int32_t F);
+hgnn_status hgnn_linear_wgrad(int64_t n, int32_t K, int32_t F, const hgnn_half* X, int64_t ldx, const hgnn_half* dY,
+                              int64_t ldy, float* dW, int64_t lddw, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Ties hgnn_gat_backward_fused to the projection of a GAT layer whose row and column side are the same
+ * table hfeat [n][ldh] (section 2.1.1: the score is a_l.h_i + a_r.h_j, so its gradient reaches the
+ * features through both vectors):
+ *   dh[i, h*D+d] = fp16( dV[i, h*D+d] + d_el[i,h] * a_l[h*D+d] + d_er[i,h] * a_r[h*D+d] )   [n][lddh]
+ *   da_l[h*D+d]  = sum_i d_el[i,h] * hfeat[i, h*D+d],  da_r likewise with d_er            fp32 [H*D]
+ * dV is [n][lddv], d_el / d_er are fp16 [n][H].  The sums over i are formed per workgroup and added in a
+ * fixed order through the workspace (at least hgnn_gat_feature_grad_workspace(H, D) bytes of device
+ * memory, caller-owned, overwritten).  Needs D % 8 == 0, H*D <= 512, ld % 8 == 0, 16-byte aligned
+ * dV, hfeat, dh. */
+size_t hgnn_gat_feature_grad_workspace(int32_t H, int32_t D);
+hgnn_status hgnn_gat_feature_grad(int64_t n, int32_t H, int32_t D, const hgnn_half* dV, int64_t lddv, const hgnn_half* d_el,
+                                  const hgnn_half* d_er, const hgnn_half* a_l, const hgnn_half* a_r, const hgnn_half* hfeat,
+                                  int64_t ldh, hgnn_half* dh, int64_t lddh, float* da_l, float* da_r, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
 /* SDDMM over the non-zeros of g (sections 2.1.2, 5.1.3), result in out[k*H + h]:
  *   DOT:        sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d],  i = row of k
  *   GAT_SCORE:  s = a_l[h].U[i,h,:] + a_r[h].Vt[col[k],h,:];  s > 0 ? s : neg_slope*s

@@ -26,7 +26,8 @@ EXPORTS = (
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
     "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
-    "hgnn_edge_to_transposed", "hgnn_scale_rows",
+    "hgnn_edge_to_transposed", "hgnn_scale_rows", "hgnn_linear", "hgnn_linear_wgrad", "hgnn_linear_wgrad_workspace",
+    "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -106,6 +107,14 @@ def load() -> ctypes.CDLL:
                                             vp, i64, vp, vp, vp]
     lib.hgnn_get_vector_halves.restype = i32
     lib.hgnn_get_vector_halves.argtypes = []
+    lib.hgnn_linear.argtypes = [i64, i32, i32, vp, i64, vp, i64, i32, vp, i64, vp]
+    lib.hgnn_linear_wgrad_workspace.argtypes = [i32, i32]
+    lib.hgnn_linear_wgrad_workspace.restype = ctypes.c_size_t
+    lib.hgnn_linear_wgrad.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp, ctypes.c_size_t, vp]
+    lib.hgnn_gat_feature_grad_workspace.argtypes = [i32, i32]
+    lib.hgnn_gat_feature_grad_workspace.restype = ctypes.c_size_t
+    lib.hgnn_gat_feature_grad.argtypes = [i64, i32, i32, vp, i64, vp, vp, vp, vp, vp, i64, vp, i64, vp, vp, vp,
+                                          ctypes.c_size_t, vp]
     for name in EXPORTS:
         getattr(lib, name)  # every declared entry point must be exported
     _lib = lib
@@ -326,6 +335,43 @@ def hgnn_scale_rows(X: torch.Tensor, scale: torch.Tensor, out: torch.Tensor, F: 
     F = X.shape[1] if F is None else F
     _check(load().hgnn_scale_rows(X.shape[0], F, _ptr(X, torch.float16), _ld(X), _ptr(scale, torch.float32),
                                   _ptr(out, torch.float16), _ld(out), _stream(stream)))
+
+
+def hgnn_linear(X: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, trans_w: bool = False, K: Optional[int] = None,
+                F: Optional[int] = None, stream=None) -> None:
+    """Y = X.W (W is [K][F]) or X.W^T (trans_w, W is [F][K])."""
+    K = X.shape[1] if K is None else K
+    F = (W.shape[0] if trans_w else W.shape[1]) if F is None else F
+    _check(load().hgnn_linear(X.shape[0], K, F, _ptr(X, torch.float16), _ld(X), _ptr(W, torch.float16), _ld(W),
+                              1 if trans_w else 0, _ptr(Y, torch.float16), _ld(Y), _stream(stream)))
+
+
+def hgnn_linear_wgrad_workspace(K: int, F: int) -> int:
+    return load().hgnn_linear_wgrad_workspace(K, F)
+
+
+def hgnn_linear_wgrad(X: torch.Tensor, dY: torch.Tensor, dW: torch.Tensor, workspace: torch.Tensor, K: Optional[int] = None,
+                      F: Optional[int] = None, stream=None) -> None:
+    """dW (fp32 [K][F]) = X^T.dY; workspace is a device byte/float tensor of hgnn_linear_wgrad_workspace(K, F) bytes."""
+    K = X.shape[1] if K is None else K
+    F = dY.shape[1] if F is None else F
+    _check(load().hgnn_linear_wgrad(X.shape[0], K, F, _ptr(X, torch.float16), _ld(X), _ptr(dY, torch.float16), _ld(dY),
+                                    _ptr(dW, torch.float32), _ld(dW), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def hgnn_gat_feature_grad_workspace(H: int, D: int) -> int:
+    return load().hgnn_gat_feature_grad_workspace(H, D)
+
+
+def hgnn_gat_feature_grad(H: int, D: int, dV: torch.Tensor, d_el: torch.Tensor, d_er: torch.Tensor, a_l: torch.Tensor,
+                          a_r: torch.Tensor, hfeat: torch.Tensor, dh: torch.Tensor, da_l: torch.Tensor, da_r: torch.Tensor,
+                          workspace: torch.Tensor, stream=None) -> None:
+    _check(load().hgnn_gat_feature_grad(dV.shape[0], H, D, _ptr(dV, torch.float16), _ld(dV), _ptr(d_el, torch.float16),
+                                        _ptr(d_er, torch.float16), _ptr(a_l, torch.float16), _ptr(a_r, torch.float16),
+                                        _ptr(hfeat, torch.float16), _ld(hfeat), _ptr(dh, torch.float16), _ld(dh),
+                                        _ptr(da_l, torch.float32), _ptr(da_r, torch.float32), workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def hgnn_edge_to_transposed(gt: Csr, H: int, t: torch.Tensor, t_T: torch.Tensor, stream=None) -> None:
