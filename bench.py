@@ -350,6 +350,41 @@ def main():
                  "gat_backward_fused_ms": round(t_b, 4), "five_call_backward_ms": round(five, 4),
                  "gat_fwd_bwd_fused_ms": round(t_f + t_b, 4), "alpha_from_lse_ms": round(t_a, 4)}
 
+    # the dense side of a layer on the matrix cores (hidden -> hidden projection of this workload's width), and for the
+    # GAT workloads a whole layer: projection + fused aggregation forward, and every gradient backward
+    Wd = (torch.randn((F, F), device=dev, dtype=torch.float32) / (F ** 0.5)).to(half)
+    hproj = torch.empty_like(X)
+    dW = torch.empty((F, F), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(hgnn.hgnn_linear_wgrad_workspace(F, F), hgnn.hgnn_gat_feature_grad_workspace(H, D)),
+                     dtype=torch.uint8, device=dev)
+    lin_bytes = V * (F + F) * 2 + F * F * 2
+    t_lin = time_call(lambda: hgnn.hgnn_linear(X, Wd, hproj))
+    t_lint = time_call(lambda: hgnn.hgnn_linear(dY, Wd, hproj, trans_w=True))
+    t_wg = time_call(lambda: hgnn.hgnn_linear_wgrad(X, dY, dW, ws))
+    dense = {"K": F, "F": F, "linear_ms": round(t_lin, 4), "linear_GBps": round(lin_bytes / (t_lin * 1e-3) / 1e9, 1),
+             "linear_transposed_ms": round(t_lint, 4), "linear_wgrad_ms": round(t_wg, 4),
+             "linear_wgrad_GBps": round((V * 2 * F * 2 + F * F * 4) / (t_wg * 1e-3) / 1e9, 1)}
+    if has_gat:
+        da_l, da_r = torch.empty(F, dtype=torch.float32, device=dev), torch.empty(F, dtype=torch.float32, device=dev)
+        dfeat, dXin = torch.empty_like(X), torch.empty_like(X)
+
+        def layer_fwd():
+            hgnn.hgnn_linear(X, Wd, hproj)
+            hgnn.hgnn_gat_forward_fused(g, plan, H, D, hproj, hproj, a_l, a_r, out, lse)
+
+        def layer_bwd():
+            hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, hproj, hproj, a_l, a_r, out, lse, dY, dh, d_el, d_er)
+            hgnn.hgnn_gat_feature_grad(H, D, dh, d_el, d_er, a_l, a_r, hproj, dfeat, da_l, da_r, ws)
+            hgnn.hgnn_linear(dfeat, Wd, dXin, trans_w=True)
+            hgnn.hgnn_linear_wgrad(X, dfeat, dW, ws)
+
+        t_lf = time_call(layer_fwd)
+        t_lb = time_call(layer_bwd)
+        t_fg = time_call(lambda: hgnn.hgnn_gat_feature_grad(H, D, dh, d_el, d_er, a_l, a_r, hproj, dfeat, da_l, da_r, ws))
+        dense.update({"gat_feature_grad_ms": round(t_fg, 4), "gat_layer_with_projection_fwd_ms": round(t_lf, 4),
+                      "gat_layer_with_projection_bwd_ms": round(t_lb, 4),
+                      "gat_layer_with_projection_fwd_bwd_ms": round(t_lf + t_lb, 4)})
+
     variants = None
     if args.variants:
         # the paper's two SpMM micro-benchmarks (atomic vs. non-atomic conflict writes; the vertex-parallel
@@ -422,7 +457,7 @@ def main():
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
-        "layers": layer_ms, "ops": detail, "column_norm": prescaled, "graph": graph_info, "static_edge_values": static_w, "gat_fused": fused, "variants": variants, "width_sweep": width_sweep,
+        "layers": layer_ms, "ops": detail, "column_norm": prescaled, "graph": graph_info, "static_edge_values": static_w, "gat_fused": fused, "dense": dense, "variants": variants, "width_sweep": width_sweep,
         "setup": {"generate_s": round(gen_s, 2), "transpose_and_plans_s": round(setup_s, 3)},
     }
     if args.detail:

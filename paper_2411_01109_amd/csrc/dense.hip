@@ -48,8 +48,24 @@ __device__ __forceinline__ unsigned pack2(float a, float b) {
 // row blocks grid-stride, otherwise once per row block and chunk of K.  The product is formed transposed
 // (features x rows), which leaves every lane with values of ONE row of Y: after one exchange between the two
 // half-waves a lane stores two 16-byte pieces.
+// the four 16-byte pieces of X that one lane feeds into four consecutive MFMA steps (64 columns from k0 on)
+struct XGroup {
+  half8_t b[4];
+};
+
+__device__ __forceinline__ XGroup load_xgroup(const half_t* xrow, bool row_ok, int k0, int kn, int hf) {
+  XGroup g;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int kk = k0 + 16 * u + 8 * hf;
+    g.b[u] = (row_ok && kk < kn) ? *reinterpret_cast<const half8_t*>(xrow + kk) : zero;
+  }
+  return g;
+}
+
 template <int NT>
-__global__ __launch_bounds__(kBlock) void linear_kernel(LinearArgs a) {
+__global__ __launch_bounds__(kBlock, NT == 4 ? 3 : 4) void linear_kernel(LinearArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   half_t* Wt = reinterpret_cast<half_t*>(lds_raw);
   const int pitch = a.KC + 8;
@@ -59,6 +75,13 @@ __global__ __launch_bounds__(kBlock) void linear_kernel(LinearArgs a) {
   const int nchunks = (a.K + a.KC - 1) / a.KC;
   const int64_t nrb = (a.n + kRowsPerBlock - 1) / kRowsPerBlock;
   bool loaded = false;
+  // The loads of X run one group (64 columns) ahead of the products, across chunk and row-block borders, so
+  // that a wave always has memory requests in flight while it multiplies and stores.
+  XGroup next{};
+  if (int64_t(blockIdx.x) < nrb) {
+    const int64_t row = int64_t(blockIdx.x) * kRowsPerBlock + wave * kRowsPerWave + m;
+    next = load_xgroup(a.X + (row < a.n ? row : 0) * a.ldx, row < a.n, 0, min(a.KC, a.K), hf);
+  }
   for (int64_t rb = blockIdx.x; rb < nrb; rb += gridDim.x) {
     const int64_t row = rb * kRowsPerBlock + wave * kRowsPerWave + m;
     const bool row_ok = row < a.n;
@@ -90,30 +113,26 @@ __global__ __launch_bounds__(kBlock) void linear_kernel(LinearArgs a) {
         __syncthreads();
         loaded = true;
       }
-      int k0 = 0;
-      for (; k0 + 64 <= kn; k0 += 64) {  // four steps at a time: their loads are issued before the first product
-        half8_t b[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
-          b[u] = row_ok ? *reinterpret_cast<const half8_t*>(xrow + kc + k0 + 16 * u + 8 * hf) : zero;
+      for (int k0 = 0; k0 < kn; k0 += 64) {
+        const XGroup cur = next;
+        // what comes after this group: more of this chunk, the next chunk of the row, or the next row block
+        if (k0 + 64 < kn) {
+          next = load_xgroup(xrow + kc, row_ok, k0 + 64, kn, hf);
+        } else if (c + 1 < nchunks) {
+          next = load_xgroup(xrow + kc + a.KC, row_ok, 0, min(a.KC, a.K - kc - a.KC), hf);
+        } else if (rb + gridDim.x < nrb) {
+          const int64_t nrow = row + int64_t(gridDim.x) * kRowsPerBlock;
+          next = load_xgroup(a.X + (nrow < a.n ? nrow : 0) * a.ldx, nrow < a.n, 0, min(a.KC, a.K), hf);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u) {
+          if (k0 + 16 * u < kn) {  // uniform; keeps the LDS reads inside the tile
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            const half8_t w = *reinterpret_cast<const half8_t*>(Wt + (32 * t + m) * pitch + k0 + 16 * u + 8 * hf);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, b[u], acc[t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t) {
+              const half8_t w = *reinterpret_cast<const half8_t*>(Wt + (32 * t + m) * pitch + k0 + 16 * u + 8 * hf);
+              acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, cur.b[u], acc[t], 0, 0, 0);
+            }
           }
-      }
-      for (; k0 < kn; k0 += 16) {
-        const int kk = k0 + 8 * hf;
-        half8_t b = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (row_ok && kk < kn) b = *reinterpret_cast<const half8_t*>(xrow + kc + kk);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const half8_t w = *reinterpret_cast<const half8_t*>(Wt + (32 * t + m) * pitch + kk);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, b, acc[t], 0, 0, 0);
         }
       }
     }
@@ -121,33 +140,28 @@ __global__ __launch_bounds__(kBlock) void linear_kernel(LinearArgs a) {
     // gets the partner's halves of them, the upper one keeps q = 2, 3.
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      unsigned own[4][2];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        own[q][0] = pack2(acc[t][4 * q + 0], acc[t][4 * q + 1]);
-        own[q][1] = pack2(acc[t][4 * q + 2], acc[t][4 * q + 3]);
-      }
-      unsigned got[2][2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const unsigned send = hf ? own[j][i] : own[2 + j][i];
-          got[j][i] = unsigned(__shfl_xor(int(send), 32));
-        }
+      const float16_t c = acc[t];
+      const unsigned p0 = pack2(c[0], c[1]), p1 = pack2(c[2], c[3]), p2 = pack2(c[4], c[5]), p3 = pack2(c[6], c[7]);
+      const unsigned p4 = pack2(c[8], c[9]), p5 = pack2(c[10], c[11]), p6 = pack2(c[12], c[13]), p7 = pack2(c[14], c[15]);
+      const unsigned k0 = hf ? p4 : p0, k1 = hf ? p5 : p1, k2 = hf ? p6 : p2, k3 = hf ? p7 : p3;  // kept
+      const unsigned g0 = unsigned(__shfl_xor(int(hf ? p0 : p4), 32)), g1 = unsigned(__shfl_xor(int(hf ? p1 : p5), 32));
+      const unsigned g2 = unsigned(__shfl_xor(int(hf ? p2 : p6), 32)), g3 = unsigned(__shfl_xor(int(hf ? p3 : p7), 32));
       if (row_ok) {
+        // lower half-wave: its own values are features 0..3 of a group, the partner's 4..7; upper: the other way
+        const int4_t va = hf ? int4_t{int(g0), int(g1), int(k0), int(k1)} : int4_t{int(k0), int(k1), int(g0), int(g1)};
+        const int4_t vb = hf ? int4_t{int(g2), int(g3), int(k2), int(k3)} : int4_t{int(k2), int(k3), int(g2), int(g3)};
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int f = fc0 + 32 * t + 8 * (2 * hf + j);
-          int4_t v;
-          if (hf) v = int4_t{int(got[j][0]), int(got[j][1]), int(own[2 + j][0]), int(own[2 + j][1])};
-          else v = int4_t{int(own[j][0]), int(own[j][1]), int(got[j][0]), int(got[j][1])};
+          const int4_t v = j ? vb : va;
           half_t* dst = a.Y + row * a.ldy + f;
           if (f + 8 <= a.F) {
             *reinterpret_cast<int4_t*>(dst) = v;
           } else if (f < a.F) {
             const half8_t h = __builtin_bit_cast(half8_t, v);
-            for (int i = 0; i < a.F - f; ++i) dst[i] = h[i];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              if (i < a.F - f) dst[i] = h[i];
           }
         }
       }
