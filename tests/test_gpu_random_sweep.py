@@ -1,0 +1,90 @@
+"""Seeded random configurations through the main entry points: shapes, segment sizes, column blocks, head counts,
+degree mixes and reductions are drawn together, so that combinations no hand-written case lists are exercised.
+Every draw is valid input; every result is compared with the CPU fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from parity import compare, down, f16, rand_graph, up
+from test_gpu_gat_fused import bwd_reference, check_lse, gat_backward_check
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(seed):
+    r = np.random.default_rng(1000 + seed)
+    V = int(r.choice([1, 2, 37, 300, 1111, 2500]))
+    avg = float(r.choice([0.3, 2.0, 8.0, 30.0]))
+    hubs = tuple((int(r.integers(0, V)), int(r.integers(300, 6000))) for _ in range(int(r.integers(0, 3)))) if V >= 37 else ()
+    empties = tuple(int(x) for x in r.integers(0, V, size=int(r.integers(0, 4)))) if V >= 37 else ()
+    H, D = [(1, 8), (1, 16), (1, 64), (1, 128), (2, 32), (4, 16), (8, 8), (3, 8), (2, 64), (8, 64), (1, 256)][int(r.integers(0, 11))]
+    S = int(r.choice([1, 5, 64, 100, 128, 256, 512]))
+    nb = int(r.choice([1, 1, 2, 3, 5])) if V >= 300 else 1
+    return dict(V=V, avg=avg, hubs=hubs, empties=empties, H=H, D=D, S=S, nb=nb, reduce=int(r.integers(0, 2)),
+                has_w=bool(r.integers(0, 2)), ng=int(r.choice([16, 64, 256])), seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(72))
+def test_random_configuration(hgnn, dev, seed):
+    c = draw(seed)
+    print(f"sweep {c}", flush=True)
+    V, H, D, S, nb = c["V"], c["H"], c["D"], c["S"], c["nb"]
+    F = H * D
+    rowptr, col = rand_graph(V, V, c["avg"], 77 + seed, hubs=c["hubs"], empties=c["empties"])
+    E = col.size
+    r = np.random.default_rng(seed)
+    X = f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, H))) if c["has_w"] else None
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, S, F, H, col_blocks=nb)
+    Xd = up(X, dev)
+    wd = None if w is None else up(w, dev)
+    # ---- SpMM: plain, discretized (with the drawn blocks), vertex groups
+    ref, sabs = oracle.spmm(rowptr, col, X, w=w, H=H, reduce=c["reduce"], want_sabs=True)
+    Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm(g, wd, H, Xd, Y, op=c["reduce"])
+    compare("plain", down(Y), ref, sabs)
+    Y.fill_(7.0)
+    hgnn.hgnn_spmm_discretized(p, g, wd, H, Xd, Y, op=c["reduce"])
+    compare("discretized", down(Y), ref, sabs)
+    hgnn.hgnn_plan_add_groups(p, g, c["ng"])
+    Y.fill_(7.0)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, Xd, Y, hgnn.HGNN_VERTEX_GROUPS, op=c["reduce"])
+    compare("vertex groups", down(Y), ref, sabs)
+    # ---- SDDMM dot and GAT score, edge softmax of the device's own scores
+    a_l, a_r = f16(0.3 * r.standard_normal(F)), f16(0.3 * r.standard_normal(F))
+    ald, ard = up(a_l, dev), up(a_r, dev)
+    dOut = f16(r.standard_normal((V, F)))
+    dOd = up(dOut, dev)
+    if E > 0:
+        e = torch.full((E, H), 7.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, dOd, Xd, e)
+        dref = oracle.sddmm_dot(rowptr, col, dOut, X, H=H)
+        row = np.repeat(np.arange(V), np.diff(rowptr))
+        dabs = (np.abs(dOut.astype(np.float64)[row]) * np.abs(X.astype(np.float64)[col])).reshape(E, H, D).sum(-1)
+        compare("sddmm dot", down(e), dref, dabs)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, Xd, Xd, e, ald, ard, 0.2)
+        sref = oracle.gat_score(rowptr, col, X, a_l, a_r, H, slope=0.2)
+        got_e = down(e)
+        assert np.abs(got_e.astype(np.float64) - sref).max() <= 2e-3 * max(1.0, np.abs(sref).max())
+        alpha = torch.full((E, H), 7.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_softmax(g, p, H, e, alpha)
+        aref = oracle.edge_softmax(rowptr, got_e.astype(np.float64))
+        assert np.abs(down(alpha).astype(np.float64) - aref).max() <= 2e-3
+    # ---- fused GAT forward and backward
+    oref, lref, oabs = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H, slope=0.2)
+    out = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    lse = torch.full((V, H), 7.0, dtype=torch.float32, device=dev)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, ald, ard, out, lse)
+    compare("gat fused", down(out), oref, oabs)
+    check_lse("gat fused", down(lse), lref, np.diff(rowptr))
+    hgnn.hgnn_plan_destroy(p)
+    (dV, dV_abs), (d_el, el_abs), (d_er, er_abs) = bwd_reference(rowptr, col, V, X, X, a_l, a_r, dOut, H)
+    g_dV, g_el, g_er = gat_backward_check(hgnn, dev, rowptr, col, V, X, X, a_l, a_r, dOut, H, S, nb, "sweep")
+    # dV of a column is staged in up to nb * (ceil(deg / S) + 1) fp16 pieces; with alpha ~ 1 / (hub degree) the pieces
+    # fall below fp16's normal range, where every stored piece is quantised to 2^-24 absolute: one such step per piece
+    pieces = nb * (np.ceil(np.bincount(col, minlength=V) / S) + 1)
+    compare("dV", g_dV, dV, dV_abs + pieces[:, None] * 2.0 ** -13)
+    compare("d_el", g_el, d_el, el_abs, rel_l2=2e-2)
+    compare("d_er", g_er, d_er, er_abs, rel_l2=2e-2)
