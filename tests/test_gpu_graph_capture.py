@@ -68,3 +68,62 @@ def test_gat_layer_and_spmm_under_graph_replay(hgnn, dev):
         assert np.all(np.isfinite(got["out"])) and np.abs(got["out"]).max() > 0
     hgnn.hgnn_plan_destroy(p)
     hgnn.hgnn_plan_destroy(pt)
+
+
+def test_dense_side_under_graph_replay(hgnn, dev):
+    """The dense calls take a caller-owned workspace and allocate nothing either: projection, GAT aggregation and all
+    gradients of a layer recorded as one graph."""
+    V, K, H, D = 2000, 48, 2, 16
+    F = H * D
+    rowptr, col = rand_graph(V, V, 10, 31, hubs=((7, 3000),), empties=(1,))
+    r = np.random.default_rng(0)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, 256, F, H)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
+    a_l, a_r = up(f16(0.2 * r.standard_normal(F)), dev), up(f16(0.2 * r.standard_normal(F)), dev)
+    W = up(f16(r.standard_normal((K, F)) / np.sqrt(K)), dev)
+    X = torch.empty((V, K), dtype=torch.float16, device=dev)
+    dO = torch.empty((V, F), dtype=torch.float16, device=dev)
+    half = lambda *s: torch.empty(s, dtype=torch.float16, device=dev)
+    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(hgnn.hgnn_linear_wgrad_workspace(K, F), hgnn.hgnn_gat_feature_grad_workspace(H, D)),
+                     dtype=torch.uint8, device=dev)
+
+    def make():
+        return {"h": half(V, F), "out": half(V, F), "dV": half(V, F), "d_el": half(V, H), "d_er": half(V, H), "dh": half(V, F),
+                "dX": half(V, K), "dW": torch.empty((K, F), dtype=torch.float32, device=dev),
+                "da_l": torch.empty(F, dtype=torch.float32, device=dev), "da_r": torch.empty(F, dtype=torch.float32, device=dev)}
+
+    def step(o):
+        hgnn.hgnn_linear(X, W, o["h"])
+        hgnn.hgnn_gat_forward_fused(g, p, H, D, o["h"], o["h"], a_l, a_r, o["out"], lse)
+        hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, o["h"], o["h"], a_l, a_r, o["out"], lse, dO, o["dV"], o["d_el"], o["d_er"])
+        hgnn.hgnn_gat_feature_grad(H, D, o["dV"], o["d_el"], o["d_er"], a_l, a_r, o["h"], o["dh"], o["da_l"], o["da_r"], ws)
+        hgnn.hgnn_linear(o["dh"], W, o["dX"], trans_w=True)
+        hgnn.hgnn_linear_wgrad(X, o["dh"], o["dW"], ws)
+
+    def fill(seed):
+        rr = np.random.default_rng(seed)
+        X.copy_(up(f16(rr.standard_normal((V, K))), dev))
+        dO.copy_(up(f16(rr.standard_normal((V, F))), dev))
+
+    bufs, eager = make(), make()
+    fill(1)
+    step(bufs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(bufs)
+    for rep in range(3):
+        fill(20 + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: down(v).copy() for k, v in bufs.items()}
+        step(eager)
+        torch.cuda.synchronize()
+        for k in bufs:
+            assert np.array_equal(got[k].view(np.uint8), down(eager[k]).view(np.uint8)), (rep, k)
+        assert np.abs(got["dW"]).max() > 0 and np.all(np.isfinite(got["dW"]))
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
