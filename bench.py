@@ -65,7 +65,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); "
-              "the path is single-GPU, see DESIGN.md for how it would shard", file=sys.stderr)
+              "the path is single-GPU; sharding by destination-row blocks is a design note only", file=sys.stderr)
         return 2
     import numpy as np
     import torch
@@ -295,7 +295,7 @@ def main():
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
     # the column-side norm applied to the table first (one V x F pass), then the SpMM without a per-edge factor:
-    # what the fused col_scale costs against this is the reason the design doc advises pre-scaling on long rows
+    # what the fused col_scale costs against this is the reason to pre-scale the table on long rows
     Xs_buf = torch.empty_like(X)
     if args.workload in ("c2", "c5"):
         def prescaled_bwd():
@@ -346,9 +346,17 @@ def main():
         hgnn.hgnn_gat_forward_fused(g, plan, H, D, X, X, a_l, a_r, out, lse)
         t_b = time_call(lambda: hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, X, X, a_l, a_r, out, lse, dY, dh,
                                                             d_el, d_er))
+        # training form: the forward also leaves the masked sums, the backward then needs one pass over the edges
+        out_m = torch.empty_like(X)
+        csum = torch.empty((V, H), dtype=torch.float32, device=dev)
+        t_fs = time_call(lambda: hgnn.hgnn_gat_forward_fused_save(g, plan, H, D, X, X, a_l, a_r, out, lse, out_m, csum))
+        t_bs = time_call(lambda: hgnn.hgnn_gat_backward_fused_saved(g, plan, gt, plan_t, H, D, X, X, a_l, a_r, out, lse, out_m,
+                                                                   csum, dY, dh, d_el, d_er))
         fused = {"gat_forward_fused_ms": round(t_f, 4), "three_call_forward_ms": round(three, 4),
                  "gat_backward_fused_ms": round(t_b, 4), "five_call_backward_ms": round(five, 4),
-                 "gat_fwd_bwd_fused_ms": round(t_f + t_b, 4), "alpha_from_lse_ms": round(t_a, 4)}
+                 "gat_fwd_bwd_fused_ms": round(t_f + t_b, 4), "alpha_from_lse_ms": round(t_a, 4),
+                 "gat_forward_fused_save_ms": round(t_fs, 4), "gat_backward_fused_saved_ms": round(t_bs, 4),
+                 "gat_fwd_bwd_fused_saved_ms": round(t_fs + t_bs, 4)}
 
     # the dense side of a layer on the matrix cores (hidden -> hidden projection of this workload's width), and for the
     # GAT workloads a whole layer: projection + fused aggregation forward, and every gradient backward
@@ -370,10 +378,11 @@ def main():
 
         def layer_fwd():
             hgnn.hgnn_linear(X, Wd, hproj)
-            hgnn.hgnn_gat_forward_fused(g, plan, H, D, hproj, hproj, a_l, a_r, out, lse)
+            hgnn.hgnn_gat_forward_fused_save(g, plan, H, D, hproj, hproj, a_l, a_r, out, lse, out_m, csum)
 
         def layer_bwd():
-            hgnn.hgnn_gat_backward_fused(g, plan, gt, plan_t, H, D, hproj, hproj, a_l, a_r, out, lse, dY, dh, d_el, d_er)
+            hgnn.hgnn_gat_backward_fused_saved(g, plan, gt, plan_t, H, D, hproj, hproj, a_l, a_r, out, lse, out_m, csum, dY, dh,
+                                               d_el, d_er)
             hgnn.hgnn_gat_feature_grad(H, D, dh, d_el, d_er, a_l, a_r, hproj, dfeat, da_l, da_r, ws)
             hgnn.hgnn_linear(dfeat, Wd, dXin, trans_w=True)
             hgnn.hgnn_linear_wgrad(X, dfeat, dW, ws)

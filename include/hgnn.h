@@ -339,6 +339,30 @@ hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_plan* p, const
                                     int64_t lddo, hgnn_half* dV, int64_t lddv, hgnn_half* d_el, hgnn_half* d_er,
                                     void* stream);
 
+/* hgnn_gat_forward_fused that also keeps what lets the backward pass skip its pass over g.  With
+ * mu_k = 1 where the score s_k > 0 and neg_slope elsewhere (the LeakyReLU derivative),
+ *   out_masked[i, h*D+d] = sum_k alpha_k * mu_k * Vt[col k, h*D+d]   (fp16 [nrows][ldom]),
+ *   csum[i,h]            = sum_k alpha_k * mu_k                      (fp32 [nrows][H]);
+ * then sum_k ds_ik = <dOut[i,h], out_masked[i,h]> - <dOut[i,h], out[i,h]> * csum[i,h] (Eq. 1
+ * differentiated, summed over the row).  Both ride on the rows the pass gathers anyway: a second
+ * accumulator per lane, no further memory traffic but the two outputs.  lse, out_masked and csum are
+ * required; neg_slope >= 0; ldom % 8 == 0 and out_masked 16-byte aligned; otherwise as
+ * hgnn_gat_forward_fused. */
+hgnn_status hgnn_gat_forward_fused_save(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                        int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                        const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                        hgnn_half* out_masked, int64_t ldom, float* csum, void* stream);
+
+/* hgnn_gat_backward_fused given out_masked and csum of hgnn_gat_forward_fused_save: d_el is formed per
+ * vertex from them and only the pass over gt runs (dV and d_er).  Same outputs, same requirements; g and
+ * p are still needed for sizes and the per-vertex scratch. */
+hgnn_status hgnn_gat_backward_fused_saved(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt, const hgnn_plan* pt,
+                                          int32_t H, int32_t D, const hgnn_half* U, int64_t ldu, const hgnn_half* Vt,
+                                          int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, float neg_slope,
+                                          const hgnn_half* out, int64_t ldo, const float* lse, const hgnn_half* out_masked,
+                                          int64_t ldom, const float* csum, const hgnn_half* dOut, int64_t lddo,
+                                          hgnn_half* dV, int64_t lddv, hgnn_half* d_el, hgnn_half* d_er, void* stream);
+
 /* Rebuilds alpha[k,h] = exp(e_k - lse[i,h]) (fp16 [nnz][H]) from the lse of
  * hgnn_gat_forward_fused, for a backward pass that wants the attention weights as a tensor.
  * Same requirements as above. */

@@ -54,7 +54,7 @@ def _load():
     lib.orc_gat_score.restype = None
     lib.orc_gat_score.argtypes = [i32, vp, vp, i32, i32, vp, i64, vp, vp, dbl, vp]
     lib.orc_gat_forward.restype = None
-    lib.orc_gat_forward.argtypes = [i32, vp, vp, i32, i32, vp, i64, vp, i64, vp, vp, dbl, vp, vp, vp]
+    lib.orc_gat_forward.argtypes = [i32, vp, vp, i32, i32, vp, i64, vp, i64, vp, vp, dbl, vp, vp, vp, vp, vp]
     lib.orc_gat_backward.restype = None
     lib.orc_gat_backward.argtypes = [i32, i32, vp, vp, i32, i32, vp, i64, vp, i64, vp, vp, dbl, vp, i64, vp, vp, vp]
     lib.orc_edge_softmax.restype = None
@@ -172,16 +172,20 @@ def gat_score(rowptr, col, feat, a_l, a_r, H: int, slope: float = 0.2):
     return out
 
 
-def gat_forward(rowptr, col, U, Vt, a_l, a_r, H: int, slope: float = 0.2):
-    """-> (out [V][F], lse [V][H], sabs [V][F]) of one GAT aggregation, nothing rounded in between."""
+def gat_forward(rowptr, col, U, Vt, a_l, a_r, H: int, slope: float = 0.2, want_saved: bool = False):
+    """-> (out [V][F], lse [V][H], sabs [V][F]) of one GAT aggregation, nothing rounded in between; with want_saved
+    also (out_masked [V][F], csum [V][H]), the sums weighted by the LeakyReLU derivative that a backward pass can use."""
     rowptr, col, U, Vt, a_l, a_r = _i32(rowptr), _i32(col), _f16(U), _f16(Vt), _f16(a_l), _f16(a_r)
     V, F = rowptr.size - 1, U.shape[1]
     out = np.empty((V, F), dtype=np.float64)
     sabs = np.empty((V, F), dtype=np.float64)
     lse = np.empty((V, H), dtype=np.float64)
+    outm = np.empty((V, F), dtype=np.float64) if want_saved else None
+    csum = np.empty((V, H), dtype=np.float64) if want_saved else None
     _load().orc_gat_forward(V, _ptr(rowptr), _ptr(col), H, F // H, _ptr(U), U.strides[0] // 2, _ptr(Vt),
-                            Vt.strides[0] // 2, _ptr(a_l), _ptr(a_r), slope, _ptr(out), _ptr(lse), _ptr(sabs))
-    return out, lse, sabs
+                            Vt.strides[0] // 2, _ptr(a_l), _ptr(a_r), slope, _ptr(out), _ptr(lse), _ptr(sabs), _ptr(outm),
+                            _ptr(csum))
+    return (out, lse, sabs, outm, csum) if want_saved else (out, lse, sabs)
 
 
 def gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H: int, slope: float = 0.2):

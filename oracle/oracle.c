@@ -177,14 +177,19 @@ void orc_gat_score(int32_t V, const int32_t* rowptr, const int32_t* col, int32_t
  *   out[i, h*D+d] = sum_k alpha_k * Vt[col k, h*D+d]
  * lse[i,h] = m + log(sum_k exp(e_k - m)) (what a backward pass needs to rebuild alpha);
  * sabs = sum_k alpha_k * |Vt| (magnitude for tolerances).  An empty row gives out = 0,
- * lse = 0.  U is [V][ldu] (row side), Vt is [ncols][ldv] (column side). ---- */
+ * lse = 0.  U is [V][ldu] (row side), Vt is [ncols][ldv] (column side).
+ * Optional (NULL to skip): with mu_k = 1 where s_k > 0 and slope elsewhere (the derivative of
+ * the LeakyReLU at s_k),  outm[i, h*D+d] = sum_k alpha_k * mu_k * Vt[col k, h*D+d]  and
+ * csum[i,h] = sum_k alpha_k * mu_k: what a forward pass can keep so that the gradient of the
+ * row-side score term, sum_k ds_k of orc_gat_backward, needs no second pass over the edges. ---- */
 void orc_gat_forward(int32_t V, const int32_t* rowptr, const int32_t* col, int32_t H, int32_t D, const uint16_t* U,
                      int64_t ldu, const uint16_t* Vt, int64_t ldv, const uint16_t* a_l, const uint16_t* a_r,
-                     double slope, double* out, double* lse, double* sabs) {
+                     double slope, double* out, double* lse, double* sabs, double* outm, double* csum) {
   int32_t F = H * D;
   for (int32_t i = 0; i < V; ++i) {
     int32_t beg = rowptr[i], end = rowptr[i + 1];
     double* e = (double*)malloc(sizeof(double) * (size_t)(end > beg ? end - beg : 1));
+    double* mu = (double*)malloc(sizeof(double) * (size_t)(end > beg ? end - beg : 1));
     for (int32_t h = 0; h < H; ++h) {
       double el = 0.0;
       for (int32_t d = 0; d < D; ++d)
@@ -195,24 +200,33 @@ void orc_gat_forward(int32_t V, const int32_t* rowptr, const int32_t* col, int32
         for (int32_t d = 0; d < D; ++d)
           s += orc_half_to_double(a_r[h * D + d]) * orc_half_to_double(Vt[(int64_t)col[k] * ldv + h * D + d]);
         e[k - beg] = s > 0.0 ? s : slope * s;
+        mu[k - beg] = s > 0.0 ? 1.0 : slope;
         m = fmax(m, e[k - beg]);
       }
       double z = 0.0;
       for (int32_t k = beg; k < end; ++k) z += exp(e[k - beg] - m);
       for (int32_t d = 0; d < D; ++d) {
-        double acc = 0.0, sa = 0.0;
+        double acc = 0.0, sa = 0.0, accm = 0.0;
         for (int32_t k = beg; k < end; ++k) {
           double alpha = exp(e[k - beg] - m) / z;
           double x = orc_half_to_double(Vt[(int64_t)col[k] * ldv + h * D + d]);
           acc += alpha * x;
           sa += alpha * fabs(x);
+          accm += alpha * mu[k - beg] * x;
         }
         out[(int64_t)i * F + h * D + d] = acc;
         if (sabs) sabs[(int64_t)i * F + h * D + d] = sa;
+        if (outm) outm[(int64_t)i * F + h * D + d] = accm;
       }
       if (lse) lse[(int64_t)i * H + h] = end > beg ? m + log(z) : 0.0;
+      if (csum) {
+        double c = 0.0;
+        for (int32_t k = beg; k < end; ++k) c += exp(e[k - beg] - m) / z * mu[k - beg];
+        csum[(int64_t)i * H + h] = c;
+      }
     }
     free(e);
+    free(mu);
   }
 }
 

@@ -27,7 +27,8 @@ EXPORTS = (
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
     "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
     "hgnn_edge_to_transposed", "hgnn_scale_rows", "hgnn_linear", "hgnn_linear_wgrad", "hgnn_linear_wgrad_workspace",
-    "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace",
+    "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace", "hgnn_gat_forward_fused_save",
+    "hgnn_gat_backward_fused_saved",
 )
 
 HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
@@ -107,6 +108,9 @@ def load() -> ctypes.CDLL:
                                             vp, i64, vp, vp, vp]
     lib.hgnn_get_vector_halves.restype = i32
     lib.hgnn_get_vector_halves.argtypes = []
+    lib.hgnn_gat_forward_fused_save.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64, vp, vp]
+    lib.hgnn_gat_backward_fused_saved.argtypes = [csr, vp, csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64,
+                                                  vp, vp, i64, vp, i64, vp, vp, vp]
     lib.hgnn_linear.argtypes = [i64, i32, i32, vp, i64, vp, i64, i32, vp, i64, vp]
     lib.hgnn_linear_wgrad_workspace.argtypes = [i32, i32]
     lib.hgnn_linear_wgrad_workspace.restype = ctypes.c_size_t
@@ -329,6 +333,29 @@ def hgnn_gat_backward_fused(g: Csr, p: Plan, gt: Csr, pt: Plan, H: int, D: int, 
                                           _ptr(lse, torch.float32), _ptr(dOut, torch.float16), _ld(dOut),
                                           _ptr(dV, torch.float16), _ld(dV), _ptr(d_el, torch.float16),
                                           _ptr(d_er, torch.float16), _stream(stream)))
+
+
+def hgnn_gat_forward_fused_save(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor, a_l: torch.Tensor,
+                                a_r: torch.Tensor, out: torch.Tensor, lse: torch.Tensor, out_masked: torch.Tensor,
+                                csum: torch.Tensor, neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_gat_forward_fused_save(g.ref, p.handle, H, D, _ptr(U, torch.float16), _ld(U), _ptr(Vt, torch.float16),
+                                              _ld(Vt), _ptr(a_l, torch.float16), _ptr(a_r, torch.float16), neg_slope,
+                                              _ptr(out, torch.float16), _ld(out), _ptr(lse, torch.float32),
+                                              _ptr(out_masked, torch.float16), _ld(out_masked), _ptr(csum, torch.float32),
+                                              _stream(stream)))
+
+
+def hgnn_gat_backward_fused_saved(g: Csr, p: Plan, gt: Csr, pt: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,
+                                  a_l: torch.Tensor, a_r: torch.Tensor, out: torch.Tensor, lse: torch.Tensor,
+                                  out_masked: torch.Tensor, csum: torch.Tensor, dOut: torch.Tensor, dV: torch.Tensor,
+                                  d_el: torch.Tensor, d_er: torch.Tensor, neg_slope: float = 0.2, stream=None) -> None:
+    _check(load().hgnn_gat_backward_fused_saved(g.ref, p.handle, gt.ref, pt.handle, H, D, _ptr(U, torch.float16), _ld(U),
+                                                _ptr(Vt, torch.float16), _ld(Vt), _ptr(a_l, torch.float16),
+                                                _ptr(a_r, torch.float16), neg_slope, _ptr(out, torch.float16), _ld(out),
+                                                _ptr(lse, torch.float32), _ptr(out_masked, torch.float16), _ld(out_masked),
+                                                _ptr(csum, torch.float32), _ptr(dOut, torch.float16), _ld(dOut),
+                                                _ptr(dV, torch.float16), _ld(dV), _ptr(d_el, torch.float16),
+                                                _ptr(d_er, torch.float16), _stream(stream)))
 
 
 def hgnn_scale_rows(X: torch.Tensor, scale: torch.Tensor, out: torch.Tensor, F: Optional[int] = None, stream=None) -> None:

@@ -95,8 +95,10 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   if (e == hipSuccess) e = hipMalloc(&p->brp, sizeof(int) * size_t(nb) * (size_t(V) + 1));
   if (e == hipSuccess) e = hipMalloc(&p->bcol, sizeof(int) * size_t(E));
   if (e == hipSuccess) e = hipMalloc(&p->beid, sizeof(int) * size_t(E));
-  if (e == hipSuccess) e = hipMalloc(&p->bstage, sizeof(hgnn_half) * n_flat * size_t(p->max_F));
-  if (e == hipSuccess) e = hipMalloc(&p->bsum, sizeof(float) * 2 * n_flat * size_t(p->max_H));  // row sums use half; GAT partials (m, z)
+  // partial rows twice over and three scalars per row and head: the fused GAT pass that saves for its backward
+  // leaves two vectors and (max, sum, masked sum) per block; row sums of edge tensors use one scalar
+  if (e == hipSuccess) e = hipMalloc(&p->bstage, sizeof(hgnn_half) * 2 * n_flat * size_t(p->max_F));
+  if (e == hipSuccess) e = hipMalloc(&p->bsum, sizeof(float) * 3 * n_flat * size_t(p->max_H));
   if (e == hipSuccess && !g->eid) e = hipMalloc(&p->bdelta, sizeof(int) * n_flat);
   if (e == hipSuccess) {
     block_cuts_kernel<<<dim3(unsigned(ceil_div(int64_t(V) * (nb + 1), kBlock))), kBlock, 0, s>>>(g->rowptr, g->col, V, nb,

@@ -210,8 +210,8 @@ struct hgnn_plan {
   int32_t* split_seg_hi = nullptr;  // [n_split]
   int32_t* big_row = nullptr;       // [n_big]
   int32_t* mid_row = nullptr;       // [n_mid]
-  hgnn_half* staging = nullptr;     // [2*nseg][max_F]
-  float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass
+  hgnn_half* staging = nullptr;     // [2][2*nseg][max_F] (second set: masked vectors of the saving GAT pass)
+  float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass, then [2*nseg][max_H] masked sums
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32
   float* vtab = nullptr;            // [nrows][max_H][4] fp32 per-vertex (el, lse, t, -) of the fused GAT backward
   // column blocking of the SpMM (nb > 1): block b holds the non-zeros whose column lies in
@@ -224,8 +224,8 @@ struct hgnn_plan {
   int32_t* bdelta = nullptr;        // [nb][nrows] graphs without edge-id map: slot = block position + bdelta[b][row]
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
-  hgnn_half* bstage = nullptr;      // [nb][nrows][max_F] per-block partial outputs
-  float* bsum = nullptr;            // [nb][nrows][max_H][2] per-block partial row sums of edge tensors / GAT (max, sum)
+  hgnn_half* bstage = nullptr;      // [2][nb][nrows][max_F] per-block partial outputs (second set: masked GAT partials)
+  float* bsum = nullptr;            // [nb][nrows][max_H][2] per-block partial row sums of edge tensors / GAT (max, sum), then [nb][nrows][max_H] masked sums
   // neighbour groups of the vertex-parallel variant (hgnn_plan_add_groups): row r owns the groups
   // goff[r] .. goff[r+1]-1, group j of the row covers the non-zeros rowptr[r] + j*ng ...
   int32_t ng = 0;                   // neighbours per group; 0 = not built

@@ -16,6 +16,12 @@
 // hence never larger than the features themselves (the discretized-scaling idea of section 5.2.2
 // applied to the softmax weights) -- and a follow-up kernel merges them.  No atomics, one writer per
 // output row, fixed merge order.
+//
+// SAVE kernels also keep, per row and head, what the backward pass needs to form the gradient of the row-side
+// score term without another pass over the edges: with mu_k = 1 where s_k > 0 and the LeakyReLU slope elsewhere,
+//   out_masked[i, h*D+d] = sum_k alpha_k * mu_k * X[col k, h*D+d],   csum[i,h] = sum_k alpha_k * mu_k
+// (then sum_k ds_k = <dOut_i, out_masked_i> - <dOut_i, out_i> * csum_i).  They ride on the same gathered rows:
+// a second accumulator and a second sum in every triple, rescaled with the first.
 #include "common.h"
 
 namespace hgnn {
@@ -33,6 +39,11 @@ struct GatArgs {
   const float* er;    // [ncols][H]  (other kernels)
   float* lse;       // [nrows][H] or nullptr
   float* part_mz;   // column blocks: [nrows][H][2] (m, z) of this block's partial rows; else nullptr
+  half_t* Ym;       // SAVE: [nrows][ldym] masked result (or this block's normalised partial rows)
+  int64_t ldym;
+  float* csum;      // SAVE: [nrows][H] masked weight sum (or, with part_mz, this block's share, relative to its z)
+  half_t* staging_m;  // SAVE: [2*nseg][stage_ld] masked counterpart of staging
+  float* stage_c;     // SAVE: [2*nseg][H] masked weight sum of a staged piece, relative to its z
   int S;
   int64_t nseg;
   const int* seg_lo;
@@ -46,29 +57,84 @@ struct GatArgs {
   int n_split;
 };
 
-// (m, z, acc) <- merge with (m2, z2, acc2)
-__device__ __forceinline__ void soft_merge(float& m, float& z, float (&acc)[8], float m2, float z2, const float (&acc2)[8]) {
-  const float M = fmaxf(m, m2);
+// A partial result of one row and head over some of its edges, as held by one lane (8 features):
+// m = largest score met, z = sum exp(e - m), acc = sum exp(e - m) * x; SAVE adds zm = sum exp(e - m) * mu and
+// accm = sum exp(e - m) * mu * x.
+template <bool SAVE>
+struct Soft {
+  float m = -INFINITY, z = 0.f, zm = 0.f;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float accm[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  __device__ __forceinline__ void clear() {
+    m = -INFINITY;
+    z = 0.f;
+    zm = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[i] = 0.f;
+      accm[i] = 0.f;
+    }
+  }
+  __device__ __forceinline__ void scale(float f) {
+    z *= f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= f;
+    if (SAVE) {
+      zm *= f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) accm[i] *= f;
+    }
+  }
+  // one more edge with weight p = exp(e - m) (relative to the current m) and features x
+  __device__ __forceinline__ void add(float p, float e, float slope, const half8_t& x) {
+    z += p;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = fmaf(p, float(x[q]), acc[q]);
+    if (SAVE) {
+      const float pm = e > 0.f ? p : p * slope;
+      zm += pm;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) accm[q] = fmaf(pm, float(x[q]), accm[q]);
+    }
+  }
+};
+
+// a <- a merged with b (both rescaled to the larger maximum)
+template <bool SAVE>
+__device__ __forceinline__ void soft_merge(Soft<SAVE>& a, const Soft<SAVE>& b) {
+  const float M = fmaxf(a.m, b.m);
   if (M == -INFINITY) return;  // both empty
-  const float fa = __expf(m - M), fb = __expf(m2 - M);  // exp(-inf) = 0 drops an empty side
-  z = z * fa + z2 * fb;
+  const float fa = __expf(a.m - M), fb = __expf(b.m - M);  // exp(-inf) = 0 drops an empty side
+  a.z = a.z * fa + b.z * fb;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = acc[i] * fa + acc2[i] * fb;
-  m = M;
+  for (int i = 0; i < 8; ++i) a.acc[i] = a.acc[i] * fa + b.acc[i] * fb;
+  if (SAVE) {
+    a.zm = a.zm * fa + b.zm * fb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a.accm[i] = a.accm[i] * fa + b.accm[i] * fb;
+  }
+  a.m = M;
 }
 
-// merge a staged piece: (mp, zp) and its normalised vector o = acc/z
-__device__ __forceinline__ void soft_merge_normalised(float& m, float& z, float (&acc)[8], float mp, float zp, const half8_t& o) {
-  const float M = fmaxf(m, mp);
+// merge a staged piece: (mp, zp), its normalised vector o = acc/z and, SAVE, cp = zm/z and om = accm/z
+template <bool SAVE>
+__device__ __forceinline__ void soft_merge_normalised(Soft<SAVE>& a, float mp, float zp, float cp, const half8_t& o,
+                                                      const half8_t& om) {
+  const float M = fmaxf(a.m, mp);
   if (M == -INFINITY) return;
-  const float fa = __expf(m - M), fb = __expf(mp - M) * zp;
-  z = z * fa + fb;
+  const float fa = __expf(a.m - M), fb = __expf(mp - M) * zp;
+  a.z = a.z * fa + fb;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = acc[i] * fa + fb * float(o[i]);
-  m = M;
+  for (int i = 0; i < 8; ++i) a.acc[i] = a.acc[i] * fa + fb * float(o[i]);
+  if (SAVE) {
+    a.zm = a.zm * fa + fb * cp;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a.accm[i] = a.accm[i] * fa + fb * float(om[i]);
+  }
+  a.m = M;
 }
 
-__device__ __forceinline__ void store_vec8(const GatArgs& a, half_t* p, int f0, const float (&v)[8], float s) {
+__device__ __forceinline__ void store_vec8(half_t* p, int f0, const float (&v)[8], float s) {
   half8_t h;
 #pragma unroll
   for (int i = 0; i < 8; ++i) h[i] = half_t(v[i] * s);
@@ -76,34 +142,40 @@ __device__ __forceinline__ void store_vec8(const GatArgs& a, half_t* p, int f0, 
 }
 
 // a finished row (or, with part_mz, a finished partial row of a column block)
-__device__ __forceinline__ void row_store(const GatArgs& a, int64_t row, int f0, int head, bool leader, float m, float z,
-                                          const float (&acc)[8]) {
-  const float inv = z > 0.f ? 1.f / z : 0.f;
-  store_vec8(a, a.Y + row * a.ldy, f0, acc, inv);
+template <bool SAVE>
+__device__ __forceinline__ void row_store(const GatArgs& a, int64_t row, int f0, int head, bool leader, const Soft<SAVE>& t) {
+  const float inv = t.z > 0.f ? 1.f / t.z : 0.f;
+  store_vec8(a.Y + row * a.ldy, f0, t.acc, inv);
+  if (SAVE) store_vec8(a.Ym + row * a.ldym, f0, t.accm, inv);
   if (!leader) return;
+  if (SAVE) a.csum[row * a.H + head] = t.zm * inv;
   if (a.part_mz) {
-    a.part_mz[(row * a.H + head) * 2] = m;
-    a.part_mz[(row * a.H + head) * 2 + 1] = z;
+    a.part_mz[(row * a.H + head) * 2] = t.m;
+    a.part_mz[(row * a.H + head) * 2 + 1] = t.z;
   } else if (a.lse) {
-    a.lse[row * a.H + head] = z > 0.f ? m + __logf(z) : 0.f;
+    a.lse[row * a.H + head] = t.z > 0.f ? t.m + __logf(t.z) : 0.f;
   }
 }
 
-__device__ __forceinline__ void stage_store(const GatArgs& a, int64_t slot, int f0, int head, bool leader, float m, float z,
-                                            const float (&acc)[8]) {
-  store_vec8(a, a.staging + slot * a.stage_ld, f0, acc, z > 0.f ? 1.f / z : 0.f);
+template <bool SAVE>
+__device__ __forceinline__ void stage_store(const GatArgs& a, int64_t slot, int f0, int head, bool leader, const Soft<SAVE>& t) {
+  const float inv = t.z > 0.f ? 1.f / t.z : 0.f;
+  store_vec8(a.staging + slot * a.stage_ld, f0, t.acc, inv);
+  if (SAVE) store_vec8(a.staging_m + slot * a.stage_ld, f0, t.accm, inv);
   if (leader) {
-    a.stage_mz[(slot * a.H + head) * 2] = m;
-    a.stage_mz[(slot * a.H + head) * 2 + 1] = z;
+    a.stage_mz[(slot * a.H + head) * 2] = t.m;
+    a.stage_mz[(slot * a.H + head) * 2 + 1] = t.z;
+    if (SAVE) a.stage_c[slot * a.H + head] = t.zm * inv;
   }
 }
 
 struct GatLds {
   int per, spad, col_off, row_off, blk_off, sc_off, vec_off, mz_off, flag_off, total;
 };
-__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L) {
+__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save) {
   GatLds o;
   const int G = kWave / L;
+  const int nv = save ? 2 : 1, ns = save ? 3 : 2;  // vectors and scalars of a parked piece
   o.per = 4 * ((S + 255) / 256);
   o.spad = kWave * o.per;
   o.col_off = 0;
@@ -111,8 +183,8 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L) {
   o.blk_off = o.row_off + o.spad * 4;
   o.sc_off = o.blk_off + ((o.spad + 15) & ~15);
   o.vec_off = o.sc_off + o.spad * H * 4;
-  o.mz_off = o.vec_off + 2 * G * 8 * L * 4;
-  o.flag_off = o.mz_off + 2 * G * L * 2 * 4;
+  o.mz_off = o.vec_off + 2 * G * nv * 8 * L * 4;
+  o.flag_off = o.mz_off + 2 * G * L * ns * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
   return o;
 }
@@ -121,10 +193,11 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L) {
 // products per lane and an exchange among the lanes of a head, no per-edge scalar fetched; wins for heads of
 // up to 16 features).  FLY = false: it is gathered from the per-vertex projection er while the segment is
 // staged (one 4-byte gather per edge and head; wins for long heads, where the exchange costs more).
-template <int L, bool OFF32, bool FLY>
+template <int L, bool OFF32, bool FLY, bool SAVE>
 __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;
+  constexpr int NV = SAVE ? 2 : 1, NS = SAVE ? 3 : 2;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
@@ -134,14 +207,14 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int head = f0c / a.D;
   const bool leader = active && (f0 % a.D) == 0;  // the lane that writes its head's scalars
   const int S = a.S;
-  const GatLds lay = gat_lds_layout(S, a.H, L);
+  const GatLds lay = gat_lds_layout(S, a.H, L, SAVE);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU
-  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
-  float* m_mz = reinterpret_cast<float*>(base + lay.mz_off);    // [2*G][L][2]: (m, z) of the parked pieces, per lane
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][NV][VEC]: slot 2g = entering, 2g+1 = leaving
+  float* m_mz = reinterpret_cast<float*>(base + lay.mz_off);    // [2*G][L][NS]: (m, z[, zm]) of the parked pieces, per lane
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
@@ -190,23 +263,44 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int C = 4 * ((S + 4 * G - 1) / (4 * G));
   const int c0 = g * C < n ? g * C : n;
   const int c1 = c0 + C < n ? c0 + C : n;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, z = 0.f;
+  Soft<SAVE> t;
   int cur = -1;
   bool lo = false;  // current piece began before this chunk
 
+  auto park = [&](int slot, const Soft<SAVE>& v) {
+    if (active) {
+      float* dst = m_vec + slot * NV * VEC + f0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dst[i] = v.acc[i];
+      if (SAVE) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[VEC + i] = v.accm[i];
+      }
+    }
+    m_mz[(slot * L + l) * NS] = v.m;
+    m_mz[(slot * L + l) * NS + 1] = v.z;
+    if (SAVE) m_mz[(slot * L + l) * NS + 2] = v.zm;
+  };
+  auto unpark = [&](int slot) -> Soft<SAVE> {
+    Soft<SAVE> v;
+    const float* src = m_vec + slot * NV * VEC + f0c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v.acc[i] = src[i];
+    if (SAVE) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v.accm[i] = src[VEC + i];
+    }
+    v.m = m_mz[(slot * L + l) * NS];
+    v.z = m_mz[(slot * L + l) * NS + 1];
+    if (SAVE) v.zm = m_mz[(slot * L + l) * NS + 2];
+    return v;
+  };
   auto flush = [&](bool ro) {
     if (!lo && !ro) {
-      if (active) row_store(a, cur, f0, head, leader, m, z, acc);
+      if (active) row_store<SAVE>(a, cur, f0, head, leader, t);
     } else {
       const int slot = lo ? 2 * g : 2 * g + 1;
-      if (active) {
-        float* dst = m_vec + slot * VEC + f0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dst[i] = acc[i];
-      }
-      m_mz[(slot * L + l) * 2] = m;
-      m_mz[(slot * L + l) * 2 + 1] = z;
+      park(slot, t);
       if (l == 0) {
         m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
         if (lo) m_hrow[g] = cur;
@@ -269,19 +363,11 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
       for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
     }
     if (blk == cur) {  // four more edges of the current row: one rescale, four terms
-      const float mn = fmaxf(fmaxf(m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
-      const float f = __expf(m - mn);
-      z *= f;
+      const float mn = fmaxf(fmaxf(t.m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
+      t.scale(__expf(t.m - mn));
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] *= f;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float p = __expf(sc[u] - mn);
-        z += p;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[q] = fmaf(p, float(x[u][q]), acc[q]);
-      }
-      m = mn;
+      for (int u = 0; u < 4; ++u) t.add(__expf(sc[u] - mn), sc[u], a.slope, x[u]);
+      t.m = mn;
     } else {
       const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
 #pragma unroll
@@ -289,19 +375,14 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
         if (i + u < c1) {
           if (rows[u] != cur) {
             flush(false);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-            m = -INFINITY;
-            z = 0.f;
+            t.clear();
             cur = rows[u];
             lo = false;
           }
-          const float mn = fmaxf(m, sc[u]);
-          const float f = __expf(m - mn), p = __expf(sc[u] - mn);
-          z = z * f + p;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[q] = fmaf(p, float(x[u][q]), acc[q] * f);
-          m = mn;
+          const float mn = fmaxf(t.m, sc[u]);
+          t.scale(__expf(t.m - mn));
+          t.add(__expf(sc[u] - mn), sc[u], a.slope, x[u]);
+          t.m = mn;
         }
       }
     }
@@ -311,18 +392,13 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
 
   // ---- merge: group 0 sews the parked pieces together in chunk order
   if (valid && g == 0) {
-    float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float rm = -INFINITY, rz = 0.f;
+    Soft<SAVE> run;
     bool open = false, from_before = false;
     int run_row = -1;
     for (int gg = 0; gg < G; ++gg) {
       const int fl = m_flag[gg];
       if (fl & 1) {
-        float t[8];
-        const float* src = m_vec + (2 * gg) * VEC + f0c;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) t[i] = src[i];
-        soft_merge(rm, rz, run, m_mz[((2 * gg) * L + l) * 2], m_mz[((2 * gg) * L + l) * 2 + 1], t);
+        soft_merge<SAVE>(run, unpark(2 * gg));
         if (gg == 0) {
           from_before = true;
           open = true;
@@ -330,30 +406,23 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
         }
         if (!(fl & 2)) {  // the row ends inside chunk gg
           if (active) {
-            if (from_before) stage_store(a, 2 * seg, f0, head, leader, rm, rz, run);
-            else row_store(a, run_row, f0, head, leader, rm, rz, run);
+            if (from_before) stage_store<SAVE>(a, 2 * seg, f0, head, leader, run);
+            else row_store<SAVE>(a, run_row, f0, head, leader, run);
           }
-#pragma unroll
-          for (int i = 0; i < 8; ++i) run[i] = 0.f;
-          rm = -INFINITY;
-          rz = 0.f;
+          run.clear();
           open = false;
           from_before = false;
         }
       }
       if (fl & 4) {
-        const float* src = m_vec + (2 * gg + 1) * VEC + f0c;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) run[i] = src[i];
-        rm = m_mz[((2 * gg + 1) * L + l) * 2];
-        rz = m_mz[((2 * gg + 1) * L + l) * 2 + 1];
+        run = unpark(2 * gg + 1);
         run_row = m_trow[gg];
         open = true;
         from_before = false;
       }
     }
     if (open && active)  // leaves into the next segment; a piece that also entered uses slot 2*seg
-      stage_store(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, rm, rz, run);
+      stage_store<SAVE>(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, run);
   }
 
   // ---- this wave's share of the empty rows
@@ -362,9 +431,9 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
   if (active) {
-    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const Soft<SAVE> none;
     for (int64_t r = r0 + g; r < r1; r += G)
-      if (a.rowptr[r] == a.rowptr[r + 1]) row_store(a, r, f0, head, leader, -INFINITY, 0.f, zero);
+      if (a.rowptr[r] == a.rowptr[r + 1]) row_store<SAVE>(a, r, f0, head, leader, none);
   }
 }
 
@@ -374,7 +443,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
 // hubs by the whole wave with a final merge across the groups.
 constexpr int kShortPieces = 8;
 
-template <int L>
+template <int L, bool SAVE>
 __global__ __launch_bounds__(kBlock) void gat_finish_kernel(GatArgs a) {
   constexpr int G = kWave / L;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -393,39 +462,60 @@ __global__ __launch_bounds__(kBlock) void gat_finish_kernel(GatArgs a) {
     sa = a.split_lo[idx];
     sb = a.split_hi[idx];
   }
-  auto take = [&](float& m, float& z, float (&acc)[8], int64_t slot) {
+  auto take = [&](Soft<SAVE>& t, int64_t slot) {
     const half8_t o = *reinterpret_cast<const half8_t*>(a.staging + slot * a.stage_ld + f0c);
-    soft_merge_normalised(m, z, acc, a.stage_mz[(slot * a.H + head) * 2], a.stage_mz[(slot * a.H + head) * 2 + 1], o);
+    half8_t om = o;
+    float cp = 0.f;
+    if (SAVE) {
+      om = *reinterpret_cast<const half8_t*>(a.staging_m + slot * a.stage_ld + f0c);
+      cp = a.stage_c[slot * a.H + head];
+    }
+    soft_merge_normalised<SAVE>(t, a.stage_mz[(slot * a.H + head) * 2], a.stage_mz[(slot * a.H + head) * 2 + 1], cp, o, om);
   };
   if (idx < a.n_split && sb - sa <= kShortPieces) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, z = 0.f;
-    take(m, z, acc, 2 * int64_t(sa) + 1);
-    for (int64_t k = int64_t(sa) + 1; k <= sb; ++k) take(m, z, acc, 2 * k);
-    if (active) row_store(a, r, f0, head, leader, m, z, acc);
+    Soft<SAVE> t;
+    take(t, 2 * int64_t(sa) + 1);
+    for (int64_t k = int64_t(sa) + 1; k <= sb; ++k) take(t, 2 * k);
+    if (active) row_store<SAVE>(a, r, f0, head, leader, t);
   }
   for (int j = 0; j < G; ++j) {
     const int rj = __shfl(r, j * L), sj = __shfl(sa, j * L), ej = __shfl(sb, j * L);
     if (ej - sj <= kShortPieces) continue;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, z = 0.f;
-    if (g == 0) take(m, z, acc, 2 * int64_t(sj) + 1);
-    for (int64_t k = int64_t(sj) + 1 + g; k <= ej; k += G) take(m, z, acc, 2 * k);
+    Soft<SAVE> t;
+    if (g == 0) take(t, 2 * int64_t(sj) + 1);
+    for (int64_t k = int64_t(sj) + 1 + g; k <= ej; k += G) take(t, 2 * k);
 #pragma unroll
     for (int off = L; off < kWave; off <<= 1) {
-      float t[8];
+      Soft<SAVE> o;
+      o.m = __shfl_xor(t.m, off);
+      o.z = __shfl_xor(t.z, off);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) t[i] = __shfl_xor(acc[i], off);
-      soft_merge(m, z, acc, __shfl_xor(m, off), __shfl_xor(z, off), t);
+      for (int i = 0; i < 8; ++i) o.acc[i] = __shfl_xor(t.acc[i], off);
+      if (SAVE) {
+        o.zm = __shfl_xor(t.zm, off);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o.accm[i] = __shfl_xor(t.accm[i], off);
+      }
+      soft_merge<SAVE>(t, o);
     }
-    if (g == 0 && active) row_store(a, rj, f0, head, leader, m, z, acc);
+    if (g == 0 && active) row_store<SAVE>(a, rj, f0, head, leader, t);
   }
 }
 
-// Column-blocked plans: merges the nb partial rows (normalised fp16 vector + (m, z)) of every row.
-template <int L>
-__global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, const half_t* __restrict__ part, int part_ld,
-                                                                 const float* __restrict__ part_mz, int64_t mz_stride, int nb) {
+// Column-blocked plans: merges the nb partial rows (normalised fp16 vectors + (m, z[, zm/z])) of every row.
+struct GatBlockParts {
+  const half_t* vec;    // [nb][nrows][ld]
+  const half_t* vec_m;  // SAVE: the masked counterpart
+  int ld;
+  const float* mz;      // [nb] x mz_stride: [nrows][H][2]
+  int64_t mz_stride;
+  const float* c;       // SAVE: [nb] x c_stride: [nrows][H]
+  int64_t c_stride;
+  int nb;
+};
+
+template <int L, bool SAVE>
+__global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, GatBlockParts q) {
   constexpr int G = kWave / L;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
@@ -433,52 +523,74 @@ __global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, cons
   const int64_t r = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
   if (r >= a.nrows || f0 >= a.F) return;
   const int head = f0 / a.D;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, z = 0.f;
-  for (int b = 0; b < nb; ++b) {
+  Soft<SAVE> t;
+  for (int b = 0; b < q.nb; ++b) {
     const int64_t pr = int64_t(b) * a.nrows + r;
-    const half8_t o = *reinterpret_cast<const half8_t*>(part + pr * part_ld + f0);
-    const float* mz = part_mz + b * mz_stride + (r * a.H + head) * 2;
-    soft_merge_normalised(m, z, acc, mz[0], mz[1], o);
+    const half8_t o = *reinterpret_cast<const half8_t*>(q.vec + pr * q.ld + f0);
+    half8_t om = o;
+    float cp = 0.f;
+    if (SAVE) {
+      om = *reinterpret_cast<const half8_t*>(q.vec_m + pr * q.ld + f0);
+      cp = q.c[b * q.c_stride + r * a.H + head];
+    }
+    const float* mz = q.mz + b * q.mz_stride + (r * a.H + head) * 2;
+    soft_merge_normalised<SAVE>(t, mz[0], mz[1], cp, o, om);
   }
-  row_store(a, r, f0, head, (f0 % a.D) == 0, m, z, acc);
+  row_store<SAVE>(a, r, f0, head, (f0 % a.D) == 0, t);
+}
+
+template <int L, bool OFF32, bool FLY>
+static void launch_gat_seg_l(bool save, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
+  if (save) gat_seg_kernel<L, OFF32, FLY, true><<<grid, threads, lds, s>>>(a);
+  else gat_seg_kernel<L, OFF32, FLY, false><<<grid, threads, lds, s>>>(a);
 }
 
 template <bool OFF32, bool FLY>
-static void launch_gat_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
+static void launch_gat_seg(int L, bool save, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
   switch (L) {
-    case 1: gat_seg_kernel<1, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    case 2: gat_seg_kernel<2, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    case 4: gat_seg_kernel<4, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    case 8: gat_seg_kernel<8, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    case 16: gat_seg_kernel<16, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    case 32: gat_seg_kernel<32, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
-    default: gat_seg_kernel<64, OFF32, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 1: launch_gat_seg_l<1, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 2: launch_gat_seg_l<2, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 4: launch_gat_seg_l<4, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 8: launch_gat_seg_l<8, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 16: launch_gat_seg_l<16, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 32: launch_gat_seg_l<32, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    default: launch_gat_seg_l<64, OFF32, FLY>(save, grid, threads, lds, s, a); break;
   }
 }
 
-static void launch_gat_finish(int L, dim3 grid, hipStream_t s, const GatArgs& a) {
+template <int L>
+static void launch_gat_finish_l(bool save, dim3 grid, hipStream_t s, const GatArgs& a) {
+  if (save) gat_finish_kernel<L, true><<<grid, kBlock, 0, s>>>(a);
+  else gat_finish_kernel<L, false><<<grid, kBlock, 0, s>>>(a);
+}
+
+static void launch_gat_finish(int L, bool save, dim3 grid, hipStream_t s, const GatArgs& a) {
   switch (L) {
-    case 1: gat_finish_kernel<1><<<grid, kBlock, 0, s>>>(a); break;
-    case 2: gat_finish_kernel<2><<<grid, kBlock, 0, s>>>(a); break;
-    case 4: gat_finish_kernel<4><<<grid, kBlock, 0, s>>>(a); break;
-    case 8: gat_finish_kernel<8><<<grid, kBlock, 0, s>>>(a); break;
-    case 16: gat_finish_kernel<16><<<grid, kBlock, 0, s>>>(a); break;
-    case 32: gat_finish_kernel<32><<<grid, kBlock, 0, s>>>(a); break;
-    default: gat_finish_kernel<64><<<grid, kBlock, 0, s>>>(a); break;
+    case 1: launch_gat_finish_l<1>(save, grid, s, a); break;
+    case 2: launch_gat_finish_l<2>(save, grid, s, a); break;
+    case 4: launch_gat_finish_l<4>(save, grid, s, a); break;
+    case 8: launch_gat_finish_l<8>(save, grid, s, a); break;
+    case 16: launch_gat_finish_l<16>(save, grid, s, a); break;
+    case 32: launch_gat_finish_l<32>(save, grid, s, a); break;
+    default: launch_gat_finish_l<64>(save, grid, s, a); break;
   }
 }
 
-static void launch_gat_block_merge(int L, dim3 grid, hipStream_t s, const GatArgs& a, const half_t* part, int part_ld,
-                                   const float* part_mz, int64_t mz_stride, int nb) {
+template <int L>
+static void launch_gat_block_merge_l(bool save, dim3 grid, hipStream_t s, const GatArgs& a, const GatBlockParts& q) {
+  if (save) gat_block_merge_kernel<L, true><<<grid, kBlock, 0, s>>>(a, q);
+  else gat_block_merge_kernel<L, false><<<grid, kBlock, 0, s>>>(a, q);
+}
+
+static void launch_gat_block_merge(int L, bool save, dim3 grid, hipStream_t s, const GatArgs& a, const GatBlockParts& q) {
   switch (L) {
-    case 1: gat_block_merge_kernel<1><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    case 2: gat_block_merge_kernel<2><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    case 4: gat_block_merge_kernel<4><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    case 8: gat_block_merge_kernel<8><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    case 16: gat_block_merge_kernel<16><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    case 32: gat_block_merge_kernel<32><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
-    default: gat_block_merge_kernel<64><<<grid, kBlock, 0, s>>>(a, part, part_ld, part_mz, mz_stride, nb); break;
+    case 1: launch_gat_block_merge_l<1>(save, grid, s, a, q); break;
+    case 2: launch_gat_block_merge_l<2>(save, grid, s, a, q); break;
+    case 4: launch_gat_block_merge_l<4>(save, grid, s, a, q); break;
+    case 8: launch_gat_block_merge_l<8>(save, grid, s, a, q); break;
+    case 16: launch_gat_block_merge_l<16>(save, grid, s, a, q); break;
+    case 32: launch_gat_block_merge_l<32>(save, grid, s, a, q); break;
+    default: launch_gat_block_merge_l<64>(save, grid, s, a, q); break;
   }
 }
 
@@ -491,12 +603,16 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   a.staging = reinterpret_cast<half_t*>(q->staging);
   a.stage_mz = q->stage_mz;
   a.stage_ld = q->max_F;
+  const bool save = a.Ym != nullptr;
+  // the plan holds a second set of staging vectors and a third scalar per staged piece behind the first
+  a.staging_m = a.staging + size_t(2) * size_t(q->nseg) * size_t(q->max_F);
+  a.stage_c = q->stage_mz + size_t(4) * size_t(q->nseg) * size_t(q->max_H);
   a.split_row = q->split_row;
   a.split_lo = q->split_seg_lo;
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L).total);
+  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L, save).total);
   const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
@@ -507,15 +623,15 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   const int threads = wpb * kWave;
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   if (a.a_r) {
-    if (off32) launch_gat_seg<true, true>(L, grid, threads, lds, s, a);
-    else launch_gat_seg<false, true>(L, grid, threads, lds, s, a);
+    if (off32) launch_gat_seg<true, true>(L, save, grid, threads, lds, s, a);
+    else launch_gat_seg<false, true>(L, save, grid, threads, lds, s, a);
   } else {
-    if (off32) launch_gat_seg<true, false>(L, grid, threads, lds, s, a);
-    else launch_gat_seg<false, false>(L, grid, threads, lds, s, a);
+    if (off32) launch_gat_seg<true, false>(L, save, grid, threads, lds, s, a);
+    else launch_gat_seg<false, false>(L, save, grid, threads, lds, s, a);
   }
   HGNN_LAUNCH_CHECK("gat_seg_kernel");
   if (a.n_split > 0) {
-    launch_gat_finish(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
+    launch_gat_finish(L, save, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
     HGNN_LAUNCH_CHECK("gat_finish_kernel");
   }
   return HGNN_OK;
@@ -525,14 +641,12 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
 
 using namespace hgnn;
 
-extern "C" {
-
-hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
-                                   int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
-                                   const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
-                                   void* stream) {
+// out_masked / csum: nullptr, or the tensors a later backward call wants (see the SAVE kernels)
+static hgnn_status gat_forward_impl(const char* who, const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D,
+                                    const hgnn_half* U, int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                    const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                    hgnn_half* out_masked, int64_t ldom, float* csum, void* stream) {
   clear_error();
-  const char* who = "hgnn_gat_forward_fused";
   hgnn_status st = check_csr_args(g, who);
   if (st != HGNN_OK) return st;
   HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
@@ -544,11 +658,16 @@ hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_
   HGNN_REQUIRE(H <= p->max_H && F <= p->max_F, HGNN_EINVAL, "%s: H = %d / F = %d exceed the plan's max_H = %d / max_F = %d",
                who, H, F, p->max_H, p->max_F);
   HGNN_REQUIRE(ldo >= F && ldv >= F && ldu >= F, HGNN_EINVAL, "%s: leading dimension smaller than F", who);
+  HGNN_REQUIRE((out_masked == nullptr) == (csum == nullptr), HGNN_EINVAL, "%s: out_masked and csum go together", who);
+  HGNN_REQUIRE(out_masked == nullptr || (ldom >= F && neg_slope >= 0.f), HGNN_EINVAL,
+               "%s: out_masked needs ldom >= F and a slope >= 0", who);
   HGNN_REQUIRE(g->nrows == 0 || out != nullptr, HGNN_EINVAL, "%s: out is NULL", who);
   if (g->nrows == 0) return HGNN_OK;
   HGNN_REQUIRE(U && Vt && a_l && a_r, HGNN_EINVAL, "%s: U, Vt, a_l or a_r is NULL", who);
   HGNN_REQUIRE(D % 8 == 0 && ldv % 8 == 0 && ldo % 8 == 0 && aligned16(Vt) && aligned16(out), HGNN_EUNSUPPORTED,
                "%s: needs D %% 8 == 0, ld %% 8 == 0 and 16-byte aligned Vt, out", who);
+  HGNN_REQUIRE(out_masked == nullptr || (ldom % 8 == 0 && aligned16(out_masked)), HGNN_EUNSUPPORTED,
+               "%s: needs ldom %% 8 == 0 and a 16-byte aligned out_masked", who);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // per-vertex projections into the plan's fp32 scratch: el[i,h] = a_l[h].U[i,h] always; er[j,h] = a_r[h].Vt[j,h]
   // only for long heads (short heads form that term in the kernel from the gathered row)
@@ -572,28 +691,62 @@ hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_
   a.a_r = fly ? reinterpret_cast<const half_t*>(a_r) : nullptr;
   a.er = p->vscratch + size_t(g->nrows) * H;
   a.lse = lse;
+  a.Ym = reinterpret_cast<half_t*>(out_masked);
+  a.ldym = ldom;
+  a.csum = csum;
+  const bool save = out_masked != nullptr;
   if (p->nb <= 1) return run_gat_segments(p, a, g->ncols, s);
-  // column-blocked plan: every block leaves a normalised partial row and its (m, z) per row; one pass merges them
+  // column-blocked plan: every block leaves normalised partial rows and their (m, z[, zm/z]) per row; one pass merges them
   const size_t V = size_t(p->nrows);
+  const size_t flat = size_t(p->nb) * V;
+  half_t* bstage = reinterpret_cast<half_t*>(p->bstage);
+  half_t* bstage_m = bstage + flat * size_t(p->max_F);    // the plan holds a second set of partial rows behind the first
+  float* bsum_c = p->bsum + 2 * flat * size_t(p->max_H);  // and a third scalar per partial row
   for (int b = 0; b < p->nb; ++b) {
     const hgnn_plan* q = p->sub[size_t(b)];
     GatArgs ab = a;
     ab.rowptr = p->brp + size_t(b) * (V + 1);
     ab.col = p->bcol + p->boff[size_t(b)];
     ab.nnz = q->nnz;
-    ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * V * size_t(p->max_F);
+    ab.Y = bstage + size_t(b) * V * size_t(p->max_F);
     ab.ldy = p->max_F;
     ab.lse = nullptr;
     ab.part_mz = p->bsum + size_t(b) * V * size_t(p->max_H) * 2;
+    if (save) {
+      ab.Ym = bstage_m + size_t(b) * V * size_t(p->max_F);
+      ab.ldym = p->max_F;
+      ab.csum = bsum_c + size_t(b) * V * size_t(p->max_H);
+    }
     st = run_gat_segments(q, ab, g->ncols, s);
     if (st != HGNN_OK) return st;
   }
   const int L = pow2_at_least(F / 8);
-  GatArgs am = a;
-  launch_gat_block_merge(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, am,
-                         reinterpret_cast<const half_t*>(p->bstage), p->max_F, p->bsum, int64_t(V) * p->max_H * 2, p->nb);
+  const GatBlockParts parts{bstage, bstage_m, p->max_F, p->bsum, int64_t(V) * p->max_H * 2, bsum_c, int64_t(V) * p->max_H, p->nb};
+  launch_gat_block_merge(L, save, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, a, parts);
   HGNN_LAUNCH_CHECK("gat_block_merge_kernel");
   return HGNN_OK;
+}
+
+extern "C" {
+
+hgnn_status hgnn_gat_forward_fused(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                   int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                   const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                   void* stream) {
+  return gat_forward_impl("hgnn_gat_forward_fused", g, p, H, D, U, ldu, Vt, ldv, a_l, a_r, neg_slope, out, ldo, lse, nullptr, 0,
+                          nullptr, stream);
+}
+
+hgnn_status hgnn_gat_forward_fused_save(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int32_t D, const hgnn_half* U,
+                                        int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                        const hgnn_half* a_r, float neg_slope, hgnn_half* out, int64_t ldo, float* lse,
+                                        hgnn_half* out_masked, int64_t ldom, float* csum, void* stream) {
+  const char* who = "hgnn_gat_forward_fused_save";
+  if (out_masked == nullptr || csum == nullptr || lse == nullptr) {
+    clear_error();
+    return fail(HGNN_EINVAL, "%s: lse, out_masked and csum are required", who);
+  }
+  return gat_forward_impl(who, g, p, H, D, U, ldu, Vt, ldv, a_l, a_r, neg_slope, out, ldo, lse, out_masked, ldom, csum, stream);
 }
 
 }  // extern "C"

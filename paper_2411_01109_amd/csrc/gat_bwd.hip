@@ -403,12 +403,16 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_block_sum_kernel(GatBwdArgs a,
   bwd_row_store<VEC>(a, r, f0, head, (f0 % a.D) == 0, acc, ds);
 }
 
-// vtab[i,h] = (el[i,h], lse[i,h], t[i,h] = <dOut[i,h], out[i,h]>, 0) for every destination vertex
+// vtab[i,h] = (el[i,h], lse[i,h], t[i,h] = <dOut[i,h], out[i,h]>, 0) for every destination vertex.  With the masked
+// result and weight sum that the saving forward pass left (outm, csum), the gradient of the row-side score term is
+// a per-vertex expression and is written here: d_el[i,h] = <dOut[i,h], outm[i,h]> - t[i,h] * csum[i,h].
 template <int L>
 __global__ __launch_bounds__(kBlock) void gat_vtab_kernel(const float* __restrict__ el, const float* __restrict__ lse,
                                                            const half_t* __restrict__ dOut, int64_t lddo,
                                                            const half_t* __restrict__ out, int64_t ldo, int nv, int F, int D,
-                                                           int H, float4* __restrict__ vtab) {
+                                                           int H, float4* __restrict__ vtab, const half_t* __restrict__ outm,
+                                                           int64_t ldom, const float* __restrict__ csum,
+                                                           half_t* __restrict__ d_el) {
   constexpr int G = kWave / L;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = lane / L, l = lane % L;
@@ -416,17 +420,26 @@ __global__ __launch_bounds__(kBlock) void gat_vtab_kernel(const float* __restric
   const bool active = f0 < F;
   const int LH = D / 8;
   const int64_t v = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
-  float p = 0.f;
+  float p = 0.f, pm = 0.f;
   if (active && v < nv) {
     const half8_t x = *reinterpret_cast<const half8_t*>(dOut + v * lddo + f0);
     const half8_t y = *reinterpret_cast<const half8_t*>(out + v * ldo + f0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) p = fmaf(float(x[i]), float(y[i]), p);
+    if (outm) {
+      const half8_t ym = *reinterpret_cast<const half8_t*>(outm + v * ldom + f0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pm = fmaf(float(x[i]), float(ym[i]), pm);
+    }
   }
-  for (int off = 1; off < LH; off <<= 1) p += __shfl_xor(p, off);
+  for (int off = 1; off < LH; off <<= 1) {
+    p += __shfl_xor(p, off);
+    pm += __shfl_xor(pm, off);
+  }
   if (active && v < nv && (l % LH) == 0) {
     const int64_t k = v * H + l / LH;
     vtab[k] = make_float4(el[k], lse[k], p, 0.f);
+    if (outm) d_el[k] = half_t(pm - p * csum[k]);
   }
 }
 
@@ -470,17 +483,27 @@ static void launch_bwd_block_sum(int L, dim3 grid, hipStream_t s, const GatBwdAr
   }
 }
 
+struct VtabSaved {
+  const half_t* outm;
+  int64_t ldom;
+  const float* csum;
+  half_t* d_el;
+};
+
 static void launch_vtab(int L, dim3 grid, hipStream_t s, const float* el, const float* lse, const half_t* dOut, int64_t lddo,
-                        const half_t* out, int64_t ldo, int nv, int F, int D, int H, float4* vtab) {
+                        const half_t* out, int64_t ldo, int nv, int F, int D, int H, float4* vtab, const VtabSaved& q) {
+#define HGNN_VTAB(LL) \
+  gat_vtab_kernel<LL><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab, q.outm, q.ldom, q.csum, q.d_el)
   switch (L) {
-    case 1: gat_vtab_kernel<1><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    case 2: gat_vtab_kernel<2><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    case 4: gat_vtab_kernel<4><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    case 8: gat_vtab_kernel<8><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    case 16: gat_vtab_kernel<16><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    case 32: gat_vtab_kernel<32><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
-    default: gat_vtab_kernel<64><<<grid, kBlock, 0, s>>>(el, lse, dOut, lddo, out, ldo, nv, F, D, H, vtab); break;
+    case 1: HGNN_VTAB(1); break;
+    case 2: HGNN_VTAB(2); break;
+    case 4: HGNN_VTAB(4); break;
+    case 8: HGNN_VTAB(8); break;
+    case 16: HGNN_VTAB(16); break;
+    case 32: HGNN_VTAB(32); break;
+    default: HGNN_VTAB(64); break;
   }
+#undef HGNN_VTAB
 }
 
 // one pass (segment kernel + follow-up) over the graph in `a` with the segment arrays of plan q
@@ -547,14 +570,16 @@ static hgnn_status run_bwd_pass(const hgnn_plan* q, const hgnn_csr* gg, GatBwdAr
 
 using namespace hgnn;
 
-extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt,
-                                               const hgnn_plan* pt, int32_t H, int32_t D, const hgnn_half* U, int64_t ldu,
-                                               const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r,
-                                               float neg_slope, const hgnn_half* out, int64_t ldo, const float* lse,
-                                               const hgnn_half* dOut, int64_t lddo, hgnn_half* dV, int64_t lddv,
-                                               hgnn_half* d_el, hgnn_half* d_er, void* stream) {
+// out_masked / csum: what hgnn_gat_forward_fused_save left (then d_el is a per-vertex expression and the pass over g
+// is not needed), or nullptr
+static hgnn_status gat_backward_impl(const char* who, const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt,
+                                     const hgnn_plan* pt, int32_t H, int32_t D, const hgnn_half* U, int64_t ldu,
+                                     const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r,
+                                     float neg_slope, const hgnn_half* out, int64_t ldo, const float* lse,
+                                     const hgnn_half* out_masked, int64_t ldom, const float* csum, const hgnn_half* dOut,
+                                     int64_t lddo, hgnn_half* dV, int64_t lddv, hgnn_half* d_el, hgnn_half* d_er,
+                                     void* stream) {
   clear_error();
-  const char* who = "hgnn_gat_backward_fused";
   hgnn_status st = check_csr_args(g, who);
   if (st != HGNN_OK) return st;
   st = check_csr_args(gt, who);
@@ -577,6 +602,10 @@ extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_pla
   HGNN_REQUIRE(U && Vt && a_l && a_r && out && lse && dOut && dV && d_el && d_er, HGNN_EINVAL, "%s: NULL argument", who);
   HGNN_REQUIRE(ldo % 8 == 0 && lddo % 8 == 0 && lddv % 8 == 0 && aligned16(out) && aligned16(dOut) && aligned16(dV),
                HGNN_EUNSUPPORTED, "%s: needs ld %% 8 == 0 and 16-byte aligned out, dOut, dV", who);
+  const bool saved = out_masked != nullptr;
+  HGNN_REQUIRE(!saved || (csum != nullptr && ldom >= F), HGNN_EINVAL, "%s: out_masked needs csum and ldom >= F", who);
+  HGNN_REQUIRE(!saved || (ldom % 8 == 0 && aligned16(out_masked)), HGNN_EUNSUPPORTED,
+               "%s: needs ldom %% 8 == 0 and a 16-byte aligned out_masked", who);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // per-vertex scalars in plan p's scratch: el, er, then (el, lse, t) packed per destination vertex
   st = gat_project(p, g, H, D, U, ldu, Vt, ldv, a_l, a_r, s, who);
@@ -588,7 +617,7 @@ extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_pla
   if (g->nrows > 0) {
     launch_vtab(L, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * G))), s, el, lse,
                 reinterpret_cast<const half_t*>(dOut), lddo, reinterpret_cast<const half_t*>(out), ldo, g->nrows, F, D, H,
-                vtab);
+                vtab, VtabSaved{reinterpret_cast<const half_t*>(out_masked), ldom, csum, reinterpret_cast<half_t*>(d_el)});
     HGNN_LAUNCH_CHECK("gat_vtab_kernel");
   }
   GatBwdArgs a{};
@@ -616,8 +645,8 @@ extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_pla
     st = run_bwd_pass<true>(pt, gt, t, s);
     if (st != HGNN_OK) return st;
   }
-  // forward pass: rows i (destinations), gathers h_j; d_el_i only
-  if (g->nrows > 0) {
+  // forward pass: rows i (destinations), gathers h_j; d_el_i only (already written above from the saved tensors)
+  if (g->nrows > 0 && !saved) {
     GatBwdArgs f = a;
     f.rowptr = g->rowptr;
     f.col = g->col;
@@ -633,4 +662,30 @@ extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_pla
     if (st != HGNN_OK) return st;
   }
   return HGNN_OK;
+}
+
+extern "C" hgnn_status hgnn_gat_backward_fused(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt,
+                                               const hgnn_plan* pt, int32_t H, int32_t D, const hgnn_half* U, int64_t ldu,
+                                               const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r,
+                                               float neg_slope, const hgnn_half* out, int64_t ldo, const float* lse,
+                                               const hgnn_half* dOut, int64_t lddo, hgnn_half* dV, int64_t lddv,
+                                               hgnn_half* d_el, hgnn_half* d_er, void* stream) {
+  return gat_backward_impl("hgnn_gat_backward_fused", g, p, gt, pt, H, D, U, ldu, Vt, ldv, a_l, a_r, neg_slope, out, ldo, lse,
+                           nullptr, 0, nullptr, dOut, lddo, dV, lddv, d_el, d_er, stream);
+}
+
+extern "C" hgnn_status hgnn_gat_backward_fused_saved(const hgnn_csr* g, const hgnn_plan* p, const hgnn_csr* gt,
+                                                     const hgnn_plan* pt, int32_t H, int32_t D, const hgnn_half* U,
+                                                     int64_t ldu, const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l,
+                                                     const hgnn_half* a_r, float neg_slope, const hgnn_half* out, int64_t ldo,
+                                                     const float* lse, const hgnn_half* out_masked, int64_t ldom,
+                                                     const float* csum, const hgnn_half* dOut, int64_t lddo, hgnn_half* dV,
+                                                     int64_t lddv, hgnn_half* d_el, hgnn_half* d_er, void* stream) {
+  const char* who = "hgnn_gat_backward_fused_saved";
+  if (out_masked == nullptr || csum == nullptr) {
+    clear_error();
+    return fail(HGNN_EINVAL, "%s: out_masked and csum are required", who);
+  }
+  return gat_backward_impl(who, g, p, gt, pt, H, D, U, ldu, Vt, ldv, a_l, a_r, neg_slope, out, ldo, lse, out_masked, ldom, csum,
+                           dOut, lddo, dV, lddv, d_el, d_er, stream);
 }

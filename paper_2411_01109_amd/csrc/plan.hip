@@ -217,9 +217,11 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
                                                                                   p->seg_row_lo, p->seg_row_hi);
     HGNN_LAUNCH_CHECK("seg_rows_kernel");
     // staging: two partial vectors (entering piece / leaving piece) per segment
-    HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F)));
-    HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(2) * size_t(p->nseg) * size_t(p->max_F), s));
-    HGNN_HIP(hipMalloc(&p->stage_mz, sizeof(float) * size_t(4) * size_t(p->nseg) * size_t(p->max_H)));
+    // (twice over, and three scalars per piece and head: the fused GAT pass that saves for its backward stages two
+    // vectors and (max, sum, masked sum) per piece)
+    HGNN_HIP(hipMalloc(&p->staging, sizeof(hgnn_half) * size_t(4) * size_t(p->nseg) * size_t(p->max_F)));
+    HGNN_HIP(hipMemsetAsync(p->staging, 0, sizeof(hgnn_half) * size_t(4) * size_t(p->nseg) * size_t(p->max_F), s));
+    HGNN_HIP(hipMalloc(&p->stage_mz, sizeof(float) * size_t(6) * size_t(p->nseg) * size_t(p->max_H)));
   }
   hgnn_status st = compact_rows(SplitPred{g->rowptr, p->S}, g->nrows, &p->split_row, &p->n_split, s);
   if (st != HGNN_OK) return st;

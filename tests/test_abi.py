@@ -100,6 +100,11 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_gat_alpha(gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, A, Y, None) == EINVAL
     assert lib.hgnn_gat_backward_fused(gp, None, gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, X, 8,
                                        Y, 8, A, A, None) == EINVAL
+    assert lib.hgnn_gat_forward_fused_save(gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, Y, 8, A, None) == EINVAL
+    assert lib.hgnn_gat_forward_fused_save(gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, None, 8, A, None) == EINVAL
+    assert b"required" in lib.hgnn_last_error()
+    assert lib.hgnn_gat_backward_fused_saved(gp, None, gp, None, 1, 8, X, 8, X, 8, A, A, 0.2, Y, 8, A, None, 8, None, X, 8,
+                                             Y, 8, A, A, None) == EINVAL
     assert lib.hgnn_edge_to_transposed(None, 1, X, Y, None) == EINVAL
     assert lib.hgnn_edge_to_transposed(gp, 1, X, Y, None) == EINVAL           # a transposed graph carries eid
     assert lib.hgnn_scale_rows(4, 0, X, 8, A, Y, 8, None) == EINVAL            # F <= 0

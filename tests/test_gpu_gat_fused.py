@@ -239,3 +239,69 @@ def test_gat_backward_fused_full_configs(hgnn, dev, maker, nb):
     (dV, dV_abs), (_, _), (d_er, er_abs) = bwd_reference(sub_ptr, sub_col, w.V, feat[need], feat, a_l, a_r, dOut[need], H)
     compare(f"{w.name} dV", g_dV[cols], dV[cols], dV_abs[cols])
     compare(f"{w.name} d_er", g_er[cols], d_er[cols], er_abs[cols], rel_l2=2e-2)
+
+
+# ------------------------------------------------------------------ forward that saves for the backward
+SAVE_CASES = [(1, 64, 256, 1), (4, 16, 256, 1), (8, 8, 128, 1), (2, 32, 64, 1), (1, 8, 7, 1), (1, 128, 256, 1), (1, 64, 256, 3),
+              (4, 16, 100, 4), (3, 8, 33, 2), (8, 64, 256, 1)]
+
+
+@pytest.mark.parametrize("H,D,S,nb", SAVE_CASES)
+def test_gat_forward_save_and_backward_saved(hgnn, dev, H, D, S, nb):
+    """The saving forward leaves out_masked / csum; the backward that takes them skips its pass over g.  Everything
+    against the oracle; the tensors both variants produce (out, lse, dV, d_er) must not depend on the variant."""
+    print(f"gat save H={H} D={D} S={S} nb={nb}", flush=True)
+    V = 1000
+    F = H * D
+    rowptr, col = rand_graph(V, V, 12, H * 100 + D + S, hubs=((5, 4500), (700, 777), (999, 300)), empties=(0, 6, 998))
+    r = np.random.default_rng(H * 11 + D)
+    X, dOut = f16(r.standard_normal((V, F))), f16(r.standard_normal((V, F)))
+    a_l, a_r = f16(0.3 * r.standard_normal(F)), f16(0.3 * r.standard_normal(F))
+    oref, lref, oabs, mref, cref = oracle.gat_forward(rowptr, col, X, X, a_l, a_r, H, slope=0.2, want_saved=True)
+    (dV, dV_abs), (d_el, el_abs), (d_er, er_abs) = bwd_reference(rowptr, col, V, X, X, a_l, a_r, dOut, H)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, S, F, H, col_blocks=nb)
+    pt = hgnn.hgnn_plan_create(gt, S, F, H, col_blocks=nb)
+    Xd, ald, ard, dOd = up(X, dev), up(a_l, dev), up(a_r, dev), up(dOut, dev)
+    half = lambda *s: torch.full(s, 7.0, dtype=torch.float16, device=dev)
+    f32 = lambda *s: torch.full(s, 7.0, dtype=torch.float32, device=dev)
+    out, outm_buf, lse, csum = half(V, F), half(V, F + 8), f32(V, H), f32(V, H)
+    outm = outm_buf[:, :F]
+    hgnn.hgnn_gat_forward_fused_save(g, p, H, D, Xd, Xd, ald, ard, out, lse, outm, csum)
+    compare("out", down(out), oref, oabs)
+    check_lse("save", down(lse), lref, np.diff(rowptr))
+    compare("out_masked", down(outm_buf)[:, :F], mref, oabs)
+    assert np.all(down(outm_buf)[:, F:] == 7.0)
+    assert np.abs(down(csum).astype(np.float64) - cref).max() <= 2e-3
+    # the plain forward gives the same out and lse
+    out0, lse0 = half(V, F), f32(V, H)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, ald, ard, out0, lse0)
+    assert np.array_equal(down(out0).view(np.uint16), down(out).view(np.uint16))
+    assert np.array_equal(down(lse0), down(lse))
+    # backward with the saved tensors
+    dVs, d_els, d_ers = half(V, F), half(V, H), half(V, H)
+    hgnn.hgnn_gat_backward_fused_saved(g, p, gt, pt, H, D, Xd, Xd, ald, ard, out, lse, outm, csum, dOd, dVs, d_els, d_ers)
+    compare("dV", down(dVs), dV, dV_abs)
+    compare("d_el saved", down(d_els), d_el, el_abs, rel_l2=2e-2)
+    compare("d_er", down(d_ers), d_er, er_abs, rel_l2=2e-2)
+    dV0, d_el0, d_er0 = half(V, F), half(V, H), half(V, H)
+    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, Xd, Xd, ald, ard, out, lse, dOd, dV0, d_el0, d_er0)
+    assert np.array_equal(down(dV0).view(np.uint16), down(dVs).view(np.uint16))
+    assert np.array_equal(down(d_er0).view(np.uint16), down(d_ers).view(np.uint16))
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
+
+
+def test_gat_save_argument_errors(hgnn, dev):
+    V, H, D = 50, 1, 8
+    rowptr, col = rand_graph(V, V, 4, 3)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 64, 8, 1)
+    X = torch.zeros((V, 8), dtype=torch.float16, device=dev)
+    a = torch.zeros(8, dtype=torch.float16, device=dev)
+    lse = torch.zeros((V, 1), dtype=torch.float32, device=dev)
+    with pytest.raises(hgnn.HgnnError) as e:
+        hgnn.hgnn_gat_forward_fused_save(g, p, H, D, X, X, a, a, X.clone(), lse, X.clone(), lse.clone(), neg_slope=-0.1)
+    assert e.value.status == hgnn.HGNN_EINVAL and "slope" in str(e.value)
+    hgnn.hgnn_plan_destroy(p)

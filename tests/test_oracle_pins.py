@@ -570,6 +570,45 @@ def test_gat_backward_special_cases_and_composition():
     assert np.max(np.abs(d_el1)) < 1e-12
 
 
+def test_gat_saved_tensors_give_the_row_side_gradient():
+    """out_masked and csum against their definition on a dense graph, and the identity that makes them useful:
+    d_el[i,h] = <dOut[i,h], out_masked[i,h]> - <dOut[i,h], out[i,h]> * csum[i,h], with d_el from the separately
+    pinned backward."""
+    V, ncols, H, D = 21, 17, 2, 4
+    F = H * D
+    rowptr, col, row = small_graph(V, ncols, 0.4, 8, empty_rows=(3,))
+    U, Vt = rng.standard_normal((V, F)).astype(np.float16), rng.standard_normal((ncols, F)).astype(np.float16)
+    dOut = rng.standard_normal((V, F)).astype(np.float16)
+    a_l, a_r = (0.6 * rng.standard_normal(F)).astype(np.float16), (0.6 * rng.standard_normal(F)).astype(np.float16)
+    slope = 0.3
+    out, lse, _, outm, csum = oracle.gat_forward(rowptr, col, U, Vt, a_l, a_r, H, slope=slope, want_saved=True)
+    # definition, edge by edge in python
+    el = (U.astype(np.float64).reshape(V, H, D) * a_l.astype(np.float64).reshape(H, D)).sum(-1)
+    er = (Vt.astype(np.float64).reshape(ncols, H, D) * a_r.astype(np.float64).reshape(H, D)).sum(-1)
+    raw = el[row] + er[col]
+    alpha = oracle.edge_softmax(rowptr, np.where(raw > 0, raw, slope * raw))
+    mu = np.where(raw > 0, 1.0, slope)
+    assert (raw > 0).any() and (raw <= 0).any()  # both branches of the mask occur
+    want_m, want_c = np.zeros((V, F)), np.zeros((V, H))
+    for k in range(col.size):
+        want_m[row[k]] += np.repeat(alpha[k] * mu[k], D) * Vt.astype(np.float64)[col[k]]
+        want_c[row[k]] += alpha[k] * mu[k]
+    np.testing.assert_allclose(outm, want_m, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(csum, want_c, rtol=1e-12, atol=1e-13)
+    assert np.all(csum[3] == 0) and np.all(outm[3] == 0)  # the empty row
+    # slope 1: the mask is all ones, so the masked sums are the plain ones
+    o1, _, _, om1, c1 = oracle.gat_forward(rowptr, col, U, Vt, a_l, a_r, H, slope=1.0, want_saved=True)
+    np.testing.assert_allclose(om1, o1, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(c1[np.diff(rowptr) > 0], 1.0, rtol=1e-13)
+    # the identity with the backward's d_el
+    _, d_el, _ = oracle.gat_backward(rowptr, col, U, Vt, a_l, a_r, dOut, H, slope=slope)
+    dO = dOut.astype(np.float64).reshape(V, H, D)
+    t = (dO * out.reshape(V, H, D)).sum(-1)
+    got = (dO * outm.reshape(V, H, D)).sum(-1) - t * csum
+    np.testing.assert_allclose(got, d_el, rtol=1e-10, atol=1e-12)
+    assert np.abs(d_el).max() > 1e-2
+
+
 def test_edge_gather_is_the_transposed_order():
     """The k-th non-zero of the transpose carries the value of non-zero eid[k]: with the pre-permuted values and no
     edge-id map the transposed SpMM gives the same result as with the map, and the dense transpose agrees."""
