@@ -183,8 +183,8 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save)
   o.blk_off = o.row_off + o.spad * 4;
   o.sc_off = o.blk_off + ((o.spad + 15) & ~15);
   o.vec_off = o.sc_off + o.spad * H * 4;
-  o.mz_off = o.vec_off + 2 * G * nv * 8 * L * 4;
-  o.flag_off = o.mz_off + 2 * G * L * ns * 4;
+  o.mz_off = o.vec_off + G * nv * 8 * L * 4;  // one parked piece per lane group: the one that entered its chunk
+  o.flag_off = o.mz_off + G * L * ns * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
   return o;
 }
@@ -213,8 +213,11 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU
-  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][NV][VEC]: slot 2g = entering, 2g+1 = leaving
-  float* m_mz = reinterpret_cast<float*>(base + lay.mz_off);    // [2*G][L][NS]: (m, z[, zm]) of the parked pieces, per lane
+  // The piece that entered a group's chunk is parked in LDS when its row ends; the piece that leaves the chunk stays
+  // in the group's registers and the merge reads it from there (cross-lane reads take no LDS allocation, and the
+  // kernel's speed follows the number of waves that fit a compute unit).
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [G][NV][VEC]: the entering piece of group g
+  float* m_mz = reinterpret_cast<float*>(base + lay.mz_off);    // [G][L][NS]: its (m, z[, zm]), per lane
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
@@ -298,14 +301,15 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   auto flush = [&](bool ro) {
     if (!lo && !ro) {
       if (active) row_store<SAVE>(a, cur, f0, head, leader, t);
-    } else {
-      const int slot = lo ? 2 * g : 2 * g + 1;
-      park(slot, t);
+    } else if (lo) {
+      park(g, t);
       if (l == 0) {
-        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
-        if (lo) m_hrow[g] = cur;
-        else m_trow[g] = cur;
+        m_flag[g] |= ro ? 3 : 1;
+        m_hrow[g] = cur;
       }
+    } else if (l == 0) {  // leaves into the next chunk (only the last flush of a chunk gets here): stays in t
+      m_flag[g] |= 4;
+      m_trow[g] = cur;
     }
   };
   auto gather = [&](int c) -> half8_t {
@@ -391,21 +395,22 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   wave_sync();
 
   // ---- merge: group 0 sews the parked pieces together in chunk order
-  if (valid && g == 0) {
+  if (valid) {  // all lanes take part in the cross-lane reads; only group 0 keeps and stores the result
     Soft<SAVE> run;
     bool open = false, from_before = false;
     int run_row = -1;
+    const bool me = g == 0 && active;
     for (int gg = 0; gg < G; ++gg) {
-      const int fl = m_flag[gg];
+      const int fl = m_flag[gg];  // the same value on every lane
       if (fl & 1) {
-        soft_merge<SAVE>(run, unpark(2 * gg));
+        if (g == 0) soft_merge<SAVE>(run, unpark(gg));
         if (gg == 0) {
           from_before = true;
           open = true;
           run_row = m_hrow[0];
         }
         if (!(fl & 2)) {  // the row ends inside chunk gg
-          if (active) {
+          if (me) {
             if (from_before) stage_store<SAVE>(a, 2 * seg, f0, head, leader, run);
             else row_store<SAVE>(a, run_row, f0, head, leader, run);
           }
@@ -414,14 +419,23 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
           from_before = false;
         }
       }
-      if (fl & 4) {
-        run = unpark(2 * gg + 1);
+      if (fl & 4) {  // the piece that left chunk gg: from the registers of group gg
+        const int src = gg * L + l;
+        run.m = __shfl(t.m, src);
+        run.z = __shfl(t.z, src);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) run.acc[i] = __shfl(t.acc[i], src);
+        if (SAVE) {
+          run.zm = __shfl(t.zm, src);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) run.accm[i] = __shfl(t.accm[i], src);
+        }
         run_row = m_trow[gg];
         open = true;
         from_before = false;
       }
     }
-    if (open && active)  // leaves into the next segment; a piece that also entered uses slot 2*seg
+    if (open && me)  // leaves into the next segment; a piece that also entered uses slot 2*seg
       stage_store<SAVE>(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, run);
   }
 

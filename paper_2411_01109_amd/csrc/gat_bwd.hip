@@ -59,8 +59,8 @@ __host__ __device__ inline GatBwdLds gat_bwd_lds_layout(int S, int H, int L, boo
   o.a_off = o.blk_off + ((o.spad + 15) & ~15);
   o.t_off = o.a_off + o.spad * H * 4;
   o.vec_off = o.t_off + o.spad * H * 4;
-  o.ds_off = o.vec_off + (vec ? 2 * G * 8 * L * 4 : 0);
-  o.flag_off = o.ds_off + 2 * G * L * 4;
+  o.ds_off = o.vec_off + (vec ? G * 8 * L * 4 : 0);  // one parked piece per lane group: the one that entered its chunk
+  o.flag_off = o.ds_off + G * L * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
   return o;
 }
@@ -114,8 +114,10 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   float* s_a = reinterpret_cast<float*>(base + lay.a_off);    // [spad][H]: alpha, negated where the score is <= 0
   float* s_t = reinterpret_cast<float*>(base + lay.t_off);    // [spad][H]: alpha * mask * t of the destination vertex
-  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VECF] parked vectors (VEC)
-  float* m_ds = reinterpret_cast<float*>(base + lay.ds_off);    // [2*G][L] parked ds sums, per lane
+  // the piece that entered a group's chunk is parked here when its row ends; the piece that leaves the chunk stays
+  // in the group's registers, from where the merge reads it (no LDS allocation: more waves per compute unit)
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [G][VECF] parked vectors (VEC)
+  float* m_ds = reinterpret_cast<float*>(base + lay.ds_off);    // [G][L] parked ds sums, per lane
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
@@ -175,6 +177,7 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   float csum = 0.f;                                           // sum alpha * m * t
   int cur = -1;
   bool lo = false;
+  float leave_ds = 0.f;     // ds sum of the piece that leaves this chunk (its vector stays in acc)
   half8_t ur = half8_t(0);  // this lane's slice of the current row's row-side vector
   auto load_row_vec = [&](int r) { ur = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c); };
   auto flush = [&](bool ro) {
@@ -186,18 +189,22 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
     const float dsv = head_sum1(d, LH) - csum;
     if (!lo && !ro) {
       if (active) bwd_row_store<VEC>(a, cur, f0, head, leader, acc, dsv);
-    } else {
-      const int slot = lo ? 2 * g : 2 * g + 1;
+    } else if (lo) {
       if (VEC && active) {
-        float* dst = m_vec + slot * VECF + f0;
+        float* dst = m_vec + g * VECF + f0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) dst[i] = acc[i];
       }
-      m_ds[slot * L + l] = dsv;
+      m_ds[g * L + l] = dsv;
       if (l == 0) {
-        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
-        if (lo) m_hrow[g] = cur;
-        else m_trow[g] = cur;
+        m_flag[g] |= ro ? 3 : 1;
+        m_hrow[g] = cur;
+      }
+    } else {  // leaves into the next chunk (only the last flush of a chunk gets here)
+      leave_ds = dsv;
+      if (l == 0) {
+        m_flag[g] |= 4;
+        m_trow[g] = cur;
       }
     }
   };
@@ -265,28 +272,31 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
   if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
   wave_sync();
 
-  // ---- merge: group 0 sews the parked pieces together in chunk order
-  if (valid && g == 0) {
+  // ---- merge: group 0 sews the pieces together in chunk order (all lanes take part in the cross-lane reads)
+  if (valid) {
     float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float rds = 0.f;
     bool open = false, from_before = false;
     int run_row = -1;
+    const bool me = g == 0 && active;
     for (int gg = 0; gg < G; ++gg) {
-      const int fl = m_flag[gg];
+      const int fl = m_flag[gg];  // the same value on every lane
       if (fl & 1) {
-        if (VEC) {
-          const float* src = m_vec + (2 * gg) * VECF + f0c;
+        if (g == 0) {
+          if (VEC) {
+            const float* src = m_vec + gg * VECF + f0c;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) run[i] += src[i];
+            for (int i = 0; i < 8; ++i) run[i] += src[i];
+          }
+          rds += m_ds[gg * L + l];
         }
-        rds += m_ds[(2 * gg) * L + l];
         if (gg == 0) {
           from_before = true;
           open = true;
           run_row = m_hrow[0];
         }
         if (!(fl & 2)) {
-          if (active) {
+          if (me) {
             if (from_before) bwd_stage_store<VEC>(a, 2 * seg, f0, head, leader, run, rds);
             else bwd_row_store<VEC>(a, run_row, f0, head, leader, run, rds);
           }
@@ -297,19 +307,19 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
           from_before = false;
         }
       }
-      if (fl & 4) {
+      if (fl & 4) {  // the piece that left chunk gg: from the registers of group gg
+        const int src = gg * L + l;
         if (VEC) {
-          const float* src = m_vec + (2 * gg + 1) * VECF + f0c;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) run[i] = src[i];
+          for (int i = 0; i < 8; ++i) run[i] = __shfl(acc[i], src);
         }
-        rds = m_ds[(2 * gg + 1) * L + l];
+        rds = __shfl(leave_ds, src);
         run_row = m_trow[gg];
         open = true;
         from_before = false;
       }
     }
-    if (open && active) bwd_stage_store<VEC>(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, run, rds);
+    if (open && me) bwd_stage_store<VEC>(a, 2 * seg + (from_before ? 0 : 1), f0, head, leader, run, rds);
   }
 
   // ---- this wave's share of the empty rows

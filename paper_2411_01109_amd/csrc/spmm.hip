@@ -385,13 +385,13 @@ __host__ __device__ inline SegLds seg_lds_layout(int S, int H, int wm, int L) {
   o.blk_off = o.row_off + o.spad * 4;
   o.w_off = o.blk_off + align16i(o.spad);  // one int per 4 edges
   o.vec_off = o.w_off + (wm == 0 ? 0 : align16i(o.spad * H * (wm == 2 ? 4 : 2)));
-  o.flag_off = o.vec_off + 2 * G * 8 * L * 4;
+  o.flag_off = o.vec_off + G * 8 * L * 4;  // one parked vector per lane group (the piece that entered its chunk)
   o.total = o.flag_off + align16i(3 * G * 4);
   return o;
 }
 
 template <int L, int WM, bool OFF32>
-__global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 7) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;  // floats per parked vector
   extern __shared__ __align__(16) unsigned char smem[];
@@ -409,7 +409,11 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);  // per 4 edges: their common row id, or -1
   half_t* s_w = reinterpret_cast<half_t*>(base + lay.w_off);   // WM == 1
   float* s_wf = reinterpret_cast<float*>(base + lay.w_off);    // WM == 2
-  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [2*G][VEC]: slot 2g = entering, 2g+1 = leaving
+  // A group's piece that entered its chunk from the previous one is parked in LDS when its row ends; the piece that
+  // leaves into the next chunk simply stays in the group's registers and is fetched from there by the merge
+  // (cross-lane reads need no LDS allocation).  Every KB of LDS less per wave is more waves per compute unit, and
+  // this latency-bound gather speeds up almost in proportion.
+  float* m_vec = reinterpret_cast<float*>(base + lay.vec_off);  // [G][VEC]: the entering piece of group g
   int* m_flag = reinterpret_cast<int*>(base + lay.flag_off);    // bit0 entering, bit1 runs through, bit2 leaving
   int* m_hrow = m_flag + G;
   int* m_trow = m_hrow + G;
@@ -477,17 +481,22 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
     const float sc = scale_of(a, cur);
     if (!lo && !ro) {
       if (active) store_row(a, cur, f0, acc, sc);
-    } else {
-      const int slot = lo ? 2 * g : 2 * g + 1;
+    } else if (lo) {
       if (active) {
-        float* dst = m_vec + slot * VEC + f0;
+        float* dst = m_vec + g * VEC + f0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) dst[i] = acc[i] * sc;
       }
       if (l == 0) {
-        m_flag[g] |= lo ? (ro ? 3 : 1) : 4;
-        if (lo) m_hrow[g] = cur;
-        else m_trow[g] = cur;
+        m_flag[g] |= ro ? 3 : 1;
+        m_hrow[g] = cur;
+      }
+    } else {  // leaves into the next chunk (only the last flush of a chunk gets here): stays in acc, scaled
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] *= sc;
+      if (l == 0) {
+        m_flag[g] |= 4;
+        m_trow[g] = cur;
       }
     }
   };
@@ -554,16 +563,17 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
   if (c0 < c1) flush(c1 < n ? s_row[c1] == cur : seg_right_open);
   wave_sync();
 
-  // ---- merge: group 0 sews the parked pieces together in chunk order
-  if (valid && g == 0) {
+  // ---- merge: group 0 sews the pieces together in chunk order (all lanes take part in the cross-lane reads)
+  if (valid) {
     float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bool open = false, from_before = false;
     int run_row = -1;
+    const bool me = g == 0 && active;
     for (int gg = 0; gg < G; ++gg) {
-      const int fl = m_flag[gg];
+      const int fl = m_flag[gg];  // the same value on every lane
       if (fl & 1) {
-        if (active) {
-          const float* src = m_vec + (2 * gg) * VEC + f0;
+        if (me) {
+          const float* src = m_vec + gg * VEC + f0;
 #pragma unroll
           for (int i = 0; i < 8; ++i) run[i] += src[i];
         }
@@ -573,7 +583,7 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
           run_row = m_hrow[0];
         }
         if (!(fl & 2)) {  // the row ends inside chunk gg
-          if (active) {
+          if (me) {
             if (!from_before) store_row(a, run_row, f0, run, 1.f);
             else if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run, a.F - f0);
             else store8(a.staging + (2 * seg) * a.stage_ld + f0, run, 1.f);
@@ -584,18 +594,15 @@ __global__ __launch_bounds__(kBlock) void spmm_seg_kernel(SpmmArgs a) {
           from_before = false;
         }
       }
-      if (fl & 4) {
-        if (active) {
-          const float* src = m_vec + (2 * gg + 1) * VEC + f0;
+      if (fl & 4) {  // the piece that left chunk gg: from the registers of group gg
 #pragma unroll
-          for (int i = 0; i < 8; ++i) run[i] = src[i];
-        }
+        for (int i = 0; i < 8; ++i) run[i] = __shfl(acc[i], gg * L + l);
         run_row = m_trow[gg];
         open = true;
         from_before = false;
       }
     }
-    if (open && active) {  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
+    if (open && me) {  // leaves into the next segment; a piece that also entered is a "middle" and uses slot 2*seg
       if (a.atomic_y) atomic_add8(a.Y + int64_t(run_row) * a.ldy + f0, run, a.F - f0);
       else store8(a.staging + (2 * seg + (from_before ? 0 : 1)) * a.stage_ld + f0, run, 1.f);
     }
