@@ -94,7 +94,7 @@ __device__ __forceinline__ void bwd_stage_store(const GatBwdArgs& a, int64_t slo
 }
 
 template <int L, bool OFF32, bool VEC>
-__global__ __launch_bounds__(kBlock) void gat_bwd_seg_kernel(GatBwdArgs a) {
+__global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwdArgs a) {
   constexpr int G = kWave / L;
   constexpr int VECF = 8 * L;
   extern __shared__ __align__(16) unsigned char smem[];
