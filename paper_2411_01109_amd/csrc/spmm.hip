@@ -391,7 +391,7 @@ __host__ __device__ inline SegLds seg_lds_layout(int S, int H, int wm, int L) {
 }
 
 template <int L, int WM, bool OFF32>
-__global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 7) void spmm_seg_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;  // floats per parked vector
   extern __shared__ __align__(16) unsigned char smem[];
