@@ -63,7 +63,7 @@ __host__ __device__ inline SddmmLds sddmm_lds_layout(int S, int H) {
 // VW = halves per lane and load: 8 (16 bytes), or 4 / 2 for the vector-width study of section 6.3.1 (a head
 // then spans D/VW lanes and the reduction across lanes has more rounds).
 template <int L, int VW, bool MASK>
-__global__ __launch_bounds__(kBlock) void sddmm_seg_kernel(SddmmArgs a) {
+__global__ __launch_bounds__(kBlock, 8) void sddmm_seg_kernel(SddmmArgs a) {
   constexpr int G = kWave / L;
   typedef _Float16 hv_t __attribute__((ext_vector_type(VW)));
   extern __shared__ __align__(16) unsigned char smem[];
