@@ -305,3 +305,47 @@ def test_gat_save_argument_errors(hgnn, dev):
         hgnn.hgnn_gat_forward_fused_save(g, p, H, D, X, X, a, a, X.clone(), lse, X.clone(), lse.clone(), neg_slope=-0.1)
     assert e.value.status == hgnn.HGNN_EINVAL and "slope" in str(e.value)
     hgnn.hgnn_plan_destroy(p)
+
+
+@pytest.mark.parametrize("maker,nb", [(wl.gat_rmat, 1), (wl.dense_degree, 0)])
+def test_gat_save_and_saved_backward_full_configs(hgnn, dev, maker, nb):
+    """Configs 3 and 5 at full size through the saving forward and the one-pass backward: out_masked, csum and d_el on
+    sampled rows against the oracle (on the sub-graph of those rows); out / lse / dV / d_er must be the bits of the
+    plain forward and the two-pass backward."""
+    w = maker()
+    print(f"gat save full config {w.name}", flush=True)
+    feat = w.tensors["h"] if "h" in w.tensors else w.tensors["X"]
+    dOut = w.tensors["dOut"] if "dOut" in w.tensors else w.tensors["dY"]
+    H, V = w.H, w.V
+    F = feat.shape[1]
+    D = F // H
+    a_l, a_r = w.tensors["a_l"].reshape(-1), w.tensors["a_r"].reshape(-1)
+    g = hgnn.Csr(up(w.rowptr, dev), up(w.col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=nb)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=nb)
+    Xd, ald, ard, dOd = up(feat, dev), up(a_l, dev), up(a_r, dev), up(dOut, dev)
+    half = lambda *s: torch.empty(s, dtype=torch.float16, device=dev)
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=dev)
+    out, outm, lse, csum = half(V, F), half(V, F), f32(V, H), f32(V, H)
+    hgnn.hgnn_gat_forward_fused_save(g, p, H, D, Xd, Xd, ald, ard, out, lse, outm, csum)
+    out0, lse0 = half(V, F), f32(V, H)
+    hgnn.hgnn_gat_forward_fused(g, p, H, D, Xd, Xd, ald, ard, out0, lse0)
+    assert np.array_equal(down(out0).view(np.uint16), down(out).view(np.uint16)) and np.array_equal(down(lse0), down(lse))
+    dVs, d_els, d_ers = half(V, F), half(V, H), half(V, H)
+    hgnn.hgnn_gat_backward_fused_saved(g, p, gt, pt, H, D, Xd, Xd, ald, ard, out, lse, outm, csum, dOd, dVs, d_els, d_ers)
+    dV0, d_el0, d_er0 = half(V, F), half(V, H), half(V, H)
+    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, D, Xd, Xd, ald, ard, out, lse, dOd, dV0, d_el0, d_er0)
+    assert np.array_equal(down(dV0).view(np.uint16), down(dVs).view(np.uint16))
+    assert np.array_equal(down(d_er0).view(np.uint16), down(d_ers).view(np.uint16))
+    rows = sample_rows(w.rowptr, 200, 9)
+    sub_ptr = np.concatenate([[0], np.cumsum(np.diff(w.rowptr)[rows])]).astype(np.int32)
+    sub_col = np.concatenate([w.col[w.rowptr[r]:w.rowptr[r + 1]] for r in rows]).astype(np.int32)
+    oref, _, oabs, mref, cref = oracle.gat_forward(sub_ptr, sub_col, feat[rows], feat, a_l, a_r, H, want_saved=True)
+    compare(f"{w.name} out_masked", down(outm)[rows], mref, oabs)
+    assert np.abs(down(csum)[rows].astype(np.float64) - cref).max() <= 2e-3
+    (_, _), (d_el, el_abs), (_, _) = bwd_reference(sub_ptr, sub_col, V, feat[rows], feat, a_l, a_r, dOut[rows], H)
+    compare(f"{w.name} d_el saved", down(d_els)[rows], d_el, el_abs, rel_l2=2e-2)
+    compare(f"{w.name} d_el two-pass", down(d_el0)[rows], d_el, el_abs, rel_l2=2e-2)
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
