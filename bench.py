@@ -410,6 +410,8 @@ def main():
             variants[f"vertex_groups_{ng}"] = {
                 "ms": round(time_call(lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS)), 4),
                 "groups": hgnn.hgnn_plan_num_groups(plan1)}
+        variants["vertex_groups_256_half2_arithmetic"] = {
+            "ms": round(time_call(lambda: hgnn.hgnn_spmm_discretized_variant(plan1, g, ew, 1, X, Y, hgnn.HGNN_VERTEX_GROUPS_HALF2)), 4)}
         variants["vertex_rows_no_plan"] = {"ms": round(time_call(lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y)), 4)}
         for k in variants:
             variants[k]["req_GBps"] = round(spmm_req(wH, False) / (variants[k]["ms"] * 1e-3) / 1e9, 1)

@@ -200,8 +200,8 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
                                         hgnn_reduce op, const float* row_scale, const hgnn_spmm_fusion* fz,
                                         void* stream);
 
-/* The two comparison variants of the discretized SpMM that the paper measures against its own
- * design (sections 5.4, 6.3.2 "atomic vs. non-atomic writes", 6.3.3 vertex-parallel form); same
+/* The comparison variants of the discretized SpMM that the paper measures against its own
+ * design (sections 4.2, 5.4, 6.3.2 "atomic vs. non-atomic writes", 6.3.3 vertex-parallel form); same
  * arguments, same result up to fp16 rounding order, always on the whole graph (a plan's
  * column blocks are not used).
  *  HGNN_EDGE_SEGMENTS          the library's own design, identical to hgnn_spmm_discretized.
@@ -214,8 +214,18 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
  *      a row of several groups stages one scaled fp16 partial per group and a follow-up kernel
  *      adds them (no atomics, deterministic).  Edge values of a group that starts at an odd
  *      position are fetched as aligned pairs from one position earlier.  Needs
- *      hgnn_plan_add_groups on the plan first. */
-typedef enum { HGNN_EDGE_SEGMENTS = 0, HGNN_EDGE_SEGMENTS_ATOMIC = 1, HGNN_VERTEX_GROUPS = 2 } hgnn_spmm_variant;
+ *      hgnn_plan_add_groups on the plan first.
+ *  HGNN_VERTEX_GROUPS_HALF2    HGNN_VERTEX_GROUPS with the paper's arithmetic (section 4.2): inside a
+ *      lane's share of a neighbour group the products and the sum are packed fp16 (two features per
+ *      instruction, the edge value mirrored into both halves); everything after that as above.  For
+ *      measurement: the result carries fp16 accumulation error (about group_edges * 2^-11 relative
+ *      to the sum of the terms' magnitudes) and a lane's partial must fit fp16. */
+typedef enum {
+  HGNN_EDGE_SEGMENTS = 0,
+  HGNN_EDGE_SEGMENTS_ATOMIC = 1,
+  HGNN_VERTEX_GROUPS = 2,
+  HGNN_VERTEX_GROUPS_HALF2 = 3
+} hgnn_spmm_variant;
 
 hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
                                           const hgnn_half* X, int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F,

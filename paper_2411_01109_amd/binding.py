@@ -31,7 +31,7 @@ EXPORTS = (
     "hgnn_gat_backward_fused_saved",
 )
 
-HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS = 0, 1, 2
+HGNN_EDGE_SEGMENTS, HGNN_EDGE_SEGMENTS_ATOMIC, HGNN_VERTEX_GROUPS, HGNN_VERTEX_GROUPS_HALF2 = 0, 1, 2, 3
 
 
 class HgnnError(RuntimeError):

@@ -704,6 +704,7 @@ struct VGroupArgs {
   int64_t n_groups;
   int ng;
   int pair_loads;  // edge values: one per edge, no edge-id map, 4-byte aligned base
+  int acc16;       // products and sums of a lane's chunk in packed fp16 (the paper's arithmetic, section 4.2)
 };
 
 __host__ __device__ inline int vgroup_lds_bytes(int ng, int H, bool has_w) {
@@ -782,6 +783,9 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
   float acc[VW];
 #pragma unroll
   for (int q = 0; q < VW; ++q) acc[q] = 0.f;
+  half2_t acc2[VW / 2 > 0 ? VW / 2 : 1];
+#pragma unroll
+  for (int q = 0; q < VW / 2; ++q) acc2[q] = half2_t{half_t(0), half_t(0)};
   auto gather = [&](int c) -> hv_t {
     if (OFF32) {
       const uint32_t boff = uint32_t(c) + uint32_t(f0c) * 2u;
@@ -808,9 +812,27 @@ __global__ __launch_bounds__(kBlock) void spmm_vgroup_kernel(SpmmArgs a, VGroupA
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (i + 4 <= c1 || i + u < c1) {
+        if (VW == 8 && v.acc16) {
+          // section 4.2: the edge value mirrored into both halves of a pair multiplies two features per
+          // instruction (v_pk_fma_f16); the sum of this lane's chunk stays in fp16
+          const half2_t w2 = {half_t(wv[u]), half_t(wv[u])};
 #pragma unroll
-        for (int q = 0; q < VW; ++q) acc[q] = fmaf(wv[u], float(x[u][q]), acc[q]);
+          for (int q = 0; q < VW / 2; ++q) {
+            const half2_t x2 = {x[u][2 * q], x[u][2 * q + 1]};
+            acc2[q] = x2 * w2 + acc2[q];
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < VW; ++q) acc[q] = fmaf(wv[u], float(x[u][q]), acc[q]);
+        }
       }
+    }
+  }
+  if (VW == 8 && v.acc16) {
+#pragma unroll
+    for (int q = 0; q < VW / 2; ++q) {
+      acc[2 * q] = float(acc2[q][0]);
+      acc[2 * q + 1] = float(acc2[q][1]);
     }
   }
 #pragma unroll
@@ -1093,8 +1115,9 @@ static void launch_vgroup_finish(int L, dim3 grid, hipStream_t s, const SpmmArgs
 }
 
 // The vertex-parallel variant for the graph in `a` with the neighbour groups of plan p.
-static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStream_t s) {
+static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, bool acc16, hipStream_t s) {
   VGroupArgs v{};
+  v.acc16 = acc16 ? 1 : 0;
   v.grp_row = p->grp_row;
   v.goff = p->goff;
   v.moff = p->moff;
@@ -1104,7 +1127,7 @@ static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, hipStr
   a.staging = reinterpret_cast<half_t*>(p->gstage);
   a.stage_ld = p->max_F;
   // halves per lane: 8 unless the process-wide setting asks for a narrower load and the shape allows it
-  int vw = vector_halves();
+  int vw = acc16 ? 8 : vector_halves();
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   if (vw != 8) {
     HGNN_REQUIRE(off32 && a.F <= kWave * vw && a.D % vw == 0, HGNN_EUNSUPPORTED,
@@ -1324,8 +1347,8 @@ hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g,
     return hgnn_spmm_discretized_fused(p, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, nullptr, stream);
   clear_error();
   const char* who = "hgnn_spmm_discretized_variant";
-  HGNN_REQUIRE(variant == HGNN_EDGE_SEGMENTS_ATOMIC || variant == HGNN_VERTEX_GROUPS, HGNN_EINVAL,
-               "%s: unknown variant %d", who, int(variant));
+  HGNN_REQUIRE(variant == HGNN_EDGE_SEGMENTS_ATOMIC || variant == HGNN_VERTEX_GROUPS || variant == HGNN_VERTEX_GROUPS_HALF2,
+               HGNN_EINVAL, "%s: unknown variant %d", who, int(variant));
   hgnn_status st = check_spmm_args(who, g, edge_val, H, X, ldx, Y, ldy, F, op);
   if (st != HGNN_OK) return st;
   HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "%s: plan is NULL", who);
@@ -1334,12 +1357,12 @@ hgnn_status hgnn_spmm_discretized_variant(const hgnn_plan* p, const hgnn_csr* g,
   HGNN_REQUIRE(F <= p->max_F, HGNN_EINVAL, "%s: F = %d exceeds the plan's max_F = %d", who, F, p->max_F);
   HGNN_REQUIRE(vector_path_ok(edge_val, H, X, ldx, Y, ldy, F), HGNN_EUNSUPPORTED,
                "%s: needs F <= 512, ld %% 8 == 0, 16-byte aligned X, Y, and D %% 8 == 0 when edge values have several heads", who);
-  HGNN_REQUIRE(variant != HGNN_VERTEX_GROUPS || p->ng > 0, HGNN_EINVAL,
+  HGNN_REQUIRE(variant == HGNN_EDGE_SEGMENTS_ATOMIC || p->ng > 0, HGNN_EINVAL,
                "%s: the plan holds no neighbour groups (hgnn_plan_add_groups)", who);
   if (g->nrows == 0) return HGNN_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
-  if (variant == HGNN_VERTEX_GROUPS) return run_vgroups(p, a, g->ncols, s);
+  if (variant != HGNN_EDGE_SEGMENTS_ATOMIC) return run_vgroups(p, a, g->ncols, variant == HGNN_VERTEX_GROUPS_HALF2, s);
   a.atomic_y = 1;  // always on the whole graph: column blocks are not used by the comparison variants
   return run_segments(p, a, g->ncols, s);
 }

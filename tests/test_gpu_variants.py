@@ -91,6 +91,44 @@ def test_vertex_groups_shapes(hgnn, dev, F, H, has_w, reduce, ng, pad):
     hgnn.hgnn_plan_destroy(p)
 
 
+@pytest.mark.parametrize("F,H,has_w,reduce,ng", [(64, 1, True, 0, 64), (64, 1, False, 1, 256), (128, 1, True, 0, 128),
+                                                 (32, 4, True, 1, 64), (16, 1, False, 0, 32), (256, 1, True, 0, 512)])
+def test_vertex_groups_half2_arithmetic(hgnn, dev, F, H, has_w, reduce, ng):
+    """The paper's packed-fp16 products and sums (section 4.2) inside a lane's share of a neighbour group.  The result
+    carries fp16 accumulation error: one rounding per term at the magnitude of the lane's running sum, so the floor of
+    the elementwise rule grows by the number of edges a lane adds up (its chunk), and the rel-L2 band is 2e-2."""
+    print(f"vgroups half2 F={F} H={H} w={has_w} reduce={reduce} ng={ng}", flush=True)
+    V, ncols = 1100, 900
+    rowptr, col = rand_graph(V, ncols, 11, F + ng, hubs=((5, 5000), (700, 777)), empties=(0, 6, 1099))
+    E = col.size
+    r = np.random.default_rng(F * 3 + H)
+    Xh = f16(r.standard_normal((ncols, F)))
+    w = f16(r.standard_normal((E, H))) if has_w else None
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, reduce=reduce, want_sabs=True)
+    p = hgnn.hgnn_plan_create(g, 256, max(F, 8), H)
+    hgnn.hgnn_plan_add_groups(p, g, ng)
+    Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    wd = None if w is None else up(w, dev)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, up(Xh, dev), Y, hgnn.HGNN_VERTEX_GROUPS_HALF2, op=reduce)
+    got = down(Y)
+    lanes_per_row = 1
+    while lanes_per_row < (F + 7) // 8:
+        lanes_per_row *= 2
+    chunk = 4 * -(-ng // (4 * (64 // lanes_per_row)))  # edges one lane adds up
+    compare("vertex groups half2", got, ref, sabs * (1 + chunk), rel_l2=2e-2)
+    # and it is not simply the fp32 kernel: some outputs differ in their last bits
+    Y2 = torch.empty_like(Y)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, up(Xh, dev), Y2, hgnn.HGNN_VERTEX_GROUPS, op=reduce)
+    assert not np.array_equal(down(Y2).view(np.uint16), got.view(np.uint16))
+    compare("vertex groups fp32", down(Y2), ref, sabs)
+    # deterministic
+    Y3 = torch.empty_like(Y)
+    hgnn.hgnn_spmm_discretized_variant(p, g, wd, H, up(Xh, dev), Y3, hgnn.HGNN_VERTEX_GROUPS_HALF2, op=reduce)
+    assert np.array_equal(down(Y3).view(np.uint16), got.view(np.uint16))
+    hgnn.hgnn_plan_destroy(p)
+
+
 @pytest.mark.parametrize("F,H,has_w,reduce,S", [(64, 1, True, 0, 256), (128, 1, False, 1, 128), (64, 4, True, 1, 64),
                                                 (32, 1, True, 0, 7)])
 def test_atomic_variant_shapes(hgnn, dev, F, H, has_w, reduce, S):
