@@ -3,6 +3,8 @@ header declares, and rejects bad arguments on the host before anything is launch
 import ctypes
 import os
 import re
+import subprocess
+import tempfile
 
 import pytest
 
@@ -116,6 +118,38 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_set_vector_halves(3) == EINVAL
     assert lib.hgnn_set_vector_halves(2) == hgnn.HGNN_OK and lib.hgnn_get_vector_halves() == 2
     assert lib.hgnn_set_vector_halves(keep) == hgnn.HGNN_OK
+
+
+def test_header_is_plain_c_and_links(lib):
+    """include/hgnn.h compiles as strict C99 (and as C++), and a C program that calls the library through it links
+    against libhgnn.so and runs the host-only calls (no GPU needed for status strings and argument errors)."""
+    src = r"""
+#include <stdio.h>
+#include <string.h>
+#include "hgnn.h"
+int main(void) {
+  hgnn_csr g;
+  memset(&g, 0, sizeof g);
+  if (strncmp(hgnn_status_str(HGNN_EINVAL), "HGNN_", 5) != 0) return 1;
+  if (hgnn_spmm(NULL, NULL, 1, NULL, 8, NULL, 8, 8, HGNN_SUM, NULL, NULL) != HGNN_EINVAL) return 2;
+  if (hgnn_last_error()[0] == 0) return 3;
+  if (hgnn_linear_wgrad_workspace(64, 64) == 0) return 4;
+  if (hgnn_plan_num_segments(NULL) != 0) return 5;
+  puts("ok");
+  return 0;
+}
+"""
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.join(ROOT, "paper_2411_01109_amd")
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "t.c")
+        open(c, "w").write(src)
+        subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", c, "-o", os.path.join(d, "t.o")])
+        subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-I", inc, "-x", "c++", "-c", c, "-o", os.path.join(d, "t2.o")])
+        exe = os.path.join(d, "t")
+        subprocess.check_call(["gcc", os.path.join(d, "t.o"), "-o", exe, "-L", libdir, "-lhgnn", "-Wl,-rpath," + libdir])
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        assert out.returncode == 0 and out.stdout.strip() == "ok", (out.returncode, out.stdout, out.stderr)
 
 
 def test_binding_refuses_cpu_tensors(hgnn):
