@@ -147,25 +147,34 @@ def main():
     # the next-step fusions, measured beside the path: degree norms / GIN epilogue inside the discretized SpMM
     deg_r = torch.clamp(g.rowptr[1:] - g.rowptr[:-1], min=1).to(torch.float32)
     deg_c = torch.clamp(gt.rowptr[1:] - gt.rowptr[:-1], min=1).to(torch.float32)
-    fused_name = f"hgnn::spmm_seg_kernel<{Lg}, 2, {off32}>"
+    # a column-side scale is applied to the table once (scaled_x workspace: one V x F pass, then no per-edge factor)
+    # where rows are long enough for that to pay, else fetched per edge inside the kernel
+    Xs_buf = torch.empty_like(X)
+    use_ws = E / V >= 24
+    ws = Xs_buf if use_ws else None
+    fused_name = seg_name(0) if use_ws else f"hgnn::spmm_seg_kernel<{Lg}, 2, {off32}>"
+    cs_min = 4 * V                                        # compulsory: the scale vector, read once
+    cs_req = (4 * V + 4 * V * F) if use_ws else 4 * E     # what is asked for: table written and re-read, or a factor per edge
     if args.workload in ("c2", "c5"):  # GIN, half-precision form: (1+eps) x + lambda * mean, forward and backward
         lam_over_deg = (0.1 / deg_r).contiguous()
         b = spmm_min(0, False) + 2 * V * F
         ops.append(("gin_fused_fwd", seg_name(0), b,
                     lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, op=hgnn.HGNN_MEAN, self_feat=X,
                                                              self_coef=1.0, agg_coef=0.1), spmm_req(0, False) + 2 * V * F))
-        ops.append(("gin_fused_bwd", fused_name, b + 4 * V + 4 * E,
+        ops.append(("gin_fused_bwd", fused_name, b + cs_min,
                     lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, col_scale=lam_over_deg,
-                                                             self_feat=dY, self_coef=1.0), spmm_req(0, True) + 2 * V * F + 4 * E))
+                                                             self_feat=dY, self_coef=1.0, scaled_x=ws),
+                    spmm_req(0, True) + 2 * V * F + cs_req))
     else:  # GCN "both" norm from degree vectors instead of per-edge values
         rs_f, cs_f = deg_r.rsqrt().contiguous(), deg_c.rsqrt().contiguous()
         b = spmm_min(0, False) + 8 * V
-        ops.append(("gcn_norm_fused_fwd", fused_name, b + 4 * E,
-                    lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, row_scale=rs_f, col_scale=cs_f),
-                    spmm_req(0, False) + 8 * V + 4 * E))
-        ops.append(("gcn_norm_fused_bwd", fused_name, b + 4 * E,
-                    lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, row_scale=cs_f, col_scale=rs_f),
-                    spmm_req(0, True) + 8 * V + 4 * E))
+        ops.append(("gcn_norm_fused_fwd", fused_name, b + cs_min,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, row_scale=rs_f, col_scale=cs_f, scaled_x=ws),
+                    spmm_req(0, False) + 8 * V + cs_req))
+        ops.append(("gcn_norm_fused_bwd", fused_name, b + cs_min,
+                    lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, row_scale=cs_f, col_scale=rs_f,
+                                                             scaled_x=ws),
+                    spmm_req(0, True) + 8 * V + cs_req))
     if has_gat:
         EH = E * H
         b = E * 4 + 4 * (V + 1) + 2 * V * F + 2 * EH
@@ -294,21 +303,20 @@ def main():
     layer_ms["spmm_fwd_bwd_disc_ms"] = round(float(op_avg[2] + op_avg[3]), 4)
     layer_ms["spmm_fwd_bwd_plain_ms"] = round(float(op_avg[0] + op_avg[1]), 4)
 
-    # the column-side norm applied to the table first (one V x F pass), then the SpMM without a per-edge factor:
-    # what the fused col_scale costs against this is the reason to pre-scale the table on long rows
-    Xs_buf = torch.empty_like(X)
+    # the column-side scale both ways, whatever the step uses: fetched per edge inside the kernel, and applied to the
+    # table first (scaled_x workspace)
     if args.workload in ("c2", "c5"):
-        def prescaled_bwd():
-            hgnn.hgnn_scale_rows(dY, lam_over_deg, Xs_buf)
-            hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, Xs_buf, Y, self_feat=dY, self_coef=1.0)
-        prescaled = {"gin_bwd_prescaled_ms": round(time_call(prescaled_bwd), 4),
-                     "gin_fused_bwd_ms": round(float(op_avg[[o[0] for o in ops].index("gin_fused_bwd")]), 4)}
+        name = "gin_fused_bwd"
+        per_edge = lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, col_scale=lam_over_deg, self_feat=dY,
+                                                            self_coef=1.0)
+        on_table = lambda: hgnn.hgnn_spmm_discretized_fused(plan_t, gt, None, 1, dY, Y, col_scale=lam_over_deg, self_feat=dY,
+                                                            self_coef=1.0, scaled_x=Xs_buf)
     else:
-        def prescaled_fwd():
-            hgnn.hgnn_scale_rows(X, cs_f, Xs_buf)
-            hgnn.hgnn_spmm_discretized(plan, g, None, 1, Xs_buf, Y, row_scale=rs_f)
-        prescaled = {"gcn_norm_prescaled_fwd_ms": round(time_call(prescaled_fwd), 4),
-                     "gcn_norm_fused_fwd_ms": round(float(op_avg[[o[0] for o in ops].index("gcn_norm_fused_fwd")]), 4)}
+        name = "gcn_norm_fused_fwd"
+        per_edge = lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, row_scale=rs_f, col_scale=cs_f)
+        on_table = lambda: hgnn.hgnn_spmm_discretized_fused(plan, g, None, 1, X, Y, row_scale=rs_f, col_scale=cs_f, scaled_x=Xs_buf)
+    prescaled = {"op": name, "step_uses": "scaled_x workspace" if use_ws else "per-edge factor",
+                 "per_edge_factor_ms": round(time_call(per_edge), 4), "scaled_table_ms": round(time_call(on_table), 4)}
 
     graph_info = None
     if args.graph:

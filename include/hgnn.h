@@ -186,13 +186,21 @@ hgnn_status hgnn_spmm_discretized(const hgnn_plan* p, const hgnn_csr* g, const h
  * deg^-1/2 of the rows, col_scale = deg^-1/2 of the columns, no edge values.  GIN:
  * self = X, self_coef = 1 + eps, agg_coef = 1 (Eq. 3) or lambda with reduce = MEAN
  * (the overflow-safe form, lambda = 0.1 in the paper).  Empty rows get the self term
- * alone.  A NULL pointer or fz == NULL drops that part (agg_coef must then be 1). */
+ * alone.  A NULL pointer or fz == NULL drops that part (agg_coef must then be 1).
+ * scaled_x is an optional workspace for the column scale: when it and col_scale are given, the call
+ * first writes fp16(col_scale[j] * X[j,f]) into it (one pass over the table) and then gathers from
+ * it without a per-edge factor.  A per-edge factor fetched from another table costs a third cache
+ * request per non-zero beside the two of a 128-byte feature row; the workspace form costs one pass
+ * over ncols x F halves and one more fp16 rounding per table element (within the tolerance of the
+ * plain call).  The caller owns the workspace; it is overwritten. */
 typedef struct {
   const float* col_scale; /* [ncols] fp32 or NULL */
   const hgnn_half* self;  /* [nrows][ld_self] fp16 or NULL; ld_self >= F, ld_self % 8 == 0, 16-byte aligned */
   int64_t ld_self;
   float self_coef;
   float agg_coef;
+  hgnn_half* scaled_x;    /* [ncols][ld_scaled] fp16 workspace or NULL; ld_scaled >= F, % 8 == 0, 16-byte aligned */
+  int64_t ld_scaled;
 } hgnn_spmm_fusion;
 
 hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,

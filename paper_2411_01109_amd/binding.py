@@ -42,7 +42,8 @@ class HgnnError(RuntimeError):
 
 class _FusionStruct(ctypes.Structure):
     _fields_ = [("col_scale", ctypes.c_void_p), ("self", ctypes.c_void_p), ("ld_self", ctypes.c_int64),
-                ("self_coef", ctypes.c_float), ("agg_coef", ctypes.c_float)]
+                ("self_coef", ctypes.c_float), ("agg_coef", ctypes.c_float), ("scaled_x", ctypes.c_void_p),
+                ("ld_scaled", ctypes.c_int64)]
 
 
 class _CsrStruct(ctypes.Structure):
@@ -276,10 +277,12 @@ def hgnn_spmm_discretized(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: 
 def hgnn_spmm_discretized_fused(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor,
                                 Y: torch.Tensor, op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None,
                                 col_scale: Optional[torch.Tensor] = None, self_feat: Optional[torch.Tensor] = None,
-                                self_coef: float = 0.0, agg_coef: float = 1.0, F: Optional[int] = None, stream=None) -> None:
+                                self_coef: float = 0.0, agg_coef: float = 1.0, F: Optional[int] = None,
+                                scaled_x: Optional[torch.Tensor] = None, stream=None) -> None:
     F = X.shape[1] if F is None else F
     fz = _FusionStruct(_ptr(col_scale, torch.float32), _ptr(self_feat, torch.float16),
-                       0 if self_feat is None else _ld(self_feat), self_coef, agg_coef)
+                       0 if self_feat is None else _ld(self_feat), self_coef, agg_coef, _ptr(scaled_x, torch.float16),
+                       0 if scaled_x is None else _ld(scaled_x))
     _check(load().hgnn_spmm_discretized_fused(p.handle, g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16),
                                               _ld(X), _ptr(Y, torch.float16), _ld(Y), F, op,
                                               _ptr(row_scale, torch.float32), ctypes.byref(fz), _stream(stream)))

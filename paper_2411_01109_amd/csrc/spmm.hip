@@ -1293,11 +1293,22 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
   if (fz && fz->self)
     HGNN_REQUIRE(fz->ld_self >= F && fz->ld_self % 8 == 0 && aligned16(fz->self), HGNN_EINVAL,
                  "%s: self features need ld_self >= F, ld_self %% 8 == 0 and a 16-byte aligned base", who);
+  const bool prescale = fz && fz->col_scale && fz->scaled_x;
+  if (prescale)
+    HGNN_REQUIRE(fz->ld_scaled >= F && fz->ld_scaled % 8 == 0 && aligned16(fz->scaled_x), HGNN_EINVAL,
+                 "%s: the scaled_x workspace needs ld_scaled >= F, ld_scaled %% 8 == 0 and a 16-byte aligned base", who);
   if (g->nrows == 0) return HGNN_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
+  if (prescale) {
+    // the column scale goes onto the table once; the kernels then run without a per-edge factor
+    st = hgnn_scale_rows(g->ncols, F, X, ldx, fz->col_scale, fz->scaled_x, fz->ld_scaled, stream);
+    if (st != HGNN_OK) return st;
+    a.X = reinterpret_cast<const half_t*>(fz->scaled_x);
+    a.ldx = fz->ld_scaled;
+  }
   if (fz) {
-    a.col_scale = fz->col_scale;
+    a.col_scale = prescale ? nullptr : fz->col_scale;
     a.self = reinterpret_cast<const half_t*>(fz->self);
     a.ld_self = fz->ld_self;
     a.self_coef = fz->self_coef;

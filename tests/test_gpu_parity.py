@@ -539,6 +539,26 @@ def test_spmm_fused_gcn_norm_and_gin_epilogue(hgnn, dev, F, nb, S):
     ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, reduce=1, row_scale=rs.astype(np.float64), col_scale=cs.astype(np.float64),
                             self_feat=Xh, self_coef=-0.5, agg_coef=2.0, want_sabs=True)
     compare("all fused", down(Y), ref, sabs)
+    # the same two with the column scale applied to the table once (scaled_x workspace, padded pitch): one more fp16
+    # rounding per table element, still inside the rule; X itself is not touched
+    ws_buf = torch.full((V, F + 8), 7.0, dtype=torch.float16, device=dev)
+    ws = ws_buf[:, :F]
+    Y.fill_(3.0)
+    hgnn.hgnn_spmm_discretized_fused(p, g, up(w, dev), H, Xd, Y, op=1, row_scale=up(rs, dev), col_scale=up(cs, dev),
+                                     self_feat=Xd, self_coef=-0.5, agg_coef=2.0, scaled_x=ws)
+    compare("all fused, pre-scaled table", down(Y), ref, sabs)
+    assert np.array_equal(down(Xd).view(np.uint16), Xh.view(np.uint16))
+    want_ws = (cs.astype(np.float32)[:, None] * Xh.astype(np.float32)).astype(np.float16)
+    assert np.array_equal(down(ws_buf)[:, :F].view(np.uint16), want_ws.view(np.uint16)) and np.all(down(ws_buf)[:, F:] == 7.0)
+    Y.fill_(3.0)
+    hgnn.hgnn_spmm_discretized_fused(p, g, None, 1, Xd, Y, row_scale=up(dr.astype(np.float32), dev),
+                                     col_scale=up(dc.astype(np.float32), dev), scaled_x=ws)
+    ref_n, sabs_n = oracle.spmm(rowptr, col, Xh, row_scale=dr.astype(np.float32).astype(np.float64),
+                                col_scale=dc.astype(np.float32).astype(np.float64), want_sabs=True)
+    compare("gcn both norm, pre-scaled table", down(Y), ref_n, sabs_n)
+    with pytest.raises(hgnn.HgnnError) as err:
+        hgnn.hgnn_spmm_discretized_fused(p, g, None, 1, Xd, Y, col_scale=up(dc.astype(np.float32), dev), scaled_x=ws_buf[:, 1:F + 1])
+    assert err.value.status == hgnn.HGNN_EINVAL and "scaled_x" in str(err.value)
     # the plain entry point is the fused one without fusion
     Y2 = torch.empty_like(Y)
     hgnn.hgnn_spmm_discretized(p, g, up(w, dev), H, Xd, Y)
