@@ -172,7 +172,7 @@ __device__ __forceinline__ void stage_store(const GatArgs& a, int64_t slot, int 
 struct GatLds {
   int per, spad, col_off, row_off, blk_off, sc_off, vec_off, mz_off, flag_off, total;
 };
-__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save) {
+__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save, bool fly) {
   GatLds o;
   const int G = kWave / L;
   const int nv = save ? 2 : 1, ns = save ? 3 : 2;  // vectors and scalars of a parked piece
@@ -182,7 +182,7 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save)
   o.row_off = o.col_off + o.spad * 4;
   o.blk_off = o.row_off + o.spad * 4;
   o.sc_off = o.blk_off + ((o.spad + 15) & ~15);
-  o.vec_off = o.sc_off + o.spad * H * 4;
+  o.vec_off = o.sc_off + (fly ? 0 : o.spad * H * 4);  // FLY keeps the row-side term in a register instead
   o.mz_off = o.vec_off + G * nv * 8 * L * 4;  // one parked piece per lane group: the one that entered its chunk
   o.flag_off = o.mz_off + G * L * ns * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
@@ -207,12 +207,12 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int head = f0c / a.D;
   const bool leader = active && (f0 % a.D) == 0;  // the lane that writes its head's scalars
   const int S = a.S;
-  const GatLds lay = gat_lds_layout(S, a.H, L, SAVE);
+  const GatLds lay = gat_lds_layout(S, a.H, L, SAVE, FLY);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
-  float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU
+  float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU (not FLY)
   // The piece that entered a group's chunk is parked in LDS when its row ends; the piece that leaves the chunk stays
   // in the group's registers and the merge reads it from there (cross-lane reads take no LDS allocation, and the
   // kernel's speed follows the number of waves that fit a compute unit).
@@ -238,27 +238,29 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
   }
 
-  // ---- phase 1: column ids, row ids, and per (edge, head) the row-side score term el[row] (FLY) or the
-  // finished score LeakyReLU(el[row] + er[col])
-  for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
+  // ---- phase 1: column ids, row ids, and (not FLY) per (edge, head) the finished score
+  // LeakyReLU(el[row] + er[col])
+  for (int i = lane; i < spad; i += kWave) {
+    const int c = i < n ? a.col[e0 + i] : 0;
+    s_col[i] = OFF32 && FLY ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;
+  }
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
-  for (int i = lane; i < spad; i += kWave) {
-    const bool in = i < n;
-    const int c = s_col[i];
-    const int r = in ? s_row[i] : 0;
-    for (int h = 0; h < a.H; ++h) {
-      float s = FLY ? 0.f : -INFINITY;  // padding (never read by FLY; weight exp(-inf - m) = 0 otherwise)
-      if (in) {
-        s = a.el[int64_t(r) * a.H + h];
-        if (!FLY) {
-          s += a.er[int64_t(c) * a.H + h];
+  if (!FLY) {
+    for (int i = lane; i < spad; i += kWave) {
+      const bool in = i < n;
+      const int c = s_col[i];
+      const int r = in ? s_row[i] : 0;
+      for (int h = 0; h < a.H; ++h) {
+        float s = -INFINITY;  // padding: weight exp(-inf - m) = 0
+        if (in) {
+          s = a.el[int64_t(r) * a.H + h] + a.er[int64_t(c) * a.H + h];
           s = s > 0.f ? s : a.slope * s;
         }
+        s_sc[i * a.H + h] = s;
       }
-      s_sc[i * a.H + h] = s;
+      if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);  // from here on: byte offset of the neighbour's row
     }
-    if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);  // from here on: byte offset of the neighbour's row
   }
   wave_sync();
 
@@ -320,9 +322,11 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
   };
 
+  float el_cur = 0.f;  // FLY: the row-side score term of the current row, fetched when the row changes
   if (c0 < c1) {
     cur = s_row[c0];
     lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
+    if (FLY) el_cur = a.el[int64_t(cur) * a.H + head];
   }
   const int LH = a.D / 8;  // lanes per head (power of two)
   typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -357,16 +361,18 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
         sc[u] = d;
       }
       head_sum4(sc, LH);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float t = sc[u] + s_sc[(i + u) * a.H + head];
-        sc[u] = t > 0.f ? t : a.slope * t;
-      }
     } else {
 #pragma unroll
       for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
     }
     if (blk == cur) {  // four more edges of the current row: one rescale, four terms
+      if (FLY) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float v = sc[u] + el_cur;
+          sc[u] = v > 0.f ? v : a.slope * v;
+        }
+      }
       const float mn = fmaxf(fmaxf(t.m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
       t.scale(__expf(t.m - mn));
 #pragma unroll
@@ -382,6 +388,11 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
             t.clear();
             cur = rows[u];
             lo = false;
+            if (FLY) el_cur = a.el[int64_t(cur) * a.H + head];
+          }
+          if (FLY) {
+            const float v = sc[u] + el_cur;
+            sc[u] = v > 0.f ? v : a.slope * v;
           }
           const float mn = fmaxf(t.m, sc[u]);
           t.scale(__expf(t.m - mn));
@@ -626,7 +637,7 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L, save).total);
+  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L, save, a.a_r != nullptr).total);
   const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
