@@ -48,7 +48,8 @@ struct GatBwdArgs {
 struct GatBwdLds {
   int per, spad, col_off, row_off, blk_off, a_off, t_off, vec_off, ds_off, flag_off, total;
 };
-__host__ __device__ inline GatBwdLds gat_bwd_lds_layout(int S, int H, int L, bool vec) {
+// fly: no per (edge, head) tables; a copy of the raw column ids instead where s_col holds byte offsets (off32)
+__host__ __device__ inline GatBwdLds gat_bwd_lds_layout(int S, int H, int L, bool vec, bool fly, bool off32) {
   GatBwdLds o;
   const int G = kWave / L;
   o.per = 4 * ((S + 255) / 256);
@@ -57,8 +58,8 @@ __host__ __device__ inline GatBwdLds gat_bwd_lds_layout(int S, int H, int L, boo
   o.row_off = o.col_off + o.spad * 4;
   o.blk_off = o.row_off + o.spad * 4;
   o.a_off = o.blk_off + ((o.spad + 15) & ~15);
-  o.t_off = o.a_off + o.spad * H * 4;
-  o.vec_off = o.t_off + o.spad * H * 4;
+  o.t_off = o.a_off + (fly ? (off32 ? o.spad * 4 : 0) : o.spad * H * 4);
+  o.vec_off = o.t_off + (fly ? 0 : o.spad * H * 4);
   o.ds_off = o.vec_off + (vec ? G * 8 * L * 4 : 0);  // one parked piece per lane group: the one that entered its chunk
   o.flag_off = o.ds_off + G * L * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
@@ -93,7 +94,12 @@ __device__ __forceinline__ void bwd_stage_store(const GatBwdArgs& a, int64_t slo
   if (leader) a.stage_ds[(slot * a.H + head) * 2] = ds;
 }
 
-template <int L, bool OFF32, bool VEC>
+// VEC = true is the pass over the transposed graph (the destination vertex of a non-zero is its column).
+// FLY = true: the weight of an edge is formed in the main loop from the destination's packed scalars and the
+// source's er, one of them gathered per edge and the other fetched when the row changes; no per-edge tables in
+// LDS, so more waves fit a compute unit (wins with several heads, where the tables are large and a head's
+// lanes repeat little of the scalar work).  FLY = false: formed once per (edge, head) while the segment is staged.
+template <int L, bool OFF32, bool VEC, bool FLY>
 __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwdArgs a) {
   constexpr int G = kWave / L;
   constexpr int VECF = 8 * L;
@@ -107,12 +113,13 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
   const bool leader = active && (f0 % a.D) == 0;
   const int LH = a.D / 8;
   const int S = a.S;
-  const GatBwdLds lay = gat_bwd_lds_layout(S, a.H, L, VEC);
+  const GatBwdLds lay = gat_bwd_lds_layout(S, a.H, L, VEC, FLY, OFF32);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   float* s_a = reinterpret_cast<float*>(base + lay.a_off);    // [spad][H]: alpha, negated where the score is <= 0
+  int* s_raw = OFF32 ? reinterpret_cast<int*>(base + lay.a_off) : s_col;  // FLY: [spad] column ids (s_a's place)
   float* s_t = reinterpret_cast<float*>(base + lay.t_off);    // [spad][H]: alpha * mask * t of the destination vertex
   // the piece that entered a group's chunk is parked here when its row ends; the piece that leaves the chunk stays
   // in the group's registers, from where the merge reads it (no LDS allocation: more waves per compute unit)
@@ -140,27 +147,37 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
 
   // ---- phase 1: column ids, row ids, then per (edge, head) the attention weight with the LeakyReLU branch in
   // its sign, and u = alpha * mask * t of the destination vertex
-  for (int i = lane; i < spad; i += kWave) s_col[i] = i < n ? a.col[e0 + i] : 0;
+  for (int i = lane; i < spad; i += kWave) {
+    const int c = i < n ? a.col[e0 + i] : 0;
+    if (FLY && OFF32) {
+      s_raw[i] = c;
+      s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
+    } else {
+      s_col[i] = c;
+    }
+  }
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
-  for (int i = lane; i < spad; i += kWave) {
-    const bool in = i < n;
-    const int c = s_col[i];
-    const int r = in ? s_row[i] : 0;
-    const int64_t dst = a.dst_is_col ? c : r, src = a.dst_is_col ? r : c;
-    for (int h = 0; h < a.H; ++h) {
-      float av = 0.f, uv = 0.f;
-      if (in) {
-        const float4 v = a.vtab[dst * a.H + h];
-        const float sc = v.x + a.er[src * a.H + h];
-        const float alpha = __expf((sc > 0.f ? sc : a.slope * sc) - v.y);
-        av = sc > 0.f ? alpha : -alpha;
-        uv = (sc > 0.f ? alpha : a.slope * alpha) * v.z;
+  if (!FLY) {
+    for (int i = lane; i < spad; i += kWave) {
+      const bool in = i < n;
+      const int c = s_col[i];
+      const int r = in ? s_row[i] : 0;
+      const int64_t dst = a.dst_is_col ? c : r, src = a.dst_is_col ? r : c;
+      for (int h = 0; h < a.H; ++h) {
+        float av = 0.f, uv = 0.f;
+        if (in) {
+          const float4 v = a.vtab[dst * a.H + h];
+          const float sc = v.x + a.er[src * a.H + h];
+          const float alpha = __expf((sc > 0.f ? sc : a.slope * sc) - v.y);
+          av = sc > 0.f ? alpha : -alpha;
+          uv = (sc > 0.f ? alpha : a.slope * alpha) * v.z;
+        }
+        s_a[i * a.H + h] = av;
+        s_t[i * a.H + h] = uv;
       }
-      s_a[i * a.H + h] = av;
-      s_t[i * a.H + h] = uv;
+      if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
     }
-    if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
   }
   wave_sync();
 
@@ -179,7 +196,15 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
   bool lo = false;
   float leave_ds = 0.f;     // ds sum of the piece that leaves this chunk (its vector stays in acc)
   half8_t ur = half8_t(0);  // this lane's slice of the current row's row-side vector
-  auto load_row_vec = [&](int r) { ur = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c); };
+  float4 v_row = make_float4(0.f, 0.f, 0.f, 0.f);  // FLY, pass over the graph: the row's (el, lse, t)
+  float er_row = 0.f;                              // FLY, transposed pass: the row's er
+  auto load_row_vec = [&](int r) {
+    ur = *reinterpret_cast<const half8_t*>(a.R + int64_t(r) * a.ldr + f0c);
+    if (FLY) {
+      if (VEC) er_row = a.er[int64_t(r) * a.H + head];
+      else v_row = a.vtab[int64_t(r) * a.H + head];
+    }
+  };
   auto flush = [&](bool ro) {
     float d = 0.f;
     if (active) {
@@ -215,10 +240,19 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
     }
     return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
   };
-  auto add_edge = [&](float av, float uv, const half8_t& x) {
-    const float alpha = fabsf(av);
-    const float am = av > 0.f ? av : -a.slope * av;
-    csum += uv;
+  // FLY: av = the destination's el, uv = the source's er, lse and t beside them; else the staged pair
+  auto add_edge = [&](float av, float uv, float lse, float tt, const half8_t& x) {
+    float alpha, am;
+    if (FLY) {
+      const float sc = av + uv;
+      alpha = __expf((sc > 0.f ? sc : a.slope * sc) - lse);
+      am = sc > 0.f ? alpha : a.slope * alpha;
+      csum = fmaf(am, tt, csum);
+    } else {
+      alpha = fabsf(av);
+      am = av > 0.f ? av : -a.slope * av;
+      csum += uv;
+    }
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const float xf = float(x[q]);
@@ -238,15 +272,37 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
     half8_t x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
-    float av[4], uv[4];
+    float av[4], uv[4], ls[4], tt[4];
+    if (FLY) {
+      const int4_t raw = OFF32 ? *reinterpret_cast<const int4_t*>(s_raw + i) : cols;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      av[u] = s_a[(i + u) * a.H + head];
-      uv[u] = s_t[(i + u) * a.H + head];
+      for (int u = 0; u < 4; ++u) {
+        if (VEC) {
+          const float4 v = a.vtab[int64_t(raw[u]) * a.H + head];
+          av[u] = v.x;
+          ls[u] = v.y;
+          tt[u] = v.z;
+        } else {
+          uv[u] = a.er[int64_t(raw[u]) * a.H + head];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        av[u] = s_a[(i + u) * a.H + head];
+        uv[u] = s_t[(i + u) * a.H + head];
+        ls[u] = tt[u] = 0.f;
+      }
     }
+    // the row-side half of a FLY edge is read when the edge is added: the row may have changed by then
+    auto add = [&](int u) {
+      if (FLY && VEC) add_edge(av[u], er_row, ls[u], tt[u], x[u]);
+      else if (FLY) add_edge(v_row.x, uv[u], v_row.y, v_row.z, x[u]);
+      else add_edge(av[u], uv[u], 0.f, 0.f, x[u]);
+    };
     if (blk == cur) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) add_edge(av[u], uv[u], x[u]);
+      for (int u = 0; u < 4; ++u) add(u);
     } else {
       const int4_t rows = *reinterpret_cast<const int4_t*>(s_row + i);
 #pragma unroll
@@ -264,7 +320,7 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
             lo = false;
             load_row_vec(cur);
           }
-          add_edge(av[u], uv[u], x[u]);
+          add(u);
         }
       }
     }
@@ -453,16 +509,16 @@ __global__ __launch_bounds__(kBlock) void gat_vtab_kernel(const float* __restric
   }
 }
 
-template <bool OFF32, bool VEC>
+template <bool OFF32, bool VEC, bool FLY>
 static void launch_bwd_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const GatBwdArgs& a) {
   switch (L) {
-    case 1: gat_bwd_seg_kernel<1, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    case 2: gat_bwd_seg_kernel<2, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    case 4: gat_bwd_seg_kernel<4, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    case 8: gat_bwd_seg_kernel<8, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    case 16: gat_bwd_seg_kernel<16, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    case 32: gat_bwd_seg_kernel<32, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
-    default: gat_bwd_seg_kernel<64, OFF32, VEC><<<grid, threads, lds, s>>>(a); break;
+    case 1: gat_bwd_seg_kernel<1, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 2: gat_bwd_seg_kernel<2, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 4: gat_bwd_seg_kernel<4, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 8: gat_bwd_seg_kernel<8, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 16: gat_bwd_seg_kernel<16, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    case 32: gat_bwd_seg_kernel<32, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
+    default: gat_bwd_seg_kernel<64, OFF32, VEC, FLY><<<grid, threads, lds, s>>>(a); break;
   }
 }
 
@@ -531,7 +587,11 @@ static hgnn_status run_bwd_segments(const hgnn_plan* q, GatBwdArgs a, int ncols,
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const size_t per_wave = size_t(gat_bwd_lds_layout(a.S, a.H, L, VEC).total);
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  // weights formed in the main loop: measured 0.26 -> 0.17 ms for the transposed pass with 4 heads of 16 (12 -> 20
+  // waves per compute unit), a tie with one head of 64
+  const bool fly = a.H >= 2;
+  const size_t per_wave = size_t(gat_bwd_lds_layout(a.S, a.H, L, VEC, fly, off32).total);
   const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
@@ -539,9 +599,13 @@ static hgnn_status run_bwd_segments(const hgnn_plan* q, GatBwdArgs a, int ncols,
                a.H, lds);
   const int64_t nblk = ceil_div(q->nseg, wpb);
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
-  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
-  if (off32) launch_bwd_seg<true, VEC>(L, grid, wpb * kWave, lds, s, a);
-  else launch_bwd_seg<false, VEC>(L, grid, wpb * kWave, lds, s, a);
+  if (fly) {
+    if (off32) launch_bwd_seg<true, VEC, true>(L, grid, wpb * kWave, lds, s, a);
+    else launch_bwd_seg<false, VEC, true>(L, grid, wpb * kWave, lds, s, a);
+  } else {
+    if (off32) launch_bwd_seg<true, VEC, false>(L, grid, wpb * kWave, lds, s, a);
+    else launch_bwd_seg<false, VEC, false>(L, grid, wpb * kWave, lds, s, a);
+  }
   HGNN_LAUNCH_CHECK("gat_bwd_seg_kernel");
   if (a.n_split > 0) {
     launch_bwd_finish<VEC>(L, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);

@@ -352,29 +352,32 @@ def test_feature_table_beyond_4gib(hgnn, dev):
     hgnn.hgnn_plan_add_groups(p, g, 64)
     hgnn.hgnn_spmm_discretized_variant(p, g, up(w, dev), 1, X, Y, hgnn.HGNN_VERTEX_GROUPS, op=hgnn.HGNN_MEAN)
     compare("vertex groups, 64-bit rows", down(Y), ref, sabs)
-    # fused GAT forward with the big table on the column side
+    # fused GAT with the big table on the column side: one head (staged scores) and four (scores formed in the
+    # main loop); the backward's forward-graph pass gathers rows of the big table too
     U = f16(r.standard_normal((V, F)))
     a_l, a_r = f16(0.2 * r.standard_normal(F)), f16(0.2 * r.standard_normal(F))
-    gref, gl, gabs = oracle.gat_forward(rowptr, col_small, U, Xs, a_l, a_r, H)
-    lse = torch.empty((V, H), dtype=torch.float32, device=dev)
-    hgnn.hgnn_gat_forward_fused(g, p, H, F, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse)
-    compare("gat fused, 64-bit rows", down(Y), gref, gabs)
-    # fused GAT backward: its forward-graph pass gathers rows of the big table
     dOut = f16(r.standard_normal((V, F)))
     gt = hgnn.hgnn_transpose(g)
-    pt = hgnn.hgnn_plan_create(gt, 256, F, H)
-    dV = torch.zeros((ncols, F), dtype=torch.float16, device=dev)
-    d_el = torch.empty((V, H), dtype=torch.float16, device=dev)
-    d_er = torch.empty((ncols, H), dtype=torch.float16, device=dev)
-    hgnn.hgnn_gat_backward_fused(g, p, gt, pt, H, F, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse, up(dOut, dev), dV,
-                                 d_el, d_er)
-    bV, b_el, b_er = oracle.gat_backward(rowptr, col_small, U, Xs, a_l, a_r, dOut, H)
     pick_d = torch.from_numpy(pick).to(dev)
-    scale = np.abs(bV).max()
-    assert np.max(np.abs(down(dV[pick_d]).astype(np.float64) - bV)) <= 2e-2 * scale
-    assert np.max(np.abs(down(d_er[pick_d]).astype(np.float64) - b_er)) <= 2e-2 * max(np.abs(b_er).max(), 1e-3)
-    assert np.max(np.abs(down(d_el).astype(np.float64) - b_el)) <= 2e-2 * max(np.abs(b_el).max(), 1e-3)
-    hgnn.hgnn_plan_destroy(pt)
+    for Hg in (1, 4):
+        pg = hgnn.hgnn_plan_create(g, 256, F, Hg)
+        pt = hgnn.hgnn_plan_create(gt, 256, F, Hg)
+        gref, gl, gabs = oracle.gat_forward(rowptr, col_small, U, Xs, a_l, a_r, Hg)
+        lse = torch.empty((V, Hg), dtype=torch.float32, device=dev)
+        hgnn.hgnn_gat_forward_fused(g, pg, Hg, F // Hg, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse)
+        compare(f"gat fused, 64-bit rows, H={Hg}", down(Y), gref, gabs)
+        dV = torch.zeros((ncols, F), dtype=torch.float16, device=dev)
+        d_el = torch.empty((V, Hg), dtype=torch.float16, device=dev)
+        d_er = torch.empty((ncols, Hg), dtype=torch.float16, device=dev)
+        hgnn.hgnn_gat_backward_fused(g, pg, gt, pt, Hg, F // Hg, up(U, dev), X, up(a_l, dev), up(a_r, dev), Y, lse,
+                                     up(dOut, dev), dV, d_el, d_er)
+        bV, b_el, b_er = oracle.gat_backward(rowptr, col_small, U, Xs, a_l, a_r, dOut, Hg)
+        scale = np.abs(bV).max()
+        assert np.max(np.abs(down(dV[pick_d]).astype(np.float64) - bV)) <= 2e-2 * scale
+        assert np.max(np.abs(down(d_er[pick_d]).astype(np.float64) - b_er)) <= 2e-2 * max(np.abs(b_er).max(), 1e-3)
+        assert np.max(np.abs(down(d_el).astype(np.float64) - b_el)) <= 2e-2 * max(np.abs(b_el).max(), 1e-3)
+        hgnn.hgnn_plan_destroy(pt)
+        hgnn.hgnn_plan_destroy(pg)
     # SDDMM dot against the big table
     e = torch.empty((col.size, 1), dtype=torch.float16, device=dev)
     hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, 1, F, up(U, dev), X, e)
