@@ -6,7 +6,8 @@
 //   s_k = el[i,h] + er[col k,h],  e_k = LeakyReLU(s_k),  alpha_k = softmax over row i (Eq. 1),
 //   out[i, h*D+d] = sum_k alpha_k * X[col k, h*D+d],    lse[i,h] = log sum_k exp(e_k)
 //
-// el / er are the per-vertex projections a_l.U[i,h], a_r.X[j,h] (fp32, formed once per vertex).
+// el[i,h] = a_l.U[i,h] is a per-vertex projection (fp32, formed once per vertex); er[j,h] = a_r.X[j,h] is formed
+// per edge from the gathered row X[j] itself.
 // A partial result over any subset of a row's edges is kept as a triple (m, z, acc): m = largest
 // score met, z = sum exp(e - m), acc = sum exp(e - m) * x.  Two triples of the same row merge by
 // rescaling both to the larger m (the online form of Eq. 1's shift by the row maximum), so the
@@ -35,8 +36,7 @@ struct GatArgs {
   int nrows, F, H, D;
   float slope;
   const float* el;  // [nrows][H]
-  const half_t* a_r;  // [H*D]  (FLY kernels)
-  const float* er;    // [ncols][H]  (other kernels)
+  const half_t* a_r;  // [H*D]
   float* lse;       // [nrows][H] or nullptr
   float* part_mz;   // column blocks: [nrows][H][2] (m, z) of this block's partial rows; else nullptr
   half_t* Ym;       // SAVE: [nrows][ldym] masked result (or this block's normalised partial rows)
@@ -170,9 +170,9 @@ __device__ __forceinline__ void stage_store(const GatArgs& a, int64_t slot, int 
 }
 
 struct GatLds {
-  int per, spad, col_off, row_off, blk_off, sc_off, vec_off, mz_off, flag_off, total;
+  int per, spad, col_off, row_off, blk_off, vec_off, mz_off, flag_off, total;
 };
-__host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save, bool fly) {
+__host__ __device__ inline GatLds gat_lds_layout(int S, int L, bool save) {
   GatLds o;
   const int G = kWave / L;
   const int nv = save ? 2 : 1, ns = save ? 3 : 2;  // vectors and scalars of a parked piece
@@ -181,19 +181,19 @@ __host__ __device__ inline GatLds gat_lds_layout(int S, int H, int L, bool save,
   o.col_off = 0;
   o.row_off = o.col_off + o.spad * 4;
   o.blk_off = o.row_off + o.spad * 4;
-  o.sc_off = o.blk_off + ((o.spad + 15) & ~15);
-  o.vec_off = o.sc_off + (fly ? 0 : o.spad * H * 4);  // FLY keeps the row-side term in a register instead
+  o.vec_off = o.blk_off + ((o.spad + 15) & ~15);
   o.mz_off = o.vec_off + G * nv * 8 * L * 4;  // one parked piece per lane group: the one that entered its chunk
   o.flag_off = o.mz_off + G * L * ns * 4;
   o.total = o.flag_off + ((3 * G * 4 + 15) & ~15);
   return o;
 }
 
-// FLY = true: the column-side score term a_r.X[col] is formed from the gathered row itself (eight extra
-// products per lane and an exchange among the lanes of a head, no per-edge scalar fetched; wins for heads of
-// up to 16 features).  FLY = false: it is gathered from the per-vertex projection er while the segment is
-// staged (one 4-byte gather per edge and head; wins for long heads, where the exchange costs more).
-template <int L, bool OFF32, bool FLY, bool SAVE>
+// The score of an edge is formed in the main loop, with no per-edge table and no per-edge scalar fetched: the
+// column-side term a_r.X[col] from the gathered row itself (four two-way dot products per lane and an exchange
+// among the lanes of a head), the row-side term el[row] from a register that is refilled when the row changes.
+// Staging finished scores per (edge, head) in LDS instead (one 4-byte gather of er[col] per edge and head) was
+// slower for every head width from 8 to 512: the table costs waves per compute unit, the gather a cache request.
+template <int L, bool OFF32, bool SAVE>
 __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;
@@ -207,12 +207,11 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int head = f0c / a.D;
   const bool leader = active && (f0 % a.D) == 0;  // the lane that writes its head's scalars
   const int S = a.S;
-  const GatLds lay = gat_lds_layout(S, a.H, L, SAVE, FLY);
+  const GatLds lay = gat_lds_layout(S, L, SAVE);
   unsigned char* base = smem + size_t(wave) * lay.total;
   int* s_col = reinterpret_cast<int*>(base + lay.col_off);
   int* s_row = reinterpret_cast<int*>(base + lay.row_off);
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
-  float* s_sc = reinterpret_cast<float*>(base + lay.sc_off);    // [spad][H] scores after LeakyReLU (not FLY)
   // The piece that entered a group's chunk is parked in LDS when its row ends; the piece that leaves the chunk stays
   // in the group's registers and the merge reads it from there (cross-lane reads take no LDS allocation, and the
   // kernel's speed follows the number of waves that fit a compute unit).
@@ -238,30 +237,13 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
   }
 
-  // ---- phase 1: column ids, row ids, and (not FLY) per (edge, head) the finished score
-  // LeakyReLU(el[row] + er[col])
+  // ---- phase 1: column ids (as byte offsets of the neighbour's row where they fit 32 bits) and row ids
   for (int i = lane; i < spad; i += kWave) {
     const int c = i < n ? a.col[e0 + i] : 0;
-    s_col[i] = OFF32 && FLY ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;
+    s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;
   }
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
-  if (!FLY) {
-    for (int i = lane; i < spad; i += kWave) {
-      const bool in = i < n;
-      const int c = s_col[i];
-      const int r = in ? s_row[i] : 0;
-      for (int h = 0; h < a.H; ++h) {
-        float s = -INFINITY;  // padding: weight exp(-inf - m) = 0
-        if (in) {
-          s = a.el[int64_t(r) * a.H + h] + a.er[int64_t(c) * a.H + h];
-          s = s > 0.f ? s : a.slope * s;
-        }
-        s_sc[i * a.H + h] = s;
-      }
-      if (OFF32) s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);  // from here on: byte offset of the neighbour's row
-    }
-  }
   wave_sync();
 
   // ---- phase 2: running (m, z, acc) over this group's chunk
@@ -322,16 +304,16 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     return *reinterpret_cast<const half8_t*>(a.X + int64_t(c) * a.ldx + f0c);
   };
 
-  float el_cur = 0.f;  // FLY: the row-side score term of the current row, fetched when the row changes
+  float el_cur = 0.f;  // the row-side score term of the current row, fetched when the row changes
   if (c0 < c1) {
     cur = s_row[c0];
     lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
-    if (FLY) el_cur = a.el[int64_t(cur) * a.H + head];
+    el_cur = a.el[int64_t(cur) * a.H + head];
   }
   const int LH = a.D / 8;  // lanes per head (power of two)
   typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
   half2_t ar2[4];
-  if (FLY) {
+  {
     const half8_t t = *reinterpret_cast<const half8_t*>(a.a_r + f0c);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -346,32 +328,25 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
     half8_t x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) x[u] = gather(cols[u]);
-    float sc[4];
-    if (FLY) {  // column-side term a_r.x from the row just gathered, summed over the lanes of the head
+    float sc[4];  // column-side term a_r.x from the row just gathered, summed over the lanes of the head
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float d = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {  // two fp16 products per instruction, fp32 sum
+        half2_t xv;
+        xv[0] = x[u][2 * q];
+        xv[1] = x[u][2 * q + 1];
+        d = __builtin_amdgcn_fdot2(ar2[q], xv, d, false);
+      }
+      sc[u] = d;
+    }
+    head_sum4(sc, LH);
+    if (blk == cur) {  // four more edges of the current row: one rescale, four terms
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        float d = 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {  // two fp16 products per instruction, fp32 sum
-          half2_t xv;
-          xv[0] = x[u][2 * q];
-          xv[1] = x[u][2 * q + 1];
-          d = __builtin_amdgcn_fdot2(ar2[q], xv, d, false);
-        }
-        sc[u] = d;
-      }
-      head_sum4(sc, LH);
-    } else {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) sc[u] = s_sc[(i + u) * a.H + head];
-    }
-    if (blk == cur) {  // four more edges of the current row: one rescale, four terms
-      if (FLY) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float v = sc[u] + el_cur;
-          sc[u] = v > 0.f ? v : a.slope * v;
-        }
+        const float v = sc[u] + el_cur;
+        sc[u] = v > 0.f ? v : a.slope * v;
       }
       const float mn = fmaxf(fmaxf(t.m, fmaxf(sc[0], sc[1])), fmaxf(sc[2], sc[3]));
       t.scale(__expf(t.m - mn));
@@ -388,15 +363,13 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
             t.clear();
             cur = rows[u];
             lo = false;
-            if (FLY) el_cur = a.el[int64_t(cur) * a.H + head];
+            el_cur = a.el[int64_t(cur) * a.H + head];
           }
-          if (FLY) {
-            const float v = sc[u] + el_cur;
-            sc[u] = v > 0.f ? v : a.slope * v;
-          }
-          const float mn = fmaxf(t.m, sc[u]);
+          const float v = sc[u] + el_cur;
+          const float e = v > 0.f ? v : a.slope * v;
+          const float mn = fmaxf(t.m, e);
           t.scale(__expf(t.m - mn));
-          t.add(__expf(sc[u] - mn), sc[u], a.slope, x[u]);
+          t.add(__expf(e - mn), e, a.slope, x[u]);
           t.m = mn;
         }
       }
@@ -564,22 +537,22 @@ __global__ __launch_bounds__(kBlock) void gat_block_merge_kernel(GatArgs a, GatB
   row_store<SAVE>(a, r, f0, head, (f0 % a.D) == 0, t);
 }
 
-template <int L, bool OFF32, bool FLY>
+template <int L, bool OFF32>
 static void launch_gat_seg_l(bool save, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
-  if (save) gat_seg_kernel<L, OFF32, FLY, true><<<grid, threads, lds, s>>>(a);
-  else gat_seg_kernel<L, OFF32, FLY, false><<<grid, threads, lds, s>>>(a);
+  if (save) gat_seg_kernel<L, OFF32, true><<<grid, threads, lds, s>>>(a);
+  else gat_seg_kernel<L, OFF32, false><<<grid, threads, lds, s>>>(a);
 }
 
-template <bool OFF32, bool FLY>
+template <bool OFF32>
 static void launch_gat_seg(int L, bool save, dim3 grid, int threads, size_t lds, hipStream_t s, const GatArgs& a) {
   switch (L) {
-    case 1: launch_gat_seg_l<1, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    case 2: launch_gat_seg_l<2, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    case 4: launch_gat_seg_l<4, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    case 8: launch_gat_seg_l<8, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    case 16: launch_gat_seg_l<16, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    case 32: launch_gat_seg_l<32, OFF32, FLY>(save, grid, threads, lds, s, a); break;
-    default: launch_gat_seg_l<64, OFF32, FLY>(save, grid, threads, lds, s, a); break;
+    case 1: launch_gat_seg_l<1, OFF32>(save, grid, threads, lds, s, a); break;
+    case 2: launch_gat_seg_l<2, OFF32>(save, grid, threads, lds, s, a); break;
+    case 4: launch_gat_seg_l<4, OFF32>(save, grid, threads, lds, s, a); break;
+    case 8: launch_gat_seg_l<8, OFF32>(save, grid, threads, lds, s, a); break;
+    case 16: launch_gat_seg_l<16, OFF32>(save, grid, threads, lds, s, a); break;
+    case 32: launch_gat_seg_l<32, OFF32>(save, grid, threads, lds, s, a); break;
+    default: launch_gat_seg_l<64, OFF32>(save, grid, threads, lds, s, a); break;
   }
 }
 
@@ -637,7 +610,7 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   a.split_hi = q->split_seg_hi;
   a.n_split = q->n_split;
   const int L = pow2_at_least(a.F / 8);
-  const size_t per_wave = size_t(gat_lds_layout(a.S, a.H, L, save, a.a_r != nullptr).total);
+  const size_t per_wave = size_t(gat_lds_layout(a.S, L, save).total);
   const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;
   HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
@@ -647,13 +620,8 @@ static hgnn_status run_gat_segments(const hgnn_plan* q, GatArgs a, int ncols, hi
   dim3 grid(unsigned(nblk > 0 ? nblk : 1));
   const int threads = wpb * kWave;
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
-  if (a.a_r) {
-    if (off32) launch_gat_seg<true, true>(L, save, grid, threads, lds, s, a);
-    else launch_gat_seg<false, true>(L, save, grid, threads, lds, s, a);
-  } else {
-    if (off32) launch_gat_seg<true, false>(L, save, grid, threads, lds, s, a);
-    else launch_gat_seg<false, false>(L, save, grid, threads, lds, s, a);
-  }
+  if (off32) launch_gat_seg<true>(L, save, grid, threads, lds, s, a);
+  else launch_gat_seg<false>(L, save, grid, threads, lds, s, a);
   HGNN_LAUNCH_CHECK("gat_seg_kernel");
   if (a.n_split > 0) {
     launch_gat_finish(L, save, dim3(unsigned(ceil_div(a.n_split, int64_t(kWavesPerBlock) * (kWave / L)))), s, a);
@@ -694,10 +662,9 @@ static hgnn_status gat_forward_impl(const char* who, const hgnn_csr* g, const hg
   HGNN_REQUIRE(out_masked == nullptr || (ldom % 8 == 0 && aligned16(out_masked)), HGNN_EUNSUPPORTED,
                "%s: needs ldom %% 8 == 0 and a 16-byte aligned out_masked", who);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // per-vertex projections into the plan's fp32 scratch: el[i,h] = a_l[h].U[i,h] always; er[j,h] = a_r[h].Vt[j,h]
-  // only for long heads (short heads form that term in the kernel from the gathered row)
-  const bool fly = D <= 16;
-  st = gat_project(p, g, H, D, U, ldu, fly ? nullptr : Vt, ldv, a_l, a_r, s, who);
+  // per-vertex projection into the plan's fp32 scratch: el[i,h] = a_l[h].U[i,h]; the column-side term is formed in
+  // the kernel from the gathered row
+  st = gat_project(p, g, H, D, U, ldu, nullptr, ldv, a_l, a_r, s, who);
   if (st != HGNN_OK) return st;
   GatArgs a{};
   a.rowptr = g->rowptr;
@@ -713,8 +680,7 @@ static hgnn_status gat_forward_impl(const char* who, const hgnn_csr* g, const hg
   a.D = D;
   a.slope = neg_slope;
   a.el = p->vscratch;
-  a.a_r = fly ? reinterpret_cast<const half_t*>(a_r) : nullptr;
-  a.er = p->vscratch + size_t(g->nrows) * H;
+  a.a_r = reinterpret_cast<const half_t*>(a_r);
   a.lse = lse;
   a.Ym = reinterpret_cast<half_t*>(out_masked);
   a.ldym = ldom;
