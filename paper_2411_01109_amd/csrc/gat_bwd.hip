@@ -97,8 +97,9 @@ __device__ __forceinline__ void bwd_stage_store(const GatBwdArgs& a, int64_t slo
 // VEC = true is the pass over the transposed graph (the destination vertex of a non-zero is its column).
 // FLY = true: the weight of an edge is formed in the main loop from the destination's packed scalars and the
 // source's er, one of them gathered per edge and the other fetched when the row changes; no per-edge tables in
-// LDS, so more waves fit a compute unit (wins with several heads, where the tables are large and a head's
-// lanes repeat little of the scalar work).  FLY = false: formed once per (edge, head) while the segment is staged.
+// LDS, so more waves fit a compute unit (wins with several heads, where the tables are large, and with one head
+// of up to 64 features, whose few lanes repeat little of the scalar work).  FLY = false: formed once per
+// (edge, head) while the segment is staged.
 template <int L, bool OFF32, bool VEC, bool FLY>
 __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwdArgs a) {
   constexpr int G = kWave / L;
@@ -589,8 +590,9 @@ static hgnn_status run_bwd_segments(const hgnn_plan* q, GatBwdArgs a, int ncols,
   const int L = pow2_at_least(a.F / 8);
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   // weights formed in the main loop: measured 0.26 -> 0.17 ms for the transposed pass with 4 heads of 16 (12 -> 20
-  // waves per compute unit), a tie with one head of 64
-  const bool fly = a.H >= 2;
+  // waves per compute unit); with one head 3-15 % faster up to 64 features, 1-3 % slower from 128 on (every lane of
+  // the head repeats the scalar work)
+  const bool fly = a.H >= 2 || a.D <= 64;
   const size_t per_wave = size_t(gat_bwd_lds_layout(a.S, a.H, L, VEC, fly, off32).total);
   const int wpb = waves_per_block_for_lds(per_wave, true);
   const size_t lds = per_wave * wpb;

@@ -188,7 +188,7 @@ def bwd_reference(rowptr, col, ncols, U, Vt, a_l, a_r, dOut, H, slope=0.2):
 
 
 BWD_CASES = [(1, 64, 256, 1), (4, 16, 256, 1), (8, 8, 128, 1), (2, 32, 64, 1), (1, 8, 7, 1), (1, 128, 256, 1),
-             (1, 64, 256, 3), (4, 16, 100, 4)]
+             (1, 64, 256, 3), (4, 16, 100, 4), (1, 256, 128, 2)]  # one head of 128 or more: weights staged per segment
 
 
 @pytest.mark.parametrize("H,D,S,nb", BWD_CASES)
@@ -243,7 +243,7 @@ def test_gat_backward_fused_full_configs(hgnn, dev, maker, nb):
 
 # ------------------------------------------------------------------ forward that saves for the backward
 SAVE_CASES = [(1, 64, 256, 1), (4, 16, 256, 1), (8, 8, 128, 1), (2, 32, 64, 1), (1, 8, 7, 1), (1, 128, 256, 1), (1, 64, 256, 3),
-              (4, 16, 100, 4), (3, 8, 33, 2), (8, 64, 256, 1)]
+              (4, 16, 100, 4), (3, 8, 33, 2), (8, 64, 256, 1), (1, 256, 128, 2)]
 
 
 @pytest.mark.parametrize("H,D,S,nb", SAVE_CASES)
