@@ -149,6 +149,20 @@ typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 // which keeps the four waves of a streaming kernel in step on consecutive segments.
 __device__ __forceinline__ int seg_slots_per_lane(int S) { return 4 * ((S + 255) / 256); }
 
+// Reads the n column ids of a segment (0 beyond n) and hands them to put(i, c) for i in [0, spad); spad is a
+// multiple of 4 * kWave (see seg_slots_per_lane).  A lane has its four loads of a round in flight together: a loop
+// of one load and one LDS store per turn waits for every load in turn, four memory latencies per 256 edges.
+template <class Put>
+__device__ __forceinline__ void seg_stage_cols(const int* __restrict__ col, int64_t e0, int lane, int spad, int n, Put&& put) {
+  for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {
+    int c[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) c[q] = i0 + q * kWave < n ? col[e0 + i0 + q * kWave] : 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) put(i0 + q * kWave, c[q]);
+  }
+}
+
 template <bool BLOCK_SYNC = false>
 __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane, int per, int n, int row_lo, int row_hi,
                                                const int* __restrict__ rowptr, int64_t e0) {

@@ -238,10 +238,8 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   }
 
   // ---- phase 1: column ids (as byte offsets of the neighbour's row where they fit 32 bits) and row ids
-  for (int i = lane; i < spad; i += kWave) {
-    const int c = i < n ? a.col[e0 + i] : 0;
-    s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;
-  }
+  seg_stage_cols(a.col, e0, lane, spad, n,
+                 [&](int i, int c) { s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c; });
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
   wave_sync();

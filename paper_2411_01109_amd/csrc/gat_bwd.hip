@@ -148,15 +148,14 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
 
   // ---- phase 1: column ids, row ids, then per (edge, head) the attention weight with the LeakyReLU branch in
   // its sign, and u = alpha * mask * t of the destination vertex
-  for (int i = lane; i < spad; i += kWave) {
-    const int c = i < n ? a.col[e0 + i] : 0;
+  seg_stage_cols(a.col, e0, lane, spad, n, [&](int i, int c) {
     if (FLY && OFF32) {
       s_raw[i] = c;
       s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);
     } else {
       s_col[i] = c;
     }
-  }
+  });
   if (lane < G) m_flag[lane] = 0;
   seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
   if (!FLY) {

@@ -434,20 +434,49 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
     seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
   }
 
-  // ---- phase 1: coalesced stage of column ids and edge values, then the row id of every edge
-  for (int i = lane; i < spad; i += kWave) {
-    const bool in = i < n;
-    const int64_t k = e0 + i;
-    const int c = in ? a.col[k] : 0;
-    s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c;  // OFF32: byte offset of the neighbour's row
-    if (!a.delta) {
-      if (WM == 1) {
-        const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
-        for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
-      } else if (WM == 2) {
-        const int64_t slot = in ? (a.eid ? int64_t(a.eid[k]) : k) : 0;
-        const float cs = (in && a.col_scale) ? a.col_scale[c] : (in ? 1.f : 0.f);
-        for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
+  // ---- phase 1: coalesced stage of column ids and edge values, then the row id of every edge.  spad is a
+  // multiple of 4 * kWave; a lane keeps its four loads of a round in flight together (column ids, then the
+  // edge-id map, then the values behind it), so a round costs one memory latency per level, not four.
+  for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {
+    int c[4];
+    int64_t slot[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = i0 + q * kWave;
+      c[q] = i < n ? a.col[e0 + i] : 0;
+    }
+    if (WM != 0 && !a.delta) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i0 + q * kWave;
+        slot[q] = i < n ? (a.eid ? int64_t(a.eid[e0 + i]) : e0 + i) : 0;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)  // OFF32: byte offset of the neighbour's row
+      s_col[i0 + q * kWave] = OFF32 ? int(uint32_t(c[q]) * uint32_t(a.ldx) * 2u) : c[q];
+    if (WM != 0 && !a.delta) {
+      float cs[4];
+      if (WM == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bool in = i0 + q * kWave < n;
+          cs[q] = (in && a.col_scale) ? a.col_scale[c[q]] : (in ? 1.f : 0.f);
+        }
+      }
+      for (int h = 0; h < a.H; ++h) {
+        half_t wv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bool in = i0 + q * kWave < n;
+          wv[q] = (in && (WM == 1 || a.w)) ? a.w[slot[q] * a.H + h] : half_t(WM == 1 ? 0 : 1);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int i = i0 + q * kWave;
+          if (WM == 1) s_w[i * a.H + h] = wv[q];
+          else s_wf[i * a.H + h] = float(wv[q]) * cs[q];
+        }
       }
     }
   }
@@ -456,14 +485,34 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   if (WM != 0 && a.delta) {
     // a row piece of a column block is a run of consecutive slots: slot = position + delta[row], so the
     // edge values are read coalesced without an edge-id array (the row ids are known only now)
-    for (int i = lane; i < spad; i += kWave) {
-      const bool in = i < n;
-      const int64_t slot = in ? e0 + i + a.delta[s_row[i]] : 0;
-      if (WM == 1) {
-        for (int h = 0; h < a.H; ++h) s_w[i * a.H + h] = in ? a.w[slot * a.H + h] : half_t(0);
-      } else {
-        const float cs = in ? (a.col_scale ? a.col_scale[a.col[e0 + i]] : 1.f) : 0.f;
-        for (int h = 0; h < a.H; ++h) s_wf[i * a.H + h] = (in && a.w) ? float(a.w[slot * a.H + h]) * cs : cs;
+    for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {  // four in flight per level, as above
+      int64_t slot[4];
+      float cs[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i0 + q * kWave;
+        slot[q] = i < n ? e0 + i + a.delta[s_row[i]] : 0;
+      }
+      if (WM == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int i = i0 + q * kWave;
+          cs[q] = i < n ? (a.col_scale ? a.col_scale[a.col[e0 + i]] : 1.f) : 0.f;
+        }
+      }
+      for (int h = 0; h < a.H; ++h) {
+        half_t wv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bool in = i0 + q * kWave < n;
+          wv[q] = (in && (WM == 1 || a.w)) ? a.w[slot[q] * a.H + h] : half_t(WM == 1 ? 0 : 1);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int i = i0 + q * kWave;
+          if (WM == 1) s_w[i * a.H + h] = wv[q];
+          else s_wf[i * a.H + h] = float(wv[q]) * cs[q];
+        }
       }
     }
     wave_sync();
