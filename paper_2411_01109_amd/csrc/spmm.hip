@@ -390,6 +390,60 @@ __host__ __device__ inline SegLds seg_lds_layout(int S, int H, int wm, int L) {
   return o;
 }
 
+// Edge values of four staged edges (i0 + q * kWave, q = 0..3) into the LDS table: fp16 as they are (WM == 1) or
+// as fp32 factors times the column scale cs (WM == 2; no values: the scale alone).  HV = 1, 2, 4, 8: the H values of
+// an edge are read as one vector (H == HV, base aligned to it); HV = 0: any head count, one value at a time.
+// All four edges' loads of a level are issued before the first LDS store.
+template <int WM, int HV>
+__device__ __forceinline__ void seg_stage_values(const SpmmArgs& a, int i0, int n, const int64_t (&slot)[4],
+                                                 const float (&cs)[4], half_t* s_w, float* s_wf) {
+  const bool have = WM == 1 || a.w != nullptr;
+  if (HV == 0) {
+    for (int h = 0; h < a.H; ++h) {
+      half_t wv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        wv[q] = (i0 + q * kWave < n && have) ? a.w[slot[q] * a.H + h] : half_t(WM == 1 ? 0 : 1);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i0 + q * kWave;
+        if (WM == 1) s_w[i * a.H + h] = wv[q];
+        else s_wf[i * a.H + h] = float(wv[q]) * cs[q];
+      }
+    }
+    return;
+  }
+  constexpr int N = HV > 0 ? HV : 1;
+  typedef _Float16 hv_t __attribute__((ext_vector_type(N)));
+  hv_t wv[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    wv[q] = hv_t(half_t(WM == 1 ? 0 : 1));
+    if (i0 + q * kWave < n && have) wv[q] = *reinterpret_cast<const hv_t*>(a.w + slot[q] * N);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int i = i0 + q * kWave;
+    if (WM == 1) {
+      *reinterpret_cast<hv_t*>(s_w + i * N) = wv[q];
+    } else {
+#pragma unroll
+      for (int h = 0; h < N; ++h) s_wf[i * N + h] = float(wv[q][h]) * cs[q];
+    }
+  }
+}
+
+template <int WM>
+__device__ __forceinline__ void seg_stage_values_any(const SpmmArgs& a, int i0, int n, const int64_t (&slot)[4],
+                                                     const float (&cs)[4], half_t* s_w, float* s_wf) {
+  const uintptr_t wa = reinterpret_cast<uintptr_t>(a.w);
+  if (a.H == 1) seg_stage_values<WM, 1>(a, i0, n, slot, cs, s_w, s_wf);
+  else if (a.H == 4 && (wa & 7u) == 0) seg_stage_values<WM, 4>(a, i0, n, slot, cs, s_w, s_wf);
+  else if (a.H == 2 && (wa & 3u) == 0) seg_stage_values<WM, 2>(a, i0, n, slot, cs, s_w, s_wf);
+  else if (a.H == 8 && (wa & 15u) == 0) seg_stage_values<WM, 8>(a, i0, n, slot, cs, s_w, s_wf);
+  else seg_stage_values<WM, 0>(a, i0, n, slot, cs, s_w, s_wf);
+}
+
 template <int L, int WM, bool OFF32>
 __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
@@ -439,7 +493,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   // edge-id map, then the values behind it), so a round costs one memory latency per level, not four.
   for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {
     int c[4];
-    int64_t slot[4];
+    int64_t slot[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int i = i0 + q * kWave;
@@ -456,7 +510,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
     for (int q = 0; q < 4; ++q)  // OFF32: byte offset of the neighbour's row
       s_col[i0 + q * kWave] = OFF32 ? int(uint32_t(c[q]) * uint32_t(a.ldx) * 2u) : c[q];
     if (WM != 0 && !a.delta) {
-      float cs[4];
+      float cs[4] = {1.f, 1.f, 1.f, 1.f};
       if (WM == 2) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -464,20 +518,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
           cs[q] = (in && a.col_scale) ? a.col_scale[c[q]] : (in ? 1.f : 0.f);
         }
       }
-      for (int h = 0; h < a.H; ++h) {
-        half_t wv[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const bool in = i0 + q * kWave < n;
-          wv[q] = (in && (WM == 1 || a.w)) ? a.w[slot[q] * a.H + h] : half_t(WM == 1 ? 0 : 1);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int i = i0 + q * kWave;
-          if (WM == 1) s_w[i * a.H + h] = wv[q];
-          else s_wf[i * a.H + h] = float(wv[q]) * cs[q];
-        }
-      }
+      seg_stage_values_any<WM>(a, i0, n, slot, cs, s_w, s_wf);
     }
   }
   if (lane < G) m_flag[lane] = 0;
@@ -487,7 +528,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
     // edge values are read coalesced without an edge-id array (the row ids are known only now)
     for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {  // four in flight per level, as above
       int64_t slot[4];
-      float cs[4];
+      float cs[4] = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int i = i0 + q * kWave;
@@ -500,20 +541,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
           cs[q] = i < n ? (a.col_scale ? a.col_scale[a.col[e0 + i]] : 1.f) : 0.f;
         }
       }
-      for (int h = 0; h < a.H; ++h) {
-        half_t wv[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const bool in = i0 + q * kWave < n;
-          wv[q] = (in && (WM == 1 || a.w)) ? a.w[slot[q] * a.H + h] : half_t(WM == 1 ? 0 : 1);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int i = i0 + q * kWave;
-          if (WM == 1) s_w[i * a.H + h] = wv[q];
-          else s_wf[i * a.H + h] = float(wv[q]) * cs[q];
-        }
-      }
+      seg_stage_values_any<WM>(a, i0, n, slot, cs, s_w, s_wf);
     }
     wave_sync();
   }
