@@ -163,13 +163,31 @@ __device__ __forceinline__ void seg_stage_cols(const int* __restrict__ col, int6
   }
 }
 
+// open (optional): [0] = the segment's first row began in an earlier segment, [1] = its last row goes on in the
+// next one.  When asked for, the two row bounds behind them and the first round of the scatter's bounds are
+// requested together, ahead of the LDS fill (one memory latency instead of two; the values held across the fill
+// cost registers, which pays for the fused GAT forward and not for the kernels held to 64 registers).
 template <bool BLOCK_SYNC = false>
 __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane, int per, int n, int row_lo, int row_hi,
-                                               const int* __restrict__ rowptr, int64_t e0) {
+                                               const int* __restrict__ rowptr, int64_t e0, bool* open = nullptr) {
+  const int r0 = row_lo + 1 + lane;
+  int p0 = 0, q0 = 0, b_lo = 0, b_hi = 0;
+  if (open && n > 0) {  // a segment of the plan: row_lo <= row_hi are rows of the graph
+    const int rc = r0 <= row_hi ? r0 : row_lo;
+    p0 = rowptr[rc];
+    q0 = rowptr[rc + 1];
+    b_lo = rowptr[row_lo];
+    b_hi = rowptr[row_hi + 1];
+  }
   for (int i = lane; i < kWave * per; i += kWave) s_row[i] = i == 0 ? row_lo : -1;
   if (BLOCK_SYNC) __syncthreads();
   else wave_sync();
-  for (int r = row_lo + 1 + lane; r <= row_hi; r += kWave) {
+  if (open) {
+    if (r0 <= row_hi && q0 > p0) s_row[p0 - int(e0)] = r0;
+    open[0] = n > 0 && int64_t(b_lo) < e0;
+    open[1] = n > 0 && int64_t(b_hi) > e0 + n;
+  }
+  for (int r = open ? r0 + kWave : r0; r <= row_hi; r += kWave) {
     const int p = rowptr[r], q = rowptr[r + 1];
     if (q > p) s_row[p - int(e0)] = r;
   }

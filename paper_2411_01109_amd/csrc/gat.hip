@@ -229,19 +229,18 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
   const int per = lay.per, spad = lay.spad;
   int row_lo = 0, row_hi = -1;
-  bool seg_left_open = false, seg_right_open = false;
   if (valid) {
     row_lo = a.seg_lo[seg];
     row_hi = a.seg_hi[seg];
-    seg_left_open = int64_t(a.rowptr[row_lo]) < e0;
-    seg_right_open = int64_t(a.rowptr[row_hi + 1]) > e0 + n;
   }
 
   // ---- phase 1: column ids (as byte offsets of the neighbour's row where they fit 32 bits) and row ids
   seg_stage_cols(a.col, e0, lane, spad, n,
                  [&](int i, int c) { s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c; });
   if (lane < G) m_flag[lane] = 0;
-  seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0);
+  bool seg_open[2];
+  seg_stage_rows(s_row, s_blk, lane, per, n, row_lo, row_hi, a.rowptr, e0, seg_open);
+  const bool seg_left_open = seg_open[0], seg_right_open = seg_open[1];
   wave_sync();
 
   // ---- phase 2: running (m, z, acc) over this group's chunk
