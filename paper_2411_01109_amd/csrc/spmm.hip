@@ -554,8 +554,10 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   int cur = -1;
   bool lo = false;  // current piece began before this chunk
 
+  // the scale of the current row (1/degree, row factor) is requested when the row begins, so that its latency has
+  // passed by the time the row ends; fetched at the flush it would stall the lane group once per row
+  float sc = 0.f;
   auto flush = [&](bool ro) {
-    const float sc = scale_of(a, cur);
     if (!lo && !ro) {
       if (active) store_row(a, cur, f0, acc, sc);
     } else if (lo) {
@@ -588,6 +590,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   if (c0 < c1) {
     cur = s_row[c0];
     lo = c0 > 0 ? s_row[c0 - 1] == cur : seg_left_open;
+    sc = scale_of(a, cur);
   }
   for (int i = c0; i < c1; i += 4) {
     const int4_t cols = *reinterpret_cast<const int4_t*>(s_col + i);
@@ -631,6 +634,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
             for (int q = 0; q < 8; ++q) acc[q] = 0.f;
             cur = rows[u];
             lo = false;
+            sc = scale_of(a, cur);
           }
           fma8(acc, wv[u], x[u]);
         }
