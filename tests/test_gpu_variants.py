@@ -439,3 +439,38 @@ def test_scale_rows_then_unweighted_spmm_is_the_column_norm(hgnn, dev):
     ref, sabs = oracle.spmm(rowptr, col, X, row_scale=rs.astype(np.float64), col_scale=cs.astype(np.float64), want_sabs=True)
     compare("pre-scaled column norm", down(Y), ref, 2 * sabs)  # the extra rounding of the scaled table
     hgnn.hgnn_plan_destroy(p)
+
+
+# ------------------------------------------------------------------ per-head edge values: vector and element-wise staging
+@pytest.mark.parametrize("H", [2, 4, 8])
+@pytest.mark.parametrize("shift", [0, 1])
+def test_edge_values_with_heads_aligned_or_not(hgnn, dev, H, shift):
+    """The segment kernel reads the H values of an edge as one 4-, 8- or 16-byte vector when the tensor's base
+    allows it and one by one otherwise (shift = 1: the tensor starts one half past an aligned address).  Forward
+    (values in edge order), transposed (through the edge-id map) and column-blocked (through per-row offsets)."""
+    print(f"edge values H={H} shift={shift}", flush=True)
+    V, ncols, F = 700, 650, 64
+    rowptr, col = rand_graph(V, ncols, 14, 90 + H, hubs=((3, 2500), (600, 400)), empties=(0, 9))
+    E = col.size
+    r = np.random.default_rng(100 + H)
+    Xh, dYh = f16(r.standard_normal((ncols, F))), f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, H)))
+    buf = torch.zeros(E * H + 8, dtype=torch.float16, device=dev)
+    wd = buf[shift:shift + E * H].view(E, H)
+    wd.copy_(up(w, dev))
+    assert (wd.data_ptr() % 16 == 0) == (shift == 0)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, want_sabs=True)
+    refb, sabsb = oracle.spmm(down(gt.rowptr), down(gt.col), dYh, w=w, H=H, eid=down(gt.eid), want_sabs=True)
+    for nb in (1, 3):
+        p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=nb)
+        pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=nb)
+        Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+        hgnn.hgnn_spmm_discretized(p, g, wd, H, up(Xh, dev), Y)
+        compare(f"forward, {nb} block(s)", down(Y), ref, sabs)
+        dX = torch.empty((ncols, F), dtype=torch.float16, device=dev)
+        hgnn.hgnn_spmm_discretized(pt, gt, wd, H, up(dYh, dev), dX)
+        compare(f"transposed, {nb} block(s)", down(dX), refb, sabsb)
+        hgnn.hgnn_plan_destroy(p)
+        hgnn.hgnn_plan_destroy(pt)
