@@ -25,7 +25,7 @@ def draw(seed):
                 has_w=bool(r.integers(0, 2)), ng=int(r.choice([16, 64, 256])), seed=seed)
 
 
-@pytest.mark.parametrize("seed", range(72))
+@pytest.mark.parametrize("seed", range(128))
 def test_random_configuration(hgnn, dev, seed):
     c = draw(seed)
     print(f"sweep {c}", flush=True)
