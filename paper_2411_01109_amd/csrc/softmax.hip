@@ -36,6 +36,34 @@ struct EdgeRowArgs {
 };
 
 // ---- teams -----------------------------------------------------------------------------------------
+// One step of an all-reduce (sum or maximum) among aligned groups of lanes: with the partner inside a row of 16
+// lanes the exchange is a DPP operand of the VALU instruction (lane ^ 1, lane ^ 2, then mirrors inside 8 and 16
+// lanes, which pair a lane with one from the other half, whose partial result is the same on all its lanes);
+// across rows it goes through ds_bpermute.
+template <int OFF, bool IS_MAX>
+__device__ __forceinline__ float team_step(float v) {
+  float o;
+  if (OFF == 1) o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));
+  else if (OFF == 2) o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));
+  else if (OFF == 4) o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));
+  else if (OFF == 8) o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));
+  else o = __shfl_xor(v, OFF);
+  return IS_MAX ? fmaxf(v, o) : v + o;
+}
+
+template <int N, int H, bool IS_MAX>  // all-reduce over aligned groups of N lanes (N a power of two up to 64)
+__device__ __forceinline__ void team_reduce(float (&v)[H]) {
+#pragma unroll
+  for (int h = 0; h < H; ++h) {
+    if (N > 1) v[h] = team_step<1, IS_MAX>(v[h]);
+    if (N > 2) v[h] = team_step<2, IS_MAX>(v[h]);
+    if (N > 4) v[h] = team_step<4, IS_MAX>(v[h]);
+    if (N > 8) v[h] = team_step<8, IS_MAX>(v[h]);
+    if (N > 16) v[h] = team_step<16, IS_MAX>(v[h]);
+    if (N > 32) v[h] = team_step<32, IS_MAX>(v[h]);
+  }
+}
+
 template <int LR>
 struct SubWaveTeam {  // LR consecutive lanes of a wave
   static constexpr int size = LR;
@@ -43,13 +71,7 @@ struct SubWaveTeam {  // LR consecutive lanes of a wave
   __device__ SubWaveTeam() : rank((threadIdx.x & (kWave - 1)) % LR) {}
   template <int H, bool IS_MAX>
   __device__ __forceinline__ void reduce(float (&v)[H]) const {
-#pragma unroll
-    for (int off = 1; off < LR; off <<= 1)
-#pragma unroll
-      for (int h = 0; h < H; ++h) {
-        const float o = __shfl_xor(v[h], off);
-        v[h] = IS_MAX ? fmaxf(v[h], o) : v[h] + o;
-      }
+    team_reduce<LR, H, IS_MAX>(v);
   }
 };
 
@@ -61,13 +83,7 @@ struct BlockTeam {  // a whole workgroup of kBigBlock threads
   template <int H, bool IS_MAX>
   __device__ __forceinline__ void reduce(float (&v)[H]) const {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1)
-#pragma unroll
-      for (int h = 0; h < H; ++h) {
-        const float o = __shfl_xor(v[h], off);
-        v[h] = IS_MAX ? fmaxf(v[h], o) : v[h] + o;
-      }
+    team_reduce<kWave, H, IS_MAX>(v);
     __syncthreads();  // protects sm against the previous use
     if (lane == 0)
 #pragma unroll
