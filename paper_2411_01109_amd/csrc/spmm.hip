@@ -244,8 +244,8 @@ __global__ __launch_bounds__(kBlock) void hub_scan_kernel(SpmmArgs a, HubLists h
   __syncthreads();
   // inclusive scan over the workgroup (Hillis-Steele; kBlock is small)
   for (int off = 1; off < kBlock; off <<= 1) {
-    const int c = threadIdx.x >= off ? s_chunks[threadIdx.x - off] : 0;
-    const int n = threadIdx.x >= off ? s_hubs[threadIdx.x - off] : 0;
+    const int c = int(threadIdx.x) >= off ? s_chunks[threadIdx.x - off] : 0;
+    const int n = int(threadIdx.x) >= off ? s_hubs[threadIdx.x - off] : 0;
     __syncthreads();
     s_chunks[threadIdx.x] += c;
     s_hubs[threadIdx.x] += n;
