@@ -88,3 +88,29 @@ def test_random_configuration(hgnn, dev, seed):
     compare("dV", g_dV, dV, dV_abs + pieces[:, None] * 2.0 ** -13)
     compare("d_el", g_el, d_el, el_abs, rel_l2=2e-2)
     compare("d_er", g_er, d_er, er_abs, rel_l2=2e-2)
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_plan_and_transpose_bit_exact(hgnn, dev, seed):
+    """Integer work on drawn graphs: segment plan (with and without column blocks the top-level arrays are the
+    same), transpose with its edge-id map, and the plan of the transpose, each against the oracle bit for bit."""
+    c = draw(500 + seed)
+    print(f"plan sweep {c}", flush=True)
+    V, S, nb = c["V"], c["S"], c["nb"]
+    ncols = V + int(np.random.default_rng(seed).integers(0, 40))
+    rowptr, col = rand_graph(V, ncols, c["avg"], 900 + seed, hubs=c["hubs"], empties=c["empties"])
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    hgnn.hgnn_csr_validate(g)
+    p = hgnn.hgnn_plan_create(g, S, 64, 1, col_blocks=nb)
+    got, ref = hgnn.hgnn_plan_export(p), oracle.segment_plan(rowptr, S)
+    for k in ref:
+        assert np.array_equal(got[k], ref[k]), k
+    hgnn.hgnn_plan_destroy(p)
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = oracle.transpose(rowptr, col, ncols)
+    assert np.array_equal(down(gt.rowptr), rT) and np.array_equal(down(gt.col), cT) and np.array_equal(down(gt.eid), eT)
+    pt = hgnn.hgnn_plan_create(gt, S, 64, 1)
+    gotT, refT = hgnn.hgnn_plan_export(pt), oracle.segment_plan(rT, S)
+    for k in refT:
+        assert np.array_equal(gotT[k], refT[k]), k
+    hgnn.hgnn_plan_destroy(pt)
