@@ -49,6 +49,8 @@ def _load():
     lib.orc_spmm_T_scatter.argtypes = [i32, i32, vp, vp, vp, i32, vp, i64, i32, vp]
     lib.orc_transpose.restype = None
     lib.orc_transpose.argtypes = [i32, i32, vp, vp, vp, vp, vp]
+    lib.orc_coo_to_csr.restype = None
+    lib.orc_coo_to_csr.argtypes = [i64, i32, vp, vp, vp, vp, vp]
     lib.orc_sddmm_dot.restype = None
     lib.orc_sddmm_dot.argtypes = [i32, vp, vp, vp, i32, i32, vp, i64, vp, i64, vp]
     lib.orc_gat_score.restype = None
@@ -152,6 +154,18 @@ def transpose(rowptr, col, ncols: int):
     eid_T = np.empty(E, dtype=np.int32)
     _load().orc_transpose(V, ncols, _ptr(rowptr), _ptr(col), _ptr(rowptr_T), _ptr(col_T), _ptr(eid_T))
     return rowptr_T, col_T, eid_T
+
+
+def coo_to_csr(row, col, nrows: int):
+    """-> (rowptr [nrows+1], col [E], eid [E]): CSR of a COO edge list, columns ascending inside a row, duplicate
+    edges in list order; eid = list index of every CSR non-zero."""
+    row, col = _i32(row), _i32(col)
+    E = row.size
+    rowptr = np.empty(nrows + 1, dtype=np.int32)
+    col_out = np.empty(E, dtype=np.int32)
+    eid = np.empty(E, dtype=np.int32)
+    _load().orc_coo_to_csr(E, nrows, _ptr(row), _ptr(col), _ptr(rowptr), _ptr(col_out), _ptr(eid))
+    return rowptr, col_out, eid
 
 
 def sddmm_dot(rowptr, col, U, Vt, H: int = 1, eid=None):

@@ -135,6 +135,37 @@ void orc_transpose(int32_t V, int32_t ncols, const int32_t* rowptr, const int32_
   free(next);
 }
 
+/* ---- CSR from a COO edge list (section 2.1.1: COO holds one (rowID, colID) pair per non-zero, CSR an offset
+ * array and the column ids row by row).  The non-zeros of row r are the edges with rowID r in ascending column
+ * order, equal columns (duplicate edges) in the order of the list; eid[p] = the list index of the non-zero at
+ * CSR position p.  Written as the definition: count per row, deal the edges out in list order, then a stable
+ * insertion sort by column inside every row. ---- */
+void orc_coo_to_csr(int64_t E, int32_t V, const int32_t* row, const int32_t* col, int32_t* rowptr, int32_t* col_out,
+                    int32_t* eid) {
+  int32_t* next = (int32_t*)calloc((size_t)V + 1, 4);
+  for (int32_t i = 0; i <= V; ++i) rowptr[i] = 0;
+  for (int64_t k = 0; k < E; ++k) rowptr[row[k] + 1]++;
+  for (int32_t i = 0; i < V; ++i) rowptr[i + 1] += rowptr[i];
+  for (int32_t i = 0; i < V; ++i) next[i] = rowptr[i];
+  for (int64_t k = 0; k < E; ++k) {
+    int32_t p = next[row[k]]++;
+    col_out[p] = col[k];
+    eid[p] = (int32_t)k;
+  }
+  for (int32_t i = 0; i < V; ++i)
+    for (int32_t p = rowptr[i] + 1; p < rowptr[i + 1]; ++p) {
+      int32_t c = col_out[p], e = eid[p], q = p;
+      while (q > rowptr[i] && col_out[q - 1] > c) {
+        col_out[q] = col_out[q - 1];
+        eid[q] = eid[q - 1];
+        --q;
+      }
+      col_out[q] = c;
+      eid[q] = e;
+    }
+  free(next);
+}
+
 /* ---- SDDMM: dW_e <- A (.) (dY X^T) (section 2.1.2), per head ----
  * out[k,h] = sum_{d<D} U[i, h*D+d] * Vt[col[k], h*D+d] for every non-zero k of row i. */
 void orc_sddmm_dot(int32_t V, const int32_t* rowptr, const int32_t* col, const int32_t* eid, int32_t H, int32_t D,

@@ -609,6 +609,34 @@ def test_gat_saved_tensors_give_the_row_side_gradient():
     assert np.abs(d_el).max() > 1e-2
 
 
+def test_coo_to_csr_hand_example_library_sort_and_round_trip():
+    """Section 2.1.1's two formats: a seven-edge list worked out by hand (a duplicate edge, an empty row), the
+    same order from numpy's lexicographic sort with the list index as the last key, the dense matrix of both
+    forms, and CSR -> shuffled COO -> CSR giving the CSR back."""
+    row = np.array([2, 0, 2, 1, 0, 2, 2], dtype=np.int32)
+    col = np.array([1, 3, 0, 1, 3, 1, 4], dtype=np.int32)
+    rowptr, c, eid = oracle.coo_to_csr(row, col, 4)
+    assert rowptr.tolist() == [0, 2, 3, 7, 7]      # rows 0..3 hold 2, 1, 4, 0 edges
+    assert c.tolist() == [3, 3, 1, 0, 1, 1, 4]     # ascending inside a row
+    assert eid.tolist() == [1, 4, 3, 2, 0, 5, 6]   # the two (0,3) and the two (2,1) edges keep their list order
+    r = np.random.default_rng(77)
+    for V, ncols, E in ((1, 1, 5), (9, 4, 60), (50, 70, 400), (30, 30, 0)):
+        row = r.integers(0, V, size=E).astype(np.int32)
+        col = r.integers(0, ncols, size=E).astype(np.int32)
+        rowptr, c, eid = oracle.coo_to_csr(row, col, V)
+        order = np.lexsort((np.arange(E), col, row))
+        assert np.array_equal(eid, order.astype(np.int32))
+        assert np.array_equal(c, col[order]) and np.array_equal(np.diff(rowptr), np.bincount(row, minlength=V))
+        A = np.zeros((V, ncols))
+        np.add.at(A, (row, col), 1.0)
+        assert np.array_equal(dense_from(rowptr, c, np.repeat(np.arange(V), np.diff(rowptr)), ncols), A)
+    rowptr, col, row = small_graph(23, 19, 0.3, 5, empty_rows=(0, 7), dup=True)
+    perm = r.permutation(col.size)
+    rp2, c2, e2 = oracle.coo_to_csr(row[perm], col[perm], 23)
+    assert np.array_equal(rp2, rowptr) and np.array_equal(c2, col)
+    assert np.array_equal(np.sort(e2), np.arange(col.size)) and np.array_equal(row[perm][e2], row)
+
+
 def test_edge_gather_is_the_transposed_order():
     """The k-th non-zero of the transpose carries the value of non-zero eid[k]: with the pre-permuted values and no
     edge-id map the transposed SpMM gives the same result as with the map, and the dense transpose agrees."""
