@@ -25,8 +25,8 @@
  *    rows longer than 1024 non-zeros from a stream-ordered memory pool of the
  *    library's own (hipMallocFromPoolAsync / hipFreeAsync on `stream`; the pool
  *    keeps its memory, so only the first call on a device reaches the driver).
- *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose and
- *    hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
+ *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose,
+ *    hgnn_coo_to_csr and hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
  *  - A plan owns scratch that the calls using it write (staging rows, per-vertex
  *    tables, per-block partial outputs): calls that use the same plan must be ordered
  *    on one stream, or otherwise not overlap in time; different plans are independent.
@@ -106,6 +106,17 @@ hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream);
  * non-zero).  Inside a row of A^T entries keep their order in A (a stable sort
  * by column).  g->eid must be NULL.  Allocates temporary storage, synchronizes. */
 hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int32_t* col_T, int32_t* eid_T, void* stream);
+
+/* CSR from a COO edge list (section 2.1.1: COO stores one (rowID, colID) pair per non-zero, CSR the
+ * offset array and the column ids row by row).  Inputs (device): row [nnz], col [nnz] in any order,
+ * 0 <= row < nrows, 0 <= col < ncols; duplicate pairs are separate edges.  Outputs (device, caller
+ * allocated): rowptr [nrows+1], col_out [nnz] (ascending inside a row, duplicates in list order: a stable
+ * sort by (row, col)) and, unless NULL, eid [nnz] = the list position of every CSR non-zero, so that an
+ * edge tensor given in list order is read through it (hgnn_csr.eid) or reordered once
+ * (hgnn_edge_to_transposed with a graph that carries this map).  Allocates temporary storage,
+ * synchronizes.  HGNN_EINVAL for an id out of range (the outputs are then unspecified). */
+hgnn_status hgnn_coo_to_csr(int32_t nrows, int32_t ncols, int64_t nnz, const int32_t* row, const int32_t* col,
+                            int32_t* rowptr, int32_t* col_out, int32_t* eid, void* stream);
 
 /* Brings an edge tensor into the edge order of the transposed graph: t_T[k,h] = t[gt->eid[k], h]
  * (fp16 [nnz][H], not in place).  For edge values that do not change between steps (the

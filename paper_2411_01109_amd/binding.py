@@ -19,7 +19,7 @@ HGNN_SUM, HGNN_MEAN = 0, 1
 HGNN_SDDMM_DOT, HGNN_SDDMM_GAT_SCORE = 0, 1
 
 EXPORTS = (
-    "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_plan_create",
+    "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_coo_to_csr", "hgnn_plan_create",
     "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks",
     "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
@@ -72,6 +72,7 @@ def load() -> ctypes.CDLL:
     lib.hgnn_last_error.argtypes = []
     lib.hgnn_csr_validate.argtypes = [csr, vp]
     lib.hgnn_transpose.argtypes = [csr, vp, vp, vp, vp]
+    lib.hgnn_coo_to_csr.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
     lib.hgnn_plan_create.argtypes = [csr, i32, i32, i32, i32, ctypes.POINTER(vp), vp]
     lib.hgnn_plan_num_segments.restype = i64
     lib.hgnn_plan_num_segments.argtypes = [vp]
@@ -200,6 +201,20 @@ def hgnn_transpose(g: Csr, stream=None) -> Csr:
     eid_T = torch.empty(g.nnz, dtype=torch.int32, device=dev)
     _check(load().hgnn_transpose(g.ref, rowptr_T.data_ptr(), col_T.data_ptr(), eid_T.data_ptr(), _stream(stream)))
     return Csr(rowptr_T, col_T, ncols=g.nrows, eid=eid_T)
+
+
+def hgnn_coo_to_csr(row: torch.Tensor, col: torch.Tensor, nrows: int, ncols: int, want_eid: bool = True, stream=None):
+    """-> (Csr without an edge-id map, eid or None): CSR of a COO edge list; eid[k] = list position of CSR non-zero k."""
+    if row.numel() != col.numel():
+        raise ValueError("row and col must have the same length")
+    dev = row.device
+    nnz = row.numel()
+    rowptr = torch.empty(nrows + 1, dtype=torch.int32, device=dev)
+    col_out = torch.empty(nnz, dtype=torch.int32, device=dev)
+    eid = torch.empty(nnz, dtype=torch.int32, device=dev) if want_eid else None
+    _check(load().hgnn_coo_to_csr(nrows, ncols, nnz, _ptr(row, torch.int32), _ptr(col, torch.int32), rowptr.data_ptr(),
+                                  col_out.data_ptr(), None if eid is None else eid.data_ptr(), _stream(stream)))
+    return Csr(rowptr, col_out, ncols=ncols), eid
 
 
 def hgnn_plan_create(g: Csr, seg_edges: int = 256, max_F: int = 128, max_H: int = 8, col_blocks: int = 1,

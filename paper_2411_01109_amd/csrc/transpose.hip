@@ -1,6 +1,7 @@
 // CSR of the transposed graph plus the edge-id map, for the backward SpMM dX <- A_w^T dY
-// (paper section 2.1.2).  One-off set-up: a stable radix sort of the non-zeros by column id
-// (rocPRIM's device radix sort is the library step), then offsets by binary search.
+// (paper section 2.1.2), and CSR from a COO edge list (section 2.1.1).  One-off set-up: a stable radix sort of
+// the non-zeros by column id, or by (row id, column id) (rocPRIM's device radix sort is the library step), then
+// offsets by binary search.
 #include <string.h>
 
 #include <rocprim/device/device_radix_sort.hpp>
@@ -25,6 +26,27 @@ __global__ void offsets_kernel(const int* __restrict__ sorted_col, int64_t nnz, 
     else hi = mid;
   }
   rowptr_T[j] = int(lo);
+}
+
+// COO -> CSR: key = (row, col) in one 64-bit word, so that one stable sort orders the edges by row, then column,
+// then position in the list; bad receives 1 when an id is out of range (such an edge gets key 0)
+__global__ void coo_keys_kernel(const int* __restrict__ row, const int* __restrict__ col, int64_t nnz, int nrows, int ncols,
+                                uint64_t* __restrict__ keys, int* __restrict__ ids, int* __restrict__ bad) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k >= nnz) return;
+  const int r = row[k], c = col[k];
+  const bool ok = r >= 0 && r < nrows && c >= 0 && c < ncols;
+  if (!ok) atomicOr(bad, 1);
+  keys[k] = ok ? (uint64_t(uint32_t(r)) << 32) | uint64_t(uint32_t(c)) : 0;
+  ids[k] = int(k);
+}
+
+__global__ void coo_split_kernel(const uint64_t* __restrict__ keys, int64_t nnz, int* __restrict__ row_sorted,
+                                 int* __restrict__ col_out) {
+  int64_t k = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (k >= nnz) return;
+  row_sorted[k] = int(keys[k] >> 32);
+  col_out[k] = int(uint32_t(keys[k]));
 }
 
 // col_T[k'] = row of the non-zero eid_T[k'] of A (upper bound over rowptr, minus one)
@@ -104,6 +126,82 @@ extern "C" hgnn_status hgnn_transpose(const hgnn_csr* g, int32_t* rowptr_T, int3
     rc = fail(e == hipErrorOutOfMemory ? HGNN_ENOMEM : HGNN_EHIP, "hgnn_transpose: %s", hipGetErrorString(e));
   (void)hipFree(ids);
   (void)hipFree(keys_out);
+  (void)hipFree(tmp);
+  return rc;
+}
+
+extern "C" hgnn_status hgnn_coo_to_csr(int32_t nrows, int32_t ncols, int64_t nnz, const int32_t* row, const int32_t* col,
+                                       int32_t* rowptr, int32_t* col_out, int32_t* eid, void* stream) {
+  clear_error();
+  const char* who = "hgnn_coo_to_csr";
+  HGNN_REQUIRE(nrows >= 0 && ncols >= 0 && nnz >= 0, HGNN_EINVAL, "%s: negative size", who);
+  HGNN_REQUIRE(nnz < (int64_t(1) << 31), HGNN_EINVAL, "%s: nnz = %lld does not fit int32", who, (long long)nnz);
+  HGNN_REQUIRE(rowptr != nullptr, HGNN_EINVAL, "%s: rowptr is NULL", who);
+  HGNN_REQUIRE(nnz == 0 || (row && col && col_out), HGNN_EINVAL, "%s: row, col or col_out is NULL", who);
+  HGNN_REQUIRE(nnz == 0 || (nrows > 0 && ncols > 0), HGNN_EINVAL, "%s: edges in a graph without rows or columns", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (nnz == 0) {
+    HGNN_HIP(hipMemsetAsync(rowptr, 0, sizeof(int) * (size_t(nrows) + 1), s));
+    HGNN_HIP(hipStreamSynchronize(s));
+    return HGNN_OK;
+  }
+  int row_bits = 1, col_bits = 1;
+  while ((int64_t(1) << row_bits) < int64_t(nrows)) ++row_bits;
+  while ((int64_t(1) << col_bits) < int64_t(ncols)) ++col_bits;
+  const size_t E = size_t(nnz);
+  uint64_t *keys = nullptr, *keys_out = nullptr;
+  int *ids = nullptr, *ids_out = nullptr, *row_sorted = nullptr, *bad = nullptr;
+  void* tmp = nullptr;
+  size_t tmp_bytes = 0;
+  int hbad = 0;
+  hgnn_status rc = HGNN_OK;
+  hipError_t e = hipMalloc(&keys, 8 * E);
+  if (e == hipSuccess) e = hipMalloc(&keys_out, 8 * E);
+  if (e == hipSuccess) e = hipMalloc(&ids, 4 * E);
+  if (e == hipSuccess) e = hipMalloc(&row_sorted, 4 * E);
+  if (e == hipSuccess) e = hipMalloc(&bad, 4);
+  if (e == hipSuccess && !eid) e = hipMalloc(&ids_out, 4 * E);
+  int* order = eid ? eid : ids_out;
+  if (e == hipSuccess) e = hipMemsetAsync(bad, 0, 4, s);
+  if (e == hipSuccess) {
+    coo_keys_kernel<<<dim3(unsigned(ceil_div(nnz, kBlock))), kBlock, 0, s>>>(row, col, nnz, nrows, ncols, keys, ids, bad);
+    // the columns occupy the low word: the bits between col_bits and 32 are zero in every key and are skipped by
+    // sorting the two fields one after the other (least significant field first; the sort is stable)
+    e = rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, keys_out, ids, order, E, 0u, unsigned(col_bits), s);
+  }
+  if (e == hipSuccess) e = hipMalloc(&tmp, tmp_bytes > 0 ? tmp_bytes : 16);
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, keys_out, ids, order, E, 0u, unsigned(col_bits), s);
+  if (e == hipSuccess) {
+    size_t need = 0;
+    e = rocprim::radix_sort_pairs(nullptr, need, keys_out, keys, order, ids, E, 32u, unsigned(32 + row_bits), s);
+    if (e == hipSuccess && need > tmp_bytes) {
+      (void)hipStreamSynchronize(s);
+      (void)hipFree(tmp);
+      tmp = nullptr;
+      tmp_bytes = need;
+      e = hipMalloc(&tmp, tmp_bytes);
+    }
+  }
+  if (e == hipSuccess)
+    e = rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_out, keys, order, ids, E, 32u, unsigned(32 + row_bits), s);
+  if (e == hipSuccess) {  // sorted keys are back in `keys`, the order in `ids`
+    coo_split_kernel<<<dim3(unsigned(ceil_div(nnz, kBlock))), kBlock, 0, s>>>(keys, nnz, row_sorted, col_out);
+    offsets_kernel<<<dim3(unsigned(ceil_div(int64_t(nrows) + 1, kBlock))), kBlock, 0, s>>>(row_sorted, nnz, nrows, rowptr);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess && eid) e = hipMemcpyAsync(eid, ids, 4 * E, hipMemcpyDeviceToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(&hbad, bad, 4, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess)
+    rc = fail(e == hipErrorOutOfMemory ? HGNN_ENOMEM : HGNN_EHIP, "%s: %s", who, hipGetErrorString(e));
+  else if (hbad)
+    rc = fail(HGNN_EINVAL, "%s: a row id outside [0, nrows) or a column id outside [0, ncols)", who);
+  (void)hipFree(keys);
+  (void)hipFree(keys_out);
+  (void)hipFree(ids);
+  (void)hipFree(ids_out);
+  (void)hipFree(row_sorted);
+  (void)hipFree(bad);
   (void)hipFree(tmp);
   return rc;
 }

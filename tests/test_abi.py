@@ -170,3 +170,16 @@ def test_product_path_has_no_oracle_or_fallback():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2411_01109_amd" not in text and "libhgnn" not in text and "hgnn.h" not in text, f
+
+
+def test_coo_to_csr_argument_errors_are_caught_on_the_host(lib, hgnn):
+    """Fake non-NULL device addresses: each call must return before anything is launched."""
+    R, C, P, O = 0x1000, 0x2000, 0x3000, 0x4000
+    EINVAL = hgnn.HGNN_EINVAL
+    assert lib.hgnn_coo_to_csr(4, 4, 8, R, C, None, O, None, None) == EINVAL      # rowptr NULL
+    assert lib.hgnn_coo_to_csr(4, 4, 8, None, C, P, O, None, None) == EINVAL      # row NULL with edges
+    assert lib.hgnn_coo_to_csr(4, 4, 8, R, C, P, None, None, None) == EINVAL      # col_out NULL with edges
+    assert lib.hgnn_coo_to_csr(-1, 4, 0, R, C, P, O, None, None) == EINVAL        # negative size
+    assert lib.hgnn_coo_to_csr(0, 4, 8, R, C, P, O, None, None) == EINVAL         # edges without rows
+    assert lib.hgnn_coo_to_csr(4, 4, 1 << 31, R, C, P, O, None, None) == EINVAL   # nnz beyond int32
+    assert b"int32" in lib.hgnn_last_error()

@@ -114,3 +114,61 @@ def test_random_plan_and_transpose_bit_exact(hgnn, dev, seed):
     for k in refT:
         assert np.array_equal(gotT[k], refT[k]), k
     hgnn.hgnn_plan_destroy(pt)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_coo_to_csr_bit_exact(hgnn, dev, seed):
+    """A drawn graph's edges in shuffled list order, with the duplicates the generator makes: rowptr, columns and
+    the list positions against the oracle bit for bit; the result passes the library's own validation and carries
+    an edge tensor given in list order to the right non-zeros."""
+    c = draw(700 + seed)
+    print(f"coo sweep {c}", flush=True)
+    V = c["V"]
+    ncols = V + seed % 5
+    rowptr, col = rand_graph(V, ncols, c["avg"], 1200 + seed, hubs=c["hubs"], empties=c["empties"])
+    E = col.size
+    r = np.random.default_rng(seed)
+    perm = r.permutation(E)
+    row_l, col_l = np.repeat(np.arange(V, dtype=np.int32), np.diff(rowptr))[perm], col[perm]
+    ref_rp, ref_col, ref_eid = oracle.coo_to_csr(row_l, col_l, V)
+    g, eid = hgnn.hgnn_coo_to_csr(up(row_l, dev), up(col_l, dev), V, ncols)
+    assert np.array_equal(down(g.rowptr), ref_rp) and np.array_equal(down(g.col), ref_col)
+    assert np.array_equal(down(eid), ref_eid)
+    assert np.array_equal(ref_rp, rowptr) and np.array_equal(ref_col, col)  # the graph the list came from
+    hgnn.hgnn_csr_validate(g)
+    g2, none = hgnn.hgnn_coo_to_csr(up(row_l, dev), up(col_l, dev), V, ncols, want_eid=False)
+    assert none is None and np.array_equal(down(g2.col), ref_col)
+    if E > 0:  # values given per list entry reach their non-zero through the map
+        w_l = f16(r.standard_normal((E, 1)))
+        X = f16(r.standard_normal((ncols, 16)))
+        ref, sabs = oracle.spmm(rowptr, col, X, w=w_l, eid=ref_eid, want_sabs=True)
+        Y = torch.empty((V, 16), dtype=torch.float16, device=dev)
+        hgnn.hgnn_spmm(hgnn.Csr(g.rowptr, g.col, ncols=ncols, eid=eid), up(w_l, dev), 1, up(X, dev), Y)
+        compare("values in list order", down(Y), ref, sabs)
+        bad = row_l.copy()
+        bad[E // 2] = V  # one row id out of range
+        with pytest.raises(hgnn.HgnnError):
+            hgnn.hgnn_coo_to_csr(up(bad, dev), up(col_l, dev), V, ncols)
+
+
+def test_coo_to_csr_full_size_round_trip(hgnn, dev):
+    """Config 4's 62 M edges as a shuffled list: the library must give the graph back (the columns of the
+    generator's CSR are ascending inside a row, so the result is unique up to the order of duplicate edges, which
+    the edge-id map must resolve in list order)."""
+    import workloads as wl
+    w = wl.gcn_large()
+    print(f"coo full size {w.name}: E = {w.col.size}", flush=True)
+    E, V = w.col.size, w.V
+    perm = torch.randperm(E, device=dev, generator=torch.Generator(device=dev).manual_seed(3))
+    row = torch.repeat_interleave(torch.arange(V, dtype=torch.int32, device=dev),
+                                  torch.from_numpy(np.diff(w.rowptr)).to(dev))
+    col = up(w.col, dev)
+    g, eid = hgnn.hgnn_coo_to_csr(row[perm].contiguous(), col[perm].contiguous(), V, V)
+    assert torch.equal(g.rowptr, up(w.rowptr, dev)) and torch.equal(g.col, col)
+    # eid[k] is a list position holding the same (row, col) pair, every position once, duplicates in list order
+    back = perm[eid.long()]  # position in the original CSR of the list entry chosen for CSR slot k
+    assert torch.equal(col[back], col) and torch.equal(row[back], row)
+    assert torch.equal(torch.sort(eid).values, torch.arange(E, dtype=torch.int32, device=dev))
+    same = (row[1:] == row[:-1]) & (col[1:] == col[:-1])
+    assert bool(torch.all(eid[1:][same] > eid[:-1][same]))
+    hgnn.hgnn_csr_validate(g)
