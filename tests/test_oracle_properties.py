@@ -113,3 +113,23 @@ def test_segment_plan_tiles_the_edges(gr, S):
     disc, _ = oracle.spmm_discretized(rowptr, col, X, S)
     pieces = np.ceil(np.diff(rowptr) / S) + 1
     assert np.all(np.abs(disc.astype(np.float64) - exact) <= (pieces[:, None] + 1) * 2.0 ** -11 * (sabs + 1e-30) + 2.0 ** -24)
+
+
+@settings(**SETTINGS)
+@given(graphs())
+def test_coo_list_in_any_order_gives_the_same_csr_and_two_transposes_do_too(gr):
+    V, ncols, rowptr, col, row, r = gr
+    perm = r.permutation(col.size)
+    rp, c, eid = oracle.coo_to_csr(row[perm], col[perm], V)
+    assert np.array_equal(rp, rowptr) and np.array_equal(c, col)
+    assert sorted(eid.tolist()) == list(range(col.size))
+    assert np.array_equal(row[perm][eid], row) and np.array_equal(col[perm][eid], col)
+    # equal (row, col) pairs keep their list order
+    same = (row[1:] == row[:-1]) & (col[1:] == col[:-1])
+    assert np.all(eid[1:][same] > eid[:-1][same])
+    # the same sort done another way: rows of the list in list order (an unsorted "CSR"), transposed twice
+    order = np.argsort(row[perm], kind="stable")
+    rT, cT, eT = oracle.transpose(rp, col[perm][order].astype(np.int32), ncols)
+    r2, c2, e2 = oracle.transpose(rT, cT, V)
+    assert np.array_equal(r2, rowptr) and np.array_equal(c2, col)
+    assert np.array_equal(order[eT[e2]].astype(np.int32), eid)
