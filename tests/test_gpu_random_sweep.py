@@ -172,3 +172,26 @@ def test_coo_to_csr_full_size_round_trip(hgnn, dev):
     same = (row[1:] == row[:-1]) & (col[1:] == col[:-1])
     assert bool(torch.all(eid[1:][same] > eid[:-1][same]))
     hgnn.hgnn_csr_validate(g)
+
+
+def test_coo_to_csr_degenerate_lists(hgnn, dev):
+    empty = torch.empty(0, dtype=torch.int32, device=dev)
+    g, eid = hgnn.hgnn_coo_to_csr(empty, empty, 5, 3)
+    assert down(g.rowptr).tolist() == [0] * 6 and g.nnz == 0 and eid.numel() == 0
+    g, eid = hgnn.hgnn_coo_to_csr(empty, empty, 0, 0)
+    assert down(g.rowptr).tolist() == [0]
+    # one pair repeated: the list order is the only order there is
+    row = torch.full((1000,), 2, dtype=torch.int32, device=dev)
+    col = torch.full((1000,), 1, dtype=torch.int32, device=dev)
+    g, eid = hgnn.hgnn_coo_to_csr(row, col, 4, 2)
+    assert down(g.rowptr).tolist() == [0, 0, 0, 1000, 1000] and np.all(down(g.col) == 1)
+    assert np.array_equal(down(eid), np.arange(1000, dtype=np.int32))
+    # the largest ids of a graph whose sizes are not powers of two, and a negative id
+    row = torch.tensor([4, 0, 4], dtype=torch.int32, device=dev)
+    col = torch.tensor([6, 6, 0], dtype=torch.int32, device=dev)
+    g, eid = hgnn.hgnn_coo_to_csr(row, col, 5, 7)
+    assert down(g.rowptr).tolist() == [0, 1, 1, 1, 1, 3] and down(g.col).tolist() == [6, 0, 6] and down(eid).tolist() == [1, 2, 0]
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_coo_to_csr(row, torch.tensor([6, -1, 0], dtype=torch.int32, device=dev), 5, 7)
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_coo_to_csr(row, torch.tensor([7, 6, 0], dtype=torch.int32, device=dev), 5, 7)
