@@ -22,9 +22,10 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  *    compute entry points are asynchronous on that stream and never synchronize;
  *    those that take a plan never allocate.  hgnn_spmm (no plan) takes scratch for
- *    rows longer than 1024 non-zeros from a stream-ordered memory pool of the
- *    library's own (hipMallocFromPoolAsync / hipFreeAsync on `stream`; the pool
- *    keeps its memory, so only the first call on a device reaches the driver).
+ *    its longest rows (above 8 times the mean, the threshold kept within 256..1024
+ *    non-zeros) from a stream-ordered memory pool of the library's own
+ *    (hipMallocFromPoolAsync / hipFreeAsync on `stream`; the pool keeps its memory,
+ *    so only the first call on a device reaches the driver).
  *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose,
  *    hgnn_coo_to_csr and hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
  *  - A plan owns scratch that the calls using it write (staging rows, per-vertex
