@@ -234,6 +234,7 @@ struct hgnn_plan {
   int32_t n_mid = 0;    // rows longer than mid_deg and at most big_deg (edge softmax: one wave each)
   int32_t mid_deg = 0;
   int32_t big_deg = 0;
+  int64_t listed_nnz = 0;  // non-zeros of the rows in mid_row and big_row (the rest belong to rows of at most mid_deg)
   int32_t max_F = 0, max_H = 0;
   int32_t* seg_row_lo = nullptr;    // [nseg]
   int32_t* seg_row_hi = nullptr;    // [nseg]

@@ -104,6 +104,23 @@ struct BigPred {  // row longer than a threshold
   __device__ bool operator()(int r) const { return rowptr[r + 1] - rowptr[r] > deg; }
 };
 
+// total[0] += the lengths of the listed rows
+__global__ void list_length_sum_kernel(const int* __restrict__ rowptr, const int* __restrict__ list, int n,
+                                       unsigned long long* __restrict__ total) {
+  __shared__ unsigned long long part[kBlock / kWave];
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  unsigned long long v = 0;
+  if (i < n) v = (unsigned long long)(rowptr[list[i] + 1] - rowptr[list[i]]);
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off);
+  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long t = 0;
+    for (int w = 0; w < kBlock / kWave; ++w) t += part[w];
+    if (t) atomicAdd(total, t);
+  }
+}
+
 constexpr int kRowsPerThread = 4;
 constexpr int kRowsPerBlock = kBlock * kRowsPerThread;
 
@@ -237,6 +254,21 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
     if (st != HGNN_OK) return st;
     st = compact_rows(MidPred{g->rowptr, p->mid_deg, p->big_deg}, g->nrows, &p->mid_row, &p->n_mid, s);
     if (st != HGNN_OK) return st;
+    if (p->n_mid + p->n_big > 0) {  // how many non-zeros the two lists hold: the edge-row kernels size their teams by the rest
+      unsigned long long* total = nullptr;
+      HGNN_HIP(hipMalloc(&total, sizeof(unsigned long long)));
+      hipError_t e = hipMemsetAsync(total, 0, sizeof(unsigned long long), s);
+      if (e == hipSuccess && p->n_mid > 0)
+        list_length_sum_kernel<<<dim3(unsigned(ceil_div(p->n_mid, kBlock))), kBlock, 0, s>>>(g->rowptr, p->mid_row, p->n_mid, total);
+      if (e == hipSuccess && p->n_big > 0)
+        list_length_sum_kernel<<<dim3(unsigned(ceil_div(p->n_big, kBlock))), kBlock, 0, s>>>(g->rowptr, p->big_row, p->n_big, total);
+      unsigned long long h = 0;
+      if (e == hipSuccess) e = hipMemcpyAsync(&h, total, sizeof(h), hipMemcpyDeviceToHost, s);
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      (void)hipFree(total);
+      if (e != hipSuccess) return fail(HGNN_EHIP, "hgnn_plan_create: %s", hipGetErrorString(e));
+      p->listed_nnz = int64_t(h);
+    }
     size_t nv = (size_t(g->nrows) + size_t(g->ncols)) * size_t(p->max_H);
     if (nv > 0) HGNN_HIP(hipMalloc(&p->vscratch, sizeof(float) * nv));
     if (g->nrows > 0) HGNN_HIP(hipMalloc(&p->vtab, sizeof(float) * 4 * size_t(g->nrows) * size_t(p->max_H)));

@@ -357,7 +357,12 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   }
   // lanes per row: about one 8-element vector per lane for the mean row (rowsum over an edge-id map
   // walks one non-zero per lane instead)
-  const double per_row = double(g->nnz) * ((OP == kSum && a.eid) ? 1.0 : H / 8.0) / double(g->nrows > 0 ? g->nrows : 1);
+  // (with a plan that lists the longer rows for the tiers below: the mean over the rows it does not list, which on
+  // a power-law graph is far below the mean over all rows)
+  double mean_len = double(g->nnz) / double(g->nrows > 0 ? g->nrows : 1);
+  if (p && p->n_mid + p->n_big > 0 && int64_t(p->n_mid) + p->n_big < g->nrows / 2)  // the listed rows are the exception
+    mean_len = double(g->nnz - p->listed_nnz) / double(g->nrows - p->n_mid - p->n_big);
+  const double per_row = mean_len * ((OP == kSum && a.eid) ? 1.0 : H / 8.0);
   int LR = 4;
   while (LR < kWave && LR < per_row) LR <<= 1;
   const int big = (p && p->n_big > 0) ? p->big_deg : 0;
