@@ -474,3 +474,25 @@ def test_edge_values_with_heads_aligned_or_not(hgnn, dev, H, shift):
         compare(f"transposed, {nb} block(s)", down(dX), refb, sabsb)
         hgnn.hgnn_plan_destroy(p)
         hgnn.hgnn_plan_destroy(pt)
+
+
+# ------------------------------------------------------------------ plan-free SpMM at its row-length thresholds
+@pytest.mark.parametrize("avg", [3, 40, 200])
+def test_plain_spmm_rows_at_the_group_wave_and_hub_thresholds(hgnn, dev, avg):
+    """hgnn_spmm hands a row to a lane group (up to 32 non-zeros), to the whole wave, or to the chunked hub kernels
+    (above 8 times the mean row length, the threshold held within 256..1024): rows whose lengths sit on and next to
+    every one of those borders, and on the 512-edge chunk border, in graphs of three densities."""
+    V, ncols, F = 900, 1300, 64
+    lengths = [31, 32, 33, 255, 256, 257, 8 * avg - 1, 8 * avg, 8 * avg + 1, 511, 512, 513, 1023, 1024, 1025, 1536, 1537]
+    hubs = tuple((20 + 7 * i, n) for i, n in enumerate(lengths))
+    rowptr, col = rand_graph(V, ncols, avg, 300 + avg, hubs=hubs, empties=(0, 1, 899))
+    r = np.random.default_rng(avg)
+    X = f16(r.standard_normal((ncols, F)))
+    w = f16(r.standard_normal((col.size, 1)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    for reduce in (0, 1):
+        for ww in (None, w):
+            ref, sabs = oracle.spmm(rowptr, col, X, w=ww, reduce=reduce, want_sabs=True)
+            Y = torch.full((V, F), 5.0, dtype=torch.float16, device=dev)
+            hgnn.hgnn_spmm(g, None if ww is None else up(ww, dev), 1, up(X, dev), Y, op=reduce)
+            compare(f"plain, avg {avg}, reduce {reduce}, w {ww is not None}", down(Y), ref, sabs)
