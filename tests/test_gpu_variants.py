@@ -496,3 +496,41 @@ def test_plain_spmm_rows_at_the_group_wave_and_hub_thresholds(hgnn, dev, avg):
             Y = torch.full((V, F), 5.0, dtype=torch.float16, device=dev)
             hgnn.hgnn_spmm(g, None if ww is None else up(ww, dev), 1, up(X, dev), Y, op=reduce)
             compare(f"plain, avg {avg}, reduce {reduce}, w {ww is not None}", down(Y), ref, sabs)
+
+
+# ------------------------------------------------------------------ edge-row kernels at their tier borders
+@pytest.mark.parametrize("H,avg", [(1, 3), (4, 3), (4, 60), (8, 12)])
+def test_edge_softmax_and_row_sums_at_the_tier_borders(hgnn, dev, H, avg):
+    """Rows on and next to every border between the tiers of the edge-row kernels: what a lane team keeps in
+    registers (8 * 2 * team / H edges for teams of 4 to 64 lanes), the plan's 32- and 2048-edge thresholds, and a
+    row that starts at an odd offset into a 16-byte vector."""
+    V = 700
+    lengths = [1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
+               1023, 1024, 1025, 2047, 2048, 2049, 4097]
+    hubs = tuple((10 + 13 * i, n) for i, n in enumerate(lengths))
+    rowptr, col = rand_graph(V, V, avg, 500 + H + avg, hubs=hubs, empties=(0, 3, 699))
+    E = col.size
+    r = np.random.default_rng(H + avg)
+    e16, da16 = f16(3 * r.standard_normal((E, H))), f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    p = hgnn.hgnn_plan_create(g, 256, 64, 8)
+    rows = np.repeat(np.arange(V), np.diff(rowptr))
+    ref_a = oracle.edge_softmax(rowptr, e16.astype(np.float64))
+    for plan in (p, None):
+        alpha = torch.full((E, H), -1.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_softmax(g, plan, H, up(e16, dev), alpha)
+        compare("alpha", down(alpha), ref_a, np.maximum(ref_a, 2.0 ** -14), rel_elem=2e-2)
+        a16 = down(alpha)
+        de = torch.empty((E, H), dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_softmax_bwd(g, plan, H, alpha, up(da16, dev), de, e=up(e16, dev))
+        ref_de = oracle.edge_softmax_bwd(rowptr, a16.astype(np.float64), da16.astype(np.float64), e=e16.astype(np.float64))
+        t_abs = np.zeros((V, H))
+        np.add.at(t_abs, rows, np.abs(a16.astype(np.float64) * da16.astype(np.float64)))
+        compare("de", down(de), ref_de, a16.astype(np.float64) * (np.abs(da16.astype(np.float64)) + t_abs[rows]) + 2.0 ** -14)
+        out = torch.empty((V, H), dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_rowsum(g, plan, H, up(da16, dev), out)
+        ref_s, abs_s = np.zeros((V, H)), np.zeros((V, H))
+        np.add.at(ref_s, rows, da16.astype(np.float64))
+        np.add.at(abs_s, rows, np.abs(da16.astype(np.float64)))
+        compare("row sums", down(out), ref_s, abs_s)
+    hgnn.hgnn_plan_destroy(p)
