@@ -224,6 +224,8 @@ __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane,
 }  // namespace hgnn
 
 // The plan object behind the opaque handle of the C ABI.
+constexpr int kHubEdges = 2048;  // non-zeros per chunk of a long row in the edge-row kernels
+
 struct hgnn_plan {
   int32_t nrows = 0, ncols = 0;
   int64_t nnz = 0;
@@ -243,6 +245,14 @@ struct hgnn_plan {
   int32_t* split_seg_hi = nullptr;  // [n_split]
   int32_t* big_row = nullptr;       // [n_big]
   int32_t* mid_row = nullptr;       // [n_mid]
+  // the rows of big_row cut into chunks of kHubEdges non-zeros for the edge-row kernels (softmax, its backward, row
+  // sums): a workgroup per chunk leaves partial results, a second pass combines those of a row
+  int32_t n_hub_chunks = 0;
+  int32_t* hub_chunk_row = nullptr;    // [n_hub_chunks] the row a chunk belongs to
+  int32_t* hub_chunk_first = nullptr;  // [n_hub_chunks] slot of the first chunk of that row (slot - first = chunk number)
+  int32_t* hub_chunk_count = nullptr;  // [n_hub_chunks] chunks of that row
+  int32_t* big_first = nullptr;        // [n_big] slot of the first chunk of big_row[i]
+  float* hub_part = nullptr;           // [n_hub_chunks][max_H][2] partial results
   hgnn_half* staging = nullptr;     // [2][2*nseg][max_F] (second set: masked vectors of the saving GAT pass)
   float* stage_mz = nullptr;        // [2*nseg][max_H][2] softmax (max, sum) of the staged pieces of the fused GAT pass, then [2*nseg][max_H] masked sums
   float* vscratch = nullptr;        // [(nrows + ncols) * max_H] fp32

@@ -254,6 +254,35 @@ hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bo
     if (st != HGNN_OK) return st;
     st = compact_rows(MidPred{g->rowptr, p->mid_deg, p->big_deg}, g->nrows, &p->mid_row, &p->n_mid, s);
     if (st != HGNN_OK) return st;
+    if (p->n_big > 0) {  // chunk table of the long rows (a short list: built on the host)
+      std::vector<int> rows(size_t(p->n_big)), rp(size_t(g->nrows) + 1);
+      HGNN_HIP(hipMemcpyAsync(rows.data(), p->big_row, sizeof(int) * rows.size(), hipMemcpyDeviceToHost, s));
+      HGNN_HIP(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int) * rp.size(), hipMemcpyDeviceToHost, s));
+      HGNN_HIP(hipStreamSynchronize(s));
+      std::vector<int> c_row, c_first, c_count, first(size_t(p->n_big));
+      for (size_t i = 0; i < rows.size(); ++i) {
+        const int deg = rp[size_t(rows[i]) + 1] - rp[size_t(rows[i])];
+        const int nch = (deg + kHubEdges - 1) / kHubEdges;
+        first[i] = int(c_row.size());
+        for (int c = 0; c < nch; ++c) {
+          c_row.push_back(rows[i]);
+          c_first.push_back(first[i]);
+          c_count.push_back(nch);
+        }
+      }
+      p->n_hub_chunks = int32_t(c_row.size());
+      const size_t nc = c_row.size();
+      HGNN_HIP(hipMalloc(&p->hub_chunk_row, sizeof(int) * nc));
+      HGNN_HIP(hipMalloc(&p->hub_chunk_first, sizeof(int) * nc));
+      HGNN_HIP(hipMalloc(&p->hub_chunk_count, sizeof(int) * nc));
+      HGNN_HIP(hipMalloc(&p->big_first, sizeof(int) * first.size()));
+      HGNN_HIP(hipMalloc(&p->hub_part, sizeof(float) * 2 * nc * size_t(p->max_H)));
+      HGNN_HIP(hipMemcpyAsync(p->hub_chunk_row, c_row.data(), sizeof(int) * nc, hipMemcpyHostToDevice, s));
+      HGNN_HIP(hipMemcpyAsync(p->hub_chunk_first, c_first.data(), sizeof(int) * nc, hipMemcpyHostToDevice, s));
+      HGNN_HIP(hipMemcpyAsync(p->hub_chunk_count, c_count.data(), sizeof(int) * nc, hipMemcpyHostToDevice, s));
+      HGNN_HIP(hipMemcpyAsync(p->big_first, first.data(), sizeof(int) * first.size(), hipMemcpyHostToDevice, s));
+      HGNN_HIP(hipStreamSynchronize(s));  // the host vectors go out of scope
+    }
     if (p->n_mid + p->n_big > 0) {  // how many non-zeros the two lists hold: the edge-row kernels size their teams by the rest
       unsigned long long* total = nullptr;
       HGNN_HIP(hipMalloc(&total, sizeof(unsigned long long)));
@@ -348,6 +377,11 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->split_seg_lo);
   (void)hipFree(p->split_seg_hi);
   (void)hipFree(p->big_row);
+  (void)hipFree(p->hub_chunk_row);
+  (void)hipFree(p->hub_chunk_first);
+  (void)hipFree(p->hub_chunk_count);
+  (void)hipFree(p->big_first);
+  (void)hipFree(p->hub_part);
   (void)hipFree(p->mid_row);
   (void)hipFree(p->staging);
   (void)hipFree(p->stage_mz);

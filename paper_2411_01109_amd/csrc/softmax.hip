@@ -3,7 +3,8 @@
 // The scores of one row (neighbourhood) are the contiguous slice e[rowptr[i]*H, rowptr[i+1]*H),
 // element j of the whole tensor belonging to head j % H.  A "team" of lanes owns a row: a
 // sub-wave group of LR lanes (LR chosen from the mean row length, so short rows do not idle a
-// whole wave), or a whole 1024-thread workgroup for rows longer than the plan's threshold.
+// whole wave) or a whole wave; rows longer than the plan's threshold are cut into chunks, a
+// workgroup each, whose partial results a second launch combines.
 // Every lane moves 16 bytes (8 halves) per access: the slice is walked in 8-element vectors
 // aligned to the tensor's base, the ragged first and last vector are masked, and because H
 // divides 8 the head of each of a lane's 8 elements is fixed.  A row that fits the lanes'
@@ -14,7 +15,6 @@
 namespace hgnn {
 
 constexpr int kKeepVec = 2;     // 8-element vectors per lane held in registers
-constexpr int kBigBlock = 1024; // threads given to one long row
 constexpr int kTeamThreads = 64;  // workgroup size of the team kernel: its waves never meet, so one wave each
 
 struct EdgeRowArgs {
@@ -72,29 +72,6 @@ struct SubWaveTeam {  // LR consecutive lanes of a wave
   template <int H, bool IS_MAX>
   __device__ __forceinline__ void reduce(float (&v)[H]) const {
     team_reduce<LR, H, IS_MAX>(v);
-  }
-};
-
-struct BlockTeam {  // a whole workgroup of kBigBlock threads
-  static constexpr int size = kBigBlock;
-  int rank;
-  float* sm;  // [kBigBlock / 64][8]
-  __device__ BlockTeam(float* s) : rank(threadIdx.x), sm(s) {}
-  template <int H, bool IS_MAX>
-  __device__ __forceinline__ void reduce(float (&v)[H]) const {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    team_reduce<kWave, H, IS_MAX>(v);
-    __syncthreads();  // protects sm against the previous use
-    if (lane == 0)
-#pragma unroll
-      for (int h = 0; h < H; ++h) sm[wave * 8 + h] = v[h];
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < H; ++h) {
-      float r = sm[h];
-      for (int w = 1; w < kBigBlock / kWave; ++w) r = IS_MAX ? fmaxf(r, sm[w * 8 + h]) : r + sm[w * 8 + h];
-      v[h] = r;
-    }
   }
 };
 
@@ -289,15 +266,177 @@ __global__ __launch_bounds__(kBlock) void edge_row_team_kernel(EdgeRowArgs a) {
   }
 }
 
+// ---- long rows in chunks ------------------------------------------------------------------------------
+// A row above the plan's long-row threshold is cut into chunks of kHubEdges non-zeros (the plan lists them): a
+// workgroup of kHubThreads per chunk leaves the chunk's partial result per head -- (max, sum of exp) for the
+// softmax, sum of alpha * dalpha for its backward, the sum for the row sums -- and a second launch combines the
+// partials of a row (a few dozen at most) and writes the chunk's outputs, or the row's sum.  The latency of a long
+// row is then that of one chunk, and a graph's longest rows keep many compute units busy instead of one each.
+constexpr int kHubThreads = 256;
+
+struct HubChunks {
+  const int* row;    // [n] row of the chunk
+  const int* first;  // [n] slot of the first chunk of that row
+  const int* count;  // [n] chunks of that row
+  float* part;       // [n][H][2]
+};
+
+template <int H, bool IS_MAX>
+__device__ __forceinline__ void hub_block_reduce(float (&v)[H], float* sm) {  // sm: [kHubThreads / kWave][8]
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  team_reduce<kWave, H, IS_MAX>(v);
+  __syncthreads();  // protects sm against the previous use
+  if (lane == 0)
+#pragma unroll
+    for (int h = 0; h < H; ++h) sm[wave * 8 + h] = v[h];
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < H; ++h) {
+    float r = sm[h];
+    for (int w = 1; w < kHubThreads / kWave; ++w) r = IS_MAX ? fmaxf(r, sm[w * 8 + h]) : r + sm[w * 8 + h];
+    v[h] = r;
+  }
+}
+
+// the chunk's non-zeros [beg, end) of its row
+__device__ __forceinline__ void hub_chunk_range(const EdgeRowArgs& a, const HubChunks& c, int slot, int& beg, int& end) {
+  const int row = c.row[slot];
+  beg = a.rowptr[row] + (slot - c.first[slot]) * kHubEdges;
+  const int row_end = a.rowptr[row + 1];
+  end = beg + kHubEdges < row_end ? beg + kHubEdges : row_end;
+}
+
 template <int OP, int H>
-__global__ __launch_bounds__(kBigBlock) void edge_row_block_kernel(EdgeRowArgs a) {
-  __shared__ float sm[(kBigBlock / kWave) * 8];
-  const int row = a.big_row[blockIdx.x];
-  const int beg = a.rowptr[row], end = a.rowptr[row + 1];
-  const BlockTeam team(sm);
-  if (OP == kSum) rowsum_row<H>(a, team, row, beg, end);
-  else if (OP == kFwd) softmax_fwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
-  else softmax_bwd_row<H>(a, team, int64_t(beg) * H, int64_t(end) * H);
+__global__ __launch_bounds__(kHubThreads) void edge_hub_partial_kernel(EdgeRowArgs a, HubChunks c) {
+  __shared__ float sm[(kHubThreads / kWave) * 8];
+  const int slot = blockIdx.x;
+  int beg, end;
+  hub_chunk_range(a, c, slot, beg, end);
+  const int64_t j0 = int64_t(beg) * H, j1 = int64_t(end) * H;
+  const int64_t a0 = j0 & ~int64_t(7);
+  const int64_t nvec = (j1 - a0 + 7) >> 3;
+  float r0[H], r1[H];
+#pragma unroll
+  for (int h = 0; h < H; ++h) {
+    r0[h] = OP == kFwd ? -INFINITY : 0.f;
+    r1[h] = 0.f;
+  }
+  if (OP == kSum && a.eid) {
+    typedef _Float16 hv_t __attribute__((ext_vector_type(H)));
+    for (int k = beg + int(threadIdx.x); k < end; k += kHubThreads) {
+      const int64_t s = a.eid[k];
+      if (H == 1) {
+        r0[0] += float(a.x0[s]);
+      } else {
+        const hv_t v = *reinterpret_cast<const hv_t*>(a.x0 + s * H);
+#pragma unroll
+        for (int h = 0; h < H; ++h) r0[h] += float(v[h]);
+      }
+    }
+  } else {
+    for (int64_t t = threadIdx.x; t < nvec; t += kHubThreads) {
+      const int64_t b = a0 + 8 * t;
+      const half8_t v = load_vec(a.x0, b, a.total);
+      half8_t d = half8_t(0);
+      if (OP == kBwd) d = load_vec(a.x1, b, a.total);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (b + q < j0 || b + q >= j1) continue;
+        if (OP == kFwd) r0[q % H] = fmaxf(r0[q % H], float(v[q]));
+        else if (OP == kBwd) r0[q % H] = fmaf(float(v[q]), float(d[q]), r0[q % H]);
+        else r0[q % H] += float(v[q]);
+      }
+    }
+  }
+  hub_block_reduce<H, OP == kFwd>(r0, sm);
+  if (OP == kFwd) {  // second walk (cache resident): the sum of exp relative to the chunk's maximum
+    for (int64_t t = threadIdx.x; t < nvec; t += kHubThreads) {
+      const int64_t b = a0 + 8 * t;
+      const half8_t v = load_vec(a.x0, b, a.total);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (b + q >= j0 && b + q < j1) r1[q % H] += __expf(float(v[q]) - r0[q % H]);
+    }
+    hub_block_reduce<H, false>(r1, sm);
+  }
+  if (threadIdx.x < H) {
+    float v0 = 0.f, v1 = 0.f;
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+      if (int(threadIdx.x) == h) {
+        v0 = r0[h];
+        v1 = r1[h];
+      }
+    c.part[(int64_t(slot) * H + threadIdx.x) * 2] = v0;
+    c.part[(int64_t(slot) * H + threadIdx.x) * 2 + 1] = v1;
+  }
+}
+
+// softmax forward / backward: the row's partials combined, then this chunk's outputs
+template <int OP, int H>
+__global__ __launch_bounds__(kHubThreads) void edge_hub_emit_kernel(EdgeRowArgs a, HubChunks c) {
+  const int slot = blockIdx.x;
+  int beg, end;
+  hub_chunk_range(a, c, slot, beg, end);
+  const int first = c.first[slot], cnt = c.count[slot];
+  float M[H], S[H];  // forward: row maximum and 1 / sum of exp; backward: S = sum of alpha * dalpha
+#pragma unroll
+  for (int h = 0; h < H; ++h) {
+    M[h] = -INFINITY;
+    S[h] = 0.f;
+  }
+  if (OP == kFwd) {
+    for (int i = 0; i < cnt; ++i)
+#pragma unroll
+      for (int h = 0; h < H; ++h) M[h] = fmaxf(M[h], c.part[(int64_t(first + i) * H + h) * 2]);
+  }
+  for (int i = 0; i < cnt; ++i)
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+      const float p0 = c.part[(int64_t(first + i) * H + h) * 2], p1 = c.part[(int64_t(first + i) * H + h) * 2 + 1];
+      S[h] += OP == kFwd ? p1 * __expf(p0 - M[h]) : p0;
+    }
+  if (OP == kFwd) {
+#pragma unroll
+    for (int h = 0; h < H; ++h) S[h] = 1.f / S[h];
+  }
+  const int64_t j0 = int64_t(beg) * H, j1 = int64_t(end) * H;
+  const int64_t a0 = j0 & ~int64_t(7);
+  const int64_t nvec = (j1 - a0 + 7) >> 3;
+  for (int64_t t = threadIdx.x; t < nvec; t += kHubThreads) {
+    const int64_t b = a0 + 8 * t;
+    const half8_t v = load_vec(a.x0, b, a.total);
+    half8_t o;
+    if (OP == kFwd) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) o[q] = half_t(__expf(float(v[q]) - M[q % H]) * S[q % H]);
+    } else {
+      const half8_t d = load_vec(a.x1, b, a.total);
+      half8_t e = half8_t(1);
+      if (a.x2) e = load_vec(a.x2, b, a.total);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        float g = float(v[q]) * (float(d[q]) - S[q % H]);
+        if (!(float(e[q]) > 0.f)) g *= a.slope;
+        o[q] = half_t(g);
+      }
+    }
+    store_vec(a.out, b, o, j0, j1);
+  }
+}
+
+// row sums of the long rows: one thread per (row, head) adds the row's partial sums in chunk order
+__global__ __launch_bounds__(kBlock) void edge_hub_rowsum_kernel(EdgeRowArgs a, HubChunks c, const int* __restrict__ big_first,
+                                                                 int n_big) {
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_big * a.H) return;
+  const int r = i / a.H, h = i - r * a.H;
+  const int first = big_first[r], cnt = c.count[first];
+  float s = 0.f;
+  for (int k = 0; k < cnt; ++k) s += c.part[(int64_t(first + k) * a.H + h) * 2];
+  const int64_t o = int64_t(a.big_row[r]) * a.H + h;
+  if (a.out_f32) a.out_f32[o] = s;
+  else a.out[o] = half_t(s);
 }
 
 // Scalar path for head counts that do not divide 8: one thread per (row, head).
@@ -345,7 +484,7 @@ static void launch_team_h(int LR, dim3 grid, hipStream_t s, const EdgeRowArgs& a
   }
 }
 
-// Launches the team kernel (and the long-row kernel when a plan lists long rows) for H in {1,2,4,8}.
+// Launches the team kernel (and the chunked kernels when a plan lists long rows) for H in {1,2,4,8}.
 template <int OP>
 static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeRowArgs a, hipStream_t s) {
   const int H = a.H;
@@ -365,10 +504,11 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   const double per_row = mean_len * ((OP == kSum && a.eid) ? 1.0 : H / 8.0);
   int LR = 4;
   while (LR < kWave && LR < per_row) LR <<= 1;
-  const int big = (p && p->n_big > 0) ? p->big_deg : 0;
+  // (the chunked long-row kernels keep partial results in the plan, sized for its max_H heads)
+  const int big = (p && p->n_big > 0 && H <= p->max_H) ? p->big_deg : 0;
   a.big_row = p ? p->big_row : nullptr;
   // tier 1: sub-wave teams take the rows they can hold in registers; tier 2: a whole wave per row
-  // for the rows between that and the plan's long-row threshold; tier 3: a workgroup per long row.
+  // for the rows between that and the plan's long-row threshold; tier 3: the long rows in chunks.
   int t1 = (OP == kSum && a.eid) ? LR * 4 : LR * 8 * kKeepVec / H;
   // a plan lists the rows between its mid and long thresholds: the wave-per-row tier then walks that list
   // instead of starting a wave for every row of the graph only to find most of them done
@@ -398,14 +538,28 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
     HGNN_LAUNCH_CHECK("edge_row_team_kernel");
   }
   if (big > 0) {
-    dim3 gb(unsigned(p->n_big));
+    const HubChunks c{p->hub_chunk_row, p->hub_chunk_first, p->hub_chunk_count, p->hub_part};
+    dim3 gc(unsigned(p->n_hub_chunks));
     switch (H) {
-      case 1: edge_row_block_kernel<OP, 1><<<gb, kBigBlock, 0, s>>>(a); break;
-      case 2: edge_row_block_kernel<OP, 2><<<gb, kBigBlock, 0, s>>>(a); break;
-      case 4: edge_row_block_kernel<OP, 4><<<gb, kBigBlock, 0, s>>>(a); break;
-      default: edge_row_block_kernel<OP, 8><<<gb, kBigBlock, 0, s>>>(a); break;
+      case 1: edge_hub_partial_kernel<OP, 1><<<gc, kHubThreads, 0, s>>>(a, c); break;
+      case 2: edge_hub_partial_kernel<OP, 2><<<gc, kHubThreads, 0, s>>>(a, c); break;
+      case 4: edge_hub_partial_kernel<OP, 4><<<gc, kHubThreads, 0, s>>>(a, c); break;
+      default: edge_hub_partial_kernel<OP, 8><<<gc, kHubThreads, 0, s>>>(a, c); break;
     }
-    HGNN_LAUNCH_CHECK("edge_row_block_kernel");
+    HGNN_LAUNCH_CHECK("edge_hub_partial_kernel");
+    if (OP == kSum) {
+      edge_hub_rowsum_kernel<<<dim3(unsigned(ceil_div(int64_t(p->n_big) * H, kBlock))), kBlock, 0, s>>>(a, c, p->big_first,
+                                                                                                       p->n_big);
+      HGNN_LAUNCH_CHECK("edge_hub_rowsum_kernel");
+    } else {
+      switch (H) {
+        case 1: edge_hub_emit_kernel<OP, 1><<<gc, kHubThreads, 0, s>>>(a, c); break;
+        case 2: edge_hub_emit_kernel<OP, 2><<<gc, kHubThreads, 0, s>>>(a, c); break;
+        case 4: edge_hub_emit_kernel<OP, 4><<<gc, kHubThreads, 0, s>>>(a, c); break;
+        default: edge_hub_emit_kernel<OP, 8><<<gc, kHubThreads, 0, s>>>(a, c); break;
+      }
+      HGNN_LAUNCH_CHECK("edge_hub_emit_kernel");
+    }
   }
   return HGNN_OK;
 }
