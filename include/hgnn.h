@@ -404,7 +404,9 @@ hgnn_status hgnn_gat_alpha(const hgnn_csr* g, const hgnn_plan* p, int32_t H, int
  *   m_i = max_k e[k,h];  alpha[k,h] = exp(e[k,h]-m_i) / sum_k exp(e[k,h]-m_i).
  * exp and the sums are fp32 in registers (the argument is <= 0, so the value is in
  * (0,1], section 3.1.2).  e and alpha are [nnz][H]; empty rows write nothing.
- * p may be NULL (then very long rows are slower).  g->eid must be NULL. */
+ * p may be NULL (then very long rows are slower; the same when H exceeds the plan's max_H, because
+ * the plan holds the partial results of its long rows' chunks for max_H heads).  With a plan the call
+ * writes that scratch: order it with the other calls on the plan.  g->eid must be NULL. */
 hgnn_status hgnn_edge_softmax(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* e, hgnn_half* alpha,
                               void* stream);
 

@@ -488,6 +488,9 @@ static void launch_team_h(int LR, dim3 grid, hipStream_t s, const EdgeRowArgs& a
 template <int OP>
 static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeRowArgs a, hipStream_t s) {
   const int H = a.H;
+  // the chunked long-row kernels keep partial results in the plan, sized for its max_H heads: with more heads than
+  // that the call runs as it does without a plan (a wave for every row above the sub-wave tier)
+  if (p && H > p->max_H) p = nullptr;
   if (!(H == 1 || H == 2 || H == 4 || H == 8) || !aligned16(a.x0) || !aligned16(a.out) ||
       (a.x1 && !aligned16(a.x1)) || (a.x2 && !aligned16(a.x2))) {
     edge_row_scalar_kernel<OP><<<dim3(unsigned(ceil_div(int64_t(g->nrows) * H, kBlock))), kBlock, 0, s>>>(a);
@@ -504,8 +507,7 @@ static hgnn_status launch_edge_rows(const hgnn_csr* g, const hgnn_plan* p, EdgeR
   const double per_row = mean_len * ((OP == kSum && a.eid) ? 1.0 : H / 8.0);
   int LR = 4;
   while (LR < kWave && LR < per_row) LR <<= 1;
-  // (the chunked long-row kernels keep partial results in the plan, sized for its max_H heads)
-  const int big = (p && p->n_big > 0 && H <= p->max_H) ? p->big_deg : 0;
+  const int big = (p && p->n_big > 0) ? p->big_deg : 0;
   a.big_row = p ? p->big_row : nullptr;
   // tier 1: sub-wave teams take the rows they can hold in registers; tier 2: a whole wave per row
   // for the rows between that and the plan's long-row threshold; tier 3: the long rows in chunks.

@@ -534,3 +534,9 @@ def test_edge_softmax_and_row_sums_at_the_tier_borders(hgnn, dev, H, avg):
         np.add.at(abs_s, rows, np.abs(da16.astype(np.float64)))
         compare("row sums", down(out), ref_s, abs_s)
     hgnn.hgnn_plan_destroy(p)
+    if H > 1:  # a plan made for fewer heads has no room for the long rows' partial results: they go to the wave tier
+        p1 = hgnn.hgnn_plan_create(g, 256, 64, 1)
+        alpha = torch.full((E, H), -1.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_softmax(g, p1, H, up(e16, dev), alpha)
+        compare("alpha, plan for one head", down(alpha), ref_a, np.maximum(ref_a, 2.0 ** -14), rel_elem=2e-2)
+        hgnn.hgnn_plan_destroy(p1)
