@@ -149,24 +149,40 @@ typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 // which keeps the four waves of a streaming kernel in step on consecutive segments.
 __device__ __forceinline__ int seg_slots_per_lane(int S) { return 4 * ((S + 255) / 256); }
 
+// The index arrays (column ids, edge ids) are read once per pass.  On graphs whose arrays are far larger than the
+// caches a non-temporal load keeps them from displacing the feature rows that the gathers reuse (config 5: 1-2 %
+// on every segment kernel, config 4 up to 3 %); on graphs that fit the Infinity Cache it would push the arrays out
+// between kernels (config 3: the next kernel's reads of the column ids 15 % slower), hence the size rule.
+__host__ __device__ inline bool stream_nontemporal(int64_t nnz) { return nnz * 4 > (int64_t(64) << 20); }
+
+// four consecutive rounds of a lane's reads from an index array, in flight together: v[q] = p[i0 + q * kWave], or 0
+// from position n on.  NT is a template parameter because a run-time choice between two loads of one address is
+// folded into a single ordinary load by the compiler.
+template <bool NT>
+__device__ __forceinline__ void stream_load4(const int* __restrict__ p, int i0, int n, int (&v)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int i = i0 + q * kWave;
+    v[q] = 0;
+    if (i < n) v[q] = NT ? __builtin_nontemporal_load(p + i) : p[i];
+  }
+}
+
 // Reads the n column ids of a segment (0 beyond n) and hands them to put(i, c) for i in [0, spad); spad is a
 // multiple of 4 * kWave (see seg_slots_per_lane).  A lane has its four loads of a round in flight together: a loop
 // of one load and one LDS store per turn waits for every load in turn, four memory latencies per 256 edges.
 template <class Put>
-__device__ __forceinline__ void seg_stage_cols(const int* __restrict__ col, int64_t e0, int lane, int spad, int n, Put&& put) {
+__device__ __forceinline__ void seg_stage_cols(const int* __restrict__ col, int64_t e0, int lane, int spad, int n, bool nt,
+                                               Put&& put) {
   for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {
     int c[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) c[q] = i0 + q * kWave < n ? col[e0 + i0 + q * kWave] : 0;
+    if (nt) stream_load4<true>(col + e0, i0, n, c);
+    else stream_load4<false>(col + e0, i0, n, c);
 #pragma unroll
     for (int q = 0; q < 4; ++q) put(i0 + q * kWave, c[q]);
   }
 }
 
-// open (optional): [0] = the segment's first row began in an earlier segment, [1] = its last row goes on in the
-// next one.  When asked for, the two row bounds behind them and the first round of the scatter's bounds are
-// requested together, ahead of the LDS fill (one memory latency instead of two; the values held across the fill
-// cost registers, which pays for the fused GAT forward and not for the kernels held to 64 registers).
 template <bool BLOCK_SYNC = false>
 __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane, int per, int n, int row_lo, int row_hi,
                                                const int* __restrict__ rowptr, int64_t e0, bool* open = nullptr) {

@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   }
 
   // ---- phase 1: column ids (as byte offsets of the neighbour's row where they fit 32 bits) and row ids
-  seg_stage_cols(a.col, e0, lane, spad, n,
+  seg_stage_cols(a.col, e0, lane, spad, n, stream_nontemporal(a.nnz),
                  [&](int i, int c) { s_col[i] = OFF32 ? int(uint32_t(c) * uint32_t(a.ldx) * 2u) : c; });
   if (lane < G) m_flag[lane] = 0;
   bool seg_open[2];

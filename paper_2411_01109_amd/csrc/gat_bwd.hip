@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
 
   // ---- phase 1: column ids, row ids, then per (edge, head) the attention weight with the LeakyReLU branch in
   // its sign, and u = alpha * mask * t of the destination vertex
-  seg_stage_cols(a.col, e0, lane, spad, n, [&](int i, int c) {
+  seg_stage_cols(a.col, e0, lane, spad, n, stream_nontemporal(a.nnz), [&](int i, int c) {
     if (FLY && OFF32) {
       s_raw[i] = c;
       s_col[i] = int(uint32_t(c) * uint32_t(a.ldx) * 2u);

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kBlock, 8) void sddmm_seg_kernel(SddmmArgs a) {
   const int64_t e0 = seg * S;
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
   const int row_lo = valid ? a.seg_lo[seg] : 0, row_hi = valid ? a.seg_hi[seg] : -1;
-  seg_stage_cols(a.col, e0, lane, lay.spad, n, [&](int i, int c) { s_col[i] = c; });
+  seg_stage_cols(a.col, e0, lane, lay.spad, n, stream_nontemporal(a.nnz), [&](int i, int c) { s_col[i] = c; });
   seg_stage_rows(s_row, s_blk, lane, lay.per, n, row_lo, row_hi, a.rowptr, e0);
 
   const int C = 4 * ((S + 4 * G - 1) / (4 * G));

@@ -492,19 +492,22 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   // ---- phase 1: coalesced stage of column ids and edge values, then the row id of every edge.  spad is a
   // multiple of 4 * kWave; a lane keeps its four loads of a round in flight together (column ids, then the
   // edge-id map, then the values behind it), so a round costs one memory latency per level, not four.
+  const bool nt = stream_nontemporal(a.nnz);
   for (int i0 = lane; i0 < spad; i0 += 4 * kWave) {
     int c[4];
     int64_t slot[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int i = i0 + q * kWave;
-      c[q] = i < n ? a.col[e0 + i] : 0;
-    }
+    if (nt) stream_load4<true>(a.col + e0, i0, n, c);
+    else stream_load4<false>(a.col + e0, i0, n, c);
     if (WM != 0 && !a.delta) {
+      if (a.eid) {
+        int e[4];
+        if (nt) stream_load4<true>(a.eid + e0, i0, n, e);
+        else stream_load4<false>(a.eid + e0, i0, n, e);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int i = i0 + q * kWave;
-        slot[q] = i < n ? (a.eid ? int64_t(a.eid[e0 + i]) : e0 + i) : 0;
+        for (int q = 0; q < 4; ++q) slot[q] = e[q];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) slot[q] = i0 + q * kWave < n ? e0 + i0 + q * kWave : 0;
       }
     }
 #pragma unroll
