@@ -10,8 +10,10 @@
  *
  * General rules
  *  - Every pointer in this header that is not marked HOST is a DEVICE pointer
- *    owned by the caller.  The library never frees or keeps caller memory,
- *    except that a plan remembers nothing but sizes of the graph it was built for.
+ *    owned by the caller.  The library never frees or keeps caller memory: a plan
+ *    remembers the sizes of the graph it was built for, and a column-blocked plan
+ *    (hgnn_plan_create, col_blocks) also keeps its own re-ordered copy of the column ids
+ *    and of the edge-id map of that graph.
  *  - fp16 data (hgnn_half) is IEEE binary16 stored as 16-bit words.
  *    Vertex-level tensors are row major [rows][ld] with ld >= F (section 2.1.1:
  *    |V| x |F|); edge-level tensors are edge major [nnz][H].  Head h owns the
@@ -20,19 +22,16 @@
  *    its neighbourhood N(i); columns are neighbour ids.  Duplicate non-zeros
  *    are separate edges.
  *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
- *    compute entry points are asynchronous on that stream and never synchronize;
- *    those that take a plan never allocate.  hgnn_spmm (no plan) takes scratch for
- *    its longest rows (above 8 times the mean, the threshold kept within 256..1024
- *    non-zeros) from a stream-ordered memory pool of the library's own
- *    (hipMallocFromPoolAsync / hipFreeAsync on `stream`; the pool keeps its memory,
- *    so only the first call on a device reaches the driver).
+ *    compute entry points are asynchronous on that stream, never synchronize and
+ *    never allocate: scratch memory comes from the plan or from a workspace argument
+ *    that the caller owns (hgnn_spmm, hgnn_linear_wgrad, hgnn_gat_feature_grad).
  *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose,
  *    hgnn_coo_to_csr and hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
  *  - A plan owns scratch that the calls using it write (staging rows, per-vertex
  *    tables, per-block partial outputs): calls that use the same plan must be ordered
  *    on one stream, or otherwise not overlap in time; different plans are independent.
- *    Host-side, the library keeps no mutable state except the thread-local error string,
- *    the vector-width setting and the per-device memory pool of hgnn_spmm (mutex-guarded).
+ *    The same holds for a workspace.  Host-side, the library keeps no mutable state
+ *    except the thread-local error string.
  *  - Arithmetic: fp16 in memory, fp32 in registers, one round-to-nearest-even
  *    conversion when a value is stored.
  *  - Errors: every call returns an hgnn_status; argument errors are detected on
@@ -146,9 +145,17 @@ hgnn_status hgnn_edge_to_transposed(const hgnn_csr* gt, int32_t H, const hgnn_ha
  * slice of X at a time, into n partial outputs [n][nrows][max_F] fp16 that one
  * more pass adds per row.  Every partial still covers at most seg_edges edges and
  * is scaled before it is rounded (section 5.2.2).  0 = automatic: blocking is
- * chosen when the feature table (ncols * max_F halves) is larger than an L2 but
- * fits the Infinity Cache and rows are long.  Costs nnz * 8 bytes plus the
- * partial outputs.  The other entry points ignore it. */
+ * chosen when the feature table (ncols * max_F halves) is larger than three L2s but
+ * fits three quarters of the cache behind them (sizes read from the device) and rows
+ * average 128 non-zeros or more; with blocks chosen this way a call whose own table
+ * (ncols * ldx halves) is below that size runs unblocked (blocks asked for by number are
+ * always used).  Costs nnz * 8 bytes plus the partial outputs.
+ * Edge tensors with a blocked plan: a call whose graph has no edge-id map reads them at the
+ * graph's own CSR positions, whatever graph the plan was built from; a call whose graph has
+ * an edge-id map reads them through the plan's blocked copy of the map, so the plan must
+ * have been built from a graph with that same map (HGNN_EINVAL when it was built without
+ * one).  hgnn_sddmm and hgnn_edge_rowsum use the blocks only where they match the call
+ * (a plan built without a map for hgnn_sddmm, with one for hgnn_edge_rowsum over a map). */
 hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F, int32_t max_H, int32_t col_blocks,
                              hgnn_plan** out, void* stream);
 int64_t hgnn_plan_num_segments(const hgnn_plan* p);
@@ -173,9 +180,18 @@ void hgnn_plan_destroy(hgnn_plan* p);
  * w == NULL means all ones (SpMMv); s_i = 1 (SUM) or 1/max(deg_i,1) (MEAN), times
  * row_scale[i] (fp32 [nrows]) when row_scale != NULL.  The scale is applied once,
  * after the whole row is reduced (post-reduction scaling).  Y is fully
- * overwritten (empty rows become 0).  X is [ncols][ldx], Y is [nrows][ldy]. */
+ * overwritten (empty rows become 0).  X is [ncols][ldx], Y is [nrows][ldy].
+ * Rows above 8 times the mean length (the threshold kept within 256..1024 non-zeros) are cut
+ * into chunks of 512 non-zeros that are reduced by a wavefront each and added in chunk order;
+ * their lists and fp32 partial rows live in `workspace`: device memory of at least
+ * hgnn_spmm_workspace(nrows, nnz, F) bytes, 16-byte aligned, owned by the caller, overwritten,
+ * not to be shared by calls that overlap in time.  The size is a bound from the three
+ * numbers alone (0 when no row of such a graph can be that long).  workspace == NULL is
+ * allowed: every long row is then reduced by a single wavefront (correct, slow on hubs). */
+size_t hgnn_spmm_workspace(int32_t nrows, int64_t nnz, int32_t F);
 hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
-                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* stream);
+                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /* Discretized-reduction SpMM, edge-parallel, no atomic writes (section 5.2):
  * same result as hgnn_spmm, but every wavefront reduces one segment of the plan,
@@ -265,15 +281,15 @@ int32_t hgnn_plan_group_edges(const hgnn_plan* p);
 hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32_t* group_row, int32_t* group_first);
 
 /* Vector-width study (sections 5.1.2-5.1.3 and 6.3.1: half2 against half8): halves that a lane
- * moves per feature load, 8 (16 bytes, the default and the library's design), 4 or 2.  A
- * process-wide setting read at launch time by the two kernels that exist in all three widths:
- * the SDDMM DOT over a plan (hgnn_sddmm) and the main kernel of HGNN_VERTEX_GROUPS.  A narrower
- * width uses more lanes per feature row (F <= 64 * halves, D % halves == 0, feature table
- * below 4 GiB for the SpMM; otherwise HGNN_EUNSUPPORTED).  Every other kernel ignores it.
- * Results are the same up to the order of the fp32 additions.  Not synchronized with calls
- * in flight on other threads. */
-hgnn_status hgnn_set_vector_halves(int32_t halves);
-int32_t hgnn_get_vector_halves(void);
+ * moves per feature load, 8 (16 bytes, the default and the library's design), 4 or 2.  A setting
+ * of the plan, read at launch time by the two kernels that exist in all three widths: the SDDMM
+ * DOT over the plan (hgnn_sddmm) and the main kernel of HGNN_VERTEX_GROUPS.  A narrower width
+ * uses more lanes per feature row (F <= 64 * halves, D % halves == 0, feature table below 4 GiB
+ * for the SpMM; otherwise HGNN_EUNSUPPORTED).  Every other kernel ignores it.  Results are the
+ * same up to the order of the fp32 additions.  Host-side state of the plan: set it while no call
+ * that uses the plan is being issued from another thread. */
+hgnn_status hgnn_plan_set_vector_halves(hgnn_plan* p, int32_t halves);
+int32_t hgnn_plan_vector_halves(const hgnn_plan* p); /* 0 for NULL */
 
 /* out[i, f] = fp16(scale[i] * X[i, f]) for i < n, f < F (rows of pitch ldx / ldo, both multiples of 8;
  * the last 16-byte piece of a row is written up to the pitch when F is not a multiple of 8).  The

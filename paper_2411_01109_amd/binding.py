@@ -24,8 +24,8 @@ EXPORTS = (
     "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
-    "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_set_vector_halves",
-    "hgnn_get_vector_halves", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
+    "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_plan_set_vector_halves",
+    "hgnn_plan_vector_halves", "hgnn_spmm_workspace", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
     "hgnn_edge_to_transposed", "hgnn_scale_rows", "hgnn_linear", "hgnn_linear_wgrad", "hgnn_linear_wgrad_workspace",
     "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace", "hgnn_gat_forward_fused_save",
     "hgnn_gat_backward_fused_saved",
@@ -86,7 +86,9 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_block_export.argtypes = [vp, i32, ctypes.POINTER(i64), vp, vp, vp, vp, vp]
     lib.hgnn_plan_destroy.restype = None
     lib.hgnn_plan_destroy.argtypes = [vp]
-    lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
+    lib.hgnn_spmm_workspace.restype = ctypes.c_size_t
+    lib.hgnn_spmm_workspace.argtypes = [i32, i64, i32]
+    lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
     lib.hgnn_spmm_discretized.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.hgnn_spmm_discretized_fused.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp,
                                                 ctypes.POINTER(_FusionStruct), vp]
@@ -101,15 +103,15 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_group_edges.restype = i32
     lib.hgnn_plan_group_edges.argtypes = [vp]
     lib.hgnn_plan_groups_export.argtypes = [vp, csr, vp, vp]
-    lib.hgnn_set_vector_halves.argtypes = [i32]
+    lib.hgnn_plan_set_vector_halves.argtypes = [vp, i32]
     lib.hgnn_gat_forward_fused.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp]
     lib.hgnn_edge_to_transposed.argtypes = [csr, i32, vp, vp, vp]
     lib.hgnn_scale_rows.argtypes = [i64, i32, vp, i64, vp, vp, i64, vp]
     lib.hgnn_gat_alpha.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, vp, vp]
     lib.hgnn_gat_backward_fused.argtypes = [csr, vp, csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64,
                                             vp, i64, vp, vp, vp]
-    lib.hgnn_get_vector_halves.restype = i32
-    lib.hgnn_get_vector_halves.argtypes = []
+    lib.hgnn_plan_vector_halves.restype = i32
+    lib.hgnn_plan_vector_halves.argtypes = [vp]
     lib.hgnn_gat_forward_fused_save.argtypes = [csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64, vp, vp]
     lib.hgnn_gat_backward_fused_saved.argtypes = [csr, vp, csr, vp, i32, i32, vp, i64, vp, i64, vp, vp, f32, vp, i64, vp, vp, i64,
                                                   vp, vp, i64, vp, i64, vp, vp, vp]
@@ -273,11 +275,20 @@ def hgnn_plan_destroy(p: Plan) -> None:
         load().hgnn_plan_destroy(h)
 
 
+def hgnn_spmm_workspace(nrows: int, nnz: int, F: int) -> int:
+    """Bytes of device workspace hgnn_spmm wants for the long rows of such a graph (0: none can be that long)."""
+    return load().hgnn_spmm_workspace(nrows, nnz, F)
+
+
 def hgnn_spmm(g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
-              op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None, stream=None) -> None:
+              op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None,
+              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """workspace: device tensor of at least hgnn_spmm_workspace(...) bytes, or None (long rows then take one wave each)."""
     F = X.shape[1] if F is None else F
     _check(load().hgnn_spmm(g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16), _ld(X),
-                            _ptr(Y, torch.float16), _ld(Y), F, op, _ptr(row_scale, torch.float32), _stream(stream)))
+                            _ptr(Y, torch.float16), _ld(Y), F, op, _ptr(row_scale, torch.float32),
+                            None if workspace is None else workspace.data_ptr(),
+                            0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def hgnn_spmm_discretized(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
@@ -430,12 +441,12 @@ def hgnn_gat_alpha(g: Csr, p: Plan, H: int, D: int, U: torch.Tensor, Vt: torch.T
                                  _ptr(alpha, torch.float16), _stream(stream)))
 
 
-def hgnn_set_vector_halves(halves: int) -> None:
-    _check(load().hgnn_set_vector_halves(halves))
+def hgnn_plan_set_vector_halves(p: Plan, halves: int) -> None:
+    _check(load().hgnn_plan_set_vector_halves(p.handle, halves))
 
 
-def hgnn_get_vector_halves() -> int:
-    return load().hgnn_get_vector_halves()
+def hgnn_plan_vector_halves(p: Plan) -> int:
+    return load().hgnn_plan_vector_halves(p.handle)
 
 
 def hgnn_sddmm(g: Csr, p: Optional[Plan], op: int, H: int, D: int, U: torch.Tensor, Vt: torch.Tensor,

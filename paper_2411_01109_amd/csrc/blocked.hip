@@ -84,6 +84,7 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   const int width = int(ceil_div(g->ncols, nb));
   p->nb = nb;
   p->block_width = width;
+  p->block_eid = g->eid != nullptr;
   int *cut = nullptr, *cnt = nullptr, *goff = nullptr;
   void* tmp = nullptr;
   size_t tmp_bytes = 0;
@@ -99,7 +100,7 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   // leaves two vectors and (max, sum, masked sum) per block; row sums of edge tensors use one scalar
   if (e == hipSuccess) e = hipMalloc(&p->bstage, sizeof(hgnn_half) * 2 * n_flat * size_t(p->max_F));
   if (e == hipSuccess) e = hipMalloc(&p->bsum, sizeof(float) * 3 * n_flat * size_t(p->max_H));
-  if (e == hipSuccess && !g->eid) e = hipMalloc(&p->bdelta, sizeof(int) * n_flat);
+  if (e == hipSuccess) e = hipMalloc(&p->bdelta, sizeof(int) * n_flat);
   if (e == hipSuccess) {
     block_cuts_kernel<<<dim3(unsigned(ceil_div(int64_t(V) * (nb + 1), kBlock))), kBlock, 0, s>>>(g->rowptr, g->col, V, nb,
                                                                                                  width, cut);
@@ -111,8 +112,7 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
   if (e == hipSuccess) {
     block_rowptr_kernel<<<dim3(unsigned(ceil_div(int64_t(nb) * (V + 1), kBlock))), kBlock, 0, s>>>(goff, V, nb, E, p->brp);
     block_fill_kernel<<<dim3(unsigned(ceil_div(E, kBlock))), kBlock, 0, s>>>(*g, cut, goff, nb, width, p->bcol, p->beid);
-    if (p->bdelta)
-      block_delta_kernel<<<dim3(unsigned(ceil_div(int64_t(n_flat), kBlock))), kBlock, 0, s>>>(cut, goff, V, nb, p->bdelta);
+    block_delta_kernel<<<dim3(unsigned(ceil_div(int64_t(n_flat), kBlock))), kBlock, 0, s>>>(cut, goff, V, nb, p->bdelta);
     e = hipGetLastError();
   }
   p->boff.assign(size_t(nb) + 1, 0);

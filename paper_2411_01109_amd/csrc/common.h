@@ -254,6 +254,10 @@ struct hgnn_plan {
   int32_t big_deg = 0;
   int64_t listed_nnz = 0;  // non-zeros of the rows in mid_row and big_row (the rest belong to rows of at most mid_deg)
   int32_t max_F = 0, max_H = 0;
+  int64_t l2_bytes = 0, llc_bytes = 0;  // cache sizes of the device the plan was built on (an XCD's L2, the cache behind the L2s)
+  int32_t vec_halves = 8;  // halves a lane moves per feature load in the kernels that exist in several widths (8, 4 or 2)
+  bool auto_blocks = false;  // the blocks were chosen by the automatic rule (col_blocks = 0): a call whose own table is small runs unblocked
+  bool block_eid = false;  // column blocks: built from a graph that carried an edge-id map (beid holds that map's slots)
   int32_t* seg_row_lo = nullptr;    // [nseg]
   int32_t* seg_row_hi = nullptr;    // [nseg]
   int32_t* split_row = nullptr;     // [n_split]
@@ -279,8 +283,8 @@ struct hgnn_plan {
   int32_t block_width = 0;
   int32_t* brp = nullptr;           // [nb][nrows+1] offset arrays of the blocks
   int32_t* bcol = nullptr;          // [nnz] column ids, block-major
-  int32_t* beid = nullptr;          // [nnz] slot in the edge tensors of every blocked non-zero
-  int32_t* bdelta = nullptr;        // [nb][nrows] graphs without edge-id map: slot = block position + bdelta[b][row]
+  int32_t* beid = nullptr;          // [nnz] slot in the edge tensors of every blocked non-zero: the creating graph's eid, else its CSR position
+  int32_t* bdelta = nullptr;        // [nb][nrows] CSR position in the whole graph of a blocked non-zero = its block position + bdelta[b][row]
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_half* bstage = nullptr;      // [2][nb][nrows][max_F] per-block partial outputs (second set: masked GAT partials)
@@ -302,7 +306,14 @@ namespace hgnn {
 hgnn_status gat_project(const hgnn_plan* p, const hgnn_csr* g, int H, int D, const hgnn_half* U, int64_t ldu,
                         const hgnn_half* Vt, int64_t ldv, const hgnn_half* a_l, const hgnn_half* a_r, hipStream_t s,
                         const char* who);
-int vector_halves();  // process-wide setting of hgnn_set_vector_halves: 8 (default), 4 or 2
+// argument checks shared by the SpMM entry points, and the plan-free SpMM with the scratch of its hub kernels at
+// `scratch` (scratch_bytes of device memory; null: no row is treated as a hub)
+hgnn_status check_spmm_args(const char* who, const hgnn_csr* g, const hgnn_half* w, int H, const hgnn_half* X, int64_t ldx,
+                            hgnn_half* Y, int64_t ldy, int F, hgnn_reduce op);
+hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X,
+                      int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale,
+                      void* scratch, size_t scratch_bytes, hipStream_t s);
+void device_cache_bytes(int64_t* l2, int64_t* llc);  // of the current device
 hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
 hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);
 }  // namespace hgnn

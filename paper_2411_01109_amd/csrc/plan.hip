@@ -4,13 +4,55 @@
 #include <stdarg.h>
 #include <stdio.h>
 
-#include "common.h"
+#include <hsa/hsa.h>
 
-#include <atomic>
+#include "common.h"
 
 namespace hgnn {
 
 static thread_local char g_err[512] = "";
+
+// ---- cache sizes of the current device ----------------------------------------------------------------
+// L2 (per XCD) from the HIP device attribute; the last-level cache behind the L2s (the Infinity Cache) is not a
+// HIP attribute, so it is read from the HSA agent's cache list (level 3).  Either falls back to the MI355X
+// figure (4 MB, 256 MB) when the query gives nothing.
+struct CacheQuery {
+  int want;      // ordinal of the GPU agent looked for
+  int seen;      // GPU agents met so far
+  int64_t l3;    // largest level-3 cache of that agent
+};
+
+static hsa_status_t cache_cb(hsa_cache_t cache, void* data) {
+  CacheQuery* q = static_cast<CacheQuery*>(data);
+  uint8_t level = 0;
+  uint32_t size = 0;
+  if (hsa_cache_get_info(cache, HSA_CACHE_INFO_LEVEL, &level) == HSA_STATUS_SUCCESS &&
+      hsa_cache_get_info(cache, HSA_CACHE_INFO_SIZE, &size) == HSA_STATUS_SUCCESS && level == 3 && int64_t(size) > q->l3)
+    q->l3 = int64_t(size);
+  return HSA_STATUS_SUCCESS;
+}
+
+static hsa_status_t agent_cb(hsa_agent_t agent, void* data) {
+  CacheQuery* q = static_cast<CacheQuery*>(data);
+  hsa_device_type_t type;
+  if (hsa_agent_get_info(agent, HSA_AGENT_INFO_DEVICE, &type) != HSA_STATUS_SUCCESS || type != HSA_DEVICE_TYPE_GPU)
+    return HSA_STATUS_SUCCESS;
+  if (q->seen++ == q->want) (void)hsa_agent_iterate_caches(agent, cache_cb, q);
+  return HSA_STATUS_SUCCESS;
+}
+
+void device_cache_bytes(int64_t* l2, int64_t* llc) {
+  *l2 = int64_t(4) << 20;
+  *llc = int64_t(256) << 20;
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeL2CacheSize, dev) == hipSuccess && v > 0) *l2 = v;
+  if (hsa_init() != HSA_STATUS_SUCCESS) return;
+  CacheQuery q{dev, 0, 0};
+  (void)hsa_iterate_agents(agent_cb, &q);
+  (void)hsa_shut_down();
+  if (q.l3 > 0) *llc = q.l3;
+}
 
 hgnn_status fail(hgnn_status s, const char* fmt, ...) {
   va_list ap;
@@ -20,9 +62,6 @@ hgnn_status fail(hgnn_status s, const char* fmt, ...) {
   return s;
 }
 void clear_error() { g_err[0] = 0; }
-
-static std::atomic<int> g_vector_halves{8};
-int vector_halves() { return g_vector_halves.load(std::memory_order_relaxed); }
 
 hgnn_status check_csr_args(const hgnn_csr* g, const char* who) {
   HGNN_REQUIRE(g != nullptr, HGNN_EINVAL, "%s: graph is NULL", who);
@@ -34,31 +73,39 @@ hgnn_status check_csr_args(const hgnn_csr* g, const char* who) {
 }
 
 // ---- validation ---------------------------------------------------------------------------------
-// err starts at kNoError and receives the smallest rule number broken
+// err starts at kNoError and receives the smallest rule number broken.  Two passes: the offset array first
+// (rules 1-3); the per-edge rules only run on a graph that passed them, because they index the offset array
+// with values that are in range only when it is monotone and has the right end points.
 constexpr int kNoError = 0x7f7f7f7f;
-__global__ void validate_kernel(hgnn_csr g, int* err) {
-  int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+__global__ void validate_rowptr_kernel(hgnn_csr g, int* err) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   int bad = 0;
   if (i == 0) {
     if (g.rowptr[0] != 0) bad = 1;
     else if (int64_t(g.rowptr[g.nrows]) != g.nnz) bad = 2;
   }
   if (!bad && i < g.nrows && g.rowptr[i] > g.rowptr[i + 1]) bad = 3;
-  if (!bad && i < g.nnz) {
-    int c = g.col[i];
-    if (c < 0 || c >= g.ncols) bad = 4;
-    if (!bad && g.eid) {
-      int e = g.eid[i];
-      if (e < 0 || int64_t(e) >= g.nnz) bad = 5;
-    }
-    if (!bad && g.row) {
-      int r = g.row[i];
-      if (r < 0 || r >= g.nrows) bad = 6;
-      else if (!(int64_t(g.rowptr[r]) <= i && i < int64_t(g.rowptr[r + 1]))) bad = 6;
-    }
-    // a column id may only drop where a new row starts
-    if (!bad && i > 0 && g.col[i - 1] > c && int64_t(g.rowptr[row_of_edge(g.rowptr, g.nrows, i)]) != i) bad = 7;
+  if (bad) atomicMin(err, bad);
+}
+
+__global__ void validate_edges_kernel(hgnn_csr g, int* err) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (i >= g.nnz) return;
+  int bad = 0;
+  const int c = g.col[i];
+  if (c < 0 || c >= g.ncols) bad = 4;
+  if (!bad && g.eid) {
+    const int e = g.eid[i];
+    if (e < 0 || int64_t(e) >= g.nnz) bad = 5;
   }
+  if (!bad && g.row) {
+    const int r = g.row[i];
+    if (r < 0 || r >= g.nrows) bad = 6;
+    else if (!(int64_t(g.rowptr[r]) <= i && i < int64_t(g.rowptr[r + 1]))) bad = 6;
+  }
+  // a column id may only drop where a new row starts (rowptr is monotone from 0 to nnz here, so the row found is
+  // in [0, nrows))
+  if (!bad && i > 0 && g.col[i - 1] > c && int64_t(g.rowptr[row_of_edge(g.rowptr, g.nrows, i)]) != i) bad = 7;
   if (bad) atomicMin(err, bad);
 }
 
@@ -325,14 +372,15 @@ const char* hgnn_status_str(hgnn_status s) {
 
 const char* hgnn_last_error(void) { return g_err; }
 
-hgnn_status hgnn_set_vector_halves(int32_t halves) {
+hgnn_status hgnn_plan_set_vector_halves(hgnn_plan* p, int32_t halves) {
   clear_error();
-  HGNN_REQUIRE(halves == 2 || halves == 4 || halves == 8, HGNN_EINVAL, "hgnn_set_vector_halves: %d is not 2, 4 or 8", halves);
-  g_vector_halves.store(halves, std::memory_order_relaxed);
+  HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_plan_set_vector_halves: plan is NULL");
+  HGNN_REQUIRE(halves == 2 || halves == 4 || halves == 8, HGNN_EINVAL, "hgnn_plan_set_vector_halves: %d is not 2, 4 or 8", halves);
+  p->vec_halves = halves;
   return HGNN_OK;
 }
 
-int32_t hgnn_get_vector_halves(void) { return vector_halves(); }
+int32_t hgnn_plan_vector_halves(const hgnn_plan* p) { return p ? p->vec_halves : 0; }
 
 hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream) {
   clear_error();
@@ -344,12 +392,17 @@ hgnn_status hgnn_csr_validate(const hgnn_csr* g, void* stream) {
   int herr = 0;
   hipError_t e = hipMemsetAsync(derr, 0x7f, sizeof(int), s);
   if (e == hipSuccess) {
-    int64_t n = g->nnz > int64_t(g->nrows) + 1 ? g->nnz : int64_t(g->nrows) + 1;
-    validate_kernel<<<dim3(unsigned(ceil_div(n, kBlock))), kBlock, 0, s>>>(*g, derr);
+    validate_rowptr_kernel<<<dim3(unsigned(ceil_div(int64_t(g->nrows) + 1, kBlock))), kBlock, 0, s>>>(*g, derr);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipMemcpyAsync(&herr, derr, sizeof(int), hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess && herr == kNoError && g->nnz > 0) {
+    validate_edges_kernel<<<dim3(unsigned(ceil_div(g->nnz, kBlock))), kBlock, 0, s>>>(*g, derr);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(&herr, derr, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+  }
   (void)hipFree(derr);
   if (e != hipSuccess) return fail(HGNN_EHIP, "hgnn_csr_validate: %s", hipGetErrorString(e));
   if (herr != kNoError) return fail(HGNN_EINVAL, "hgnn_csr_validate: %s", kRule[herr > 0 && herr < 8 ? herr : 0]);
@@ -421,19 +474,21 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
   p->max_H = max_H;
   p->big_deg = 2048;
   p->mid_deg = 32;
+  device_cache_bytes(&p->l2_bytes, &p->llc_bytes);
   hipStream_t s = static_cast<hipStream_t>(stream);
   st = plan_build_arrays(p, g, s, false);
   if (st == HGNN_OK) {
     int nb = col_blocks;
+    p->auto_blocks = nb == 0;
     if (nb == 0) {
-      // automatic: block only when the feature table is too large for an XCD's 4 MB L2 but small enough
-      // for the 256 MB Infinity Cache, and rows are long enough that a row piece per block still amortises
-      // its partial vector; about 8 MB of feature rows per block
+      // automatic: block only when the feature table is too large for an XCD's L2 (beyond three times its size)
+      // but fits the last-level cache with room for the streams (three quarters of it), and rows are long enough
+      // that a row piece per block still amortises its partial vector; about two L2 sizes of feature rows per block
       const double table = double(g->ncols) * max_F * 2.0;
       const double mean_deg = g->nrows > 0 ? double(g->nnz) / g->nrows : 0.0;
       nb = 1;
-      if (table > 12e6 && table < 200e6 && mean_deg >= 128.0) {
-        nb = int(table / 8e6 + 0.5);
+      if (table > 3.0 * double(p->l2_bytes) && table < 0.75 * double(p->llc_bytes) && mean_deg >= 128.0) {
+        nb = int(table / (2.0 * double(p->l2_bytes)) + 0.5);
         if (nb < 2) nb = 2;
         if (nb > 16) nb = 16;
       }

@@ -509,8 +509,8 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     return launch_edge_score(a, seg_blocks, s);
   }
   if ((vec || masked) && !score && p) {
-    // halves per lane: the process-wide setting, when the shape allows a narrower load than 16 bytes
-    int vw = vector_halves();
+    // halves per lane: the plan's setting, when the shape allows a narrower load than 16 bytes
+    int vw = p->vec_halves;
     int Ls = L;
     if (vw != 8) {
       const int lh = D / vw;
@@ -521,7 +521,7 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     const size_t seg_per_wave = size_t(sddmm_lds_layout(a.S, H).total);
     const int wpb = waves_per_block_for_lds(seg_per_wave, true);
     const size_t lds = seg_per_wave * wpb;
-    if (lds <= 65536 && p->nb > 1) {
+    if (lds <= 65536 && p->nb > 1 && !p->block_eid) {  // (a plan built over an edge-id map maps its blocks to that map's slots)
       // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
       for (int b = 0; b < p->nb; ++b) {
         const hgnn_plan* q = p->sub[size_t(b)];

@@ -647,7 +647,7 @@ hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, c
   a.nrows = g->nrows;
   a.H = H;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!(p && p->nb > 1 && g->eid && H <= p->max_H && g->nnz > 0)) return launch_edge_rows<kSum>(g, p, a, s);
+  if (!(p && p->nb > 1 && g->eid && p->block_eid && H <= p->max_H && g->nnz > 0)) return launch_edge_rows<kSum>(g, p, a, s);
   // column-blocked plan of a graph with an edge-id map (the transposed view): the slots a block reads
   // lie in one contiguous part of the edge tensor, so block after block the random reads stay cache
   // resident; fp32 partial sums per block, then one pass adds them

@@ -8,7 +8,8 @@
 // Products are formed and accumulated in fp32 (v_fma_mix), fp16 only when a value is stored.
 #include "common.h"
 
-#include <mutex>
+#include <algorithm>
+#include <climits>
 
 namespace hgnn {
 
@@ -993,7 +994,7 @@ __global__ __launch_bounds__(kBlock) void zero_split_rows_kernel(SpmmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-static hgnn_status check_spmm_args(const char* who, const hgnn_csr* g, const hgnn_half* w, int H, const hgnn_half* X,
+hgnn_status check_spmm_args(const char* who, const hgnn_csr* g, const hgnn_half* w, int H, const hgnn_half* X,
                                    int64_t ldx, hgnn_half* Y, int64_t ldy, int F, hgnn_reduce op) {
   hgnn_status st = check_csr_args(g, who);
   if (st != HGNN_OK) return st;
@@ -1066,62 +1067,52 @@ static void launch_row(int L, dim3 grid, hipStream_t s, const SpmmArgs& a, const
   }
 }
 
-// Stream-ordered scratch for the hub kernels, from a memory pool of the library's own per device
-// that keeps what it has been given, so that only the first call on a device pays for an allocation.
-constexpr int kMaxDevices = 64;
-static hipMemPool_t g_pool[kMaxDevices] = {};
-static std::mutex g_pool_mutex;
-
-static hgnn_status scratch_pool(hipMemPool_t* out) {
-  int dev = 0;
-  HGNN_HIP(hipGetDevice(&dev));
-  HGNN_REQUIRE(dev >= 0 && dev < kMaxDevices, HGNN_EUNSUPPORTED, "hgnn_spmm: device ordinal %d not supported", dev);
-  std::lock_guard<std::mutex> lock(g_pool_mutex);
-  if (!g_pool[dev]) {
-    hipMemPoolProps props{};
-    props.allocType = hipMemAllocationTypePinned;
-    props.handleTypes = hipMemHandleTypeNone;
-    props.location.type = hipMemLocationTypeDevice;
-    props.location.id = dev;
-    hipMemPool_t pool = nullptr;
-    HGNN_HIP(hipMemPoolCreate(&pool, &props));
-    uint64_t keep = UINT64_MAX;
-    HGNN_HIP(hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep));
-    g_pool[dev] = pool;
-  }
-  *out = g_pool[dev];
-  return HGNN_OK;
+// Scratch of the hub kernels: chunk and hub lists and one fp32 partial row per chunk, in one block of device memory
+// that the caller hands over (hgnn_spmm) or that sits in the library's static device array (hgnn_spmm_static).
+// The sizes are worst-case bounds taken from the graph's sizes alone, so that they are known without a look at the
+// graph: the sum over the hubs of ceil(deg / chunk) is at most nnz / chunk + the number of hubs, and there are
+// fewer than nnz / long_row hubs.
+static int hub_threshold(int64_t nrows, int64_t nnz) {
+  // hubs: rows longer than 8 times the mean, but never a threshold below 256 or above 1024 non-zeros (on sparse
+  // power-law graphs 256 balanced better than 1024: 17 % on an R-MAT of mean degree 16, 1-3 % at mean degree
+  // 21-26; with rows of 500 on average 1024 was 2 % better than 4000)
+  const int64_t mean = nrows > 0 ? nnz / nrows : 0;
+  return int(std::min<int64_t>(std::max<int64_t>(kLongRowMin, 8 * mean), kLongRowMax));
 }
 
-// Lists and partial rows for the hubs of a graph with nnz non-zeros; nothing when no row can be a hub.
-static hgnn_status hub_lists_alloc(int64_t nnz, int long_row, int F, hipStream_t s, HubLists* h, void** base) {
-  *base = nullptr;
-  if (nnz <= long_row) return HGNN_OK;
-  // sum over hubs of ceil(deg / chunk) <= nnz / chunk + number of hubs, and there are fewer than nnz / long_row hubs
-  const int64_t max_hubs = nnz / long_row + 1;
-  const int64_t max_chunks = nnz / kHubChunk + max_hubs + 1;
+struct HubLayout {
+  int64_t o_count, o_crow, o_cno, o_hrow, o_hbase, o_part, bytes;
+  int64_t max_chunks, max_hubs;
+};
+
+static HubLayout hub_layout(int64_t nnz, int long_row, int F) {
+  HubLayout o{};
+  if (nnz <= long_row) return o;  // no row can be a hub: bytes = 0
+  o.max_hubs = nnz / long_row + 1;
+  o.max_chunks = nnz / kHubChunk + o.max_hubs + 1;
   auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
-  const int64_t o_count = 0;
-  const int64_t o_crow = o_count + 256;
-  const int64_t o_cno = o_crow + up(max_chunks * 4);
-  const int64_t o_hrow = o_cno + up(max_chunks * 4);
-  const int64_t o_hbase = o_hrow + up(max_hubs * 4);
-  const int64_t o_part = o_hbase + up(max_hubs * 4);
-  const int64_t bytes = o_part + up(max_chunks * int64_t((F + 7) & ~7) * 4);
-  hipMemPool_t pool = nullptr;
-  hgnn_status st = scratch_pool(&pool);
-  if (st != HGNN_OK) return st;
-  HGNN_HIP(hipMallocFromPoolAsync(base, size_t(bytes), pool, s));
-  char* p = static_cast<char*>(*base);
-  h->count = reinterpret_cast<int*>(p + o_count);
-  h->chunk_row = reinterpret_cast<int*>(p + o_crow);
-  h->chunk_no = reinterpret_cast<int*>(p + o_cno);
-  h->hub_row = reinterpret_cast<int*>(p + o_hrow);
-  h->hub_base = reinterpret_cast<int*>(p + o_hbase);
-  h->part = reinterpret_cast<float*>(p + o_part);
-  h->max_chunks = int(max_chunks);
-  h->max_hubs = int(max_hubs);
-  return HGNN_OK;
+  o.o_count = 0;
+  o.o_crow = o.o_count + 256;
+  o.o_cno = o.o_crow + up(o.max_chunks * 4);
+  o.o_hrow = o.o_cno + up(o.max_chunks * 4);
+  o.o_hbase = o.o_hrow + up(o.max_hubs * 4);
+  o.o_part = o.o_hbase + up(o.max_hubs * 4);
+  o.bytes = o.o_part + up(o.max_chunks * int64_t((F + 7) & ~7) * 4);
+  return o;
+}
+
+static HubLists hub_lists_at(void* base, const HubLayout& o) {
+  HubLists h{};
+  char* p = static_cast<char*>(base);
+  h.count = reinterpret_cast<int*>(p + o.o_count);
+  h.chunk_row = reinterpret_cast<int*>(p + o.o_crow);
+  h.chunk_no = reinterpret_cast<int*>(p + o.o_cno);
+  h.hub_row = reinterpret_cast<int*>(p + o.o_hrow);
+  h.hub_base = reinterpret_cast<int*>(p + o.o_hbase);
+  h.part = reinterpret_cast<float*>(p + o.o_part);
+  h.max_chunks = int(o.max_chunks);
+  h.max_hubs = int(o.max_hubs);
+  return h;
 }
 
 template <int WM, bool OFF32>
@@ -1211,8 +1202,8 @@ static hgnn_status run_vgroups(const hgnn_plan* p, SpmmArgs a, int ncols, bool a
   v.pair_loads = (a.w && a.H == 1 && !a.eid && (reinterpret_cast<uintptr_t>(a.w) & 3u) == 0) ? 1 : 0;
   a.staging = reinterpret_cast<half_t*>(p->gstage);
   a.stage_ld = p->max_F;
-  // halves per lane: 8 unless the process-wide setting asks for a narrower load and the shape allows it
-  int vw = acc16 ? 8 : vector_halves();
+  // halves per lane: 8 unless the plan's setting asks for a narrower load and the shape allows it
+  int vw = acc16 ? 8 : p->vec_halves;
   const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
   if (vw != 8) {
     HGNN_REQUIRE(off32 && a.F <= kWave * vw && a.D % vw == 0, HGNN_EUNSUPPORTED,
@@ -1321,48 +1312,62 @@ static void launch_block_sum(int L, dim3 grid, hipStream_t s, const SpmmArgs& a,
   }
 }
 
+// The plan-free SpMM with its hub scratch at `scratch` (scratch_bytes of device memory, may be null: then no row is
+// treated as a hub and a long row is reduced by one wave).
+hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X,
+                             int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale,
+                             void* scratch, size_t scratch_bytes, hipStream_t s) {
+  SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
+  if (!vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
+    dim3 grid(unsigned(ceil_div(int64_t(g->nrows) * F, kBlock)));
+    spmm_scalar_kernel<<<grid, kBlock, 0, s>>>(a);
+    HGNN_LAUNCH_CHECK("spmm_scalar_kernel");
+    return HGNN_OK;
+  }
+  const int L = pow2_at_least((F + 7) / 8);
+  // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
+  a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
+  dim3 grid(unsigned(ceil_div(g->nrows, a.rows_per_wave)));
+  a.long_row = hub_threshold(g->nrows, g->nnz);
+  const HubLayout lay = hub_layout(g->nnz, a.long_row, F);
+  HubLists h{};
+  const bool hubs = lay.bytes > 0 && scratch != nullptr;
+  if (hubs) {
+    HGNN_REQUIRE(scratch_bytes >= size_t(lay.bytes), HGNN_EINVAL, "%s: the workspace holds %zu bytes, this graph needs %lld", who,
+                 scratch_bytes, (long long)lay.bytes);
+    HGNN_REQUIRE((reinterpret_cast<uintptr_t>(scratch) & 15u) == 0, HGNN_EINVAL, "%s: the workspace must be 16-byte aligned", who);
+    h = hub_lists_at(scratch, lay);
+    hub_zero_kernel<<<1, kBlock, 0, s>>>(h);
+    hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock * kScanRows))), kBlock, 0, s>>>(a, h);
+  } else {
+    a.long_row = INT_MAX;  // no scratch: every row above the short-row limit is reduced by one wave
+  }
+  if (edge_val) launch_row<true>(L, grid, s, a, hubs ? &h : nullptr);
+  else launch_row<false>(L, grid, s, a, hubs ? &h : nullptr);
+  HGNN_LAUNCH_CHECK("spmm_row_kernel");
+  return HGNN_OK;
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
 
 extern "C" {
 
+size_t hgnn_spmm_workspace(int32_t nrows, int64_t nnz, int32_t F) {
+  if (nrows <= 0 || nnz <= 0 || F <= 0) return 0;
+  return size_t(hub_layout(nnz, hub_threshold(nrows, nnz), F).bytes);
+}
+
 hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
-                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* stream) {
+                      hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   clear_error();
   hgnn_status st = check_spmm_args("hgnn_spmm", g, edge_val, H, X, ldx, Y, ldy, F, op);
   if (st != HGNN_OK) return st;
   if (g->nrows == 0) return HGNN_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  SpmmArgs a = make_args(g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale);
-  if (vector_path_ok(edge_val, H, X, ldx, Y, ldy, F)) {
-    const int L = pow2_at_least((F + 7) / 8);
-    // sparse rows: a wave takes one row per lane group; dense rows: one row per wave, for balance
-    a.rows_per_wave = g->nnz / g->nrows >= 64 ? 1 : kWave / L;
-    dim3 grid(unsigned(ceil_div(g->nrows, a.rows_per_wave)));
-    HubLists h{};
-    void* scratch = nullptr;
-    // hubs: rows longer than 8 times the mean, but never a threshold below 256 or above 1024 non-zeros (on sparse
-    // power-law graphs 256 balanced better than 1024: 17 % on an R-MAT of mean degree 16, 1-3 % at mean degree
-    // 21-26; with rows of 500 on average 1024 was 2 % better than 4000)
-    a.long_row = int(std::min<int64_t>(std::max<int64_t>(kLongRowMin, 8 * (g->nnz / g->nrows)), kLongRowMax));
-    st = hub_lists_alloc(g->nnz, a.long_row, F, s, &h, &scratch);
-    if (st != HGNN_OK) return st;
-    if (scratch) {
-      hub_zero_kernel<<<1, kBlock, 0, s>>>(h);
-      hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock * kScanRows))), kBlock, 0, s>>>(a, h);
-    }
-    if (edge_val) launch_row<true>(L, grid, s, a, scratch ? &h : nullptr);
-    else launch_row<false>(L, grid, s, a, scratch ? &h : nullptr);
-    const hipError_t launch_err = hipGetLastError();
-    if (scratch) HGNN_HIP(hipFreeAsync(scratch, s));
-    HGNN_REQUIRE(launch_err == hipSuccess, HGNN_EHIP, "hgnn_spmm: kernel launch failed: %s", hipGetErrorString(launch_err));
-  } else {
-    dim3 grid(unsigned(ceil_div(int64_t(g->nrows) * F, kBlock)));
-    spmm_scalar_kernel<<<grid, kBlock, 0, s>>>(a);
-    HGNN_LAUNCH_CHECK("spmm_scalar_kernel");
-  }
-  return HGNN_OK;
+  return spmm_rows("hgnn_spmm", g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, workspace, workspace_bytes,
+                   static_cast<hipStream_t>(stream));
 }
 
 hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, const hgnn_half* edge_val, int32_t H,
@@ -1407,7 +1412,12 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
       a.D = F;
     }
   }
-  if (p->nb <= 1) return run_segments(p, a, g->ncols, s);
+  // blocks that the automatic rule chose (for max_F) are used when the table of this call is beyond an L2 too
+  const bool use_blocks = p->nb > 1 && (!p->auto_blocks || double(g->ncols) * double(a.ldx) * 2.0 > 3.0 * double(p->l2_bytes));
+  if (!use_blocks) return run_segments(p, a, g->ncols, s);
+  HGNN_REQUIRE(!(edge_val && g->eid && !p->block_eid), HGNN_EINVAL,
+               "%s: the column-blocked plan was built from a graph without an edge-id map; build the plan from the graph "
+               "that carries the map", who);
   // column-blocked plan: one discretized SpMM per block into that block's partial output, blocks one
   // after the other so that all compute units gather from the same slice of X, then one pass adds
   // the partials of every row (and the self term, once).  Scales are applied per partial (section 5.2.2).
@@ -1416,8 +1426,10 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
     SpmmArgs ab = a;
     ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
     ab.col = p->bcol + p->boff[size_t(b)];
-    ab.eid = p->beid + p->boff[size_t(b)];
-    ab.delta = p->bdelta ? p->bdelta + size_t(b) * size_t(p->nrows) : nullptr;
+    // slots in the edge tensors: a graph without an edge-id map reads at its own CSR positions (block position +
+    // the row's offset, a coalesced read); a graph with one reads through the blocked copy of the map
+    ab.eid = g->eid ? p->beid + p->boff[size_t(b)] : nullptr;
+    ab.delta = g->eid ? nullptr : p->bdelta + size_t(b) * size_t(p->nrows);
     ab.nnz = q->nnz;
     ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * size_t(p->nrows) * size_t(p->max_F);
     ab.ldy = p->max_F;

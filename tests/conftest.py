@@ -53,3 +53,15 @@ def dev():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     return torch.device("cuda:0")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """One line per run: how often the norm rule's cancelling branch was taken (tests/parity.py)."""
+    try:
+        import parity
+    except ImportError:
+        return
+    log = parity.CANCEL_LOG
+    worst = max((t[1] for t in log), default=0.0)
+    terminalreporter.write_line(f"[parity] cancelling branch of the norm rule taken {len(log)} time(s)"
+                                + (f"; largest true rel-L2 it replaced {worst:.3e}" if log else ""))

@@ -9,12 +9,18 @@ REL_ELEM = 2e-2    # elementwise relative error
 FP16_MAX = 65504.0
 
 
-def compare(name, got16, ref, sabs=None, rel_l2=REL_L2, rel_elem=REL_ELEM, check_finite=True):
+CANCEL_LOG = []  # one entry per compare() call that took the cancelling branch: (name, true ratio, ||ref|| / ||sabs||)
+
+
+def compare(name, got16, ref, sabs=None, rel_l2=REL_L2, rel_elem=REL_ELEM, check_finite=True, allow_cancel=False):
     """got16: numpy float16 from the GPU; ref: float64 oracle values; sabs: oracle's sum of |terms|
     (natural magnitude).  Elementwise rule: |y - ref| <= rel_elem*|ref| + 2^-11 * sabs, i.e. the stated
     relative bound plus one fp16 rounding at the magnitude the sum passed through (a pure relative
     bound cannot be met next to zero by any fp16 output).  Norm rule: ||y - ref|| <= rel_l2 * ||ref||, except where
     ||ref|| <= 2^-8 ||sabs|| (the result is a near-complete cancellation): there ||y - ref|| <= 2^-11 ||sabs||.
+    That branch is only taken with allow_cancel=True (the randomized sweep passes it; everything else, the five
+    configurations included, is held to the ratio), it is
+    recorded in CANCEL_LOG, and the returned dict carries `cancelled` and the true ratio `rel_l2` it replaced.
     Entries whose fp64 value does not fit fp16
     are excluded from the value checks and must be +-inf with the right sign."""
     got = got16.astype(np.float64)
@@ -30,17 +36,22 @@ def compare(name, got16, ref, sabs=None, rel_l2=REL_L2, rel_elem=REL_ELEM, check
     over = np.abs(ref) > FP16_MAX
     g, r = got[fits], ref[fits]
     if r.size == 0:
-        return {"rel_l2": 0.0, "max_rel": 0.0, "n_over": int(over.sum())}
+        return {"rel_l2": 0.0, "max_rel": 0.0, "n_over": int(over.sum()), "cancelled": False}
     denom = np.linalg.norm(r)
     l2 = np.linalg.norm(g - r) / denom if denom > 0 else np.linalg.norm(g - r)
-    if sabs is not None and denom <= (2.0 ** -8) * np.linalg.norm(sabs[fits]):
+    cancelled = False
+    if allow_cancel and sabs is not None and denom <= (2.0 ** -8) * np.linalg.norm(sabs[fits]):
         # the exact result is what is left after at least 8 bits of its terms have cancelled (down to exactly zero
         # for some inputs): one fp16 rounding at the magnitude of the terms, which no fp16 path can avoid, is then
         # 2^-3 of the result or more, and a ratio to the result's norm measures the input, not the kernel.  There
         # the error must stay below that one rounding, in norm as it must element by element
         assert np.linalg.norm(g - r) <= (2.0 ** -11) * np.linalg.norm(sabs[fits]), f"{name}: cancelling result off"
-        l2 = 0.0
-    assert l2 <= rel_l2, f"{name}: rel-L2 {l2:.3e} > {rel_l2}"
+        cancelled = True
+        CANCEL_LOG.append((name, float(l2), float(denom / np.linalg.norm(sabs[fits]))))
+        print(f"[parity] {name}: cancelling branch (||ref||/||sum|terms||| = {CANCEL_LOG[-1][2]:.2e}), true rel-L2 {l2:.3e}",
+              flush=True)
+    else:
+        assert l2 <= rel_l2, f"{name}: rel-L2 {l2:.3e} > {rel_l2}"
     floor = (2.0 ** -11) * (sabs[fits] if sabs is not None else np.abs(r)) + 2.0 ** -24
     err = np.abs(g - r)
     viol = err > rel_elem * np.abs(r) + floor
@@ -48,7 +59,24 @@ def compare(name, got16, ref, sabs=None, rel_l2=REL_L2, rel_elem=REL_ELEM, check
                             f"{err[viol].max():.3e} at ref {r[viol][np.argmax(err[viol])]:.3e}")
     nz = np.abs(r) > 0
     strict = np.max(err[nz] / np.abs(r[nz])) if nz.any() else 0.0
-    return {"rel_l2": float(l2), "max_rel": float(strict), "n_over": int(over.sum())}
+    return {"rel_l2": float(l2), "max_rel": float(strict), "n_over": int(over.sum()), "cancelled": cancelled}
+
+
+_WS = {}
+
+
+def spmm_plain(hgnn, g, edge_val, H, X, Y, workspace=True, **kw):
+    """hgnn_spmm with the workspace its long rows want (one buffer per size, kept for the session);
+    workspace=False runs the call without one (every long row on a single wavefront)."""
+    F = kw.get("F") or X.shape[1]
+    ws = None
+    if workspace:
+        need = hgnn.hgnn_spmm_workspace(g.nrows, g.nnz, F)
+        if need:
+            ws = _WS.get(need)
+            if ws is None:
+                ws = _WS[need] = torch.empty(need, dtype=torch.uint8, device=X.device)
+    hgnn.hgnn_spmm(g, edge_val, H, X, Y, workspace=ws, **kw)
 
 
 def sample_rows(rowptr, n, seed, extra_top=8):

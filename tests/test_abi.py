@@ -47,19 +47,20 @@ def test_argument_errors_are_caught_on_the_host(lib, hgnn):
     X, Y = 0x10000, 0x20000
     EINVAL, EUNSUP = hgnn.HGNN_EINVAL, hgnn.HGNN_EUNSUPPORTED
     call = lambda *a: lib.hgnn_spmm(ctypes.byref(g), None, 1, *a)
-    assert call(X, 8, Y, 8, 7, 0, None, None) == EINVAL          # odd F: pad to even (section 4.1)
+    assert call(X, 8, Y, 8, 7, 0, None, None, 0, None) == EINVAL          # odd F: pad to even (section 4.1)
     assert b"odd" in lib.hgnn_last_error()
-    assert call(X, 8, Y, 8, 0, 0, None, None) == EINVAL          # F <= 0
-    assert call(X, 4, Y, 8, 8, 0, None, None) == EINVAL          # ldx < F
-    assert call(X, 8, Y, 8, 8, 5, None, None) == EINVAL          # unknown reduce op
-    assert call(None, 8, Y, 8, 8, 0, None, None) == EINVAL       # X NULL with nnz > 0
-    assert call(X, 8, None, 8, 8, 0, None, None) == EINVAL       # Y NULL
-    assert lib.hgnn_spmm(ctypes.byref(g), None, 3, X, 8, Y, 8, 8, 0, None, None) == EINVAL  # H does not divide F
-    assert lib.hgnn_spmm(None, None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL             # graph NULL
+    assert call(X, 8, Y, 8, 0, 0, None, None, 0, None) == EINVAL          # F <= 0
+    assert call(X, 4, Y, 8, 8, 0, None, None, 0, None) == EINVAL          # ldx < F
+    assert call(X, 8, Y, 8, 8, 5, None, None, 0, None) == EINVAL          # unknown reduce op
+    assert call(None, 8, Y, 8, 8, 0, None, None, 0, None) == EINVAL       # X NULL with nnz > 0
+    assert call(X, 8, None, 8, 8, 0, None, None, 0, None) == EINVAL       # Y NULL
+    assert lib.hgnn_plan_create(ctypes.byref(g), 256, 64, 1, -1, ctypes.byref(ctypes.c_void_p()), None) == EINVAL
+    assert lib.hgnn_spmm(ctypes.byref(g), None, 3, X, 8, Y, 8, 8, 0, None, None, 0, None) == EINVAL  # H does not divide F
+    assert lib.hgnn_spmm(None, None, 1, X, 8, Y, 8, 8, 0, None, None, 0, None) == EINVAL             # graph NULL
     bad = make_csr(hgnn, rowptr=None)
-    assert lib.hgnn_spmm(ctypes.byref(bad), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    assert lib.hgnn_spmm(ctypes.byref(bad), None, 1, X, 8, Y, 8, 8, 0, None, None, 0, None) == EINVAL
     big = make_csr(hgnn, nnz=1 << 31)
-    assert lib.hgnn_spmm(ctypes.byref(big), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    assert lib.hgnn_spmm(ctypes.byref(big), None, 1, X, 8, Y, 8, 8, 0, None, None, 0, None) == EINVAL
     # discretized: plan required
     assert lib.hgnn_spmm_discretized(None, ctypes.byref(g), None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
     # sddmm / softmax
@@ -114,10 +115,13 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_scale_rows(4, 8, X, 4, A, Y, 8, None) == EINVAL            # pitch < F
     assert lib.hgnn_scale_rows(4, 8, X, 8, None, Y, 8, None) == EINVAL         # scale NULL
     assert lib.hgnn_scale_rows(-1, 8, X, 8, A, Y, 8, None) == EINVAL
-    keep = lib.hgnn_get_vector_halves()
-    assert lib.hgnn_set_vector_halves(3) == EINVAL
-    assert lib.hgnn_set_vector_halves(2) == hgnn.HGNN_OK and lib.hgnn_get_vector_halves() == 2
-    assert lib.hgnn_set_vector_halves(keep) == hgnn.HGNN_OK
+    assert lib.hgnn_plan_set_vector_halves(None, 8) == EINVAL
+    assert lib.hgnn_plan_vector_halves(None) == 0
+    # workspace of the plan-free SpMM: a bound from the sizes alone; nothing when no row can be long
+    assert lib.hgnn_spmm_workspace(4, 8, 64) == 0
+    assert lib.hgnn_spmm_workspace(0, 0, 64) == 0
+    small, big = lib.hgnn_spmm_workspace(1000, 100000, 64), lib.hgnn_spmm_workspace(1000, 100000, 128)
+    assert 0 < small < big and small % 256 == 0
 
 
 def test_header_is_plain_c_and_links(lib):
@@ -131,7 +135,7 @@ int main(void) {
   hgnn_csr g;
   memset(&g, 0, sizeof g);
   if (strncmp(hgnn_status_str(HGNN_EINVAL), "HGNN_", 5) != 0) return 1;
-  if (hgnn_spmm(NULL, NULL, 1, NULL, 8, NULL, 8, 8, HGNN_SUM, NULL, NULL) != HGNN_EINVAL) return 2;
+  if (hgnn_spmm(NULL, NULL, 1, NULL, 8, NULL, 8, 8, HGNN_SUM, NULL, NULL, 0, NULL) != HGNN_EINVAL) return 2;
   if (hgnn_last_error()[0] == 0) return 3;
   if (hgnn_linear_wgrad_workspace(64, 64) == 0) return 4;
   if (hgnn_plan_num_segments(NULL) != 0) return 5;

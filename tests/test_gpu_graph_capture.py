@@ -70,6 +70,80 @@ def test_gat_layer_and_spmm_under_graph_replay(hgnn, dev):
     hgnn.hgnn_plan_destroy(pt)
 
 
+def test_all_sixteen_ops_of_a_step_under_graph_replay(hgnn, dev):
+    """Every op of the benchmark's step on a GAT workload -- plain SpMM forward and backward (with its caller-owned
+    workspace), discretized SUM / MEAN, the GIN fusions, score, softmax, weighted SpMM both ways, SDDMM, softmax
+    backward, row and column sums -- recorded as one graph; no call allocates or synchronizes."""
+    V, H, D = 2500, 1, 64
+    F = H * D
+    rowptr, col = rand_graph(V, V, 20, 77, hubs=((11, 7000), (2400, 1300)), empties=(0, 5))
+    E = col.size
+    r = np.random.default_rng(3)
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=2)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=2)
+    a_l, a_r = up(f16(0.2 * r.standard_normal(F)), dev), up(f16(0.2 * r.standard_normal(F)), dev)
+    X = torch.empty((V, F), dtype=torch.float16, device=dev)
+    dY = torch.empty((V, F), dtype=torch.float16, device=dev)
+    ws = torch.empty(hgnn.hgnn_spmm_workspace(V, E, F), dtype=torch.uint8, device=dev)
+    assert ws.numel() > 0
+    scaled = torch.empty((V, F), dtype=torch.float16, device=dev)
+    lam = up((0.1 / np.maximum(np.diff(rowptr), 1)).astype(np.float32), dev)
+    half = lambda *s: torch.empty(s, dtype=torch.float16, device=dev)
+    names = ("y0", "y1", "y2", "y3", "y4", "y5", "y6", "y7", "out", "dh")
+    edge_names = ("e", "alpha", "dalpha", "ds")
+
+    def make():
+        o = {k: half(V, F) for k in names}
+        o.update({k: half(E, H) for k in edge_names})
+        o.update({"d_el": half(V, H), "d_er": half(V, H)})
+        return o
+
+    def step(o):
+        hgnn.hgnn_spmm(g, None, 1, X, o["y0"], workspace=ws)
+        hgnn.hgnn_spmm(gt, None, 1, dY, o["y1"], workspace=ws)
+        hgnn.hgnn_spmm_discretized(p, g, None, 1, X, o["y2"])
+        hgnn.hgnn_spmm_discretized(pt, gt, None, 1, dY, o["y3"])
+        hgnn.hgnn_spmm_discretized(p, g, None, 1, X, o["y4"], op=hgnn.HGNN_MEAN)
+        hgnn.hgnn_spmm_discretized(pt, gt, None, 1, dY, o["y5"], op=hgnn.HGNN_MEAN)
+        hgnn.hgnn_spmm_discretized_fused(p, g, None, 1, X, o["y6"], op=hgnn.HGNN_MEAN, self_feat=X, self_coef=1.0, agg_coef=0.1)
+        hgnn.hgnn_spmm_discretized_fused(pt, gt, None, 1, dY, o["y7"], col_scale=lam, self_feat=dY, self_coef=1.0, scaled_x=scaled)
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, X, X, o["e"], a_l, a_r, 0.2)
+        hgnn.hgnn_edge_softmax(g, p, H, o["e"], o["alpha"])
+        hgnn.hgnn_spmm_discretized(p, g, o["alpha"], H, X, o["out"])
+        hgnn.hgnn_spmm_discretized(pt, gt, o["alpha"], H, dY, o["dh"])
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, dY, X, o["dalpha"])
+        hgnn.hgnn_edge_softmax_bwd(g, p, H, o["alpha"], o["dalpha"], o["ds"], e=o["e"], neg_slope=0.2)
+        hgnn.hgnn_edge_rowsum(g, p, H, o["ds"], o["d_el"])
+        hgnn.hgnn_edge_rowsum(gt, pt, H, o["ds"], o["d_er"])
+
+    def fill(seed):
+        rr = np.random.default_rng(seed)
+        X.copy_(up(f16(rr.standard_normal((V, F))), dev))
+        dY.copy_(up(f16(rr.standard_normal((V, F))), dev))
+
+    bufs, eager = make(), make()
+    fill(1)
+    step(bufs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(bufs)
+    for rep in range(3):
+        fill(40 + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: down(v).copy() for k, v in bufs.items()}
+        step(eager)
+        torch.cuda.synchronize()
+        for k in bufs:
+            assert np.array_equal(got[k].view(np.uint16), down(eager[k]).view(np.uint16)), (rep, k)
+        assert np.all(np.isfinite(got["y0"].astype(np.float32))) and np.abs(got["dh"].astype(np.float32)).max() > 0
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
+
+
 def test_dense_side_under_graph_replay(hgnn, dev):
     """The dense calls take a caller-owned workspace and allocate nothing either: projection, GAT aggregation and all
     gradients of a layer recorded as one graph."""

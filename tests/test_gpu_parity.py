@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import workloads as wl
-from parity import compare, down, f16, rand_graph, sample_rows, up
+from parity import compare, down, f16, rand_graph, sample_rows, spmm_plain, up
 
 pytestmark = pytest.mark.gpu
 
@@ -37,7 +37,7 @@ def test_plan_degenerate_graphs(hgnn, dev):
     hgnn.hgnn_spmm_discretized(p, g, None, 1, X, Y)
     assert np.all(down(Y) == 0)
     Y.fill_(3.0)
-    hgnn.hgnn_spmm(g, None, 1, X, Y)
+    spmm_plain(hgnn, g, None, 1, X, Y)
     assert np.all(down(Y) == 0)
     # one segment holding everything (S >= E): no split rows
     rowptr, col = rand_graph(20, 20, 3, 5)
@@ -102,7 +102,7 @@ def test_spmm_plain_and_discretized_shapes(hgnn, dev, F, H, has_w, reduce, S, pa
                             want_sabs=True)
     Yfull = torch.full((V, F + pad), 7.0, dtype=torch.float16, device=dev)
     Y = Yfull[:, :F]
-    hgnn.hgnn_spmm(g, wd, H, Xd, Y, op=reduce, row_scale=up(rs, dev))
+    spmm_plain(hgnn, g, wd, H, Xd, Y, op=reduce, row_scale=up(rs, dev))
     compare("plain", down(Y), ref, sabs)
     if pad:
         assert np.all(down(Yfull)[:, F:] == 7.0)  # padding columns untouched
@@ -126,7 +126,7 @@ def test_spmm_scalar_path_and_unsupported(hgnn, dev, F, H):
     Xh, w = f16(r.standard_normal((V, F))), f16(r.standard_normal((col.size, H)))
     g = hgnn.Csr(up(rowptr, dev), up(col, dev))
     Y = torch.empty((V, F), dtype=torch.float16, device=dev)
-    hgnn.hgnn_spmm(g, up(w, dev), H, up(Xh, dev), Y)
+    spmm_plain(hgnn, g, up(w, dev), H, up(Xh, dev), Y)
     ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, H=H, want_sabs=True)
     compare("scalar", down(Y), ref, sabs)
     p = hgnn.hgnn_plan_create(g, 64, 64, 16)
@@ -163,7 +163,7 @@ def test_config1_gcn_forward_backward(hgnn, dev):
     rT, cT, eT = oracle.transpose(w.rowptr, w.col, w.V)
     _, sabs_b = oracle.spmm(rT, cT, w.tensors["dY"], w=ew, eid=eT, want_sabs=True)
     Y = torch.empty_like(X)
-    for name, fn in (("plain", lambda G, P, A, B: hgnn.hgnn_spmm(G, ewd, 1, A, B)),
+    for name, fn in (("plain", lambda G, P, A, B: spmm_plain(hgnn, G, ewd, 1, A, B)),
                      ("disc", lambda G, P, A, B: hgnn.hgnn_spmm_discretized(P, G, ewd, 1, A, B))):
         fn(g, p, X, Y)
         s = compare(f"c1 fwd {name}", down(Y), ref_f, sabs_f)
@@ -184,7 +184,7 @@ def test_config2_gin_overflow(hgnn, dev, positive):
     ref_sum, sabs = oracle.spmm(w.rowptr, w.col, w.tensors["X"], want_sabs=True)
     ref_mean = ref_sum / np.maximum(np.diff(w.rowptr), 1)[:, None]
     sabs_mean = sabs / np.maximum(np.diff(w.rowptr), 1)[:, None]
-    hgnn.hgnn_spmm(g, None, 1, X, Y)
+    spmm_plain(hgnn, g, None, 1, X, Y)
     s_plain = compare("c2 plain sum", down(Y), ref_sum, sabs)
     hgnn.hgnn_spmm_discretized(p, g, None, 1, X, Y)
     s_disc = compare("c2 disc sum", down(Y), ref_sum, sabs)
@@ -475,6 +475,97 @@ def test_spmm_blocked_matches_oracle(hgnn, dev, F, H, has_w, reduce, S, nb):
     compare("blocked bwd", down(dX), refb, sabsb)
     if reduce == 0:
         np.testing.assert_allclose(refb, oracle.spmm_T_scatter(rowptr, col, dYh, ncols, w=w, H=H), rtol=1e-9, atol=1e-9)
+
+
+@pytest.mark.parametrize("nb,H,F", [(3, 1, 64), (4, 2, 64), (2, 1, 40)])
+def test_blocked_plan_reads_edge_tensors_through_the_calls_graph(hgnn, dev, nb, H, F):
+    """Edge values that do not change are brought into the transposed order once and the transposed graph is then run
+    without its edge-id map, on the plan built from the graph that has one: a blocked plan must read them at the call's
+    own positions.  The mirror cases: a plan built without a map refuses a call with one (SpMM with edge values), and the
+    row sums / SDDMM only use the blocks that match the call."""
+    print(f"blocked slots nb={nb} H={H} F={F}", flush=True)
+    V, S = 1100, 128
+    rowptr, col = rand_graph(V, V, 30, 7 * nb + H, hubs=((9, 4000), (600, 900)), empties=(0, 3, 1099))
+    E = col.size
+    r = np.random.default_rng(nb + H)
+    dYh = f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    gt_plain = hgnn.Csr(gt.rowptr, gt.col, ncols=V)
+    wd, dY = up(w, dev), up(dYh, dev)
+    ref, sabs = oracle.spmm(rT, cT, dYh, w=w, H=H, eid=eT, want_sabs=True)
+    pt = hgnn.hgnn_plan_create(gt, S, 64, H, col_blocks=nb)          # built from the graph with the map
+    pt_plain = hgnn.hgnn_plan_create(gt_plain, S, 64, H, col_blocks=nb)  # built without
+    assert hgnn.hgnn_plan_col_blocks(pt) == nb and hgnn.hgnn_plan_col_blocks(pt_plain) == nb
+    w_T = torch.empty_like(wd)
+    hgnn.hgnn_edge_to_transposed(gt, H, wd, w_T)
+    assert np.array_equal(down(w_T).view(np.uint16), oracle.edge_gather(eT, w).view(np.uint16))
+    dX = torch.empty((V, F), dtype=torch.float16, device=dev)
+    for name, plan, graph, vals in (("map, plan with map", pt, gt, wd), ("no map, plan with map", pt, gt_plain, w_T),
+                                    ("no map, plan without map", pt_plain, gt_plain, w_T)):
+        dX.fill_(3.0)
+        hgnn.hgnn_spmm_discretized(plan, graph, vals, H, dY, dX)
+        compare(f"blocked spmm: {name}", down(dX), ref, sabs)
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_spmm_discretized(pt_plain, gt, wd, H, dY, dX)
+    assert ei.value.status == hgnn.HGNN_EINVAL and "edge-id map" in str(ei.value)
+    hgnn.hgnn_spmm_discretized(pt_plain, gt, None, 1, dY, dX)  # without edge values nothing is looked up: fine
+    compare("blocked spmm: no values", down(dX), *oracle.spmm(rT, cT, dYh, want_sabs=True))
+    # column sums of an edge tensor = row sums over the transposed graph with its map, on either plan
+    t64 = w.astype(np.float64)
+    cs = torch.empty((V, H), dtype=torch.float16, device=dev)
+    for name, plan in (("plan with map", pt), ("plan without map", pt_plain)):
+        cs.fill_(5.0)
+        hgnn.hgnn_edge_rowsum(gt, plan, H, wd, cs)
+        compare(f"column sums: {name}", down(cs), oracle.edge_colsum(rowptr, col, t64, V), oracle.edge_colsum(rowptr, col, np.abs(t64), V))
+    # SDDMM over the transposed graph (no map in the call): results in that graph's own edge order, on either plan
+    if F % (8 * H) == 0:
+        D = F // H
+        Uh, Vh = f16(r.standard_normal((V, F))), f16(r.standard_normal((V, F)))
+        dref = oracle.sddmm_dot(rT, cT, Uh, Vh, H=H)
+        rowT = np.repeat(np.arange(V), np.diff(rT))
+        dabs = (np.abs(Uh[rowT].astype(np.float64)) * np.abs(Vh[cT].astype(np.float64))).reshape(E, H, D).sum(-1)
+        out = torch.empty((E, H), dtype=torch.float16, device=dev)
+        for name, plan in (("plan with map", pt), ("plan without map", pt_plain)):
+            out.fill_(9.0)
+            hgnn.hgnn_sddmm(gt_plain, plan, hgnn.HGNN_SDDMM_DOT, H, D, up(Uh, dev), up(Vh, dev), out)
+            compare(f"sddmm: {name}", down(out), dref, dabs)
+    hgnn.hgnn_plan_destroy(pt)
+    hgnn.hgnn_plan_destroy(pt_plain)
+
+
+@pytest.mark.parametrize("F,has_w", [(64, True), (128, False), (24, True)])
+def test_spmm_workspace_forms(hgnn, dev, F, has_w):
+    """hgnn_spmm with the workspace its long rows want, with none at all (long rows on one wavefront each), and with
+    one that is too small (refused on the host); a graph without long rows needs none."""
+    V = 1500
+    rowptr, col = rand_graph(V, V, 6, F, hubs=((3, 9000), (700, 1500), (1499, 300)), empties=(0, 8))
+    r = np.random.default_rng(F)
+    Xh = f16(r.standard_normal((V, F)))
+    w = f16(r.standard_normal((col.size, 1))) if has_w else None
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    X, wd = up(Xh, dev), None if w is None else up(w, dev)
+    ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, reduce=oracle.MEAN, want_sabs=True)
+    need = hgnn.hgnn_spmm_workspace(V, col.size, F)
+    assert need > 0
+    ws = torch.empty(need + 64, dtype=torch.uint8, device=dev)
+    Y = torch.empty((V, F), dtype=torch.float16, device=dev)
+    outs = []
+    for name, wsp in (("workspace", ws[:need]), ("larger workspace", ws), ("no workspace", None)):
+        Y.fill_(2.0)
+        hgnn.hgnn_spmm(g, wd, 1, X, Y, op=hgnn.HGNN_MEAN, workspace=wsp)
+        outs.append(down(Y).copy())
+        compare(f"hgnn_spmm, {name}", outs[-1], ref, sabs)
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+    with pytest.raises(hgnn.HgnnError) as ei:
+        hgnn.hgnn_spmm(g, wd, 1, X, Y, workspace=ws[:need - 256])
+    assert ei.value.status == hgnn.HGNN_EINVAL and "workspace" in str(ei.value)
+    with pytest.raises(hgnn.HgnnError):
+        hgnn.hgnn_spmm(g, wd, 1, X, Y, workspace=ws[8:need + 8])  # not 16-byte aligned
+    rowptr2, col2 = rand_graph(40, 40, 3, 5)
+    assert hgnn.hgnn_spmm_workspace(40, col2.size, F) == 0
 
 
 @pytest.mark.parametrize("H,D,nb", [(1, 64, 4), (4, 16, 3), (2, 32, 8)])

@@ -6,10 +6,17 @@ import pytest
 import torch
 
 import oracle
-from parity import compare, down, f16, rand_graph, up
+import functools
+
+import parity
+from parity import down, f16, rand_graph, spmm_plain, up
 from test_gpu_gat_fused import bwd_reference, check_lse, gat_backward_check
 
 pytestmark = pytest.mark.gpu
+
+# drawn shapes include graphs of one or two vertices whose results cancel to (nearly) nothing: the sweep alone may take
+# the cancelling branch of the norm rule, and every time it does the call is recorded and printed
+compare = functools.partial(parity.compare, allow_cancel=True)
 
 
 def draw(seed):
@@ -43,7 +50,7 @@ def test_random_configuration(hgnn, dev, seed):
     # ---- SpMM: plain, discretized (with the drawn blocks), vertex groups
     ref, sabs = oracle.spmm(rowptr, col, X, w=w, H=H, reduce=c["reduce"], want_sabs=True)
     Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
-    hgnn.hgnn_spmm(g, wd, H, Xd, Y, op=c["reduce"])
+    spmm_plain(hgnn, g, wd, H, Xd, Y, op=c["reduce"])
     compare("plain", down(Y), ref, sabs)
     Y.fill_(7.0)
     hgnn.hgnn_spmm_discretized(p, g, wd, H, Xd, Y, op=c["reduce"])
@@ -143,7 +150,7 @@ def test_random_coo_to_csr_bit_exact(hgnn, dev, seed):
         X = f16(r.standard_normal((ncols, 16)))
         ref, sabs = oracle.spmm(rowptr, col, X, w=w_l, eid=ref_eid, want_sabs=True)
         Y = torch.empty((V, 16), dtype=torch.float16, device=dev)
-        hgnn.hgnn_spmm(hgnn.Csr(g.rowptr, g.col, ncols=ncols, eid=eid), up(w_l, dev), 1, up(X, dev), Y)
+        spmm_plain(hgnn, hgnn.Csr(g.rowptr, g.col, ncols=ncols, eid=eid), up(w_l, dev), 1, up(X, dev), Y)
         compare("values in list order", down(Y), ref, sabs)
         bad = row_l.copy()
         bad[E // 2] = V  # one row id out of range

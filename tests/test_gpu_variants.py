@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import workloads as wl
-from parity import compare, down, f16, rand_graph, sample_rows, up
+from parity import compare, down, f16, rand_graph, sample_rows, spmm_plain, up
 
 pytestmark = pytest.mark.gpu
 
@@ -241,7 +241,7 @@ def test_padded_feature_lengths(hgnn, dev, F):
         assert np.all(got[:, F:] == 7.0), f"{name}: padding columns written"
         Yfull.fill_(7.0)
 
-    hgnn.hgnn_spmm(g, wd, 1, Xd[:, :F], Y, op=hgnn.HGNN_MEAN)
+    spmm_plain(hgnn, g, wd, 1, Xd[:, :F], Y, op=hgnn.HGNN_MEAN)
     check("plain")
     for nb in (1, 3):
         p = hgnn.hgnn_plan_create(g, 64, pitch, 1, col_blocks=nb)
@@ -277,14 +277,8 @@ def test_padded_feature_lengths(hgnn, dev, F):
 
 
 # ------------------------------------------------------------------ vector-width study: 2, 4, 8 halves per lane
-@pytest.fixture
-def restore_width(hgnn):
-    yield
-    hgnn.hgnn_set_vector_halves(8)
-
-
 @pytest.mark.parametrize("F,H", [(16, 1), (32, 1), (64, 1), (128, 1), (64, 4), (128, 8), (256, 2)])
-def test_vector_width_variants(hgnn, dev, restore_width, F, H):
+def test_vector_width_variants(hgnn, dev, F, H):
     print(f"width F={F} H={H}", flush=True)
     V, ncols = 900, 800
     rowptr, col = rand_graph(V, ncols, 10, F + H, hubs=((5, 2500), (300, 300)), empties=(0, 899))
@@ -304,8 +298,8 @@ def test_vector_width_variants(hgnn, dev, restore_width, F, H):
     Y = torch.empty((V, F), dtype=torch.float16, device=dev)
     e = torch.empty((E, H), dtype=torch.float16, device=dev)
     for vw in (2, 4, 8):
-        hgnn.hgnn_set_vector_halves(vw)
-        assert hgnn.hgnn_get_vector_halves() == vw
+        hgnn.hgnn_plan_set_vector_halves(p, vw)
+        assert hgnn.hgnn_plan_vector_halves(p) == vw
         fits = F <= 64 * vw and D % vw == 0
         if not fits:
             with pytest.raises(hgnn.HgnnError) as ei:
@@ -319,7 +313,11 @@ def test_vector_width_variants(hgnn, dev, restore_width, F, H):
         hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, Ud, Xd, e)
         compare(f"sddmm dot, {vw} halves per lane", down(e), dref, dabs)
     with pytest.raises(hgnn.HgnnError):
-        hgnn.hgnn_set_vector_halves(3)
+        hgnn.hgnn_plan_set_vector_halves(p, 3)
+    # the width belongs to the plan: a second plan of the same graph keeps the default
+    p2 = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=1)
+    assert hgnn.hgnn_plan_vector_halves(p2) == 8 and hgnn.hgnn_plan_vector_halves(p) == 8
+    hgnn.hgnn_plan_destroy(p2)
     hgnn.hgnn_plan_destroy(p)
 
 
@@ -345,7 +343,7 @@ def test_feature_table_beyond_4gib(hgnn, dev):
     p = hgnn.hgnn_plan_create(g, 256, F, H)
     Y = torch.empty((V, F), dtype=torch.float16, device=dev)
     X = Xbig[:, :F]
-    hgnn.hgnn_spmm(g, up(w, dev), 1, X, Y, op=hgnn.HGNN_MEAN)
+    spmm_plain(hgnn, g, up(w, dev), 1, X, Y, op=hgnn.HGNN_MEAN)
     compare("plain, 64-bit rows", down(Y), ref, sabs)
     hgnn.hgnn_spmm_discretized(p, g, up(w, dev), 1, X, Y, op=hgnn.HGNN_MEAN)
     compare("discretized, 64-bit rows", down(Y), ref, sabs)
@@ -494,7 +492,7 @@ def test_plain_spmm_rows_at_the_group_wave_and_hub_thresholds(hgnn, dev, avg):
         for ww in (None, w):
             ref, sabs = oracle.spmm(rowptr, col, X, w=ww, reduce=reduce, want_sabs=True)
             Y = torch.full((V, F), 5.0, dtype=torch.float16, device=dev)
-            hgnn.hgnn_spmm(g, None if ww is None else up(ww, dev), 1, up(X, dev), Y, op=reduce)
+            spmm_plain(hgnn, g, None if ww is None else up(ww, dev), 1, up(X, dev), Y, op=reduce)
             compare(f"plain, avg {avg}, reduce {reduce}, w {ww is not None}", down(Y), ref, sabs)
 
 
