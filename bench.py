@@ -13,7 +13,7 @@ JSON line.  Its top-level fields are those of the first workload (config 5); `co
 object per workload with its ops, layers, roofline and cpu_baseline.  `value` is the algorithmic
 (compulsory, infinite-cache) bytes of one step divided by the step time; `roofline` is the same figure
 for the dominant kernel alone, measured with events on the launch stream inside the timed region, with
-the measured traffic per launch (L2 misses, and HBM bytes where the counter run gave them) read from
+the measured traffic per launch (L2 misses towards the memory side) read from
 the data file that the profile summaries are made from; `cpu_baseline` is the fp64 oracle timed on a
 bounded, degree-stratified row sample of the same workload on one host core, kernel by kernel.
 """
@@ -66,7 +66,7 @@ def parse_args():
 
 
 def load_traffic():
-    """{workload name: {kernel name: {fetch_bytes, write_bytes, hbm_read_bytes?, hbm_write_bytes?, avg_us, ...}}} as
+    """{workload name: {kernel name: {fetch_bytes, write_bytes, local_memory_read_bytes?, l2_hit_rate?, avg_us, ...}}} as
     written by paper_2411_01109_amd/profile_summary.py from rocprofv3 counter runs; {} when the file is missing."""
     try:
         with open(TRAFFIC_FILE) as fh:
@@ -299,9 +299,9 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
     kdb = traffic_db.get(w.name, {})
     krec = kdb.get(dom_kernel)
     traffic = None if krec is None else float(krec["fetch_bytes"] + krec["write_bytes"])
-    hbm = None
-    if krec is not None and krec.get("hbm_read_bytes") is not None:
-        hbm = float(krec["hbm_read_bytes"] + krec.get("hbm_write_bytes", 0.0))
+    mem_side = None  # bytes between the L2s and the memory side (Infinity Cache + HBM) per launch, from the request counters
+    if krec is not None and krec.get("local_memory_read_bytes") is not None:
+        mem_side = float(krec["local_memory_read_bytes"] + krec.get("local_memory_write_bytes", 0.0))
     # a call on a column-blocked plan launches the segment kernel once per block: per-launch figures are the
     # call's figures divided by the number of blocks (the short follow-up kernels ride along in the time)
     nb_plan = hgnn.hgnn_plan_col_blocks(plan)
@@ -314,16 +314,18 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
                 "requested_bytes": int(dom_req / per_call),
                 "requested_GBps": round(dom_req / (dom_ms * 1e-3) / 1e9, 1),
                 "traffic_GBps": None if traffic is None else round(traffic * per_call / (dom_ms * 1e-3) / 1e9, 1),
-                "hbm_bytes": hbm,
-                "hbm_GBps": None if hbm is None else round(hbm * per_call / (dom_ms * 1e-3) / 1e9, 1),
-                "hbm_frac_of_peak": None if hbm is None else round(hbm * per_call / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "memory_side_bytes": mem_side,
+                "memory_side_GBps": None if mem_side is None else round(mem_side * per_call / (dom_ms * 1e-3) / 1e9, 1),
+                "memory_side_frac_of_hbm_peak": None if mem_side is None else round(mem_side * per_call / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "l2_hit_rate": None if krec is None else krec.get("l2_hit_rate"),
                 "profiled_avg_us": None if krec is None else krec.get("avg_us"),
                 "traffic_source": os.path.relpath(TRAFFIC_FILE, ROOT) if krec is not None else None,
                 "note": "per launch of the kernel: achieved = compulsory (infinite-cache) bytes / time, HIP events "
                         "around the call divided by its launches; requested_* counts one gathered feature row per "
-                        "non-zero and may exceed the peak when caches hit; traffic = L2-miss bytes per launch (fetch + "
-                        "write, includes reads the Infinity Cache serves) and hbm_bytes = bytes the memory controllers "
-                        "moved per launch, both from the rocprofv3 counter runs summarised under profiles/"}
+                        "non-zero and may exceed the peak when caches hit; traffic = L2-miss bytes per launch (FETCH_SIZE + "
+                        "WRITE_SIZE, calibrated) and memory_side_bytes = the same flow counted at the L2s' request "
+                        "interface to local memory (TCC_EA0_*_DRAM_32B): both include what the Infinity Cache serves, "
+                        "no counter of this chip separates it from HBM; from the rocprofv3 runs summarised under profiles/"}
 
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     detail = {}
@@ -491,7 +493,8 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
         "value": round(value, 1), "unit": "GB/s", "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "timed_region_s": round(wall, 3),
         "config": {"workload": w.name, "V": V, "E": E, "F": F, "H": H, "seg_edges": args.seg_edges,
-                   "col_blocks": hgnn.hgnn_plan_col_blocks(plan), "ops_per_step": [o[0] for o in ops]},
+                   "col_blocks": hgnn.hgnn_plan_col_blocks(plan), "cache_bytes_l2_llc": list(hgnn.hgnn_plan_cache_bytes(plan)),
+                   "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),
         "layers": layer_ms, "ops": detail, "column_norm": prescaled, "graph": graph_info, "static_edge_values": static_w,

@@ -162,6 +162,9 @@ int64_t hgnn_plan_num_segments(const hgnn_plan* p);
 int32_t hgnn_plan_num_split_rows(const hgnn_plan* p);
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p);
 int32_t hgnn_plan_col_blocks(const hgnn_plan* p); /* 1 when the plan is not column blocked */
+/* The cache sizes that hgnn_plan_create read from the device for its automatic column-block rule (HOST
+ * outputs, each may be NULL): one L2 (per XCD) and the last-level cache behind the L2s, in bytes. */
+void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_bytes);
 /* Column block b of a blocked plan, copied to HOST buffers (each may be NULL):
  * *nnz_b; rowptr_b [nrows+1]; col_b, eid_b [*nnz_b] (eid_b = slot in the edge
  * tensors = g->eid[k] or k of the original non-zero k); seg_row_lo / seg_row_hi

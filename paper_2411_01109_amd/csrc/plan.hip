@@ -27,8 +27,13 @@ static hsa_status_t cache_cb(hsa_cache_t cache, void* data) {
   uint8_t level = 0;
   uint32_t size = 0;
   if (hsa_cache_get_info(cache, HSA_CACHE_INFO_LEVEL, &level) == HSA_STATUS_SUCCESS &&
-      hsa_cache_get_info(cache, HSA_CACHE_INFO_SIZE, &size) == HSA_STATUS_SUCCESS && level == 3 && int64_t(size) > q->l3)
-    q->l3 = int64_t(size);
+      hsa_cache_get_info(cache, HSA_CACHE_INFO_SIZE, &size) == HSA_STATUS_SUCCESS && level == 3) {
+    // the attribute is specified in bytes; runtimes have been seen to hand through the driver's KiB figure.  No
+    // last-level cache is below 1 MiB and none is 2^30 KiB, so the unit can be told from the value
+    int64_t bytes = int64_t(size);
+    if (bytes < (int64_t(1) << 20)) bytes <<= 10;
+    if (bytes > q->l3) q->l3 = bytes;
+  }
   return HSA_STATUS_SUCCESS;
 }
 
@@ -414,6 +419,11 @@ int32_t hgnn_plan_num_split_rows(const hgnn_plan* p) { return p ? p->n_split : 0
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p) { return p ? p->S : 0; }
 
 int32_t hgnn_plan_col_blocks(const hgnn_plan* p) { return p ? p->nb : 0; }
+
+void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_bytes) {
+  if (l2_bytes) *l2_bytes = p ? p->l2_bytes : 0;
+  if (llc_bytes) *llc_bytes = p ? p->llc_bytes : 0;
+}
 
 void hgnn_plan_destroy(hgnn_plan* p) {
   if (!p) return;
