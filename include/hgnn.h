@@ -196,6 +196,18 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
                       hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* hgnn_spmm for callers that cannot allocate and own no workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as hgnn_spmm with a
+ * workspace; the scratch of the long rows is a static device array of hgnn_spmm_static_limit() bytes
+ * (32 MiB) inside the library, held by every device the library runs on until the process ends.  A graph
+ * whose bound hgnn_spmm_workspace(nrows, nnz, F) exceeds that limit is refused with HGNN_EUNSUPPORTED
+ * before anything is launched (use hgnn_spmm with a workspace).  Allocates nothing, asynchronous on
+ * `stream`.  All calls on one device share the array: calls that overlap in time on one device (two
+ * streams, two threads) race; order them on one stream. */
+size_t hgnn_spmm_static_limit(void);
+hgnn_status hgnn_spmm_static(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
+                             hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* stream);
+
 /* Discretized-reduction SpMM, edge-parallel, no atomic writes (section 5.2):
  * same result as hgnn_spmm, but every wavefront reduces one segment of the plan,
  * each partial sum covers at most seg_edges edges and is scaled by s_i before it

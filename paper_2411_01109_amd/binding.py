@@ -25,7 +25,7 @@ EXPORTS = (
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_plan_set_vector_halves",
-    "hgnn_plan_vector_halves", "hgnn_spmm_workspace", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
+    "hgnn_plan_vector_halves", "hgnn_spmm_workspace", "hgnn_spmm_static", "hgnn_spmm_static_limit", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
     "hgnn_edge_to_transposed", "hgnn_scale_rows", "hgnn_linear", "hgnn_linear_wgrad", "hgnn_linear_wgrad_workspace",
     "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace", "hgnn_gat_forward_fused_save",
     "hgnn_gat_backward_fused_saved",
@@ -91,6 +91,9 @@ def load() -> ctypes.CDLL:
     lib.hgnn_spmm_workspace.restype = ctypes.c_size_t
     lib.hgnn_spmm_workspace.argtypes = [i32, i64, i32]
     lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+    lib.hgnn_spmm_static_limit.restype = ctypes.c_size_t
+    lib.hgnn_spmm_static_limit.argtypes = []
+    lib.hgnn_spmm_static.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.hgnn_spmm_discretized.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.hgnn_spmm_discretized_fused.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp,
                                                 ctypes.POINTER(_FusionStruct), vp]
@@ -298,6 +301,18 @@ def hgnn_spmm(g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor,
                             _ptr(Y, torch.float16), _ld(Y), F, op, _ptr(row_scale, torch.float32),
                             None if workspace is None else workspace.data_ptr(),
                             0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def hgnn_spmm_static_limit() -> int:
+    return load().hgnn_spmm_static_limit()
+
+
+def hgnn_spmm_static(g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
+                     op: int = HGNN_SUM, row_scale: Optional[torch.Tensor] = None, F: Optional[int] = None, stream=None) -> None:
+    """hgnn_spmm with the library's static scratch array instead of a workspace: allocates nothing."""
+    F = X.shape[1] if F is None else F
+    _check(load().hgnn_spmm_static(g.ref, _ptr(edge_val, torch.float16), H, _ptr(X, torch.float16), _ld(X),
+                                   _ptr(Y, torch.float16), _ld(Y), F, op, _ptr(row_scale, torch.float32), _stream(stream)))
 
 
 def hgnn_spmm_discretized(p: Plan, g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,
