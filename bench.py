@@ -198,7 +198,8 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
     if has_gat:
         EH = E * H
         b = E * 4 + 4 * (V + 1) + 2 * V * F + 2 * EH
-        ops.append(("gat_score", f"hgnn::edge_score_seg_kernel<{H}>", b,
+        sliced = H == 1 and hgnn.hgnn_plan_num_slices(plan) > 0  # the plan cut the columns into LDS-sized slices
+        ops.append(("gat_score", "hgnn::edge_slice_kernel<false>" if sliced else f"hgnn::edge_score_seg_kernel<{H}>", b,
                     lambda: hgnn.hgnn_sddmm(g, plan, hgnn.HGNN_SDDMM_GAT_SCORE, H, D, X, X, e, a_l, a_r, 0.2), b + 8 * EH))
         b = 4 * EH + 4 * (V + 1)
         ops.append(("edge_softmax", "hgnn::edge_row_team_kernel<0, ..>", b,
@@ -216,8 +217,12 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
         b = 2 * EH + 4 * (V + 1) + 2 * V * H
         ops.append(("score_bwd_rowsum", "hgnn::edge_row_team_kernel<2, ..>", b,
                     lambda: hgnn.hgnn_edge_rowsum(g, plan, H, ds, d_el), b))
-        ops.append(("score_bwd_colsum", "hgnn::edge_row_team_kernel<2, ..>", b + 4 * E,
-                    lambda: hgnn.hgnn_edge_rowsum(gt, plan_t, H, ds, d_er), b + 4 * E))
+        if sliced:  # column sums over the graph itself, accumulated in LDS slice by slice
+            ops.append(("score_bwd_colsum", "hgnn::edge_slice_kernel<true>", b + 4 * E,
+                        lambda: hgnn.hgnn_edge_colsum(g, plan, H, ds, d_er), b + 4 * E))
+        else:       # row sums over the transposed graph, gathered through its edge-id map
+            ops.append(("score_bwd_colsum", "hgnn::edge_row_team_kernel<2, ..>", b + 4 * E,
+                        lambda: hgnn.hgnn_edge_rowsum(gt, plan_t, H, ds, d_er), b + 4 * E))
     step_bytes = sum(o[2] for o in ops)
 
     def step(events=None):
@@ -493,7 +498,7 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
         "value": round(value, 1), "unit": "GB/s", "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "timed_region_s": round(wall, 3),
         "config": {"workload": w.name, "V": V, "E": E, "F": F, "H": H, "seg_edges": args.seg_edges,
-                   "col_blocks": hgnn.hgnn_plan_col_blocks(plan), "cache_bytes_l2_llc": list(hgnn.hgnn_plan_cache_bytes(plan)),
+                   "col_blocks": hgnn.hgnn_plan_col_blocks(plan), "col_slices": hgnn.hgnn_plan_num_slices(plan), "cache_bytes_l2_llc": list(hgnn.hgnn_plan_cache_bytes(plan)),
                    "ops_per_step": [o[0] for o in ops]},
         "roofline": roofline, "cpu_baseline": cpu,
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4), "step_algorithmic_bytes": int(step_bytes),

@@ -295,6 +295,19 @@ int32_t hgnn_plan_group_edges(const hgnn_plan* p);
  * group j, group_first[j] = CSR position of its first non-zero.  Synchronizes the device. */
 hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32_t* group_row, int32_t* group_first);
 
+/* Column slices for the per-edge passes whose only random access is one scalar per column (section 3.1.2: the
+ * factorised GAT score adds a per-column term to every non-zero; section 2.1.2: the backward pass sums an edge
+ * tensor per column): the columns are cut into slices of slice_cols columns (64 .. 16384, 0 = 16384: the scalars of
+ * a slice then fill the LDS of one workgroup), the rows into chunks of about equal numbers of non-zeros, and the
+ * plan stores where every row's piece of every slice begins ((slices + 1) * nrows ints) plus partial column sums
+ * (8 bytes * ncols per row chunk).  hgnn_sddmm GAT_SCORE, hgnn_gat_alpha (one head) and hgnn_edge_colsum then walk
+ * (slice, chunk) pairs with the slice's scalars in LDS, so that memory only sees the streams of column ids and
+ * edge values.  It pays where rows are long: hgnn_plan_create(col_blocks = 0) adds the slices by itself when a
+ * row's piece of a slice averages 16 non-zeros or more.  Device allocations owned by the plan; synchronizes the
+ * stream; not to be called while a kernel that uses the plan is in flight. */
+hgnn_status hgnn_plan_add_slices(hgnn_plan* p, const hgnn_csr* g, int32_t slice_cols, void* stream);
+int32_t hgnn_plan_num_slices(const hgnn_plan* p); /* 0 = none */
+
 /* Vector-width study (sections 5.1.2-5.1.3 and 6.3.1: half2 against half8): halves that a lane
  * moves per feature load, 8 (16 bytes, the default and the library's design), 4 or 2.  A setting
  * of the plan, read at launch time by the two kernels that exist in all three widths: the SDDMM
@@ -453,6 +466,15 @@ hgnn_status hgnn_edge_softmax_bwd(const hgnn_csr* g, const hgnn_plan* p, int32_t
  * map) it gives the column sums d(e_r) of the GAT score backward.  p may be NULL
  * (then very long rows are slower); when given it must be the plan of g. */
 hgnn_status hgnn_edge_rowsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* t, hgnn_half* out,
+                             void* stream);
+
+/* Column sums of an edge tensor over the graph itself: out[j] = sum_{k: col[k] = j} t[k], t fp16 [nnz] (one head),
+ * out fp16 [ncols]; the same values as hgnn_edge_rowsum on the transposed graph with its edge-id map (d(e_r) of the
+ * GAT score backward), without a transposed graph and without a gather through that map.  Needs column slices in
+ * the plan (hgnn_plan_add_slices, HGNN_EINVAL otherwise) and g without an edge-id map.  The sums are formed exactly
+ * (64-bit fixed point, integer adds in LDS and per row chunk) and rounded once, so the result does not depend on the
+ * order of the additions.  Writes the plan's partial sums: order it with the other calls on the plan. */
+hgnn_status hgnn_edge_colsum(const hgnn_csr* g, const hgnn_plan* p, int32_t H, const hgnn_half* t, hgnn_half* out,
                              void* stream);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ EXPORTS = (
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
     "hgnn_edge_softmax_bwd", "hgnn_edge_rowsum", "hgnn_spmm_discretized_variant", "hgnn_plan_add_groups",
     "hgnn_plan_num_groups", "hgnn_plan_group_edges", "hgnn_plan_groups_export", "hgnn_plan_set_vector_halves",
-    "hgnn_plan_vector_halves", "hgnn_spmm_workspace", "hgnn_spmm_static", "hgnn_spmm_static_limit", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
+    "hgnn_plan_vector_halves", "hgnn_spmm_workspace", "hgnn_plan_add_slices", "hgnn_plan_num_slices", "hgnn_edge_colsum", "hgnn_spmm_static", "hgnn_spmm_static_limit", "hgnn_gat_forward_fused", "hgnn_gat_alpha", "hgnn_gat_backward_fused",
     "hgnn_edge_to_transposed", "hgnn_scale_rows", "hgnn_linear", "hgnn_linear_wgrad", "hgnn_linear_wgrad_workspace",
     "hgnn_gat_feature_grad", "hgnn_gat_feature_grad_workspace", "hgnn_gat_forward_fused_save",
     "hgnn_gat_backward_fused_saved",
@@ -101,6 +101,10 @@ def load() -> ctypes.CDLL:
     lib.hgnn_edge_softmax.argtypes = [csr, vp, i32, vp, vp, vp]
     lib.hgnn_edge_softmax_bwd.argtypes = [csr, vp, i32, vp, vp, vp, f32, vp, vp]
     lib.hgnn_edge_rowsum.argtypes = [csr, vp, i32, vp, vp, vp]
+    lib.hgnn_edge_colsum.argtypes = [csr, vp, i32, vp, vp, vp]
+    lib.hgnn_plan_add_slices.argtypes = [vp, csr, i32, vp]
+    lib.hgnn_plan_num_slices.restype = i32
+    lib.hgnn_plan_num_slices.argtypes = [vp]
     lib.hgnn_spmm_discretized_variant.argtypes = [vp, csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, ctypes.c_int, vp]
     lib.hgnn_plan_add_groups.argtypes = [vp, csr, i32, vp]
     lib.hgnn_plan_num_groups.restype = i64
@@ -496,3 +500,16 @@ def hgnn_edge_softmax_bwd(g: Csr, p: Optional[Plan], H: int, alpha: torch.Tensor
 def hgnn_edge_rowsum(g: Csr, p: Optional[Plan], H: int, t: torch.Tensor, out: torch.Tensor, stream=None) -> None:
     _check(load().hgnn_edge_rowsum(g.ref, None if p is None else p.handle, H, _ptr(t, torch.float16),
                                    _ptr(out, torch.float16), _stream(stream)))
+
+
+def hgnn_edge_colsum(g: Csr, p: Plan, H: int, t: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """out[j] = sum of t over the non-zeros of column j (needs column slices in the plan)."""
+    _check(load().hgnn_edge_colsum(g.ref, p.handle, H, _ptr(t, torch.float16), _ptr(out, torch.float16), _stream(stream)))
+
+
+def hgnn_plan_add_slices(p: Plan, g: Csr, slice_cols: int = 0, stream=None) -> None:
+    _check(load().hgnn_plan_add_slices(p.handle, g.ref, slice_cols, _stream(stream)))
+
+
+def hgnn_plan_num_slices(p: Plan) -> int:
+    return load().hgnn_plan_num_slices(p.handle)

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libhgnn.so")
-SOURCES = ["plan.hip", "blocked.hip", "groups.hip", "spmm.hip", "spmm_static.hip", "sddmm.hip", "gat.hip", "gat_bwd.hip", "softmax.hip", "transpose.hip", "dense.hip"]
+SOURCES = ["plan.hip", "blocked.hip", "groups.hip", "spmm.hip", "spmm_static.hip", "slices.hip", "sddmm.hip", "gat.hip", "gat_bwd.hip", "softmax.hip", "transpose.hip", "dense.hip"]
 # packed-fp32 instructions are switched off on purpose (the compiler must not emit v_pk_*_f32)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -298,6 +298,15 @@ struct hgnn_plan {
   int32_t* moff = nullptr;          // [nrows+1] first staging slot of a row with more than one group
   int32_t* grp_row = nullptr;       // [n_groups]
   hgnn_half* gstage = nullptr;      // [n_gslots][max_F]
+  // column slices (hgnn_plan_add_slices): slice s holds the columns [s*slice_w, (s+1)*slice_w); the edge-score and
+  // column-sum kernels keep one slice's per-column scalars in LDS
+  int32_t ns = 0;                   // slices; 0 = not built
+  int32_t slice_w = 0;
+  int32_t nch = 0;                  // row chunks of about nnz / nch non-zeros each (a multiple of 8)
+  int32_t* scut = nullptr;          // [ns+1][nrows] first CSR position of row r whose column is >= s*slice_w
+  int32_t* chunk_row = nullptr;     // [nch+1]
+  unsigned long long* col_part = nullptr;  // [nch][ncols] fixed-point partial column sums of the row chunks
+  float* col_poison = nullptr;      // [ncols] sums of non-finite inputs; zero between calls
 };
 
 namespace hgnn {
@@ -316,4 +325,8 @@ hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_
 void device_cache_bytes(int64_t* l2, int64_t* llc);  // of the current device
 hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
 hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);
+constexpr int kSliceMaxCols = 16384;  // columns per slice: 8 bytes each fill 128 KB of the 160 KB of LDS a workgroup may hold
+hgnn_status build_col_slices(hgnn_plan* p, const hgnn_csr* g, int W, hipStream_t s);
+hgnn_status slice_edge_score(const hgnn_plan* p, const hgnn_csr* g, const float* el, const float* er, const float* lse,
+                             float slope, hgnn_half* out, hipStream_t s);
 }  // namespace hgnn

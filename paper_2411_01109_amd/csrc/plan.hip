@@ -454,6 +454,10 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->moff);
   (void)hipFree(p->grp_row);
   (void)hipFree(p->gstage);
+  (void)hipFree(p->scut);
+  (void)hipFree(p->chunk_row);
+  (void)hipFree(p->col_part);
+  (void)hipFree(p->col_poison);
   delete p;
 }
 
@@ -504,6 +508,12 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
       }
     }
     if (nb > 1 && g->nnz > 0 && g->ncols >= nb) st = build_col_blocks(p, g, nb, s);
+    // column slices for the per-edge passes over per-vertex scalars: where a row's share of a slice still is a piece
+    // of 16 non-zeros or more on average
+    if (st == HGNN_OK && col_blocks == 0 && g->nrows > 0 && g->nnz > 0) {
+      const int64_t ns = ceil_div(g->ncols, kSliceMaxCols);
+      if (double(g->nnz) / g->nrows >= 16.0 * double(ns)) st = build_col_slices(p, g, kSliceMaxCols, s);
+    }
   }
   if (st != HGNN_OK) {
     hgnn_plan_destroy(p);

@@ -506,6 +506,7 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     if (st2 != HGNN_OK) return st2;
     a.el = p->vscratch;
     a.er = p->vscratch + size_t(g->nrows) * H;
+    if (H == 1 && p->ns > 0) return slice_edge_score(p, g, a.el, a.er, nullptr, neg_slope, out, s);
     return launch_edge_score(a, seg_blocks, s);
   }
   if ((vec || masked) && !score && p) {
@@ -596,5 +597,6 @@ extern "C" hgnn_status hgnn_gat_alpha(const hgnn_csr* g, const hgnn_plan* p, int
   a.el = p->vscratch;
   a.er = p->vscratch + size_t(g->nrows) * H;
   a.lse = lse;
+  if (H == 1 && p->ns > 0) return slice_edge_score(p, g, a.el, a.er, lse, neg_slope, alpha, s);
   return launch_edge_score(a, ceil_div(p->nseg, kWavesPerBlock), s);
 }
