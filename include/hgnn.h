@@ -297,8 +297,8 @@ hgnn_status hgnn_plan_groups_export(const hgnn_plan* p, const hgnn_csr* g, int32
 
 /* Column slices for the per-edge passes whose only random access is one scalar per column (section 3.1.2: the
  * factorised GAT score adds a per-column term to every non-zero; section 2.1.2: the backward pass sums an edge
- * tensor per column): the columns are cut into slices of slice_cols columns (64 .. 16384, 0 = 16384: the scalars of
- * a slice then fill the LDS of one workgroup), the rows into chunks of about equal numbers of non-zeros, and the
+ * tensor per column): the columns are cut into equal slices of at most slice_cols columns (64 .. 16384, 0 = 16384: the
+ * scalars of a slice then fill the LDS of one workgroup), the rows into chunks of about equal numbers of non-zeros, and the
  * plan stores where every row's piece of every slice begins ((slices + 1) * nrows ints) plus partial column sums
  * (8 bytes * ncols per row chunk).  hgnn_sddmm GAT_SCORE, hgnn_gat_alpha (one head) and hgnn_edge_colsum then walk
  * (slice, chunk) pairs with the slice's scalars in LDS, so that memory only sees the streams of column ids and
