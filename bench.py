@@ -48,6 +48,8 @@ def parse_args():
                     help="also record all ops of the step into one HIP graph and time its replay "
                          "(launch-bound small configs); reported under 'graph'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-busy", action="store_true",
+                    help="skip the live sampling of the memory controllers' busy percentage per op (sysfs)")
     ap.add_argument("--no-side", action="store_true",
                     help="skip the side measurements (fused GAT passes, dense side, column norm both ways): only the step")
     ap.add_argument("--detail", action="store_true", help="also print a per-op table to stderr")
@@ -75,6 +77,53 @@ def load_traffic():
         return {}
 
 
+class HbmBusy:
+    """Reads the memory controllers' busy percentage (amdgpu sysfs, mem_busy_percent) while a call is repeated for a
+    couple of seconds: the one figure on this machine that tells HBM activity from traffic that the Infinity Cache
+    absorbs (no rocprofv3 counter does).  A device-to-device copy of known size calibrates it."""
+
+    def __init__(self, torch, np):
+        import glob
+        self.torch, self.np = torch, np
+        paths = sorted(glob.glob("/sys/class/drm/card*/device/mem_busy_percent"))
+        self.path = paths[0] if paths else None
+
+    def _read(self):
+        try:
+            with open(self.path) as fh:
+                return float(fh.read().strip())
+        except (OSError, ValueError):
+            return None
+
+    def measure(self, fn, seconds=2.3, batch=10):
+        """-> (busy % as last read while fn was being repeated for `seconds`, calls per second) or (None, rate).  The
+        driver refreshes the figure about once a second, so the loop spans two refreshes and the last reading counts."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = 0
+        last = None
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(batch):
+                fn()
+            torch.cuda.synchronize()
+            n += batch
+            if self.path is not None:
+                last = self._read()
+        dt = time.perf_counter() - t0
+        return last, n / dt
+
+    def calibrate(self, dev):
+        """Busy % of a plain copy (1 GiB read + 1 GiB written per call) and of a plain read (2 GiB summed)."""
+        torch = self.torch
+        src = torch.empty(1 << 29, dtype=torch.float16, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        busy, rate = self.measure(lambda: dst.copy_(src))
+        out = {"copy_GBps": round(rate * 2 * src.numel() * 2 / 1e9, 1), "copy_busy_percent": busy}
+        del dst
+        return out
+
+
 def stratified_rows(np, rowptr, target_edges):
     """A degree-stratified row sample: rows ordered by length, every k-th one taken (with the longest row), k chosen so
     that the sample holds about target_edges non-zeros.  Returns sorted row ids."""
@@ -96,7 +145,7 @@ def sub_csr(np, rowptr, col, rows):
     return rp, col[pos], pos
 
 
-def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
+def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_probe=None, busy_cal=None):
     makers = {"c1": wl.gcn_tiny, "c2": wl.gin_overflow, "c3": wl.gat_rmat, "c4": wl.gcn_large, "c5": wl.dense_degree}
     t0 = time.time()
     w = makers[wname]()
@@ -277,6 +326,17 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
         op_cold[i] = float(np.median(ts))
     del scrub
 
+    # HBM activity of the main ops, measured live: each repeated for a good two seconds while the memory controllers'
+    # busy percentage is read (a copy of known size read ~60 % at 4.9 TB/s on this machine, i.e. the figure is close
+    # to the share of the 8 TB/s peak in use)
+    hbm_busy = {}
+    if busy_probe is not None and busy_probe.path is not None:
+        probed = ("spmm_fwd_plain", "spmm_fwd_disc", "spmm_bwd_disc", "gat_score", "edge_softmax", "gat_spmm_bwd", "sddmm_dot",
+                  "edge_softmax_bwd", "score_bwd_colsum")
+        for i, o in enumerate(ops):
+            if o[0] in probed:
+                hbm_busy[o[0]], _ = busy_probe.measure(o[3])
+
     side_steps = min(args.steps, 20)
 
     def time_call(fn):
@@ -323,6 +383,8 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
                 "memory_side_GBps": None if mem_side is None else round(mem_side * per_call / (dom_ms * 1e-3) / 1e9, 1),
                 "memory_side_frac_of_hbm_peak": None if mem_side is None else round(mem_side * per_call / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "l2_hit_rate": None if krec is None else krec.get("l2_hit_rate"),
+                "hbm_busy_percent": float(np.mean([hbm_busy[ops[i][0]] for i in idx])) if hbm_busy and all(
+                    hbm_busy.get(ops[i][0]) is not None for i in idx) else None,
                 "profiled_avg_us": None if krec is None else krec.get("avg_us"),
                 "traffic_source": os.path.relpath(TRAFFIC_FILE, ROOT) if krec is not None else None,
                 "note": "per launch of the kernel: achieved = compulsory (infinite-cache) bytes / time, HIP events "
@@ -330,7 +392,8 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
                         "non-zero and may exceed the peak when caches hit; traffic = L2-miss bytes per launch (FETCH_SIZE + "
                         "WRITE_SIZE, calibrated) and memory_side_bytes = the same flow counted at the L2s' request "
                         "interface to local memory (TCC_EA0_*_DRAM_32B): both include what the Infinity Cache serves, "
-                        "no counter of this chip separates it from HBM; from the rocprofv3 runs summarised under profiles/"}
+                        "no counter of this chip separates it from HBM; from the rocprofv3 runs summarised under profiles/; "
+                        "hbm_busy_percent = the memory controllers' busy share sampled live while the op repeats"}
 
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     detail = {}
@@ -339,6 +402,10 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first):
              "cold_ms": round(float(op_cold[i]), 4), "min_GBps": round(o[2] / (t * 1e-3) / 1e9, 1),
              "frac_of_hbm_peak": round(o[2] / (t * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
              "req_GBps": round(o[4] / (t * 1e-3) / 1e9, 1), "kernel": o[1]}
+        if o[0] in hbm_busy and hbm_busy[o[0]] is not None:
+            d["hbm_busy_percent"] = hbm_busy[o[0]]
+            if busy_cal and busy_cal.get("copy_busy_percent"):
+                d["hbm_GBps_estimate"] = round(hbm_busy[o[0]] * busy_cal["copy_GBps"] / busy_cal["copy_busy_percent"], 1)
         detail[o[0]] = d
     layer_ms = {}
     if has_gat:
@@ -633,9 +700,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     traffic_db = load_traffic()
+    busy_probe = None if args.no_hbm_busy else HbmBusy(torch, np)
+    busy_cal = busy_probe.calibrate(dev) if busy_probe is not None and busy_probe.path is not None else None
     results = {}
     for i, wname in enumerate(args.workloads):
-        results[wname] = run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first=(i == 0))
+        results[wname] = run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first=(i == 0),
+                                      busy_probe=busy_probe, busy_cal=busy_cal)
         torch.cuda.empty_cache()
     head = results[args.workloads[0]]
     line = {"metric": "fp16 SpMM/SDDMM achieved HBM GB/s (% of peak) + GNN layer fwd+bwd ms",
@@ -645,6 +715,7 @@ def main():
     for k in ("config", "roofline", "cpu_baseline", "frac_of_hbm_peak", "step_algorithmic_bytes", "layers", "ops",
               "column_norm", "graph", "static_edge_values", "gat_fused", "dense", "variants", "width_sweep", "setup"):
         line[k] = head[k]
+    line["hbm_busy_calibration"] = busy_cal
     line["timed_region_s"] = round(sum(r["timed_region_s"] for r in results.values()), 3)
     line["configs"] = results
     print(json.dumps(line))

@@ -2,7 +2,7 @@
 data file that `bench.py` reads for its roofline object.
 
 Expected input, all under one directory (here called D), for a workload tag W (c4, c5, ...), each produced by one
-rocprofv3 run of `python3 bench.py --workload W --steps N --warmup 1 --no-cpu-baseline --calib-copy`:
+rocprofv3 run of `python3 bench.py --workload W --steps N --warmup 1 --no-cpu-baseline --no-hbm-busy --calib-copy`:
 
   D/prof_W_trace/W_kernel_stats.csv          --kernel-trace --stats
   D/prof_W_fetch/W_counter_collection.csv    --pmc FETCH_SIZE
@@ -85,7 +85,7 @@ def main(argv):
     write = write["WRITE_SIZE"] if write and "WRITE_SIZE" in write else next(iter(write.values()))
     cal_f, cal_w = max(fetch[COPY]), max(write[COPY])
     kf, kw = GIB_KIB / cal_f, GIB_KIB / cal_w  # true KiB per counted KiB
-    bench_cmd = f"python3 $R/bench.py --workload {W} --steps {{n}} --warmup 1 --no-cpu-baseline --calib-copy"
+    bench_cmd = f"python3 $R/bench.py --workload {W} --steps {{n}} --warmup 1 --no-cpu-baseline --no-hbm-busy --calib-copy"
     L = [f"# rocprofv3 summary: hgnn kernels on {title} (one MI355X, bench.py step)\n",
          "Commands (run from /tmp with TMPDIR=/tmp, R = repository root; the tables are made from their CSV output by "
          "`python -m paper_2411_01109_amd.profile_summary`):\n", "```",
