@@ -137,3 +137,34 @@ def test_slices_are_added_automatically_for_long_rows(hgnn, dev):
     assert hgnn.hgnn_plan_num_slices(p3) == 0
     for q in (p, p2, p3):
         hgnn.hgnn_plan_destroy(q)
+
+
+def test_slices_degenerate_graphs(hgnn, dev):
+    """No non-zeros, a single row, fewer columns than the narrowest slice, slice widths that do not divide the columns."""
+    D = 8
+    r = np.random.default_rng(11)
+    cases = [("no non-zeros", np.zeros(6, np.int32), np.zeros(0, np.int32), 5, 70, 64),
+             ("one row", np.array([0, 40], np.int32), np.sort(r.integers(0, 300, 40)).astype(np.int32), 1, 300, 100),
+             ("few columns", *rand_graph(50, 9, 4, 3), 50, 9, 64),
+             ("193 columns in slices of 65", *rand_graph(300, 193, 30, 4, hubs=((7, 500),)), 300, 193, 65)]
+    for name, rowptr, col, V, ncols, W in cases:
+        print("degenerate:", name, flush=True)
+        E = col.size
+        g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+        p = hgnn.hgnn_plan_create(g, 64, D, 1, col_blocks=1)
+        hgnn.hgnn_plan_add_slices(p, g, W)
+        t = f16(r.standard_normal((E, 1)))
+        out = torch.full((ncols, 1), 3.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_edge_colsum(g, p, 1, up(t, dev) if E else None, out)
+        ref = oracle.edge_colsum(rowptr, col, t.astype(np.float64), ncols)
+        compare(f"column sums, {name}", down(out), ref, oracle.edge_colsum(rowptr, col, np.abs(t.astype(np.float64)), ncols))
+        if E:
+            n = max(V, ncols)
+            feat = f16(r.standard_normal((n, D)))
+            a_l, a_r = f16(0.3 * r.standard_normal(D)), f16(0.3 * r.standard_normal(D))
+            e = torch.full((E, 1), 9.0, dtype=torch.float16, device=dev)
+            hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_GAT_SCORE, 1, D, up(feat[:V], dev), up(feat[:ncols], dev), e, up(a_l, dev), up(a_r, dev), 0.2)
+            e_ref = oracle.gat_score(np.concatenate([rowptr, np.full(n - V, rowptr[-1], np.int32)]), col, feat, a_l.reshape(1, D),
+                                     a_r.reshape(1, D), 1)
+            compare(f"score, {name}", down(e), e_ref, np.abs(e_ref) + 0.5)
+        hgnn.hgnn_plan_destroy(p)
