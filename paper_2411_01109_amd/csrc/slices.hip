@@ -311,12 +311,14 @@ static SliceArgs slice_args(const hgnn_plan* p, const hgnn_csr* g) {
 template <bool COLSUM>
 static hgnn_status launch_slices(const hgnn_plan* p, const SliceArgs& a, hipStream_t s) {
   const size_t lds = slice_lds_bytes(a.W, COLSUM);
-  // beyond 64 KB of dynamic LDS the runtime wants to be told once per kernel
-  static bool told[2] = {false, false};
-  if (!told[COLSUM ? 1 : 0]) {
+  // beyond 64 KB of dynamic LDS the runtime wants to be told, once per kernel and device
+  static bool told[64][2] = {};
+  int dev = 0;
+  HGNN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64 || !told[dev][COLSUM ? 1 : 0]) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&edge_slice_kernel<COLSUM>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, int(slice_lds_bytes(kSliceMaxCols, true))));
-    told[COLSUM ? 1 : 0] = true;
+    if (dev >= 0 && dev < 64) told[dev][COLSUM ? 1 : 0] = true;
   }
   edge_slice_kernel<COLSUM><<<dim3(unsigned(p->ns) * unsigned(p->nch)), kSliceThreads, lds, s>>>(a);
   HGNN_LAUNCH_CHECK("edge_slice_kernel");

@@ -115,6 +115,20 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_scale_rows(4, 8, X, 4, A, Y, 8, None) == EINVAL            # pitch < F
     assert lib.hgnn_scale_rows(4, 8, X, 8, None, Y, 8, None) == EINVAL         # scale NULL
     assert lib.hgnn_scale_rows(-1, 8, X, 8, A, Y, 8, None) == EINVAL
+    # column slices and the column sums over them; the static-scratch SpMM: argument checks come before any launch
+    assert lib.hgnn_plan_add_slices(None, gp, 0, None) == EINVAL
+    assert lib.hgnn_plan_num_slices(None) == 0
+    assert lib.hgnn_edge_colsum(gp, None, 1, X, Y, None) == EINVAL
+    assert lib.hgnn_edge_colsum(None, None, 1, X, Y, None) == EINVAL
+    assert lib.hgnn_spmm_static_limit() == 32 << 20
+    assert lib.hgnn_spmm_static(None, None, 1, X, 8, Y, 8, 8, 0, None, None) == EINVAL
+    assert lib.hgnn_spmm_static(gp, None, 1, X, 8, Y, 8, 7, 0, None, None) == EINVAL   # odd F
+    huge = make_csr(hgnn, nrows=1000, ncols=1000, nnz=40_000_000)
+    assert lib.hgnn_spmm_static(ctypes.byref(huge), None, 1, X, 128, Y, 128, 128, 0, None, None) == hgnn.HGNN_EUNSUPPORTED
+    assert b"static" in lib.hgnn_last_error()
+    l2, llc = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    lib.hgnn_plan_cache_bytes(None, ctypes.byref(l2), ctypes.byref(llc))
+    assert l2.value == 0 and llc.value == 0
     assert lib.hgnn_plan_set_vector_halves(None, 8) == EINVAL
     assert lib.hgnn_plan_vector_halves(None) == 0
     # workspace of the plan-free SpMM: a bound from the sizes alone; nothing when no row can be long
