@@ -367,10 +367,9 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     mem_side = None  # bytes between the L2s and the memory side (Infinity Cache + HBM) per launch, from the request counters
     if krec is not None and krec.get("local_memory_read_bytes") is not None:
         mem_side = float(krec["local_memory_read_bytes"] + krec.get("local_memory_write_bytes", 0.0))
-    # a call on a column-blocked plan launches the segment kernel once per block: per-launch figures are the
-    # call's figures divided by the number of blocks (the short follow-up kernels ride along in the time)
-    nb_plan = hgnn.hgnn_plan_col_blocks(plan)
-    per_call = nb_plan if (dom_kernel.startswith("hgnn::spmm_seg_kernel") and nb_plan > 1) else 1
+    # every call launches its main kernel once (a column-blocked plan walks all its blocks inside one launch); the
+    # short follow-up kernels of a call ride along in the time
+    per_call = 1
     roofline = {"bound": "hbm", "kernel": dom_kernel, "calls_per_step": len(idx), "kernel_launches_per_call": per_call,
                 "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,

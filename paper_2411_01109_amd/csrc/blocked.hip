@@ -148,6 +148,30 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
     rc = plan_build_arrays(q, &view, s, true);
     if (rc != HGNN_OK) return rc;
   }
+  // the blocks' arrays in one device table
+  std::vector<hgnn_seg_block> desc{};
+  desc.resize(size_t(nb));
+  for (int b = 0; b < nb; ++b) {
+    const hgnn_plan* q = p->sub[size_t(b)];
+    hgnn_seg_block& d = desc[size_t(b)];
+    d.rowptr = p->brp + size_t(b) * (size_t(V) + 1);
+    d.col = p->bcol + p->boff[size_t(b)];
+    d.eid = p->beid + p->boff[size_t(b)];
+    d.delta = p->bdelta + size_t(b) * size_t(V);
+    d.seg_lo = q->seg_row_lo;
+    d.seg_hi = q->seg_row_hi;
+    d.staging = q->staging;
+    d.split_row = q->split_row;
+    d.split_lo = q->split_seg_lo;
+    d.split_hi = q->split_seg_hi;
+    d.nnz = q->nnz;
+    d.nseg = q->nseg;
+    d.n_split = q->n_split;
+    d.pad = 0;
+  }
+  HGNN_HIP(hipMalloc(&p->bdesc, sizeof(hgnn_seg_block) * size_t(nb)));
+  HGNN_HIP(hipMemcpyAsync(p->bdesc, desc.data(), sizeof(hgnn_seg_block) * size_t(nb), hipMemcpyHostToDevice, s));
+  HGNN_HIP(hipStreamSynchronize(s));
   return HGNN_OK;
 }
 

@@ -239,6 +239,22 @@ __device__ __forceinline__ void seg_stage_rows(int* s_row, int* s_blk, int lane,
 
 }  // namespace hgnn
 
+// One column block of a blocked plan as the kernels see it when all blocks run in one launch (device array in the plan).
+struct hgnn_seg_block {
+  const int32_t* rowptr;   // the block's own offset array [nrows+1]
+  const int32_t* col;
+  const int32_t* eid;      // slots of the creating graph's edge-id map (or CSR positions), block order
+  const int32_t* delta;    // [nrows] CSR position in the whole graph = block position + delta[row]
+  const int32_t* seg_lo;
+  const int32_t* seg_hi;
+  hgnn_half* staging;
+  const int32_t* split_row;
+  const int32_t* split_lo;
+  const int32_t* split_hi;
+  int64_t nnz, nseg;
+  int32_t n_split, pad;
+};
+
 // The plan object behind the opaque handle of the C ABI.
 constexpr int kHubEdges = 2048;  // non-zeros per chunk of a long row in the edge-row kernels
 
@@ -287,6 +303,7 @@ struct hgnn_plan {
   int32_t* bdelta = nullptr;        // [nb][nrows] CSR position in the whole graph of a blocked non-zero = its block position + bdelta[b][row]
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
+  hgnn_seg_block* bdesc = nullptr;  // [nb] the blocks' arrays, for kernels that walk all blocks in one launch
   hgnn_half* bstage = nullptr;      // [2][nb][nrows][max_F] per-block partial outputs (second set: masked GAT partials)
   float* bsum = nullptr;            // [nb][nrows][max_H][2] per-block partial row sums of edge tensors / GAT (max, sum), then [nb][nrows][max_H] masked sums
   // neighbour groups of the vertex-parallel variant (hgnn_plan_add_groups): row r owns the groups

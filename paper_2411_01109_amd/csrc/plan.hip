@@ -434,6 +434,7 @@ void hgnn_plan_destroy(hgnn_plan* p) {
   (void)hipFree(p->bdelta);
   (void)hipFree(p->bstage);
   (void)hipFree(p->bsum);
+  (void)hipFree(p->bdesc);
   (void)hipFree(p->seg_row_lo);
   (void)hipFree(p->seg_row_hi);
   (void)hipFree(p->split_row);

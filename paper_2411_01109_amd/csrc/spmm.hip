@@ -49,7 +49,47 @@ struct SpmmArgs {
   const int* split_hi;
   int n_split;
   int atomic_y;  // 1: conflicting pieces are added to Y with packed fp16 atomics instead of being staged (comparison variant)
+  // all column blocks of a plan in one launch: workgroups are numbered block after block (they are dispatched in that
+  // order, so the compute units still gather from one slice of X at a time, without a drain between the blocks)
+  const hgnn_seg_block* blocks;  // nullptr: the arrays above describe the one graph of the launch
+  int nblocks;
+  int use_eid;             // the call's graph has an edge-id map: slots through the blocks' copy of it, else through delta
+  int64_t block_y_stride;  // halves between the blocks' partial outputs
 };
+
+// Finds the block of workgroup `wg` when blocks are walked in one launch (per block cnt(b) workgroups, at least one
+// so that an empty block still zero-fills its partial output), rewrites `a` to that block's arrays and returns the
+// workgroup's number inside the block; wg_count receives the block's workgroup count.
+template <class Count>
+__device__ __forceinline__ int64_t enter_block(SpmmArgs& a, int64_t wg, int64_t& wg_count, Count cnt) {
+  int b = 0;
+  int64_t first = 0;
+  for (;;) {
+    const int64_t c = cnt(a.blocks[b]);
+    if (wg < first + c || b + 1 == a.nblocks) {
+      wg_count = c;
+      break;
+    }
+    first += c;
+    ++b;
+  }
+  const hgnn_seg_block& B = a.blocks[b];
+  a.rowptr = B.rowptr;
+  a.col = B.col;
+  a.eid = a.use_eid ? B.eid : nullptr;
+  a.delta = a.use_eid ? nullptr : B.delta;
+  a.seg_lo = B.seg_lo;
+  a.seg_hi = B.seg_hi;
+  a.staging = reinterpret_cast<half_t*>(B.staging);
+  a.split_row = B.split_row;
+  a.split_lo = B.split_lo;
+  a.split_hi = B.split_hi;
+  a.nnz = B.nnz;
+  a.nseg = B.nseg;
+  a.n_split = B.n_split;
+  a.Y += int64_t(b) * a.block_y_stride;
+  return wg - first;
+}
 
 __device__ __forceinline__ float scale_of(const SpmmArgs& a, int r) {
   float s = 1.f;
@@ -475,7 +515,13 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   int* m_trow = m_hrow + G;
 
   const int wpb = int(blockDim.x) / kWave;  // waves per workgroup (4, 2 or 1, chosen on the host for LDS packing)
-  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = enter_block(a, wg, wg_count, [&](const hgnn_seg_block& B) {
+      const int64_t c = (B.nseg + wpb - 1) / wpb;
+      return c > 0 ? c : int64_t(1);
+    });
+  const int64_t wid = wg * wpb + wave;
   const int64_t seg = wid;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
@@ -695,7 +741,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
   }
 
   // ---- zero-fill this wave's share of the empty rows
-  const int64_t nw = int64_t(gridDim.x) * wpb;
+  const int64_t nw = wg_count * wpb;
   const int rpw = int((a.nrows + nw - 1) / nw);
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
@@ -740,7 +786,11 @@ __global__ __launch_bounds__(kBlock) void spmm_finish_kernel(SpmmArgs a) {
   const int f0 = 8 * l;
   const bool active = f0 < a.F;
   const int f0c = active ? f0 : 0;
-  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = enter_block(a, wg, wg_count,
+                     [&](const hgnn_seg_block& B) { return (int64_t(B.n_split) + kWavesPerBlock * G - 1) / (kWavesPerBlock * G); });
+  const int64_t i0 = (wg * kWavesPerBlock + wave) * G;
   if (i0 >= a.n_split) return;
   const int64_t idx = i0 + g;
   int r = 0, sa = 0, sb = -1;
@@ -1280,6 +1330,49 @@ static hgnn_status run_segments(const hgnn_plan* q, SpmmArgs a, int ncols, hipSt
   return HGNN_OK;
 }
 
+// Pass 1 and pass 2 over all column blocks of plan p, one launch each: a.Y / a.ldy / a.block_y_stride describe the
+// blocks' partial outputs.
+static hgnn_status run_segments_blocked(const hgnn_plan* p, SpmmArgs a, int ncols, hipStream_t s) {
+  const int wm = a.col_scale ? 2 : (a.w ? 1 : 0);
+  a.blocks = p->bdesc;
+  a.nblocks = p->nb;
+  a.S = p->S;
+  a.stage_ld = p->max_F;
+  const int L = pow2_at_least((a.F + 7) / 8);
+  const int G = kWave / L;
+  const SegLds lay = seg_lds_layout(a.S, a.H, wm, L);
+  const int wpb = waves_per_block_for_lds(size_t(lay.total), wm != 0);
+  const size_t lds = size_t(lay.total) * wpb;
+  HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+               "hgnn_spmm_discretized: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", a.S,
+               a.H, lds);
+  int64_t wgs = 0, wgs2 = 0;
+  for (const hgnn_plan* q : p->sub) {
+    const int64_t c = ceil_div(q->nseg, wpb);
+    wgs += c > 0 ? c : 1;
+    wgs2 += ceil_div(q->n_split, int64_t(kWavesPerBlock) * G);
+  }
+  const bool off32 = uint64_t(ncols) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);
+  dim3 grid{unsigned(wgs)};
+  const int threads = wpb * kWave;
+  if (wm == 2) {
+    if (off32) launch_seg<2, true>(L, grid, threads, lds, s, a);
+    else launch_seg<2, false>(L, grid, threads, lds, s, a);
+  } else if (wm == 1) {
+    if (off32) launch_seg<1, true>(L, grid, threads, lds, s, a);
+    else launch_seg<1, false>(L, grid, threads, lds, s, a);
+  } else {
+    if (off32) launch_seg<0, true>(L, grid, threads, lds, s, a);
+    else launch_seg<0, false>(L, grid, threads, lds, s, a);
+  }
+  HGNN_LAUNCH_CHECK("spmm_seg_kernel");
+  if (wgs2 > 0) {
+    launch_finish(L, dim3(unsigned(wgs2)), s, a);
+    HGNN_LAUNCH_CHECK("spmm_finish_kernel");
+  }
+  return HGNN_OK;
+}
+
 // Column-blocked plans: Y[r] = sum over the blocks of their (already scaled, fp16) partial rows; fp32 sum in
 // block order, one store per row.
 template <int L>
@@ -1421,20 +1514,17 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
   // column-blocked plan: one discretized SpMM per block into that block's partial output, blocks one
   // after the other so that all compute units gather from the same slice of X, then one pass adds
   // the partials of every row (and the self term, once).  Scales are applied per partial (section 5.2.2).
-  for (int b = 0; b < p->nb; ++b) {
-    const hgnn_plan* q = p->sub[size_t(b)];
+  {
+    // all blocks in one launch of each kernel (workgroups numbered block after block), into the blocks' partial outputs.
+    // Slots in the edge tensors: a graph without an edge-id map reads at its own CSR positions (block position + the
+    // row's offset, a coalesced read); a graph with one reads through the blocked copy of the map
     SpmmArgs ab = a;
-    ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
-    ab.col = p->bcol + p->boff[size_t(b)];
-    // slots in the edge tensors: a graph without an edge-id map reads at its own CSR positions (block position +
-    // the row's offset, a coalesced read); a graph with one reads through the blocked copy of the map
-    ab.eid = g->eid ? p->beid + p->boff[size_t(b)] : nullptr;
-    ab.delta = g->eid ? nullptr : p->bdelta + size_t(b) * size_t(p->nrows);
-    ab.nnz = q->nnz;
-    ab.Y = reinterpret_cast<half_t*>(p->bstage) + size_t(b) * size_t(p->nrows) * size_t(p->max_F);
+    ab.use_eid = g->eid ? 1 : 0;
+    ab.Y = reinterpret_cast<half_t*>(p->bstage);
     ab.ldy = p->max_F;
+    ab.block_y_stride = int64_t(p->nrows) * p->max_F;
     ab.self = nullptr;
-    st = run_segments(q, ab, g->ncols, s);
+    st = run_segments_blocked(p, ab, g->ncols, s);
     if (st != HGNN_OK) return st;
   }
   const int L = pow2_at_least((F + 7) / 8);
