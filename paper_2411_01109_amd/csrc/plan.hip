@@ -382,6 +382,7 @@ hgnn_status hgnn_plan_set_vector_halves(hgnn_plan* p, int32_t halves) {
   HGNN_REQUIRE(p != nullptr, HGNN_EINVAL, "hgnn_plan_set_vector_halves: plan is NULL");
   HGNN_REQUIRE(halves == 2 || halves == 4 || halves == 8, HGNN_EINVAL, "hgnn_plan_set_vector_halves: %d is not 2, 4 or 8", halves);
   p->vec_halves = halves;
+  if (p->fine) p->fine->vec_halves = halves;
   return HGNN_OK;
 }
 
@@ -419,6 +420,7 @@ int32_t hgnn_plan_num_split_rows(const hgnn_plan* p) { return p ? p->n_split : 0
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p) { return p ? p->S : 0; }
 
 int32_t hgnn_plan_col_blocks(const hgnn_plan* p) { return p ? p->nb : 0; }
+int32_t hgnn_plan_col_blocks_mapped(const hgnn_plan* p) { return p ? (p->fine ? p->fine->nb : p->nb) : 0; }
 
 void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_bytes) {
   if (l2_bytes) *l2_bytes = p ? p->l2_bytes : 0;
@@ -428,6 +430,7 @@ void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_b
 void hgnn_plan_destroy(hgnn_plan* p) {
   if (!p) return;
   for (hgnn_plan* q : p->sub) hgnn_plan_destroy(q);
+  hgnn_plan_destroy(p->fine);
   (void)hipFree(p->brp);
   (void)hipFree(p->bcol);
   (void)hipFree(p->beid);
@@ -509,6 +512,31 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
       }
     }
     if (nb > 1 && g->nnz > 0 && g->ncols >= nb) st = build_col_blocks(p, g, nb, s);
+    // A call that reads edge values through the edge-id map gathers from two tables at once: the feature rows of the
+    // block's columns and, for each of those columns, the 128-byte line of the edge tensor that the walk is currently
+    // passing (the slots of one source row are consecutive).  Both sets grow with the block's width, so such calls get
+    // blocks of half the width.
+    if (st == HGNN_OK && p->auto_blocks && p->nb > 1 && g->eid != nullptr && g->ncols >= 2 * p->nb) {
+      hgnn_plan* f = new (std::nothrow) hgnn_plan();
+      if (f == nullptr) {
+        st = fail(HGNN_ENOMEM, "hgnn_plan_create: host allocation failed");
+      } else {
+        p->fine = f;
+        f->nrows = p->nrows;
+        f->ncols = p->ncols;
+        f->nnz = p->nnz;
+        f->S = p->S;
+        f->nseg = p->nseg;
+        f->max_F = p->max_F;
+        f->max_H = p->max_H;
+        f->big_deg = p->big_deg;
+        f->mid_deg = p->mid_deg;
+        f->l2_bytes = p->l2_bytes;
+        f->llc_bytes = p->llc_bytes;
+        f->auto_blocks = true;
+        st = build_col_blocks(f, g, 2 * p->nb, s);
+      }
+    }
     // column slices for the per-edge passes over per-vertex scalars: where a row's share of a slice still is a piece
     // of 16 non-zeros or more on average
     if (st == HGNN_OK && col_blocks == 0 && g->nrows > 0 && g->nnz > 0) {

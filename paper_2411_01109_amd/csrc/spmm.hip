@@ -1514,6 +1514,8 @@ hgnn_status hgnn_spmm_discretized_fused(const hgnn_plan* p, const hgnn_csr* g, c
   // column-blocked plan: one discretized SpMM per block into that block's partial output, blocks one
   // after the other so that all compute units gather from the same slice of X, then one pass adds
   // the partials of every row (and the self term, once).  Scales are applied per partial (section 5.2.2).
+  // edge values behind an edge-id map: the plan's finer blocks, where it has them
+  if (edge_val && g->eid && p->fine) p = p->fine;
   {
     // all blocks in one launch of each kernel (workgroups numbered block after block), into the blocks' partial outputs.
     // Slots in the edge tensors: a graph without an edge-id map reads at its own CSR positions (block position + the

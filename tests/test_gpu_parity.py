@@ -543,6 +543,48 @@ def test_blocked_plan_reads_edge_tensors_through_the_calls_graph(hgnn, dev, nb, 
     hgnn.hgnn_plan_destroy(pt_plain)
 
 
+def test_auto_blocked_plan_takes_finer_blocks_behind_an_edge_map(hgnn, dev):
+    """Blocks chosen by the plan itself (a 13 MB table, rows of ~130 edges): a call that reads edge values through the
+    edge-id map runs on twice as many blocks as one that does not; both match the oracle and the unblocked plan."""
+    V, F, H = 52000, 128, 2
+    rowptr, col = rand_graph(V, V, 130, 77, hubs=((11, 30000), (40000, 5000)), empties=(0, 5, 51999))
+    E = col.size
+    r = np.random.default_rng(78)
+    dYh, w = f16(r.standard_normal((V, F))), f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    p = hgnn.hgnn_plan_create(g, 256, F, H, col_blocks=0)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=0)
+    pt1 = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=1)
+    nb = hgnn.hgnn_plan_col_blocks(pt)
+    print(f"automatic blocks: {nb}, behind the map {hgnn.hgnn_plan_col_blocks_mapped(pt)}", flush=True)
+    assert nb >= 2 and hgnn.hgnn_plan_col_blocks_mapped(pt) == 2 * nb
+    assert hgnn.hgnn_plan_col_blocks(p) == nb and hgnn.hgnn_plan_col_blocks_mapped(p) == nb  # no map, nothing finer
+    assert hgnn.hgnn_plan_col_blocks_mapped(pt1) == 1
+    rows = sample_rows(rT, 2500, 79)
+    wd, dY = up(w, dev), up(dYh, dev)
+    dX, dX1 = torch.full((V, F), 3.0, dtype=torch.float16, device=dev), torch.empty((V, F), dtype=torch.float16, device=dev)
+    for name, vals, heads in (("values behind the map", wd, H), ("no values", None, 1)):
+        ref, sabs = oracle.spmm(rT, cT, dYh, w=None if vals is None else w, H=heads, eid=None if vals is None else eT,
+                                reduce=oracle.MEAN, rows=rows, want_sabs=True)
+        hgnn.hgnn_spmm_discretized(pt, gt, vals, heads, dY, dX, op=hgnn.HGNN_MEAN)
+        hgnn.hgnn_spmm_discretized(pt1, gt, vals, heads, dY, dX1, op=hgnn.HGNN_MEAN)
+        got, got1 = down(dX), down(dX1)
+        compare(f"auto blocks, {name}", got[rows], ref, sabs)
+        compare(f"one block, {name}", got1[rows], ref, sabs)
+        # every row: the two plans differ by the rounding of the blocks' partial rows only
+        assert np.all(np.isfinite(got)) and np.all(got[np.diff(rT) == 0] == 0)
+        d = np.abs(got.astype(np.float64) - got1.astype(np.float64))
+        bound = 2.0 ** -9 * np.maximum(np.abs(got1.astype(np.float64)), 1.0) * (2 * nb + 2)
+        assert np.all(d <= bound), (name, float(d.max()))
+        again = torch.empty_like(dX)
+        hgnn.hgnn_spmm_discretized(pt, gt, vals, heads, dY, again, op=hgnn.HGNN_MEAN)
+        assert torch.equal(again, dX)
+    for q in (p, pt, pt1):
+        hgnn.hgnn_plan_destroy(q)
+
+
 @pytest.mark.parametrize("F,has_w", [(64, True), (128, False), (24, True)])
 def test_spmm_workspace_forms(hgnn, dev, F, has_w):
     """hgnn_spmm with the workspace its long rows want, with none at all (long rows on one wavefront each), and with
