@@ -168,7 +168,7 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     ew = up(w.tensors["w"]).reshape(-1, 1) if "w" in w.tensors else None
     Y = torch.empty_like(X)
     half = torch.float16
-    ws_bytes = hgnn.hgnn_spmm_workspace(V, E, F)
+    ws_bytes = hgnn.hgnn_spmm_workspace(V, V, E, F)
     spmm_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
     if has_gat:
         a_l, a_r = up(w.tensors["a_l"]), up(w.tensors["a_r"])

@@ -192,11 +192,20 @@ void hgnn_plan_destroy(hgnn_plan* p);
  * Rows above 8 times the mean length (the threshold kept within 256..1024 non-zeros) are cut
  * into chunks of 512 non-zeros that are reduced by a wavefront each and added in chunk order;
  * their lists and fp32 partial rows live in `workspace`: device memory of at least
- * hgnn_spmm_workspace(nrows, nnz, F) bytes, 16-byte aligned, owned by the caller, overwritten,
- * not to be shared by calls that overlap in time.  The size is a bound from the three
- * numbers alone (0 when no row of such a graph can be that long).  workspace == NULL is
- * allowed: every long row is then reduced by a single wavefront (correct, slow on hubs). */
-size_t hgnn_spmm_workspace(int32_t nrows, int64_t nnz, int32_t F);
+ * hgnn_spmm_workspace(nrows, ncols, nnz, F) bytes, 16-byte aligned, owned by the caller,
+ * overwritten, not to be shared by calls that overlap in time.  The size is a bound from the
+ * four numbers alone (0 when no row of such a graph can be that long).  workspace == NULL is
+ * allowed: every long row is then reduced by a single wavefront (correct, slow on hubs).
+ * Where the table X (ncols rows of F halves) is beyond three L2s, fits three quarters of the
+ * cache behind them and rows average 128 non-zeros or more, the call walks the columns in
+ * passes (ranges of about two L2 sizes of feature rows, all wavefronts in the same range at
+ * the same time): a row's share of a pass is reduced into an fp32 partial row in the
+ * workspace and the partials are added in pass order, scaled and rounded once -- the same
+ * arithmetic, the sums in another fixed order.  hgnn_spmm_workspace counts that room in
+ * (npass * nrows * F * 4 bytes and the cut positions); with ncols = 0 it returns the bound of
+ * the long rows alone, and a workspace of that size is accepted too: the call then takes one
+ * sweep per row. */
+size_t hgnn_spmm_workspace(int32_t nrows, int32_t ncols, int64_t nnz, int32_t F);
 hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,
                       hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale, void* workspace,
                       size_t workspace_bytes, void* stream);
@@ -205,7 +214,7 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as hgnn_spmm with a
  * workspace; the scratch of the long rows is a static device array of hgnn_spmm_static_limit() bytes
  * (32 MiB) inside the library, held by every device the library runs on until the process ends.  A graph
- * whose bound hgnn_spmm_workspace(nrows, nnz, F) exceeds that limit is refused with HGNN_EUNSUPPORTED
+ * whose bound for the long rows, hgnn_spmm_workspace(nrows, 0, nnz, F), exceeds that limit is refused with HGNN_EUNSUPPORTED
  * before anything is launched (use hgnn_spmm with a workspace).  Allocates nothing, asynchronous on
  * `stream`.  All calls on one device share the array: calls that overlap in time on one device (two
  * streams, two threads) race; order them on one stream. */

@@ -92,7 +92,7 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_destroy.restype = None
     lib.hgnn_plan_destroy.argtypes = [vp]
     lib.hgnn_spmm_workspace.restype = ctypes.c_size_t
-    lib.hgnn_spmm_workspace.argtypes = [i32, i64, i32]
+    lib.hgnn_spmm_workspace.argtypes = [i32, i32, i64, i32]
     lib.hgnn_spmm.argtypes = [csr, vp, i32, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
     lib.hgnn_spmm_static_limit.restype = ctypes.c_size_t
     lib.hgnn_spmm_static_limit.argtypes = []
@@ -298,9 +298,10 @@ def hgnn_plan_destroy(p: Plan) -> None:
         load().hgnn_plan_destroy(h)
 
 
-def hgnn_spmm_workspace(nrows: int, nnz: int, F: int) -> int:
-    """Bytes of device workspace hgnn_spmm wants for the long rows of such a graph (0: none can be that long)."""
-    return load().hgnn_spmm_workspace(nrows, nnz, F)
+def hgnn_spmm_workspace(nrows: int, ncols: int, nnz: int, F: int) -> int:
+    """Bytes of device workspace hgnn_spmm wants for such a graph: the long rows' scratch (0: none can be that long)
+    plus, where it walks the columns in passes, the partial rows; ncols = 0 gives the long rows' part alone."""
+    return load().hgnn_spmm_workspace(nrows, ncols, nnz, F)
 
 
 def hgnn_spmm(g: Csr, edge_val: Optional[torch.Tensor], H: int, X: torch.Tensor, Y: torch.Tensor,

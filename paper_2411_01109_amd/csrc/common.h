@@ -342,6 +342,7 @@ hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_
                       int64_t ldx, hgnn_half* Y, int64_t ldy, int32_t F, hgnn_reduce op, const float* row_scale,
                       void* scratch, size_t scratch_bytes, hipStream_t s);
 void device_cache_bytes(int64_t* l2, int64_t* llc);  // of the current device
+size_t spmm_hub_scratch_bytes(int32_t nrows, int64_t nnz, int32_t F);  // scratch of the plan-free SpMM's hub kernels alone
 hgnn_status plan_build_arrays(hgnn_plan* p, const hgnn_csr* g, hipStream_t s, bool sub);
 hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_t s);
 constexpr int kSliceMaxCols = 16384;  // columns per slice: 8 bytes each fill 128 KB of the 160 KB of LDS a workgroup may hold

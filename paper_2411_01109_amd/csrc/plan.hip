@@ -6,6 +6,8 @@
 
 #include <hsa/hsa.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace hgnn {
@@ -51,12 +53,29 @@ void device_cache_bytes(int64_t* l2, int64_t* llc) {
   *llc = int64_t(256) << 20;
   int dev = 0, v = 0;
   if (hipGetDevice(&dev) != hipSuccess) return;
+  // asked once per device: compute calls consult the sizes too
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static bool known[kMaxDev];
+  static int64_t kept[kMaxDev][2];
+  std::lock_guard<std::mutex> lock(mu);
+  if (dev >= 0 && dev < kMaxDev && known[dev]) {
+    *l2 = kept[dev][0];
+    *llc = kept[dev][1];
+    return;
+  }
   if (hipDeviceGetAttribute(&v, hipDeviceAttributeL2CacheSize, dev) == hipSuccess && v > 0) *l2 = v;
-  if (hsa_init() != HSA_STATUS_SUCCESS) return;
-  CacheQuery q{dev, 0, 0};
-  (void)hsa_iterate_agents(agent_cb, &q);
-  (void)hsa_shut_down();
-  if (q.l3 > 0) *llc = q.l3;
+  if (hsa_init() == HSA_STATUS_SUCCESS) {
+    CacheQuery q{dev, 0, 0};
+    (void)hsa_iterate_agents(agent_cb, &q);
+    (void)hsa_shut_down();
+    if (q.l3 > 0) *llc = q.l3;
+  }
+  if (dev >= 0 && dev < kMaxDev) {
+    kept[dev][0] = *l2;
+    kept[dev][1] = *llc;
+    known[dev] = true;
+  }
 }
 
 hgnn_status fail(hgnn_status s, const char* fmt, ...) {

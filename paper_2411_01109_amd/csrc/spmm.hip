@@ -248,6 +248,8 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SpmmArgs a) {
 // scratch memory; spmm_hub_sum_kernel adds a hub's partial rows in chunk order and stores the row.
 // No atomics touch feature data and the summation order is fixed.
 constexpr int kHubChunk = 512;
+constexpr int kHubGrid = 131072;  // single-wave workgroups walking the chunk list with a grid stride (with 16384 of them the
+                                  // plain SpMM of a 62 M-edge power-law graph took 5 % longer; an idle launch costs 25 us)
 
 struct HubLists {
   int* count;      // [0] chunks handed out, [1] hubs listed
@@ -372,6 +374,102 @@ __global__ __launch_bounds__(kBlock) void spmm_hub_sum_kernel(SpmmArgs a, HubLis
   }
   groups_reduce<L>(acc);
   if (g == 0 && active) store_row(a, row, f0, acc, scale_of(a, row));
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Column passes of the plan-free SpMM.  Where the feature table misses the L2s but rows are long (hundreds of
+// non-zeros), waves that each sweep their own row from its first column to its last are spread all over the table at
+// any moment and share little in the L2s.  The passes align them: the columns are cut into npass equal ranges and
+// the launch walks pass after pass (workgroups are numbered pass-major and dispatched in that order), a wave reducing
+// the piece of its row that falls into the pass's range -- contiguous, because columns ascend inside a row -- into an
+// fp32 partial row in the caller's workspace; one more kernel adds a row's npass partials in pass order, scales and
+// rounds once.  Same arithmetic as one sweep (fp32 sums, one rounding), fixed summation order, no atomics.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kPassLongRow = 16384;  // rows beyond this still go to the hub kernels
+
+// cuts[r*(npass+1) + b] = first CSR position of row r whose column is >= b*width (b = npass: end of the row).
+// One wave per row: 64 evenly spaced samples of the row give every range border a bracket of n/64 positions,
+// which the lane that owns the border then searches by bisection (two to four dependent loads in all).
+__global__ __launch_bounds__(kBlock) void row_cuts_kernel(const int* __restrict__ rowptr, const int* __restrict__ col,
+                                                           int nrows, int npass, int width, int long_row,
+                                                           int* __restrict__ cuts) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t r = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+  if (r >= nrows) return;
+  const int beg = rowptr[r], end = rowptr[r + 1];
+  const int n = end - beg;
+  int* out = cuts + r * (npass + 1);
+  if (n == 0 || n > long_row) {  // nothing to cut / a hub: its passes are empty
+    if (lane <= npass) out[lane] = lane == npass && n <= long_row ? end : beg;
+    return;
+  }
+  const int sample = col[beg + int((int64_t(lane) * n) >> 6)];
+  int below = 0;  // samples below this lane's border
+  for (int b = 1; b < npass; ++b) {
+    const int64_t key = int64_t(b) * width;
+    const int cnt = __popcll(__ballot(int64_t(sample) < key));
+    if (lane == b) below = cnt;
+  }
+  int cut = lane == 0 ? beg : end;
+  if (lane >= 1 && lane < npass) {
+    const int64_t key = int64_t(lane) * width;
+    int lo = below == 0 ? beg : beg + int((int64_t(below - 1) * n) >> 6) + 1;
+    int hi = below == kWave ? end : beg + int((int64_t(below) * n) >> 6);
+    if (below == 0) hi = beg;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (col[mid] < key) lo = mid + 1;
+      else hi = mid;
+    }
+    cut = lo;
+  }
+  if (lane <= npass) out[lane] = cut;
+}
+
+// one single-wave workgroup per (pass, row), pass-major
+template <int L, bool HAS_W>
+__global__ __launch_bounds__(kWave) void spmm_row_pass_kernel(SpmmArgs a, const int* __restrict__ cuts,
+                                                              float* __restrict__ part, int npass) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x;
+  const int g = lane / L, l = lane % L;
+  const int b = int(blockIdx.x / unsigned(a.nrows));
+  const int64_t r = blockIdx.x % unsigned(a.nrows);
+  const int f0 = 8 * l;
+  const bool active = f0 < a.F;
+  const int f0c = active ? f0 : 0;
+  const int beg = cuts[r * (npass + 1) + b], end = cuts[r * (npass + 1) + b + 1];
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  edges_accumulate<G, HAS_W, 4>(a, beg + g, end, f0c, f0c / a.D, acc);
+  groups_reduce<L>(acc);
+  if (g == 0 && active) {
+    const int pitch = (a.F + 7) & ~7;
+    float* out = part + (int64_t(b) * a.nrows + r) * pitch + f0;
+    *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
+}
+
+// a lane group per row: adds the row's partials in pass order and stores the row (hubs are left to spmm_hub_sum_kernel)
+template <int L>
+__global__ __launch_bounds__(kBlock) void spmm_pass_sum_kernel(SpmmArgs a, const float* __restrict__ part, int npass) {
+  constexpr int G = kWave / L;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / L, l = lane % L;
+  const int64_t r = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G + g;
+  const int f0 = 8 * l;
+  if (r >= a.nrows || f0 >= a.F) return;
+  if (a.rowptr[r + 1] - a.rowptr[r] > a.long_row) return;
+  const int pitch = (a.F + 7) & ~7;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int b = 0; b < npass; ++b) {
+    const float* p = part + (int64_t(b) * a.nrows + r) * pitch + f0;
+    const float4 lo = *reinterpret_cast<const float4*>(p);
+    const float4 hi = *reinterpret_cast<const float4*>(p + 4);
+    acc[0] += lo.x, acc[1] += lo.y, acc[2] += lo.z, acc[3] += lo.w;
+    acc[4] += hi.x, acc[5] += hi.y, acc[6] += hi.z, acc[7] += hi.w;
+  }
+  store_row(a, r, f0, acc, scale_of(a, int(r)));
 }
 
 // Scalar path for shapes the 16-byte path cannot take: one thread per (row, feature).
@@ -1099,8 +1197,32 @@ template <int L, bool HAS_W>
 static void launch_row_set(dim3 grid, hipStream_t s, const SpmmArgs& a, const HubLists* h) {
   spmm_row_kernel<L, HAS_W><<<grid, kWave, 0, s>>>(a);  // its waves never meet: single-wave workgroups
   if (h) {
-    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < 131072 ? h->max_chunks : 131072)), kWave, 0, s>>>(a, *h);
+    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < kHubGrid ? h->max_chunks : kHubGrid)), kWave, 0, s>>>(a, *h);
     spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
+  }
+}
+
+template <int L, bool HAS_W>
+static void launch_pass_set(hipStream_t s, const SpmmArgs& a, const HubLists* h, const int* cuts, float* part, int npass) {
+  constexpr int G = kWave / L;
+  spmm_row_pass_kernel<L, HAS_W><<<dim3(unsigned(int64_t(npass) * a.nrows)), kWave, 0, s>>>(a, cuts, part, npass);
+  spmm_pass_sum_kernel<L><<<dim3(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * G))), kBlock, 0, s>>>(a, part, npass);
+  if (h) {
+    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < kHubGrid ? h->max_chunks : kHubGrid)), kWave, 0, s>>>(a, *h);
+    spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
+  }
+}
+
+template <bool HAS_W>
+static void launch_pass(int L, hipStream_t s, const SpmmArgs& a, const HubLists* h, const int* cuts, float* part, int npass) {
+  switch (L) {
+    case 1: launch_pass_set<1, HAS_W>(s, a, h, cuts, part, npass); break;
+    case 2: launch_pass_set<2, HAS_W>(s, a, h, cuts, part, npass); break;
+    case 4: launch_pass_set<4, HAS_W>(s, a, h, cuts, part, npass); break;
+    case 8: launch_pass_set<8, HAS_W>(s, a, h, cuts, part, npass); break;
+    case 16: launch_pass_set<16, HAS_W>(s, a, h, cuts, part, npass); break;
+    case 32: launch_pass_set<32, HAS_W>(s, a, h, cuts, part, npass); break;
+    default: launch_pass_set<64, HAS_W>(s, a, h, cuts, part, npass); break;
   }
 }
 
@@ -1148,6 +1270,33 @@ static HubLayout hub_layout(int64_t nnz, int long_row, int F) {
   o.o_hbase = o.o_hrow + up(o.max_hubs * 4);
   o.o_part = o.o_hbase + up(o.max_hubs * 4);
   o.bytes = o.o_part + up(o.max_chunks * int64_t((F + 7) & ~7) * 4);
+  return o;
+}
+
+// Column passes are taken under the rule that makes a plan cut its graph into column blocks: the table (ncols rows of
+// F halves) is beyond three L2s, fits three quarters of the cache behind them, and rows average 128 non-zeros or more;
+// about two L2 sizes of feature rows per pass.  1 = one sweep.
+static int row_passes(int64_t nrows, int64_t ncols, int64_t nnz, int F) {
+  if (nrows <= 0 || nnz / nrows < 128) return 1;
+  int64_t l2 = 0, llc = 0;
+  device_cache_bytes(&l2, &llc);
+  const double table = double(ncols) * F * 2.0;
+  if (!(table > 3.0 * double(l2) && table < 0.75 * double(llc))) return 1;
+  if (int64_t(16) * nrows >= (int64_t(1) << 31)) return 1;  // one workgroup per (pass, row)
+  int np = int(table / (2.0 * double(l2)) + 0.5);
+  return np < 2 ? 2 : (np > 16 ? 16 : np);
+}
+
+struct PassLayout {
+  int64_t o_cuts, o_part, bytes;  // offsets from the end of the hub scratch
+};
+
+static PassLayout pass_layout(int64_t nrows, int npass, int F) {
+  PassLayout o{};
+  auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
+  o.o_cuts = 0;
+  o.o_part = up(nrows * (npass + 1) * 4);
+  o.bytes = o.o_part + up(int64_t(npass) * nrows * ((F + 7) & ~7) * 4);
   return o;
 }
 
@@ -1425,6 +1574,29 @@ hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_
   const HubLayout lay = hub_layout(g->nnz, a.long_row, F);
   HubLists h{};
   const bool hubs = lay.bytes > 0 && scratch != nullptr;
+  const int npass = scratch ? row_passes(g->nrows, g->ncols, g->nnz, F) : 1;
+  const PassLayout pl = pass_layout(g->nrows, npass, F);
+  if (npass > 1 && scratch_bytes >= size_t(lay.bytes + pl.bytes)) {
+    HGNN_REQUIRE((reinterpret_cast<uintptr_t>(scratch) & 15u) == 0, HGNN_EINVAL, "%s: the workspace must be 16-byte aligned", who);
+    a.long_row = kPassLongRow > a.long_row ? kPassLongRow : a.long_row;
+    if (hubs) {
+      h = hub_lists_at(scratch, lay);
+      hub_zero_kernel<<<1, kBlock, 0, s>>>(h);
+      hub_scan_kernel<<<dim3(unsigned(ceil_div(g->nrows, kBlock * kScanRows))), kBlock, 0, s>>>(a, h);
+    } else {
+      a.long_row = INT_MAX;
+    }
+    char* base = static_cast<char*>(scratch) + lay.bytes;
+    int* cuts = reinterpret_cast<int*>(base + pl.o_cuts);
+    float* part = reinterpret_cast<float*>(base + pl.o_part);
+    const int width = int(ceil_div(g->ncols, npass));
+    row_cuts_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(g->rowptr, g->col, g->nrows, npass,
+                                                                                        width, a.long_row, cuts);
+    if (edge_val) launch_pass<true>(L, s, a, hubs ? &h : nullptr, cuts, part, npass);
+    else launch_pass<false>(L, s, a, hubs ? &h : nullptr, cuts, part, npass);
+    HGNN_LAUNCH_CHECK("spmm_row_pass_kernel");
+    return HGNN_OK;
+  }
   if (hubs) {
     HGNN_REQUIRE(scratch_bytes >= size_t(lay.bytes), HGNN_EINVAL, "%s: the workspace holds %zu bytes, this graph needs %lld", who,
                  scratch_bytes, (long long)lay.bytes);
@@ -1441,15 +1613,23 @@ hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_
   return HGNN_OK;
 }
 
+size_t spmm_hub_scratch_bytes(int32_t nrows, int64_t nnz, int32_t F) {
+  if (nrows <= 0 || nnz <= 0 || F <= 0) return 0;
+  return size_t(hub_layout(nnz, hub_threshold(nrows, nnz), F).bytes);
+}
+
 }  // namespace hgnn
 
 using namespace hgnn;
 
 extern "C" {
 
-size_t hgnn_spmm_workspace(int32_t nrows, int64_t nnz, int32_t F) {
+size_t hgnn_spmm_workspace(int32_t nrows, int32_t ncols, int64_t nnz, int32_t F) {
   if (nrows <= 0 || nnz <= 0 || F <= 0) return 0;
-  return size_t(hub_layout(nnz, hub_threshold(nrows, nnz), F).bytes);
+  size_t need = spmm_hub_scratch_bytes(nrows, nnz, F);
+  const int npass = ncols > 0 ? row_passes(nrows, ncols, nnz, F) : 1;
+  if (npass > 1) need += size_t(pass_layout(nrows, npass, F).bytes);
+  return need;
 }
 
 hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, const hgnn_half* X, int64_t ldx,

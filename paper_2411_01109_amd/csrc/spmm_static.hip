@@ -49,7 +49,7 @@ hgnn_status hgnn_spmm_static(const hgnn_csr* g, const hgnn_half* edge_val, int32
   hgnn_status st = check_spmm_args(who, g, edge_val, H, X, ldx, Y, ldy, F, op);
   if (st != HGNN_OK) return st;
   if (g->nrows == 0) return HGNN_OK;
-  const size_t need = hgnn_spmm_workspace(g->nrows, g->nnz, F);
+  const size_t need = spmm_hub_scratch_bytes(g->nrows, g->nnz, F);
   HGNN_REQUIRE(need <= kStaticScratchBytes, HGNN_EUNSUPPORTED,
                "%s: a graph of %lld non-zeros with F = %d needs %zu bytes of scratch, the static array holds %zu; use hgnn_spmm "
                "with a workspace", who, (long long)g->nnz, F, need, kStaticScratchBytes);

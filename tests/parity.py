@@ -72,7 +72,7 @@ def spmm_plain(hgnn, g, edge_val, H, X, Y, workspace=True, **kw):
     F = kw.get("F") or X.shape[1]
     ws = None
     if workspace:
-        need = hgnn.hgnn_spmm_workspace(g.nrows, g.nnz, F)
+        need = hgnn.hgnn_spmm_workspace(g.nrows, g.ncols, g.nnz, F)
         if need:
             ws = _WS.get(need)
             if ws is None:

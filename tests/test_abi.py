@@ -132,9 +132,9 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_plan_set_vector_halves(None, 8) == EINVAL
     assert lib.hgnn_plan_vector_halves(None) == 0
     # workspace of the plan-free SpMM: a bound from the sizes alone; nothing when no row can be long
-    assert lib.hgnn_spmm_workspace(4, 8, 64) == 0
-    assert lib.hgnn_spmm_workspace(0, 0, 64) == 0
-    small, big = lib.hgnn_spmm_workspace(1000, 100000, 64), lib.hgnn_spmm_workspace(1000, 100000, 128)
+    assert lib.hgnn_spmm_workspace(4, 4, 8, 64) == 0
+    assert lib.hgnn_spmm_workspace(0, 0, 0, 64) == 0
+    small, big = lib.hgnn_spmm_workspace(1000, 1000, 100000, 64), lib.hgnn_spmm_workspace(1000, 1000, 100000, 128)
     assert 0 < small < big and small % 256 == 0
 
 

@@ -86,7 +86,7 @@ def test_all_sixteen_ops_of_a_step_under_graph_replay(hgnn, dev):
     a_l, a_r = up(f16(0.2 * r.standard_normal(F)), dev), up(f16(0.2 * r.standard_normal(F)), dev)
     X = torch.empty((V, F), dtype=torch.float16, device=dev)
     dY = torch.empty((V, F), dtype=torch.float16, device=dev)
-    ws = torch.empty(hgnn.hgnn_spmm_workspace(V, E, F), dtype=torch.uint8, device=dev)
+    ws = torch.empty(hgnn.hgnn_spmm_workspace(V, V, E, F), dtype=torch.uint8, device=dev)
     assert ws.numel() > 0
     scaled = torch.empty((V, F), dtype=torch.float16, device=dev)
     lam = up((0.1 / np.maximum(np.diff(rowptr), 1)).astype(np.float32), dev)

@@ -585,6 +585,46 @@ def test_auto_blocked_plan_takes_finer_blocks_behind_an_edge_map(hgnn, dev):
         hgnn.hgnn_plan_destroy(q)
 
 
+def test_plain_spmm_column_passes(hgnn, dev):
+    """hgnn_spmm on a graph whose table misses the L2s and whose rows are long walks the columns in passes when the
+    workspace has room for the partial rows: same results as one sweep per row (workspace of the long rows alone, or
+    none), up to the order of the fp32 sums, on the graph and on its transpose with values behind the edge-id map."""
+    V, F = 52000, 128
+    rowptr, col = rand_graph(V, V, 130, 91, hubs=((11, 30000), (40000, 5000), (51998, 17000)), empties=(0, 5, 51999))
+    E = col.size
+    r = np.random.default_rng(92)
+    Xh, w = f16(r.standard_normal((V, F))), f16(r.standard_normal((E, 1)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    full, hubs_only = hgnn.hgnn_spmm_workspace(V, V, E, F), hgnn.hgnn_spmm_workspace(V, 0, E, F)
+    print(f"workspace: {full} bytes with passes, {hubs_only} for the long rows alone", flush=True)
+    assert 0 < hubs_only and full >= hubs_only + 2 * V * F * 4
+    assert hgnn.hgnn_spmm_workspace(V, V, E, 32) == hgnn.hgnn_spmm_workspace(V, 0, E, 32)  # a 3 MB table: one sweep
+    ws_full = torch.empty(full, dtype=torch.uint8, device=dev)
+    ws_hubs = torch.empty(hubs_only, dtype=torch.uint8, device=dev)
+    X, wd = up(Xh, dev), up(w, dev)
+    for tag, G, rp, cl, ei in (("graph", g, rowptr, col, None), ("transpose", gt, rT, cT, eT)):
+        rows = sample_rows(rp, 2000, 93, extra_top=4)
+        for vals, red in ((None, oracle.SUM), (wd, oracle.MEAN)):
+            ref, sabs = oracle.spmm(rp, cl, Xh, w=None if vals is None else w, eid=None if vals is None else ei, reduce=red,
+                                    rows=rows, want_sabs=True)
+            outs = {}
+            for name, ws in (("passes", ws_full), ("one sweep", ws_hubs), ("no workspace", None)):
+                Y = torch.full((V, F), 3.0, dtype=torch.float16, device=dev)
+                hgnn.hgnn_spmm(G, vals, 1, X, Y, op=red, workspace=ws)
+                outs[name] = down(Y)
+                compare(f"plain spmm, {tag}, {name}, values={vals is not None}", outs[name][rows], ref, sabs)
+                assert np.all(outs[name][np.diff(rp) == 0] == 0)
+            # every row: the forms differ in the order of fp32 additions only, i.e. by an fp16 rounding at most
+            a, b = outs["passes"].astype(np.float64), outs["one sweep"].astype(np.float64)
+            assert np.all(np.isfinite(a))
+            assert np.all(np.abs(a - b) <= 2.0 ** -9 * np.maximum(np.abs(b), 2.0 ** -6)), float(np.abs(a - b).max())
+            Y2 = torch.empty((V, F), dtype=torch.float16, device=dev)
+            hgnn.hgnn_spmm(G, vals, 1, X, Y2, op=red, workspace=ws_full)
+            assert np.array_equal(down(Y2).view(np.uint16), outs["passes"].view(np.uint16))  # fixed summation order
+
+
 @pytest.mark.parametrize("F,has_w", [(64, True), (128, False), (24, True)])
 def test_spmm_workspace_forms(hgnn, dev, F, has_w):
     """hgnn_spmm with the workspace its long rows want, with none at all (long rows on one wavefront each), and with
@@ -597,7 +637,7 @@ def test_spmm_workspace_forms(hgnn, dev, F, has_w):
     g = hgnn.Csr(up(rowptr, dev), up(col, dev))
     X, wd = up(Xh, dev), None if w is None else up(w, dev)
     ref, sabs = oracle.spmm(rowptr, col, Xh, w=w, reduce=oracle.MEAN, want_sabs=True)
-    need = hgnn.hgnn_spmm_workspace(V, col.size, F)
+    need = hgnn.hgnn_spmm_workspace(V, V, col.size, F)
     assert need > 0
     ws = torch.empty(need + 64, dtype=torch.uint8, device=dev)
     Y = torch.empty((V, F), dtype=torch.float16, device=dev)
@@ -614,7 +654,7 @@ def test_spmm_workspace_forms(hgnn, dev, F, has_w):
     with pytest.raises(hgnn.HgnnError):
         hgnn.hgnn_spmm(g, wd, 1, X, Y, workspace=ws[8:need + 8])  # not 16-byte aligned
     rowptr2, col2 = rand_graph(40, 40, 3, 5)
-    assert hgnn.hgnn_spmm_workspace(40, col2.size, F) == 0
+    assert hgnn.hgnn_spmm_workspace(40, 40, col2.size, F) == 0
 
 
 @pytest.mark.parametrize("H,D,nb", [(1, 64, 4), (4, 16, 3), (2, 32, 8)])

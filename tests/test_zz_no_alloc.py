@@ -19,7 +19,7 @@ def run_pair(hgnn, dev, V, avg, hubs, F, has_w, reduce, seed):
     w = f16(r.standard_normal((col.size, 1))) if has_w else None
     g = hgnn.Csr(up(rowptr, dev), up(col, dev))
     X, wd = up(Xh, dev), None if w is None else up(w, dev)
-    need = hgnn.hgnn_spmm_workspace(V, col.size, F)
+    need = hgnn.hgnn_spmm_workspace(V, 0, col.size, F)
     assert 0 < need <= hgnn.hgnn_spmm_static_limit()
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     Y_ws = torch.full((V, F), 3.0, dtype=torch.float16, device=dev)
@@ -45,7 +45,7 @@ def test_static_scratch_rejects_what_does_not_fit(hgnn, dev):
     limit = hgnn.hgnn_spmm_static_limit()
     assert limit == 32 << 20
     V, E, F = 1000, 40_000_000, 128
-    assert hgnn.hgnn_spmm_workspace(V, E, F) > limit
+    assert hgnn.hgnn_spmm_workspace(V, 0, E, F) > limit
     # the arrays are never touched: the size check comes first (rowptr / col only need to be non-null device tensors)
     rowptr = torch.zeros(V + 1, dtype=torch.int32, device=dev)
     col = torch.zeros(16, dtype=torch.int32, device=dev)
