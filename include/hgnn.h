@@ -149,11 +149,11 @@ hgnn_status hgnn_edge_to_transposed(const hgnn_csr* gt, int32_t H, const hgnn_ha
  * fits three quarters of the cache behind them (sizes read from the device) and rows
  * average 128 non-zeros or more; with blocks chosen this way a call whose own table
  * (ncols * ldx halves) is below that size runs unblocked (blocks asked for by number are
- * always used).  Costs nnz * 8 bytes plus the partial outputs.  A graph with an edge-id map
- * that is blocked by the automatic rule is also kept in twice as many blocks, and
- * hgnn_spmm_discretized takes those when it has edge values to read through the map (the
- * scattered reads of the edge tensor are a second table to keep in the L2s); the same cost
- * once more.
+ * always used).  Costs nnz * 8 bytes plus the partial outputs.  A graph that is blocked by
+ * the automatic rule is also kept in twice as many blocks: hgnn_spmm_discretized takes those
+ * when it has edge values to read through an edge-id map (the scattered reads of the edge
+ * tensor are a second table to keep in the L2s), hgnn_sddmm (dot) always (it leaves no
+ * partial rows behind); the same cost once more.
  * Edge tensors with a blocked plan: a call whose graph has no edge-id map reads them at the
  * graph's own CSR positions, whatever graph the plan was built from; a call whose graph has
  * an edge-id map reads them through the plan's blocked copy of the map, so the plan must
@@ -166,7 +166,7 @@ int64_t hgnn_plan_num_segments(const hgnn_plan* p);
 int32_t hgnn_plan_num_split_rows(const hgnn_plan* p);
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p);
 int32_t hgnn_plan_col_blocks(const hgnn_plan* p); /* 1 when the plan is not column blocked */
-int32_t hgnn_plan_col_blocks_mapped(const hgnn_plan* p); /* blocks of a call with edge values behind an edge-id map */
+int32_t hgnn_plan_col_blocks_fine(const hgnn_plan* p); /* blocks of the finer cut (= col_blocks when there is none) */
 /* The cache sizes that hgnn_plan_create read from the device for its automatic column-block rule (HOST
  * outputs, each may be NULL): one L2 (per XCD) and the last-level cache behind the L2s, in bytes. */
 void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_bytes);

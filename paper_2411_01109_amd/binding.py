@@ -20,7 +20,7 @@ HGNN_SDDMM_DOT, HGNN_SDDMM_GAT_SCORE = 0, 1
 
 EXPORTS = (
     "hgnn_status_str", "hgnn_last_error", "hgnn_csr_validate", "hgnn_transpose", "hgnn_coo_to_csr", "hgnn_plan_create",
-    "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks", "hgnn_plan_col_blocks_mapped",
+    "hgnn_plan_num_segments", "hgnn_plan_num_split_rows", "hgnn_plan_seg_edges", "hgnn_plan_col_blocks", "hgnn_plan_col_blocks_fine",
     "hgnn_plan_cache_bytes",
     "hgnn_plan_block_export", "hgnn_plan_export",
     "hgnn_plan_destroy", "hgnn_spmm", "hgnn_spmm_discretized", "hgnn_spmm_discretized_fused", "hgnn_sddmm", "hgnn_edge_softmax",
@@ -84,8 +84,8 @@ def load() -> ctypes.CDLL:
     lib.hgnn_plan_export.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.hgnn_plan_col_blocks.restype = i32
     lib.hgnn_plan_col_blocks.argtypes = [vp]
-    lib.hgnn_plan_col_blocks_mapped.restype = i32
-    lib.hgnn_plan_col_blocks_mapped.argtypes = [vp]
+    lib.hgnn_plan_col_blocks_fine.restype = i32
+    lib.hgnn_plan_col_blocks_fine.argtypes = [vp]
     lib.hgnn_plan_cache_bytes.restype = None
     lib.hgnn_plan_cache_bytes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.hgnn_plan_block_export.argtypes = [vp, i32, ctypes.POINTER(i64), vp, vp, vp, vp, vp]
@@ -243,8 +243,8 @@ def hgnn_plan_col_blocks(p: Plan) -> int:
     return load().hgnn_plan_col_blocks(p.handle)
 
 
-def hgnn_plan_col_blocks_mapped(p: Plan) -> int:
-    return load().hgnn_plan_col_blocks_mapped(p.handle)
+def hgnn_plan_col_blocks_fine(p: Plan) -> int:
+    return load().hgnn_plan_col_blocks_fine(p.handle)
 
 
 def hgnn_plan_cache_bytes(p: Plan):

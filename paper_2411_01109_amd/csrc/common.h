@@ -304,8 +304,9 @@ struct hgnn_plan {
   std::vector<int64_t> boff;        // [nb+1] first non-zero of every block in bcol / beid
   std::vector<hgnn_plan*> sub;      // [nb] segment plans of the blocks
   hgnn_seg_block* bdesc = nullptr;  // [nb] the blocks' arrays, for kernels that walk all blocks in one launch
-  hgnn_plan* fine = nullptr;        // the same graph in twice the blocks (blocked arrays only), for calls that gather edge
-                                    // values through the edge-id map; only where the automatic rule chose the blocks
+  hgnn_plan* fine = nullptr;        // the same graph in twice the blocks (blocked arrays only), for the SpMM that gathers edge
+                                    // values through the edge-id map and for the SDDMM; only where the automatic rule
+                                    // chose the blocks
   hgnn_half* bstage = nullptr;      // [2][nb][nrows][max_F] per-block partial outputs (second set: masked GAT partials)
   float* bsum = nullptr;            // [nb][nrows][max_H][2] per-block partial row sums of edge tensors / GAT (max, sum), then [nb][nrows][max_H] masked sums
   // neighbour groups of the vertex-parallel variant (hgnn_plan_add_groups): row r owns the groups

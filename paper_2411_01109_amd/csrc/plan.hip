@@ -439,7 +439,7 @@ int32_t hgnn_plan_num_split_rows(const hgnn_plan* p) { return p ? p->n_split : 0
 int32_t hgnn_plan_seg_edges(const hgnn_plan* p) { return p ? p->S : 0; }
 
 int32_t hgnn_plan_col_blocks(const hgnn_plan* p) { return p ? p->nb : 0; }
-int32_t hgnn_plan_col_blocks_mapped(const hgnn_plan* p) { return p ? (p->fine ? p->fine->nb : p->nb) : 0; }
+int32_t hgnn_plan_col_blocks_fine(const hgnn_plan* p) { return p ? (p->fine ? p->fine->nb : p->nb) : 0; }
 
 void hgnn_plan_cache_bytes(const hgnn_plan* p, int64_t* l2_bytes, int64_t* llc_bytes) {
   if (l2_bytes) *l2_bytes = p ? p->l2_bytes : 0;
@@ -534,8 +534,9 @@ hgnn_status hgnn_plan_create(const hgnn_csr* g, int32_t seg_edges, int32_t max_F
     // A call that reads edge values through the edge-id map gathers from two tables at once: the feature rows of the
     // block's columns and, for each of those columns, the 128-byte line of the edge tensor that the walk is currently
     // passing (the slots of one source row are consecutive).  Both sets grow with the block's width, so such calls get
-    // blocks of half the width.
-    if (st == HGNN_OK && p->auto_blocks && p->nb > 1 && g->eid != nullptr && g->ncols >= 2 * p->nb) {
+    // blocks of half the width.  So does the SDDMM, which leaves no partial row per block behind and only gains from
+    // the narrower slice.
+    if (st == HGNN_OK && p->auto_blocks && p->nb > 1 && g->ncols >= 2 * p->nb) {
       hgnn_plan* f = new (std::nothrow) hgnn_plan();
       if (f == nullptr) {
         st = fail(HGNN_ENOMEM, "hgnn_plan_create: host allocation failed");

@@ -523,7 +523,9 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
     const int wpb = waves_per_block_for_lds(seg_per_wave, true);
     const size_t lds = seg_per_wave * wpb;
     if (lds <= 65536 && p->nb > 1 && !p->block_eid) {  // (a plan built over an edge-id map maps its blocks to that map's slots)
-      // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident
+      // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident; on the plan's
+      // finer cut where it has one (no partial rows here, so narrower blocks cost nothing)
+      if (p->fine) p = p->fine;
       for (int b = 0; b < p->nb; ++b) {
         const hgnn_plan* q = p->sub[size_t(b)];
         if (q->nnz == 0) continue;

@@ -121,7 +121,7 @@ def test_config5_dense_degree_gin_and_gat(hgnn, dev):
     pb = hgnn.hgnn_plan_create(g, 256, 64, 1, col_blocks=0)
     ptb = hgnn.hgnn_plan_create(gt, 256, 64, 1, col_blocks=0)
     assert hgnn.hgnn_plan_col_blocks(pb) == 4 and hgnn.hgnn_plan_col_blocks(ptb) == 4
-    assert hgnn.hgnn_plan_col_blocks_mapped(pb) == 4 and hgnn.hgnn_plan_col_blocks_mapped(ptb) == 8  # only gt carries a map
+    assert hgnn.hgnn_plan_col_blocks_fine(pb) == 8 and hgnn.hgnn_plan_col_blocks_fine(ptb) == 8
     assert hgnn.hgnn_plan_num_slices(pb) == 15 and hgnn.hgnn_plan_num_slices(p) == 0  # 233 000 columns in slices of <= 16 384
     hgnn.hgnn_plan_add_groups(p, g, 256)
     Xh, dYh = w.tensors["X"], w.tensors["dY"]

@@ -558,10 +558,10 @@ def test_auto_blocked_plan_takes_finer_blocks_behind_an_edge_map(hgnn, dev):
     pt = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=0)
     pt1 = hgnn.hgnn_plan_create(gt, 256, F, H, col_blocks=1)
     nb = hgnn.hgnn_plan_col_blocks(pt)
-    print(f"automatic blocks: {nb}, behind the map {hgnn.hgnn_plan_col_blocks_mapped(pt)}", flush=True)
-    assert nb >= 2 and hgnn.hgnn_plan_col_blocks_mapped(pt) == 2 * nb
-    assert hgnn.hgnn_plan_col_blocks(p) == nb and hgnn.hgnn_plan_col_blocks_mapped(p) == nb  # no map, nothing finer
-    assert hgnn.hgnn_plan_col_blocks_mapped(pt1) == 1
+    print(f"automatic blocks: {nb}, finer cut {hgnn.hgnn_plan_col_blocks_fine(pt)}", flush=True)
+    assert nb >= 2 and hgnn.hgnn_plan_col_blocks_fine(pt) == 2 * nb
+    assert hgnn.hgnn_plan_col_blocks(p) == nb and hgnn.hgnn_plan_col_blocks_fine(p) == 2 * nb
+    assert hgnn.hgnn_plan_col_blocks_fine(pt1) == 1
     rows = sample_rows(rT, 2500, 79)
     wd, dY = up(w, dev), up(dYh, dev)
     dX, dX1 = torch.full((V, F), 3.0, dtype=torch.float16, device=dev), torch.empty((V, F), dtype=torch.float16, device=dev)
@@ -581,6 +581,18 @@ def test_auto_blocked_plan_takes_finer_blocks_behind_an_edge_map(hgnn, dev):
         again = torch.empty_like(dX)
         hgnn.hgnn_spmm_discretized(pt, gt, vals, heads, dY, again, op=hgnn.HGNN_MEAN)
         assert torch.equal(again, dX)
+    # the SDDMM takes the finer cut of the plan of the graph without a map: every edge against the oracle
+    D = F // H
+    Uh, Vh = f16(r.standard_normal((V, F))), f16(r.standard_normal((V, F)))
+    dref = oracle.sddmm_dot(rowptr, col, Uh, Vh, H=H)
+    rowi = np.repeat(np.arange(V), np.diff(rowptr))
+    dabs = np.empty((E, H))
+    for lo in range(0, E, 1 << 20):
+        sl = slice(lo, min(E, lo + (1 << 20)))
+        dabs[sl] = (np.abs(Uh[rowi[sl]].astype(np.float32)) * np.abs(Vh[col[sl]].astype(np.float32))).reshape(-1, H, D).sum(-1)
+    out = torch.full((E, H), 9.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, up(Uh, dev), up(Vh, dev), out)
+    compare("sddmm dot on the finer cut", down(out), dref, dabs)
     for q in (p, pt, pt1):
         hgnn.hgnn_plan_destroy(q)
 
