@@ -1208,8 +1208,11 @@ static void launch_pass_set(hipStream_t s, const SpmmArgs& a, const HubLists* h,
   spmm_row_pass_kernel<L, HAS_W><<<dim3(unsigned(int64_t(npass) * a.nrows)), kWave, 0, s>>>(a, cuts, part, npass);
   spmm_pass_sum_kernel<L><<<dim3(unsigned(ceil_div(a.nrows, int64_t(kWavesPerBlock) * G))), kBlock, 0, s>>>(a, part, npass);
   if (h) {
-    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < kHubGrid ? h->max_chunks : kHubGrid)), kWave, 0, s>>>(a, *h);
-    spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(h->max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
+    // only rows beyond kPassLongRow are left to the chunks here: a small grid walks the list
+    constexpr int kGrid = 8192;
+    spmm_hub_kernel<L, HAS_W><<<dim3(unsigned(h->max_chunks < kGrid ? h->max_chunks : kGrid)), kWave, 0, s>>>(a, *h);
+    const int64_t max_hubs = std::min<int64_t>(h->max_hubs, a.nnz / kPassLongRow + 1);
+    spmm_hub_sum_kernel<L><<<dim3(unsigned(ceil_div(max_hubs, kWavesPerBlock))), kBlock, 0, s>>>(a, *h);
   }
 }
 
