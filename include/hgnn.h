@@ -212,7 +212,7 @@ hgnn_status hgnn_spmm(const hgnn_csr* g, const hgnn_half* edge_val, int32_t H, c
 
 /* hgnn_spmm for callers that cannot allocate and own no workspace: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as hgnn_spmm with a
- * workspace; the scratch of the long rows is a static device array of hgnn_spmm_static_limit() bytes
+ * workspace of hgnn_spmm_workspace(nrows, 0, nnz, F) bytes (one sweep per row, no column passes); the scratch of the long rows is a static device array of hgnn_spmm_static_limit() bytes
  * (32 MiB) inside the library, held by every device the library runs on until the process ends.  A graph
  * whose bound for the long rows, hgnn_spmm_workspace(nrows, 0, nnz, F), exceeds that limit is refused with HGNN_EUNSUPPORTED
  * before anything is launched (use hgnn_spmm with a workspace).  Allocates nothing, asynchronous on

@@ -56,8 +56,8 @@ hgnn_status hgnn_spmm_static(const hgnn_csr* g, const hgnn_half* edge_val, int32
   void* scratch = nullptr;
   st = static_scratch(&scratch);
   if (st != HGNN_OK) return st;
-  return spmm_rows(who, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, scratch, kStaticScratchBytes,
-                   static_cast<hipStream_t>(stream));
+  // the array is offered as the scratch of the long rows and nothing more: one sweep per row, never column passes
+  return spmm_rows(who, g, edge_val, H, X, ldx, Y, ldy, F, op, row_scale, scratch, need, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"
