@@ -602,9 +602,14 @@ def test_plain_spmm_column_passes(hgnn, dev):
     workspace has room for the partial rows: same results as one sweep per row (workspace of the long rows alone, or
     none), up to the order of the fp32 sums, on the graph and on its transpose with values behind the edge-id map."""
     V, F = 52000, 128
-    rowptr, col = rand_graph(V, V, 130, 91, hubs=((11, 30000), (40000, 5000), (51998, 17000)), empties=(0, 5, 51999))
+    rowptr, col = rand_graph(V, V, 130, 91, hubs=((11, 30000), (40000, 5000), (51998, 17000), (100, 1), (101, 2), (102, 63),
+                                                  (103, 64), (104, 65), (105, 7), (106, 4097)), empties=(0, 5, 51999))
     E = col.size
     r = np.random.default_rng(92)
+    # rows that lie in one column range only (the first, the last), in one column, and right at a range border
+    for row, lo, hi in ((200, 0, 100), (201, V - 50, V), (202, 777, 778), (203, V // 2 - 3, V // 2 + 3), (106, V // 2, V // 2 + 1)):
+        k0, k1 = rowptr[row], rowptr[row + 1]
+        col[k0:k1] = np.sort(r.integers(lo, hi, size=k1 - k0)).astype(np.int32)
     Xh, w = f16(r.standard_normal((V, F))), f16(r.standard_normal((E, 1)))
     g = hgnn.Csr(up(rowptr, dev), up(col, dev))
     gt = hgnn.hgnn_transpose(g)
@@ -618,6 +623,8 @@ def test_plain_spmm_column_passes(hgnn, dev):
     X, wd = up(Xh, dev), up(w, dev)
     for tag, G, rp, cl, ei in (("graph", g, rowptr, col, None), ("transpose", gt, rT, cT, eT)):
         rows = sample_rows(rp, 2000, 93, extra_top=4)
+        if tag == "graph":
+            rows = np.unique(np.concatenate([rows, np.arange(100, 107), np.arange(200, 204)])).astype(np.int32)
         for vals, red in ((None, oracle.SUM), (wd, oracle.MEAN)):
             ref, sabs = oracle.spmm(rp, cl, Xh, w=None if vals is None else w, eid=None if vals is None else ei, reduce=red,
                                     rows=rows, want_sabs=True)
