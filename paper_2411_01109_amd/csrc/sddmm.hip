@@ -31,6 +31,10 @@ struct SddmmArgs {
   int nrows, ncols;
   int H, D, F, S;
   float slope;
+  // all column blocks of a plan in one launch (workgroups numbered block after block): the table of the blocks'
+  // arrays, or nullptr when the arrays above describe the one graph of the launch
+  const hgnn_seg_block* blocks;
+  int nblocks;
 };
 
 constexpr int kTile = 256;  // non-zeros per wave in the kernels that run without a plan
@@ -100,7 +104,26 @@ __global__ __launch_bounds__(kBlock, 8) void sddmm_seg_kernel(SddmmArgs a) {
   int* s_blk = reinterpret_cast<int*>(base + lay.blk_off);
   half_t* s_out = reinterpret_cast<half_t*>(base + lay.out_off);
 
-  const int64_t seg = int64_t(blockIdx.x) * (int(blockDim.x) / kWave) + wave;
+  const int wpb = int(blockDim.x) / kWave;
+  int64_t wg = blockIdx.x;
+  if (a.blocks) {  // find this workgroup's block and take over its arrays
+    int b = 0;
+    for (;;) {
+      const int64_t c = (a.blocks[b].nseg + wpb - 1) / wpb;
+      if (wg < c || b + 1 == a.nblocks) break;
+      wg -= c;
+      ++b;
+    }
+    const hgnn_seg_block& B = a.blocks[b];
+    a.rowptr = B.rowptr;
+    a.col = B.col;
+    a.eid = B.eid;
+    a.seg_lo = B.seg_lo;
+    a.seg_hi = B.seg_hi;
+    a.nseg = B.nseg;
+    a.nnz = B.nnz;
+  }
+  const int64_t seg = wg * wpb + wave;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
   const int n = valid ? int(a.nnz - e0 < S ? a.nnz - e0 : S) : 0;
@@ -526,18 +549,14 @@ extern "C" hgnn_status hgnn_sddmm(const hgnn_csr* g, const hgnn_plan* p, hgnn_sd
       // column-blocked plan: block after block, so that the gathered slice of Vt stays cache resident; on the plan's
       // finer cut where it has one (no partial rows here, so narrower blocks cost nothing)
       if (p->fine) p = p->fine;
-      for (int b = 0; b < p->nb; ++b) {
-        const hgnn_plan* q = p->sub[size_t(b)];
-        if (q->nnz == 0) continue;
-        SddmmArgs ab = a;
-        ab.rowptr = p->brp + size_t(b) * (size_t(p->nrows) + 1);
-        ab.col = p->bcol + p->boff[size_t(b)];
-        ab.eid = p->beid + p->boff[size_t(b)];
-        ab.seg_lo = q->seg_row_lo;
-        ab.seg_hi = q->seg_row_hi;
-        ab.nseg = q->nseg;
-        ab.nnz = q->nnz;
-        launch_seg(Ls, vw, masked, dim3(unsigned(ceil_div(q->nseg, wpb))), wpb * kWave, lds, s, ab);
+      // one launch over all blocks: workgroups numbered block after block and dispatched in that order
+      SddmmArgs ab = a;
+      ab.blocks = p->bdesc;
+      ab.nblocks = p->nb;
+      int64_t wgs = 0;
+      for (const hgnn_plan* q : p->sub) wgs += ceil_div(q->nseg, wpb);
+      if (wgs > 0) {
+        launch_seg(Ls, vw, masked, dim3(unsigned(wgs)), wpb * kWave, lds, s, ab);
         HGNN_LAUNCH_CHECK("sddmm_seg_kernel");
       }
       return HGNN_OK;
