@@ -121,7 +121,7 @@ __device__ __forceinline__ void store_row(const SpmmArgs& a, int64_t row, int f0
   }
   half_t* y = a.Y + row * a.ldy + f0;
   if (f0 + 8 <= a.F) {
-    *reinterpret_cast<half8_t*>(y) = h;
+    __builtin_nontemporal_store(h, reinterpret_cast<half8_t*>(y));
   } else {  // F is not a multiple of 8: the last lane of a row owns fewer than 8 features
 #pragma unroll
     for (int i = 0; i < 8; ++i)
