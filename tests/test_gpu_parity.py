@@ -644,6 +644,35 @@ def test_plain_spmm_column_passes(hgnn, dev):
             assert np.array_equal(down(Y2).view(np.uint16), outs["passes"].view(np.uint16))  # fixed summation order
 
 
+@pytest.mark.parametrize("nrows,ncols,F,ld,H", [(20000, 160000, 42, 48, 1), (30000, 52000, 128, 128, 4)])
+def test_plain_spmm_column_passes_shapes(hgnn, dev, nrows, ncols, F, ld, H):
+    """Column passes on a rectangular graph with a feature length that is no multiple of 8 (padded pitch), and with
+    several heads of edge values."""
+    rowptr, col = rand_graph(nrows, ncols, 132, 7 * F + H, hubs=((3, 20000), (4, 3)), empties=(0, nrows - 1))
+    E = col.size
+    r = np.random.default_rng(F + H)
+    Xh = np.zeros((ncols, ld), dtype=np.float16)
+    Xh[:, :F] = f16(r.standard_normal((ncols, F)))
+    Xh[:, F:] = np.float16(777.0)  # padding columns never reach a result
+    w = f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    full, hubs_only = hgnn.hgnn_spmm_workspace(nrows, ncols, E, F), hgnn.hgnn_spmm_workspace(nrows, 0, E, F)
+    assert full > hubs_only > 0
+    rows = sample_rows(rowptr, 1500, 5, extra_top=2)
+    ref, sabs = oracle.spmm(rowptr, col, np.ascontiguousarray(Xh[:, :F]), w=w, H=H, reduce=oracle.MEAN, rows=rows, want_sabs=True)
+    X, wd = up(Xh, dev), up(w, dev)
+    outs = []
+    for nbytes in (full, hubs_only):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        Y = torch.full((nrows, ld), 5.0, dtype=torch.float16, device=dev)
+        hgnn.hgnn_spmm(g, wd, H, X, Y, op=hgnn.HGNN_MEAN, F=F, workspace=ws)
+        got = down(Y)
+        compare(f"passes F={F} H={H} workspace={nbytes}", got[rows][:, :F], ref, sabs)
+        assert np.all(got[:, F:] == np.float16(5.0))  # padding columns of the output are not written
+        outs.append(got[:, :F].astype(np.float64))
+    assert np.all(np.abs(outs[0] - outs[1]) <= 2.0 ** -9 * np.maximum(np.abs(outs[1]), 2.0 ** -6))
+
+
 @pytest.mark.parametrize("F,has_w", [(64, True), (128, False), (24, True)])
 def test_spmm_workspace_forms(hgnn, dev, F, has_w):
     """hgnn_spmm with the workspace its long rows want, with none at all (long rows on one wavefront each), and with
