@@ -201,3 +201,55 @@ def test_dense_side_under_graph_replay(hgnn, dev):
         assert np.abs(got["dW"]).max() > 0 and np.all(np.isfinite(got["dW"]))
     hgnn.hgnn_plan_destroy(p)
     hgnn.hgnn_plan_destroy(pt)
+
+
+def test_long_row_forms_under_graph_replay(hgnn, dev):
+    """The forms that the library picks for long rows over a table beyond the L2s -- column passes of the plan-free
+    SpMM, automatic column blocks and their finer cut (values behind the edge-id map, SDDMM) -- recorded as one graph."""
+    V, F = 52000, 128
+    rowptr, col = rand_graph(V, V, 130, 31, hubs=((7, 20000), (900, 3000)), empties=(0, 51999))
+    E = col.size
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev))
+    gt = hgnn.hgnn_transpose(g)
+    p = hgnn.hgnn_plan_create(g, 256, F, 1, col_blocks=0)
+    pt = hgnn.hgnn_plan_create(gt, 256, F, 1, col_blocks=0)
+    assert hgnn.hgnn_plan_col_blocks(p) >= 2 and hgnn.hgnn_plan_col_blocks_fine(pt) == 2 * hgnn.hgnn_plan_col_blocks(pt)
+    need = hgnn.hgnn_spmm_workspace(V, V, E, F)
+    assert need > hgnn.hgnn_spmm_workspace(V, 0, E, F)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    X = torch.empty((V, F), dtype=torch.float16, device=dev)
+    w = torch.empty((E, 1), dtype=torch.float16, device=dev)
+    names = ("plain", "plain_T", "blocked", "mapped", "dot")
+    bufs = {k: torch.empty((E, 1) if k == "dot" else (V, F), dtype=torch.float16, device=dev) for k in names}
+
+    def step(o):
+        hgnn.hgnn_spmm(g, None, 1, X, o["plain"], op=hgnn.HGNN_MEAN, workspace=ws)
+        hgnn.hgnn_spmm(gt, w, 1, X, o["plain_T"], workspace=ws)
+        hgnn.hgnn_spmm_discretized(p, g, None, 1, X, o["blocked"])
+        hgnn.hgnn_spmm_discretized(pt, gt, w, 1, X, o["mapped"])
+        hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, 1, F, X, X, o["dot"])
+
+    def fill(seed):
+        rr = np.random.default_rng(seed)
+        X.copy_(up(f16(rr.standard_normal((V, F))), dev))
+        w.copy_(up(f16(rr.standard_normal((E, 1))), dev))
+
+    fill(1)
+    step(bufs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(bufs)
+    eager = {k: torch.empty_like(v) for k, v in bufs.items()}
+    for rep in range(3):
+        fill(20 + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: down(v).copy() for k, v in bufs.items()}
+        step(eager)
+        torch.cuda.synchronize()
+        for k in names:
+            assert np.array_equal(got[k].view(np.uint16), down(eager[k]).view(np.uint16)), (rep, k)
+            assert np.all(np.isfinite(got[k])) and np.abs(got[k].astype(np.float32)).max() > 0
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
