@@ -584,8 +584,10 @@ __device__ __forceinline__ void seg_stage_values_any(const SpmmArgs& a, int i0, 
   else seg_stage_values<WM, 0>(a, i0, n, slot, cs, s_w, s_wf);
 }
 
-template <int L, int WM, bool OFF32>
-__global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmArgs a) {
+// MAPPED = false: the call has no edge-id map (only instantiated for WM == 1, where the code of the map costs the
+// registers of a seventh wave per SIMD)
+template <int L, int WM, bool OFF32, bool MAPPED = true>
+__global__ __launch_bounds__(kBlock, WM == 0 ? 8 : ((WM == 1 && !MAPPED) ? 7 : 1)) void spmm_seg_kernel(SpmmArgs a) {
   constexpr int G = kWave / L;
   constexpr int VEC = 8 * L;  // floats per parked vector
   extern __shared__ __align__(16) unsigned char smem[];
@@ -644,7 +646,7 @@ __global__ __launch_bounds__(kBlock, WM == 0 ? 8 : 1) void spmm_seg_kernel(SpmmA
     if (nt) stream_load4<true>(a.col + e0, i0, n, c);
     else stream_load4<false>(a.col + e0, i0, n, c);
     if (WM != 0 && !a.delta) {
-      if (a.eid) {
+      if (MAPPED && a.eid) {
         int e[4];
         if (nt) stream_load4<true>(a.eid + e0, i0, n, e);
         else stream_load4<false>(a.eid + e0, i0, n, e);
@@ -1319,6 +1321,18 @@ static HubLists hub_lists_at(void* base, const HubLayout& o) {
 
 template <int WM, bool OFF32>
 static void launch_seg(int L, dim3 grid, int threads, size_t lds, hipStream_t s, const SpmmArgs& a) {
+  if (WM == 1 && !a.eid && !(a.blocks && a.use_eid)) {  // edge values at the graph's own positions
+    switch (L) {
+      case 1: spmm_seg_kernel<1, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      case 2: spmm_seg_kernel<2, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      case 4: spmm_seg_kernel<4, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      case 8: spmm_seg_kernel<8, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      case 16: spmm_seg_kernel<16, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      case 32: spmm_seg_kernel<32, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+      default: spmm_seg_kernel<64, WM, OFF32, WM != 1><<<grid, threads, lds, s>>>(a); break;
+    }
+    return;
+  }
   switch (L) {
     case 1: spmm_seg_kernel<1, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
     case 2: spmm_seg_kernel<2, WM, OFF32><<<grid, threads, lds, s>>>(a); break;
