@@ -387,11 +387,34 @@ __global__ __launch_bounds__(kBlock) void spmm_hub_sum_kernel(SpmmArgs a, HubLis
 // ---------------------------------------------------------------------------------------------------
 constexpr int kPassLongRow = 16384;  // rows beyond this still go to the hub kernels
 
+// First position p of [lo, hi) with col[p] >= key (hi if there is none), found by all 64 lanes of a wave together; every
+// lane passes the same arguments and receives the same answer: 64 evenly spaced samples narrow the range 64-fold per
+// step.  Reads stay inside [lo, hi) whatever the entries hold (an unsorted row gives a wrong cut, never a position
+// outside the row).
+__device__ __forceinline__ int wave_lower_bound(const int* __restrict__ col, int lo, int hi, int64_t key, int lane) {
+  while (hi - lo > kWave) {
+    const int n = hi - lo;
+    const int v = col[lo + int((int64_t(lane) * n) >> 6)];
+    const int cnt = __popcll(__ballot(int64_t(v) < key));
+    if (cnt == 0) return lo;
+    const int nlo = lo + int((int64_t(cnt - 1) * n) >> 6) + 1;
+    const int nhi = cnt == kWave ? hi : lo + int((int64_t(cnt) * n) >> 6);
+    lo = nlo;
+    hi = nhi;
+  }
+  const int v = lo + lane < hi ? col[lo + lane] : INT_MAX;
+  return lo + __popcll(__ballot(int64_t(v) < key));
+}
+
+constexpr int kMaxPasses = 16;
+
 // cuts[r*(npass+1) + b] = first CSR position of row r whose column is >= b*width (b = npass: end of the row).
-// One wave per row: 64 evenly spaced samples of the row give every range border a bracket of n/64 positions,
-// which the lane that owns the border then searches by bisection (two to four dependent loads in all).
+// One wave per row.  Every border is first looked for in a window of 64 entries around the place that an even spread
+// of the columns over the row would give it; the windows of all borders are loaded together, so a row whose borders
+// lie inside them costs one memory latency after its offsets.  A border outside its window is searched in the part
+// of the row that the window rules in.
 __global__ __launch_bounds__(kBlock) void row_cuts_kernel(const int* __restrict__ rowptr, const int* __restrict__ col,
-                                                           int nrows, int npass, int width, int long_row,
+                                                           int nrows, int ncols, int npass, int width, int long_row,
                                                            int* __restrict__ cuts) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t r = int64_t(blockIdx.x) * kWavesPerBlock + wave;
@@ -403,25 +426,32 @@ __global__ __launch_bounds__(kBlock) void row_cuts_kernel(const int* __restrict_
     if (lane <= npass) out[lane] = lane == npass && n <= long_row ? end : beg;
     return;
   }
-  const int sample = col[beg + int((int64_t(lane) * n) >> 6)];
-  int below = 0;  // samples below this lane's border
-  for (int b = 1; b < npass; ++b) {
-    const int64_t key = int64_t(b) * width;
-    const int cnt = __popcll(__ballot(int64_t(sample) < key));
-    if (lane == b) below = cnt;
+  int wlo[kMaxPasses], v[kMaxPasses];
+#pragma unroll
+  for (int b = 1; b < kMaxPasses; ++b) {
+    wlo[b] = beg;
+    v[b] = INT_MAX;
+    if (b < npass) {
+      int w = beg + int(int64_t(n) * b * width / ncols) - kWave / 2;
+      if (w > end - kWave) w = end - kWave;
+      if (w < beg) w = beg;
+      wlo[b] = w;
+      if (w + lane < end) v[b] = col[w + lane];
+    }
   }
   int cut = lane == 0 ? beg : end;
-  if (lane >= 1 && lane < npass) {
-    const int64_t key = int64_t(lane) * width;
-    int lo = below == 0 ? beg : beg + int((int64_t(below - 1) * n) >> 6) + 1;
-    int hi = below == kWave ? end : beg + int((int64_t(below) * n) >> 6);
-    if (below == 0) hi = beg;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (col[mid] < key) lo = mid + 1;
-      else hi = mid;
+#pragma unroll
+  for (int b = 1; b < kMaxPasses; ++b) {
+    if (b < npass) {
+      const int64_t key = int64_t(b) * width;
+      const int whi = wlo[b] + kWave < end ? wlo[b] + kWave : end;
+      const int cnt = __popcll(__ballot(int64_t(v[b]) < key));
+      int c;
+      if (cnt > 0 && cnt < whi - wlo[b]) c = wlo[b] + cnt;                          // inside the window
+      else if (cnt == 0) c = wlo[b] == beg ? beg : wave_lower_bound(col, beg, wlo[b], key, lane);  // before it
+      else c = whi == end ? end : wave_lower_bound(col, whi, end, key, lane);       // after it
+      if (lane == b) cut = c;
     }
-    cut = lo;
   }
   if (lane <= npass) out[lane] = cut;
 }
@@ -1289,7 +1319,7 @@ static int row_passes(int64_t nrows, int64_t ncols, int64_t nnz, int F) {
   if (!(table > 3.0 * double(l2) && table < 0.75 * double(llc))) return 1;
   if (int64_t(16) * nrows >= (int64_t(1) << 31)) return 1;  // one workgroup per (pass, row)
   int np = int(table / (2.0 * double(l2)) + 0.5);
-  return np < 2 ? 2 : (np > 16 ? 16 : np);
+  return np < 2 ? 2 : (np > kMaxPasses ? kMaxPasses : np);
 }
 
 struct PassLayout {
@@ -1607,8 +1637,8 @@ hgnn_status spmm_rows(const char* who, const hgnn_csr* g, const hgnn_half* edge_
     int* cuts = reinterpret_cast<int*>(base + pl.o_cuts);
     float* part = reinterpret_cast<float*>(base + pl.o_part);
     const int width = int(ceil_div(g->ncols, npass));
-    row_cuts_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(g->rowptr, g->col, g->nrows, npass,
-                                                                                        width, a.long_row, cuts);
+    row_cuts_kernel<<<dim3(unsigned(ceil_div(g->nrows, kWavesPerBlock))), kBlock, 0, s>>>(g->rowptr, g->col, g->nrows, g->ncols,
+                                                                                        npass, width, a.long_row, cuts);
     if (edge_val) launch_pass<true>(L, s, a, hubs ? &h : nullptr, cuts, part, npass);
     else launch_pass<false>(L, s, a, hubs ? &h : nullptr, cuts, part, npass);
     HGNN_LAUNCH_CHECK("spmm_row_pass_kernel");
