@@ -191,7 +191,9 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     while Lg < F // 8:
         Lg *= 2
     off32 = "true" if V * X.stride(0) * 2 < (1 << 32) else "false"
-    seg_name = lambda hw: f"hgnn::spmm_seg_kernel<{Lg}, {1 if hw else 0}, {off32}>"
+    # the weighted segment kernel exists without the code of the edge-id map (last template argument false) for calls
+    # whose graph has none, i.e. the forward graph here; every other instantiation carries it
+    seg_name = lambda hw, mapped=True: f"hgnn::spmm_seg_kernel<{Lg}, {1 if hw else 0}, {off32}, {'true' if (mapped or not hw) else 'false'}>"
     # the plan-free SpMM walks the columns in passes where its workspace bound says so (room for the partial rows)
     passes = ws_bytes > hgnn.hgnn_spmm_workspace(V, 0, E, F)
     row_name = lambda hw: f"hgnn::spmm_row{'_pass' if passes else ''}_kernel<{Lg}, {'true' if hw else 'false'}>"
@@ -199,7 +201,7 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     wH = 1 if ew is not None else 0
     ops.append(("spmm_fwd_plain", row_name(wH), spmm_min(wH, False), lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y, workspace=spmm_ws), spmm_req(wH, False)))
     ops.append(("spmm_bwd_plain", row_name(wH), spmm_min(wH, True), lambda: hgnn.hgnn_spmm(gt, ew, 1, dY, Y, workspace=spmm_ws), spmm_req(wH, True)))
-    ops.append(("spmm_fwd_disc", seg_name(wH), spmm_min(wH, False),
+    ops.append(("spmm_fwd_disc", seg_name(wH, False), spmm_min(wH, False),
                 lambda: hgnn.hgnn_spmm_discretized(plan, g, ew, 1, X, Y), spmm_req(wH, False)))
     ops.append(("spmm_bwd_disc", seg_name(wH), spmm_min(wH, True),
                 lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, ew, 1, dY, Y), spmm_req(wH, True)))
@@ -223,7 +225,7 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     Xs_buf = torch.empty_like(X)
     use_ws = E / V >= 24
     ws = Xs_buf if use_ws else None
-    fused_name = seg_name(0) if use_ws else f"hgnn::spmm_seg_kernel<{Lg}, 2, {off32}>"
+    fused_name = seg_name(0) if use_ws else f"hgnn::spmm_seg_kernel<{Lg}, 2, {off32}, true>"
     cs_min = 4 * V                                        # compulsory: the scale vector, read once
     cs_req = (4 * V + 4 * V * F) if use_ws else 4 * E     # what is asked for: table written and re-read, or a factor per edge
     if gin:  # GIN, half-precision form: (1+eps) x + lambda * mean, forward and backward
@@ -255,7 +257,7 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
         b = 4 * EH + 4 * (V + 1)
         ops.append(("edge_softmax", "hgnn::edge_row_team_kernel<0, ..>", b,
                     lambda: hgnn.hgnn_edge_softmax(g, plan, H, e, alpha), b))
-        ops.append(("gat_spmm_fwd", seg_name(H), spmm_min(H, False),
+        ops.append(("gat_spmm_fwd", seg_name(H, False), spmm_min(H, False),
                     lambda: hgnn.hgnn_spmm_discretized(plan, g, alpha, H, X, out), spmm_req(H, False)))
         ops.append(("gat_spmm_bwd", seg_name(H), spmm_min(H, True),
                     lambda: hgnn.hgnn_spmm_discretized(plan_t, gt, alpha, H, dY, dh), spmm_req(H, True)))
