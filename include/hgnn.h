@@ -25,13 +25,14 @@
  *    compute entry points are asynchronous on that stream, never synchronize and
  *    never allocate: scratch memory comes from the plan or from a workspace argument
  *    that the caller owns (hgnn_spmm, hgnn_linear_wgrad, hgnn_gat_feature_grad).
- *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_export, hgnn_transpose,
+ *    hgnn_plan_create, hgnn_plan_add_groups, hgnn_plan_add_slices, the export calls, hgnn_transpose,
  *    hgnn_coo_to_csr and hgnn_csr_validate allocate and/or synchronize (one-off set-up calls).
  *  - A plan owns scratch that the calls using it write (staging rows, per-vertex
  *    tables, per-block partial outputs): calls that use the same plan must be ordered
  *    on one stream, or otherwise not overlap in time; different plans are independent.
  *    The same holds for a workspace.  Host-side, the library keeps no mutable state
- *    except the thread-local error string.
+ *    except the thread-local error string and two per-device facts that are looked up once
+ *    (the cache sizes, the address of the static scratch array of hgnn_spmm_static).
  *  - Arithmetic: fp16 in memory, fp32 in registers, one round-to-nearest-even
  *    conversion when a value is stored.
  *  - Errors: every call returns an hgnn_status; argument errors are detected on
