@@ -136,6 +136,13 @@ def test_extension_entry_points_check_arguments_on_the_host(lib, hgnn):
     assert lib.hgnn_spmm_workspace(0, 0, 0, 64) == 0
     small, big = lib.hgnn_spmm_workspace(1000, 1000, 100000, 64), lib.hgnn_spmm_workspace(1000, 1000, 100000, 128)
     assert 0 < small < big and small % 256 == 0
+    # long rows over a table beyond the L2s (30 MB, rows of 490): room for the fp32 partial rows of the column passes
+    # on top of the long rows' scratch, which ncols = 0 gives alone; a short-row graph of the same size gets none
+    V, E, F = 233000, 114000000, 64
+    hubs_only, full = lib.hgnn_spmm_workspace(V, 0, E, F), lib.hgnn_spmm_workspace(V, V, E, F)
+    assert hubs_only > 0 and full >= hubs_only + 2 * V * F * 4 and (full - hubs_only) % 256 == 0
+    assert lib.hgnn_spmm_workspace(V, V, 20 * V, F) == lib.hgnn_spmm_workspace(V, 0, 20 * V, F)
+    assert lib.hgnn_plan_col_blocks(None) == 0 and lib.hgnn_plan_col_blocks_fine(None) == 0
 
 
 def test_header_is_plain_c_and_links(lib):
