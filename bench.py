@@ -196,7 +196,9 @@ def run_workload(args, wname, torch, np, hgnn, wl, dev, traffic_db, first, busy_
     seg_name = lambda hw, mapped=True: f"hgnn::spmm_seg_kernel<{Lg}, {1 if hw else 0}, {off32}, {'true' if (mapped or not hw) else 'false'}>"
     # the plan-free SpMM walks the columns in passes where its workspace bound says so (room for the partial rows)
     passes = ws_bytes > hgnn.hgnn_spmm_workspace(V, 0, E, F)
-    row_name = lambda hw: f"hgnn::spmm_row{'_pass' if passes else ''}_kernel<{Lg}, {'true' if hw else 'false'}>"
+    # (otherwise rows and the chunks of long rows share one launch wherever a row of the graph could be long)
+    row_kind = "row_pass" if passes else ("row_hub" if ws_bytes else "row")
+    row_name = lambda hw: f"hgnn::spmm_{row_kind}_kernel<{Lg}, {'true' if hw else 'false'}>"
     ops = []  # (name, kernel, min bytes, fn, requested bytes)
     wH = 1 if ew is not None else 0
     ops.append(("spmm_fwd_plain", row_name(wH), spmm_min(wH, False), lambda: hgnn.hgnn_spmm(g, ew, 1, X, Y, workspace=spmm_ws), spmm_req(wH, False)))
