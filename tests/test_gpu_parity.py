@@ -543,6 +543,47 @@ def test_blocked_plan_reads_edge_tensors_through_the_calls_graph(hgnn, dev, nb, 
     hgnn.hgnn_plan_destroy(pt_plain)
 
 
+@pytest.mark.parametrize("nb", [2, 8, 64])
+def test_blocked_plan_with_empty_blocks(hgnn, dev, nb):
+    """Column blocks that hold no non-zero at all (every column of the graph lies in the first or in the last block),
+    or a single segment, still leave their partial rows zero: SpMM with and without values, through an edge-id map,
+    and the SDDMM, all blocks walked in one launch."""
+    V, ncols, F, H = 700, 6400, 64, 2
+    r = np.random.default_rng(nb)
+    rowptr, col = rand_graph(V, 90, 9, 40 + nb, hubs=((3, 900),), empties=(0, 1, 699))
+    last = r.random(col.size) < 0.3  # a third of the non-zeros moves to the last columns, order inside rows kept
+    col = np.where(last, ncols - 90 + col, col).astype(np.int32)
+    for i in range(V):
+        col[rowptr[i]:rowptr[i + 1]].sort()
+    E = col.size
+    Xh, dYh, w = f16(r.standard_normal((ncols, F))), f16(r.standard_normal((V, F))), f16(r.standard_normal((E, H)))
+    g = hgnn.Csr(up(rowptr, dev), up(col, dev), ncols=ncols)
+    gt = hgnn.hgnn_transpose(g)
+    rT, cT, eT = down(gt.rowptr), down(gt.col), down(gt.eid)
+    p = hgnn.hgnn_plan_create(g, 64, F, H, col_blocks=nb)
+    pt = hgnn.hgnn_plan_create(gt, 64, F, H, col_blocks=min(nb, 8))
+    assert hgnn.hgnn_plan_col_blocks(p) == nb
+    X, dY, wd = up(Xh, dev), up(dYh, dev), up(w, dev)
+    Y = torch.full((V, F), 7.0, dtype=torch.float16, device=dev)
+    for vals, heads in ((None, 1), (wd, H)):
+        hgnn.hgnn_spmm_discretized(p, g, vals, heads, X, Y, op=hgnn.HGNN_MEAN)
+        compare(f"empty blocks nb={nb} values={vals is not None}", down(Y),
+                *oracle.spmm(rowptr, col, Xh, w=None if vals is None else w, H=heads, reduce=oracle.MEAN, want_sabs=True))
+    dX = torch.full((ncols, F), 7.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_spmm_discretized(pt, gt, wd, H, dY, dX)
+    compare(f"empty blocks nb={nb}, transposed through the map", down(dX), *oracle.spmm(rT, cT, dYh, w=w, H=H, eid=eT, want_sabs=True))
+    assert np.all(down(dX)[90:ncols - 90] == 0)  # columns that no edge touches
+    D = F // H
+    Uh = f16(r.standard_normal((V, F)))
+    out = torch.full((E, H), 9.0, dtype=torch.float16, device=dev)
+    hgnn.hgnn_sddmm(g, p, hgnn.HGNN_SDDMM_DOT, H, D, up(Uh, dev), X, out)
+    rowi = np.repeat(np.arange(V), np.diff(rowptr))
+    dabs = (np.abs(Uh[rowi].astype(np.float64)) * np.abs(Xh[col].astype(np.float64))).reshape(E, H, D).sum(-1)
+    compare(f"empty blocks nb={nb}, sddmm", down(out), oracle.sddmm_dot(rowptr, col, Uh, Xh, H=H), dabs)
+    hgnn.hgnn_plan_destroy(p)
+    hgnn.hgnn_plan_destroy(pt)
+
+
 def test_auto_blocked_plan_takes_finer_blocks_behind_an_edge_map(hgnn, dev):
     """Blocks chosen by the plan itself (a 13 MB table, rows of ~130 edges): a call that reads edge values through the
     edge-id map runs on twice as many blocks as one that does not; both match the oracle and the unblocked plan."""
