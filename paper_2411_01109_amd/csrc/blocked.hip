@@ -168,6 +168,7 @@ hgnn_status build_col_blocks(hgnn_plan* p, const hgnn_csr* g, int nb, hipStream_
     d.nseg = q->nseg;
     d.n_split = q->n_split;
     d.pad = 0;
+    d.stage_mz = q->stage_mz;
   }
   HGNN_HIP(hipMalloc(&p->bdesc, sizeof(hgnn_seg_block) * size_t(nb)));
   HGNN_HIP(hipMemcpyAsync(p->bdesc, desc.data(), sizeof(hgnn_seg_block) * size_t(nb), hipMemcpyHostToDevice, s));

@@ -253,6 +253,7 @@ struct hgnn_seg_block {
   const int32_t* split_hi;
   int64_t nnz, nseg;
   int32_t n_split, pad;
+  float* stage_mz;         // scalars of the staged pieces of the fused GAT passes
 };
 
 // The plan object behind the opaque handle of the C ABI.

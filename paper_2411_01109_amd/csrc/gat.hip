@@ -55,7 +55,49 @@ struct GatArgs {
   const int* split_lo;
   const int* split_hi;
   int n_split;
+  // all column blocks of a plan in one launch (workgroups numbered block after block): the table of the blocks'
+  // arrays, or nullptr when the fields above describe the one graph of the launch.  Y, part_mz, Ym and csum then
+  // point at block 0's partial results and advance by the strides per block.
+  const hgnn_seg_block* blocks;
+  int nblocks, max_F, max_H;
+  int64_t y_stride, mz_stride, c_stride;
 };
+
+// Finds the block of workgroup wg (cnt(B) workgroups per block), rewrites `a` to that block and returns the
+// workgroup's number inside the block; wg_count receives the block's workgroup count.
+template <class Count>
+__device__ __forceinline__ int64_t gat_enter_block(GatArgs& a, int64_t wg, int64_t& wg_count, Count cnt) {
+  int b = 0;
+  for (;;) {
+    const int64_t c = cnt(a.blocks[b]);
+    wg_count = c;
+    if (wg < c || b + 1 == a.nblocks) break;
+    wg -= c;
+    ++b;
+  }
+  const hgnn_seg_block& B = a.blocks[b];
+  a.rowptr = B.rowptr;
+  a.col = B.col;
+  a.nnz = B.nnz;
+  a.seg_lo = B.seg_lo;
+  a.seg_hi = B.seg_hi;
+  a.nseg = B.nseg;
+  a.staging = reinterpret_cast<half_t*>(B.staging);
+  a.stage_mz = B.stage_mz;
+  a.staging_m = a.staging + size_t(2) * size_t(B.nseg) * size_t(a.max_F);
+  a.stage_c = B.stage_mz + size_t(4) * size_t(B.nseg) * size_t(a.max_H);
+  a.split_row = B.split_row;
+  a.split_lo = B.split_lo;
+  a.split_hi = B.split_hi;
+  a.n_split = B.n_split;
+  a.Y += int64_t(b) * a.y_stride;
+  a.part_mz += int64_t(b) * a.mz_stride;
+  if (a.Ym) {
+    a.Ym += int64_t(b) * a.y_stride;
+    a.csum += int64_t(b) * a.c_stride;
+  }
+  return wg;
+}
 
 // A partial result of one row and head over some of its edges, as held by one lane (8 features):
 // m = largest score met, z = sum exp(e - m), acc = sum exp(e - m) * x; SAVE adds zm = sum exp(e - m) * mu and
@@ -222,7 +264,13 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   int* m_trow = m_hrow + G;
 
   const int wpb = int(blockDim.x) / kWave;  // waves per workgroup (4, 2 or 1, chosen on the host for LDS packing)
-  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = gat_enter_block(a, wg, wg_count, [&](const hgnn_seg_block& B) {
+      const int64_t c = (B.nseg + wpb - 1) / wpb;
+      return c > 0 ? c : int64_t(1);
+    });
+  const int64_t wid = wg * wpb + wave;
   const int64_t seg = wid;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
@@ -421,7 +469,7 @@ __global__ __launch_bounds__(kBlock) void gat_seg_kernel(GatArgs a) {
   }
 
   // ---- this wave's share of the empty rows
-  const int64_t nw = int64_t(gridDim.x) * wpb;
+  const int64_t nw = wg_count * wpb;
   const int rpw = int((a.nrows + nw - 1) / nw);
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
@@ -448,7 +496,12 @@ __global__ __launch_bounds__(kBlock) void gat_finish_kernel(GatArgs a) {
   const int f0c = active ? f0 : 0;
   const int head = f0c / a.D;
   const bool leader = active && (f0 % a.D) == 0;
-  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = gat_enter_block(a, wg, wg_count, [&](const hgnn_seg_block& B) {
+      return (int64_t(B.n_split) + kWavesPerBlock * G - 1) / (kWavesPerBlock * G);
+    });
+  const int64_t i0 = (wg * kWavesPerBlock + wave) * G;
   if (i0 >= a.n_split) return;
   const int64_t idx = i0 + g;
   int r = 0, sa = 0, sb = -1;
@@ -690,25 +743,46 @@ static hgnn_status gat_forward_impl(const char* who, const hgnn_csr* g, const hg
   half_t* bstage = reinterpret_cast<half_t*>(p->bstage);
   half_t* bstage_m = bstage + flat * size_t(p->max_F);    // the plan holds a second set of partial rows behind the first
   float* bsum_c = p->bsum + 2 * flat * size_t(p->max_H);  // and a third scalar per partial row
-  for (int b = 0; b < p->nb; ++b) {
-    const hgnn_plan* q = p->sub[size_t(b)];
+  const int L = pow2_at_least(F / 8);
+  {
+    // all blocks in one launch of each kernel: workgroups numbered block after block and dispatched in that order
     GatArgs ab = a;
-    ab.rowptr = p->brp + size_t(b) * (V + 1);
-    ab.col = p->bcol + p->boff[size_t(b)];
-    ab.nnz = q->nnz;
-    ab.Y = bstage + size_t(b) * V * size_t(p->max_F);
+    ab.Y = bstage;
     ab.ldy = p->max_F;
     ab.lse = nullptr;
-    ab.part_mz = p->bsum + size_t(b) * V * size_t(p->max_H) * 2;
-    if (save) {
-      ab.Ym = bstage_m + size_t(b) * V * size_t(p->max_F);
-      ab.ldym = p->max_F;
-      ab.csum = bsum_c + size_t(b) * V * size_t(p->max_H);
+    ab.part_mz = p->bsum;
+    ab.Ym = save ? bstage_m : nullptr;
+    ab.ldym = p->max_F;
+    ab.csum = save ? bsum_c : nullptr;
+    ab.blocks = p->bdesc;
+    ab.nblocks = p->nb;
+    ab.max_F = p->max_F;
+    ab.max_H = p->max_H;
+    ab.y_stride = int64_t(V) * p->max_F;
+    ab.mz_stride = int64_t(V) * p->max_H * 2;
+    ab.c_stride = int64_t(V) * p->max_H;
+    ab.S = p->S;
+    ab.stage_ld = p->max_F;
+    const size_t per_wave = size_t(gat_lds_layout(ab.S, L, save).total);
+    const int wpb = waves_per_block_for_lds(per_wave, true);
+    const size_t lds = per_wave * wpb;
+    HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+                 "%s: seg_edges = %d with H = %d needs %zu bytes of LDS per workgroup (limit 65536)", who, ab.S, ab.H, lds);
+    int64_t wgs = 0, wgs2 = 0;
+    for (const hgnn_plan* q : p->sub) {
+      const int64_t c = ceil_div(q->nseg, wpb);
+      wgs += c > 0 ? c : 1;
+      wgs2 += ceil_div(q->n_split, int64_t(kWavesPerBlock) * (kWave / L));
     }
-    st = run_gat_segments(q, ab, g->ncols, s);
-    if (st != HGNN_OK) return st;
+    const bool off32 = uint64_t(g->ncols) * uint64_t(ab.ldx) * 2u < (uint64_t(1) << 32);
+    if (off32) launch_gat_seg<true>(L, save, dim3(unsigned(wgs)), wpb * kWave, lds, s, ab);
+    else launch_gat_seg<false>(L, save, dim3(unsigned(wgs)), wpb * kWave, lds, s, ab);
+    HGNN_LAUNCH_CHECK("gat_seg_kernel");
+    if (wgs2 > 0) {
+      launch_gat_finish(L, save, dim3(unsigned(wgs2)), s, ab);
+      HGNN_LAUNCH_CHECK("gat_finish_kernel");
+    }
   }
-  const int L = pow2_at_least(F / 8);
   const GatBlockParts parts{bstage, bstage_m, p->max_F, p->bsum, int64_t(V) * p->max_H * 2, bsum_c, int64_t(V) * p->max_H, p->nb};
   launch_gat_block_merge(L, save, dim3(unsigned(ceil_div(g->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, a, parts);
   HGNN_LAUNCH_CHECK("gat_block_merge_kernel");

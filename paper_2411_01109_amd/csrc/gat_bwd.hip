@@ -43,7 +43,43 @@ struct GatBwdArgs {
   const int* split_lo;
   const int* split_hi;
   int n_split;
+  // all column blocks of a plan in one launch (workgroups numbered block after block): the table of the blocks'
+  // arrays, or nullptr when the fields above describe the one graph of the launch.  Y and dsum_f32 then point at
+  // block 0's partial results and advance by the strides per block.
+  const hgnn_seg_block* blocks;
+  int nblocks;
+  int64_t y_stride, ds_stride;
 };
+
+// Finds the block of workgroup wg (cnt(B) workgroups per block), rewrites `a` to that block and returns the
+// workgroup's number inside the block; wg_count receives the block's workgroup count.
+template <class Count>
+__device__ __forceinline__ int64_t gat_bwd_enter_block(GatBwdArgs& a, int64_t wg, int64_t& wg_count, Count cnt) {
+  int b = 0;
+  for (;;) {
+    const int64_t c = cnt(a.blocks[b]);
+    wg_count = c;
+    if (wg < c || b + 1 == a.nblocks) break;
+    wg -= c;
+    ++b;
+  }
+  const hgnn_seg_block& B = a.blocks[b];
+  a.rowptr = B.rowptr;
+  a.col = B.col;
+  a.nnz = B.nnz;
+  a.seg_lo = B.seg_lo;
+  a.seg_hi = B.seg_hi;
+  a.nseg = B.nseg;
+  a.staging = reinterpret_cast<half_t*>(B.staging);
+  a.stage_ds = B.stage_mz;
+  a.split_row = B.split_row;
+  a.split_lo = B.split_lo;
+  a.split_hi = B.split_hi;
+  a.n_split = B.n_split;
+  if (a.Y) a.Y += int64_t(b) * a.y_stride;
+  a.dsum_f32 += int64_t(b) * a.ds_stride;
+  return wg;
+}
 
 struct GatBwdLds {
   int per, spad, col_off, row_off, blk_off, a_off, t_off, vec_off, ds_off, flag_off, total;
@@ -131,7 +167,13 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
   int* m_trow = m_hrow + G;
 
   const int wpb = int(blockDim.x) / kWave;  // 4 waves per workgroup, fewer when the heads' LDS tables are large
-  const int64_t wid = int64_t(blockIdx.x) * wpb + wave;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = gat_bwd_enter_block(a, wg, wg_count, [&](const hgnn_seg_block& B) {
+      const int64_t c = (B.nseg + wpb - 1) / wpb;
+      return c > 0 ? c : int64_t(1);
+    });
+  const int64_t wid = wg * wpb + wave;
   const int64_t seg = wid;
   const bool valid = seg < a.nseg;
   const int64_t e0 = seg * S;
@@ -379,7 +421,7 @@ __global__ __launch_bounds__(kBlock, VEC ? 1 : 6) void gat_bwd_seg_kernel(GatBwd
   }
 
   // ---- this wave's share of the empty rows
-  const int64_t nw = int64_t(gridDim.x) * wpb;
+  const int64_t nw = wg_count * wpb;
   const int rpw = int((a.nrows + nw - 1) / nw);
   const int64_t r0 = wid * rpw;
   const int64_t r1 = r0 + rpw < a.nrows ? r0 + rpw : a.nrows;
@@ -401,7 +443,12 @@ __global__ __launch_bounds__(kBlock) void gat_bwd_finish_kernel(GatBwdArgs a) {
   const int f0c = active ? f0 : 0;
   const int head = f0c / a.D;
   const bool leader = active && (f0 % a.D) == 0;
-  const int64_t i0 = (int64_t(blockIdx.x) * kWavesPerBlock + wave) * G;
+  int64_t wg = blockIdx.x, wg_count = gridDim.x;
+  if (a.blocks)
+    wg = gat_bwd_enter_block(a, wg, wg_count, [&](const hgnn_seg_block& B) {
+      return (int64_t(B.n_split) + kWavesPerBlock * G - 1) / (kWavesPerBlock * G);
+    });
+  const int64_t i0 = (wg * kWavesPerBlock + wave) * G;
   if (i0 >= a.n_split) return;
   const int64_t idx = i0 + g;
   int r = 0, sa = 0, sb = -1;
@@ -621,20 +668,48 @@ static hgnn_status run_bwd_pass(const hgnn_plan* q, const hgnn_csr* gg, GatBwdAr
   if (q->nb <= 1) return run_bwd_segments<VEC>(q, a, gg->ncols, s);
   const size_t V = size_t(q->nrows);
   const int64_t ds_stride = int64_t(V) * q->max_H * 2;
-  for (int b = 0; b < q->nb; ++b) {
-    const hgnn_plan* sub = q->sub[size_t(b)];
+  const int L = pow2_at_least(a.F / 8);
+  {
+    // all blocks in one launch of each kernel: workgroups numbered block after block and dispatched in that order
     GatBwdArgs ab = a;
-    ab.rowptr = q->brp + size_t(b) * (V + 1);
-    ab.col = q->bcol + q->boff[size_t(b)];
-    ab.nnz = sub->nnz;
-    ab.Y = reinterpret_cast<half_t*>(q->bstage) + size_t(b) * V * size_t(q->max_F);
+    ab.Y = reinterpret_cast<half_t*>(q->bstage);
     ab.ldy = q->max_F;
     ab.dsum = nullptr;
-    ab.dsum_f32 = q->bsum + size_t(b) * size_t(ds_stride);
-    hgnn_status st = run_bwd_segments<VEC>(sub, ab, gg->ncols, s);
-    if (st != HGNN_OK) return st;
+    ab.dsum_f32 = q->bsum;
+    ab.blocks = q->bdesc;
+    ab.nblocks = q->nb;
+    ab.y_stride = int64_t(V) * q->max_F;
+    ab.ds_stride = ds_stride;
+    ab.S = q->S;
+    ab.stage_ld = q->max_F;
+    const bool off32 = uint64_t(gg->ncols) * uint64_t(ab.ldx) * 2u < (uint64_t(1) << 32);
+    const bool fly = ab.H >= 2 || ab.D <= 64;  // as in run_bwd_segments
+    const size_t per_wave = size_t(gat_bwd_lds_layout(ab.S, ab.H, L, VEC, fly, off32).total);
+    const int wpb = waves_per_block_for_lds(per_wave, true);
+    const size_t lds = per_wave * wpb;
+    HGNN_REQUIRE(lds <= 65536, HGNN_EUNSUPPORTED,
+                 "hgnn_gat_backward_fused: seg_edges = %d with H = %d needs %zu bytes of LDS per wavefront (limit 65536)", ab.S,
+                 ab.H, lds);
+    int64_t wgs = 0, wgs2 = 0;
+    for (const hgnn_plan* sub : q->sub) {
+      const int64_t c = ceil_div(sub->nseg, wpb);
+      wgs += c > 0 ? c : 1;
+      wgs2 += ceil_div(sub->n_split, int64_t(kWavesPerBlock) * (kWave / L));
+    }
+    const dim3 grid{unsigned(wgs)};
+    if (fly) {
+      if (off32) launch_bwd_seg<true, VEC, true>(L, grid, wpb * kWave, lds, s, ab);
+      else launch_bwd_seg<false, VEC, true>(L, grid, wpb * kWave, lds, s, ab);
+    } else {
+      if (off32) launch_bwd_seg<true, VEC, false>(L, grid, wpb * kWave, lds, s, ab);
+      else launch_bwd_seg<false, VEC, false>(L, grid, wpb * kWave, lds, s, ab);
+    }
+    HGNN_LAUNCH_CHECK("gat_bwd_seg_kernel");
+    if (wgs2 > 0) {
+      launch_bwd_finish<VEC>(L, dim3(unsigned(wgs2)), s, ab);
+      HGNN_LAUNCH_CHECK("gat_bwd_finish_kernel");
+    }
   }
-  const int L = pow2_at_least(a.F / 8);
   launch_bwd_block_sum<VEC>(L, dim3(unsigned(ceil_div(gg->nrows, int64_t(kWavesPerBlock) * (kWave / L)))), s, a,
                             reinterpret_cast<const half_t*>(q->bstage), q->max_F, q->bsum, ds_stride, q->nb);
   HGNN_LAUNCH_CHECK("gat_bwd_block_sum_kernel");
