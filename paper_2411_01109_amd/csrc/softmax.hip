@@ -84,6 +84,18 @@ __device__ __forceinline__ half8_t load_vec(const half_t* p, int64_t b, int64_t 
     if (b + q < total) v[q] = p[b + q];
   return v;
 }
+// load_vec with the elements outside [j0, j1) replaced by `fill` (the neutral value of what the caller does with
+// them), so that the passes over the vector need no bounds checks of their own: two 32-bit compares and a select
+// per element, once, instead of two 64-bit compares per element and pass
+__device__ __forceinline__ half8_t load_vec_in(const half_t* p, int64_t b, int64_t total, int64_t j0, int64_t j1, half_t fill) {
+  half8_t v = load_vec(p, b, total);
+  const int lo = j0 > b ? int(j0 - b) : 0;          // first valid element
+  const int hi = j1 - b < 8 ? int(j1 - b) : 8;      // one past the last valid element
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    if (q < lo || q >= hi) v[q] = fill;
+  return v;
+}
 __device__ __forceinline__ void store_vec(half_t* p, int64_t b, const half8_t& v, int64_t j0, int64_t j1) {
   if (b >= j0 && b + 8 <= j1) {
     *reinterpret_cast<half8_t*>(p + b) = v;
@@ -103,38 +115,47 @@ __device__ __forceinline__ void softmax_fwd_row(const EdgeRowArgs& a, const Team
   float m[H];
 #pragma unroll
   for (int h = 0; h < H; ++h) m[h] = -INFINITY;
-  auto visit_max = [&](const half8_t& v, int64_t b) {
+  // elements of a vector that lie outside the row are read as -inf: they lose every maximum and add exp(-inf) = 0
+  const half_t ninf = half_t(-INFINITY);
+  auto visit_max = [&](const half8_t& v) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (b + q >= j0 && b + q < j1) m[q % H] = fmaxf(m[q % H], float(v[q]));
+    for (int q = 0; q < 8; ++q) m[q % H] = fmaxf(m[q % H], float(v[q]));
   };
 #pragma unroll
   for (int i = 0; i < kKeepVec; ++i) {
     const int64_t t = team.rank + int64_t(Team::size) * i;
-    keep[i] = half8_t(0);
+    keep[i] = half8_t(ninf);
     if (t < nvec) {
-      keep[i] = load_vec(a.x0, a0 + 8 * t, a.total);
-      visit_max(keep[i], a0 + 8 * t);
+      keep[i] = load_vec_in(a.x0, a0 + 8 * t, a.total, j0, j1, ninf);
+      visit_max(keep[i]);
     }
   }
   for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
-    visit_max(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
+    visit_max(load_vec_in(a.x0, a0 + 8 * t, a.total, j0, j1, ninf));
   team.template reduce<H, true>(m);
   float z[H];
 #pragma unroll
   for (int h = 0; h < H; ++h) z[h] = 0.f;
-  auto visit_sum = [&](const half8_t& v, int64_t b) {
+  auto visit_sum = [&](const half8_t& v) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (b + q >= j0 && b + q < j1) z[q % H] += __expf(float(v[q]) - m[q % H]);
+    for (int q = 0; q < 8; ++q) z[q % H] += __expf(float(v[q]) - m[q % H]);
   };
+  float ex[kKeepVec][8];  // the exponentials of the vectors held in registers, formed once
 #pragma unroll
   for (int i = 0; i < kKeepVec; ++i) {
     const int64_t t = team.rank + int64_t(Team::size) * i;
-    if (t < nvec) visit_sum(keep[i], a0 + 8 * t);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) ex[i][q] = 0.f;
+    if (t < nvec) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        ex[i][q] = __expf(float(keep[i][q]) - m[q % H]);
+        z[q % H] += ex[i][q];
+      }
+    }
   }
   for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
-    visit_sum(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
+    visit_sum(load_vec_in(a.x0, a0 + 8 * t, a.total, j0, j1, ninf));
   team.template reduce<H, false>(z);
   float inv[H];
 #pragma unroll
@@ -148,7 +169,12 @@ __device__ __forceinline__ void softmax_fwd_row(const EdgeRowArgs& a, const Team
 #pragma unroll
   for (int i = 0; i < kKeepVec; ++i) {
     const int64_t t = team.rank + int64_t(Team::size) * i;
-    if (t < nvec) emit(keep[i], a0 + 8 * t);
+    if (t < nvec) {
+      half8_t o;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) o[q] = half_t(ex[i][q] * inv[q % H]);
+      store_vec(a.out, a0 + 8 * t, o, j0, j1);
+    }
   }
   for (int64_t t = team.rank + int64_t(Team::size) * kKeepVec; t < nvec; t += Team::size)
     emit(load_vec(a.x0, a0 + 8 * t, a.total), a0 + 8 * t);
@@ -163,10 +189,11 @@ __device__ __forceinline__ void softmax_bwd_row(const EdgeRowArgs& a, const Team
   float t[H];
 #pragma unroll
   for (int h = 0; h < H; ++h) t[h] = 0.f;
-  auto visit = [&](const half8_t& va, const half8_t& vd, int64_t b) {
+  // elements outside the row are read as zero on both sides, so their products vanish (a neighbouring row's
+  // infinity times zero would not)
+  auto visit = [&](const half8_t& va, const half8_t& vd) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (b + q >= j0 && b + q < j1) t[q % H] = fmaf(float(va[q]), float(vd[q]), t[q % H]);
+    for (int q = 0; q < 8; ++q) t[q % H] = fmaf(float(va[q]), float(vd[q]), t[q % H]);
   };
 #pragma unroll
   for (int i = 0; i < kKeepVec; ++i) {
@@ -174,13 +201,13 @@ __device__ __forceinline__ void softmax_bwd_row(const EdgeRowArgs& a, const Team
     ka[i] = half8_t(0);
     kd[i] = half8_t(0);
     if (v < nvec) {
-      ka[i] = load_vec(a.x0, a0 + 8 * v, a.total);
-      kd[i] = load_vec(a.x1, a0 + 8 * v, a.total);
-      visit(ka[i], kd[i], a0 + 8 * v);
+      ka[i] = load_vec_in(a.x0, a0 + 8 * v, a.total, j0, j1, half_t(0));
+      kd[i] = load_vec_in(a.x1, a0 + 8 * v, a.total, j0, j1, half_t(0));
+      visit(ka[i], kd[i]);
     }
   }
   for (int64_t v = team.rank + int64_t(Team::size) * kKeepVec; v < nvec; v += Team::size)
-    visit(load_vec(a.x0, a0 + 8 * v, a.total), load_vec(a.x1, a0 + 8 * v, a.total), a0 + 8 * v);
+    visit(load_vec_in(a.x0, a0 + 8 * v, a.total, j0, j1, half_t(0)), load_vec_in(a.x1, a0 + 8 * v, a.total, j0, j1, half_t(0)));
   team.template reduce<H, false>(t);
   auto emit = [&](const half8_t& va, const half8_t& vd, int64_t b) {
     half8_t o;
